@@ -1,0 +1,22 @@
+"""CPU oracle for one DiffuSpec speculative round.
+
+TEST INFRASTRUCTURE ONLY.  This package is a plain, slow, readable CPU statement of
+what the round computes, written from the paper.  It exists so that the HIP path can
+be checked against something independent.  It shares no code with the HIP path and
+must never be imported by it: only the tests, the smoke check and the benchmark's
+`cpu_baseline` leg may use it.
+
+Precision: the decoder forward works in float64 on the given (fp32 / bf16-exact)
+weights and rounds logits once to float32.  Lattice, path search and acceptance take
+float32 logits / log-scores as data and follow the float32 operation order stated in
+each function, because those steps end in integer decisions.
+
+Pins (tests marked "not gpu"): KV-cached forward == full-sequence recompute; a third
+implementation in primitive PyTorch CPU ops; RoPE shift invariance; GQA == MHA with
+replicated heads; mask-row symmetry; causality; softmax mass == 1 and top-M == stable
+full sort; hand-made mass-pruning rows; brute-force enumeration of all lattice paths and
+a Viterbi DP for the path search; both forms of the accepted-length formula; hand traces
+of the draft-length controller.  Parity unpinned: the beam path for beams narrower than
+exhaustive is fixed only by the step-by-step reading of the search procedure.
+"""
+from . import model, lattice, cps, accept, adl, round  # noqa: F401

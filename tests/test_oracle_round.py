@@ -1,0 +1,56 @@
+"""Pins for the oracle's whole round and loop (no GPU): the committed stream equals the
+verifier's own greedy decode (greedy verification is lossless), and a draft equal to that
+greedy continuation is accepted in full."""
+import numpy as np
+
+from oracle import adl, model, round as oround
+from paper_2510_02358_amd import synth
+
+CFG = synth.ModelCfg(n_layers=2, d_model=64, n_q=4, n_kv=2, head_dim=16, d_ffn=96, vocab=96,
+                     rope_base=1.0e4, dtype="f32")
+LOG2 = 12
+
+
+def _setup(seed_d=0, seed_v=1):
+    dw = synth.make_weights(CFG, seed_d, std=0.3)
+    vw = synth.make_weights(CFG, seed_v, std=0.3)
+    prefix = synth.make_prefix(CFG, 12, 2)
+    return dw, vw, prefix
+
+
+def test_committed_stream_equals_verifier_greedy_decode():
+    dw, vw, prefix = _setup()
+    table = synth.make_ngram_table(3, LOG2)
+    st = oround.SpecState(CFG, dw, CFG, vw, prefix)
+    recs = oround.generate(st, 6, 5, adl.AdlState(2, 8, 2, 0.5), 3, 1.0, 2, 0.5, table, LOG2)
+    produced = st.tokens[len(prefix):]
+    ref = oround.ar_greedy(CFG, vw, prefix, len(produced))
+    assert produced == ref
+    assert sum(len(r["committed"]) for r in recs) + 1 == len(produced)
+    # caches hold exactly the committed tokens minus the one still pending for the verifier
+    assert st.vcache.length == len(st.tokens) - 1
+
+
+def test_same_model_as_drafter_and_verifier_still_lossless_and_forced_greedy_path_fully_accepted():
+    dw, vw, prefix = _setup()
+    k = 5
+    st = oround.SpecState(CFG, dw, CFG, vw, prefix)
+    greedy = oround.ar_greedy(CFG, vw, prefix, k + 2)       # greedy[0] is the pending token
+    r = oround.spec_round(st, k, 3, 1.0, 2, 1.0, None, LOG2, forced_path=greedy[1:k + 1])
+    assert r["n_accept"] == k and r["next_token"] == greedy[k + 1]
+    assert r["committed"] == greedy[1:k + 2]
+    # wrong first token -> nothing accepted, correction equals the greedy token
+    st = oround.SpecState(CFG, dw, CFG, vw, prefix)
+    bad = [(greedy[1] + 1) % CFG.n_plain_tokens] + greedy[2:k + 1]
+    r = oround.spec_round(st, k, 3, 1.0, 2, 1.0, None, LOG2, forced_path=bad)
+    assert r["n_accept"] == 0 and r["next_token"] == greedy[1]
+    # partial: first two right
+    st = oround.SpecState(CFG, dw, CFG, vw, prefix)
+    part = greedy[1:3] + [(greedy[3] + 1) % CFG.n_plain_tokens] + greedy[4:k + 1]
+    r = oround.spec_round(st, k, 3, 1.0, 2, 1.0, None, LOG2, forced_path=part)
+    assert r["n_accept"] == 2 and r["next_token"] == greedy[3]
+    # next round still continues the greedy stream (KV rollback by truncation is right)
+    r2 = oround.spec_round(st, k, 3, 1.0, 2, 1.0, None, LOG2)
+    ref = oround.ar_greedy(CFG, vw, prefix, len(st.tokens) - len(prefix))
+    assert st.tokens[len(prefix):] == ref
+    assert st.pending == r2["committed"]
