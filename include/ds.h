@@ -1,0 +1,183 @@
+/*
+ * libdiffuspec: one DiffuSpec speculative-decoding round on one MI355X (gfx950).
+ *
+ * The round (Alg. 1 of the paper, "DIFFUSPEC (4-stage)"):
+ *   (1) the diffusion-LM drafter fills K [MASK] positions in a single pass      -> ds_draft_block
+ *       and exposes a per-position top-M candidate lattice with log-scores       -> ds_build_lattice
+ *   (2) causal-consistency path search picks one left-to-right path              -> ds_cps_path
+ *   (3) the autoregressive target verifies the path in one parallel pass and
+ *       keeps the longest accepted prefix (greedy verification)                  -> ds_verify_block
+ *   (4) the adaptive draft-length controller sets the next K                     -> ds_adl_update
+ *
+ * Conventions
+ *   - Plain C ABI.  Every function returns an int status (DS_OK = 0, negatives are errors);
+ *     ds_last_error() gives the text of the calling thread's last error.
+ *   - Arguments are validated on the host before anything is launched: a failed call enqueues
+ *     no work and changes no state.
+ *   - Ownership: the caller allocates and frees ALL device memory (weights, packed weights, KV
+ *     caches, workspace, inputs, outputs) and passes raw device pointers.  The library only
+ *     allocates small host structs behind the opaque handles, released by the *_destroy calls.
+ *     Pointers marked [dev] are device memory, [host] host memory.
+ *   - All device work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and the call returns without synchronising.  Outputs are device memory; the caller
+ *     synchronises the stream before reading them.
+ *   - Determinism: the same inputs give bit-identical outputs (no floating-point atomics).
+ *   - One GPU; calls that use the same handle or the same workspace must not overlap.
+ */
+#ifndef DS_H
+#define DS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DS_OK 0
+#define DS_E_INVALID (-1)     /* null pointer, bad alignment, value out of range */
+#define DS_E_SHAPE (-2)       /* shape not supported by the kernels */
+#define DS_E_CAPACITY (-3)    /* KV cache, workspace or packed-weight buffer too small */
+#define DS_E_UNSUPPORTED (-4) /* dtype / head_dim / feature not implemented */
+#define DS_E_HIP (-5)         /* a HIP runtime call failed */
+
+#define DS_F32 0
+#define DS_BF16 1
+
+#define DS_MAX_ROWS 144 /* most rows one forward call may carry (pending + K, or m + 1) */
+#define DS_MAX_TOPM 16  /* largest lattice width M_max */
+#define DS_MAX_BEAM 16  /* largest beam width B */
+
+typedef struct ds_model ds_model;
+typedef struct ds_ngram ds_ngram;
+typedef struct ds_adl ds_adl;
+
+/* Shape of one pre-RMSNorm decoder with grouped-query attention, rotary embedding (rotate-half
+ * pairing, absolute positions) and a SwiGLU MLP; no biases; untied embedding and LM head. */
+typedef struct {
+  int32_t n_layers, d_model, n_q, n_kv, head_dim, d_ffn, vocab;
+  float rope_base, rms_eps;
+  int32_t dtype;       /* DS_F32 or DS_BF16: storage type of weights, KV cache and hidden states */
+  int32_t kv_capacity; /* tokens each layer's KV buffer can hold (bf16: a multiple of 64) */
+} ds_model_cfg;
+
+/* Canonical weights: every matrix row-major [out_features, in_features] in cfg.dtype;
+ * norm gains are float32 vectors of d_model. */
+typedef struct {
+  const void *wq, *wk, *wv, *wo, *w_gate, *w_up, *w_down; /* [dev] */
+  const float *norm1, *norm2;                              /* [dev] */
+} ds_layer_weights;
+
+typedef struct {
+  const void* embed;              /* [dev] [vocab, d_model] */
+  const ds_layer_weights* layers; /* [host] array of n_layers */
+  const float* final_norm;        /* [dev] */
+  const void* lm_head;            /* [dev] [vocab, d_model] */
+} ds_weights;
+
+const char* ds_version(void);
+const char* ds_last_error(void);
+
+/* Bytes the caller must provide for kernel-order copies of the weights (0 for DS_F32) and for the
+ * per-call workspace when at most max_rows rows go through one call. */
+int ds_model_packed_bytes(const ds_model_cfg* cfg, size_t* bytes);
+int ds_workspace_bytes(const ds_model_cfg* cfg, int max_rows, size_t* bytes);
+/* Bytes of ONE of the two KV buffers (keys or values) for cfg. */
+int ds_kv_bytes(const ds_model_cfg* cfg, size_t* bytes);
+
+/* Bind a model.  For DS_BF16 this enqueues kernels that copy the matrices into the order the GEMM
+ * kernels stream them in (`packed`, ds_model_packed_bytes() bytes, 256-byte aligned); after the
+ * stream has run them the canonical matrices other than `embed` are no longer read.  For DS_F32
+ * nothing is copied and the canonical matrices are read by every call.  kv_k / kv_v: ds_kv_bytes()
+ * each; their internal layout is private to the library.  The committed KV length starts at 0. */
+int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, size_t packed_bytes,
+                    void* kv_k, void* kv_v, void* stream, ds_model** out);
+void ds_model_destroy(ds_model* m);
+
+/* Committed KV length: query, and set (truncate after a rejection / commit after verification). */
+int ds_model_kv_len(const ds_model* m, int* len);
+int ds_model_kv_set_len(ds_model* m, int len);
+
+/* Causal forward of n real tokens (any n >= 1; processed in chunks), appended to the KV cache and
+ * committed.  tokens [dev] int32[n].  last_logits [dev] float[vocab] or NULL: logits of the last
+ * token.  Setup path: not part of the timed round. */
+int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, void* ws, size_t ws_bytes,
+               void* stream);
+
+/* Step 1, drafter pass with S = 1 (Sec. 3.1 "Inference"; Alg. 1 step (1)).
+ * Rows = n_pend real tokens (tokens committed since the drafter last ran; causal) followed by K
+ * [MASK] tokens (each sees the whole cached prefix, the pending tokens and all K block positions).
+ * Keys/values of the pending rows are appended and committed (length += n_pend); those of the mask
+ * rows are scratch and never committed.  pending [dev] int32[n_pend] (may be NULL iff n_pend == 0).
+ * hidden_out [dev] [K, d_model] in cfg.dtype: final-normed hidden states of the mask rows; the state
+ * at block position i gives the distribution of the token AT position i.
+ * Requires 1 <= K, n_pend + K <= DS_MAX_ROWS, kv_len + n_pend + K <= kv_capacity. */
+int ds_draft_block(ds_model* drafter, const int32_t* pending, int n_pend, int K, int32_t mask_id,
+                   void* hidden_out, void* ws, size_t ws_bytes, void* stream);
+
+/* logits[rows, vocab] (float32) = hidden[rows, d_model] (cfg.dtype) times the LM head. */
+int ds_lm_head(ds_model* m, const void* hidden, int rows, float* logits, void* ws, size_t ws_bytes,
+               void* stream);
+
+/* Step 2, token lattice (Sec. 3.2 "Lattice and pruning").  Per row r of logits [dev] float[rows, vocab]:
+ *   lse[r]           = log sum_v exp(logit)
+ *   cand_id[r, :]    = the M_max largest logits' token ids (logit descending, ties: lower id)
+ *   cand_logp[r, :]  = logit - lse  (the drafter log-score l_dlm of each candidate)
+ *   cand_cnt[r]      = smallest m <= M_max whose cumulative probability >= tau (M_max if none;
+ *                      tau >= 1 disables pruning)
+ *   eos_logp[r]      = logit[eos_id] - lse (0 if eos_id < 0)
+ * Outputs [dev]: cand_id int32[rows, M_max], cand_logp float[rows, M_max], cand_cnt int32[rows],
+ * eos_logp float[rows], lse float[rows].  1 <= M_max <= DS_MAX_TOPM <= vocab.
+ * ws: ds_lattice_workspace_bytes(rows, vocab, M_max) bytes.  NaN logits are a caller error. */
+int ds_lattice_workspace_bytes(int rows, int vocab, int M_max, size_t* bytes);
+int ds_build_lattice(const float* logits, int rows, int vocab, int M_max, float tau, int32_t eos_id,
+                     int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* Causal proxy for the path search: a table of 2^log2_size float32 natural-log scores [dev]; the
+ * 3-gram (u, v, w) reads slot hash(u, v, w) (fixed uint32 multiply / xor-shift mix). */
+int ds_ngram_create(const float* table, int log2_size, ds_ngram** out);
+void ds_ngram_destroy(ds_ngram* g);
+
+/* Step 3, causal-consistency path search (Sec. 3.2 "Scoring and search"; Alg. 1 step (2)).
+ * For each of `batch` independent sequences (lattice rows [s*K, (s+1)*K)): left-to-right beam search of
+ * width B over the pruned lattice (EOS always a candidate, appended last if absent) maximising
+ *   S(path) = sum_i [ lambda * l_dlm_i + (1 - lambda) * l_ng(path_i | two previous tokens) ],
+ * float32 unfused, kept hypotheses ordered by (score desc, parent asc, candidate rank asc); returns at
+ * the first depth whose best hypothesis ends in EOS (EOS included), else after K positions.
+ * proxy NULL: l_ng = 0.  ctx [dev] int32[batch, 2]: the two tokens before each block (older first).
+ * Outputs [dev]: path int32[batch, K] (tail beyond the length = -1), path_len int32[batch],
+ * path_score float[batch].  1 <= B <= DS_MAX_BEAM, 1 <= M_max <= DS_MAX_TOPM, 1 <= K <= 256. */
+int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
+                const float* eos_logp, int batch, int K, int M_max, int B, float lambda,
+                const ds_ngram* proxy, const int32_t* ctx, int32_t eos_id, int32_t* path,
+                int32_t* path_len, float* path_score, void* stream);
+
+/* Step 4, parallel verification with greedy acceptance (Sec. 2 "Parallel verification" and
+ * "Accepted prefix length"; Alg. 1 step (3); greedy verification as in Sec. 4).
+ * block [dev] int32[m + 1] = last committed token followed by the path (ids outside [0, vocab) are
+ * read as token 0; such rows lie past path_len and are ignored).  path_len [dev] int32 or NULL: if
+ * given, only the first min(m, *path_len) path tokens take part in acceptance.
+ * Causal forward of the m + 1 rows against the verifier's KV cache, LM head, per-row arg-max (ties:
+ * lower id); n_accept = number of leading path tokens equal to the arg-max of the row before them;
+ * next_token = argmax[n_accept]; eos_accepted = 1 if an accepted token or next_token is eos_id.
+ * Keys/values of all rows are written at [len, len + m + 1) but the committed length is NOT advanced:
+ * after reading n_accept the caller commits with ds_model_kv_set_len(len + 1 + n_accept).
+ * Outputs [dev]: n_accept, next_token, eos_accepted int32[1]; argmax int32[m + 1];
+ * logits_out float[m + 1, vocab] or NULL.  0 <= m, m + 1 <= DS_MAX_ROWS. */
+int ds_verify_block(ds_model* verifier, const int32_t* block, int m, const int32_t* path_len,
+                    int32_t eos_id, int32_t* n_accept, int32_t* next_token, int32_t* argmax,
+                    int32_t* eos_accepted, float* logits_out, void* ws, size_t ws_bytes, void* stream);
+
+/* Step 4 tail, adaptive draft length (Sec. 3.3: generation-length signal, moving averages,
+ * controller).  Pure host code in double precision.  first_eos: 1-based index of the first EOS in the
+ * raw draft (per-position top-1 before the search), 0 if none.  Averages start at 0 (Alg. 1 init). */
+int ds_adl_create(int k_min, int k_max, double delta, double rho, ds_adl** out);
+void ds_adl_destroy(ds_adl* a);
+int ds_adl_update(ds_adl* a, int k_t, int first_eos, int l_acc, int* k_next);
+int ds_adl_state(const ds_adl* a, double* l_gen_ema, double* l_acc_ema);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DS_H */

@@ -1,0 +1,251 @@
+"""Thin ctypes binding of libdiffuspec.so: same names as include/ds.h, argument marshalling only.
+
+PyTorch supplies device memory and streams; every step of the round runs in the library's kernels.
+There is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdiffuspec.so")
+_lib = None
+
+DS_F32, DS_BF16 = 0, 1
+DS_MAX_ROWS, DS_MAX_TOPM, DS_MAX_BEAM = 144, 16, 16
+DS_OK, DS_E_INVALID, DS_E_SHAPE, DS_E_CAPACITY, DS_E_UNSUPPORTED, DS_E_HIP = 0, -1, -2, -3, -4, -5
+
+EXPORTS = [
+    "ds_version", "ds_last_error", "ds_model_packed_bytes", "ds_workspace_bytes", "ds_kv_bytes",
+    "ds_model_create", "ds_model_destroy", "ds_model_kv_len", "ds_model_kv_set_len", "ds_prefill",
+    "ds_draft_block", "ds_lm_head", "ds_lattice_workspace_bytes", "ds_build_lattice", "ds_ngram_create",
+    "ds_ngram_destroy", "ds_cps_path", "ds_verify_block", "ds_adl_create", "ds_adl_destroy",
+    "ds_adl_update", "ds_adl_state",
+]
+
+
+class DsError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libdiffuspec error {code}: {text}")
+        self.code = code
+
+
+class ModelCfgC(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q", C.c_int32), ("n_kv", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
+                ("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32),
+                ("kv_capacity", C.c_int32)]
+
+
+class LayerWeightsC(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm1", "norm2")]
+
+
+class WeightsC(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(LayerWeightsC)), ("final_norm", C.c_void_p),
+                ("lm_head", C.c_void_p)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2510_02358_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = C.CDLL(_LIB_PATH)
+    lib.ds_version.restype = C.c_char_p
+    lib.ds_last_error.restype = C.c_char_p
+    lib.ds_model_destroy.restype = None
+    lib.ds_ngram_destroy.restype = None
+    lib.ds_adl_destroy.restype = None
+    vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
+    lib.ds_model_packed_bytes.argtypes = [C.POINTER(ModelCfgC), C.POINTER(sz)]
+    lib.ds_workspace_bytes.argtypes = [C.POINTER(ModelCfgC), C.c_int, C.POINTER(sz)]
+    lib.ds_kv_bytes.argtypes = [C.POINTER(ModelCfgC), C.POINTER(sz)]
+    lib.ds_model_create.argtypes = [C.POINTER(ModelCfgC), C.POINTER(WeightsC), vp, sz, vp, vp, vp, C.POINTER(vp)]
+    lib.ds_model_destroy.argtypes = [vp]
+    lib.ds_model_kv_len.argtypes = [vp, C.POINTER(C.c_int)]
+    lib.ds_model_kv_set_len.argtypes = [vp, C.c_int]
+    lib.ds_prefill.argtypes = [vp, vp, C.c_int, vp, vp, sz, vp]
+    lib.ds_draft_block.argtypes = [vp, vp, C.c_int, C.c_int, i32, vp, vp, sz, vp]
+    lib.ds_lm_head.argtypes = [vp, vp, C.c_int, vp, vp, sz, vp]
+    lib.ds_lattice_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(sz)]
+    lib.ds_build_lattice.argtypes = [vp, C.c_int, C.c_int, C.c_int, f32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ds_ngram_create.argtypes = [vp, C.c_int, C.POINTER(vp)]
+    lib.ds_ngram_destroy.argtypes = [vp]
+    lib.ds_cps_path.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, vp, i32, vp, vp, vp, vp]
+    lib.ds_verify_block.argtypes = [vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ds_adl_create.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.POINTER(vp)]
+    lib.ds_adl_destroy.argtypes = [vp]
+    lib.ds_adl_update.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int)]
+    lib.ds_adl_state.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise DsError(rc, load().ds_last_error().decode())
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a torch tensor / raw int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream
+
+
+def ds_version() -> str:
+    return load().ds_version().decode()
+
+
+def ds_last_error() -> str:
+    return load().ds_last_error().decode()
+
+
+def make_cfg(cfg, kv_capacity: int) -> ModelCfgC:
+    return ModelCfgC(cfg.n_layers, cfg.d_model, cfg.n_q, cfg.n_kv, cfg.head_dim, cfg.d_ffn, cfg.vocab,
+                     cfg.rope_base, cfg.rms_eps, DS_BF16 if cfg.dtype == "bf16" else DS_F32, kv_capacity)
+
+
+def ds_model_packed_bytes(cfgc: ModelCfgC) -> int:
+    out = C.c_size_t(0)
+    _check(load().ds_model_packed_bytes(C.byref(cfgc), C.byref(out)))
+    return out.value
+
+
+def ds_workspace_bytes(cfgc: ModelCfgC, max_rows: int) -> int:
+    out = C.c_size_t(0)
+    _check(load().ds_workspace_bytes(C.byref(cfgc), max_rows, C.byref(out)))
+    return out.value
+
+
+def ds_kv_bytes(cfgc: ModelCfgC) -> int:
+    out = C.c_size_t(0)
+    _check(load().ds_kv_bytes(C.byref(cfgc), C.byref(out)))
+    return out.value
+
+
+def ds_lattice_workspace_bytes(rows: int, vocab: int, m_max: int) -> int:
+    out = C.c_size_t(0)
+    _check(load().ds_lattice_workspace_bytes(rows, vocab, m_max, C.byref(out)))
+    return out.value
+
+
+def ds_model_create(cfgc: ModelCfgC, weights: dict, packed, kv_k, kv_v, stream=None) -> int:
+    """weights: {"embed", "layers": [{wq,..,norm1,norm2}], "final_norm", "lm_head"} of device tensors."""
+    n = cfgc.n_layers
+    layers = (LayerWeightsC * n)()
+    for i, lw in enumerate(weights["layers"]):
+        for name, _ in LayerWeightsC._fields_:
+            setattr(layers[i], name, _ptr(lw[name]))
+    wc = WeightsC(_ptr(weights["embed"]), layers, _ptr(weights["final_norm"]), _ptr(weights["lm_head"]))
+    out = C.c_void_p(None)
+    pbytes = packed.numel() * packed.element_size() if packed is not None else 0
+    _check(load().ds_model_create(C.byref(cfgc), C.byref(wc), _ptr(packed), pbytes, _ptr(kv_k), _ptr(kv_v),
+                                  _stream(stream), C.byref(out)))
+    return out.value
+
+
+def ds_model_destroy(model: int) -> None:
+    load().ds_model_destroy(model)
+
+
+def ds_model_kv_len(model: int) -> int:
+    out = C.c_int(0)
+    _check(load().ds_model_kv_len(model, C.byref(out)))
+    return out.value
+
+
+def ds_model_kv_set_len(model: int, length: int) -> None:
+    _check(load().ds_model_kv_set_len(model, length))
+
+
+def _nbytes(t) -> int:
+    return t.numel() * t.element_size()
+
+
+def ds_prefill(model: int, tokens, n: int, last_logits, ws, stream=None) -> None:
+    _check(load().ds_prefill(model, _ptr(tokens), n, _ptr(last_logits), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ds_draft_block(model: int, pending, n_pend: int, k: int, mask_id: int, hidden_out, ws, stream=None) -> None:
+    _check(load().ds_draft_block(model, _ptr(pending), n_pend, k, mask_id, _ptr(hidden_out), _ptr(ws), _nbytes(ws),
+                                 _stream(stream)))
+
+
+def ds_lm_head(model: int, hidden, rows: int, logits, ws, stream=None) -> None:
+    _check(load().ds_lm_head(model, _ptr(hidden), rows, _ptr(logits), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ds_build_lattice(logits, rows: int, vocab: int, m_max: int, tau: float, eos_id: int, cand_id, cand_logp,
+                     cand_cnt, eos_logp, lse, ws, stream=None) -> None:
+    _check(load().ds_build_lattice(_ptr(logits), rows, vocab, m_max, tau, eos_id, _ptr(cand_id), _ptr(cand_logp),
+                                   _ptr(cand_cnt), _ptr(eos_logp), _ptr(lse), _ptr(ws),
+                                   _nbytes(ws) if ws is not None else 0, _stream(stream)))
+
+
+def ds_ngram_create(table, log2_size: int) -> int:
+    out = C.c_void_p(None)
+    _check(load().ds_ngram_create(_ptr(table), log2_size, C.byref(out)))
+    return out.value
+
+
+def ds_ngram_destroy(handle: int) -> None:
+    load().ds_ngram_destroy(handle)
+
+
+def ds_cps_path(cand_id, cand_logp, cand_cnt, eos_logp, batch: int, k: int, m_max: int, beam: int, lam: float,
+                proxy: Optional[int], ctx, eos_id: int, path, path_len, path_score, stream=None) -> None:
+    _check(load().ds_cps_path(_ptr(cand_id), _ptr(cand_logp), _ptr(cand_cnt), _ptr(eos_logp), batch, k, m_max, beam,
+                              lam, proxy, _ptr(ctx), eos_id, _ptr(path), _ptr(path_len), _ptr(path_score),
+                              _stream(stream)))
+
+
+def ds_verify_block(model: int, block, m: int, path_len, eos_id: int, n_accept, next_token, argmax, eos_accepted,
+                    logits_out, ws, stream=None) -> None:
+    _check(load().ds_verify_block(model, _ptr(block), m, _ptr(path_len), eos_id, _ptr(n_accept), _ptr(next_token),
+                                  _ptr(argmax), _ptr(eos_accepted), _ptr(logits_out), _ptr(ws), _nbytes(ws),
+                                  _stream(stream)))
+
+
+def ds_adl_create(k_min: int, k_max: int, delta: float, rho: float) -> int:
+    out = C.c_void_p(None)
+    _check(load().ds_adl_create(k_min, k_max, delta, rho, C.byref(out)))
+    return out.value
+
+
+def ds_adl_destroy(handle: int) -> None:
+    load().ds_adl_destroy(handle)
+
+
+def ds_adl_update(handle: int, k_t: int, first_eos: int, l_acc: int) -> int:
+    out = C.c_int(0)
+    _check(load().ds_adl_update(handle, k_t, first_eos, l_acc, C.byref(out)))
+    return out.value
+
+
+def ds_adl_state(handle: int):
+    a, b = C.c_double(0), C.c_double(0)
+    _check(load().ds_adl_state(handle, C.byref(a), C.byref(b)))
+    return a.value, b.value

@@ -1,0 +1,67 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "ds.h"
+
+namespace ds {
+
+// ---- error reporting -------------------------------------------------------------------------
+int fail(int code, const char* fmt, ...);  // records the thread's error text, returns code
+void clear_error();
+
+#define DS_REQUIRE(cond, code, ...) \
+  do {                              \
+    if (!(cond)) return ::ds::fail((code), __VA_ARGS__); \
+  } while (0)
+
+#define DS_HIP_CHECK(expr)                                                                  \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return ::ds::fail(DS_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+#define DS_LAUNCH_CHECK(name)                                                                  \
+  do {                                                                                         \
+    hipError_t e_ = hipGetLastError();                                                         \
+    if (e_ != hipSuccess) return ::ds::fail(DS_E_HIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+  } while (0)
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+constexpr int kWave = 64;
+
+// ---- activation tile order (bf16 GEMM input) ---------------------------------------------------
+// A bf16 activation matrix X[M, K] that feeds a GEMM is kept in "tile order": tiles of 16 rows x 32
+// columns, tile (mb, ks) at ((mb * K/32) + ks) * 512 elements; inside a tile the 8 consecutive
+// columns (8g .. 8g+7) of row j sit at lane (16g + j), i.e. element offset (16g + j) * 8.  This is
+// the register image of the 16x16x32 bf16 MFMA's 16-wide operand, so a wave fetches one tile with a
+// single coalesced 16-byte-per-lane load.  Rows are padded to a multiple of 16 (pad rows hold zeros
+// or stale finite values; their products land in accumulator columns that are never stored).
+__host__ __device__ static inline size_t xt_offset(int m, int k, int K) {
+  int mb = m >> 4, j = m & 15, ks = k >> 5, g = (k >> 3) & 3, e = k & 7;
+  return ((size_t)mb * (size_t)(K >> 5) + (size_t)ks) * 512 + (size_t)((g << 4) + j) * 8 + e;
+}
+
+// ---- lattice / acceptance kernels (k_lattice.hip) ----------------------------------------------
+size_t lattice_ws_bytes(int rows, int vocab, int m_max);
+int launch_lattice(const float* logits, int rows, int vocab, int m_max, float tau, int32_t eos_id,
+                   int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
+                   void* ws, size_t ws_bytes, hipStream_t st);
+size_t accept_ws_bytes(int rows, int vocab);
+int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t* block,
+                         const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
+                         int32_t* argmax, int32_t* eos_accepted, void* ws, size_t ws_bytes, hipStream_t st);
+
+// ---- path search (k_cps.hip) --------------------------------------------------------------------
+int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
+               const float* eos_logp, int batch, int K, int m_max, int B, float lambda,
+               const float* table, int log2_size, const int32_t* ctx, int32_t eos_id, int32_t* path,
+               int32_t* path_len, float* path_score, hipStream_t st);
+
+}  // namespace ds

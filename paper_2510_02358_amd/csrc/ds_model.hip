@@ -1,0 +1,451 @@
+// Model handle and the forward passes behind ds_prefill / ds_draft_block / ds_lm_head /
+// ds_verify_block.  Host code only orchestrates: every arithmetic step runs in a kernel.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "ds_act.h"
+#include "ds_common.h"
+
+using namespace ds;
+
+namespace {
+
+struct PackedLayer {
+  const void *wqkv, *wo, *wgu, *wdown;  // bf16 stream order
+};
+
+// Carve-up of the caller's workspace for a call with `rows` rows (all offsets 256-byte aligned).
+struct Workspace {
+  int32_t* tok;
+  float* x;        // [rows, d] residual stream
+  float2* cs;      // [rows, hd/2] rotary table
+  void* h;         // GEMM input, d columns
+  void* q;         // [n_q][rows_pad, hd]
+  void* att;       // GEMM input, n_q*hd columns
+  void* act;       // GEMM input, d_ffn columns
+  void* y;         // GEMM input, d columns (final-normed rows)
+  float* gemm_out; // split-K planes of the widest projection
+  float* att_o;    // attention partials
+  float* att_ml;
+  float* logits;   // [rows, vocab]
+  void* scan;      // acceptance partials
+  size_t scan_bytes;
+  size_t total;
+};
+
+}  // namespace
+
+struct ds_model {
+  ds_model_cfg cfg;
+  const void* embed;
+  std::vector<ds_layer_weights> canon;
+  std::vector<PackedLayer> packed;
+  const float* final_norm;
+  const void* lm_head;  // bf16: stream order; f32: canonical
+  void *kv_k, *kv_v;
+  int kv_len;
+  size_t esize;
+};
+
+namespace {
+
+int n_qkv(const ds_model_cfg& c) { return (c.n_q + 2 * c.n_kv) * c.head_dim; }
+
+int validate_cfg(const ds_model_cfg* c) {
+  DS_REQUIRE(c, DS_E_INVALID, "cfg is NULL");
+  DS_REQUIRE(c->dtype == DS_F32 || c->dtype == DS_BF16, DS_E_UNSUPPORTED, "dtype %d is neither DS_F32 nor DS_BF16",
+             c->dtype);
+  DS_REQUIRE(c->n_layers >= 1 && c->d_model >= 1 && c->n_q >= 1 && c->n_kv >= 1 && c->head_dim >= 2 &&
+                 c->d_ffn >= 1 && c->vocab >= 2 && c->kv_capacity >= 1,
+             DS_E_SHAPE, "model dimensions must be positive");
+  DS_REQUIRE(c->n_q % c->n_kv == 0, DS_E_SHAPE, "n_q %d is not a multiple of n_kv %d", c->n_q, c->n_kv);
+  DS_REQUIRE(c->d_model <= 8192, DS_E_SHAPE, "d_model %d exceeds 8192", c->d_model);
+  DS_REQUIRE(c->head_dim % 2 == 0 && c->head_dim <= 128, DS_E_UNSUPPORTED, "head_dim %d: need even and <= 128",
+             c->head_dim);
+  DS_REQUIRE(c->rope_base > 1.f && c->rms_eps >= 0.f, DS_E_INVALID, "rope_base must exceed 1, rms_eps >= 0");
+  if (c->dtype == DS_BF16) {
+    DS_REQUIRE(c->head_dim == 128, DS_E_UNSUPPORTED, "bf16 path needs head_dim 128 (got %d)", c->head_dim);
+    DS_REQUIRE(c->d_model % 128 == 0 && c->d_ffn % 128 == 0 && c->vocab % 16 == 0, DS_E_SHAPE,
+               "bf16 path needs d_model %% 128 == 0, d_ffn %% 128 == 0, vocab %% 16 == 0");
+    DS_REQUIRE(c->kv_capacity % 64 == 0, DS_E_SHAPE, "bf16 path needs kv_capacity %% 64 == 0 (got %d)",
+               c->kv_capacity);
+  }
+  return DS_OK;
+}
+
+size_t esize_of(int dtype) { return dtype == DS_BF16 ? 2 : 4; }
+
+size_t packed_bytes_of(const ds_model_cfg& c) {
+  if (c.dtype != DS_BF16) return 0;
+  const size_t d = c.d_model, f = c.d_ffn, qo = (size_t)c.n_q * c.head_dim;
+  const size_t per_layer = ((size_t)n_qkv(c) * d + d * qo + 2 * f * d + d * f) * 2;
+  return per_layer * c.n_layers + (size_t)c.vocab * d * 2;
+}
+
+size_t kv_bytes_of(const ds_model_cfg& c) {
+  return (size_t)c.n_layers * c.n_kv * c.kv_capacity * c.head_dim * esize_of(c.dtype);
+}
+
+int widest_split_floats(const ds_model_cfg& c, int rows, size_t* out) {
+  // largest rows x N x splits over the four projections of a layer
+  size_t best = 0;
+  const int d = c.d_model, f = c.d_ffn, qo = c.n_q * c.head_dim;
+  const int shapes[4][2] = {{n_qkv(c), d}, {d, qo}, {2 * f, d}, {d, f}};
+  for (auto& s : shapes) {
+    const int sp = c.dtype == DS_BF16 ? gemm_bf16_splits(s[0], s[1], 1) : 1;
+    const size_t v = (size_t)rows * s[0] * sp;
+    best = v > best ? v : best;
+  }
+  *out = best;
+  return DS_OK;
+}
+
+Workspace carve(const ds_model_cfg& c, int rows, void* base) {
+  Workspace w{};
+  const size_t es = esize_of(c.dtype);
+  const int rp = ceil_div(rows, 16) * 16;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    void* p = base ? static_cast<char*>(base) + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  w.tok = static_cast<int32_t*>(take((size_t)rows * 4));
+  w.x = static_cast<float*>(take((size_t)rows * c.d_model * 4));
+  w.cs = static_cast<float2*>(take((size_t)rows * (c.head_dim / 2) * 8));
+  w.h = take((size_t)rp * c.d_model * es);
+  w.q = take((size_t)c.n_q * rp * c.head_dim * es);
+  w.att = take((size_t)rp * c.n_q * c.head_dim * es);
+  w.act = take((size_t)rp * c.d_ffn * es);
+  w.y = take((size_t)rp * c.d_model * es);
+  size_t gf = 0;
+  widest_split_floats(c, rows, &gf);
+  w.gemm_out = static_cast<float*>(take(gf * 4));
+  const int max_split = attn_splits(c.dtype, c.kv_capacity);
+  w.att_o = static_cast<float*>(take((size_t)max_split * c.n_q * rp * c.head_dim * 4));
+  w.att_ml = static_cast<float*>(take((size_t)max_split * c.n_q * rp * 2 * 4));
+  w.logits = static_cast<float*>(take((size_t)rows * c.vocab * 4));
+  w.scan_bytes = accept_ws_bytes(rows, c.vocab);
+  w.scan = take(w.scan_bytes);
+  w.total = off;
+  return w;
+}
+
+template <typename T>
+int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float* out, int* n_split,
+         hipStream_t st) {
+  // which: 0 qkv, 1 o, 2 gate/up, 3 down, 4 lm head
+  const ds_model_cfg& c = m->cfg;
+  const int d = c.d_model, f = c.d_ffn, qo = c.n_q * c.head_dim;
+  int N = 0, K = 0;
+  switch (which) {
+    case 0: N = n_qkv(c); K = d; break;
+    case 1: N = d; K = qo; break;
+    case 2: N = 2 * f; K = d; break;
+    case 3: N = d; K = f; break;
+    default: N = c.vocab; K = d; break;
+  }
+  if (c.dtype == DS_BF16) {
+    const void* w = nullptr;
+    if (which == 4) w = m->lm_head;
+    else {
+      const PackedLayer& pl = m->packed[li];
+      w = which == 0 ? pl.wqkv : which == 1 ? pl.wo : which == 2 ? pl.wgu : pl.wdown;
+    }
+    const int nbw = which == 4 ? 2 : 1;
+    *n_split = which == 4 ? 1 : gemm_bf16_splits(N, K, nbw);
+    return launch_gemm_bf16(w, x_in, rows, N, K, nbw, *n_split, out, st);
+  }
+  *n_split = 1;
+  const float* x = static_cast<const float*>(x_in);
+  if (which == 4) return launch_gemm_f32(x, static_cast<const float*>(m->lm_head), rows, N, K, out, N, st);
+  const ds_layer_weights& lw = m->canon[li];
+  int rc = DS_OK;
+  switch (which) {
+    case 0: {
+      const int nq = c.n_q * c.head_dim, nk = c.n_kv * c.head_dim;
+      rc = launch_gemm_f32(x, static_cast<const float*>(lw.wq), rows, nq, K, out, N, st);
+      if (rc) return rc;
+      rc = launch_gemm_f32(x, static_cast<const float*>(lw.wk), rows, nk, K, out + nq, N, st);
+      if (rc) return rc;
+      return launch_gemm_f32(x, static_cast<const float*>(lw.wv), rows, nk, K, out + nq + nk, N, st);
+    }
+    case 1: return launch_gemm_f32(x, static_cast<const float*>(lw.wo), rows, N, K, out, N, st);
+    case 2:
+      rc = launch_gemm_f32(x, static_cast<const float*>(lw.w_gate), rows, f, K, out, N, st);
+      if (rc) return rc;
+      return launch_gemm_f32(x, static_cast<const float*>(lw.w_up), rows, f, K, out + f, N, st);
+    default: return launch_gemm_f32(x, static_cast<const float*>(lw.w_down), rows, N, K, out, N, st);
+  }
+}
+
+// Forward of `rows` token rows placed after the committed cache.  Rows [0, n_causal) are causal real
+// tokens, the rest are [MASK] rows.  Leaves the final-normed states of all rows in ws.y (GEMM input
+// order) and, if hidden_out is given, a row-major copy of rows >= hidden_row0 there.
+template <typename T>
+int forward_rows(ds_model* m, const Workspace& w, int rows, int n_causal, void* hidden_out, int hidden_row0,
+                 hipStream_t st) {
+  const ds_model_cfg& c = m->cfg;
+  const int rp = ceil_div(rows, 16) * 16;
+  const int pos0 = m->kv_len, n_keys = pos0 + rows;
+  const int d = c.d_model, hd = c.head_dim;
+  int rc;
+  if ((rc = launch_rope_table(pos0, rows, hd, (double)c.rope_base, w.cs, st))) return rc;
+  if ((rc = launch_embed_norm<T>(w.tok, m->embed, w.x, rows, d, m->canon[0].norm1, c.rms_eps, w.h, st))) return rc;
+  const int n_split_att = attn_splits(c.dtype, n_keys);
+  for (int li = 0; li < c.n_layers; ++li) {
+    const size_t layer_elems = (size_t)c.n_kv * c.kv_capacity * hd;
+    char* kc = static_cast<char*>(m->kv_k) + (size_t)li * layer_elems * m->esize;
+    char* vc = static_cast<char*>(m->kv_v) + (size_t)li * layer_elems * m->esize;
+    int sp = 1;
+    if ((rc = gemm<T>(m, li, 0, w.h, rows, w.gemm_out, &sp, st))) return rc;
+    if ((rc = launch_qkv_rope<T>(w.gemm_out, sp, rows, rp, c.n_q, c.n_kv, hd, w.cs, pos0, c.kv_capacity, w.q, kc, vc,
+                                 st)))
+      return rc;
+    if ((rc = launch_attention(c.dtype, w.q, kc, vc, rows, rp, n_causal, pos0, n_keys, c.n_q, c.n_kv, hd,
+                               c.kv_capacity, n_split_att, w.att_o, w.att_ml, w.att, st)))
+      return rc;
+    if ((rc = gemm<T>(m, li, 1, w.att, rows, w.gemm_out, &sp, st))) return rc;
+    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr, 0, st)))
+      return rc;
+    if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st))) return rc;
+    if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, c.d_ffn, w.act, st))) return rc;
+    if ((rc = gemm<T>(m, li, 3, w.act, rows, w.gemm_out, &sp, st))) return rc;
+    const bool last = li + 1 == c.n_layers;
+    const float* gain = last ? m->final_norm : m->canon[li + 1].norm1;
+    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, d, gain, c.rms_eps, last ? w.y : w.h,
+                                 last ? hidden_out : nullptr, hidden_row0, st)))
+      return rc;
+  }
+  return DS_OK;
+}
+
+int forward_dispatch(ds_model* m, const Workspace& w, int rows, int n_causal, void* hidden_out, int hidden_row0,
+                     hipStream_t st) {
+  return m->cfg.dtype == DS_BF16 ? forward_rows<bf16_t>(m, w, rows, n_causal, hidden_out, hidden_row0, st)
+                                 : forward_rows<float>(m, w, rows, n_causal, hidden_out, hidden_row0, st);
+}
+
+int lm_head_rows(ds_model* m, const void* y_gemm_in, int rows, float* logits, hipStream_t st) {
+  int sp = 1;
+  return m->cfg.dtype == DS_BF16 ? gemm<bf16_t>(m, 0, 4, y_gemm_in, rows, logits, &sp, st)
+                                 : gemm<float>(m, 0, 4, y_gemm_in, rows, logits, &sp, st);
+}
+
+int check_ws(const ds_model* m, int rows, void* ws, size_t ws_bytes, Workspace* out) {
+  DS_REQUIRE(ws, DS_E_INVALID, "workspace is NULL");
+  DS_REQUIRE((((uintptr_t)ws) & 255) == 0, DS_E_INVALID, "workspace not 256-byte aligned");
+  *out = carve(m->cfg, rows, ws);
+  DS_REQUIRE(ws_bytes >= out->total, DS_E_CAPACITY, "workspace: %d rows need %zu bytes, got %zu", rows, out->total,
+             ws_bytes);
+  return DS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ds_model_packed_bytes(const ds_model_cfg* cfg, size_t* bytes) {
+  DS_REQUIRE(bytes, DS_E_INVALID, "bytes is NULL");
+  int rc = validate_cfg(cfg);
+  if (rc) return rc;
+  *bytes = packed_bytes_of(*cfg);
+  return DS_OK;
+}
+
+int ds_kv_bytes(const ds_model_cfg* cfg, size_t* bytes) {
+  DS_REQUIRE(bytes, DS_E_INVALID, "bytes is NULL");
+  int rc = validate_cfg(cfg);
+  if (rc) return rc;
+  *bytes = kv_bytes_of(*cfg);
+  return DS_OK;
+}
+
+int ds_workspace_bytes(const ds_model_cfg* cfg, int max_rows, size_t* bytes) {
+  DS_REQUIRE(bytes, DS_E_INVALID, "bytes is NULL");
+  int rc = validate_cfg(cfg);
+  if (rc) return rc;
+  DS_REQUIRE(max_rows >= 1 && max_rows <= DS_MAX_ROWS, DS_E_SHAPE, "max_rows %d outside [1, %d]", max_rows,
+             DS_MAX_ROWS);
+  *bytes = carve(*cfg, max_rows, nullptr).total;
+  return DS_OK;
+}
+
+int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, size_t packed_bytes, void* kv_k,
+                    void* kv_v, void* stream, ds_model** out) {
+  DS_REQUIRE(out, DS_E_INVALID, "out is NULL");
+  *out = nullptr;
+  int rc = validate_cfg(cfg);
+  if (rc) return rc;
+  DS_REQUIRE(w && w->embed && w->layers && w->final_norm && w->lm_head, DS_E_INVALID, "weights: NULL pointer");
+  DS_REQUIRE(kv_k && kv_v, DS_E_INVALID, "KV buffers: NULL pointer");
+  DS_REQUIRE((((uintptr_t)kv_k | (uintptr_t)kv_v | (uintptr_t)w->embed | (uintptr_t)w->lm_head) & 15) == 0,
+             DS_E_INVALID, "KV buffers and matrices must be 16-byte aligned");
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const ds_layer_weights& lw = w->layers[l];
+    DS_REQUIRE(lw.wq && lw.wk && lw.wv && lw.wo && lw.w_gate && lw.w_up && lw.w_down && lw.norm1 && lw.norm2,
+               DS_E_INVALID, "layer %d: NULL weight pointer", l);
+  }
+  const size_t need = packed_bytes_of(*cfg);
+  if (need) {
+    DS_REQUIRE(packed, DS_E_INVALID, "packed buffer is NULL");
+    DS_REQUIRE((((uintptr_t)packed) & 255) == 0, DS_E_INVALID, "packed buffer not 256-byte aligned");
+    DS_REQUIRE(packed_bytes >= need, DS_E_CAPACITY, "packed buffer: need %zu bytes, got %zu", need, packed_bytes);
+  }
+  ds_model* m = new (std::nothrow) ds_model();
+  DS_REQUIRE(m, DS_E_INVALID, "out of host memory");
+  m->cfg = *cfg;
+  m->embed = w->embed;
+  m->canon.assign(w->layers, w->layers + cfg->n_layers);
+  m->final_norm = w->final_norm;
+  m->kv_k = kv_k;
+  m->kv_v = kv_v;
+  m->kv_len = 0;
+  m->esize = esize_of(cfg->dtype);
+  m->lm_head = w->lm_head;
+  if (cfg->dtype == DS_BF16) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* p = static_cast<char*>(packed);
+    const int d = cfg->d_model, f = cfg->d_ffn, hd = cfg->head_dim, qo = cfg->n_q * hd, kvn = cfg->n_kv * hd;
+    auto put = [&](const void* src, int N, int K) -> int {
+      int r = launch_pack_weight(src, N, K, p, st);
+      p += (size_t)N * K * 2;
+      return r;
+    };
+    for (int l = 0; l < cfg->n_layers && !rc; ++l) {
+      const ds_layer_weights& lw = w->layers[l];
+      PackedLayer pl{};
+      pl.wqkv = p;
+      if ((rc = put(lw.wq, qo, d)) || (rc = put(lw.wk, kvn, d)) || (rc = put(lw.wv, kvn, d))) break;
+      pl.wo = p;
+      if ((rc = put(lw.wo, d, qo))) break;
+      pl.wgu = p;
+      if ((rc = put(lw.w_gate, f, d)) || (rc = put(lw.w_up, f, d))) break;
+      pl.wdown = p;
+      if ((rc = put(lw.w_down, d, f))) break;
+      m->packed.push_back(pl);
+    }
+    if (!rc) {
+      m->lm_head = p;
+      rc = put(w->lm_head, cfg->vocab, d);
+    }
+    if (rc) {
+      delete m;
+      return rc;
+    }
+  }
+  *out = m;
+  return DS_OK;
+}
+
+void ds_model_destroy(ds_model* m) { delete m; }
+
+int ds_model_kv_len(const ds_model* m, int* len) {
+  DS_REQUIRE(m && len, DS_E_INVALID, "ds_model_kv_len: NULL pointer argument");
+  *len = m->kv_len;
+  return DS_OK;
+}
+
+int ds_model_kv_set_len(ds_model* m, int len) {
+  DS_REQUIRE(m, DS_E_INVALID, "model is NULL");
+  DS_REQUIRE(len >= 0 && len <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV length %d outside [0, %d]", len,
+             m->cfg.kv_capacity);
+  m->kv_len = len;
+  return DS_OK;
+}
+
+int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, void* ws, size_t ws_bytes,
+               void* stream) {
+  DS_REQUIRE(m && tokens, DS_E_INVALID, "ds_prefill: NULL pointer argument");
+  DS_REQUIRE(n >= 1, DS_E_SHAPE, "n %d must be >= 1", n);
+  DS_REQUIRE(m->kv_len + n <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d tokens exceed capacity %d",
+             m->kv_len, n, m->cfg.kv_capacity);
+  // largest chunk the workspace can carry
+  int chunk = n < DS_MAX_ROWS ? n : DS_MAX_ROWS;
+  DS_REQUIRE(ws, DS_E_INVALID, "workspace is NULL");
+  while (chunk > 1 && carve(m->cfg, chunk, nullptr).total > ws_bytes) chunk = chunk > 16 ? chunk - 16 : chunk - 1;
+  Workspace w;
+  int rc = check_ws(m, chunk, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int start_len = m->kv_len;
+  for (int done = 0; done < n; done += chunk) {
+    const int rows = n - done < chunk ? n - done : chunk;
+    w = carve(m->cfg, rows, ws);
+    if ((rc = launch_tokens(tokens + done, rows, rows, 0, m->cfg.vocab, w.tok, st)) ||
+        (rc = forward_dispatch(m, w, rows, rows, nullptr, 0, st))) {
+      m->kv_len = start_len;
+      return rc;
+    }
+    m->kv_len += rows;
+    if (last_logits && done + rows == n) {
+      // logits of all rows of the last chunk, then copy the last row out
+      if ((rc = lm_head_rows(m, w.y, rows, w.logits, st))) return rc;
+      DS_HIP_CHECK(hipMemcpyAsync(last_logits, w.logits + (size_t)(rows - 1) * m->cfg.vocab,
+                                  (size_t)m->cfg.vocab * 4, hipMemcpyDeviceToDevice, st));
+    }
+  }
+  return DS_OK;
+}
+
+int ds_draft_block(ds_model* m, const int32_t* pending, int n_pend, int K, int32_t mask_id, void* hidden_out,
+                   void* ws, size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m && hidden_out, DS_E_INVALID, "ds_draft_block: NULL pointer argument");
+  DS_REQUIRE(n_pend >= 0 && K >= 1, DS_E_SHAPE, "need n_pend >= 0 and K >= 1 (got %d, %d)", n_pend, K);
+  DS_REQUIRE(pending || n_pend == 0, DS_E_INVALID, "pending is NULL while n_pend > 0");
+  const int rows = n_pend + K;
+  DS_REQUIRE(rows <= DS_MAX_ROWS, DS_E_SHAPE, "n_pend + K = %d exceeds %d rows", rows, DS_MAX_ROWS);
+  DS_REQUIRE(mask_id >= 0 && mask_id < m->cfg.vocab, DS_E_INVALID, "mask_id %d outside the vocabulary", mask_id);
+  DS_REQUIRE(m->kv_len + rows <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d rows exceed capacity %d",
+             m->kv_len, rows, m->cfg.kv_capacity);
+  Workspace w;
+  int rc = check_ws(m, rows, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = launch_tokens(pending, n_pend, rows, mask_id, m->cfg.vocab, w.tok, st))) return rc;
+  if ((rc = forward_dispatch(m, w, rows, n_pend, hidden_out, n_pend, st))) return rc;
+  m->kv_len += n_pend;  // mask rows are never committed
+  return DS_OK;
+}
+
+int ds_lm_head(ds_model* m, const void* hidden, int rows, float* logits, void* ws, size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m && hidden && logits, DS_E_INVALID, "ds_lm_head: NULL pointer argument");
+  DS_REQUIRE(rows >= 1 && rows <= DS_MAX_ROWS, DS_E_SHAPE, "rows %d outside [1, %d]", rows, DS_MAX_ROWS);
+  Workspace w;
+  int rc = check_ws(m, rows, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (m->cfg.dtype == DS_BF16) {
+    if ((rc = launch_to_gemm_input<bf16_t>(hidden, rows, m->cfg.d_model, w.y, st))) return rc;
+    return lm_head_rows(m, w.y, rows, logits, st);
+  }
+  return lm_head_rows(m, hidden, rows, logits, st);
+}
+
+int ds_verify_block(ds_model* m, const int32_t* block, int mlen, const int32_t* path_len, int32_t eos_id,
+                    int32_t* n_accept, int32_t* next_token, int32_t* argmax, int32_t* eos_accepted,
+                    float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m && block && n_accept && next_token && argmax && eos_accepted, DS_E_INVALID,
+             "ds_verify_block: NULL pointer argument");
+  DS_REQUIRE(mlen >= 0 && mlen + 1 <= DS_MAX_ROWS, DS_E_SHAPE, "m = %d: m + 1 rows outside [1, %d]", mlen,
+             DS_MAX_ROWS);
+  DS_REQUIRE(eos_id < m->cfg.vocab, DS_E_INVALID, "eos_id %d >= vocab", eos_id);
+  const int rows = mlen + 1;
+  DS_REQUIRE(m->kv_len + rows <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d rows exceed capacity %d",
+             m->kv_len, rows, m->cfg.kv_capacity);
+  Workspace w;
+  int rc = check_ws(m, rows, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = launch_tokens(block, rows, rows, 0, m->cfg.vocab, w.tok, st))) return rc;
+  if ((rc = forward_dispatch(m, w, rows, rows, nullptr, 0, st))) return rc;
+  float* logits = logits_out ? logits_out : w.logits;
+  if ((rc = lm_head_rows(m, w.y, rows, logits, st))) return rc;
+  return launch_argmax_accept(logits, rows, m->cfg.vocab, block, path_len, eos_id, n_accept, next_token, argmax,
+                              eos_accepted, w.scan, w.scan_bytes, st);
+}
+
+}  // extern "C"

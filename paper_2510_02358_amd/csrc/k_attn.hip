@@ -1,0 +1,317 @@
+// Grouped-query attention of a few query rows against the KV cache (cached prefix + the rows of the
+// current call), split over the key axis ("flash-decoding" style) with an exact log-sum-exp merge.
+//
+// Visibility: row r (absolute position pos0 + r) sees key p iff p < n_keys and
+//   r >= n_causal (a [MASK] row of the draft block: sees everything)  or  p <= pos0 + r (causal).
+//
+// bf16 kernel (head_dim 128): the query rows of all heads that share a KV head are packed together,
+// so one pass over that head's keys/values serves group x rows query rows; both products run on the
+// 16x16x32 bf16 matrix cores.  Scores are computed transposed, S^T = K Q^T, because the accumulator
+// layout of S^T (lane = query row, 4 consecutive keys per register quad) is already the operand
+// layout the second product P V needs: probabilities never leave registers.  For that product the
+// value cache is stored transposed ([head_dim][capacity]) so that a lane reads its keys contiguously.
+// K and V^T chunks of 64 keys are staged once per workgroup into LDS in operand order.
+//
+// f32 kernel: plain ALU version for the float32 parity mode (any head_dim <= 128).
+#include <math.h>
+
+#include "ds_act.h"
+#include "ds_common.h"
+
+namespace ds {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kChunk = 64;  // keys per staged chunk
+constexpr int kHd = 128;    // head_dim of the bf16 kernel
+
+union Pack8 {
+  bf16x8 v;
+  uint16_t h[8];
+  uint2 half[2];
+  uint4 q;
+};
+
+template <int QB>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restrict__ q,
+                                                        const uint16_t* __restrict__ kc,
+                                                        const uint16_t* __restrict__ vt, int rows_pad,
+                                                        int n_causal, int pos0, int n_keys, int n_q, int n_kv,
+                                                        int cap, int chunks_per_split, float scale,
+                                                        float* __restrict__ part_o, float* __restrict__ part_ml) {
+  __shared__ __attribute__((aligned(16))) uint16_t ks_lds[16 * 512];
+  __shared__ __attribute__((aligned(16))) uint16_t vs_lds[16 * 512];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int split = blockIdx.x, kvh = blockIdx.y;
+  const int group = n_q / n_kv, rb_count = rows_pad >> 4, n_qb = group * rb_count;
+  const int n_chunks = (n_keys + kChunk - 1) / kChunk;
+  const int c_begin = split * chunks_per_split;
+  int c_end = c_begin + chunks_per_split;
+  if (c_end > n_chunks) c_end = n_chunks;
+
+  int qb[QB], head[QB], rb[QB];
+  bool valid[QB];
+  bf16x8 bq[QB][4];
+  f32x4 o[QB][8];
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int t = 0; t < QB; ++t) {
+    qb[t] = (blockIdx.z * 4 + wave) * QB + t;
+    valid[t] = qb[t] < n_qb;
+    const int qbc = valid[t] ? qb[t] : 0;
+    head[t] = kvh * group + qbc / rb_count;
+    rb[t] = qbc % rb_count;
+    const uint16_t* qh = q + (size_t)head[t] * rows_pad * kHd + (size_t)rb[t] * 4 * 512;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) bq[t][s] = *reinterpret_cast<const bf16x8*>(qh + s * 512 + lane * 8);
+#pragma unroll
+    for (int d = 0; d < 8; ++d) o[t][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m_run[t] = -INFINITY;
+    l_run[t] = 0.f;
+  }
+
+  const uint16_t* kbase = kc + (size_t)kvh * cap * kHd;
+  const uint16_t* vbase = vt + (size_t)kvh * kHd * cap;
+
+  for (int c = c_begin; c < c_end; ++c) {
+    const int c0 = c * kChunk;
+    __syncthreads();  // previous chunk fully consumed
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int tile = wave + 4 * p;
+      {  // K tile (kb, ks): lane (16 g + i) <- K[c0 + 16 kb + i][32 ks + 8 g ..]
+        const int kb = tile >> 2, s = tile & 3;
+        int key = c0 + kb * 16 + j;
+        key = key < n_keys ? key : n_keys - 1;
+        const uint4 v = *reinterpret_cast<const uint4*>(kbase + (size_t)key * kHd + s * 32 + g * 8);
+        *reinterpret_cast<uint4*>(&ks_lds[(tile * 64 + lane) * 8]) = v;
+      }
+      {  // V^T tile (db, t2): lane (16 g + i) <- V^T[16 db + i][c0 + 32 t2 + {4g..4g+3, 16+4g..16+4g+3}]
+        const int db = tile >> 1, t2 = tile & 1;
+        const uint16_t* src = vbase + (size_t)(db * 16 + j) * cap + c0 + 32 * t2 + 4 * g;
+        Pack8 pk;
+        pk.half[0] = *reinterpret_cast<const uint2*>(src);
+        pk.half[1] = *reinterpret_cast<const uint2*>(src + 16);
+        if (c0 + kChunk > n_keys) {  // tail chunk: slots past the last key may hold anything -> zero
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int key = c0 + 32 * t2 + 4 * g + (e & 3) + ((e >> 2) << 4);
+            if (key >= n_keys) pk.h[e] = 0;
+          }
+        }
+        *reinterpret_cast<uint4*>(&vs_lds[(tile * 64 + lane) * 8]) = pk.q;
+      }
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int t = 0; t < QB; ++t) {
+      if (!valid[t]) continue;
+      f32x4 s4[4];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) {
+        s4[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ks_lds[((kb * 4 + s) * 64 + lane) * 8]);
+          s4[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[t][s], s4[kb], 0, 0, 0);
+        }
+      }
+      // s4[kb][e] = score of key c0 + 16 kb + 4 g + e for query row 16 rb + j
+      const int r = rb[t] * 16 + j;
+      const int limit = (r >= n_causal) ? n_keys - 1 : pos0 + r;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int key = c0 + kb * 16 + 4 * g + e;
+          const float sv = (key <= limit && key < n_keys) ? s4[kb][e] * scale : -INFINITY;
+          s4[kb][e] = sv;
+          mx = fmaxf(mx, sv);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[t], mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __expf(m_run[t] - m_use);
+      float psum = 0.f;
+      Pack8 pb[2];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p = __expf(s4[kb][e] - m_use);
+          psum += p;
+          pb[kb >> 1].h[(kb & 1) * 4 + e] = float_to_bf16_bits(p);
+        }
+      l_run[t] = l_run[t] * alpha + psum;
+      m_run[t] = m_new;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) {
+        o[t][d] *= alpha;
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vs_lds[((d * 2 + t2) * 64 + lane) * 8]);
+          o[t][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[t2].v, o[t][d], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+#pragma unroll
+  for (int t = 0; t < QB; ++t) {
+    if (!valid[t]) continue;
+    float l = l_run[t];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const int r = rb[t] * 16 + j;
+    const size_t row = ((size_t)split * n_q + head[t]) * rows_pad + r;
+#pragma unroll
+    for (int d = 0; d < 8; ++d)
+      *reinterpret_cast<float4*>(part_o + row * kHd + d * 16 + 4 * g) =
+          make_float4(o[t][d][0], o[t][d][1], o[t][d][2], o[t][d][3]);
+    if (g == 0) *reinterpret_cast<float2*>(part_ml + row * 2) = make_float2(m_run[t], l);
+  }
+}
+
+// float32 parity mode.  grid (n_split, n_q); each wavefront walks rows r = wave, wave + 4, ...
+__global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__ q, const float* __restrict__ kc,
+                                                       const float* __restrict__ vc, int rows, int rows_pad,
+                                                       int n_causal, int pos0, int n_keys, int n_q, int n_kv,
+                                                       int hd, int cap, int chunks_per_split, float scale,
+                                                       float* __restrict__ part_o, float* __restrict__ part_ml) {
+  __shared__ float qbuf[4][128];
+  __shared__ float pbuf[4][kChunk];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int split = blockIdx.x, head = blockIdx.y;
+  const int kvh = head / (n_q / n_kv);
+  const int n_chunks = (n_keys + kChunk - 1) / kChunk;
+  const int c_begin = split * chunks_per_split;
+  int c_end = c_begin + chunks_per_split;
+  if (c_end > n_chunks) c_end = n_chunks;
+  const float* kh = kc + (size_t)kvh * cap * hd;
+  const float* vh = vc + (size_t)kvh * cap * hd;
+
+  for (int r = wave; r < rows; r += 4) {
+    const float* qr = q + ((size_t)head * rows_pad + r) * hd;
+    for (int d = lane; d < hd; d += 64) qbuf[wave][d] = qr[d];
+    __builtin_amdgcn_wave_barrier();
+    const int limit = (r >= n_causal) ? n_keys - 1 : pos0 + r;
+    float m_run = -INFINITY, l_run = 0.f, o0 = 0.f, o1 = 0.f;
+    for (int c = c_begin; c < c_end; ++c) {
+      const int key = c * kChunk + lane;
+      float s = -INFINITY;
+      if (key < n_keys && key <= limit) {
+        const float* kr = kh + (size_t)key * hd;
+        float acc = 0.f;
+        for (int d = 0; d < hd; ++d) acc = fmaf(qbuf[wave][d], kr[d], acc);
+        s = acc * scale;
+      }
+      float mx = s;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+      const float m_new = fmaxf(m_run, mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = expf(m_run - m_use);
+      const float p = expf(s - m_use);
+      float ps = p;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) ps += __shfl_xor(ps, off);
+      l_run = l_run * alpha + ps;
+      m_run = m_new;
+      pbuf[wave][lane] = p;
+      __builtin_amdgcn_wave_barrier();
+      o0 *= alpha;
+      o1 *= alpha;
+      const int kmax = min(kChunk, n_keys - c * kChunk);
+      for (int jj = 0; jj < kmax; ++jj) {
+        const float pj = pbuf[wave][jj];
+        const float* vr = vh + (size_t)(c * kChunk + jj) * hd;
+        if (lane < hd) o0 = fmaf(pj, vr[lane], o0);
+        if (lane + 64 < hd) o1 = fmaf(pj, vr[lane + 64], o1);
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+    const size_t row = ((size_t)split * n_q + head) * rows_pad + r;
+    if (lane < hd) part_o[row * hd + lane] = o0;
+    if (lane + 64 < hd) part_o[row * hd + lane + 64] = o1;
+    if (lane == 0) {
+      part_ml[row * 2 + 0] = m_run;
+      part_ml[row * 2 + 1] = l_run;
+    }
+  }
+}
+
+// Exact merge of the per-split partial results: out = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M).
+template <typename T>
+__global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int n_split,
+                                  int n_q, int rows_pad, int hd, T* __restrict__ att) {
+  const int r = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
+  if (d >= hd) return;
+  float mx = -INFINITY;
+  for (int s = 0; s < n_split; ++s)
+    mx = fmaxf(mx, part_ml[(((size_t)s * n_q + head) * rows_pad + r) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < n_split; ++s) {
+    const size_t row = ((size_t)s * n_q + head) * rows_pad + r;
+    const float m = part_ml[row * 2], l = part_ml[row * 2 + 1];
+    if (m == -INFINITY) continue;
+    const float w = expf(m - mx);
+    num += part_o[row * hd + d] * w;
+    den += l * w;
+  }
+  att[Act<T>::off(r, head * hd + d, n_q * hd)] = Act<T>::from_float(num / den);
+}
+
+int chunks_per_split(int dtype, int n_keys) {
+  const int n_chunks = ceil_div(n_keys, kChunk);
+  const int max_split = dtype == DS_BF16 ? 32 : 16;
+  return ceil_div(n_chunks, max_split);
+}
+
+}  // namespace
+
+int attn_splits(int dtype, int n_keys) {
+  return ceil_div(ceil_div(n_keys, kChunk), chunks_per_split(dtype, n_keys));
+}
+
+size_t attn_partial_floats(int n_split, int n_q, int rows_pad, int hd) {
+  return (size_t)n_split * n_q * rows_pad * (hd + 2);
+}
+
+int launch_attention(int dtype, const void* q, const void* kc, const void* vc, int rows, int rows_pad, int n_causal,
+                     int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, int n_split, float* part_o,
+                     float* part_ml, void* att_out, hipStream_t st) {
+  const float scale = 1.0f / sqrtf((float)hd);
+  const int cps = chunks_per_split(dtype, n_keys);
+  if (dtype == DS_BF16) {
+    DS_REQUIRE(hd == kHd, DS_E_UNSUPPORTED, "bf16 attention needs head_dim 128 (got %d)", hd);
+    const int n_qb = (n_q / n_kv) * (rows_pad >> 4);
+    constexpr int QB = 2;
+    dim3 grid(n_split, n_kv, ceil_div(n_qb, 4 * QB));
+    hipLaunchKernelGGL((attn_bf16_kernel<QB>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
+                       static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc), rows_pad, n_causal, pos0,
+                       n_keys, n_q, n_kv, cap, cps, scale, part_o, part_ml);
+    DS_LAUNCH_CHECK("attn_bf16_kernel");
+    hipLaunchKernelGGL((attn_merge_kernel<bf16_t>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, n_split, n_q,
+                       rows_pad, hd, static_cast<bf16_t*>(att_out));
+    DS_LAUNCH_CHECK("attn_merge_kernel<bf16>");
+  } else {
+    DS_REQUIRE(hd <= 128 && (hd & 1) == 0, DS_E_UNSUPPORTED, "f32 attention needs even head_dim <= 128 (got %d)", hd);
+    hipLaunchKernelGGL(attn_f32_kernel, dim3(n_split, n_q), dim3(256), 0, st, static_cast<const float*>(q),
+                       static_cast<const float*>(kc), static_cast<const float*>(vc), rows, rows_pad, n_causal, pos0,
+                       n_keys, n_q, n_kv, hd, cap, cps, scale, part_o, part_ml);
+    DS_LAUNCH_CHECK("attn_f32_kernel");
+    hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, n_split, n_q,
+                       rows_pad, hd, static_cast<float*>(att_out));
+    DS_LAUNCH_CHECK("attn_merge_kernel<f32>");
+  }
+  return DS_OK;
+}
+
+}  // namespace ds

@@ -1,0 +1,258 @@
+// Skinny-M GEMMs: out[M, N] = X[M, K] * W[N, K]^T with M <= 144 rows.
+//
+// Every projection of the round (QKV, O, gate/up, down, LM head) has this shape, and with so few
+// rows each one is a weight stream: every weight byte is read exactly once, so the kernel is bound
+// by HBM bandwidth, not by the matrix cores.  MFMA is used because the work is a dense contraction
+// and plain ALUs would become the limiter at M = 33..130.
+//
+// bf16 path
+//   * W is kept in "stream order": tiles of 16 output rows x 32 inputs, 1 KB each, laid out
+//     [N/16][K/32][64 lanes][8 bf16] so that lane (16 g + i) holds W[16 nb + i][32 ks + 8 g .. + 7].
+//     That is exactly the register image of the 16x16x32 MFMA's first operand: a wavefront reads
+//     one tile with one fully coalesced 16-byte-per-lane load and feeds it to the matrix core
+//     with no LDS round trip.  A wavefront walks K for its NB row blocks, so its loads form NB
+//     contiguous streams.
+//   * X (tile order, see xt_offset) is staged through LDS in chunks of 128 columns and shared by
+//     the 4 wavefronts of the workgroup; weight tiles for the next chunk are already in flight
+//     while the current chunk is multiplied.
+//   * D[i][j] of the MFMA = out[16 mb + j][16 nb + i]: lane (16 g + j) ends with 4 consecutive
+//     output columns of row j, stored as one float4.
+//   * Split-K writes float32 partial planes out[s][M][N]; the consumer kernel sums them in a fixed
+//     order (deterministic, no atomics).
+//
+// f32 path: a plain wavefront-per-output-column kernel for the float32 parity mode.
+#include "ds_common.h"
+
+namespace ds {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kGemmThreads = 256;
+constexpr int kKSC = 4;  // k-steps (of 32) per LDS chunk: 128 columns
+
+// Copy a canonical row-major bf16 matrix W[N, K] into stream order.  One thread per 16-byte piece.
+__global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K, uint16_t* __restrict__ dst) {
+  const size_t piece = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t n_piece = (size_t)N * K / 8;
+  if (piece >= n_piece) return;
+  const int lane = piece & 63;
+  const size_t tile = piece >> 6;
+  const int ksteps = K >> 5;
+  const int ks = (int)(tile % ksteps);
+  const int nb = (int)(tile / ksteps);
+  const int i = lane & 15, g = lane >> 4;
+  const uint4 v = *reinterpret_cast<const uint4*>(w + (size_t)(nb * 16 + i) * K + ks * 32 + g * 8);
+  *reinterpret_cast<uint4*>(dst + piece * 8) = v;
+}
+
+template <int MB, int NB>
+__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
+                                                                 const uint16_t* __restrict__ xt, int M, int N,
+                                                                 int K, int chunks_per_split,
+                                                                 float* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) uint16_t xs[2][MB * kKSC * 512];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_blocks = N >> 4, ksteps = K >> 5, n_chunks = ksteps / kKSC;
+  const int c_begin = blockIdx.y * chunks_per_split;
+  int c_end = c_begin + chunks_per_split;
+  if (c_end > n_chunks) c_end = n_chunks;
+
+  int nb[NB];
+  const uint16_t* wrow[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    nb[b] = (blockIdx.x * 4 + wave) * NB + b;
+    const int nbc = nb[b] < n_blocks ? nb[b] : n_blocks - 1;  // clamp: loads stay in bounds, result dropped
+    wrow[b] = wp + ((size_t)nbc * ksteps) * 512 + lane * 8;
+  }
+
+  f32x4 acc[NB][MB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int m = 0; m < MB; ++m) acc[b][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  constexpr int kPieces = MB * kKSC * 64;  // 16-byte pieces of X per chunk
+  constexpr int kXPer = (kPieces + kGemmThreads - 1) / kGemmThreads;
+  uint4 xreg[kXPer];
+  bf16x8 areg[2][NB][kKSC];
+
+  auto load_x = [&](int c) {
+#pragma unroll
+    for (int p = 0; p < kXPer; ++p) {
+      const int piece = threadIdx.x + p * kGemmThreads;
+      if (piece < kPieces) {
+        const int mb = piece / (kKSC * 64), rest = piece - mb * (kKSC * 64);
+        xreg[p] = *reinterpret_cast<const uint4*>(xt + ((size_t)mb * ksteps + (size_t)c * kKSC) * 512 + rest * 8);
+      }
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < kXPer; ++p) {
+      const int piece = threadIdx.x + p * kGemmThreads;
+      if (piece < kPieces) *reinterpret_cast<uint4*>(&xs[buf][piece * 8]) = xreg[p];
+    }
+  };
+  auto load_a = [&](int set, int c) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int s = 0; s < kKSC; ++s)
+        areg[set][b][s] = *reinterpret_cast<const bf16x8*>(wrow[b] + ((size_t)c * kKSC + s) * 512);
+  };
+  auto compute = [&](int set, int buf) {
+#pragma unroll
+    for (int s = 0; s < kKSC; ++s) {
+      bf16x8 bx[MB];
+#pragma unroll
+      for (int m = 0; m < MB; ++m)
+        bx[m] = *reinterpret_cast<const bf16x8*>(&xs[buf][((m * kKSC + s) * 64 + lane) * 8]);
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int m = 0; m < MB; ++m)
+          acc[b][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[set][b][s], bx[m], acc[b][m], 0, 0, 0);
+    }
+  };
+
+  if (c_begin < c_end) {
+    load_a(0, c_begin);
+    load_x(c_begin);
+    store_x(0);
+    __syncthreads();
+    int buf = 0;
+    for (int c = c_begin; c < c_end; c += 2) {
+      // even step: registers set 0 hold chunk c
+      if (c + 1 < c_end) {
+        load_a(1, c + 1);
+        load_x(c + 1);
+      }
+      compute(0, buf);
+      if (c + 1 < c_end) store_x(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
+      if (c + 1 >= c_end) break;
+      // odd step: registers set 1 hold chunk c + 1
+      if (c + 2 < c_end) {
+        load_a(0, c + 2);
+        load_x(c + 2);
+      }
+      compute(1, buf);
+      if (c + 2 < c_end) store_x(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+
+  // D[i][j]: lane (16 g + j) holds rows i = 4 g .. 4 g + 3 of column j  ->  out[m = 16 mb + j][n = 16 nb + 4 g ..]
+  const int j = lane & 15, g = lane >> 4;
+  float* plane = out + (size_t)blockIdx.y * M * N;
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    if (nb[b] >= n_blocks) continue;
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+      const int row = m * 16 + j;
+      if (row < M) {
+        float4 v = make_float4(acc[b][m][0], acc[b][m][1], acc[b][m][2], acc[b][m][3]);
+        *reinterpret_cast<float4*>(plane + (size_t)row * N + nb[b] * 16 + g * 4) = v;
+      }
+    }
+  }
+}
+
+// float32 parity mode: one wavefront per output column n, lanes stride over k, rows in blocks of 8.
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                       int M, int N, int K, float* __restrict__ out, int ldc) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  const float* wr = w + (size_t)n * K;
+  for (int m0 = 0; m0 < M; m0 += 8) {
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int k = lane; k < K; k += 64) {
+      const float wv = wr[k];
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (m0 + i < M) acc[i] = fmaf(x[(size_t)(m0 + i) * K + k], wv, acc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float v = acc[i];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+      if (lane == 0 && m0 + i < M) out[(size_t)(m0 + i) * ldc + n] = v;
+    }
+  }
+}
+
+template <int MB>
+int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, int nbw, int n_split, float* out,
+                   hipStream_t st) {
+  const int n_chunks = (K >> 5) / kKSC;
+  const int cps = ceil_div(n_chunks, n_split);
+  dim3 grid(ceil_div(N >> 4, 4 * nbw), n_split);
+  if (nbw == 1)
+    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 1>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, cps, out);
+  else
+    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 2>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, cps, out);
+  DS_LAUNCH_CHECK("gemm_bf16_kernel");
+  return DS_OK;
+}
+
+}  // namespace
+
+int launch_pack_weight(const void* w, int N, int K, void* dst, hipStream_t st) {
+  DS_REQUIRE((N & 15) == 0 && (K & 127) == 0, DS_E_SHAPE,
+             "bf16 matrix [%d, %d]: rows must be a multiple of 16 and columns of 128", N, K);
+  const size_t n_piece = (size_t)N * K / 8;
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n_piece + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const uint16_t*>(w), N, K, static_cast<uint16_t*>(dst));
+  DS_LAUNCH_CHECK("pack_weight_kernel");
+  return DS_OK;
+}
+
+// Number of float32 partial planes gemm_bf16 will write for this shape (the consumer sums them).
+int gemm_bf16_splits(int N, int K, int nbw) {
+  const int units = ceil_div(N >> 4, 4 * nbw);
+  const int n_chunks = (K >> 5) / kKSC;
+  int s = ceil_div(640, units);
+  if (s > 8) s = 8;
+  if (s > n_chunks) s = n_chunks;
+  if (s < 1) s = 1;
+  const int cps = ceil_div(n_chunks, s);
+  return ceil_div(n_chunks, cps);
+}
+
+int launch_gemm_bf16(const void* wp, const void* xt, int M, int N, int K, int nbw, int n_split, float* out,
+                     hipStream_t st) {
+  DS_REQUIRE(M >= 1 && M <= DS_MAX_ROWS, DS_E_SHAPE, "GEMM rows %d outside [1, %d]", M, DS_MAX_ROWS);
+  DS_REQUIRE((N & 15) == 0 && (K & 127) == 0, DS_E_SHAPE, "GEMM [%d x %d]: N %% 16 and K %% 128 must be 0", N, K);
+  const uint16_t* w = static_cast<const uint16_t*>(wp);
+  const uint16_t* x = static_cast<const uint16_t*>(xt);
+  switch (ceil_div(M, 16)) {
+    case 1: return launch_bf16_mb<1>(w, x, M, N, K, nbw, n_split, out, st);
+    case 2: return launch_bf16_mb<2>(w, x, M, N, K, nbw, n_split, out, st);
+    case 3: return launch_bf16_mb<3>(w, x, M, N, K, nbw, n_split, out, st);
+    case 4: return launch_bf16_mb<4>(w, x, M, N, K, nbw, n_split, out, st);
+    case 5: return launch_bf16_mb<5>(w, x, M, N, K, nbw, n_split, out, st);
+    case 6: return launch_bf16_mb<6>(w, x, M, N, K, nbw, n_split, out, st);
+    case 7: return launch_bf16_mb<7>(w, x, M, N, K, nbw, n_split, out, st);
+    case 8: return launch_bf16_mb<8>(w, x, M, N, K, nbw, n_split, out, st);
+    default: return launch_bf16_mb<9>(w, x, M, N, K, nbw, n_split, out, st);
+  }
+}
+
+int launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* out, int ldc, hipStream_t st) {
+  hipLaunchKernelGGL(gemm_f32_kernel, dim3(ceil_div(N, 4)), dim3(256), 0, st, x, w, M, N, K, out, ldc);
+  DS_LAUNCH_CHECK("gemm_f32_kernel");
+  return DS_OK;
+}
+
+}  // namespace ds

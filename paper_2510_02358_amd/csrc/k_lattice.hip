@@ -1,0 +1,315 @@
+// Vocabulary-wide scans: token lattice (log-sum-exp + per-row top-M) and greedy acceptance
+// (per-row arg-max, compare with the drafted path, longest accepted prefix).
+//
+// Both are one pass over the float32 logits, 4 bytes per logit, HBM-bound.  A row is cut into
+// segments so that even a few rows fill the chip; every wavefront keeps its running top-M as a
+// sorted list spread over its lanes (lane i holds the i-th best) and only touches it when some
+// lane's value beats the current M-th best, which becomes rare after the first few hundred values.
+// A second tiny kernel merges the per-wavefront partial results of each row.
+#include <limits.h>
+#include <math.h>
+
+#include "ds_common.h"
+
+namespace ds {
+namespace {
+
+constexpr int kScanThreads = 256;
+constexpr int kUnroll = 8;                                  // float4 loads in flight per thread
+constexpr int kWaveChunk = kWave * 4 * kUnroll;             // 2048 logits per wavefront step
+constexpr int kTile = kWaveChunk * (kScanThreads / kWave);  // 8192 logits per workgroup step
+
+__device__ __forceinline__ bool beats(float v, int id, float w, int jd) {
+  return v > w || (v == w && id < jd);
+}
+
+// Insert (x, xid) into the lane-distributed list sorted best-first.  All 64 lanes call this.
+__device__ __forceinline__ void list_insert(float& ev, int& eid, float x, int xid, int lane) {
+  unsigned long long ahead = __ballot(beats(ev, eid, x, xid));
+  int pos = __popcll(ahead);
+  float pv = __shfl_up(ev, 1);
+  int pid = __shfl_up(eid, 1);
+  if (lane == pos) {
+    ev = x;
+    eid = xid;
+  } else if (lane > pos) {
+    ev = pv;
+    eid = pid;
+  }
+}
+
+// Offer one value per lane to the list; only values beating the current m_max-th entry are inserted.
+__device__ __forceinline__ void list_offer(float& ev, int& eid, float x, int xid, int m_max, int lane) {
+  float thr = __shfl(ev, m_max - 1);
+  int thrid = __shfl(eid, m_max - 1);
+  unsigned long long mask = __ballot(beats(x, xid, thr, thrid));
+  while (mask) {
+    int src = __ffsll((long long)mask) - 1;
+    mask &= mask - 1;
+    float bx = __shfl(x, src);
+    int bid = __shfl(xid, src);
+    if (!beats(bx, bid, thr, thrid)) continue;  // the bar moved up since the ballot
+    list_insert(ev, eid, bx, bid, lane);
+    thr = __shfl(ev, m_max - 1);
+    thrid = __shfl(eid, m_max - 1);
+  }
+}
+
+// Partial record of one wavefront for one row: { max, sum exp(v - max), m_max values, m_max ids }.
+__host__ __device__ inline int rec_dwords(int m_max) { return 2 + 2 * m_max; }
+
+template <bool SOFTMAX>
+__global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __restrict__ logits, int vocab,
+                                                                 int m_max, int tiles_per_seg,
+                                                                 uint32_t* __restrict__ partial) {
+  const int row = blockIdx.y, seg = blockIdx.x, n_seg = gridDim.x;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const float* rowp = logits + (size_t)row * (size_t)vocab;
+  const bool vec = ((vocab & 3) == 0) && ((((uintptr_t)logits) & 15) == 0);
+
+  float ev = -INFINITY;  // this lane's list entry
+  int eid = INT_MAX;
+  float run_max = -INFINITY, run_sum = 0.f;
+
+  const int tile0 = seg * tiles_per_seg;
+  for (int t = 0; t < tiles_per_seg; ++t) {
+    const int base = (tile0 + t) * kTile + wave * kWaveChunk;
+    if (base >= vocab) break;
+    float v[kUnroll][4];
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) {
+      const int i0 = base + j * (kWave * 4) + lane * 4;
+      if (vec && i0 + 3 < vocab) {
+        float4 q = *reinterpret_cast<const float4*>(rowp + i0);
+        v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[j][c] = (i0 + c < vocab) ? rowp[i0 + c] : -INFINITY;
+      }
+    }
+    float loc = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) loc = fmaxf(loc, v[j][c]);
+    if (SOFTMAX) {
+      if (loc > run_max) {
+        run_sum *= __expf(run_max - loc);  // run_max = -inf gives 0 * 0
+        run_max = loc;
+      }
+      if (run_max > -INFINITY) {
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc += __expf(v[j][c] - run_max);
+        run_sum += acc;
+      }
+    }
+    float thr = __shfl(ev, m_max - 1);
+    if (__ballot(loc >= thr)) {
+#pragma unroll
+      for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int idx = base + j * (kWave * 4) + lane * 4 + c;
+          list_offer(ev, eid, v[j][c], idx < vocab ? idx : INT_MAX, m_max, lane);
+        }
+    }
+  }
+
+  if (SOFTMAX) {  // wavefront reduction of (max, sum)
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+      float om = __shfl_xor(run_max, off), os = __shfl_xor(run_sum, off);
+      float nm = fmaxf(run_max, om);
+      float a = (run_max > -INFINITY) ? run_sum * __expf(run_max - nm) : 0.f;
+      float b = (om > -INFINITY) ? os * __expf(om - nm) : 0.f;
+      run_max = nm;
+      run_sum = a + b;
+    }
+  }
+  const int part = (row * n_seg + seg) * (kScanThreads / kWave) + wave;
+  uint32_t* rec = partial + (size_t)part * rec_dwords(m_max);
+  if (lane == 0) {
+    rec[0] = __float_as_uint(run_max);
+    rec[1] = __float_as_uint(run_sum);
+  }
+  if (lane < m_max) {
+    rec[2 + lane] = __float_as_uint(ev);
+    rec[2 + m_max + lane] = (uint32_t)eid;
+  }
+}
+
+// Merge the partial top lists of one row; returns with lane i holding the i-th best overall.
+__device__ __forceinline__ void merge_lists(const uint32_t* rec0, int n_part, int m_max, int lane, float& ev,
+                                            int& eid) {
+  ev = -INFINITY;
+  eid = INT_MAX;
+  const int total = n_part * m_max;
+  for (int b = 0; b < total; b += kWave) {
+    const int e = b + lane;
+    float x = -INFINITY;
+    int xid = INT_MAX;
+    if (e < total) {
+      const uint32_t* rec = rec0 + (size_t)(e / m_max) * rec_dwords(m_max);
+      x = __uint_as_float(rec[2 + e % m_max]);
+      xid = (int)rec[2 + m_max + e % m_max];
+    }
+    list_offer(ev, eid, x, xid, m_max, lane);
+  }
+}
+
+__global__ __launch_bounds__(kWave) void lattice_merge_kernel(const float* __restrict__ logits, int vocab,
+                                                              int m_max, float tau, int32_t eos_id,
+                                                              int n_part, const uint32_t* __restrict__ partial,
+                                                              int32_t* __restrict__ cand_id,
+                                                              float* __restrict__ cand_logp,
+                                                              int32_t* __restrict__ cand_cnt,
+                                                              float* __restrict__ eos_logp,
+                                                              float* __restrict__ lse_out) {
+  const int row = blockIdx.x, lane = threadIdx.x;
+  const uint32_t* rec0 = partial + (size_t)row * n_part * rec_dwords(m_max);
+  float mx = -INFINITY;
+  for (int p = lane; p < n_part; p += kWave)
+    mx = fmaxf(mx, __uint_as_float(rec0[(size_t)p * rec_dwords(m_max)]));
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  float sum = 0.f;
+  for (int p = lane; p < n_part; p += kWave) {
+    const uint32_t* rec = rec0 + (size_t)p * rec_dwords(m_max);
+    float pm = __uint_as_float(rec[0]), ps = __uint_as_float(rec[1]);
+    if (pm > -INFINITY) sum += ps * __expf(pm - mx);
+  }
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+  const float lse = mx + logf(sum);
+
+  float ev;
+  int eid;
+  merge_lists(rec0, n_part, m_max, lane, ev, eid);
+  const float lp = ev - lse;
+  if (lane < m_max) {
+    cand_id[(size_t)row * m_max + lane] = eid;
+    cand_logp[(size_t)row * m_max + lane] = lp;
+  }
+  // mass-adaptive pruning: smallest m with cumulative probability >= tau, float32 in candidate order
+  int cnt = m_max;
+  if (tau < 1.0f) {
+    float cum = 0.f;
+    bool done = false;
+    for (int i = 0; i < m_max; ++i) {
+      float p = expf(__shfl(lp, i));
+      cum = __fadd_rn(cum, p);
+      if (!done && cum >= tau) {
+        cnt = i + 1;
+        done = true;
+      }
+    }
+  }
+  if (lane == 0) {
+    cand_cnt[row] = cnt;
+    lse_out[row] = lse;
+    eos_logp[row] = (eos_id >= 0) ? logits[(size_t)row * vocab + eos_id] - lse : 0.f;
+  }
+}
+
+// One workgroup: arg-max of every row from the partial lists, then the accepted-prefix rule.
+__global__ __launch_bounds__(256) void accept_merge_kernel(int rows, int n_part,
+                                                           const uint32_t* __restrict__ partial,
+                                                           const int32_t* __restrict__ block,
+                                                           const int32_t* __restrict__ path_len, int32_t eos_id,
+                                                           int32_t* __restrict__ n_accept,
+                                                           int32_t* __restrict__ next_token,
+                                                           int32_t* __restrict__ argmax_out,
+                                                           int32_t* __restrict__ eos_accepted) {
+  __shared__ int32_t am[DS_MAX_ROWS];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  for (int r = wave; r < rows; r += 4) {
+    const uint32_t* rec0 = partial + (size_t)r * n_part * rec_dwords(1);
+    float ev;
+    int eid;
+    merge_lists(rec0, n_part, 1, lane, ev, eid);
+    if (lane == 0) {
+      am[r] = eid;
+      argmax_out[r] = eid;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int m = rows - 1;
+    if (path_len) {
+      int pl = *path_len;
+      m = pl < m ? (pl < 0 ? 0 : pl) : m;
+    }
+    int n = 0;
+    bool eos = false;
+    while (n < m && am[n] == block[n + 1]) {
+      eos |= (eos_id >= 0 && block[n + 1] == eos_id);
+      ++n;
+    }
+    const int nxt = am[n];
+    eos |= (eos_id >= 0 && nxt == eos_id);
+    *n_accept = n;
+    *next_token = nxt;
+    *eos_accepted = eos ? 1 : 0;
+  }
+}
+
+struct ScanPlan {
+  int n_seg, tiles_per_seg, n_part;
+};
+
+ScanPlan plan_scan(int rows, int vocab) {
+  int tiles = ceil_div(vocab, kTile);
+  int want = ceil_div(4096, rows);
+  int n_seg = want < 1 ? 1 : (want > tiles ? tiles : want);
+  int tps = ceil_div(tiles, n_seg);
+  n_seg = ceil_div(tiles, tps);
+  return {n_seg, tps, n_seg * (kScanThreads / kWave)};
+}
+
+}  // namespace
+
+size_t lattice_ws_bytes(int rows, int vocab, int m_max) {
+  ScanPlan p = plan_scan(rows, vocab);
+  return align_up((size_t)rows * p.n_part * rec_dwords(m_max) * sizeof(uint32_t), 256);
+}
+
+int launch_lattice(const float* logits, int rows, int vocab, int m_max, float tau, int32_t eos_id,
+                   int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
+                   void* ws, size_t ws_bytes, hipStream_t st) {
+  DS_REQUIRE(ws_bytes >= lattice_ws_bytes(rows, vocab, m_max), DS_E_CAPACITY,
+             "lattice workspace: need %zu bytes, got %zu", lattice_ws_bytes(rows, vocab, m_max), ws_bytes);
+  ScanPlan p = plan_scan(rows, vocab);
+  uint32_t* partial = static_cast<uint32_t*>(ws);
+  hipLaunchKernelGGL(scan_rows_kernel<true>, dim3(p.n_seg, rows), dim3(kScanThreads), 0, st, logits, vocab,
+                     m_max, p.tiles_per_seg, partial);
+  DS_LAUNCH_CHECK("scan_rows_kernel<softmax>");
+  hipLaunchKernelGGL(lattice_merge_kernel, dim3(rows), dim3(kWave), 0, st, logits, vocab, m_max, tau, eos_id,
+                     p.n_part, partial, cand_id, cand_logp, cand_cnt, eos_logp, lse);
+  DS_LAUNCH_CHECK("lattice_merge_kernel");
+  return DS_OK;
+}
+
+size_t accept_ws_bytes(int rows, int vocab) { return lattice_ws_bytes(rows, vocab, 1); }
+
+int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t* block,
+                         const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
+                         int32_t* argmax, int32_t* eos_accepted, void* ws, size_t ws_bytes, hipStream_t st) {
+  DS_REQUIRE(ws_bytes >= accept_ws_bytes(rows, vocab), DS_E_CAPACITY,
+             "acceptance workspace: need %zu bytes, got %zu", accept_ws_bytes(rows, vocab), ws_bytes);
+  DS_REQUIRE(rows >= 1 && rows <= DS_MAX_ROWS, DS_E_SHAPE, "acceptance rows %d outside [1, %d]", rows,
+             DS_MAX_ROWS);
+  ScanPlan p = plan_scan(rows, vocab);
+  uint32_t* partial = static_cast<uint32_t*>(ws);
+  hipLaunchKernelGGL(scan_rows_kernel<false>, dim3(p.n_seg, rows), dim3(kScanThreads), 0, st, logits, vocab, 1,
+                     p.tiles_per_seg, partial);
+  DS_LAUNCH_CHECK("scan_rows_kernel<argmax>");
+  hipLaunchKernelGGL(accept_merge_kernel, dim3(1), dim3(256), 0, st, rows, p.n_part, partial, block, path_len,
+                     eos_id, n_accept, next_token, argmax, eos_accepted);
+  DS_LAUNCH_CHECK("accept_merge_kernel");
+  return DS_OK;
+}
+
+}  // namespace ds

@@ -1,0 +1,190 @@
+"""Host-side driver of the speculative loop (Alg. 1): chains the C-ABI calls of one round and keeps the
+bookkeeping (committed KV lengths, pending tokens, draft length).  No arithmetic of the method happens
+here: drafting, lattice, path search, verification and acceptance all run inside libdiffuspec.so, and the
+draft-length controller is the library's host function.
+
+PyTorch is used for device memory only.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as ds
+from . import synth
+
+DEV = "cuda:0"
+
+
+def upload(a: np.ndarray, bf16: bool = False) -> torch.Tensor:
+    if bf16:
+        bits = synth.f32_to_bf16_bits(a).reshape(a.shape)
+        return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+class DeviceModel:
+    """Model handle + its device buffers (weights, stream-order weights, KV cache, workspace)."""
+
+    def __init__(self, cfg: synth.ModelCfg, weights: dict, kv_capacity: int, max_rows: int = ds.DS_MAX_ROWS):
+        self.cfg = cfg
+        bf = cfg.dtype == "bf16"
+        dev_w = {"embed": upload(weights["embed"], bf), "lm_head": upload(weights["lm_head"], bf),
+                 "final_norm": upload(weights["final_norm"]), "layers": []}
+        for lw in weights["layers"]:
+            d = {n: upload(lw[n], bf) for n in synth.LAYER_TENSORS}
+            d["norm1"], d["norm2"] = upload(lw["norm1"]), upload(lw["norm2"])
+            dev_w["layers"].append(d)
+        self.cfgc = ds.make_cfg(cfg, kv_capacity)
+        pbytes = ds.ds_model_packed_bytes(self.cfgc)
+        self.packed = torch.empty(max(pbytes, 256), dtype=torch.uint8, device=DEV)
+        kvb = ds.ds_kv_bytes(self.cfgc)
+        self.kv_k = torch.zeros(kvb, dtype=torch.uint8, device=DEV)
+        self.kv_v = torch.zeros(kvb, dtype=torch.uint8, device=DEV)
+        self.ws = torch.empty(ds.ds_workspace_bytes(self.cfgc, max_rows), dtype=torch.uint8, device=DEV)
+        self.handle = ds.ds_model_create(self.cfgc, dev_w, self.packed if pbytes else None, self.kv_k, self.kv_v)
+        torch.cuda.synchronize()
+        if bf:  # after packing only the embedding and the norm gains are still read
+            for d in dev_w["layers"]:
+                for n in synth.LAYER_TENSORS:
+                    d[n] = None
+            dev_w["lm_head"] = None
+        self.dev_w = dev_w
+        self.torch_dtype = torch.bfloat16 if bf else torch.float32
+
+    def close(self) -> None:
+        if self.handle:
+            ds.ds_model_destroy(self.handle)
+            self.handle = None
+
+    @property
+    def kv_len(self) -> int:
+        return ds.ds_model_kv_len(self.handle)
+
+    def set_kv_len(self, n: int) -> None:
+        ds.ds_model_kv_set_len(self.handle, n)
+
+
+@dataclass
+class RoundParams:
+    m_max: int = 8
+    tau: float = 1.0
+    beam: int = 4
+    lam: float = 0.5
+    k_min: int = 4
+    k_max: int = 64
+    delta: float = 10.0
+    rho: float = 0.5
+
+
+class SpecDecoder:
+    """One drafter + one verifier on one GPU, both caches holding the same prefix."""
+
+    def __init__(self, drafter: DeviceModel, verifier: DeviceModel, table: Optional[np.ndarray], log2_size: int,
+                 params: RoundParams, k_cap: int = 64):
+        self.d, self.v, self.p = drafter, verifier, params
+        self.eos_id = drafter.cfg.eos_id
+        self.mask_id = drafter.cfg.mask_id
+        vocab = drafter.cfg.vocab
+        self.table = upload(table) if table is not None else None
+        self.proxy = ds.ds_ngram_create(self.table, log2_size) if table is not None else None
+        self.adl = ds.ds_adl_create(params.k_min, params.k_max, params.delta, params.rho)
+        m = params.m_max
+        i32, f32 = torch.int32, torch.float32
+        self.hidden = torch.empty(k_cap, drafter.cfg.d_model, dtype=drafter.torch_dtype, device=DEV)
+        self.d_logits = torch.empty(k_cap, vocab, dtype=f32, device=DEV)
+        self.cand_id = torch.empty(k_cap, m, dtype=i32, device=DEV)
+        self.cand_logp = torch.empty(k_cap, m, dtype=f32, device=DEV)
+        self.cand_cnt = torch.empty(k_cap, dtype=i32, device=DEV)
+        self.eos_logp = torch.empty(k_cap, dtype=f32, device=DEV)
+        self.lse = torch.empty(k_cap, dtype=f32, device=DEV)
+        self.lat_ws = torch.empty(ds.ds_lattice_workspace_bytes(k_cap, vocab, m), dtype=torch.uint8, device=DEV)
+        self.block = torch.zeros(k_cap + 1, dtype=i32, device=DEV)       # [last token, path...]
+        self.ctx = torch.zeros(2, dtype=i32, device=DEV)
+        self.path_len = torch.zeros(1, dtype=i32, device=DEV)
+        self.path_score = torch.zeros(1, dtype=f32, device=DEV)
+        self.result = torch.zeros(3, dtype=i32, device=DEV)               # n_accept, next_token, eos_accepted
+        self.argmax = torch.empty(k_cap + 1, dtype=i32, device=DEV)
+        self.pending_dev = torch.zeros(ds.DS_MAX_ROWS, dtype=i32, device=DEV)
+        self.host = torch.empty(4 + k_cap + 1, dtype=i32).pin_memory()
+        self.k_cap = k_cap
+        self.tokens: List[int] = []
+        self.pending: List[int] = []
+
+    def close(self) -> None:
+        if self.proxy:
+            ds.ds_ngram_destroy(self.proxy)
+            self.proxy = None
+        if self.adl:
+            ds.ds_adl_destroy(self.adl)
+            self.adl = None
+
+    def start(self, prefix: np.ndarray) -> None:
+        """Prefill both caches with the prefix; the verifier's greedy token after it becomes pending."""
+        t = upload(np.asarray(prefix, dtype=np.int32))
+        last = torch.empty(self.v.cfg.vocab, dtype=torch.float32, device=DEV)
+        self.d.set_kv_len(0)
+        self.v.set_kv_len(0)
+        ds.ds_prefill(self.d.handle, t, len(prefix), None, self.d.ws)
+        ds.ds_prefill(self.v.handle, t, len(prefix), last, self.v.ws)
+        # first pending token = verifier arg-max after the prefix: a verify call with an empty path
+        # would need the token before it; the arg-max of `last` is taken by the acceptance kernel
+        # through a 1-row lattice (top-1, ties to the lower id)
+        cid = torch.empty(1, 1, dtype=torch.int32, device=DEV)
+        clp = torch.empty(1, 1, dtype=torch.float32, device=DEV)
+        tmp_i = torch.empty(1, dtype=torch.int32, device=DEV)
+        tmp_f = torch.empty(2, dtype=torch.float32, device=DEV)
+        ws = torch.empty(ds.ds_lattice_workspace_bytes(1, self.v.cfg.vocab, 1), dtype=torch.uint8, device=DEV)
+        ds.ds_build_lattice(last, 1, self.v.cfg.vocab, 1, 1.0, -1, cid, clp, tmp_i, tmp_f[0:1], tmp_f[1:2], ws)
+        torch.cuda.synchronize()
+        first = int(cid.item())
+        self.tokens = [int(x) for x in prefix] + [first]
+        self.pending = [first]
+
+    def enqueue_round(self, k: int, stream=None) -> None:
+        """Enqueue draft -> LM head -> lattice -> path search -> verify for the current state.  No sync."""
+        p = self.p
+        n_pend = len(self.pending)
+        ds.ds_draft_block(self.d.handle, self.pending_dev, n_pend, k, self.mask_id, self.hidden, self.d.ws, stream)
+        ds.ds_lm_head(self.d.handle, self.hidden, k, self.d_logits, self.d.ws, stream)
+        ds.ds_build_lattice(self.d_logits, k, self.d.cfg.vocab, p.m_max, p.tau, self.eos_id, self.cand_id,
+                            self.cand_logp, self.cand_cnt, self.eos_logp, self.lse, self.lat_ws, stream)
+        ds.ds_cps_path(self.cand_id, self.cand_logp, self.cand_cnt, self.eos_logp, 1, k, p.m_max, p.beam, p.lam,
+                       self.proxy, self.ctx, self.eos_id, self.block[1:], self.path_len, self.path_score, stream)
+        ds.ds_verify_block(self.v.handle, self.block, k, self.path_len, self.eos_id, self.result[0:1],
+                           self.result[1:2], self.argmax, self.result[2:3], None, self.v.ws, stream)
+
+    def stage_inputs(self) -> None:
+        """Host -> device: pending tokens, last committed token, proxy context (a few ints)."""
+        n = len(self.pending)
+        h = self.host
+        h[:n] = torch.tensor(self.pending, dtype=torch.int32)
+        self.pending_dev[:n].copy_(h[:n], non_blocking=True)
+        h[n] = self.tokens[-1]
+        self.block[0:1].copy_(h[n:n + 1], non_blocking=True)
+        h[n + 1] = self.tokens[-2]
+        h[n + 2] = self.tokens[-1]
+        self.ctx.copy_(h[n + 1:n + 3], non_blocking=True)
+
+    def round(self, k: int) -> dict:
+        """One full round including the host read-back, KV commit and the draft-length update."""
+        self.stage_inputs()
+        v_len = self.v.kv_len
+        self.enqueue_round(k)
+        res = self.result.cpu()                 # synchronises the stream
+        raw0 = self.cand_id[:k, 0].cpu().numpy()
+        plen = int(self.path_len.item())
+        path = self.block[1:1 + plen].cpu().numpy()
+        n_acc, nxt, eos = int(res[0]), int(res[1]), int(res[2])
+        self.v.set_kv_len(v_len + 1 + n_acc)
+        committed = [int(t) for t in path[:n_acc]] + [nxt]
+        self.tokens += committed
+        self.pending = committed
+        eos_pos = np.nonzero(raw0 == self.eos_id)[0]
+        first_eos = int(eos_pos[0]) + 1 if len(eos_pos) else 0
+        k_next = ds.ds_adl_update(self.adl, k, first_eos, n_acc)
+        return {"k": k, "path": path, "path_len": plen, "n_accept": n_acc, "next_token": nxt, "eos_accepted": eos,
+                "committed": committed, "first_eos": first_eos, "k_next": k_next}

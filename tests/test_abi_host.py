@@ -1,0 +1,98 @@
+"""CPU-side checks of the C-ABI library (no GPU, no compute kernels): it loads, exports every symbol the
+header declares, runs the host-only draft-length controller, and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_02358_amd import binding as ds
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ds.h")
+GOLDEN = os.path.join(ROOT, "tests", "golden", "adl_traces.txt")
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ds_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = ds.load()
+    declared = _declared_symbols()
+    assert len(declared) >= 20
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in ds.h but not exported"
+    assert sorted(ds.EXPORTS) == declared
+    assert "gfx950" in ds.ds_version()
+
+
+def test_adl_through_the_c_abi_matches_hand_traces():
+    n = 0
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        head, steps, ks = [p.strip() for p in line.split("|")]
+        k_min, k_max, delta, rho, k1 = head.split()
+        h = ds.ds_adl_create(int(k_min), int(k_max), float(delta), float(rho))
+        k = int(k1)
+        got = []
+        for s in steps.split():
+            first_eos, l_acc = (int(x) for x in s.split(":"))
+            k = ds.ds_adl_update(h, k, first_eos, l_acc)
+            got.append(k)
+        ds.ds_adl_destroy(h)
+        assert got == [int(x) for x in ks.split()], line
+        n += 1
+    assert n >= 8
+
+
+def test_adl_state_and_argument_errors():
+    h = ds.ds_adl_create(4, 64, 10.0, 0.5)
+    assert ds.ds_adl_update(h, 16, 0, 0) == 8
+    assert ds.ds_adl_state(h) == (8.0, 0.0)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_adl_update(h, 0, 0, 0)
+    assert e.value.code == ds.DS_E_INVALID
+    ds.ds_adl_destroy(h)
+    for bad in [(0, 4, 1.0, 0.5), (8, 4, 1.0, 0.5), (4, 8, -1.0, 0.5), (4, 8, 1.0, 0.0), (4, 8, 1.0, 1.5)]:
+        with pytest.raises(ds.DsError):
+            ds.ds_adl_create(*bad)
+
+
+def test_bad_arguments_are_rejected_on_the_host_before_any_launch():
+    lib = ds.load()
+    # lattice: null pointers / bad widths
+    assert lib.ds_build_lattice(None, 4, 100, 4, 1.0, -1, None, None, None, None, None, None, 0, None) == ds.DS_E_INVALID
+    assert "NULL" in ds.ds_last_error()
+    assert lib.ds_build_lattice(None, 0, 100, 4, 1.0, -1, None, None, None, None, None, None, 0, None) == ds.DS_OK
+    one = C.c_void_p(256)
+    assert lib.ds_build_lattice(one, 4, 100, 17, 1.0, -1, one, one, one, one, one, one, 1 << 20, None) == ds.DS_E_SHAPE
+    assert lib.ds_build_lattice(one, 4, 100, 4, 1.0, 100, one, one, one, one, one, one, 1 << 20, None) == ds.DS_E_INVALID
+    assert lib.ds_build_lattice(one, 4, 100, 4, 1.0, -1, one, one, one, one, one, one, 16, None) == ds.DS_E_CAPACITY
+    # path search
+    assert lib.ds_cps_path(None, None, None, None, 0, 8, 4, 4, 0.5, None, None, -1, None, None, None, None) == ds.DS_OK
+    assert lib.ds_cps_path(one, one, one, one, 1, 0, 4, 4, 0.5, None, one, -1, one, one, one, None) == ds.DS_E_SHAPE
+    assert lib.ds_cps_path(one, one, one, one, 1, 8, 4, 17, 0.5, None, one, -1, one, one, one, None) == ds.DS_E_SHAPE
+    assert lib.ds_cps_path(one, one, one, one, 1, 8, 4, 4, 1.5, None, one, -1, one, one, one, None) == ds.DS_E_INVALID
+    # model configuration
+    cfg = ds.ModelCfgC(1, 3584, 28, 4, 128, 18944, 152064, 1e6, 1e-6, ds.DS_BF16, 4096)
+    assert ds.ds_model_packed_bytes(cfg) == (233046016 + 544997376) * 2
+    assert ds.ds_kv_bytes(cfg) == 4 * 4096 * 128 * 2
+    assert ds.ds_workspace_bytes(cfg, 33) > 33 * 152064 * 4
+    bad = ds.ModelCfgC(1, 3584, 28, 5, 128, 18944, 152064, 1e6, 1e-6, ds.DS_BF16, 4096)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_model_packed_bytes(bad)
+    assert e.value.code == ds.DS_E_SHAPE
+    bad = ds.ModelCfgC(1, 3584, 28, 4, 64, 18944, 152064, 1e6, 1e-6, ds.DS_BF16, 4096)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_workspace_bytes(bad, 8)
+    assert e.value.code == ds.DS_E_UNSUPPORTED
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_workspace_bytes(cfg, 145)
+    assert e.value.code == ds.DS_E_SHAPE
+    out = C.c_void_p(None)
+    assert lib.ds_model_create(C.byref(cfg), None, None, 0, None, None, None, C.byref(out)) == ds.DS_E_INVALID

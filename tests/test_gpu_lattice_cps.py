@@ -1,0 +1,169 @@
+"""GPU parity: token lattice and path search kernels vs the CPU oracle, through the C ABI.
+
+Bars: token ids, candidate counts, paths, path lengths: bit-exact.  Path scores: bit-exact
+(float32, same unfused operation order, lattice log-scores passed as data).  lse / log-probabilities: 1e-5
+absolute (the kernel sums exp() in float32 tree order, the oracle in float64; both round to float32).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cps as o_cps
+from oracle import lattice as o_lat
+from paper_2510_02358_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+LSE_TOL = 1e-5
+VOCAB = 152064
+
+
+def _compare_lattice(got: dict, ref: dict, logits: np.ndarray):
+    g = {k: gu.from_dev(v) for k, v in got.items()}
+    assert np.array_equal(g["cand_id"], ref["cand_id"])
+    assert np.max(np.abs(g["lse"] - ref["lse"])) <= LSE_TOL
+    assert np.max(np.abs(g["cand_logp"] - ref["cand_logp"])) <= LSE_TOL
+    assert np.max(np.abs(g["eos_logp"] - ref["eos_logp"])) <= LSE_TOL
+    assert np.array_equal(g["cand_cnt"], ref["cand_cnt"])
+    # internal consistency, exact: log-prob is logit - lse in float32
+    rows = logits.shape[0]
+    assert np.array_equal(g["cand_logp"], logits[np.arange(rows)[:, None], g["cand_id"]] - g["lse"][:, None])
+    return g
+
+
+@pytest.mark.parametrize("k_len", [8, 16])
+def test_lattice_full_vocab_batch16(k_len):
+    """Stress-test shape: 16 sequences x K positions x 152064 logits, top-16."""
+    logits = synth.make_logits(16, k_len, VOCAB, seed=40 + k_len)
+    eos = VOCAB - 2
+    ref = o_lat.build_lattice(logits, 16, 1.0, eos)
+    got = gu.gpu_lattice(gu.to_dev(logits), 16, 1.0, eos)
+    _compare_lattice(got, ref, logits)
+
+
+@pytest.mark.parametrize("rows,vocab,m_max", [(1, 16, 16), (3, 4099, 5), (7, 8192, 8), (5, 8193, 1), (2, 20001, 16),
+                                             (33, 152064, 8), (40, 32768 + 12, 4)])
+def test_lattice_ragged_shapes(rows, vocab, m_max):
+    rng = np.random.default_rng(rows * 1000 + vocab)
+    logits = (rng.standard_normal((rows, vocab)) * 3).astype(np.float32)
+    eos = vocab - 2 if vocab > 2 else -1
+    ref = o_lat.build_lattice(logits, m_max, 1.0, eos)
+    got = gu.gpu_lattice(gu.to_dev(logits), m_max, 1.0, eos)
+    _compare_lattice(got, ref, logits)
+
+
+def test_lattice_ties_flat_rows_and_pruning():
+    vocab = 12000
+    rng = np.random.default_rng(5)
+    logits = (rng.standard_normal((6, vocab))).astype(np.float32)
+    logits[0, :] = 0.5                                   # flat: ids 0..M-1
+    logits[1, [11999, 7, 8191, 8192, 4096]] = 9.0        # exact ties across tiles and wavefronts
+    logits[2, :] = -np.inf
+    logits[2, [5, 600, 7000, 11998]] = [1.0, 1.0, 0.0, -3.0]   # -inf elsewhere
+    p = np.full(vocab, 0.05 / (vocab - 3)); p[[100, 9000, 3]] = [0.50, 0.35, 0.10]
+    logits[3] = np.log(p).astype(np.float32)             # mass pruning: two survive at tau = 0.8
+    p = np.full(vocab, 0.07 / (vocab - 1)); p[11000] = 0.93
+    logits[4] = np.log(p).astype(np.float32)             # peaky: one survives
+    ref = o_lat.build_lattice(logits, 4, 0.8, vocab - 2)
+    got = gu.gpu_lattice(gu.to_dev(logits), 4, 0.8, vocab - 2)
+    g = _compare_lattice(got, ref, logits)
+    assert list(g["cand_id"][0]) == [0, 1, 2, 3]
+    assert list(g["cand_id"][1]) == [7, 4096, 8191, 8192]
+    assert list(g["cand_id"][2]) == [5, 600, 7000, 11998]
+    assert g["cand_cnt"][3] == 2 and g["cand_cnt"][4] == 1 and g["cand_cnt"][0] == 4
+
+
+def test_lattice_is_deterministic():
+    logits = gu.to_dev(synth.make_logits(4, 8, 50000, seed=9))
+    a = gu.gpu_lattice(logits, 8, 1.0, -1)
+    b = gu.gpu_lattice(logits, 8, 1.0, -1)
+    for k in a:
+        assert torch.equal(a[k], b[k])
+
+
+# ------------------------------------------------------------------------------------------ path search
+
+def _cps_case(batch, k_len, m_max, beam, lam, eos_id, seed, vocab=VOCAB, use_table=True, peaky=False, tau=1.0):
+    rng = np.random.default_rng(seed)
+    # lattice built by the ORACLE from seeded logits restricted to a small random vocabulary slice per row
+    rows = batch * k_len
+    cand_id = np.zeros((rows, m_max), dtype=np.int32)
+    cand_logp = np.zeros((rows, m_max), dtype=np.float32)
+    for r in range(rows):
+        ids = rng.choice(vocab - 2, size=m_max, replace=False)
+        lp = np.sort(rng.standard_normal(m_max).astype(np.float32) * (3.0 if peaky else 0.7) - 8.0)[::-1]
+        cand_id[r], cand_logp[r] = ids, lp
+    cnt = rng.integers(1, m_max + 1, size=rows).astype(np.int32) if tau < 1.0 else np.full(rows, m_max, np.int32)
+    eos_logp = (cand_logp[:, 0] - rng.uniform(0.0, 2.0, rows).astype(np.float32)).astype(np.float32)
+    if eos_id >= 0:   # sometimes make EOS the clear winner so the early stop triggers at different depths
+        hot = rng.random(rows) < 0.04
+        eos_logp[hot] = cand_logp[hot, 0] + np.float32(6.0)
+        inside = rng.random(rows) < 0.05
+        cand_id[inside, m_max - 1] = eos_id
+    lat = {"cand_id": cand_id, "cand_logp": cand_logp, "cand_cnt": cnt, "eos_logp": eos_logp}
+    ctx = synth.make_contexts(vocab, batch, seed + 1)
+    table = synth.make_ngram_table(3) if use_table else None
+    ref_path, ref_len, ref_score = o_cps.cps_batch(lat, batch, k_len, beam, lam, table, synth.NGRAM_LOG2_SIZE, ctx,
+                                                   eos_id)
+    table_d = gu.to_dev(table) if use_table else None
+    path, plen, score = gu.gpu_cps(lat, batch, k_len, m_max, beam, lam, table_d, synth.NGRAM_LOG2_SIZE, ctx, eos_id)
+    assert np.array_equal(plen, ref_len)
+    assert np.array_equal(path, ref_path)
+    assert np.array_equal(score.view(np.uint32), ref_score.view(np.uint32))
+    return ref_len
+
+
+@pytest.mark.parametrize("k_len", [8, 16, 32, 64])
+def test_cps_stress_shape_batch16_top16_beam8(k_len):
+    _cps_case(16, k_len, 16, 8, 0.5, VOCAB - 2, seed=100 + k_len)
+
+
+@pytest.mark.parametrize("batch,k_len,m_max,beam,lam,eos,tau", [
+    (1, 1, 1, 1, 0.5, -1, 1.0), (3, 7, 4, 4, 0.5, 4094, 1.0), (2, 33, 8, 4, 0.5, -1, 1.0), (5, 20, 15, 3, 0.5, 100, 0.8),
+    (2, 256, 16, 16, 0.25, 7, 0.8), (4, 12, 16, 16, 0.0, -1, 1.0), (4, 12, 6, 5, 1.0, 9, 1.0), (1, 64, 2, 16, 0.75, -1, 0.8),
+])
+def test_cps_shapes_and_edge_parameters(batch, k_len, m_max, beam, lam, eos, tau):
+    _cps_case(batch, k_len, m_max, beam, lam, eos, seed=batch * 7 + k_len, tau=tau)
+
+
+def test_cps_without_proxy_and_peaky_lattice():
+    _cps_case(4, 16, 8, 4, 0.5, -1, seed=3, use_table=False)
+    lens = _cps_case(8, 24, 8, 4, 0.5, VOCAB - 2, seed=4, peaky=True)
+    assert lens.min() >= 1
+
+
+def test_cps_eos_first_position_and_ties():
+    # EOS wins immediately: length 1
+    m_max, k_len = 4, 5
+    lat = {"cand_id": np.tile(np.array([[10, 11, 12, 13]], dtype=np.int32), (k_len, 1)),
+           "cand_logp": np.tile(np.array([[-1.0, -1.0, -2.0, -2.0]], dtype=np.float32), (k_len, 1)),
+           "cand_cnt": np.full(k_len, 4, dtype=np.int32), "eos_logp": np.full(k_len, -0.5, dtype=np.float32)}
+    ctx = np.array([[1, 2]], dtype=np.int32)
+    path, plen, score = gu.gpu_cps(lat, 1, k_len, m_max, 3, 1.0, None, 0, ctx, 99)
+    assert plen[0] == 1 and path[0, 0] == 99 and list(path[0, 1:]) == [-1] * 4
+    ref = o_cps.cps_batch(lat, 1, k_len, 3, 1.0, None, 0, ctx, 99)
+    assert np.array_equal(path, ref[0]) and score[0] == ref[2][0]
+    # exact score ties: lower parent, then lower rank
+    path, plen, score = gu.gpu_cps(lat, 1, k_len, m_max, 3, 1.0, None, 0, ctx, -1)
+    ref = o_cps.cps_batch(lat, 1, k_len, 3, 1.0, None, 0, ctx, -1)
+    assert np.array_equal(path, ref[0]) and list(path[0]) == [10] * 5
+
+
+def test_lattice_then_cps_end_to_end_on_device():
+    """Lattice arrays stay on the device between the two calls; compared against the oracle chain fed
+    with the SAME float32 logits.  Path equality can only break at float32 near-ties of scores, which
+    are flagged rather than hidden."""
+    batch, k_len, m_max, beam = 4, 16, 8, 4
+    logits = synth.make_logits(batch, k_len, 30000, seed=77)
+    eos = 29998
+    got = gu.gpu_lattice(gu.to_dev(logits), m_max, 1.0, eos)
+    ctx = synth.make_contexts(30000, batch, 78)
+    table = synth.make_ngram_table(3)
+    path, plen, score = gu.gpu_cps(got, batch, k_len, m_max, beam, 0.5, gu.to_dev(table), synth.NGRAM_LOG2_SIZE, ctx, eos)
+    ref_lat = o_lat.build_lattice(logits, m_max, 1.0, eos)
+    rpath, rlen, rscore = o_cps.cps_batch(ref_lat, batch, k_len, beam, 0.5, table, synth.NGRAM_LOG2_SIZE, ctx, eos)
+    agree = np.mean(path == rpath)
+    assert agree == 1.0, f"token agreement {agree}"
+    assert np.max(np.abs(score - rscore)) < 1e-3
