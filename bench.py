@@ -1,0 +1,195 @@
+"""Benchmark: speculative rounds per second on one MI355X, 7B-shaped layer + LM head (bf16).
+
+A step is one full round through the C ABI: drafter pass over 1 pending + K=32 [MASK] rows against a
+2048-token KV cache -> LM head -> token lattice (top-8) -> path search (beam 4) -> verifier pass over 33
+causal rows + LM head + greedy acceptance -> host read-back of the accepted length -> draft-length update.
+Inputs (weights, KV caches, proxy table) are resident in HBM before the timed region.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+PREFIX, K_DRAFT, M_MAX, BEAM, LAM = 2048, 32, 8, 4, 0.5
+
+
+def algorithmic_bytes(cfg, rows_prefix):
+    """Bytes the method must move per stage (weights once + KV once); activations and logits excluded."""
+    from paper_2510_02358_amd import synth
+    layer = synth.layer_param_count(cfg) * 2
+    head = cfg.vocab * cfg.d_model * 2
+    kv = (rows_prefix + K_DRAFT + 1) * 2 * cfg.n_kv * cfg.head_dim * 2
+    return {"draft": layer + kv, "lm_head": head, "verify": layer + kv + head,
+            "round": 2 * (layer + kv) + 2 * head}
+
+
+def traffic_from_profiles():
+    """HBM bytes per LM-head launch measured with rocprofv3 --pmc (committed summary), or None."""
+    path = os.path.join(ROOT, "profiles", "lm_head_gemm_cfg1_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2510_02358_amd import binding as ds
+    from paper_2510_02358_amd import round as rnd
+    from paper_2510_02358_amd import synth
+
+    ds.load()  # raises if the HIP library is missing: there is no fallback
+    torch.cuda.set_device(0)
+    cfg = synth.CFG_7B_LAYER
+    t0 = time.time()
+    dw, vw = synth.make_weights(cfg, 0), synth.make_weights(cfg, 1)
+    prefix = synth.make_prefix(cfg, PREFIX, 2)
+    table = synth.make_ngram_table(3)
+    cap = PREFIX + 192
+    dm, vm = rnd.DeviceModel(cfg, dw, cap), rnd.DeviceModel(cfg, vw, cap)
+    dec = rnd.SpecDecoder(dm, vm, table, synth.NGRAM_LOG2_SIZE,
+                          rnd.RoundParams(m_max=M_MAX, beam=BEAM, lam=LAM), k_cap=K_DRAFT)
+    dec.start(prefix)
+    dec.stage_inputs()
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+    p0 = PREFIX
+
+    n_ev = args.steps
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    acc_tokens = 0
+    k_next = K_DRAFT
+
+    def one_round(i_timed):
+        nonlocal acc_tokens, k_next
+        dm.set_kv_len(p0)
+        vm.set_kv_len(p0)
+        p = dec.p
+        ds.ds_draft_block(dm.handle, dec.pending_dev, 1, K_DRAFT, dec.mask_id, dec.hidden, dm.ws)
+        if i_timed >= 0:
+            ev[i_timed][0].record()
+        ds.ds_lm_head(dm.handle, dec.hidden, K_DRAFT, dec.d_logits, dm.ws)
+        if i_timed >= 0:
+            ev[i_timed][1].record()
+        ds.ds_build_lattice(dec.d_logits, K_DRAFT, cfg.vocab, p.m_max, p.tau, dec.eos_id, dec.cand_id, dec.cand_logp,
+                            dec.cand_cnt, dec.eos_logp, dec.lse, dec.lat_ws)
+        ds.ds_cps_path(dec.cand_id, dec.cand_logp, dec.cand_cnt, dec.eos_logp, 1, K_DRAFT, p.m_max, p.beam, p.lam,
+                       dec.proxy, dec.ctx, dec.eos_id, dec.block[1:], dec.path_len, dec.path_score)
+        ds.ds_verify_block(vm.handle, dec.block, K_DRAFT, dec.path_len, dec.eos_id, dec.result[0:1],
+                           dec.result[1:2], dec.argmax, dec.result[2:3], None, vm.ws)
+        dec.host[:3].copy_(dec.result, non_blocking=True)
+        torch.cuda.current_stream().synchronize()      # the round's one host crossing: accepted length
+        n_acc = int(dec.host[0])
+        k_next = ds.ds_adl_update(dec.adl, K_DRAFT, 0, n_acc)
+        if i_timed >= 0:
+            acc_tokens += n_acc + 1
+
+    for _ in range(args.warmup):
+        one_round(-1)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(args.steps):
+        one_round(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    ms_per_step = elapsed * 1e3 / args.steps
+    rounds_per_s = args.steps / elapsed
+
+    lm_ms = sum(a.elapsed_time(b) for a, b in ev) / n_ev
+    ab = algorithmic_bytes(cfg, PREFIX)
+    achieved = ab["lm_head"] / (lm_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel (LM head 152064x3584, 32 rows)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_from_profiles(),
+                "avg_launch_us": round(lm_ms * 1e3, 2), "algorithmic_bytes": ab["lm_head"]}
+
+    # per-stage times (separate untimed pass, events between the calls)
+    stages = {}
+    names = ["draft", "lm_head", "lattice", "cps", "verify"]
+    n_rep = 20
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_rep)]
+    for r in range(n_rep):
+        dm.set_kv_len(p0)
+        vm.set_kv_len(p0)
+        p = dec.p
+        marks[r][0].record()
+        ds.ds_draft_block(dm.handle, dec.pending_dev, 1, K_DRAFT, dec.mask_id, dec.hidden, dm.ws)
+        marks[r][1].record()
+        ds.ds_lm_head(dm.handle, dec.hidden, K_DRAFT, dec.d_logits, dm.ws)
+        marks[r][2].record()
+        ds.ds_build_lattice(dec.d_logits, K_DRAFT, cfg.vocab, p.m_max, p.tau, dec.eos_id, dec.cand_id, dec.cand_logp,
+                            dec.cand_cnt, dec.eos_logp, dec.lse, dec.lat_ws)
+        marks[r][3].record()
+        ds.ds_cps_path(dec.cand_id, dec.cand_logp, dec.cand_cnt, dec.eos_logp, 1, K_DRAFT, p.m_max, p.beam, p.lam,
+                       dec.proxy, dec.ctx, dec.eos_id, dec.block[1:], dec.path_len, dec.path_score)
+        marks[r][4].record()
+        ds.ds_verify_block(vm.handle, dec.block, K_DRAFT, dec.path_len, dec.eos_id, dec.result[0:1],
+                           dec.result[1:2], dec.argmax, dec.result[2:3], None, vm.ws)
+        marks[r][5].record()
+        torch.cuda.synchronize()
+    for i, nm in enumerate(names):
+        us = float(np.median([marks[r][i].elapsed_time(marks[r][i + 1]) for r in range(n_rep)])) * 1e3
+        st = {"us": round(us, 1)}
+        if nm in ab:
+            st["hbm_frac"] = round(ab[nm] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+        stages[nm] = st
+
+    out = {
+        "metric": "spec_rounds_per_s", "value": round(rounds_per_s, 2), "unit": "rounds/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg1: 7B-shaped decoder layer + LM head (d=3584, 28q/4kv x128, FFN 18944, "
+                               "vocab 152064), drafter + verifier, prefix 2048, K=32, top-8 lattice, beam 4, "
+                               "33 verify rows, batch 1"},
+        "accepted_tokens_per_s": round(acc_tokens / elapsed, 2),
+        "round_hbm_frac": round(ab["round"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": roofline, "stages": stages, "setup_s": round(setup_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import round as o_round
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        st = o_round.SpecState(cfg, dw, cfg, vw, prefix)     # oracle prefill, untimed like the GPU's
+        c0 = time.perf_counter()
+        o_round.spec_round(st, K_DRAFT, M_MAX, 1.0, BEAM, LAM, table, synth.NGRAM_LOG2_SIZE)
+        c_el = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": round(1.0 / c_el, 4), "unit": "rounds/s", "cores": int(cores),
+                               "kind": "oracle", "sample": "1 full round of the same workload (same weights, "
+                               "prefix and parameters; float64 numpy oracle), prefill untimed"}
+    print(json.dumps(out))
+    dec.close(); dm.close(); vm.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

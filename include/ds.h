@@ -57,7 +57,8 @@ typedef struct ds_adl ds_adl;
 typedef struct {
   int32_t n_layers, d_model, n_q, n_kv, head_dim, d_ffn, vocab;
   float rope_base, rms_eps;
-  int32_t dtype;       /* DS_F32 or DS_BF16: storage type of weights, KV cache and hidden states */
+  int32_t dtype;       /* DS_F32 or DS_BF16: storage type of the weights.  DS_BF16: bf16 weights, 16-bit
+                          (IEEE half) KV cache, float32 accumulation.  DS_F32: everything float32. */
   int32_t kv_capacity; /* tokens each layer's KV buffer can hold (bf16: a multiple of 64) */
 } ds_model_cfg;
 
@@ -109,14 +110,15 @@ int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, vo
  * [MASK] tokens (each sees the whole cached prefix, the pending tokens and all K block positions).
  * Keys/values of the pending rows are appended and committed (length += n_pend); those of the mask
  * rows are scratch and never committed.  pending [dev] int32[n_pend] (may be NULL iff n_pend == 0).
- * hidden_out [dev] [K, d_model] in cfg.dtype: final-normed hidden states of the mask rows; the state
- * at block position i gives the distribution of the token AT position i.
+ * hidden_out [dev] float[K, d_model]: final-normed hidden states of the mask rows; the state at block
+ * position i gives the distribution of the token AT position i.
  * Requires 1 <= K, n_pend + K <= DS_MAX_ROWS, kv_len + n_pend + K <= kv_capacity. */
 int ds_draft_block(ds_model* drafter, const int32_t* pending, int n_pend, int K, int32_t mask_id,
-                   void* hidden_out, void* ws, size_t ws_bytes, void* stream);
+                   float* hidden_out, void* ws, size_t ws_bytes, void* stream);
 
-/* logits[rows, vocab] (float32) = hidden[rows, d_model] (cfg.dtype) times the LM head. */
-int ds_lm_head(ds_model* m, const void* hidden, int rows, float* logits, void* ws, size_t ws_bytes,
+/* logits[rows, vocab] = hidden[rows, d_model] times the LM head (all [dev] float32; DS_BF16 models split
+ * each hidden value into two bf16 terms and accumulate both products in float32). */
+int ds_lm_head(ds_model* m, const float* hidden, int rows, float* logits, void* ws, size_t ws_bytes,
                void* stream);
 
 /* Step 2, token lattice (Sec. 3.2 "Lattice and pruning").  Per row r of logits [dev] float[rows, vocab]:

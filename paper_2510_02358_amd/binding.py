@@ -58,6 +58,9 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
+    # torch ships its own HIP runtime (same SONAME as the system one).  Import it first so that this
+    # library binds to the SAME runtime instance: streams and device pointers are shared with torch.
+    import torch  # noqa: F401
     if not os.path.exists(_LIB_PATH):
         raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2510_02358_amd.build` "
                            "(there is no CPU fallback)")

@@ -116,15 +116,16 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
   w.tok = static_cast<int32_t*>(take((size_t)rows * 4));
   w.x = static_cast<float*>(take((size_t)rows * c.d_model * 4));
   w.cs = static_cast<float2*>(take((size_t)rows * (c.head_dim / 2) * 8));
-  w.h = take((size_t)rp * c.d_model * es);
+  const size_t planes = c.dtype == DS_BF16 ? 2 : 1;  // GEMM inputs: (hi, lo) bf16 pair or one float32 plane
+  w.h = take(planes * rp * c.d_model * es);
   w.q = take((size_t)c.n_q * rp * c.head_dim * es);
-  w.att = take((size_t)rp * c.n_q * c.head_dim * es);
-  w.act = take((size_t)rp * c.d_ffn * es);
-  w.y = take((size_t)rp * c.d_model * es);
+  w.att = take(planes * rp * c.n_q * c.head_dim * es);
+  w.act = take(planes * rp * c.d_ffn * es);
+  w.y = take(planes * rp * c.d_model * es);
   size_t gf = 0;
   widest_split_floats(c, rows, &gf);
   w.gemm_out = static_cast<float*>(take(gf * 4));
-  const int max_split = attn_splits(c.dtype, c.kv_capacity);
+  const int max_split = attn_max_splits(c.dtype, c.kv_capacity);
   w.att_o = static_cast<float*>(take((size_t)max_split * c.n_q * rp * c.head_dim * 4));
   w.att_ml = static_cast<float*>(take((size_t)max_split * c.n_q * rp * 2 * 4));
   w.logits = static_cast<float*>(take((size_t)rows * c.vocab * 4));
@@ -186,7 +187,7 @@ int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float
 // tokens, the rest are [MASK] rows.  Leaves the final-normed states of all rows in ws.y (GEMM input
 // order) and, if hidden_out is given, a row-major copy of rows >= hidden_row0 there.
 template <typename T>
-int forward_rows(ds_model* m, const Workspace& w, int rows, int n_causal, void* hidden_out, int hidden_row0,
+int forward_rows(ds_model* m, const Workspace& w, int rows, int n_causal, float* hidden_out, int hidden_row0,
                  hipStream_t st) {
   const ds_model_cfg& c = m->cfg;
   const int rp = ceil_div(rows, 16) * 16;
@@ -194,8 +195,11 @@ int forward_rows(ds_model* m, const Workspace& w, int rows, int n_causal, void* 
   const int d = c.d_model, hd = c.head_dim;
   int rc;
   if ((rc = launch_rope_table(pos0, rows, hd, (double)c.rope_base, w.cs, st))) return rc;
-  if ((rc = launch_embed_norm<T>(w.tok, m->embed, w.x, rows, d, m->canon[0].norm1, c.rms_eps, w.h, st))) return rc;
+  if ((rc = launch_embed_norm<T>(w.tok, m->embed, w.x, rows, rp, d, m->canon[0].norm1, c.rms_eps, w.h, st))) return rc;
   const int n_split_att = attn_splits(c.dtype, n_keys);
+  DS_REQUIRE(n_split_att <= attn_max_splits(c.dtype, c.kv_capacity), DS_E_CAPACITY,
+             "attention partials: %d splits exceed the workspace's %d", n_split_att,
+             attn_max_splits(c.dtype, c.kv_capacity));
   for (int li = 0; li < c.n_layers; ++li) {
     const size_t layer_elems = (size_t)c.n_kv * c.kv_capacity * hd;
     char* kc = static_cast<char*>(m->kv_k) + (size_t)li * layer_elems * m->esize;
@@ -209,21 +213,21 @@ int forward_rows(ds_model* m, const Workspace& w, int rows, int n_causal, void* 
                                c.kv_capacity, n_split_att, w.att_o, w.att_ml, w.att, st)))
       return rc;
     if ((rc = gemm<T>(m, li, 1, w.att, rows, w.gemm_out, &sp, st))) return rc;
-    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr, 0, st)))
+    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr, 0, st)))
       return rc;
     if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st))) return rc;
-    if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, c.d_ffn, w.act, st))) return rc;
+    if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, rp, c.d_ffn, w.act, st))) return rc;
     if ((rc = gemm<T>(m, li, 3, w.act, rows, w.gemm_out, &sp, st))) return rc;
     const bool last = li + 1 == c.n_layers;
     const float* gain = last ? m->final_norm : m->canon[li + 1].norm1;
-    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, d, gain, c.rms_eps, last ? w.y : w.h,
+    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, gain, c.rms_eps, last ? w.y : w.h,
                                  last ? hidden_out : nullptr, hidden_row0, st)))
       return rc;
   }
   return DS_OK;
 }
 
-int forward_dispatch(ds_model* m, const Workspace& w, int rows, int n_causal, void* hidden_out, int hidden_row0,
+int forward_dispatch(ds_model* m, const Workspace& w, int rows, int n_causal, float* hidden_out, int hidden_row0,
                      hipStream_t st) {
   return m->cfg.dtype == DS_BF16 ? forward_rows<bf16_t>(m, w, rows, n_causal, hidden_out, hidden_row0, st)
                                  : forward_rows<float>(m, w, rows, n_causal, hidden_out, hidden_row0, st);
@@ -391,7 +395,7 @@ int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, vo
   return DS_OK;
 }
 
-int ds_draft_block(ds_model* m, const int32_t* pending, int n_pend, int K, int32_t mask_id, void* hidden_out,
+int ds_draft_block(ds_model* m, const int32_t* pending, int n_pend, int K, int32_t mask_id, float* hidden_out,
                    void* ws, size_t ws_bytes, void* stream) {
   DS_REQUIRE(m && hidden_out, DS_E_INVALID, "ds_draft_block: NULL pointer argument");
   DS_REQUIRE(n_pend >= 0 && K >= 1, DS_E_SHAPE, "need n_pend >= 0 and K >= 1 (got %d, %d)", n_pend, K);
@@ -411,7 +415,7 @@ int ds_draft_block(ds_model* m, const int32_t* pending, int n_pend, int K, int32
   return DS_OK;
 }
 
-int ds_lm_head(ds_model* m, const void* hidden, int rows, float* logits, void* ws, size_t ws_bytes, void* stream) {
+int ds_lm_head(ds_model* m, const float* hidden, int rows, float* logits, void* ws, size_t ws_bytes, void* stream) {
   DS_REQUIRE(m && hidden && logits, DS_E_INVALID, "ds_lm_head: NULL pointer argument");
   DS_REQUIRE(rows >= 1 && rows <= DS_MAX_ROWS, DS_E_SHAPE, "rows %d outside [1, %d]", rows, DS_MAX_ROWS);
   Workspace w;
@@ -419,7 +423,8 @@ int ds_lm_head(ds_model* m, const void* hidden, int rows, float* logits, void* w
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (m->cfg.dtype == DS_BF16) {
-    if ((rc = launch_to_gemm_input<bf16_t>(hidden, rows, m->cfg.d_model, w.y, st))) return rc;
+    const int rp = ceil_div(rows, 16) * 16;
+    if ((rc = launch_to_gemm_input<bf16_t>(hidden, rows, rp, m->cfg.d_model, w.y, st))) return rc;
     return lm_head_rows(m, w.y, rows, logits, st);
   }
   return lm_head_rows(m, hidden, rows, logits, st);

@@ -4,9 +4,9 @@
 // Visibility: row r (absolute position pos0 + r) sees key p iff p < n_keys and
 //   r >= n_causal (a [MASK] row of the draft block: sees everything)  or  p <= pos0 + r (causal).
 //
-// bf16 kernel (head_dim 128): the query rows of all heads that share a KV head are packed together,
-// so one pass over that head's keys/values serves group x rows query rows; both products run on the
-// 16x16x32 bf16 matrix cores.  Scores are computed transposed, S^T = K Q^T, because the accumulator
+// Half-precision kernel (bf16 models, head_dim 128; q, K, V and probabilities are IEEE half): the
+// query rows of all heads that share a KV head are packed together, so one pass over that head's
+// keys/values serves group x rows query rows; both products run on the 16x16x32 f16 matrix cores.  Scores are computed transposed, S^T = K Q^T, because the accumulator
 // layout of S^T (lane = query row, 4 consecutive keys per register quad) is already the operand
 // layout the second product P V needs: probabilities never leave registers.  For that product the
 // value cache is stored transposed ([head_dim][capacity]) so that a lane reads its keys contiguously.
@@ -20,7 +20,7 @@
 
 namespace ds {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
@@ -29,14 +29,14 @@ constexpr int kChunk = 64;  // keys per staged chunk
 constexpr int kHd = 128;    // head_dim of the bf16 kernel
 
 union Pack8 {
-  bf16x8 v;
+  f16x8 v;
   uint16_t h[8];
   uint2 half[2];
   uint4 q;
 };
 
 template <int QB>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(256) void attn_f16_kernel(const uint16_t* __restrict__ q,
                                                         const uint16_t* __restrict__ kc,
                                                         const uint16_t* __restrict__ vt, int rows_pad,
                                                         int n_causal, int pos0, int n_keys, int n_q, int n_kv,
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restri
 
   int qb[QB], head[QB], rb[QB];
   bool valid[QB];
-  bf16x8 bq[QB][4];
+  f16x8 bq[QB][4];
   f32x4 o[QB][8];
   float m_run[QB], l_run[QB];
 #pragma unroll
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restri
     rb[t] = qbc % rb_count;
     const uint16_t* qh = q + (size_t)head[t] * rows_pad * kHd + (size_t)rb[t] * 4 * 512;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) bq[t][s] = *reinterpret_cast<const bf16x8*>(qh + s * 512 + lane * 8);
+    for (int s = 0; s < 4; ++s) bq[t][s] = *reinterpret_cast<const f16x8*>(qh + s * 512 + lane * 8);
 #pragma unroll
     for (int d = 0; d < 8; ++d) o[t][d] = f32x4{0.f, 0.f, 0.f, 0.f};
     m_run[t] = -INFINITY;
@@ -117,8 +117,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restri
         s4[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ks_lds[((kb * 4 + s) * 64 + lane) * 8]);
-          s4[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[t][s], s4[kb], 0, 0, 0);
+          const f16x8 a = *reinterpret_cast<const f16x8*>(&ks_lds[((kb * 4 + s) * 64 + lane) * 8]);
+          s4[kb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[t][s], s4[kb], 0, 0, 0);
         }
       }
       // s4[kb][e] = score of key c0 + 16 kb + 4 g + e for query row 16 rb + j
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restri
         for (int e = 0; e < 4; ++e) {
           const float p = __expf(s4[kb][e] - m_use);
           psum += p;
-          pb[kb >> 1].h[(kb & 1) * 4 + e] = float_to_bf16_bits(p);
+          pb[kb >> 1].h[(kb & 1) * 4 + e] = float_to_half_bits(p);
         }
       l_run[t] = l_run[t] * alpha + psum;
       m_run[t] = m_new;
@@ -156,8 +156,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restri
         o[t][d] *= alpha;
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vs_lds[((d * 2 + t2) * 64 + lane) * 8]);
-          o[t][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[t2].v, o[t][d], 0, 0, 0);
+          const f16x8 a = *reinterpret_cast<const f16x8*>(&vs_lds[((d * 2 + t2) * 64 + lane) * 8]);
+          o[t][d] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pb[t2].v, o[t][d], 0, 0, 0);
         }
       }
     }
@@ -251,6 +251,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
 template <typename T>
 __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int n_split,
                                   int n_q, int rows_pad, int hd, T* __restrict__ att) {
+  // att: GEMM input [rows_pad, n_q * hd] of the output projection
   const int r = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
   if (d >= hd) return;
   float mx = -INFINITY;
@@ -265,7 +266,7 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
     num += part_o[row * hd + d] * w;
     den += l * w;
   }
-  att[Act<T>::off(r, head * hd + d, n_q * hd)] = Act<T>::from_float(num / den);
+  Act<T>::put(att, r, head * hd + d, n_q * hd, (size_t)rows_pad * n_q * hd, num / den);
 }
 
 int chunks_per_split(int dtype, int n_keys) {
@@ -280,8 +281,11 @@ int attn_splits(int dtype, int n_keys) {
   return ceil_div(ceil_div(n_keys, kChunk), chunks_per_split(dtype, n_keys));
 }
 
-size_t attn_partial_floats(int n_split, int n_q, int rows_pad, int hd) {
-  return (size_t)n_split * n_q * rows_pad * (hd + 2);
+// Upper bound of attn_splits over every n_keys <= capacity (the split count is not monotone in n_keys).
+int attn_max_splits(int dtype, int capacity) {
+  const int cap_chunks = ceil_div(capacity, kChunk);
+  const int max_split = dtype == DS_BF16 ? 32 : 16;
+  return cap_chunks < max_split ? cap_chunks : max_split;
 }
 
 int launch_attention(int dtype, const void* q, const void* kc, const void* vc, int rows, int rows_pad, int n_causal,
@@ -294,10 +298,10 @@ int launch_attention(int dtype, const void* q, const void* kc, const void* vc, i
     const int n_qb = (n_q / n_kv) * (rows_pad >> 4);
     constexpr int QB = 2;
     dim3 grid(n_split, n_kv, ceil_div(n_qb, 4 * QB));
-    hipLaunchKernelGGL((attn_bf16_kernel<QB>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
+    hipLaunchKernelGGL((attn_f16_kernel<QB>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
                        static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc), rows_pad, n_causal, pos0,
                        n_keys, n_q, n_kv, cap, cps, scale, part_o, part_ml);
-    DS_LAUNCH_CHECK("attn_bf16_kernel");
+    DS_LAUNCH_CHECK("attn_f16_kernel");
     hipLaunchKernelGGL((attn_merge_kernel<bf16_t>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, n_split, n_q,
                        rows_pad, hd, static_cast<bf16_t*>(att_out));
     DS_LAUNCH_CHECK("attn_merge_kernel<bf16>");

@@ -3,7 +3,7 @@
 // (fixed-order) sum of the GEMM's split-K partial planes, so no separate reduction pass exists.
 //
 // The residual stream x stays float32 [rows, d_model].  Activations that feed a GEMM are written in
-// the model's storage type: bf16 in tile order (xt_offset) or float32 row-major.
+// the model's storage form: a (hi, lo) pair of bf16 planes in tile order, or float32 row-major.
 #include <math.h>
 
 #include "ds_act.h"
@@ -45,13 +45,13 @@ __global__ void rope_table_kernel(int pos0, int rows, int half, double base, flo
 
 // x[r] = E[tok[r]] (+ sum of partial planes) ; h[r] = rmsnorm(x[r]) * gain, written as GEMM input.
 // FROM_EMBED: start from the embedding row, else from the float32 residual x plus `n_part` planes.
-// rm_out (optional): row-major copy of rows >= rm_row0 in the storage type (the boundary's hidden_out).
+// rm_out (optional): row-major float32 copy of rows >= rm_row0 (the boundary's hidden_out).
 template <typename T, bool FROM_EMBED>
 __global__ __launch_bounds__(256) void norm_kernel(const int32_t* __restrict__ tok, const T* __restrict__ embed,
                                                    float* __restrict__ x, const float* __restrict__ part,
-                                                   int n_part, int rows, int d, const float* __restrict__ gain,
-                                                   float eps, T* __restrict__ h, T* __restrict__ rm_out,
-                                                   int rm_row0) {
+                                                   int n_part, int rows, int rows_pad, int d,
+                                                   const float* __restrict__ gain, float eps, T* __restrict__ h,
+                                                   float* __restrict__ rm_out, int rm_row0) {
   __shared__ float red[4];
   const int r = blockIdx.x;
   float v[kMaxPerThread];
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const int32_t* __restrict__ t
     if (c < d) {
       float a;
       if (FROM_EMBED) {
-        a = Act<T>::to_float(embed[(size_t)tok[r] * d + c]);
+        a = Act<T>::weight(embed[(size_t)tok[r] * d + c]);
       } else {
         a = x[(size_t)r * d + c];
         for (int s = 0; s < n_part; ++s) a += part[((size_t)s * rows + r) * d + c];
@@ -80,17 +80,18 @@ __global__ __launch_bounds__(256) void norm_kernel(const int32_t* __restrict__ t
     const int c = threadIdx.x + i * 256;
     if (c < d) {
       const float y = v[i] * inv * gain[c];
-      h[Act<T>::off(r, c, d)] = Act<T>::from_float(y);
-      if (rm_out && r >= rm_row0) rm_out[(size_t)(r - rm_row0) * d + c] = Act<T>::from_float(y);
+      Act<T>::put(h, r, c, d, (size_t)rows_pad * d, y);
+      if (rm_out && r >= rm_row0) rm_out[(size_t)(r - rm_row0) * d + c] = y;
     }
   }
 }
 
-// Row-major hidden states [rows, d] (storage type) -> GEMM input order.
+// Row-major float32 hidden states [rows, d] -> GEMM input order.
 template <typename T>
-__global__ void to_gemm_input_kernel(const T* __restrict__ src, int rows, int d, T* __restrict__ dst) {
+__global__ void to_gemm_input_kernel(const float* __restrict__ src, int rows_pad, int d, T* __restrict__ dst) {
   const int r = blockIdx.x;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) dst[Act<T>::off(r, c, d)] = src[(size_t)r * d + c];
+  for (int c = threadIdx.x; c < d; c += blockDim.x)
+    Act<T>::put(dst, r, c, d, (size_t)rows_pad * d, src[(size_t)r * d + c]);
 }
 
 // One wavefront per (row, head slot): sums the QKV partial planes, rotates q and k, writes q in the
@@ -99,7 +100,9 @@ __global__ void to_gemm_input_kernel(const T* __restrict__ src, int rows, int d,
 template <typename T>
 __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int n_q,
                                 int n_kv, int hd, const float2* __restrict__ cs, int pos0, int cap,
-                                T* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc) {
+                                typename Act<T>::kv_t* __restrict__ q, typename Act<T>::kv_t* __restrict__ kc,
+                                typename Act<T>::kv_t* __restrict__ vc) {
+  using KV = typename Act<T>::kv_t;
   const int r = blockIdx.x, slot = blockIdx.y, i = threadIdx.x, half = hd >> 1;
   if (i >= half) return;
   const int n_tot = (n_q + 2 * n_kv) * hd;
@@ -118,30 +121,31 @@ __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int 
   }
   const int pos = pos0 + r;
   if (slot < n_q) {
-    T* qh = q + (size_t)slot * rows_pad * hd;
-    qh[Act<T>::off(r, i, hd)] = Act<T>::from_float(a);
-    qh[Act<T>::off(r, i + half, hd)] = Act<T>::from_float(b);
+    KV* qh = q + (size_t)slot * rows_pad * hd;
+    qh[Act<T>::q_off(r, i, hd)] = Act<T>::to_kv(a);
+    qh[Act<T>::q_off(r, i + half, hd)] = Act<T>::to_kv(b);
   } else if (slot < n_q + n_kv) {
-    T* kh = kc + ((size_t)(slot - n_q) * cap + pos) * hd;
-    kh[i] = Act<T>::from_float(a);
-    kh[i + half] = Act<T>::from_float(b);
+    KV* kh = kc + ((size_t)(slot - n_q) * cap + pos) * hd;
+    kh[i] = Act<T>::to_kv(a);
+    kh[i + half] = Act<T>::to_kv(b);
   } else {
     const int kvh = slot - n_q - n_kv;
     if (Act<T>::kTransposedV) {
-      T* vh = vc + (size_t)kvh * hd * cap;
-      vh[(size_t)i * cap + pos] = Act<T>::from_float(a);
-      vh[(size_t)(i + half) * cap + pos] = Act<T>::from_float(b);
+      KV* vh = vc + (size_t)kvh * hd * cap;
+      vh[(size_t)i * cap + pos] = Act<T>::to_kv(a);
+      vh[(size_t)(i + half) * cap + pos] = Act<T>::to_kv(b);
     } else {
-      T* vh = vc + ((size_t)kvh * cap + pos) * hd;
-      vh[i] = Act<T>::from_float(a);
-      vh[i + half] = Act<T>::from_float(b);
+      KV* vh = vc + ((size_t)kvh * cap + pos) * hd;
+      vh[i] = Act<T>::to_kv(a);
+      vh[i + half] = Act<T>::to_kv(b);
     }
   }
 }
 
 // act[r][f] = silu(gate) * up with gate = sum_s part[s][r][f], up = sum_s part[s][r][F + f].
 template <typename T>
-__global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int rows, int F, T* __restrict__ act) {
+__global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int F,
+                              T* __restrict__ act) {
   const int r = blockIdx.y;
   const int f = blockIdx.x * blockDim.x + threadIdx.x;
   if (f >= F) return;
@@ -152,7 +156,7 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
     u += p[F + f];
   }
   const float y = g / (1.0f + expf(-g)) * u;
-  act[Act<T>::off(r, f, F)] = Act<T>::from_float(y);
+  Act<T>::put(act, r, f, F, (size_t)rows_pad * F, y);
 }
 
 }  // namespace
@@ -170,27 +174,27 @@ int launch_rope_table(int pos0, int rows, int hd, double base, float2* cs, hipSt
 }
 
 template <typename T>
-int launch_embed_norm(const int32_t* tok, const void* embed, float* x, int rows, int d, const float* gain, float eps,
-                      void* h, hipStream_t st) {
+int launch_embed_norm(const int32_t* tok, const void* embed, float* x, int rows, int rows_pad, int d,
+                      const float* gain, float eps, void* h, hipStream_t st) {
   hipLaunchKernelGGL((norm_kernel<T, true>), dim3(rows), dim3(256), 0, st, tok, static_cast<const T*>(embed), x,
-                     (const float*)nullptr, 0, rows, d, gain, eps, static_cast<T*>(h), (T*)nullptr, 0);
+                     (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr, 0);
   DS_LAUNCH_CHECK("norm_kernel<embed>");
   return DS_OK;
 }
 
 template <typename T>
-int launch_add_norm(float* x, const float* part, int n_part, int rows, int d, const float* gain, float eps, void* h,
-                    void* rm_out, int rm_row0, hipStream_t st) {
+int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
+                    float eps, void* h, float* rm_out, int rm_row0, hipStream_t st) {
   hipLaunchKernelGGL((norm_kernel<T, false>), dim3(rows), dim3(256), 0, st, (const int32_t*)nullptr,
-                     (const T*)nullptr, x, part, n_part, rows, d, gain, eps, static_cast<T*>(h),
-                     static_cast<T*>(rm_out), rm_row0);
+                     (const T*)nullptr, x, part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out,
+                     rm_row0);
   DS_LAUNCH_CHECK("norm_kernel<add>");
   return DS_OK;
 }
 
 template <typename T>
-int launch_to_gemm_input(const void* src, int rows, int d, void* dst, hipStream_t st) {
-  hipLaunchKernelGGL((to_gemm_input_kernel<T>), dim3(rows), dim3(256), 0, st, static_cast<const T*>(src), rows, d,
+int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* dst, hipStream_t st) {
+  hipLaunchKernelGGL((to_gemm_input_kernel<T>), dim3(rows), dim3(256), 0, st, src, rows_pad, d,
                      static_cast<T*>(dst));
   DS_LAUNCH_CHECK("to_gemm_input_kernel");
   return DS_OK;
@@ -200,29 +204,29 @@ template <typename T>
 int launch_qkv_rope(const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv, int hd,
                     const float2* cs, int pos0, int cap, void* q, void* kc, void* vc, hipStream_t st) {
   hipLaunchKernelGGL((qkv_rope_kernel<T>), dim3(rows, n_q + 2 * n_kv), dim3(hd / 2), 0, st, part, n_part, rows,
-                     rows_pad, n_q, n_kv, hd, cs, pos0, cap, static_cast<T*>(q), static_cast<T*>(kc),
-                     static_cast<T*>(vc));
+                     rows_pad, n_q, n_kv, hd, cs, pos0, cap, static_cast<typename Act<T>::kv_t*>(q),
+                     static_cast<typename Act<T>::kv_t*>(kc), static_cast<typename Act<T>::kv_t*>(vc));
   DS_LAUNCH_CHECK("qkv_rope_kernel");
   return DS_OK;
 }
 
 template <typename T>
-int launch_swiglu(const float* part, int n_part, int rows, int F, void* act, hipStream_t st) {
-  hipLaunchKernelGGL((swiglu_kernel<T>), dim3(ceil_div(F, 256), rows), dim3(256), 0, st, part, n_part, rows, F,
-                     static_cast<T*>(act));
+int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, hipStream_t st) {
+  hipLaunchKernelGGL((swiglu_kernel<T>), dim3(ceil_div(F, 256), rows), dim3(256), 0, st, part, n_part, rows,
+                     rows_pad, F, static_cast<T*>(act));
   DS_LAUNCH_CHECK("swiglu_kernel");
   return DS_OK;
 }
 
 #define DS_INSTANTIATE(T)                                                                                          \
-  template int launch_embed_norm<T>(const int32_t*, const void*, float*, int, int, const float*, float, void*,     \
-                                    hipStream_t);                                                                  \
-  template int launch_add_norm<T>(float*, const float*, int, int, int, const float*, float, void*, void*, int,    \
-                                  hipStream_t);                                                                    \
-  template int launch_to_gemm_input<T>(const void*, int, int, void*, hipStream_t);                                 \
+  template int launch_embed_norm<T>(const int32_t*, const void*, float*, int, int, int, const float*, float,       \
+                                    void*, hipStream_t);                                                           \
+  template int launch_add_norm<T>(float*, const float*, int, int, int, int, const float*, float, void*, float*,   \
+                                  int, hipStream_t);                                                               \
+  template int launch_to_gemm_input<T>(const float*, int, int, int, void*, hipStream_t);                           \
   template int launch_qkv_rope<T>(const float*, int, int, int, int, int, int, const float2*, int, int, void*,     \
                                   void*, void*, hipStream_t);                                                      \
-  template int launch_swiglu<T>(const float*, int, int, int, void*, hipStream_t);
+  template int launch_swiglu<T>(const float*, int, int, int, int, void*, hipStream_t);
 DS_INSTANTIATE(float)
 DS_INSTANTIATE(bf16_t)
 

@@ -12,9 +12,11 @@
 //     one tile with one fully coalesced 16-byte-per-lane load and feeds it to the matrix core
 //     with no LDS round trip.  A wavefront walks K for its NB row blocks, so its loads form NB
 //     contiguous streams.
-//   * X (tile order, see xt_offset) is staged through LDS in chunks of 128 columns and shared by
-//     the 4 wavefronts of the workgroup; weight tiles for the next chunk are already in flight
-//     while the current chunk is multiplied.
+//   * X arrives as two bf16 planes (hi, lo with x ~ hi + lo, tile order, see xt_offset); both are
+//     multiplied with the same weight tile, so the activation keeps ~16 mantissa bits although every
+//     matrix-core product is bf16 x bf16 with float32 accumulation.  X is staged through LDS in
+//     chunks of 128 (or 64) columns and shared by the 4 wavefronts of the workgroup; weight tiles
+//     for the next chunk are already in flight while the current chunk is multiplied.
 //   * D[i][j] of the MFMA = out[16 mb + j][16 nb + i]: lane (16 g + j) ends with 4 consecutive
 //     output columns of row j, stored as one float4.
 //   * Split-K writes float32 partial planes out[s][M][N]; the consumer kernel sums them in a fixed
@@ -31,7 +33,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr int kGemmThreads = 256;
-constexpr int kKSC = 4;  // k-steps (of 32) per LDS chunk: 128 columns
+constexpr int kGroup = 4;  // split-K granularity in k-steps of 32: 128 columns
+// k-steps per LDS chunk: 128 columns for up to 64 rows, 64 columns above (keeps LDS <= 72 KB)
+constexpr int ksc_for(int MB) { return MB <= 4 ? 4 : 2; }
 
 // Copy a canonical row-major bf16 matrix W[N, K] into stream order.  One thread per 16-byte piece.
 __global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K, uint16_t* __restrict__ dst) {
@@ -51,14 +55,17 @@ __global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K,
 template <int MB, int NB>
 __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
                                                                  const uint16_t* __restrict__ xt, int M, int N,
-                                                                 int K, int chunks_per_split,
+                                                                 int K, int groups_per_split,
                                                                  float* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) uint16_t xs[2][MB * kKSC * 512];
+  constexpr int kKSC = ksc_for(MB);
+  constexpr int kTiles = 2 * MB * kKSC;  // X tiles per chunk: (hi, lo) x row blocks x k-steps
+  __shared__ __attribute__((aligned(16))) uint16_t xs[2][kTiles * 512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n_blocks = N >> 4, ksteps = K >> 5, n_chunks = ksteps / kKSC;
-  const int c_begin = blockIdx.y * chunks_per_split;
-  int c_end = c_begin + chunks_per_split;
+  const int c_begin = blockIdx.y * groups_per_split * (kGroup / kKSC);
+  int c_end = c_begin + groups_per_split * (kGroup / kKSC);
   if (c_end > n_chunks) c_end = n_chunks;
+  const size_t plane = (size_t)MB * 16 * K;  // elements between the hi and the lo plane
 
   int nb[NB];
   const uint16_t* wrow[NB];
@@ -75,7 +82,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
 #pragma unroll
     for (int m = 0; m < MB; ++m) acc[b][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  constexpr int kPieces = MB * kKSC * 64;  // 16-byte pieces of X per chunk
+  constexpr int kPieces = kTiles * 64;  // 16-byte pieces of X per chunk, order [plane][mb][s][lane]
   constexpr int kXPer = (kPieces + kGemmThreads - 1) / kGemmThreads;
   uint4 xreg[kXPer];
   bf16x8 areg[2][NB][kKSC];
@@ -85,8 +92,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
     for (int p = 0; p < kXPer; ++p) {
       const int piece = threadIdx.x + p * kGemmThreads;
       if (piece < kPieces) {
-        const int mb = piece / (kKSC * 64), rest = piece - mb * (kKSC * 64);
-        xreg[p] = *reinterpret_cast<const uint4*>(xt + ((size_t)mb * ksteps + (size_t)c * kKSC) * 512 + rest * 8);
+        const int pm = piece / (kKSC * 64), rest = piece - pm * (kKSC * 64);  // pm = plane * MB + mb
+        const int pl = pm / MB, mb = pm - pl * MB;
+        xreg[p] = *reinterpret_cast<const uint4*>(xt + pl * plane + ((size_t)mb * ksteps + (size_t)c * kKSC) * 512 +
+                                                  rest * 8);
       }
     }
   };
@@ -107,15 +116,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
   auto compute = [&](int set, int buf) {
 #pragma unroll
     for (int s = 0; s < kKSC; ++s) {
-      bf16x8 bx[MB];
 #pragma unroll
-      for (int m = 0; m < MB; ++m)
-        bx[m] = *reinterpret_cast<const bf16x8*>(&xs[buf][((m * kKSC + s) * 64 + lane) * 8]);
-#pragma unroll
-      for (int b = 0; b < NB; ++b)
+      for (int pl = 0; pl < 2; ++pl) {
+        bf16x8 bx[MB];
 #pragma unroll
         for (int m = 0; m < MB; ++m)
-          acc[b][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[set][b][s], bx[m], acc[b][m], 0, 0, 0);
+          bx[m] = *reinterpret_cast<const bf16x8*>(&xs[buf][(((pl * MB + m) * kKSC + s) * 64 + lane) * 8]);
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+          for (int m = 0; m < MB; ++m)
+            acc[b][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[set][b][s], bx[m], acc[b][m], 0, 0, 0);
+      }
     }
   };
 
@@ -150,7 +162,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
 
   // D[i][j]: lane (16 g + j) holds rows i = 4 g .. 4 g + 3 of column j  ->  out[m = 16 mb + j][n = 16 nb + 4 g ..]
   const int j = lane & 15, g = lane >> 4;
-  float* plane = out + (size_t)blockIdx.y * M * N;
+  float* out_plane = out + (size_t)blockIdx.y * M * N;
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
     if (nb[b] >= n_blocks) continue;
@@ -159,7 +171,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
       const int row = m * 16 + j;
       if (row < M) {
         float4 v = make_float4(acc[b][m][0], acc[b][m][1], acc[b][m][2], acc[b][m][3]);
-        *reinterpret_cast<float4*>(plane + (size_t)row * N + nb[b] * 16 + g * 4) = v;
+        *reinterpret_cast<float4*>(out_plane + (size_t)row * N + nb[b] * 16 + g * 4) = v;
       }
     }
   }
@@ -195,13 +207,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 template <int MB>
 int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, int nbw, int n_split, float* out,
                    hipStream_t st) {
-  const int n_chunks = (K >> 5) / kKSC;
-  const int cps = ceil_div(n_chunks, n_split);
+  const int n_groups = (K >> 5) / kGroup;
+  const int gps = ceil_div(n_groups, n_split);
   dim3 grid(ceil_div(N >> 4, 4 * nbw), n_split);
   if (nbw == 1)
-    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 1>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, cps, out);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 1>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, out);
   else
-    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 2>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, cps, out);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 2>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, out);
   DS_LAUNCH_CHECK("gemm_bf16_kernel");
   return DS_OK;
 }
@@ -221,13 +233,13 @@ int launch_pack_weight(const void* w, int N, int K, void* dst, hipStream_t st) {
 // Number of float32 partial planes gemm_bf16 will write for this shape (the consumer sums them).
 int gemm_bf16_splits(int N, int K, int nbw) {
   const int units = ceil_div(N >> 4, 4 * nbw);
-  const int n_chunks = (K >> 5) / kKSC;
+  const int n_groups = (K >> 5) / kGroup;
   int s = ceil_div(640, units);
   if (s > 8) s = 8;
-  if (s > n_chunks) s = n_chunks;
+  if (s > n_groups) s = n_groups;
   if (s < 1) s = 1;
-  const int cps = ceil_div(n_chunks, s);
-  return ceil_div(n_chunks, cps);
+  const int gps = ceil_div(n_groups, s);
+  return ceil_div(n_groups, gps);
 }
 
 int launch_gemm_bf16(const void* wp, const void* xt, int M, int N, int K, int nbw, int n_split, float* out,

@@ -94,7 +94,7 @@ class SpecDecoder:
         self.adl = ds.ds_adl_create(params.k_min, params.k_max, params.delta, params.rho)
         m = params.m_max
         i32, f32 = torch.int32, torch.float32
-        self.hidden = torch.empty(k_cap, drafter.cfg.d_model, dtype=drafter.torch_dtype, device=DEV)
+        self.hidden = torch.empty(k_cap, drafter.cfg.d_model, dtype=torch.float32, device=DEV)
         self.d_logits = torch.empty(k_cap, vocab, dtype=f32, device=DEV)
         self.cand_id = torch.empty(k_cap, m, dtype=i32, device=DEV)
         self.cand_logp = torch.empty(k_cap, m, dtype=f32, device=DEV)

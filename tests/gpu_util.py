@@ -79,7 +79,7 @@ class GpuModel:
 
     def draft(self, pending, k: int) -> torch.Tensor:
         p = to_dev(np.asarray(pending, dtype=np.int32)) if len(pending) else None
-        hid = torch.empty(k, self.cfg.d_model, dtype=self.torch_dtype, device=DEV)
+        hid = torch.empty(k, self.cfg.d_model, dtype=torch.float32, device=DEV)
         ds.ds_draft_block(self.handle, p, len(pending), k, self.cfg.mask_id, hid, self.ws)
         return hid
 

@@ -58,7 +58,7 @@ def _round_trip(cfg, w, prefix, pending_extra, k1, k2, kv_cap, seed):
         torch.cuda.synchronize()
         assert gm.kv_len == len(prefix) + 1 and oc.length == gm.kv_len
         h_err = np.max(np.abs(gu.from_dev(hid) - ref_hid))
-        assert h_err <= (5e-2 if cfg.dtype == "bf16" else 1e-4), f"draft hidden err {h_err}"
+        assert h_err <= (1e-2 if cfg.dtype == "bf16" else 1e-4), f"draft hidden err {h_err}"
         ref_logits = o_model.lm_head(w, ref_hid)
         l_err = np.max(np.abs(gu.from_dev(logits) - ref_logits))
         assert l_err <= tol, f"draft logits err {l_err}"
@@ -143,16 +143,17 @@ def test_small_bf16_two_layers_gqa():
     _round_trip(cfg, w, prefix, [9, 8, 7, 6, 5], 17, 40, kv_cap=256, seed=3)
 
 
-def test_bf16_lm_head_is_a_plain_gemm_on_bf16_inputs():
-    """hidden (bf16) x W^T with float32 accumulation: only summation order differs from the oracle."""
+def test_bf16_lm_head_is_a_plain_gemm():
+    """hidden (float32, split into two bf16 terms) x W^T with float32 accumulation: only the ~2^-17 relative
+    residue of the split and the summation order differ from the oracle."""
     cfg = SMALL_BF16
     w = synth.make_weights(cfg, 20, std=0.05)
     gm = gu.GpuModel(cfg, w, 64)
     try:
         rng = np.random.default_rng(0)
         for rows in (1, 16, 17, 33, 100, 144):
-            hid = synth.round_to_bf16(rng.standard_normal((rows, cfg.d_model)).astype(np.float32))
-            got = gu.from_dev(gm.lm_head(gu.to_dev(hid, bf16=True)))
+            hid = rng.standard_normal((rows, cfg.d_model)).astype(np.float32)
+            got = gu.from_dev(gm.lm_head(gu.to_dev(hid)))
             ref = o_model.lm_head(w, hid.astype(np.float64))
             assert np.max(np.abs(got - ref)) < 2e-5 * np.sqrt(cfg.d_model), rows
     finally:
@@ -183,7 +184,7 @@ def test_argument_errors_with_a_live_model():
             gm.set_kv_len(65)
         assert e.value.code == ds.DS_E_CAPACITY
         small_ws = torch.empty(1024, dtype=torch.uint8, device=gu.DEV)
-        hid = torch.empty(4, cfg.d_model, dtype=torch.bfloat16, device=gu.DEV)
+        hid = torch.empty(4, cfg.d_model, dtype=torch.float32, device=gu.DEV)
         with pytest.raises(ds.DsError) as e:
             ds.ds_draft_block(gm.handle, None, 0, 4, cfg.mask_id, hid, small_ws)
         assert e.value.code == ds.DS_E_CAPACITY
