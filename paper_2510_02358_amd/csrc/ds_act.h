@@ -45,6 +45,10 @@ struct Act<float> {
   __device__ static __forceinline__ void put(float* base, int m, int k, int K, size_t /*plane*/, float v) {
     base[(size_t)m * K + k] = v;
   }
+  // four consecutive columns k .. k+3 (k % 4 == 0)
+  __device__ static __forceinline__ void put4(float* base, int m, int k, int K, size_t /*plane*/, float4 v) {
+    *reinterpret_cast<float4*>(base + (size_t)m * K + k) = v;
+  }
   __device__ static __forceinline__ size_t q_off(int m, int k, int K) { return (size_t)m * K + k; }
   __device__ static __forceinline__ float to_kv(float v) { return v; }
   __device__ static __forceinline__ float weight(float v) { return v; }
@@ -60,6 +64,20 @@ struct Act<bf16_t> {
     const uint16_t hi = float_to_bf16_bits(v);
     base[off].bits = hi;
     base[plane + off].bits = float_to_bf16_bits(v - bf16_bits_to_float(hi));
+  }
+  // four consecutive columns k .. k+3 (k % 4 == 0) are adjacent in tile order: one 8-byte store per plane
+  __device__ static __forceinline__ void put4(bf16_t* base, int m, int k, int K, size_t plane, float4 v) {
+    const size_t off = xt_offset(m, k, K);
+    const float f[4] = {v.x, v.y, v.z, v.w};
+    uint16_t hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      hi[i] = float_to_bf16_bits(f[i]);
+      lo[i] = float_to_bf16_bits(f[i] - bf16_bits_to_float(hi[i]));
+    }
+    *reinterpret_cast<uint2*>(base + off) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+    *reinterpret_cast<uint2*>(base + plane + off) =
+        make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
   }
   __device__ static __forceinline__ size_t q_off(int m, int k, int K) { return xt_offset(m, k, K); }
   __device__ static __forceinline__ uint16_t to_kv(float v) { return float_to_half_bits(v); }

@@ -62,7 +62,8 @@ int validate_cfg(const ds_model_cfg* c) {
                  c->d_ffn >= 1 && c->vocab >= 2 && c->kv_capacity >= 1,
              DS_E_SHAPE, "model dimensions must be positive");
   DS_REQUIRE(c->n_q % c->n_kv == 0, DS_E_SHAPE, "n_q %d is not a multiple of n_kv %d", c->n_q, c->n_kv);
-  DS_REQUIRE(c->d_model <= 8192, DS_E_SHAPE, "d_model %d exceeds 8192", c->d_model);
+  DS_REQUIRE(c->d_model <= 8192 && c->d_model % 4 == 0, DS_E_SHAPE, "d_model %d: need a multiple of 4, at most 8192",
+             c->d_model);
   DS_REQUIRE(c->head_dim % 2 == 0 && c->head_dim <= 128, DS_E_UNSUPPORTED, "head_dim %d: need even and <= 128",
              c->head_dim);
   DS_REQUIRE(c->rope_base > 1.f && c->rms_eps >= 0.f, DS_E_INVALID, "rope_base must exceed 1, rms_eps >= 0");

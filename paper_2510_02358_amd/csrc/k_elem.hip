@@ -22,8 +22,6 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
   return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-constexpr int kMaxPerThread = 32;  // d_model <= 8192 with 256 threads
-
 // tok[r] = r < n_real ? src[r] : fill ; ids outside [0, vocab) become 0.
 __global__ void tokens_kernel(const int32_t* __restrict__ src, int n_real, int rows, int32_t fill, int vocab,
                               int32_t* __restrict__ tok) {
@@ -43,9 +41,14 @@ __global__ void rope_table_kernel(int pos0, int rows, int half, double base, flo
   cs[r * half + i] = make_float2((float)c, (float)s);
 }
 
-// x[r] = E[tok[r]] (+ sum of partial planes) ; h[r] = rmsnorm(x[r]) * gain, written as GEMM input.
+constexpr int kMaxVec = 8;     // float4 groups per thread: d_model <= 8192 with 256 threads
+constexpr int kMaxPlanes = 8;  // split-K planes summed per element
+
+// x[r] = E[tok[r]] or x[r] + sum of split-K planes ; h[r] = rmsnorm(x[r]) * gain, written as GEMM input.
 // FROM_EMBED: start from the embedding row, else from the float32 residual x plus `n_part` planes.
 // rm_out (optional): row-major float32 copy of rows >= rm_row0 (the boundary's hidden_out).
+// One workgroup per row, four consecutive columns per thread and step (d_model % 4 == 0); the planes
+// are summed in index order, all loads of a step issued before the first add.
 template <typename T, bool FROM_EMBED>
 __global__ __launch_bounds__(256) void norm_kernel(const int32_t* __restrict__ tok, const T* __restrict__ embed,
                                                    float* __restrict__ x, const float* __restrict__ part,
@@ -54,34 +57,44 @@ __global__ __launch_bounds__(256) void norm_kernel(const int32_t* __restrict__ t
                                                    float* __restrict__ rm_out, int rm_row0) {
   __shared__ float red[4];
   const int r = blockIdx.x;
-  float v[kMaxPerThread];
+  float4 v[kMaxVec];
   float ss = 0.f;
 #pragma unroll
-  for (int i = 0; i < kMaxPerThread; ++i) {
-    const int c = threadIdx.x + i * 256;
-    v[i] = 0.f;
+  for (int i = 0; i < kMaxVec; ++i) {
+    const int c = (threadIdx.x + i * 256) * 4;
+    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (c < d) {
-      float a;
+      float4 a;
       if (FROM_EMBED) {
-        a = Act<T>::weight(embed[(size_t)tok[r] * d + c]);
+        const T* e = embed + (size_t)tok[r] * d + c;
+        a = make_float4(Act<T>::weight(e[0]), Act<T>::weight(e[1]), Act<T>::weight(e[2]), Act<T>::weight(e[3]));
       } else {
-        a = x[(size_t)r * d + c];
-        for (int s = 0; s < n_part; ++s) a += part[((size_t)s * rows + r) * d + c];
+        a = *reinterpret_cast<const float4*>(x + (size_t)r * d + c);
+        float4 p[kMaxPlanes];
+#pragma unroll
+        for (int s = 0; s < kMaxPlanes; ++s)
+          p[s] = s < n_part ? *reinterpret_cast<const float4*>(part + ((size_t)s * rows + r) * d + c)
+                            : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int s = 0; s < kMaxPlanes; ++s) {
+          a.x += p[s].x; a.y += p[s].y; a.z += p[s].z; a.w += p[s].w;
+        }
       }
-      x[(size_t)r * d + c] = a;
+      *reinterpret_cast<float4*>(x + (size_t)r * d + c) = a;
       v[i] = a;
-      ss += a * a;
+      ss += (a.x * a.x + a.y * a.y) + (a.z * a.z + a.w * a.w);
     }
   }
   ss = block_sum_256(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
-  for (int i = 0; i < kMaxPerThread; ++i) {
-    const int c = threadIdx.x + i * 256;
+  for (int i = 0; i < kMaxVec; ++i) {
+    const int c = (threadIdx.x + i * 256) * 4;
     if (c < d) {
-      const float y = v[i] * inv * gain[c];
-      Act<T>::put(h, r, c, d, (size_t)rows_pad * d, y);
-      if (rm_out && r >= rm_row0) rm_out[(size_t)(r - rm_row0) * d + c] = y;
+      const float4 gn = *reinterpret_cast<const float4*>(gain + c);
+      const float4 y = make_float4(v[i].x * inv * gn.x, v[i].y * inv * gn.y, v[i].z * inv * gn.z, v[i].w * inv * gn.w);
+      Act<T>::put4(h, r, c, d, (size_t)rows_pad * d, y);
+      if (rm_out && r >= rm_row0) *reinterpret_cast<float4*>(rm_out + (size_t)(r - rm_row0) * d + c) = y;
     }
   }
 }

@@ -23,12 +23,15 @@
 //     order (deterministic, no atomics).
 //
 // f32 path: a plain wavefront-per-output-column kernel for the float32 parity mode.
+#include <type_traits>
+
 #include "ds_common.h"
 
 namespace ds {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -82,38 +85,37 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
 #pragma unroll
     for (int m = 0; m < MB; ++m) acc[b][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  constexpr int kPieces = kTiles * 64;  // 16-byte pieces of X per chunk, order [plane][mb][s][lane]
-  constexpr int kXPer = (kPieces + kGemmThreads - 1) / kGemmThreads;
-  uint4 xreg[kXPer];
-  bf16x8 areg[2][NB][kKSC];
+  // 16-byte pieces of X per chunk, order [plane][mb][s][lane]; kTiles is a multiple of 4, so every
+  // thread moves exactly kXPer pieces (no tail predicate: the loads issue back to back).
+  constexpr int kXPer = kTiles * 64 / kGemmThreads;
+  static_assert((kTiles * 64) % kGemmThreads == 0, "X chunk must split evenly over the workgroup");
+  constexpr int kStages = 3;  // weight-tile register sets: two chunks are in flight while one is multiplied
+  u32x4 xreg[kXPer];
+  bf16x8 areg[kStages][NB][kKSC];
 
   auto load_x = [&](int c) {
 #pragma unroll
     for (int p = 0; p < kXPer; ++p) {
       const int piece = threadIdx.x + p * kGemmThreads;
-      if (piece < kPieces) {
-        const int pm = piece / (kKSC * 64), rest = piece - pm * (kKSC * 64);  // pm = plane * MB + mb
-        const int pl = pm / MB, mb = pm - pl * MB;
-        xreg[p] = *reinterpret_cast<const uint4*>(xt + pl * plane + ((size_t)mb * ksteps + (size_t)c * kKSC) * 512 +
-                                                  rest * 8);
-      }
+      const int pm = piece / (kKSC * 64), rest = piece - pm * (kKSC * 64);  // pm = plane * MB + mb
+      const int pl = pm / MB, mb = pm - pl * MB;
+      xreg[p] = *reinterpret_cast<const u32x4*>(xt + pl * plane + ((size_t)mb * ksteps + (size_t)c * kKSC) * 512 +
+                                                rest * 8);
     }
   };
   auto store_x = [&](int buf) {
 #pragma unroll
-    for (int p = 0; p < kXPer; ++p) {
-      const int piece = threadIdx.x + p * kGemmThreads;
-      if (piece < kPieces) *reinterpret_cast<uint4*>(&xs[buf][piece * 8]) = xreg[p];
-    }
+    for (int p = 0; p < kXPer; ++p)
+      *reinterpret_cast<u32x4*>(&xs[buf][(threadIdx.x + p * kGemmThreads) * 8]) = xreg[p];
   };
-  auto load_a = [&](int set, int c) {
+  auto load_a = [&](auto set, int c) {
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int s = 0; s < kKSC; ++s)
         areg[set][b][s] = *reinterpret_cast<const bf16x8*>(wrow[b] + ((size_t)c * kKSC + s) * 512);
   };
-  auto compute = [&](int set, int buf) {
+  auto compute = [&](auto set, int buf) {
 #pragma unroll
     for (int s = 0; s < kKSC; ++s) {
 #pragma unroll
@@ -130,33 +132,42 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
       }
     }
   };
+  // One pipeline step for chunk c held in register set SET and LDS buffer buf: issue the X loads of chunk
+  // c + 1 and the weight loads of chunk c + 2 first, multiply chunk c, then publish X(c + 1) in LDS.  X is
+  // loaded BEFORE the weights so that waiting for it leaves the younger weight loads in flight.
+  // Past the last chunk the loads are clamped to it instead of predicated (branch-free body; the
+  // redundant tiles are never multiplied).
+  const int c_last = c_end - 1;
+  auto step = [&](auto set, int c, int buf) {
+    constexpr int SET = decltype(set)::value;
+    load_x(c + 1 < c_last ? c + 1 : c_last);
+    __builtin_amdgcn_sched_barrier(0);  // keep the issue order: X loads, then weight loads, then math
+    load_a(std::integral_constant<int, (SET + 2) % kStages>{}, c + 2 < c_last ? c + 2 : c_last);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(set, buf);
+    __builtin_amdgcn_sched_barrier(0);
+    store_x(buf ^ 1);
+    __syncthreads();
+  };
 
   if (c_begin < c_end) {
-    load_a(0, c_begin);
     load_x(c_begin);
+    load_a(std::integral_constant<int, 0>{}, c_begin);
+    load_a(std::integral_constant<int, 1>{}, c_begin + 1 < c_last ? c_begin + 1 : c_last);
     store_x(0);
     __syncthreads();
-    int buf = 0;
-    for (int c = c_begin; c < c_end; c += 2) {
-      // even step: registers set 0 hold chunk c
-      if (c + 1 < c_end) {
-        load_a(1, c + 1);
-        load_x(c + 1);
-      }
-      compute(0, buf);
-      if (c + 1 < c_end) store_x(buf ^ 1);
-      __syncthreads();
+    // Main loop: groups of three chunks with no branch between the steps, so that the three steps form
+    // one basic block and every prefetch stays where it is issued (two chunks ahead of its use).
+    int buf = 0, c = c_begin;
+    for (; c + kStages <= c_end; c += kStages) {
+      step(std::integral_constant<int, 0>{}, c, buf);
+      step(std::integral_constant<int, 1>{}, c + 1, buf ^ 1);
+      step(std::integral_constant<int, 2>{}, c + 2, buf);
       buf ^= 1;
-      if (c + 1 >= c_end) break;
-      // odd step: registers set 1 hold chunk c + 1
-      if (c + 2 < c_end) {
-        load_a(0, c + 2);
-        load_x(c + 2);
-      }
-      compute(1, buf);
-      if (c + 2 < c_end) store_x(buf ^ 1);
-      __syncthreads();
-      buf ^= 1;
+    }
+    if (c < c_end) {  // one or two chunks left; c - c_begin is a multiple of three, so set 0 holds chunk c
+      step(std::integral_constant<int, 0>{}, c, buf);
+      if (c + 1 < c_end) step(std::integral_constant<int, 1>{}, c + 1, buf ^ 1);
     }
   }
 

@@ -226,10 +226,27 @@ __global__ __launch_bounds__(256) void accept_merge_kernel(int rows, int n_part,
   __shared__ int32_t am[DS_MAX_ROWS];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   for (int r = wave; r < rows; r += 4) {
+    // arg-max over the per-wavefront winners of this row: plain (value, lower id) reduction
     const uint32_t* rec0 = partial + (size_t)r * n_part * rec_dwords(1);
-    float ev;
-    int eid;
-    merge_lists(rec0, n_part, 1, lane, ev, eid);
+    float ev = -INFINITY;
+    int eid = INT_MAX;
+    for (int p = lane; p < n_part; p += kWave) {
+      const float x = __uint_as_float(rec0[(size_t)p * rec_dwords(1) + 2]);
+      const int xid = (int)rec0[(size_t)p * rec_dwords(1) + 3];
+      if (beats(x, xid, ev, eid)) {
+        ev = x;
+        eid = xid;
+      }
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+      const float ov = __shfl_xor(ev, off);
+      const int oid = __shfl_xor(eid, off);
+      if (beats(ov, oid, ev, eid)) {
+        ev = ov;
+        eid = oid;
+      }
+    }
     if (lane == 0) {
       am[r] = eid;
       argmax_out[r] = eid;
