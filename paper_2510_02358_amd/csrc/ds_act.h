@@ -85,11 +85,11 @@ struct Act<bf16_t> {
 };
 
 // ---- launchers implemented in k_elem.hip / k_gemm.hip / k_attn.hip --------------------------------
-int launch_tokens(const int32_t* src, int n_real, int rows, int32_t fill, int vocab, int32_t* tok, hipStream_t st);
-int launch_rope_table(int pos0, int rows, int hd, double base, float2* cs, hipStream_t st);
+// First kernel of a forward: token gather (rows past n_real are `fill`), rotary table, embedding, RMSNorm.
 template <typename T>
-int launch_embed_norm(const int32_t* tok, const void* embed, float* x, int rows, int rows_pad, int d,
-                      const float* gain, float eps, void* h, hipStream_t st);
+int launch_embed_norm(const int32_t* src, int n_real, int32_t fill, int vocab, int pos0, int hd, double rope_base,
+                      float2* cs, const void* embed, float* x, int rows, int rows_pad, int d, const float* gain,
+                      float eps, void* h, hipStream_t st);
 template <typename T>
 int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
                     float eps, void* h, float* rm_out, int rm_row0, hipStream_t st);

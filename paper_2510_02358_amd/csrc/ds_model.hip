@@ -19,7 +19,6 @@ struct PackedLayer {
 
 // Carve-up of the caller's workspace for a call with `rows` rows (all offsets 256-byte aligned).
 struct Workspace {
-  int32_t* tok;
   float* x;        // [rows, d] residual stream
   float2* cs;      // [rows, hd/2] rotary table
   void* h;         // GEMM input, d columns
@@ -64,6 +63,7 @@ int validate_cfg(const ds_model_cfg* c) {
   DS_REQUIRE(c->n_q % c->n_kv == 0, DS_E_SHAPE, "n_q %d is not a multiple of n_kv %d", c->n_q, c->n_kv);
   DS_REQUIRE(c->d_model <= 8192 && c->d_model % 4 == 0, DS_E_SHAPE, "d_model %d: need a multiple of 4, at most 8192",
              c->d_model);
+  DS_REQUIRE(c->d_ffn % 4 == 0, DS_E_SHAPE, "d_ffn %d: need a multiple of 4", c->d_ffn);
   DS_REQUIRE(c->head_dim % 2 == 0 && c->head_dim <= 128, DS_E_UNSUPPORTED, "head_dim %d: need even and <= 128",
              c->head_dim);
   DS_REQUIRE(c->rope_base > 1.f && c->rms_eps >= 0.f, DS_E_INVALID, "rope_base must exceed 1, rms_eps >= 0");
@@ -114,7 +114,6 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
     off += align_up(bytes, 256);
     return p;
   };
-  w.tok = static_cast<int32_t*>(take((size_t)rows * 4));
   w.x = static_cast<float*>(take((size_t)rows * c.d_model * 4));
   w.cs = static_cast<float2*>(take((size_t)rows * (c.head_dim / 2) * 8));
   const size_t planes = c.dtype == DS_BF16 ? 2 : 1;  // GEMM inputs: (hi, lo) bf16 pair or one float32 plane
@@ -188,15 +187,16 @@ int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float
 // tokens, the rest are [MASK] rows.  Leaves the final-normed states of all rows in ws.y (GEMM input
 // order) and, if hidden_out is given, a row-major copy of rows >= hidden_row0 there.
 template <typename T>
-int forward_rows(ds_model* m, const Workspace& w, int rows, int n_causal, float* hidden_out, int hidden_row0,
-                 hipStream_t st) {
+int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real, int32_t fill, int rows,
+                 int n_causal, float* hidden_out, int hidden_row0, hipStream_t st) {
   const ds_model_cfg& c = m->cfg;
   const int rp = ceil_div(rows, 16) * 16;
   const int pos0 = m->kv_len, n_keys = pos0 + rows;
   const int d = c.d_model, hd = c.head_dim;
   int rc;
-  if ((rc = launch_rope_table(pos0, rows, hd, (double)c.rope_base, w.cs, st))) return rc;
-  if ((rc = launch_embed_norm<T>(w.tok, m->embed, w.x, rows, rp, d, m->canon[0].norm1, c.rms_eps, w.h, st))) return rc;
+  if ((rc = launch_embed_norm<T>(src, n_real, fill, c.vocab, pos0, hd, (double)c.rope_base, w.cs, m->embed, w.x, rows,
+                                 rp, d, m->canon[0].norm1, c.rms_eps, w.h, st)))
+    return rc;
   const int n_split_att = attn_splits(c.dtype, n_keys);
   DS_REQUIRE(n_split_att <= attn_max_splits(c.dtype, c.kv_capacity), DS_E_CAPACITY,
              "attention partials: %d splits exceed the workspace's %d", n_split_att,
@@ -228,10 +228,12 @@ int forward_rows(ds_model* m, const Workspace& w, int rows, int n_causal, float*
   return DS_OK;
 }
 
-int forward_dispatch(ds_model* m, const Workspace& w, int rows, int n_causal, float* hidden_out, int hidden_row0,
-                     hipStream_t st) {
-  return m->cfg.dtype == DS_BF16 ? forward_rows<bf16_t>(m, w, rows, n_causal, hidden_out, hidden_row0, st)
-                                 : forward_rows<float>(m, w, rows, n_causal, hidden_out, hidden_row0, st);
+// src: n_real device tokens; rows past n_real are `fill` ([MASK]).
+int forward_dispatch(ds_model* m, const Workspace& w, const int32_t* src, int n_real, int32_t fill, int rows,
+                     int n_causal, float* hidden_out, int hidden_row0, hipStream_t st) {
+  return m->cfg.dtype == DS_BF16
+             ? forward_rows<bf16_t>(m, w, src, n_real, fill, rows, n_causal, hidden_out, hidden_row0, st)
+             : forward_rows<float>(m, w, src, n_real, fill, rows, n_causal, hidden_out, hidden_row0, st);
 }
 
 int lm_head_rows(ds_model* m, const void* y_gemm_in, int rows, float* logits, hipStream_t st) {
@@ -380,8 +382,7 @@ int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, vo
   for (int done = 0; done < n; done += chunk) {
     const int rows = n - done < chunk ? n - done : chunk;
     w = carve(m->cfg, rows, ws);
-    if ((rc = launch_tokens(tokens + done, rows, rows, 0, m->cfg.vocab, w.tok, st)) ||
-        (rc = forward_dispatch(m, w, rows, rows, nullptr, 0, st))) {
+    if ((rc = forward_dispatch(m, w, tokens + done, rows, 0, rows, rows, nullptr, 0, st))) {
       m->kv_len = start_len;
       return rc;
     }
@@ -410,8 +411,7 @@ int ds_draft_block(ds_model* m, const int32_t* pending, int n_pend, int K, int32
   int rc = check_ws(m, rows, ws, ws_bytes, &w);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = launch_tokens(pending, n_pend, rows, mask_id, m->cfg.vocab, w.tok, st))) return rc;
-  if ((rc = forward_dispatch(m, w, rows, n_pend, hidden_out, n_pend, st))) return rc;
+  if ((rc = forward_dispatch(m, w, pending, n_pend, mask_id, rows, n_pend, hidden_out, n_pend, st))) return rc;
   m->kv_len += n_pend;  // mask rows are never committed
   return DS_OK;
 }
@@ -446,8 +446,7 @@ int ds_verify_block(ds_model* m, const int32_t* block, int mlen, const int32_t* 
   int rc = check_ws(m, rows, ws, ws_bytes, &w);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = launch_tokens(block, rows, rows, 0, m->cfg.vocab, w.tok, st))) return rc;
-  if ((rc = forward_dispatch(m, w, rows, rows, nullptr, 0, st))) return rc;
+  if ((rc = forward_dispatch(m, w, block, rows, 0, rows, rows, nullptr, 0, st))) return rc;
   float* logits = logits_out ? logits_out : w.logits;
   if ((rc = lm_head_rows(m, w.y, rows, logits, st))) return rc;
   return launch_argmax_accept(logits, rows, m->cfg.vocab, block, path_len, eos_id, n_accept, next_token, argmax,

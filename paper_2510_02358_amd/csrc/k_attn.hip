@@ -22,6 +22,8 @@ namespace ds {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -31,8 +33,8 @@ constexpr int kHd = 128;    // head_dim of the bf16 kernel
 union Pack8 {
   f16x8 v;
   uint16_t h[8];
-  uint2 half[2];
-  uint4 q;
+  u32x2 half[2];
+  u32x4 q;
 };
 
 template <int QB>
@@ -77,9 +79,12 @@ __global__ __launch_bounds__(256) void attn_f16_kernel(const uint16_t* __restric
   const uint16_t* kbase = kc + (size_t)kvh * cap * kHd;
   const uint16_t* vbase = vt + (size_t)kvh * kHd * cap;
 
-  for (int c = c_begin; c < c_end; ++c) {
+  // Staging: each thread moves 4 K pieces (16 B) and 4 V^T pieces (2 x 8 B) per chunk, global -> registers ->
+  // LDS; the registers of chunk c + 1 are filled while chunk c is multiplied.
+  u32x4 kreg[4];
+  u32x2 vreg[4][2];
+  auto load_chunk = [&](int c) {
     const int c0 = c * kChunk;
-    __syncthreads();  // previous chunk fully consumed
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       const int tile = wave + 4 * p;
@@ -87,26 +92,47 @@ __global__ __launch_bounds__(256) void attn_f16_kernel(const uint16_t* __restric
         const int kb = tile >> 2, s = tile & 3;
         int key = c0 + kb * 16 + j;
         key = key < n_keys ? key : n_keys - 1;
-        const uint4 v = *reinterpret_cast<const uint4*>(kbase + (size_t)key * kHd + s * 32 + g * 8);
-        *reinterpret_cast<uint4*>(&ks_lds[(tile * 64 + lane) * 8]) = v;
+        kreg[p] = *reinterpret_cast<const u32x4*>(kbase + (size_t)key * kHd + s * 32 + g * 8);
       }
       {  // V^T tile (db, t2): lane (16 g + i) <- V^T[16 db + i][c0 + 32 t2 + {4g..4g+3, 16+4g..16+4g+3}]
         const int db = tile >> 1, t2 = tile & 1;
         const uint16_t* src = vbase + (size_t)(db * 16 + j) * cap + c0 + 32 * t2 + 4 * g;
-        Pack8 pk;
-        pk.half[0] = *reinterpret_cast<const uint2*>(src);
-        pk.half[1] = *reinterpret_cast<const uint2*>(src + 16);
-        if (c0 + kChunk > n_keys) {  // tail chunk: slots past the last key may hold anything -> zero
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int key = c0 + 32 * t2 + 4 * g + (e & 3) + ((e >> 2) << 4);
-            if (key >= n_keys) pk.h[e] = 0;
-          }
-        }
-        *reinterpret_cast<uint4*>(&vs_lds[(tile * 64 + lane) * 8]) = pk.q;
+        vreg[p][0] = *reinterpret_cast<const u32x2*>(src);
+        vreg[p][1] = *reinterpret_cast<const u32x2*>(src + 16);
       }
     }
-    __syncthreads();
+  };
+  auto store_chunk = [&](int c) {
+    const int c0 = c * kChunk;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int tile = wave + 4 * p;
+      *reinterpret_cast<u32x4*>(&ks_lds[(tile * 64 + lane) * 8]) = kreg[p];
+      Pack8 pk;
+      pk.half[0] = vreg[p][0];
+      pk.half[1] = vreg[p][1];
+      if (c0 + kChunk > n_keys) {  // tail chunk: slots past the last key may hold anything -> zero
+        const int t2 = tile & 1;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int key = c0 + 32 * t2 + 4 * g + (e & 3) + ((e >> 2) << 4);
+          if (key >= n_keys) pk.h[e] = 0;
+        }
+      }
+      *reinterpret_cast<u32x4*>(&vs_lds[(tile * 64 + lane) * 8]) = pk.q;
+    }
+  };
+
+  if (c_begin < c_end) {
+    load_chunk(c_begin);
+    store_chunk(c_begin);
+  }
+  __syncthreads();
+  for (int c = c_begin; c < c_end; ++c) {
+    const int c0 = c * kChunk;
+    const int c_next = c + 1 < c_end ? c + 1 : c;  // clamped: the last iteration reloads its own chunk
+    load_chunk(c_next);
+    __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
     for (int t = 0; t < QB; ++t) {
@@ -161,6 +187,10 @@ __global__ __launch_bounds__(256) void attn_f16_kernel(const uint16_t* __restric
         }
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();  // every wavefront is done reading chunk c
+    store_chunk(c_next);
+    __syncthreads();
   }
 
 #pragma unroll
@@ -248,22 +278,27 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
 }
 
 // Exact merge of the per-split partial results: out = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M).
+// One workgroup per (row, head), one thread per output column; loops are unrolled so that the loads of
+// several splits are in flight together.
 template <typename T>
 __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int n_split,
                                   int n_q, int rows_pad, int hd, T* __restrict__ att) {
   // att: GEMM input [rows_pad, n_q * hd] of the output projection
   const int r = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
   if (d >= hd) return;
+  const size_t stride = (size_t)n_q * rows_pad;           // rows between consecutive splits
+  const size_t row0 = (size_t)head * rows_pad + r;
   float mx = -INFINITY;
-  for (int s = 0; s < n_split; ++s)
-    mx = fmaxf(mx, part_ml[(((size_t)s * n_q + head) * rows_pad + r) * 2]);
+#pragma unroll 8
+  for (int s = 0; s < n_split; ++s) mx = fmaxf(mx, part_ml[(row0 + s * stride) * 2]);
   float num = 0.f, den = 0.f;
+#pragma unroll 8
   for (int s = 0; s < n_split; ++s) {
-    const size_t row = ((size_t)s * n_q + head) * rows_pad + r;
+    const size_t row = row0 + s * stride;
     const float m = part_ml[row * 2], l = part_ml[row * 2 + 1];
-    if (m == -INFINITY) continue;
-    const float w = expf(m - mx);
-    num += part_o[row * hd + d] * w;
+    const float o = part_o[row * hd + d];
+    const float w = (m == -INFINITY) ? 0.f : expf(m - mx);
+    num += o * w;
     den += l * w;
   }
   Act<T>::put(att, r, head * hd + d, n_q * hd, (size_t)rows_pad * n_q * hd, num / den);
@@ -271,7 +306,7 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
 
 int chunks_per_split(int dtype, int n_keys) {
   const int n_chunks = ceil_div(n_keys, kChunk);
-  const int max_split = dtype == DS_BF16 ? 32 : 16;
+  const int max_split = 16;
   return ceil_div(n_chunks, max_split);
 }
 
@@ -284,7 +319,7 @@ int attn_splits(int dtype, int n_keys) {
 // Upper bound of attn_splits over every n_keys <= capacity (the split count is not monotone in n_keys).
 int attn_max_splits(int dtype, int capacity) {
   const int cap_chunks = ceil_div(capacity, kChunk);
-  const int max_split = dtype == DS_BF16 ? 32 : 16;
+  const int max_split = 16;
   return cap_chunks < max_split ? cap_chunks : max_split;
 }
 

@@ -1,10 +1,16 @@
 // Causal-consistency path search: left-to-right beam search over the pruned token lattice.
 //
-// One wavefront per sequence.  The search is a chain of K dependent steps, each tiny
-// (B live hypotheses x C candidates <= 16 x 17 expansions), so it is latency-bound: the wavefront
-// keeps the beam in registers (lane b holds hypothesis b), scores one expansion per lane slot,
-// selects the B best with wavefront arg-max reductions over a 64-bit (score, order) key, and
-// records (parent, token) back-pointers in LDS for the final back-track.
+// One workgroup per sequence.  The search itself is a chain of K dependent steps, each tiny
+// (B live hypotheses x C candidates <= 16 x 17 expansions), so it is latency-bound and runs in ONE
+// wavefront: the beam lives in registers (lane b holds hypothesis b), every expansion gets a lane slot,
+// the B best are picked by wavefront arg-max reductions, and (parent, token) back-pointers go to LDS
+// for the final back-track.
+//
+// What dominates a step is the dependent gather of the causal-proxy score T[hash(u, v, w)] from a 16 MB
+// table.  The lattice fixes in advance which tokens can occupy each position, so when K * C^3 scores fit
+// in LDS the whole workgroup first gathers the proxy score of EVERY (u in C[i-2], v in C[i-1], w in C[i])
+// combination in parallel; the sequential search then only touches LDS.  Larger lattices gather on
+// demand inside the step.
 //
 // Arithmetic is float32 with explicitly unfused multiply/add in the order
 //   term = (lambda * l_dlm) + ((1 - lambda) * l_ng);  score = score + term
@@ -19,7 +25,8 @@ namespace {
 
 constexpr int kMaxCand = DS_MAX_TOPM + 1;                          // + retained EOS
 constexpr int kMaxExp = DS_MAX_BEAM * kMaxCand;                    // 272 expansions
-constexpr int kSlots = (kMaxExp + kWave - 1) / kWave;              // 5 per lane
+constexpr int kMaxSlots = (kMaxExp + kWave - 1) / kWave;           // 5 lane slots cover every case
+constexpr size_t kLdsBudget = 120 * 1024;                          // bytes this kernel may use
 
 __device__ __forceinline__ uint32_t ngram_slot(uint32_t u, uint32_t v, uint32_t w, uint32_t mask) {
   uint32_t x = u * 0x9E3779B1u;
@@ -31,174 +38,232 @@ __device__ __forceinline__ uint32_t ngram_slot(uint32_t u, uint32_t v, uint32_t 
   return x & mask;
 }
 
-// Monotone map float -> uint32 (larger float, larger integer).
+// Monotone map float -> uint32 (larger float, larger integer; never 0 for a non-NaN input).
 __device__ __forceinline__ uint32_t ordered_bits(float f) {
   uint32_t u = __float_as_uint(f);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long k) {
-#pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) {
-    unsigned long long o = __shfl_xor(k, off);
-    k = o > k ? o : k;
-  }
-  return k;
+// Wavefront-wide maximum of a uint32, returned in a scalar register: butterfly inside each row of 16
+// lanes with DPP lane permutes (xor 1, xor 2, mirror within 8, mirror within 16), then the four row
+// results are read with constant-lane reads and combined on the scalar unit.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  uint32_t o;
+  o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+  v = o > v ? o : v;
+  o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+  v = o > v ? o : v;
+  o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false);  // row_half_mirror
+  v = o > v ? o : v;
+  o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false);  // row_mirror
+  v = o > v ? o : v;
+  const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+  const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+  const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  const uint32_t a = r0 > r1 ? r0 : r1, b = r2 > r3 ? r2 : r3;
+  return a > b ? a : b;
 }
 
-__global__ __launch_bounds__(kWave) void cps_kernel(const int32_t* __restrict__ cand_id,
-                                                    const float* __restrict__ cand_logp,
-                                                    const int32_t* __restrict__ cand_cnt,
-                                                    const float* __restrict__ eos_logp, int K, int m_max, int B,
-                                                    float lambda, const float* __restrict__ table,
-                                                    uint32_t table_mask, const int32_t* __restrict__ ctx,
-                                                    int32_t eos_id, int32_t* __restrict__ path,
-                                                    int32_t* __restrict__ path_len,
-                                                    float* __restrict__ path_score) {
-  extern __shared__ int32_t smem[];
-  int32_t* bp_tok = smem;                                                  // [K][B]
-  uint8_t* bp_par = reinterpret_cast<uint8_t*>(smem + (size_t)K * B);      // [K][B]
-  const int seq = blockIdx.x, lane = threadIdx.x;
+struct Lds {
+  int4* meta;         // [K] {n_cand, eos_rank (-1: none), ceil(65536 / n_cand), 0}
+  int4* beam;         // [2][B] {score bits, u, v, rank_u | rank_v << 8}
+  int32_t* cand_tok;  // [K][CM]
+  float* cand_lp;     // [K][CM]
+  int32_t* bp_tok;    // [K][B]
+  uint8_t* bp_par;    // [K][B]
+  float* ng;          // [K][CM][CM][CM] or nullptr
+};
+
+__host__ __device__ inline size_t lds_fixed_bytes(int K, int CM, int B) {
+  return (size_t)K * 16 + (size_t)2 * B * 16 + (size_t)K * CM * 8 + (size_t)K * B * 4 +
+         ((size_t)K * B + 15) / 16 * 16;
+}
+
+// PRE: proxy scores pre-gathered into LDS.  kSlots: expansions per lane (B * (M_max + 1) <= 64 * kSlots).
+template <bool PRE, int kSlots>
+__global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ cand_id,
+                                                   const float* __restrict__ cand_logp,
+                                                   const int32_t* __restrict__ cand_cnt,
+                                                   const float* __restrict__ eos_logp, int K, int m_max, int B,
+                                                   float lambda, const float* __restrict__ table,
+                                                   uint32_t table_mask, const int32_t* __restrict__ ctx,
+                                                   int32_t eos_id, int32_t* __restrict__ path,
+                                                   int32_t* __restrict__ path_len, float* __restrict__ path_score) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int CM = m_max + 1;
+  Lds L;
+  {
+    unsigned char* p = smem;
+    L.meta = reinterpret_cast<int4*>(p);        p += (size_t)K * 16;
+    L.beam = reinterpret_cast<int4*>(p);        p += (size_t)2 * B * 16;
+    L.cand_tok = reinterpret_cast<int32_t*>(p); p += (size_t)K * CM * 4;
+    L.cand_lp = reinterpret_cast<float*>(p);    p += (size_t)K * CM * 4;
+    L.bp_tok = reinterpret_cast<int32_t*>(p);   p += (size_t)K * B * 4;
+    L.bp_par = p;                               p += ((size_t)K * B + 15) / 16 * 16;
+    L.ng = PRE ? reinterpret_cast<float*>(p) : nullptr;
+  }
+  const int seq = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), n_thr = blockDim.x;
   const size_t row0 = (size_t)seq * K;
+  const int ctx_u = ctx[seq * 2 + 0], ctx_v = ctx[seq * 2 + 1];
+
+  // ---- phase A (whole workgroup): candidate lists of every position, EOS retained ------------------
+  for (int i = tid; i < K; i += n_thr) {
+    int cnt = cand_cnt[row0 + i];
+    cnt = cnt < 1 ? 1 : (cnt > m_max ? m_max : cnt);
+    int eos_rank = -1;
+    for (int c = 0; c < cnt; ++c) {
+      const int t = cand_id[(row0 + i) * m_max + c];
+      L.cand_tok[i * CM + c] = t;
+      L.cand_lp[i * CM + c] = cand_logp[(row0 + i) * m_max + c];
+      if (eos_id >= 0 && t == eos_id && eos_rank < 0) eos_rank = c;
+    }
+    if (eos_id >= 0 && eos_rank < 0) {
+      L.cand_tok[i * CM + cnt] = eos_id;
+      L.cand_lp[i * CM + cnt] = eos_logp[row0 + i];
+      eos_rank = cnt;
+      ++cnt;
+    }
+    L.meta[i] = make_int4(cnt, eos_rank, (65536 + cnt - 1) / cnt, 0);
+  }
+  __syncthreads();
+
+  if (PRE) {  // proxy score of every (u, v, w) the search can ask for; positions before the block = context
+    const int pairs = K * CM * CM;
+    for (int p = tid; p < pairs; p += n_thr) {
+      const int i = p / (CM * CM), rem = p - i * (CM * CM);
+      const int a = rem / CM, b = rem - a * CM;
+      const int na = i >= 2 ? L.meta[i - 2].x : 1, nb = i >= 1 ? L.meta[i - 1].x : 1;
+      if (a >= na || b >= nb) continue;
+      const uint32_t u = (uint32_t)(i >= 2 ? L.cand_tok[(i - 2) * CM + a] : (i == 1 ? ctx_v : ctx_u));
+      const uint32_t v = (uint32_t)(i >= 1 ? L.cand_tok[(i - 1) * CM + b] : ctx_v);
+      const int nc = L.meta[i].x;
+      float vals[kMaxCand];
+#pragma unroll
+      for (int c = 0; c < kMaxCand; ++c)
+        vals[c] = c < nc ? table[ngram_slot(u, v, (uint32_t)L.cand_tok[i * CM + c], table_mask)] : 0.f;
+#pragma unroll
+      for (int c = 0; c < kMaxCand; ++c)
+        if (c < nc) L.ng[(size_t)p * CM + c] = vals[c];
+    }
+  }
+  if (tid == 0) L.beam[0] = make_int4((int)__float_as_uint(0.f), ctx_u, ctx_v, 0);
+  __syncthreads();
+  if (tid >= kWave) return;  // the search runs in the first wavefront
+
+  // ---- phase B: the beam lives in LDS (beam[depth parity][slot]); lanes hold expansions --------------
   const float one_minus = __fsub_rn(1.0f, lambda);
-
-  // beam: lane b < n_live holds hypothesis b
   int n_live = 1;
-  float h_score = 0.f;
-  int h_u = ctx[seq * 2 + 0], h_v = ctx[seq * 2 + 1];
-
-  int out_len = K, out_slot = 0;
+  int out_len = K;
   float out_score = 0.f;
   bool finished = false;
 
   for (int i = 0; i < K && !finished; ++i) {
-    // candidates of this position: lane c < n_cand
-    int cnt = cand_cnt[row0 + i];
-    cnt = cnt < 1 ? 1 : (cnt > m_max ? m_max : cnt);
-    int c_tok = 0;
-    float c_lp = 0.f;
-    if (lane < cnt) {
-      c_tok = cand_id[(row0 + i) * m_max + lane];
-      c_lp = cand_logp[(row0 + i) * m_max + lane];
-    }
-    int n_cand = cnt;
-    if (eos_id >= 0) {
-      bool has = __ballot(lane < cnt && c_tok == eos_id) != 0ull;
-      if (!has) {
-        if (lane == cnt) {
-          c_tok = eos_id;
-          c_lp = eos_logp[row0 + i];
-        }
-        n_cand = cnt + 1;
-      }
-    }
+    const int4 mt = L.meta[i];
+    const int n_cand = __builtin_amdgcn_readfirstlane(mt.x), eos_rank = __builtin_amdgcn_readfirstlane(mt.y);
+    const uint32_t inv = (uint32_t)__builtin_amdgcn_readfirstlane(mt.z);
     const int n_exp = n_live * n_cand;
+    const int4* cur = L.beam + (i & 1) * B;
+    int4* nxt = L.beam + ((i + 1) & 1) * B;
 
     // score the expansions: slot j of lane l is expansion e = l + 64 j = parent * n_cand + cand
+    uint32_t e_bits[kSlots];   // ordered score bits, 0 = no open expansion in this slot
     float e_score[kSlots];
-    unsigned taken = 0;
+    int e_v[kSlots], e_tok[kSlots], e_rank[kSlots];
 #pragma unroll
     for (int j = 0; j < kSlots; ++j) {
       const int e = lane + j * kWave;
-      const int b = e / n_cand, c = e - b * n_cand;
-      const int src_b = b < kWave ? b : 0, src_c = c;
-      float ps = __shfl(h_score, src_b);
-      int pu = __shfl(h_u, src_b), pv = __shfl(h_v, src_b);
-      int w = __shfl(c_tok, src_c);
-      float ld = __shfl(c_lp, src_c);
-      float lng = 0.f;
-      if (e < n_exp && table) lng = table[ngram_slot((uint32_t)pu, (uint32_t)pv, (uint32_t)w, table_mask)];
-      float term = __fadd_rn(__fmul_rn(lambda, ld), __fmul_rn(one_minus, lng));
-      e_score[j] = __fadd_rn(ps, term);
-      if (e >= n_exp) taken |= 1u << j;
+      e_bits[j] = 0u;
+      e_score[j] = 0.f;
+      e_v[j] = e_tok[j] = e_rank[j] = 0;
+      if (j * kWave >= n_exp) continue;  // wavefront-uniform
+      if (e < n_exp) {
+        const int b = (int)(((uint32_t)e * inv) >> 16), c = e - b * n_cand;
+        const int4 st = cur[b];
+        const float ld = L.cand_lp[i * CM + c];
+        const int tok = L.cand_tok[i * CM + c];
+        const int ra = st.w & 0xFF, rb = (st.w >> 8) & 0xFF;
+        float lng = 0.f;
+        if (PRE) {
+          lng = L.ng[(((size_t)i * CM + ra) * CM + rb) * CM + c];
+        } else if (table) {
+          lng = table[ngram_slot((uint32_t)st.y, (uint32_t)st.z, (uint32_t)tok, table_mask)];
+        }
+        const float term = __fadd_rn(__fmul_rn(lambda, ld), __fmul_rn(one_minus, lng));
+        e_score[j] = __fadd_rn(__uint_as_float((uint32_t)st.x), term);
+        e_bits[j] = ordered_bits(e_score[j]);
+        e_v[j] = st.z;
+        e_tok[j] = tok;
+        e_rank[j] = rb | (c << 8);  // (rank of the previous token, rank of this token)
+      }
     }
 
-    // keep the best B by (score descending, expansion index ascending)
+    // keep the best B by (score descending, expansion index ascending); survivors (not ending in EOS)
+    // are written straight into the next beam by the lane that owns the winning expansion
     const int n_keep = n_exp < B ? n_exp : B;
-    float k_score = 0.f;   // lane r < n_keep: r-th kept expansion
-    int k_exp = 0;
+    int live = 0;
     for (int r = 0; r < n_keep; ++r) {
-      unsigned long long best = 0ull;
+      uint32_t best_bits = 0;
+      int best_slot = 0;
 #pragma unroll
-      for (int j = 0; j < kSlots; ++j) {
-        if (!(taken & (1u << j))) {
-          unsigned long long key = ((unsigned long long)ordered_bits(e_score[j]) << 32) |
-                                   (unsigned long long)(0xFFFFFFFFu - (uint32_t)(lane + j * kWave));
-          best = key > best ? key : best;
+      for (int j = kSlots - 1; j >= 0; --j) {
+        if (e_bits[j] != 0u && e_bits[j] >= best_bits) {
+          best_bits = e_bits[j];
+          best_slot = j;
         }
       }
-      best = wave_max_u64(best);
-      const int e = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
-      const int owner = e & (kWave - 1), slot = e / kWave;
-      float sc = 0.f;
+      const uint32_t top = wave_max_u32(best_bits);
+      int e;
+      if (kSlots == 1) {
+        e = __ffsll((long long)__ballot(best_bits == top)) - 1;
+      } else {
+        const uint32_t my_e = best_bits == top ? (uint32_t)(lane + best_slot * kWave) : 0xFFFFFFFFu;
+        e = (int)(0xFFFFFFFFu - wave_max_u32(0xFFFFFFFFu - my_e));
+      }
+      e = __builtin_amdgcn_readfirstlane(e);
+      const int owner = e & (kWave - 1), slot = e >> 6;
+      const int par = (int)(((uint32_t)e * inv) >> 16), c = e - par * n_cand;
+      const bool is_eos = (c == eos_rank);
+      if (r == 0 && is_eos) {  // the best kept hypothesis ends in EOS: it is the result
+        if (lane == owner) {
 #pragma unroll
-      for (int j = 0; j < kSlots; ++j)
-        if (j == slot) sc = e_score[j];
-      sc = __shfl(sc, owner);
-      if (lane == owner) taken |= 1u << slot;
-      if (lane == r) {
-        k_score = sc;
-        k_exp = e;
+          for (int j = 0; j < kSlots; ++j)
+            if (j == slot) {
+              L.bp_tok[i * B] = e_tok[j];
+              L.bp_par[i * B] = (uint8_t)par;
+            }
+        }
+        out_len = i + 1;
+        out_score = __uint_as_float(top & 0x80000000u ? (top & 0x7FFFFFFFu) : ~top);
+        finished = true;
+        break;
+      }
+      if (lane == owner) {
+#pragma unroll
+        for (int j = 0; j < kSlots; ++j)
+          if (j == slot) {
+            e_bits[j] = 0u;  // taken
+            if (!is_eos) {
+              nxt[live] = make_int4((int)__float_as_uint(e_score[j]), e_v[j], e_tok[j], e_rank[j]);
+              L.bp_tok[i * B + live] = e_tok[j];
+              L.bp_par[i * B + live] = (uint8_t)par;
+            }
+          }
+      }
+      if (!is_eos) {
+        if (live == 0 && i == K - 1) out_score = __uint_as_float(top & 0x80000000u ? (top & 0x7FFFFFFFu) : ~top);
+        ++live;
       }
     }
-
-    // kept lane r: parent, token
-    const int k_par = k_exp / n_cand, k_c = k_exp - k_par * n_cand;
-    const int k_tok = __shfl(c_tok, k_c);
-    const int k_v = __shfl(h_v, k_par < kWave ? k_par : 0);
-    const bool k_valid = lane < n_keep;
-    const bool k_eos = k_valid && eos_id >= 0 && k_tok == eos_id;
-
-    // the best kept hypothesis ends in EOS: it is the result
-    const bool best_eos = __shfl((int)k_eos, 0) != 0;
-    // survivors: kept hypotheses that do not end in EOS, order preserved
-    unsigned long long live_mask = __ballot(k_valid && !k_eos);
-    const int new_slot = __popcll(live_mask & ((1ull << lane) - 1ull));
-    if (best_eos) {
-      if (lane == 0) {
-        bp_tok[i * B + 0] = k_tok;
-        bp_par[i * B + 0] = (uint8_t)k_par;
-      }
-      out_len = i + 1;
-      out_slot = 0;
-      out_score = __shfl(k_score, 0);
-      finished = true;
-    } else {
-      if (k_valid && !k_eos) {
-        bp_tok[i * B + new_slot] = k_tok;
-        bp_par[i * B + new_slot] = (uint8_t)k_par;
-      }
-      // compact the survivors into lanes 0 .. n_live-1
-      n_live = __popcll(live_mask);
-      // lane t takes the t-th set bit of live_mask
-      int src = 0;
-      {
-        unsigned long long m = live_mask;
-        for (int t = 0; t < lane && m; ++t) m &= m - 1;
-        src = m ? (__ffsll((long long)m) - 1) : 0;
-      }
-      float ns = __shfl(k_score, src);
-      int nu = __shfl(k_v, src), nv = __shfl(k_tok, src);
-      if (lane < n_live) {
-        h_score = ns;
-        h_u = nu;
-        h_v = nv;
-      }
-      if (i == K - 1) {
-        out_len = K;
-        out_slot = 0;
-        out_score = __shfl(h_score, 0);
-      }
-    }
-    __syncthreads();  // back-pointers of this depth visible (single wavefront: orders LDS traffic)
+    n_live = live;
   }
 
-  // back-track
+  // back-track (lane 0 reads what other lanes of this wavefront wrote: LDS operations complete in order)
   if (lane == 0) {
-    int slot = out_slot;
+    int slot = 0;
     for (int i = out_len - 1; i >= 0; --i) {
-      path[row0 + i] = bp_tok[i * B + slot];
-      slot = bp_par[i * B + slot];
+      path[row0 + i] = L.bp_tok[i * B + slot];
+      slot = L.bp_par[i * B + slot];
     }
     path_len[seq] = out_len;
     path_score[seq] = out_score;
@@ -212,10 +277,38 @@ int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* ca
                const float* eos_logp, int batch, int K, int m_max, int B, float lambda,
                const float* table, int log2_size, const int32_t* ctx, int32_t eos_id, int32_t* path,
                int32_t* path_len, float* path_score, hipStream_t st) {
-  size_t lds = (size_t)K * B * sizeof(int32_t) + align_up((size_t)K * B, 4);
-  uint32_t mask = table ? ((1u << log2_size) - 1u) : 0u;
-  hipLaunchKernelGGL(cps_kernel, dim3(batch), dim3(kWave), lds, st, cand_id, cand_logp, cand_cnt, eos_logp, K,
-                     m_max, B, lambda, table, mask, ctx, eos_id, path, path_len, path_score);
+  const int CM = m_max + 1;
+  const size_t fixed = align_up(lds_fixed_bytes(K, CM, B), 16);
+  const size_t pre = (size_t)K * CM * CM * CM * sizeof(float);
+  const bool use_pre = table != nullptr && fixed + pre <= kLdsBudget;
+  const uint32_t mask = table ? ((1u << log2_size) - 1u) : 0u;
+  const int slots = ceil_div(B * CM, kWave);  // 1 .. kMaxSlots
+#define DS_CPS_LAUNCH(PRE_, SLOTS_, THREADS_, LDS_)                                                          \
+  hipLaunchKernelGGL((cps_kernel<PRE_, SLOTS_>), dim3(batch), dim3(THREADS_), LDS_, st, cand_id, cand_logp,   \
+                     cand_cnt, eos_logp, K, m_max, B, lambda, table, mask, ctx, eos_id, path, path_len,      \
+                     path_score)
+  if (use_pre) {
+    const size_t lds = fixed + pre;
+    if (lds > 48 * 1024) {
+      static thread_local bool granted[3] = {false, false, false};
+      const int which = slots == 1 ? 0 : (slots <= 3 ? 1 : 2);
+      if (!granted[which]) {
+        const void* fn = which == 0   ? reinterpret_cast<const void*>(&cps_kernel<true, 1>)
+                         : which == 1 ? reinterpret_cast<const void*>(&cps_kernel<true, 3>)
+                                      : reinterpret_cast<const void*>(&cps_kernel<true, kMaxSlots>);
+        DS_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget));
+        granted[which] = true;
+      }
+    }
+    if (slots == 1) DS_CPS_LAUNCH(true, 1, 1024, lds);
+    else if (slots <= 3) DS_CPS_LAUNCH(true, 3, 1024, lds);
+    else DS_CPS_LAUNCH(true, kMaxSlots, 1024, lds);
+  } else {
+    if (slots == 1) DS_CPS_LAUNCH(false, 1, kWave, fixed);
+    else if (slots <= 3) DS_CPS_LAUNCH(false, 3, kWave, fixed);
+    else DS_CPS_LAUNCH(false, kMaxSlots, kWave, fixed);
+  }
+#undef DS_CPS_LAUNCH
   DS_LAUNCH_CHECK("cps_kernel");
   return DS_OK;
 }

@@ -22,41 +22,44 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
   return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// tok[r] = r < n_real ? src[r] : fill ; ids outside [0, vocab) become 0.
-__global__ void tokens_kernel(const int32_t* __restrict__ src, int n_real, int rows, int32_t fill, int vocab,
-                              int32_t* __restrict__ tok) {
-  const int r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r >= rows) return;
-  int32_t t = r < n_real ? src[r] : fill;
-  tok[r] = (t < 0 || t >= vocab) ? 0 : t;
-}
-
-// cs[r][i] = (cos, sin)(pos_r * base^(-2i/hd)), angles in double so that long contexts stay exact.
-__global__ void rope_table_kernel(int pos0, int rows, int half, double base, float2* __restrict__ cs) {
-  const int r = blockIdx.x, i = threadIdx.x;
-  if (i >= half) return;
-  const double theta = exp2(-((double)i / (double)half) * log2(base));
-  double s, c;
-  sincos((double)(pos0 + r) * theta, &s, &c);
-  cs[r * half + i] = make_float2((float)c, (float)s);
-}
-
 constexpr int kMaxVec = 8;     // float4 groups per thread: d_model <= 8192 with 256 threads
 constexpr int kMaxPlanes = 8;  // split-K planes summed per element
 
+// Token and rotary arguments of the first kernel of a forward (FROM_EMBED).
+struct Prologue {
+  const int32_t* src;  // [n_real] real tokens, rows past n_real are `fill`; ids outside [0, vocab) read as 0
+  int n_real, vocab;
+  int32_t fill;
+  int pos0, half;      // rotary table: cs[r][i] = (cos, sin)((pos0 + r) * base^(-i / half)), i < half
+  double log2_base;
+  float2* cs;
+};
+
 // x[r] = E[tok[r]] or x[r] + sum of split-K planes ; h[r] = rmsnorm(x[r]) * gain, written as GEMM input.
-// FROM_EMBED: start from the embedding row, else from the float32 residual x plus `n_part` planes.
+// FROM_EMBED: start from the embedding row (and fill this row of the rotary table, angles in double so
+// that long contexts stay exact), else from the float32 residual x plus `n_part` planes.
 // rm_out (optional): row-major float32 copy of rows >= rm_row0 (the boundary's hidden_out).
 // One workgroup per row, four consecutive columns per thread and step (d_model % 4 == 0); the planes
 // are summed in index order, all loads of a step issued before the first add.
 template <typename T, bool FROM_EMBED>
-__global__ __launch_bounds__(256) void norm_kernel(const int32_t* __restrict__ tok, const T* __restrict__ embed,
+__global__ __launch_bounds__(256) void norm_kernel(Prologue pro, const T* __restrict__ embed,
                                                    float* __restrict__ x, const float* __restrict__ part,
                                                    int n_part, int rows, int rows_pad, int d,
                                                    const float* __restrict__ gain, float eps, T* __restrict__ h,
                                                    float* __restrict__ rm_out, int rm_row0) {
   __shared__ float red[4];
   const int r = blockIdx.x;
+  int token = 0;
+  if (FROM_EMBED) {
+    token = r < pro.n_real ? pro.src[r] : pro.fill;
+    token = (token < 0 || token >= pro.vocab) ? 0 : token;
+    if ((int)threadIdx.x < pro.half) {
+      const double theta = exp2(-((double)threadIdx.x / (double)pro.half) * pro.log2_base);
+      double sn, cs;
+      sincos((double)(pro.pos0 + r) * theta, &sn, &cs);
+      pro.cs[r * pro.half + threadIdx.x] = make_float2((float)cs, (float)sn);
+    }
+  }
   float4 v[kMaxVec];
   float ss = 0.f;
 #pragma unroll
@@ -66,7 +69,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const int32_t* __restrict__ t
     if (c < d) {
       float4 a;
       if (FROM_EMBED) {
-        const T* e = embed + (size_t)tok[r] * d + c;
+        const T* e = embed + (size_t)token * d + c;
         a = make_float4(Act<T>::weight(e[0]), Act<T>::weight(e[1]), Act<T>::weight(e[2]), Act<T>::weight(e[3]));
       } else {
         a = *reinterpret_cast<const float4*>(x + (size_t)r * d + c);
@@ -103,8 +106,8 @@ __global__ __launch_bounds__(256) void norm_kernel(const int32_t* __restrict__ t
 template <typename T>
 __global__ void to_gemm_input_kernel(const float* __restrict__ src, int rows_pad, int d, T* __restrict__ dst) {
   const int r = blockIdx.x;
-  for (int c = threadIdx.x; c < d; c += blockDim.x)
-    Act<T>::put(dst, r, c, d, (size_t)rows_pad * d, src[(size_t)r * d + c]);
+  for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4)
+    Act<T>::put4(dst, r, c, d, (size_t)rows_pad * d, *reinterpret_cast<const float4*>(src + (size_t)r * d + c));
 }
 
 // One wavefront per (row, head slot): sums the QKV partial planes, rotates q and k, writes q in the
@@ -155,41 +158,35 @@ __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int 
   }
 }
 
-// act[r][f] = silu(gate) * up with gate = sum_s part[s][r][f], up = sum_s part[s][r][F + f].
+// act[r][f] = silu(gate) * up with gate = sum_s part[s][r][f], up = sum_s part[s][r][F + f]; four
+// consecutive f per thread (F % 4 == 0).
 template <typename T>
 __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int F,
                               T* __restrict__ act) {
   const int r = blockIdx.y;
-  const int f = blockIdx.x * blockDim.x + threadIdx.x;
+  const int f = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (f >= F) return;
-  float g = 0.f, u = 0.f;
+  float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
   for (int s = 0; s < n_part; ++s) {
     const float* p = part + ((size_t)s * rows + r) * (2 * (size_t)F);
-    g += p[f];
-    u += p[F + f];
+    const float4 a = *reinterpret_cast<const float4*>(p + f);
+    const float4 b = *reinterpret_cast<const float4*>(p + F + f);
+    g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
+    u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
   }
-  const float y = g / (1.0f + expf(-g)) * u;
-  Act<T>::put(act, r, f, F, (size_t)rows_pad * F, y);
+  const float4 y = make_float4(g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
+                               g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w);
+  Act<T>::put4(act, r, f, F, (size_t)rows_pad * F, y);
 }
 
 }  // namespace
 
-int launch_tokens(const int32_t* src, int n_real, int rows, int32_t fill, int vocab, int32_t* tok, hipStream_t st) {
-  hipLaunchKernelGGL(tokens_kernel, dim3(ceil_div(rows, 256)), dim3(256), 0, st, src, n_real, rows, fill, vocab, tok);
-  DS_LAUNCH_CHECK("tokens_kernel");
-  return DS_OK;
-}
-
-int launch_rope_table(int pos0, int rows, int hd, double base, float2* cs, hipStream_t st) {
-  hipLaunchKernelGGL(rope_table_kernel, dim3(rows), dim3(hd / 2), 0, st, pos0, rows, hd / 2, base, cs);
-  DS_LAUNCH_CHECK("rope_table_kernel");
-  return DS_OK;
-}
-
 template <typename T>
-int launch_embed_norm(const int32_t* tok, const void* embed, float* x, int rows, int rows_pad, int d,
-                      const float* gain, float eps, void* h, hipStream_t st) {
-  hipLaunchKernelGGL((norm_kernel<T, true>), dim3(rows), dim3(256), 0, st, tok, static_cast<const T*>(embed), x,
+int launch_embed_norm(const int32_t* src, int n_real, int32_t fill, int vocab, int pos0, int hd, double rope_base,
+                      float2* cs, const void* embed, float* x, int rows, int rows_pad, int d, const float* gain,
+                      float eps, void* h, hipStream_t st) {
+  Prologue pro{src, n_real, vocab, fill, pos0, hd / 2, log2(rope_base), cs};
+  hipLaunchKernelGGL((norm_kernel<T, true>), dim3(rows), dim3(256), 0, st, pro, static_cast<const T*>(embed), x,
                      (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr, 0);
   DS_LAUNCH_CHECK("norm_kernel<embed>");
   return DS_OK;
@@ -198,9 +195,8 @@ int launch_embed_norm(const int32_t* tok, const void* embed, float* x, int rows,
 template <typename T>
 int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
                     float eps, void* h, float* rm_out, int rm_row0, hipStream_t st) {
-  hipLaunchKernelGGL((norm_kernel<T, false>), dim3(rows), dim3(256), 0, st, (const int32_t*)nullptr,
-                     (const T*)nullptr, x, part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out,
-                     rm_row0);
+  hipLaunchKernelGGL((norm_kernel<T, false>), dim3(rows), dim3(256), 0, st, Prologue{}, (const T*)nullptr, x, part,
+                     n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, rm_row0);
   DS_LAUNCH_CHECK("norm_kernel<add>");
   return DS_OK;
 }
@@ -225,15 +221,15 @@ int launch_qkv_rope(const float* part, int n_part, int rows, int rows_pad, int n
 
 template <typename T>
 int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, hipStream_t st) {
-  hipLaunchKernelGGL((swiglu_kernel<T>), dim3(ceil_div(F, 256), rows), dim3(256), 0, st, part, n_part, rows,
+  hipLaunchKernelGGL((swiglu_kernel<T>), dim3(ceil_div(F, 1024), rows), dim3(256), 0, st, part, n_part, rows,
                      rows_pad, F, static_cast<T*>(act));
   DS_LAUNCH_CHECK("swiglu_kernel");
   return DS_OK;
 }
 
 #define DS_INSTANTIATE(T)                                                                                          \
-  template int launch_embed_norm<T>(const int32_t*, const void*, float*, int, int, int, const float*, float,       \
-                                    void*, hipStream_t);                                                           \
+  template int launch_embed_norm<T>(const int32_t*, int, int32_t, int, int, int, double, float2*, const void*,     \
+                                    float*, int, int, int, const float*, float, void*, hipStream_t);               \
   template int launch_add_norm<T>(float*, const float*, int, int, int, int, const float*, float, void*, float*,   \
                                   int, hipStream_t);                                                               \
   template int launch_to_gemm_input<T>(const float*, int, int, int, void*, hipStream_t);                           \

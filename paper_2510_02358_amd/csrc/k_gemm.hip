@@ -58,7 +58,7 @@ __global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K,
 template <int MB, int NB>
 __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
                                                                  const uint16_t* __restrict__ xt, int M, int N,
-                                                                 int K, int groups_per_split,
+                                                                 int K, int groups_per_split, int n_big,
                                                                  float* __restrict__ out) {
   constexpr int kKSC = ksc_for(MB);
   constexpr int kTiles = 2 * MB * kKSC;  // X tiles per chunk: (hi, lo) x row blocks x k-steps
@@ -70,12 +70,28 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
   if (c_end > n_chunks) c_end = n_chunks;
   const size_t plane = (size_t)MB * 16 * K;  // elements between the hi and the lo plane
 
+  // This workgroup's share of the output row blocks.  The first n_big workgroups take a full pass of
+  // 4 * NB blocks each; a remainder goes to later workgroups in half-size pieces.
+  const int full = 4 * NB, half = full / 2 > 0 ? full / 2 : 1;
+  int nb_begin, nb_end;
+  if ((int)blockIdx.x < n_big) {
+    nb_begin = (int)blockIdx.x * full;
+    nb_end = nb_begin + full;
+  } else {
+    nb_begin = n_big * full + ((int)blockIdx.x - n_big) * half;
+    nb_end = nb_begin + half;
+  }
+  if (nb_end > n_blocks) nb_end = n_blocks;
+  const int j_out = lane & 15, g_out = lane >> 4;
+  float* out_plane = out + (size_t)blockIdx.y * M * N;
+
+  for (int pass0 = nb_begin; pass0 < nb_end; pass0 += 4 * NB) {
   int nb[NB];
   const uint16_t* wrow[NB];
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
-    nb[b] = (blockIdx.x * 4 + wave) * NB + b;
-    const int nbc = nb[b] < n_blocks ? nb[b] : n_blocks - 1;  // clamp: loads stay in bounds, result dropped
+    nb[b] = pass0 + b * 4 + wave;
+    const int nbc = nb[b] < nb_end ? nb[b] : nb_end - 1;  // clamp: loads stay in this workgroup's range
     wrow[b] = wp + ((size_t)nbc * ksteps) * 512 + lane * 8;
   }
 
@@ -132,21 +148,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
       }
     }
   };
-  // One pipeline step for chunk c held in register set SET and LDS buffer buf: issue the X loads of chunk
-  // c + 1 and the weight loads of chunk c + 2 first, multiply chunk c, then publish X(c + 1) in LDS.  X is
-  // loaded BEFORE the weights so that waiting for it leaves the younger weight loads in flight.
-  // Past the last chunk the loads are clamped to it instead of predicated (branch-free body; the
-  // redundant tiles are never multiplied).
+  // One pipeline step for chunk c (weights in register set SET, X in LDS buffer buf).  X(c + 1) was
+  // loaded during the previous step and is published to the other LDS buffer first; then the X loads of
+  // chunk c + 2 and the weight loads of chunk c + 2 are issued (X BEFORE the weights, so that waiting for
+  // X next step leaves the younger weight loads in flight); then chunk c is multiplied.  Nothing that a
+  // step waits for was issued less than one full step earlier.  Past the last chunk the loads are clamped
+  // to it instead of predicated (branch-free body; the redundant tiles are never multiplied).
   const int c_last = c_end - 1;
   auto step = [&](auto set, int c, int buf) {
     constexpr int SET = decltype(set)::value;
-    load_x(c + 1 < c_last ? c + 1 : c_last);
+    store_x(buf ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_x(c + 2 < c_last ? c + 2 : c_last);
     __builtin_amdgcn_sched_barrier(0);  // keep the issue order: X loads, then weight loads, then math
     load_a(std::integral_constant<int, (SET + 2) % kStages>{}, c + 2 < c_last ? c + 2 : c_last);
     __builtin_amdgcn_sched_barrier(0);
     compute(set, buf);
-    __builtin_amdgcn_sched_barrier(0);
-    store_x(buf ^ 1);
     __syncthreads();
   };
 
@@ -155,6 +172,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
     load_a(std::integral_constant<int, 0>{}, c_begin);
     load_a(std::integral_constant<int, 1>{}, c_begin + 1 < c_last ? c_begin + 1 : c_last);
     store_x(0);
+    load_x(c_begin + 1 < c_last ? c_begin + 1 : c_last);
     __syncthreads();
     // Main loop: groups of three chunks with no branch between the steps, so that the three steps form
     // one basic block and every prefetch stays where it is issued (two chunks ahead of its use).
@@ -172,20 +190,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
   }
 
   // D[i][j]: lane (16 g + j) holds rows i = 4 g .. 4 g + 3 of column j  ->  out[m = 16 mb + j][n = 16 nb + 4 g ..]
-  const int j = lane & 15, g = lane >> 4;
-  float* out_plane = out + (size_t)blockIdx.y * M * N;
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
-    if (nb[b] >= n_blocks) continue;
+    if (nb[b] >= nb_end) continue;
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
-      const int row = m * 16 + j;
+      const int row = m * 16 + j_out;
       if (row < M) {
         float4 v = make_float4(acc[b][m][0], acc[b][m][1], acc[b][m][2], acc[b][m][3]);
-        *reinterpret_cast<float4*>(out_plane + (size_t)row * N + nb[b] * 16 + g * 4) = v;
+        *reinterpret_cast<float4*>(out_plane + (size_t)row * N + nb[b] * 16 + g_out * 4) = v;
       }
     }
   }
+  __syncthreads();  // the next pass restages X into the same LDS buffers
+  }  // passes
 }
 
 // float32 parity mode: one wavefront per output column n, lanes stride over k, rows in blocks of 8.
@@ -220,11 +238,15 @@ int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, 
                    hipStream_t st) {
   const int n_groups = (K >> 5) / kGroup;
   const int gps = ceil_div(n_groups, n_split);
-  dim3 grid(ceil_div(N >> 4, 4 * nbw), n_split);
+  // One workgroup per full pass of 4 * nbw row blocks; a remainder goes to half-size workgroups at the end.
+  const int n_blocks = N >> 4, full = 4 * nbw, half = full / 2 > 0 ? full / 2 : 1;
+  const int n_big = n_blocks / full;
+  const int n_small = ceil_div(n_blocks - n_big * full, half);
+  dim3 grid(n_big + n_small, n_split);
   if (nbw == 1)
-    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 1>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, out);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 1>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, n_big, out);
   else
-    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 2>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, out);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 2>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, n_big, out);
   DS_LAUNCH_CHECK("gemm_bf16_kernel");
   return DS_OK;
 }

@@ -23,12 +23,18 @@ __device__ __forceinline__ bool beats(float v, int id, float w, int jd) {
   return v > w || (v == w && id < jd);
 }
 
-// Insert (x, xid) into the lane-distributed list sorted best-first.  All 64 lanes call this.
+// Read lane `src` (wavefront-uniform) of a value into a scalar register.
+__device__ __forceinline__ float lane_value(float v, int src) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
+}
+__device__ __forceinline__ int lane_value(int v, int src) { return __builtin_amdgcn_readlane(v, src); }
+
+// Insert the wavefront-uniform pair (x, xid) into the lane-distributed list sorted best-first: the
+// entries it beats move one lane up (one DPP whole-wavefront shift), it lands in the gap.
 __device__ __forceinline__ void list_insert(float& ev, int& eid, float x, int xid, int lane) {
-  unsigned long long ahead = __ballot(beats(ev, eid, x, xid));
-  int pos = __popcll(ahead);
-  float pv = __shfl_up(ev, 1);
-  int pid = __shfl_up(eid, 1);
+  const int pos = __popcll(__ballot(beats(ev, eid, x, xid)));  // entries that stay ahead of x
+  const float pv = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(ev), 0x138, 0xF, 0xF, false));
+  const int pid = __builtin_amdgcn_update_dpp(0, eid, 0x138, 0xF, 0xF, false);  // wave_shr:1
   if (lane == pos) {
     ev = x;
     eid = xid;
@@ -39,25 +45,49 @@ __device__ __forceinline__ void list_insert(float& ev, int& eid, float x, int xi
 }
 
 // Offer one value per lane to the list; only values beating the current m_max-th entry are inserted.
+// Everything that crosses lanes here is a scalar read of one lane (no LDS-path permutes).
 __device__ __forceinline__ void list_offer(float& ev, int& eid, float x, int xid, int m_max, int lane) {
-  float thr = __shfl(ev, m_max - 1);
-  int thrid = __shfl(eid, m_max - 1);
+  float thr = lane_value(ev, m_max - 1);
+  int thrid = lane_value(eid, m_max - 1);
   unsigned long long mask = __ballot(beats(x, xid, thr, thrid));
   while (mask) {
-    int src = __ffsll((long long)mask) - 1;
+    const int src = __ffsll((long long)mask) - 1;
     mask &= mask - 1;
-    float bx = __shfl(x, src);
-    int bid = __shfl(xid, src);
+    const float bx = lane_value(x, src);
+    const int bid = lane_value(xid, src);
     if (!beats(bx, bid, thr, thrid)) continue;  // the bar moved up since the ballot
     list_insert(ev, eid, bx, bid, lane);
-    thr = __shfl(ev, m_max - 1);
-    thrid = __shfl(eid, m_max - 1);
+    thr = lane_value(ev, m_max - 1);
+    thrid = lane_value(eid, m_max - 1);
+  }
+}
+
+// Sort one (value, id) pair per lane across the wavefront, best first (bitonic network, 21 exchange steps).
+// Used to start a list from 64 values at once instead of 64 sequential insertions.
+__device__ __forceinline__ void wave_sort_best_first(float& v, int& id, int lane) {
+#pragma unroll
+  for (int k = 2; k <= kWave; k <<= 1) {
+#pragma unroll
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      const float ov = __shfl_xor(v, j);
+      const int oid = __shfl_xor(id, j);
+      const bool descending_block = (lane & k) == 0;     // k == 64: every lane
+      const bool lower_lane = (lane & j) == 0;
+      const bool want_better = lower_lane == descending_block;
+      const bool take = want_better ? beats(ov, oid, v, id) : beats(v, id, ov, oid);
+      if (take) {
+        v = ov;
+        id = oid;
+      }
+    }
   }
 }
 
 // Partial record of one wavefront for one row: { max, sum exp(v - max), m_max values, m_max ids }.
 __host__ __device__ inline int rec_dwords(int m_max) { return 2 + 2 * m_max; }
 
+// SOFTMAX = true: lattice scan (running max / sum of exp, top-m_max list).
+// SOFTMAX = false: arg-max scan (m_max = 1): a plain per-lane running best, reduced once at the end.
 template <bool SOFTMAX>
 __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __restrict__ logits, int vocab,
                                                                  int m_max, int tiles_per_seg,
@@ -67,9 +97,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
   const float* rowp = logits + (size_t)row * (size_t)vocab;
   const bool vec = ((vocab & 3) == 0) && ((((uintptr_t)logits) & 15) == 0);
 
-  float ev = -INFINITY;  // this lane's list entry
+  float ev = -INFINITY;  // SOFTMAX: this lane's list entry; else: this lane's running best
   int eid = INT_MAX;
   float run_max = -INFINITY, run_sum = 0.f;
+  bool list_empty = true;
 
   const int tile0 = seg * tiles_per_seg;
   for (int t = 0; t < tiles_per_seg; ++t) {
@@ -87,35 +118,58 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
         for (int c = 0; c < 4; ++c) v[j][c] = (i0 + c < vocab) ? rowp[i0 + c] : -INFINITY;
       }
     }
+    // this lane's best of its 32 values (value descending, index ascending)
     float loc = -INFINITY;
+    int loc_idx = INT_MAX;
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) loc = fmaxf(loc, v[j][c]);
-    if (SOFTMAX) {
-      if (loc > run_max) {
-        run_sum *= __expf(run_max - loc);  // run_max = -inf gives 0 * 0
-        run_max = loc;
+      for (int c = 0; c < 4; ++c) {
+        const int idx = base + j * (kWave * 4) + lane * 4 + c;
+        if (idx < vocab && beats(v[j][c], idx, loc, loc_idx)) {
+          loc = v[j][c];
+          loc_idx = idx;
+        }
       }
-      if (run_max > -INFINITY) {
-        float acc = 0.f;
-#pragma unroll
-        for (int j = 0; j < kUnroll; ++j)
-#pragma unroll
-          for (int c = 0; c < 4; ++c) acc += __expf(v[j][c] - run_max);
-        run_sum += acc;
+    if (!SOFTMAX) {
+      if (beats(loc, loc_idx, ev, eid)) {
+        ev = loc;
+        eid = loc_idx;
       }
+      continue;
     }
-    float thr = __shfl(ev, m_max - 1);
-    if (__ballot(loc >= thr)) {
+    if (loc > run_max) {
+      run_sum *= __expf(run_max - loc);  // run_max = -inf gives 0 * 0
+      run_max = loc;
+    }
+    if (run_max > -INFINITY) {
+      float acc = 0.f;
 #pragma unroll
       for (int j = 0; j < kUnroll; ++j)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int idx = base + j * (kWave * 4) + lane * 4 + c;
-          list_offer(ev, eid, v[j][c], idx < vocab ? idx : INT_MAX, m_max, lane);
-        }
+        for (int c = 0; c < 4; ++c) acc += __expf(v[j][c] - run_max);
+      run_sum += acc;
     }
+    int own = -1;  // index already in the list (skipped below)
+    if (list_empty) {
+      // start the list from the 64 per-lane bests in one sort; the bar is then already high
+      ev = loc;
+      eid = loc_idx;
+      wave_sort_best_first(ev, eid, lane);
+      own = loc_idx;
+      list_empty = false;
+    } else {
+      const float thr = lane_value(ev, m_max - 1);
+      if (!__ballot(loc >= thr)) continue;
+    }
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int idx = base + j * (kWave * 4) + lane * 4 + c;
+        const bool skip = idx >= vocab || idx == own;
+        list_offer(ev, eid, skip ? -INFINITY : v[j][c], skip ? INT_MAX : idx, m_max, lane);
+      }
   }
 
   if (SOFTMAX) {  // wavefront reduction of (max, sum)
@@ -127,6 +181,16 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
       float b = (om > -INFINITY) ? os * __expf(om - nm) : 0.f;
       run_max = nm;
       run_sum = a + b;
+    }
+  } else {  // wavefront reduction of the running best into lane 0
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+      const float ov = __shfl_xor(ev, off);
+      const int oid = __shfl_xor(eid, off);
+      if (beats(ov, oid, ev, eid)) {
+        ev = ov;
+        eid = oid;
+      }
     }
   }
   const int part = (row * n_seg + seg) * (kScanThreads / kWave) + wave;
@@ -142,6 +206,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
 }
 
 // Merge the partial top lists of one row; returns with lane i holding the i-th best overall.
+// Entries are visited rank-major (all partials' best first), the first 64 sorted in one go.
 __device__ __forceinline__ void merge_lists(const uint32_t* rec0, int n_part, int m_max, int lane, float& ev,
                                             int& eid) {
   ev = -INFINITY;
@@ -152,11 +217,18 @@ __device__ __forceinline__ void merge_lists(const uint32_t* rec0, int n_part, in
     float x = -INFINITY;
     int xid = INT_MAX;
     if (e < total) {
-      const uint32_t* rec = rec0 + (size_t)(e / m_max) * rec_dwords(m_max);
-      x = __uint_as_float(rec[2 + e % m_max]);
-      xid = (int)rec[2 + m_max + e % m_max];
+      const int rank = e / n_part, p = e - rank * n_part;
+      const uint32_t* rec = rec0 + (size_t)p * rec_dwords(m_max);
+      x = __uint_as_float(rec[2 + rank]);
+      xid = (int)rec[2 + m_max + rank];
     }
-    list_offer(ev, eid, x, xid, m_max, lane);
+    if (b == 0) {
+      ev = x;
+      eid = xid;
+      wave_sort_best_first(ev, eid, lane);
+    } else {
+      list_offer(ev, eid, x, xid, m_max, lane);
+    }
   }
 }
 
