@@ -51,6 +51,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -78,6 +80,12 @@ def main() -> int:
     dec.start(prefix)
     dec.stage_inputs()
     torch.cuda.synchronize()
+    if args.calibrate:  # known traffic: reads 1 GiB, writes 1 GiB
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     setup_s = time.time() - t0
     p0 = PREFIX
 
@@ -100,7 +108,7 @@ def main() -> int:
         ds.ds_build_lattice(dec.d_logits, K_DRAFT, cfg.vocab, p.m_max, p.tau, dec.eos_id, dec.cand_id, dec.cand_logp,
                             dec.cand_cnt, dec.eos_logp, dec.lse, dec.lat_ws)
         ds.ds_cps_path(dec.cand_id, dec.cand_logp, dec.cand_cnt, dec.eos_logp, 1, K_DRAFT, p.m_max, p.beam, p.lam,
-                       dec.proxy, dec.ctx, dec.eos_id, dec.block[1:], dec.path_len, dec.path_score)
+                       dec.proxy, dec.ctx, dec.eos_id, dec.block[1:], dec.path_len, dec.path_score, dec.cps_ws)
         ds.ds_verify_block(vm.handle, dec.block, K_DRAFT, dec.path_len, dec.eos_id, dec.result[0:1],
                            dec.result[1:2], dec.argmax, dec.result[2:3], None, vm.ws)
         dec.host[:3].copy_(dec.result, non_blocking=True)
@@ -147,7 +155,7 @@ def main() -> int:
                             dec.cand_cnt, dec.eos_logp, dec.lse, dec.lat_ws)
         marks[r][3].record()
         ds.ds_cps_path(dec.cand_id, dec.cand_logp, dec.cand_cnt, dec.eos_logp, 1, K_DRAFT, p.m_max, p.beam, p.lam,
-                       dec.proxy, dec.ctx, dec.eos_id, dec.block[1:], dec.path_len, dec.path_score)
+                       dec.proxy, dec.ctx, dec.eos_id, dec.block[1:], dec.path_len, dec.path_score, dec.cps_ws)
         marks[r][4].record()
         ds.ds_verify_block(vm.handle, dec.block, K_DRAFT, dec.path_len, dec.eos_id, dec.result[0:1],
                            dec.result[1:2], dec.argmax, dec.result[2:3], None, vm.ws)

@@ -149,11 +149,14 @@ void ds_ngram_destroy(ds_ngram* g);
  * the first depth whose best hypothesis ends in EOS (EOS included), else after K positions.
  * proxy NULL: l_ng = 0.  ctx [dev] int32[batch, 2]: the two tokens before each block (older first).
  * Outputs [dev]: path int32[batch, K] (tail beyond the length = -1), path_len int32[batch],
- * path_score float[batch].  1 <= B <= DS_MAX_BEAM, 1 <= M_max <= DS_MAX_TOPM, 1 <= K <= 256. */
+ * path_score float[batch].  1 <= B <= DS_MAX_BEAM, 1 <= M_max <= DS_MAX_TOPM, 1 <= K <= 256.
+ * ws [dev], optional (NULL allowed): ds_cps_workspace_bytes() bytes of scratch that lets the proxy scores
+ * be gathered by the whole chip before the search starts; results do not depend on it. */
+int ds_cps_workspace_bytes(int batch, int K, int M_max, size_t* bytes);
 int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
                 const float* eos_logp, int batch, int K, int M_max, int B, float lambda,
                 const ds_ngram* proxy, const int32_t* ctx, int32_t eos_id, int32_t* path,
-                int32_t* path_len, float* path_score, void* stream);
+                int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, void* stream);
 
 /* Step 4, parallel verification with greedy acceptance (Sec. 2 "Parallel verification" and
  * "Accepted prefix length"; Alg. 1 step (3); greedy verification as in Sec. 4).

@@ -22,7 +22,7 @@ EXPORTS = [
     "ds_version", "ds_last_error", "ds_model_packed_bytes", "ds_workspace_bytes", "ds_kv_bytes",
     "ds_model_create", "ds_model_destroy", "ds_model_kv_len", "ds_model_kv_set_len", "ds_prefill",
     "ds_draft_block", "ds_lm_head", "ds_lattice_workspace_bytes", "ds_build_lattice", "ds_ngram_create",
-    "ds_ngram_destroy", "ds_cps_path", "ds_verify_block", "ds_adl_create", "ds_adl_destroy",
+    "ds_ngram_destroy", "ds_cps_workspace_bytes", "ds_cps_path", "ds_verify_block", "ds_adl_create", "ds_adl_destroy",
     "ds_adl_update", "ds_adl_state",
 ]
 
@@ -85,7 +85,9 @@ def load():
     lib.ds_build_lattice.argtypes = [vp, C.c_int, C.c_int, C.c_int, f32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_ngram_create.argtypes = [vp, C.c_int, C.POINTER(vp)]
     lib.ds_ngram_destroy.argtypes = [vp]
-    lib.ds_cps_path.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, vp, i32, vp, vp, vp, vp]
+    lib.ds_cps_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(sz)]
+    lib.ds_cps_path.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, vp, i32, vp, vp, vp, vp, sz,
+                                vp]
     lib.ds_verify_block.argtypes = [vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_adl_create.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.POINTER(vp)]
     lib.ds_adl_destroy.argtypes = [vp]
@@ -218,11 +220,17 @@ def ds_ngram_destroy(handle: int) -> None:
     load().ds_ngram_destroy(handle)
 
 
+def ds_cps_workspace_bytes(batch: int, k: int, m_max: int) -> int:
+    out = C.c_size_t(0)
+    _check(load().ds_cps_workspace_bytes(batch, k, m_max, C.byref(out)))
+    return out.value
+
+
 def ds_cps_path(cand_id, cand_logp, cand_cnt, eos_logp, batch: int, k: int, m_max: int, beam: int, lam: float,
-                proxy: Optional[int], ctx, eos_id: int, path, path_len, path_score, stream=None) -> None:
+                proxy: Optional[int], ctx, eos_id: int, path, path_len, path_score, ws=None, stream=None) -> None:
     _check(load().ds_cps_path(_ptr(cand_id), _ptr(cand_logp), _ptr(cand_cnt), _ptr(eos_logp), batch, k, m_max, beam,
                               lam, proxy, _ptr(ctx), eos_id, _ptr(path), _ptr(path_len), _ptr(path_score),
-                              _stream(stream)))
+                              _ptr(ws), _nbytes(ws) if ws is not None else 0, _stream(stream)))
 
 
 def ds_verify_block(model: int, block, m: int, path_len, eos_id: int, n_accept, next_token, argmax, eos_accepted,

@@ -70,6 +70,14 @@ int ds_build_lattice(const float* logits, int rows, int vocab, int M_max, float 
                         ws_bytes, static_cast<hipStream_t>(stream));
 }
 
+int ds_cps_workspace_bytes(int batch, int K, int M_max, size_t* bytes) {
+  DS_REQUIRE(bytes, DS_E_INVALID, "bytes is NULL");
+  DS_REQUIRE(batch >= 0 && K >= 1 && K <= 256, DS_E_SHAPE, "batch %d / K %d out of range", batch, K);
+  DS_REQUIRE(M_max >= 1 && M_max <= DS_MAX_TOPM, DS_E_SHAPE, "M_max %d outside [1, %d]", M_max, DS_MAX_TOPM);
+  *bytes = cps_ws_bytes(batch, K, M_max);
+  return DS_OK;
+}
+
 int ds_ngram_create(const float* table, int log2_size, ds_ngram** out) {
   DS_REQUIRE(out, DS_E_INVALID, "out is NULL");
   *out = nullptr;
@@ -86,7 +94,7 @@ void ds_ngram_destroy(ds_ngram* g) { delete g; }
 int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
                 const float* eos_logp, int batch, int K, int M_max, int B, float lambda,
                 const ds_ngram* proxy, const int32_t* ctx, int32_t eos_id, int32_t* path,
-                int32_t* path_len, float* path_score, void* stream) {
+                int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, void* stream) {
   DS_REQUIRE(batch >= 0, DS_E_SHAPE, "batch %d is negative", batch);
   if (batch == 0) return DS_OK;
   DS_REQUIRE(cand_id && cand_logp && cand_cnt && ctx && path && path_len && path_score, DS_E_INVALID,
@@ -96,9 +104,10 @@ int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* c
   DS_REQUIRE(M_max >= 1 && M_max <= DS_MAX_TOPM, DS_E_SHAPE, "M_max %d outside [1, %d]", M_max, DS_MAX_TOPM);
   DS_REQUIRE(B >= 1 && B <= DS_MAX_BEAM, DS_E_SHAPE, "B %d outside [1, %d]", B, DS_MAX_BEAM);
   DS_REQUIRE(lambda >= 0.f && lambda <= 1.f, DS_E_INVALID, "lambda %g outside [0, 1]", (double)lambda);
+  DS_REQUIRE(!ws || (((uintptr_t)ws) & 15) == 0, DS_E_INVALID, "workspace not 16-byte aligned");
   return launch_cps(cand_id, cand_logp, cand_cnt, eos_logp, batch, K, M_max, B, lambda,
                     proxy ? proxy->table : nullptr, proxy ? proxy->log2_size : 0, ctx, eos_id, path, path_len,
-                    path_score, static_cast<hipStream_t>(stream));
+                    path_score, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int ds_adl_create(int k_min, int k_max, double delta, double rho, ds_adl** out) {

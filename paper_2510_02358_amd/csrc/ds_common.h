@@ -62,6 +62,7 @@ int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t
 int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
                const float* eos_logp, int batch, int K, int m_max, int B, float lambda,
                const float* table, int log2_size, const int32_t* ctx, int32_t eos_id, int32_t* path,
-               int32_t* path_len, float* path_score, hipStream_t st);
+               int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, hipStream_t st);
+size_t cps_ws_bytes(int batch, int K, int m_max);
 
 }  // namespace ds

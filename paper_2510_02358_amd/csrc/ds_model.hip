@@ -96,7 +96,7 @@ int widest_split_floats(const ds_model_cfg& c, int rows, size_t* out) {
   const int d = c.d_model, f = c.d_ffn, qo = c.n_q * c.head_dim;
   const int shapes[4][2] = {{n_qkv(c), d}, {d, qo}, {2 * f, d}, {d, f}};
   for (auto& s : shapes) {
-    const int sp = c.dtype == DS_BF16 ? gemm_bf16_splits(s[0], s[1], 1) : 1;
+    const int sp = c.dtype == DS_BF16 ? gemm_bf16_splits(s[0], s[1], &s == &shapes[2] ? 2 : 1) : 1;
     const size_t v = (size_t)rows * s[0] * sp;
     best = v > best ? v : best;
   }
@@ -156,7 +156,8 @@ int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float
       const PackedLayer& pl = m->packed[li];
       w = which == 0 ? pl.wqkv : which == 1 ? pl.wo : which == 2 ? pl.wgu : pl.wdown;
     }
-    const int nbw = which == 4 ? 2 : 1;
+    // two row blocks per wavefront where N is large (LM head, gate/up): half the X traffic per weight byte
+    const int nbw = (which == 4 || which == 2) ? 2 : 1;
     *n_split = which == 4 ? 1 : gemm_bf16_splits(N, K, nbw);
     return launch_gemm_bf16(w, x_in, rows, N, K, nbw, *n_split, out, st);
   }

@@ -80,6 +80,50 @@ __host__ __device__ inline size_t lds_fixed_bytes(int K, int CM, int B) {
          ((size_t)K * B + 15) / 16 * 16;
 }
 
+// Candidate list of one lattice position (first cand_cnt entries, EOS appended if absent): token ids only.
+__device__ __forceinline__ int position_tokens(const int32_t* __restrict__ cand_id, const int32_t* __restrict__ cand_cnt,
+                                               size_t row, int m_max, int32_t eos_id, int32_t* tok) {
+  int cnt = cand_cnt[row];
+  cnt = cnt < 1 ? 1 : (cnt > m_max ? m_max : cnt);
+  bool has_eos = false;
+  for (int c = 0; c < cnt; ++c) {
+    tok[c] = cand_id[row * m_max + c];
+    has_eos |= (tok[c] == eos_id);
+  }
+  if (eos_id >= 0 && !has_eos) tok[cnt++] = eos_id;
+  return cnt;
+}
+
+// Proxy scores of every (u in C[i-2], v in C[i-1], w in C[i]) for one position i of one sequence, spread
+// over the chip (grid = positions x sequences) and written to g[seq][i][a][b][c]; the search kernel then
+// copies its sequence's block into LDS with plain coalesced loads.
+__global__ __launch_bounds__(256) void cps_gather_kernel(const int32_t* __restrict__ cand_id,
+                                                         const int32_t* __restrict__ cand_cnt, int K, int m_max,
+                                                         const float* __restrict__ table, uint32_t table_mask,
+                                                         const int32_t* __restrict__ ctx, int32_t eos_id,
+                                                         float* __restrict__ g) {
+  __shared__ int32_t tok[3][kMaxCand];
+  __shared__ int n[3];
+  const int i = blockIdx.x, seq = blockIdx.y, CM = m_max + 1;
+  if (threadIdx.x < 3) {
+    const int t = threadIdx.x, pos = i - 2 + t;  // t = 0: position i-2, 1: i-1, 2: i
+    if (pos >= 0) {
+      n[t] = position_tokens(cand_id, cand_cnt, (size_t)seq * K + pos, m_max, eos_id, tok[t]);
+    } else {  // before the block: the context token (pos -2 -> older, -1 -> newer)
+      tok[t][0] = ctx[seq * 2 + (pos + 2)];
+      n[t] = 1;
+    }
+  }
+  __syncthreads();
+  const int cube = CM * CM * CM;
+  float* out = g + ((size_t)seq * K + i) * cube;
+  for (int idx = threadIdx.x; idx < cube; idx += blockDim.x) {
+    const int a = idx / (CM * CM), rem = idx - a * (CM * CM), b = rem / CM, c = rem - b * CM;
+    if (a < n[0] && b < n[1] && c < n[2])
+      out[idx] = table[ngram_slot((uint32_t)tok[0][a], (uint32_t)tok[1][b], (uint32_t)tok[2][c], table_mask)];
+  }
+}
+
 // PRE: proxy scores pre-gathered into LDS.  kSlots: expansions per lane (B * (M_max + 1) <= 64 * kSlots).
 template <bool PRE, int kSlots>
 __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ cand_id,
@@ -88,8 +132,9 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
                                                    const float* __restrict__ eos_logp, int K, int m_max, int B,
                                                    float lambda, const float* __restrict__ table,
                                                    uint32_t table_mask, const int32_t* __restrict__ ctx,
-                                                   int32_t eos_id, int32_t* __restrict__ path,
-                                                   int32_t* __restrict__ path_len, float* __restrict__ path_score) {
+                                                   int32_t eos_id, const float* __restrict__ g,
+                                                   int32_t* __restrict__ path, int32_t* __restrict__ path_len,
+                                                   float* __restrict__ path_score) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int CM = m_max + 1;
   Lds L;
@@ -128,7 +173,11 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
   }
   __syncthreads();
 
-  if (PRE) {  // proxy score of every (u, v, w) the search can ask for; positions before the block = context
+  if (PRE && g) {  // scores were gathered by cps_gather_kernel: plain copy into LDS
+    const int total = K * CM * CM * CM;
+    const float* src = g + (size_t)seq * total;
+    for (int idx = tid; idx < total; idx += n_thr) L.ng[idx] = src[idx];
+  } else if (PRE) {  // gather here: proxy score of every (u, v, w) the search can ask for
     const int pairs = K * CM * CM;
     for (int p = tid; p < pairs; p += n_thr) {
       const int i = p / (CM * CM), rem = p - i * (CM * CM);
@@ -273,10 +322,15 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
 
 }  // namespace
 
+size_t cps_ws_bytes(int batch, int K, int m_max) {
+  const size_t CM = (size_t)m_max + 1;
+  return align_up((size_t)batch * K * CM * CM * CM * sizeof(float), 256);
+}
+
 int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
                const float* eos_logp, int batch, int K, int m_max, int B, float lambda,
                const float* table, int log2_size, const int32_t* ctx, int32_t eos_id, int32_t* path,
-               int32_t* path_len, float* path_score, hipStream_t st) {
+               int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, hipStream_t st) {
   const int CM = m_max + 1;
   const size_t fixed = align_up(lds_fixed_bytes(K, CM, B), 16);
   const size_t pre = (size_t)K * CM * CM * CM * sizeof(float);
@@ -285,8 +339,16 @@ int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* ca
   const int slots = ceil_div(B * CM, kWave);  // 1 .. kMaxSlots
 #define DS_CPS_LAUNCH(PRE_, SLOTS_, THREADS_, LDS_)                                                          \
   hipLaunchKernelGGL((cps_kernel<PRE_, SLOTS_>), dim3(batch), dim3(THREADS_), LDS_, st, cand_id, cand_logp,   \
-                     cand_cnt, eos_logp, K, m_max, B, lambda, table, mask, ctx, eos_id, path, path_len,      \
+                     cand_cnt, eos_logp, K, m_max, B, lambda, table, mask, ctx, eos_id, g, path, path_len,   \
                      path_score)
+  const float* g = nullptr;
+  if (use_pre && ws && ws_bytes >= cps_ws_bytes(batch, K, m_max)) {
+    float* gw = static_cast<float*>(ws);
+    hipLaunchKernelGGL(cps_gather_kernel, dim3(K, batch), dim3(256), 0, st, cand_id, cand_cnt, K, m_max, table, mask,
+                       ctx, eos_id, gw);
+    DS_LAUNCH_CHECK("cps_gather_kernel");
+    g = gw;
+  }
   if (use_pre) {
     const size_t lds = fixed + pre;
     if (lds > 48 * 1024) {

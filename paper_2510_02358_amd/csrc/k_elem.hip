@@ -12,17 +12,21 @@
 namespace ds {
 namespace {
 
-__device__ __forceinline__ float block_sum_256(float v, float* red) {
+// Sum over the workgroup (THREADS / 64 wavefronts), same value and same summation order in every thread.
+template <int THREADS>
+__device__ __forceinline__ float block_sum(float v, float* red) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   __syncthreads();
   if (lane == 0) red[wave] = v;
   __syncthreads();
-  return (red[0] + red[1]) + (red[2] + red[3]);
+  float s = 0.f;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) s += red[w];
+  return s;
 }
 
-constexpr int kMaxVec = 8;     // float4 groups per thread: d_model <= 8192 with 256 threads
 constexpr int kMaxPlanes = 8;  // split-K planes summed per element
 
 // Token and rotary arguments of the first kernel of a forward (FROM_EMBED).
@@ -39,15 +43,17 @@ struct Prologue {
 // FROM_EMBED: start from the embedding row (and fill this row of the rotary table, angles in double so
 // that long contexts stay exact), else from the float32 residual x plus `n_part` planes.
 // rm_out (optional): row-major float32 copy of rows >= rm_row0 (the boundary's hidden_out).
-// One workgroup per row, four consecutive columns per thread and step (d_model % 4 == 0); the planes
+// One workgroup per row (1024 threads for wide models so that every load of the row is issued at once),
+// four consecutive columns per thread and step (d_model % 4 == 0); the planes
 // are summed in index order, all loads of a step issued before the first add.
-template <typename T, bool FROM_EMBED>
-__global__ __launch_bounds__(256) void norm_kernel(Prologue pro, const T* __restrict__ embed,
+template <typename T, bool FROM_EMBED, int THREADS>
+__global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, const T* __restrict__ embed,
                                                    float* __restrict__ x, const float* __restrict__ part,
                                                    int n_part, int rows, int rows_pad, int d,
                                                    const float* __restrict__ gain, float eps, T* __restrict__ h,
                                                    float* __restrict__ rm_out, int rm_row0) {
-  __shared__ float red[4];
+  constexpr int kMaxVec = 8192 / (4 * THREADS);  // float4 groups per thread (d_model <= 8192)
+  __shared__ float red[THREADS / 64];
   const int r = blockIdx.x;
   int token = 0;
   if (FROM_EMBED) {
@@ -64,7 +70,7 @@ __global__ __launch_bounds__(256) void norm_kernel(Prologue pro, const T* __rest
   float ss = 0.f;
 #pragma unroll
   for (int i = 0; i < kMaxVec; ++i) {
-    const int c = (threadIdx.x + i * 256) * 4;
+    const int c = (threadIdx.x + i * THREADS) * 4;
     v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (c < d) {
       float4 a;
@@ -88,11 +94,11 @@ __global__ __launch_bounds__(256) void norm_kernel(Prologue pro, const T* __rest
       ss += (a.x * a.x + a.y * a.y) + (a.z * a.z + a.w * a.w);
     }
   }
-  ss = block_sum_256(ss, red);
+  ss = block_sum<THREADS>(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
   for (int i = 0; i < kMaxVec; ++i) {
-    const int c = (threadIdx.x + i * 256) * 4;
+    const int c = (threadIdx.x + i * THREADS) * 4;
     if (c < d) {
       const float4 gn = *reinterpret_cast<const float4*>(gain + c);
       const float4 y = make_float4(v[i].x * inv * gn.x, v[i].y * inv * gn.y, v[i].z * inv * gn.z, v[i].w * inv * gn.w);
@@ -186,8 +192,14 @@ int launch_embed_norm(const int32_t* src, int n_real, int32_t fill, int vocab, i
                       float2* cs, const void* embed, float* x, int rows, int rows_pad, int d, const float* gain,
                       float eps, void* h, hipStream_t st) {
   Prologue pro{src, n_real, vocab, fill, pos0, hd / 2, log2(rope_base), cs};
-  hipLaunchKernelGGL((norm_kernel<T, true>), dim3(rows), dim3(256), 0, st, pro, static_cast<const T*>(embed), x,
-                     (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr, 0);
+  if (d >= 2048)
+    hipLaunchKernelGGL((norm_kernel<T, true, 1024>), dim3(rows), dim3(1024), 0, st, pro, static_cast<const T*>(embed),
+                       x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr,
+                       0);
+  else
+    hipLaunchKernelGGL((norm_kernel<T, true, 256>), dim3(rows), dim3(256), 0, st, pro, static_cast<const T*>(embed),
+                       x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr,
+                       0);
   DS_LAUNCH_CHECK("norm_kernel<embed>");
   return DS_OK;
 }
@@ -195,8 +207,12 @@ int launch_embed_norm(const int32_t* src, int n_real, int32_t fill, int vocab, i
 template <typename T>
 int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
                     float eps, void* h, float* rm_out, int rm_row0, hipStream_t st) {
-  hipLaunchKernelGGL((norm_kernel<T, false>), dim3(rows), dim3(256), 0, st, Prologue{}, (const T*)nullptr, x, part,
-                     n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, rm_row0);
+  if (d >= 2048)
+    hipLaunchKernelGGL((norm_kernel<T, false, 1024>), dim3(rows), dim3(1024), 0, st, Prologue{}, (const T*)nullptr, x,
+                       part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, rm_row0);
+  else
+    hipLaunchKernelGGL((norm_kernel<T, false, 256>), dim3(rows), dim3(256), 0, st, Prologue{}, (const T*)nullptr, x,
+                       part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, rm_row0);
   DS_LAUNCH_CHECK("norm_kernel<add>");
   return DS_OK;
 }

@@ -287,7 +287,7 @@ __global__ __launch_bounds__(kWave) void lattice_merge_kernel(const float* __res
 }
 
 // One workgroup: arg-max of every row from the partial lists, then the accepted-prefix rule.
-__global__ __launch_bounds__(256) void accept_merge_kernel(int rows, int n_part,
+__global__ __launch_bounds__(1024) void accept_merge_kernel(int rows, int n_part,
                                                            const uint32_t* __restrict__ partial,
                                                            const int32_t* __restrict__ block,
                                                            const int32_t* __restrict__ path_len, int32_t eos_id,
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(256) void accept_merge_kernel(int rows, int n_part,
                                                            int32_t* __restrict__ eos_accepted) {
   __shared__ int32_t am[DS_MAX_ROWS];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  for (int r = wave; r < rows; r += 4) {
+  for (int r = wave; r < rows; r += (int)(blockDim.x / kWave)) {
     // arg-max over the per-wavefront winners of this row: plain (value, lower id) reduction
     const uint32_t* rec0 = partial + (size_t)r * n_part * rec_dwords(1);
     float ev = -INFINITY;
@@ -395,7 +395,7 @@ int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t
   hipLaunchKernelGGL(scan_rows_kernel<false>, dim3(p.n_seg, rows), dim3(kScanThreads), 0, st, logits, vocab, 1,
                      p.tiles_per_seg, partial);
   DS_LAUNCH_CHECK("scan_rows_kernel<argmax>");
-  hipLaunchKernelGGL(accept_merge_kernel, dim3(1), dim3(256), 0, st, rows, p.n_part, partial, block, path_len,
+  hipLaunchKernelGGL(accept_merge_kernel, dim3(1), dim3(1024), 0, st, rows, p.n_part, partial, block, path_len,
                      eos_id, n_accept, next_token, argmax, eos_accepted);
   DS_LAUNCH_CHECK("accept_merge_kernel");
   return DS_OK;

@@ -102,6 +102,7 @@ class SpecDecoder:
         self.eos_logp = torch.empty(k_cap, dtype=f32, device=DEV)
         self.lse = torch.empty(k_cap, dtype=f32, device=DEV)
         self.lat_ws = torch.empty(ds.ds_lattice_workspace_bytes(k_cap, vocab, m), dtype=torch.uint8, device=DEV)
+        self.cps_ws = torch.empty(ds.ds_cps_workspace_bytes(1, k_cap, m), dtype=torch.uint8, device=DEV)
         self.block = torch.zeros(k_cap + 1, dtype=i32, device=DEV)       # [last token, path...]
         self.ctx = torch.zeros(2, dtype=i32, device=DEV)
         self.path_len = torch.zeros(1, dtype=i32, device=DEV)
@@ -153,7 +154,8 @@ class SpecDecoder:
         ds.ds_build_lattice(self.d_logits, k, self.d.cfg.vocab, p.m_max, p.tau, self.eos_id, self.cand_id,
                             self.cand_logp, self.cand_cnt, self.eos_logp, self.lse, self.lat_ws, stream)
         ds.ds_cps_path(self.cand_id, self.cand_logp, self.cand_cnt, self.eos_logp, 1, k, p.m_max, p.beam, p.lam,
-                       self.proxy, self.ctx, self.eos_id, self.block[1:], self.path_len, self.path_score, stream)
+                       self.proxy, self.ctx, self.eos_id, self.block[1:], self.path_len, self.path_score, self.cps_ws,
+                       stream)
         ds.ds_verify_block(self.v.handle, self.block, k, self.path_len, self.eos_id, self.result[0:1],
                            self.result[1:2], self.argmax, self.result[2:3], None, self.v.ws, stream)
 

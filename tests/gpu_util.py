@@ -119,7 +119,8 @@ def gpu_lattice(logits: torch.Tensor, m_max: int, tau: float, eos_id: int) -> di
     return out
 
 
-def gpu_cps(lat: dict, batch: int, k: int, m_max: int, beam: int, lam: float, table, log2_size: int, ctx, eos_id: int):
+def gpu_cps(lat: dict, batch: int, k: int, m_max: int, beam: int, lam: float, table, log2_size: int, ctx, eos_id: int,
+            with_ws: bool = True):
     """lat: dict of device tensors (or numpy arrays, uploaded here).  Returns numpy (path, path_len, score)."""
     d = {n: (v if isinstance(v, torch.Tensor) else to_dev(v)) for n, v in lat.items()}
     path = torch.empty(batch, k, dtype=torch.int32, device=DEV)
@@ -127,8 +128,9 @@ def gpu_cps(lat: dict, batch: int, k: int, m_max: int, beam: int, lam: float, ta
     score = torch.empty(batch, dtype=torch.float32, device=DEV)
     proxy = ds.ds_ngram_create(table, log2_size) if table is not None else None
     ctx_d = ctx if isinstance(ctx, torch.Tensor) else to_dev(np.asarray(ctx, dtype=np.int32))
+    ws = torch.empty(ds.ds_cps_workspace_bytes(batch, k, m_max), dtype=torch.uint8, device=DEV) if with_ws else None
     ds.ds_cps_path(d["cand_id"], d["cand_logp"], d["cand_cnt"], d["eos_logp"], batch, k, m_max, beam, lam, proxy,
-                   ctx_d, eos_id, path, plen, score)
+                   ctx_d, eos_id, path, plen, score, ws)
     torch.cuda.synchronize()
     if proxy:
         ds.ds_ngram_destroy(proxy)

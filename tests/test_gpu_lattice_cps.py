@@ -108,10 +108,12 @@ def _cps_case(batch, k_len, m_max, beam, lam, eos_id, seed, vocab=VOCAB, use_tab
     ref_path, ref_len, ref_score = o_cps.cps_batch(lat, batch, k_len, beam, lam, table, synth.NGRAM_LOG2_SIZE, ctx,
                                                    eos_id)
     table_d = gu.to_dev(table) if use_table else None
-    path, plen, score = gu.gpu_cps(lat, batch, k_len, m_max, beam, lam, table_d, synth.NGRAM_LOG2_SIZE, ctx, eos_id)
-    assert np.array_equal(plen, ref_len)
-    assert np.array_equal(path, ref_path)
-    assert np.array_equal(score.view(np.uint32), ref_score.view(np.uint32))
+    for with_ws in (True, False):   # with and without the optional scratch: same bits
+        path, plen, score = gu.gpu_cps(lat, batch, k_len, m_max, beam, lam, table_d, synth.NGRAM_LOG2_SIZE, ctx,
+                                       eos_id, with_ws=with_ws)
+        assert np.array_equal(plen, ref_len)
+        assert np.array_equal(path, ref_path)
+        assert np.array_equal(score.view(np.uint32), ref_score.view(np.uint32))
     return ref_len
 
 
@@ -167,3 +169,31 @@ def test_lattice_then_cps_end_to_end_on_device():
     agree = np.mean(path == rpath)
     assert agree == 1.0, f"token agreement {agree}"
     assert np.max(np.abs(score - rscore)) < 1e-3
+
+
+def test_lattice_stress_full_size_k64_sampled_rows_and_properties():
+    """16 x 64 = 1024 rows x 152064 logits (622.9 MB), top-16: sampled rows against the oracle, and
+    size-independent properties on every row."""
+    k_len, m_max = 64, 16
+    logits = synth.make_logits(16, k_len, VOCAB, seed=123)
+    eos = VOCAB - 2
+    got = {k: gu.from_dev(v) for k, v in gu.gpu_lattice(gu.to_dev(logits), m_max, 0.8, eos).items()}
+    rows = logits.shape[0]
+    sample = np.random.default_rng(0).choice(rows, size=24, replace=False)
+    ref = o_lat.build_lattice(logits[sample], m_max, 0.8, eos)
+    assert np.array_equal(got["cand_id"][sample], ref["cand_id"])
+    assert np.array_equal(got["cand_cnt"][sample], ref["cand_cnt"])
+    assert np.max(np.abs(got["lse"][sample] - ref["lse"])) <= LSE_TOL
+    assert np.max(np.abs(got["cand_logp"][sample] - ref["cand_logp"])) <= LSE_TOL
+    # every row: candidates are the row's largest values in order, log-prob identity, mass bound
+    picked = logits[np.arange(rows)[:, None], got["cand_id"]]
+    assert np.all(np.diff(picked, axis=1) <= 0)
+    assert np.array_equal(picked[:, 0], logits.max(axis=1))
+    kth = np.partition(logits, VOCAB - m_max, axis=1)[:, VOCAB - m_max]
+    assert np.array_equal(picked[:, -1], kth)
+    assert np.array_equal(got["cand_logp"], picked - got["lse"][:, None])
+    assert np.array_equal(got["eos_logp"], logits[:, eos] - got["lse"])
+    mass = np.exp(got["cand_logp"].astype(np.float64)).sum(axis=1)
+    assert np.all(mass < 1.0) and np.all(got["cand_cnt"] >= 1) and np.all(got["cand_cnt"] <= m_max)
+    lse64 = np.log(np.exp(logits[::37].astype(np.float64) - 20.0).sum(axis=1)) + 20.0
+    assert np.max(np.abs(got["lse"][::37] - lse64)) <= LSE_TOL

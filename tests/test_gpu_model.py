@@ -190,3 +190,30 @@ def test_argument_errors_with_a_live_model():
         assert e.value.code == ds.DS_E_CAPACITY
     finally:
         gm.close()
+
+
+@pytest.mark.parametrize("cfg_name", ["f32", "bf16"])
+def test_degenerate_row_counts(cfg_name):
+    """K = 1 draft with no pending token, and an empty path (m = 0: one verifier row)."""
+    cfg = synth.CFG_TINY if cfg_name == "f32" else SMALL_BF16
+    tol = TOL[cfg.dtype]
+    w = synth.make_weights(cfg, 40)
+    prefix = synth.make_prefix(cfg, 70, 41)
+    gm = gu.GpuModel(cfg, w, 128)
+    try:
+        oc = o_model.KVCache(cfg)
+        o_model.prefill(cfg, w, oc, prefix)
+        gm.prefill(prefix, want_logits=False)
+        ref_hid = o_model.draft_block(cfg, w, oc, [], 1)
+        hid = gm.draft([], 1)
+        logits = gu.from_dev(gm.lm_head(hid))
+        assert gm.kv_len == len(prefix)
+        assert np.max(np.abs(logits - o_model.lm_head(w, ref_hid))) <= tol
+        last = int(prefix[-1])
+        ref_v = o_model.verify_logits(cfg, w, oc, [last])
+        out = gm.verify(np.array([last], dtype=np.int32), eos_id=cfg.eos_id)
+        assert np.max(np.abs(out["logits"] - ref_v)) <= tol
+        assert out["n_accept"] == 0 and out["next_token"] == int(out["argmax"][0])
+        assert _check_argmax(out["argmax"], ref_v, tol) in (0, 1)
+    finally:
+        gm.close()
