@@ -19,7 +19,9 @@ from . import synth
 DEV = "cuda:0"
 
 
-def upload(a: np.ndarray, bf16: bool = False) -> torch.Tensor:
+def upload(a, bf16: bool = False) -> torch.Tensor:
+    if isinstance(a, torch.Tensor):  # already on the device (weights drawn there for the deep workloads)
+        return a
     if bf16:
         bits = synth.f32_to_bf16_bits(a).reshape(a.shape)
         return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
@@ -145,8 +147,13 @@ class SpecDecoder:
         self.tokens = [int(x) for x in prefix] + [first]
         self.pending = [first]
 
-    def enqueue_round(self, k: int, stream=None) -> None:
-        """Enqueue draft -> LM head -> lattice -> path search -> verify for the current state.  No sync."""
+    def enqueue_round(self, k: int, stream=None, inject=None) -> None:
+        """Enqueue draft -> LM head -> lattice -> path search -> verify for the current state.  No sync.
+
+        inject = (device int32 tensor, a): overwrite the first `a` searched path tokens with these tokens before
+        verification and let all k block positions take part in acceptance (synthetic acceptance for benchmarks
+        and tests; plain device copies).
+        """
         p = self.p
         n_pend = len(self.pending)
         ds.ds_draft_block(self.d.handle, self.pending_dev, n_pend, k, self.mask_id, self.hidden, self.d.ws, stream)
@@ -156,6 +163,9 @@ class SpecDecoder:
         ds.ds_cps_path(self.cand_id, self.cand_logp, self.cand_cnt, self.eos_logp, 1, k, p.m_max, p.beam, p.lam,
                        self.proxy, self.ctx, self.eos_id, self.block[1:], self.path_len, self.path_score, self.cps_ws,
                        stream)
+        if inject is not None and inject[1] > 0:
+            self.block[1:1 + inject[1]].copy_(inject[0][:inject[1]], non_blocking=True)
+            self.path_len.fill_(k)  # the searched path may have stopped at an EOS before the injected length
         ds.ds_verify_block(self.v.handle, self.block, k, self.path_len, self.eos_id, self.result[0:1],
                            self.result[1:2], self.argmax, self.result[2:3], None, self.v.ws, stream)
 
@@ -171,11 +181,11 @@ class SpecDecoder:
         h[n + 2] = self.tokens[-1]
         self.ctx.copy_(h[n + 1:n + 3], non_blocking=True)
 
-    def round(self, k: int) -> dict:
+    def round(self, k: int, inject=None) -> dict:
         """One full round including the host read-back, KV commit and the draft-length update."""
         self.stage_inputs()
         v_len = self.v.kv_len
-        self.enqueue_round(k)
+        self.enqueue_round(k, inject=inject)
         res = self.result.cpu()                 # synchronises the stream
         raw0 = self.cand_id[:k, 0].cpu().numpy()
         plen = int(self.path_len.item())
@@ -190,3 +200,57 @@ class SpecDecoder:
         k_next = ds.ds_adl_update(self.adl, k, first_eos, n_acc)
         return {"k": k, "path": path, "path_len": plen, "n_accept": n_acc, "next_token": nxt, "eos_accepted": eos,
                 "committed": committed, "first_eos": first_eos, "k_next": k_next}
+
+
+def ar_greedy(model: DeviceModel, prefix: np.ndarray, n_new: int, timing: Optional[dict] = None) -> List[int]:
+    """Plain greedy decoding of `model` on the GPU, one token per step (the baseline that speed-ups are quoted
+    against, and the reference stream of the lossless check).  Every step is a ds_verify_block call with an
+    empty path (one row); tokens stay on the device between steps, so there is no host sync inside the loop.
+    """
+    t = upload(np.asarray(prefix, dtype=np.int32))
+    vocab = model.cfg.vocab
+    last = torch.empty(vocab, dtype=torch.float32, device=DEV)
+    model.set_kv_len(0)
+    ds.ds_prefill(model.handle, t, len(prefix), last, model.ws)
+    toks = torch.zeros(n_new + 1, dtype=torch.int32, device=DEV)
+    scratch_f = torch.empty(3, dtype=torch.float32, device=DEV)
+    scratch_i = torch.empty(4, dtype=torch.int32, device=DEV)
+    ws = torch.empty(ds.ds_lattice_workspace_bytes(1, vocab, 1), dtype=torch.uint8, device=DEV)
+    # first token: top-1 of the prefill logits (ties to the lower id)
+    ds.ds_build_lattice(last, 1, vocab, 1, 1.0, -1, toks[0:1], scratch_f[0:1], scratch_i[0:1], scratch_f[1:2],
+                        scratch_f[2:3], ws)
+    base = len(prefix)
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for i in range(n_new - 1):
+        ds.ds_verify_block(model.handle, toks[i:i + 1], 0, None, -1, scratch_i[1:2], toks[i + 1:i + 2],
+                           scratch_i[2:3], scratch_i[3:4], None, model.ws)
+        model.set_kv_len(base + i + 1)
+    t1.record()
+    torch.cuda.synchronize()
+    if timing is not None:
+        timing["decode_ms"] = t0.elapsed_time(t1)
+        timing["steps"] = n_new - 1
+    return [int(x) for x in toks[:n_new].cpu().numpy()]
+
+
+def device_weights(cfg: synth.ModelCfg, seed: int, std: float = 0.02) -> dict:
+    """Random-init weights drawn directly on the GPU (torch generator), for workloads too large to draw on
+    the host in reasonable time.  Same structure as synth.make_weights; no oracle consumes these."""
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+
+    def draw(shape):
+        return (torch.randn(shape, generator=gen, device=DEV, dtype=torch.float32) * std).to(dt)
+
+    out = {"embed": draw((cfg.vocab, cfg.d_model)), "layers": []}
+    shapes = synth.layer_shapes(cfg)
+    for _ in range(cfg.n_layers):
+        lw = {n: draw(shapes[n]) for n in synth.LAYER_TENSORS}
+        lw["norm1"] = torch.ones(cfg.d_model, device=DEV)
+        lw["norm2"] = torch.ones(cfg.d_model, device=DEV)
+        out["layers"].append(lw)
+    out["final_norm"] = torch.ones(cfg.d_model, device=DEV)
+    out["lm_head"] = draw((cfg.vocab, cfg.d_model))
+    return out
