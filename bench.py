@@ -45,29 +45,46 @@ def traffic_from_profiles():
     return None
 
 
-def run_cfg2(args) -> int:
-    """Full-depth pair: 28-layer drafter + 28-layer verifier (7B-shaped), prefix 1024, 64 rounds, draft length
-    adapted in [4, 64] from k_1 = 16.  Two variants: natural (independent random models accept nothing) and
-    synthetic acceptance injected from the verifier's greedy stream.  Weights are drawn on the device."""
+def run_deep(args) -> int:
+    """Full-depth pairs (extra evidence beside the default workload; weights are drawn on the device, no CPU leg).
+
+    cfg2: 28-layer drafter + 28-layer verifier (7B-shaped), prefix 1024, 64 rounds, draft length adapted in
+          [4, 64] from k_1 = 16.
+    cfg4: 28-layer 7B-shaped drafter + 64-layer 32B-shaped verifier, prefix 16384, K = 64 fixed, 16 rounds.
+    Two variants each: natural (independent random models accept nothing) and synthetic acceptance injected
+    from the verifier's greedy stream.
+    """
     import numpy as np
     import torch
 
     from paper_2510_02358_amd import round as rnd
     from paper_2510_02358_amd import synth
 
-    cfg = synth.with_layers(synth.CFG_7B_LAYER, 28)
-    n_rounds, prefix_len, k1 = 64, 1024, 16
+    d_cfg = synth.with_layers(synth.CFG_7B_LAYER, 28)
+    if args.workload == "cfg2":
+        v_cfg, n_rounds, prefix_len, k1, k_min, k_max = d_cfg, 64, 1024, 16, 4, 64
+        name = ("cfg2: 28-layer 7B-shaped drafter + 28-layer verifier, prefix 1024, ADL k in [4, 64] from 16, "
+                "64 rounds, top-8 lattice, beam 4, batch 1")
+    else:
+        v_cfg, n_rounds, prefix_len, k1, k_min, k_max = synth.with_layers(synth.CFG_32B_LAYER, 64), 16, 16384, 64, 64, 64
+        name = ("cfg4: 28-layer 7B-shaped drafter + 64-layer 32B-shaped verifier (d=5120, 40q/8kv x128, FFN 27648), "
+                "prefix 16384, K=64, 16 rounds, top-8 lattice, beam 4, batch 1")
     t0 = time.time()
-    prefix = synth.make_prefix(cfg, prefix_len, 2)
+    prefix = synth.make_prefix(d_cfg, prefix_len, 2)
     table = synth.make_ngram_table(3)
     cap = prefix_len + 1024
-    dm = rnd.DeviceModel(cfg, rnd.device_weights(cfg, 0), cap)
-    vm = rnd.DeviceModel(cfg, rnd.device_weights(cfg, 1), cap)
-    params = rnd.RoundParams(m_max=M_MAX, beam=BEAM, lam=LAM, k_min=4, k_max=64, delta=10.0, rho=0.5)
-    layer = synth.layer_param_count(cfg) * 2
-    head = cfg.vocab * cfg.d_model * 2
-    weights_bytes = 2 * (28 * layer + head)
-    res = {}
+    dm = rnd.DeviceModel(d_cfg, rnd.device_weights(d_cfg, 0), cap)
+    vm = rnd.DeviceModel(v_cfg, rnd.device_weights(v_cfg, 1), cap)
+    params = rnd.RoundParams(m_max=M_MAX, beam=BEAM, lam=LAM, k_min=k_min, k_max=k_max, delta=10.0, rho=0.5)
+
+    def model_bytes(c):
+        return c.n_layers * synth.layer_param_count(c) * 2 + c.vocab * c.d_model * 2
+
+    def kv_bytes(c, n):
+        return c.n_layers * 2 * c.n_kv * c.head_dim * 2 * n
+
+    round_bytes = model_bytes(d_cfg) + model_bytes(v_cfg) + kv_bytes(d_cfg, prefix_len) + kv_bytes(v_cfg, prefix_len)
+    res = {"algorithmic_bytes_per_round": round_bytes}
     for variant in ("natural", "synthetic_acceptance"):
         dec = rnd.SpecDecoder(dm, vm, table, synth.NGRAM_LOG2_SIZE, params, k_cap=64)
         stream = stream_dev = None
@@ -76,6 +93,8 @@ def run_cfg2(args) -> int:
             stream = rnd.ar_greedy(vm, prefix, n_rounds * 9 + 72, timing=ar_t)
             stream_dev = rnd.upload(np.asarray(stream, dtype=np.int32))
             res["ar_greedy_tokens_per_s"] = round(ar_t["steps"] / (ar_t["decode_ms"] * 1e-3), 1)
+            res["ar_greedy_hbm_frac"] = round((model_bytes(v_cfg) + kv_bytes(v_cfg, prefix_len)) /
+                                              (ar_t["decode_ms"] * 1e-3 / ar_t["steps"]) / 1e9 / HBM_PEAK_GBS, 4)
         dec.start(prefix)
         rng = np.random.default_rng(5)
         k, ks, n_tok, n_acc_sum = k1, [], 0, 0
@@ -97,7 +116,7 @@ def run_cfg2(args) -> int:
         res[variant] = {"rounds_per_s": round(n_rounds / el, 2), "ms_per_round": round(el * 1e3 / n_rounds, 3),
                         "tokens_per_s": round(n_tok / el, 1), "mean_accepted": round(n_acc_sum / n_rounds, 2),
                         "mean_k": round(float(np.mean(ks)), 1), "k_last": ks[-1],
-                        "weights_hbm_frac": round(weights_bytes / (el / n_rounds) / 1e9 / HBM_PEAK_GBS, 4)}
+                        "round_hbm_frac": round(round_bytes / (el / n_rounds) / 1e9 / HBM_PEAK_GBS, 4)}
         if stream is not None:
             res[variant]["committed_stream_equals_ar_greedy"] = bool(
                 dec.tokens[len(prefix):] == stream[:len(dec.tokens) - len(prefix)])
@@ -107,11 +126,11 @@ def run_cfg2(args) -> int:
     out = {"metric": "spec_rounds_per_s", "value": nat["rounds_per_s"], "unit": "rounds/s", "n_gpus": 1,
            "steps": n_rounds, "warmup": 0, "ms_per_step": nat["ms_per_round"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic (weights drawn on the device)",
-           "config": {"workload": "cfg2: 28-layer 7B-shaped drafter + 28-layer verifier, prefix 1024, ADL k in "
-                                  "[4, 64] from 16, 64 rounds, top-8 lattice, beam 4, batch 1"},
-           "variants": res, "setup_s": round(time.time() - t0, 1), "roofline": None, "cpu_baseline": None}
+           "config": {"workload": name}, "variants": res, "setup_s": round(time.time() - t0, 1), "roofline": None,
+           "cpu_baseline": None}
     print(json.dumps(out))
-    dm.close(); vm.close()
+    dm.close()
+    vm.close()
     return 0
 
 
@@ -121,9 +140,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["cfg1", "cfg2"], default="cfg1",
+    ap.add_argument("--workload", choices=["cfg1", "cfg2", "cfg4"], default="cfg1",
                     help="cfg1 (default): the benchmark workload.  cfg2: full 28-layer 7B-shaped drafter + verifier, "
-                         "prefix 1024, draft length adapted in [4, 64] over 64 rounds (extra evidence, no CPU leg)")
+                         "prefix 1024, draft length adapted in [4, 64] over 64 rounds.  cfg4: that drafter + 64-layer "
+                         "32B-shaped verifier, prefix 16384, K=64 (both: extra evidence, no CPU leg)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -141,8 +161,8 @@ def main() -> int:
 
     ds.load()  # raises if the HIP library is missing: there is no fallback
     torch.cuda.set_device(0)
-    if args.workload == "cfg2":
-        return run_cfg2(args)
+    if args.workload != "cfg1":
+        return run_deep(args)
     cfg = synth.CFG_7B_LAYER
     t0 = time.time()
     dw, vw = synth.make_weights(cfg, 0), synth.make_weights(cfg, 1)

@@ -57,8 +57,10 @@ typedef struct ds_adl ds_adl;
 typedef struct {
   int32_t n_layers, d_model, n_q, n_kv, head_dim, d_ffn, vocab;
   float rope_base, rms_eps;
-  int32_t dtype;       /* DS_F32 or DS_BF16: storage type of the weights.  DS_BF16: bf16 weights, 16-bit
-                          (IEEE half) KV cache, float32 accumulation.  DS_F32: everything float32. */
+  int32_t dtype;       /* DS_F32 or DS_BF16: storage type of the weights.  DS_BF16: bf16 weights (re-encoded
+                          exactly as IEEE half inside the library), IEEE-half activations at every matrix
+                          product and in the KV cache, float32 accumulation, residual stream and logits.
+                          DS_F32: everything float32. */
   int32_t kv_capacity; /* tokens each layer's KV buffer can hold (bf16: a multiple of 64) */
 } ds_model_cfg;
 
@@ -86,10 +88,12 @@ int ds_workspace_bytes(const ds_model_cfg* cfg, int max_rows, size_t* bytes);
 /* Bytes of ONE of the two KV buffers (keys or values) for cfg. */
 int ds_kv_bytes(const ds_model_cfg* cfg, size_t* bytes);
 
-/* Bind a model.  For DS_BF16 this enqueues kernels that copy the matrices into the order the GEMM
- * kernels stream them in (`packed`, ds_model_packed_bytes() bytes, 256-byte aligned); after the
- * stream has run them the canonical matrices other than `embed` are no longer read.  For DS_F32
- * nothing is copied and the canonical matrices are read by every call.  kv_k / kv_v: ds_kv_bytes()
+/* Bind a model.  For DS_BF16 this runs kernels that copy the matrices, re-encoded as IEEE half, into
+ * the order the GEMM kernels stream them in (`packed`, ds_model_packed_bytes() bytes, 256-byte
+ * aligned) and waits for them (this one call synchronises `stream`); afterwards the canonical matrices
+ * other than `embed` are no longer read.  The re-encoding is exact for 2^-14 <= |w| <= 65504 (smaller
+ * magnitudes round to multiples of 2^-24); a NaN or a weight beyond +-65504 fails the call with
+ * DS_E_UNSUPPORTED.  For DS_F32 nothing is copied and the canonical matrices are read by every call.  kv_k / kv_v: ds_kv_bytes()
  * each; their internal layout is private to the library.  The committed KV length starts at 0. */
 int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, size_t packed_bytes,
                     void* kv_k, void* kv_v, void* stream, ds_model** out);
@@ -116,8 +120,8 @@ int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, vo
 int ds_draft_block(ds_model* drafter, const int32_t* pending, int n_pend, int K, int32_t mask_id,
                    float* hidden_out, void* ws, size_t ws_bytes, void* stream);
 
-/* logits[rows, vocab] = hidden[rows, d_model] times the LM head (all [dev] float32; DS_BF16 models split
- * each hidden value into two bf16 terms and accumulate both products in float32). */
+/* logits[rows, vocab] = hidden[rows, d_model] times the LM head (all [dev] float32; DS_BF16 models round
+ * each hidden value to IEEE half and accumulate the half x half products in float32). */
 int ds_lm_head(ds_model* m, const float* hidden, int rows, float* logits, void* ws, size_t ws_bytes,
                void* stream);
 

@@ -1,13 +1,17 @@
 // Storage-type traits.
 //
 // DS_F32 (parity mode): everything float32, row-major.
-// DS_BF16: weights bf16.  An activation that feeds a GEMM is kept as a PAIR of bf16 planes
-//   hi = bf16(x), lo = bf16(x - hi), both in tile order (xt_offset); the GEMM multiplies the bf16
-//   weights with both planes and accumulates in float32, so the activation keeps ~16 mantissa bits
-//   while every matrix-core product is still bf16 x bf16.  Queries, keys, values and attention
-//   probabilities are IEEE half (11 mantissa bits, 2 bytes like bf16): with N(0, 0.02) random-init
-//   weights the residual stream is ~0.03 rms, the RMSNorm after attention amplifies any error of
-//   the attention output ~30x, and a bf16 KV cache alone would consume the whole 2e-2 logit budget.
+// DS_BF16: the caller's weights are bf16.  Every activation that meets a weight on the matrix cores
+//   is IEEE half (11 mantissa bits, 2 bytes like bf16) in tile order (xt_offset), and the weight
+//   copies the GEMM kernels stream are re-encoded from bf16 to half when they are packed: a bf16
+//   value has 8 mantissa bits, so the re-encoding is exact for 2^-14 <= |w| <= 65504 (smaller values
+//   land on the half subnormal grid, absolute error <= 2^-25; larger ones are refused).  One product
+//   per element then carries ~8x less activation rounding than a bf16 activation would, at the same
+//   matrix-core rate and with half the operand traffic of a two-term bf16 split.  Queries, keys,
+//   values and attention probabilities are half as well: with N(0, 0.02) random-init weights the
+//   residual stream is ~0.03 rms, the RMSNorm after attention amplifies any error of the attention
+//   output ~30x, and a bf16 KV cache alone would consume the whole 2e-2 logit budget.
+//   Accumulation, the residual stream, split-K partial sums and logits are float32.
 #pragma once
 
 #include "ds_common.h"
@@ -40,13 +44,12 @@ template <>
 struct Act<float> {
   using kv_t = float;                         // element type of q / K cache / V cache
   static constexpr bool kTransposedV = false;
-  static constexpr int kPlanes = 1;
   // GEMM-input store: element (m, k) of a [rows_pad, K] activation
-  __device__ static __forceinline__ void put(float* base, int m, int k, int K, size_t /*plane*/, float v) {
+  __device__ static __forceinline__ void put(float* base, int m, int k, int K, float v) {
     base[(size_t)m * K + k] = v;
   }
   // four consecutive columns k .. k+3 (k % 4 == 0)
-  __device__ static __forceinline__ void put4(float* base, int m, int k, int K, size_t /*plane*/, float4 v) {
+  __device__ static __forceinline__ void put4(float* base, int m, int k, int K, float4 v) {
     *reinterpret_cast<float4*>(base + (size_t)m * K + k) = v;
   }
   __device__ static __forceinline__ size_t q_off(int m, int k, int K) { return (size_t)m * K + k; }
@@ -58,26 +61,18 @@ template <>
 struct Act<bf16_t> {
   using kv_t = uint16_t;                      // IEEE half bits
   static constexpr bool kTransposedV = true;  // V cache kept as [head_dim][capacity] per head
-  static constexpr int kPlanes = 2;
-  __device__ static __forceinline__ void put(bf16_t* base, int m, int k, int K, size_t plane, float v) {
-    const size_t off = xt_offset(m, k, K);
-    const uint16_t hi = float_to_bf16_bits(v);
-    base[off].bits = hi;
-    base[plane + off].bits = float_to_bf16_bits(v - bf16_bits_to_float(hi));
+  // GEMM-input store: element (m, k) of a [rows_pad, K] half activation in tile order (values beyond the half
+  // range saturate to +-65504 instead of becoming infinite)
+  __device__ static __forceinline__ uint16_t gemm_in(float v) {
+    return float_to_half_bits(fminf(fmaxf(v, -65504.f), 65504.f));
   }
-  // four consecutive columns k .. k+3 (k % 4 == 0) are adjacent in tile order: one 8-byte store per plane
-  __device__ static __forceinline__ void put4(bf16_t* base, int m, int k, int K, size_t plane, float4 v) {
-    const size_t off = xt_offset(m, k, K);
-    const float f[4] = {v.x, v.y, v.z, v.w};
-    uint16_t hi[4], lo[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      hi[i] = float_to_bf16_bits(f[i]);
-      lo[i] = float_to_bf16_bits(f[i] - bf16_bits_to_float(hi[i]));
-    }
-    *reinterpret_cast<uint2*>(base + off) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
-    *reinterpret_cast<uint2*>(base + plane + off) =
-        make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+  __device__ static __forceinline__ void put(bf16_t* base, int m, int k, int K, float v) {
+    base[xt_offset(m, k, K)].bits = gemm_in(v);
+  }
+  // four consecutive columns k .. k+3 (k % 4 == 0) are adjacent in tile order: one 8-byte store
+  __device__ static __forceinline__ void put4(bf16_t* base, int m, int k, int K, float4 v) {
+    const uint32_t h0 = gemm_in(v.x), h1 = gemm_in(v.y), h2 = gemm_in(v.z), h3 = gemm_in(v.w);
+    *reinterpret_cast<uint2*>(base + xt_offset(m, k, K)) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
   }
   __device__ static __forceinline__ size_t q_off(int m, int k, int K) { return xt_offset(m, k, K); }
   __device__ static __forceinline__ uint16_t to_kv(float v) { return float_to_half_bits(v); }
@@ -101,7 +96,8 @@ int launch_qkv_rope(const float* part, int n_part, int rows, int rows_pad, int n
 template <typename T>
 int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, hipStream_t st);
 
-int launch_pack_weight(const void* w, int N, int K, void* dst, hipStream_t st);
+// bf16 -> half re-encoding into stream order; *range_flag [dev] is set to 1 if any |w| exceeds the half range
+int launch_pack_weight(const void* w, int N, int K, void* dst, uint32_t* range_flag, hipStream_t st);
 int gemm_bf16_splits(int N, int K, int nbw);
 int launch_gemm_bf16(const void* wp, const void* xt, int M, int N, int K, int nbw, int n_split, float* out,
                      hipStream_t st);

@@ -79,11 +79,13 @@ int validate_cfg(const ds_model_cfg* c) {
 
 size_t esize_of(int dtype) { return dtype == DS_BF16 ? 2 : 4; }
 
+constexpr size_t kFlagBytes = 256;  // tail of the packed buffer: weight-range flag written by the packing kernels
+
 size_t packed_bytes_of(const ds_model_cfg& c) {
   if (c.dtype != DS_BF16) return 0;
   const size_t d = c.d_model, f = c.d_ffn, qo = (size_t)c.n_q * c.head_dim;
   const size_t per_layer = ((size_t)n_qkv(c) * d + d * qo + 2 * f * d + d * f) * 2;
-  return per_layer * c.n_layers + (size_t)c.vocab * d * 2;
+  return per_layer * c.n_layers + (size_t)c.vocab * d * 2 + kFlagBytes;
 }
 
 size_t kv_bytes_of(const ds_model_cfg& c) {
@@ -116,12 +118,11 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
   };
   w.x = static_cast<float*>(take((size_t)rows * c.d_model * 4));
   w.cs = static_cast<float2*>(take((size_t)rows * (c.head_dim / 2) * 8));
-  const size_t planes = c.dtype == DS_BF16 ? 2 : 1;  // GEMM inputs: (hi, lo) bf16 pair or one float32 plane
-  w.h = take(planes * rp * c.d_model * es);
+  w.h = take((size_t)rp * c.d_model * es);  // GEMM inputs: half in tile order, or float32 row-major
   w.q = take((size_t)c.n_q * rp * c.head_dim * es);
-  w.att = take(planes * rp * c.n_q * c.head_dim * es);
-  w.act = take(planes * rp * c.d_ffn * es);
-  w.y = take(planes * rp * c.d_model * es);
+  w.att = take((size_t)rp * c.n_q * c.head_dim * es);
+  w.act = take((size_t)rp * c.d_ffn * es);
+  w.y = take((size_t)rp * c.d_model * es);
   size_t gf = 0;
   widest_split_floats(c, rows, &gf);
   w.gemm_out = static_cast<float*>(take(gf * 4));
@@ -318,8 +319,13 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* p = static_cast<char*>(packed);
     const int d = cfg->d_model, f = cfg->d_ffn, hd = cfg->head_dim, qo = cfg->n_q * hd, kvn = cfg->n_kv * hd;
+    uint32_t* flag = reinterpret_cast<uint32_t*>(p + need - kFlagBytes);
+    if (hipMemsetAsync(flag, 0, sizeof(uint32_t), st) != hipSuccess) {
+      delete m;
+      return fail(DS_E_HIP, "hipMemsetAsync(weight-range flag) failed");
+    }
     auto put = [&](const void* src, int N, int K) -> int {
-      int r = launch_pack_weight(src, N, K, p, st);
+      int r = launch_pack_weight(src, N, K, p, flag, st);
       p += (size_t)N * K * 2;
       return r;
     };
@@ -339,6 +345,14 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
     if (!rc) {
       m->lm_head = p;
       rc = put(w->lm_head, cfg->vocab, d);
+    }
+    if (!rc) {  // the packed copies are half precision: refuse weights outside the half range
+      uint32_t bad = 0;
+      if (hipMemcpyAsync(&bad, flag, sizeof(bad), hipMemcpyDeviceToHost, st) != hipSuccess ||
+          hipStreamSynchronize(st) != hipSuccess)
+        rc = fail(DS_E_HIP, "reading the weight-range flag failed");
+      else if (bad)
+        rc = fail(DS_E_UNSUPPORTED, "a weight is NaN or exceeds the half-precision range (|w| > 65504)");
     }
     if (rc) {
       delete m;

@@ -301,7 +301,7 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
     num += o * w;
     den += l * w;
   }
-  Act<T>::put(att, r, head * hd + d, n_q * hd, (size_t)rows_pad * n_q * hd, num / den);
+  Act<T>::put(att, r, head * hd + d, n_q * hd, num / den);
 }
 
 int chunks_per_split(int dtype, int n_keys) {

@@ -3,7 +3,7 @@
 // (fixed-order) sum of the GEMM's split-K partial planes, so no separate reduction pass exists.
 //
 // The residual stream x stays float32 [rows, d_model].  Activations that feed a GEMM are written in
-// the model's storage form: a (hi, lo) pair of bf16 planes in tile order, or float32 row-major.
+// the model's storage form: IEEE half in tile order, or float32 row-major.
 #include <math.h>
 
 #include "ds_act.h"
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, const T* __
     if (c < d) {
       const float4 gn = *reinterpret_cast<const float4*>(gain + c);
       const float4 y = make_float4(v[i].x * inv * gn.x, v[i].y * inv * gn.y, v[i].z * inv * gn.z, v[i].w * inv * gn.w);
-      Act<T>::put4(h, r, c, d, (size_t)rows_pad * d, y);
+      Act<T>::put4(h, r, c, d, y);
       if (rm_out && r >= rm_row0) *reinterpret_cast<float4*>(rm_out + (size_t)(r - rm_row0) * d + c) = y;
     }
   }
@@ -113,7 +113,7 @@ template <typename T>
 __global__ void to_gemm_input_kernel(const float* __restrict__ src, int rows_pad, int d, T* __restrict__ dst) {
   const int r = blockIdx.x;
   for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4)
-    Act<T>::put4(dst, r, c, d, (size_t)rows_pad * d, *reinterpret_cast<const float4*>(src + (size_t)r * d + c));
+    Act<T>::put4(dst, r, c, d, *reinterpret_cast<const float4*>(src + (size_t)r * d + c));
 }
 
 // One wavefront per (row, head slot): sums the QKV partial planes, rotates q and k, writes q in the
@@ -182,7 +182,7 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
   }
   const float4 y = make_float4(g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
                                g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w);
-  Act<T>::put4(act, r, f, F, (size_t)rows_pad * F, y);
+  Act<T>::put4(act, r, f, F, y);
 }
 
 }  // namespace

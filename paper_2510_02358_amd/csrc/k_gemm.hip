@@ -5,18 +5,19 @@
 // by HBM bandwidth, not by the matrix cores.  MFMA is used because the work is a dense contraction
 // and plain ALUs would become the limiter at M = 33..130.
 //
-// bf16 path
+// bf16 path (bf16 weights from the caller, half-precision products)
 //   * W is kept in "stream order": tiles of 16 output rows x 32 inputs, 1 KB each, laid out
-//     [N/16][K/32][64 lanes][8 bf16] so that lane (16 g + i) holds W[16 nb + i][32 ks + 8 g .. + 7].
+//     [N/16][K/32][64 lanes][8 half] so that lane (16 g + i) holds W[16 nb + i][32 ks + 8 g .. + 7].
 //     That is exactly the register image of the 16x16x32 MFMA's first operand: a wavefront reads
 //     one tile with one fully coalesced 16-byte-per-lane load and feeds it to the matrix core
 //     with no LDS round trip.  A wavefront walks K for its NB row blocks, so its loads form NB
-//     contiguous streams.
-//   * X arrives as two bf16 planes (hi, lo with x ~ hi + lo, tile order, see xt_offset); both are
-//     multiplied with the same weight tile, so the activation keeps ~16 mantissa bits although every
-//     matrix-core product is bf16 x bf16 with float32 accumulation.  X is staged through LDS in
-//     chunks of 128 (or 64) columns and shared by the 4 wavefronts of the workgroup; weight tiles
-//     for the next chunk are already in flight while the current chunk is multiplied.
+//     contiguous streams.  The packing kernel re-encodes each bf16 weight as IEEE half (exact for
+//     2^-14 <= |w| <= 65504; smaller magnitudes round to the half subnormal grid, larger ones raise
+//     a flag that fails model creation), so the activation operand can be half too.
+//   * X arrives as IEEE half in tile order (see xt_offset): 11 mantissa bits per activation in a
+//     single product per weight, float32 accumulation.  X is staged through LDS in chunks of 128
+//     columns and shared by the 4 wavefronts of the workgroup; weight tiles for the next two chunks
+//     are already in flight while the current chunk is multiplied.
 //   * D[i][j] of the MFMA = out[16 mb + j][16 nb + i]: lane (16 g + j) ends with 4 consecutive
 //     output columns of row j, stored as one float4.
 //   * Split-K writes float32 partial planes out[s][M][N]; the consumer kernel sums them in a fixed
@@ -29,7 +30,7 @@
 
 namespace ds {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -37,11 +38,14 @@ namespace {
 
 constexpr int kGemmThreads = 256;
 constexpr int kGroup = 4;  // split-K granularity in k-steps of 32: 128 columns
-// k-steps per LDS chunk: 128 columns for up to 64 rows, 64 columns above (keeps LDS <= 72 KB)
-constexpr int ksc_for(int MB) { return MB <= 4 ? 4 : 2; }
+constexpr int kKSC = 4;    // k-steps per LDS chunk: 128 columns (8 KB of X per row block and buffer pair)
+// Register budget: two wavefronts per SIMD (<= 256 VGPRs) wherever the tile fits without spilling; the
+// widest tiles keep one wavefront per SIMD and the full register file.
+constexpr int min_waves_for(int MB, int NB) { return (NB == 2 && MB >= 6) ? 1 : 2; }
 
-// Copy a canonical row-major bf16 matrix W[N, K] into stream order.  One thread per 16-byte piece.
-__global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K, uint16_t* __restrict__ dst) {
+// Copy a canonical row-major bf16 matrix W[N, K] into stream order as IEEE half.  One thread per 16-byte piece.
+__global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K, uint16_t* __restrict__ dst,
+                                   uint32_t* __restrict__ range_flag) {
   const size_t piece = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t n_piece = (size_t)N * K / 8;
   if (piece >= n_piece) return;
@@ -52,23 +56,33 @@ __global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K,
   const int nb = (int)(tile / ksteps);
   const int i = lane & 15, g = lane >> 4;
   const uint4 v = *reinterpret_cast<const uint4*>(w + (size_t)(nb * 16 + i) * K + ks * 32 + g * 8);
-  *reinterpret_cast<uint4*>(dst + piece * 8) = v;
+  const uint32_t in[4] = {v.x, v.y, v.z, v.w};
+  uint32_t o[4];
+  bool bad = false;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float lo = __uint_as_float(in[e] << 16), hi = __uint_as_float(in[e] & 0xFFFF0000u);
+    bad |= !(fabsf(lo) <= 65504.f) || !(fabsf(hi) <= 65504.f);  // also true for NaN
+    const _Float16 hl = (_Float16)lo, hh = (_Float16)hi;         // round to nearest even
+    o[e] = (uint32_t)__builtin_bit_cast(uint16_t, hl) | ((uint32_t)__builtin_bit_cast(uint16_t, hh) << 16);
+  }
+  *reinterpret_cast<uint4*>(dst + piece * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+  if (bad) atomicOr(range_flag, 1u);
 }
 
 template <int MB, int NB>
-__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
+__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(min_waves_for(MB, NB))))
+void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
                                                                  const uint16_t* __restrict__ xt, int M, int N,
                                                                  int K, int groups_per_split, int n_big,
                                                                  float* __restrict__ out) {
-  constexpr int kKSC = ksc_for(MB);
-  constexpr int kTiles = 2 * MB * kKSC;  // X tiles per chunk: (hi, lo) x row blocks x k-steps
+  constexpr int kTiles = MB * kKSC;  // X tiles per chunk: row blocks x k-steps
   __shared__ __attribute__((aligned(16))) uint16_t xs[2][kTiles * 512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n_blocks = N >> 4, ksteps = K >> 5, n_chunks = ksteps / kKSC;
   const int c_begin = blockIdx.y * groups_per_split * (kGroup / kKSC);
   int c_end = c_begin + groups_per_split * (kGroup / kKSC);
   if (c_end > n_chunks) c_end = n_chunks;
-  const size_t plane = (size_t)MB * 16 * K;  // elements between the hi and the lo plane
 
   // This workgroup's share of the output row blocks.  The first n_big workgroups take a full pass of
   // 4 * NB blocks each; a remainder goes to later workgroups in half-size pieces.
@@ -101,22 +115,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
 #pragma unroll
     for (int m = 0; m < MB; ++m) acc[b][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // 16-byte pieces of X per chunk, order [plane][mb][s][lane]; kTiles is a multiple of 4, so every
+  // 16-byte pieces of X per chunk, order [mb][s][lane]; kTiles is a multiple of 4, so every
   // thread moves exactly kXPer pieces (no tail predicate: the loads issue back to back).
   constexpr int kXPer = kTiles * 64 / kGemmThreads;
   static_assert((kTiles * 64) % kGemmThreads == 0, "X chunk must split evenly over the workgroup");
   constexpr int kStages = 3;  // weight-tile register sets: two chunks are in flight while one is multiplied
   u32x4 xreg[kXPer];
-  bf16x8 areg[kStages][NB][kKSC];
+  f16x8 areg[kStages][NB][kKSC];
 
   auto load_x = [&](int c) {
 #pragma unroll
     for (int p = 0; p < kXPer; ++p) {
       const int piece = threadIdx.x + p * kGemmThreads;
-      const int pm = piece / (kKSC * 64), rest = piece - pm * (kKSC * 64);  // pm = plane * MB + mb
-      const int pl = pm / MB, mb = pm - pl * MB;
-      xreg[p] = *reinterpret_cast<const u32x4*>(xt + pl * plane + ((size_t)mb * ksteps + (size_t)c * kKSC) * 512 +
-                                                rest * 8);
+      const int mb = piece / (kKSC * 64), rest = piece - mb * (kKSC * 64);
+      xreg[p] = *reinterpret_cast<const u32x4*>(xt + ((size_t)mb * ksteps + (size_t)c * kKSC) * 512 + rest * 8);
     }
   };
   auto store_x = [&](int buf) {
@@ -129,23 +141,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const uint16_t*
     for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int s = 0; s < kKSC; ++s)
-        areg[set][b][s] = *reinterpret_cast<const bf16x8*>(wrow[b] + ((size_t)c * kKSC + s) * 512);
+        areg[set][b][s] = *reinterpret_cast<const f16x8*>(wrow[b] + ((size_t)c * kKSC + s) * 512);
   };
   auto compute = [&](auto set, int buf) {
 #pragma unroll
     for (int s = 0; s < kKSC; ++s) {
+      f16x8 bx[MB];
 #pragma unroll
-      for (int pl = 0; pl < 2; ++pl) {
-        bf16x8 bx[MB];
+      for (int m = 0; m < MB; ++m)
+        bx[m] = *reinterpret_cast<const f16x8*>(&xs[buf][((m * kKSC + s) * 64 + lane) * 8]);
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int m = 0; m < MB; ++m)
-          bx[m] = *reinterpret_cast<const bf16x8*>(&xs[buf][(((pl * MB + m) * kKSC + s) * 64 + lane) * 8]);
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-          for (int m = 0; m < MB; ++m)
-            acc[b][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[set][b][s], bx[m], acc[b][m], 0, 0, 0);
-      }
+          acc[b][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(areg[set][b][s], bx[m], acc[b][m], 0, 0, 0);
     }
   };
   // One pipeline step for chunk c (weights in register set SET, X in LDS buffer buf).  X(c + 1) was
@@ -253,12 +262,12 @@ int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, 
 
 }  // namespace
 
-int launch_pack_weight(const void* w, int N, int K, void* dst, hipStream_t st) {
+int launch_pack_weight(const void* w, int N, int K, void* dst, uint32_t* range_flag, hipStream_t st) {
   DS_REQUIRE((N & 15) == 0 && (K & 127) == 0, DS_E_SHAPE,
              "bf16 matrix [%d, %d]: rows must be a multiple of 16 and columns of 128", N, K);
   const size_t n_piece = (size_t)N * K / 8;
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n_piece + 255) / 256)), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(w), N, K, static_cast<uint16_t*>(dst));
+                     static_cast<const uint16_t*>(w), N, K, static_cast<uint16_t*>(dst), range_flag);
   DS_LAUNCH_CHECK("pack_weight_kernel");
   return DS_OK;
 }

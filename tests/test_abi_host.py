@@ -81,7 +81,7 @@ def test_bad_arguments_are_rejected_on_the_host_before_any_launch():
     assert ds.ds_cps_workspace_bytes(1, 32, 8) == (32 * 729 * 4 + 255) // 256 * 256
     # model configuration
     cfg = ds.ModelCfgC(1, 3584, 28, 4, 128, 18944, 152064, 1e6, 1e-6, ds.DS_BF16, 4096)
-    assert ds.ds_model_packed_bytes(cfg) == (233046016 + 544997376) * 2
+    assert ds.ds_model_packed_bytes(cfg) == (233046016 + 544997376) * 2 + 256   # + weight-range flag
     assert ds.ds_kv_bytes(cfg) == 4 * 4096 * 128 * 2
     assert ds.ds_workspace_bytes(cfg, 33) > 33 * 152064 * 4
     bad = ds.ModelCfgC(1, 3584, 28, 5, 128, 18944, 152064, 1e6, 1e-6, ds.DS_BF16, 4096)
