@@ -27,7 +27,7 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return s;
 }
 
-constexpr int kMaxPlanes = 8;  // split-K planes summed per element
+constexpr int kMaxPlanes = 10;  // split-K planes summed per element (gemm_bf16_splits never exceeds it)
 
 // Token and rotary arguments of the first kernel of a forward (FROM_EMBED).
 struct Prologue {
@@ -207,6 +207,7 @@ int launch_embed_norm(const int32_t* src, int n_real, int32_t fill, int vocab, i
 template <typename T>
 int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
                     float eps, void* h, float* rm_out, int rm_row0, hipStream_t st) {
+  DS_REQUIRE(n_part >= 0 && n_part <= kMaxPlanes, DS_E_SHAPE, "norm: %d partial planes, at most %d", n_part, kMaxPlanes);
   if (d >= 2048)
     hipLaunchKernelGGL((norm_kernel<T, false, 1024>), dim3(rows), dim3(1024), 0, st, Prologue{}, (const T*)nullptr, x,
                        part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, rm_row0);
