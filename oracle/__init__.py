@@ -16,7 +16,10 @@ implementation in primitive PyTorch CPU ops; RoPE shift invariance; GQA == MHA w
 replicated heads; mask-row symmetry; causality; softmax mass == 1 and top-M == stable
 full sort; hand-made mass-pruning rows; brute-force enumeration of all lattice paths and
 a Viterbi DP for the path search; both forms of the accepted-length formula; hand traces
-of the draft-length controller.  Parity unpinned: the beam path for beams narrower than
+of the draft-length controller; refinement with one step == the single-pass draft, update-set sizes
+and order checked against an independent sort; stochastic verification against the exact output
+distribution it must reproduce (enumerated over a uniform grid on a tiny vocabulary) and numpy's
+searchsorted for the inverse CDF.  Parity unpinned: the beam path for beams narrower than
 exhaustive is fixed only by the step-by-step reading of the search procedure.
 """
-from . import model, lattice, cps, accept, adl, round  # noqa: F401
+from . import model, lattice, cps, accept, adl, round, refine, sample  # noqa: F401

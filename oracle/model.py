@@ -140,15 +140,23 @@ def prefill(cfg, w, cache: KVCache, tokens, use_rope: bool = True) -> np.ndarray
     return lm_head(w, y[-1:])[0]
 
 
-def draft_block(cfg, w, cache: KVCache, pending, k_draft: int, use_rope: bool = True) -> np.ndarray:
-    """One drafter pass (S = 1): rows = pending real tokens, then k_draft [MASK] tokens.
+def draft_block(cfg, w, cache: KVCache, pending, k_draft: int, use_rope: bool = True,
+                block_tokens=None) -> np.ndarray:
+    """One drafter pass: rows = pending real tokens, then the k_draft block positions.
 
-    Commits only the pending rows.  Returns y of the mask rows, [k_draft, d_model] float64.
-    The hidden state at mask row i yields the distribution of the token at that position.
+    With block_tokens None every block position holds [MASK] (the single pass of S = 1, and the first
+    pass of a refinement); otherwise block_tokens gives the current draft y^(s-1) of the refinement
+    update (already fixed tokens, [MASK] elsewhere).  Block rows see the whole block either way.
+    Commits only the pending rows.  Returns y of the block rows, [k_draft, d_model] float64.
+    The hidden state at block row i yields the distribution of the token at that position.
     """
     pending = np.asarray(pending, dtype=np.int64)
     n_pend = pending.shape[0]
-    tokens = np.concatenate([pending, np.full(k_draft, cfg.mask_id, dtype=np.int64)])
+    if block_tokens is None:
+        block_tokens = np.full(k_draft, cfg.mask_id, dtype=np.int64)
+    block_tokens = np.asarray(block_tokens, dtype=np.int64)
+    assert block_tokens.shape == (k_draft,)
+    tokens = np.concatenate([pending, block_tokens])
     sees_all = np.arange(n_pend + k_draft) >= n_pend
     y = decoder_rows(cfg, w, cache, tokens, sees_all, n_pend, use_rope)
     return y[n_pend:]
