@@ -178,6 +178,45 @@ int ds_verify_block(ds_model* verifier, const int32_t* block, int m, const int32
                     int32_t eos_id, int32_t* n_accept, int32_t* next_token, int32_t* argmax,
                     int32_t* eos_accepted, float* logits_out, void* ws, size_t ws_bytes, void* stream);
 
+/* Stochastic block verification (Sec. 2 "Parallel verification": acceptance probability
+ * alpha_i = min(1, p(y_i) / q(y_i)), residual resampling; Sec. 2 left-to-right proxy q^L2R: with a single
+ * drafter pass every in-block position is [MASK], so the drafter row of block position i IS the proxy).
+ * Stand-alone form on given logits (all [dev]): p_logits float[m + 1, vocab] verifier rows (row r scores the
+ * token after block[r]), q_logits float[m, vocab] drafter rows of the path positions, block int32[m + 1],
+ * path_len int32 or NULL (as in ds_verify_block), u float[m + 1]: u[i] < alpha_i accepts draft token i + 1,
+ * u[m] drives the one draw.  After the accepted prefix of length L the next token is drawn by inverse CDF in
+ * vocabulary order (smallest v whose cumulative weight exceeds u[m] * total) from max(p_L - q_L, 0) after a
+ * rejection, from p_L after full acceptance (also when the residual is empty).  float32 arithmetic, fixed
+ * summation order; the caller owns the random stream.  Outputs [dev]: n_accept, next_token, eos_accepted
+ * int32[1], alpha float[m].  ws: ds_sample_workspace_bytes(m) bytes.  0 <= m < DS_MAX_ROWS. */
+int ds_sample_workspace_bytes(int m, size_t* bytes);
+int ds_accept_stochastic(const float* p_logits, const float* q_logits, int m, int vocab, const int32_t* block,
+                         const int32_t* path_len, const float* u, int32_t eos_id, int32_t* n_accept,
+                         int32_t* next_token, int32_t* eos_accepted, float* alpha, void* ws, size_t ws_bytes,
+                         void* stream);
+/* The verifier pass of ds_verify_block followed by ds_accept_stochastic on its logits (same KV rules: nothing
+ * is committed).  q_logits [dev] float[m, vocab]: the drafter's logits of block positions 1..m (what
+ * ds_lm_head wrote for the draft block).  The model workspace `ws` also holds the sampling scratch. */
+int ds_verify_block_stochastic(ds_model* verifier, const int32_t* block, int m, const int32_t* path_len,
+                               const float* q_logits, const float* u, int32_t eos_id, int32_t* n_accept,
+                               int32_t* next_token, int32_t* eos_accepted, float* alpha, float* logits_out,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/* Multi-pass refinement of the draft block (Sec. 2 "Inference (iterative refinement)", refinement update
+ * equation; S > 1 in Sec. 4).  ds_draft_block_tokens is ds_draft_block with explicit block contents:
+ * block_tokens [dev] int32[K] holds the current draft (fixed tokens, mask_id where still masked); every block
+ * row still sees the whole block.  ds_refine_select is the update: among the positions still holding mask_id,
+ * the n_update with the largest top-1 log-probability cand_logp[i, 0] (ties: lower position) are fixed to
+ * cand_id[i, 0] in block_tokens, and their rows of the pass lattice (cand_*, eos_logp, lse: as written by
+ * ds_build_lattice for this pass) are copied to the out_* lattice, which after the last pass is the lattice the
+ * path search runs on.  1 <= K <= 256, 1 <= M_max <= DS_MAX_TOPM, 0 <= n_update. */
+int ds_draft_block_tokens(ds_model* drafter, const int32_t* pending, int n_pend, const int32_t* block_tokens,
+                          int K, float* hidden_out, void* ws, size_t ws_bytes, void* stream);
+int ds_refine_select(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
+                     const float* eos_logp, const float* lse, int K, int M_max, int n_update, int32_t mask_id,
+                     int32_t* block_tokens, int32_t* out_cand_id, float* out_cand_logp, int32_t* out_cand_cnt,
+                     float* out_eos_logp, float* out_lse, void* stream);
+
 /* Step 4 tail, adaptive draft length (Sec. 3.3: generation-length signal, moving averages,
  * controller).  Pure host code in double precision.  first_eos: 1-based index of the first EOS in the
  * raw draft (per-position top-1 before the search), 0 if none.  Averages start at 0 (Alg. 1 init). */

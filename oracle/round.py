@@ -10,7 +10,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import accept, adl, cps, lattice, model
+from . import accept, adl, cps, lattice, model, refine, sample
 
 
 class SpecState:
@@ -25,27 +25,46 @@ class SpecState:
 
 
 def spec_round(st: SpecState, k_draft: int, m_max: int, tau: float, beam: int, lam: float,
-               table, log2_size: int, forced_path=None) -> dict:
-    """One round.  `forced_path` (tests only) replaces the searched path before verification."""
+               table, log2_size: int, forced_path=None, refine_steps: int = 1, uniforms=None) -> dict:
+    """One round.  `forced_path` (tests only) replaces the searched path before verification.
+
+    refine_steps > 1: the drafter refines the block over several passes and the lattice is frozen row by row
+    (refinement update equation).  uniforms (float [k_draft + 1]): verify with the stochastic acceptance rule,
+    u[i] deciding draft token i + 1 and u[k_draft] driving the replacement / bonus draw; needs the single-pass
+    draft, whose rows are the left-to-right proxy's distributions.
+    """
     eos_id = st.dcfg.eos_id
     ctx = st.tokens[-2:]
-    hidden = model.draft_block(st.dcfg, st.dw, st.dcache, st.pending, k_draft)
-    d_logits = model.lm_head(st.dw, hidden)
-    lat = lattice.build_lattice(d_logits, m_max, tau, eos_id)
+    hidden = d_logits = None
+    if refine_steps > 1:
+        assert uniforms is None
+        lat, _, _ = refine.refine_block(st.dcfg, st.dw, st.dcache, st.pending, k_draft, refine_steps, m_max, tau,
+                                        eos_id)
+    else:
+        hidden = model.draft_block(st.dcfg, st.dw, st.dcache, st.pending, k_draft)
+        d_logits = model.lm_head(st.dw, hidden)
+        lat = lattice.build_lattice(d_logits, m_max, tau, eos_id)
     path, score, _ = cps.cps_path(lat, 0, k_draft, beam, lam, table, log2_size, ctx, eos_id)
     if forced_path is not None:
         path = [int(t) for t in forced_path]
     block = [st.tokens[-1]] + path
     old_len = st.vcache.length
     v_logits = model.verify_logits(st.vcfg, st.vw, st.vcache, block)
-    n_acc, nxt, am, eos = accept.verify_greedy(v_logits, np.asarray(path), eos_id)
+    alpha = None
+    if uniforms is None:
+        n_acc, nxt, am, eos = accept.verify_greedy(v_logits, np.asarray(path), eos_id)
+    else:
+        am = accept.greedy_argmax(v_logits)
+        n_acc, nxt, eos, alpha = sample.verify_stochastic(v_logits, d_logits[:len(path)], np.asarray(path),
+                                                          np.asarray(uniforms)[:len(path)],
+                                                          float(np.asarray(uniforms)[k_draft]), eos_id)
     st.vcache.truncate(old_len + 1 + n_acc)
     committed = path[:n_acc] + [nxt]
     st.tokens += committed
     st.pending = committed
     return {"hidden": hidden, "d_logits": d_logits, "lattice": lat, "path": path, "score": score,
             "v_logits": v_logits, "argmax": am, "n_accept": n_acc, "next_token": nxt,
-            "eos_accepted": eos, "committed": committed,
+            "eos_accepted": eos, "committed": committed, "alpha": alpha,
             "first_eos": adl.first_eos_index(lattice.raw_draft(lat), eos_id)}
 
 

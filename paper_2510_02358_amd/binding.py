@@ -23,7 +23,8 @@ EXPORTS = [
     "ds_model_create", "ds_model_destroy", "ds_model_kv_len", "ds_model_kv_set_len", "ds_prefill",
     "ds_draft_block", "ds_lm_head", "ds_lattice_workspace_bytes", "ds_build_lattice", "ds_ngram_create",
     "ds_ngram_destroy", "ds_cps_workspace_bytes", "ds_cps_path", "ds_verify_block", "ds_adl_create", "ds_adl_destroy",
-    "ds_adl_update", "ds_adl_state",
+    "ds_adl_update", "ds_adl_state", "ds_sample_workspace_bytes", "ds_accept_stochastic",
+    "ds_verify_block_stochastic", "ds_draft_block_tokens", "ds_refine_select",
 ]
 
 
@@ -89,6 +90,11 @@ def load():
     lib.ds_cps_path.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, vp, i32, vp, vp, vp, vp, sz,
                                 vp]
     lib.ds_verify_block.argtypes = [vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ds_sample_workspace_bytes.argtypes = [C.c_int, C.POINTER(sz)]
+    lib.ds_accept_stochastic.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.ds_verify_block_stochastic.argtypes = [vp, vp, C.c_int, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ds_draft_block_tokens.argtypes = [vp, vp, C.c_int, vp, C.c_int, vp, vp, sz, vp]
+    lib.ds_refine_select.argtypes = [vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.ds_adl_create.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.POINTER(vp)]
     lib.ds_adl_destroy.argtypes = [vp]
     lib.ds_adl_update.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int)]
@@ -238,6 +244,39 @@ def ds_verify_block(model: int, block, m: int, path_len, eos_id: int, n_accept, 
     _check(load().ds_verify_block(model, _ptr(block), m, _ptr(path_len), eos_id, _ptr(n_accept), _ptr(next_token),
                                   _ptr(argmax), _ptr(eos_accepted), _ptr(logits_out), _ptr(ws), _nbytes(ws),
                                   _stream(stream)))
+
+
+def ds_sample_workspace_bytes(m: int) -> int:
+    out = C.c_size_t(0)
+    _check(load().ds_sample_workspace_bytes(m, C.byref(out)))
+    return out.value
+
+
+def ds_accept_stochastic(p_logits, q_logits, m: int, vocab: int, block, path_len, u, eos_id: int, n_accept,
+                         next_token, eos_accepted, alpha, ws, stream=None) -> None:
+    _check(load().ds_accept_stochastic(_ptr(p_logits), _ptr(q_logits), m, vocab, _ptr(block), _ptr(path_len), _ptr(u),
+                                       eos_id, _ptr(n_accept), _ptr(next_token), _ptr(eos_accepted), _ptr(alpha),
+                                       _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ds_verify_block_stochastic(model: int, block, m: int, path_len, q_logits, u, eos_id: int, n_accept, next_token,
+                               eos_accepted, alpha, logits_out, ws, stream=None) -> None:
+    _check(load().ds_verify_block_stochastic(model, _ptr(block), m, _ptr(path_len), _ptr(q_logits), _ptr(u), eos_id,
+                                             _ptr(n_accept), _ptr(next_token), _ptr(eos_accepted), _ptr(alpha),
+                                             _ptr(logits_out), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ds_draft_block_tokens(model: int, pending, n_pend: int, block_tokens, k: int, hidden_out, ws, stream=None) -> None:
+    _check(load().ds_draft_block_tokens(model, _ptr(pending), n_pend, _ptr(block_tokens), k, _ptr(hidden_out),
+                                        _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ds_refine_select(cand_id, cand_logp, cand_cnt, eos_logp, lse, k: int, m_max: int, n_update: int, mask_id: int,
+                     block_tokens, out_cand_id, out_cand_logp, out_cand_cnt, out_eos_logp, out_lse,
+                     stream=None) -> None:
+    _check(load().ds_refine_select(_ptr(cand_id), _ptr(cand_logp), _ptr(cand_cnt), _ptr(eos_logp), _ptr(lse), k, m_max,
+                                   n_update, mask_id, _ptr(block_tokens), _ptr(out_cand_id), _ptr(out_cand_logp),
+                                   _ptr(out_cand_cnt), _ptr(out_eos_logp), _ptr(out_lse), _stream(stream)))
 
 
 def ds_adl_create(k_min: int, k_max: int, delta: float, rho: float) -> int:

@@ -80,11 +80,12 @@ struct Act<bf16_t> {
 };
 
 // ---- launchers implemented in k_elem.hip / k_gemm.hip / k_attn.hip --------------------------------
-// First kernel of a forward: token gather (rows past n_real are `fill`), rotary table, embedding, RMSNorm.
+// First kernel of a forward: token gather (rows past n_real read src2, or are `fill` if src2 is NULL), rotary
+// table, embedding, RMSNorm.
 template <typename T>
-int launch_embed_norm(const int32_t* src, int n_real, int32_t fill, int vocab, int pos0, int hd, double rope_base,
-                      float2* cs, const void* embed, float* x, int rows, int rows_pad, int d, const float* gain,
-                      float eps, void* h, hipStream_t st);
+int launch_embed_norm(const int32_t* src, int n_real, const int32_t* src2, int32_t fill, int vocab, int pos0, int hd,
+                      double rope_base, float2* cs, const void* embed, float* x, int rows, int rows_pad, int d,
+                      const float* gain, float eps, void* h, hipStream_t st);
 template <typename T>
 int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
                     float eps, void* h, float* rm_out, int rm_row0, hipStream_t st);

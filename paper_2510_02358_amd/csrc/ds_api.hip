@@ -110,6 +110,43 @@ int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* c
                     path_score, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
+int ds_sample_workspace_bytes(int m, size_t* bytes) {
+  DS_REQUIRE(bytes, DS_E_INVALID, "bytes is NULL");
+  DS_REQUIRE(m >= 0 && m < DS_MAX_ROWS, DS_E_SHAPE, "m %d outside [0, %d)", m, DS_MAX_ROWS);
+  *bytes = sample_ws_bytes(m);
+  return DS_OK;
+}
+
+int ds_accept_stochastic(const float* p_logits, const float* q_logits, int m, int vocab, const int32_t* block,
+                         const int32_t* path_len, const float* u, int32_t eos_id, int32_t* n_accept,
+                         int32_t* next_token, int32_t* eos_accepted, float* alpha, void* ws, size_t ws_bytes,
+                         void* stream) {
+  DS_REQUIRE(m >= 0 && m < DS_MAX_ROWS, DS_E_SHAPE, "m %d outside [0, %d)", m, DS_MAX_ROWS);
+  DS_REQUIRE(vocab >= 1, DS_E_SHAPE, "vocab %d must be positive", vocab);
+  DS_REQUIRE(p_logits && block && u && n_accept && next_token && eos_accepted && ws, DS_E_INVALID,
+             "ds_accept_stochastic: NULL pointer argument");
+  DS_REQUIRE(m == 0 || (q_logits && alpha), DS_E_INVALID, "q_logits / alpha is NULL while m > 0");
+  DS_REQUIRE(eos_id < vocab, DS_E_INVALID, "eos_id %d >= vocab %d", eos_id, vocab);
+  DS_REQUIRE((((uintptr_t)ws) & 3) == 0, DS_E_INVALID, "workspace not 4-byte aligned");
+  return launch_sample_accept(p_logits, q_logits, m, vocab, block, path_len, u, eos_id, n_accept, next_token,
+                              eos_accepted, alpha, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int ds_refine_select(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
+                     const float* eos_logp, const float* lse, int K, int M_max, int n_update, int32_t mask_id,
+                     int32_t* block_tokens, int32_t* out_cand_id, float* out_cand_logp, int32_t* out_cand_cnt,
+                     float* out_eos_logp, float* out_lse, void* stream) {
+  DS_REQUIRE(K >= 1 && K <= 256, DS_E_SHAPE, "K %d outside [1, 256]", K);
+  DS_REQUIRE(M_max >= 1 && M_max <= DS_MAX_TOPM, DS_E_SHAPE, "M_max %d outside [1, %d]", M_max, DS_MAX_TOPM);
+  DS_REQUIRE(n_update >= 0, DS_E_SHAPE, "n_update %d is negative", n_update);
+  DS_REQUIRE(cand_id && cand_logp && cand_cnt && eos_logp && lse && block_tokens && out_cand_id && out_cand_logp &&
+                 out_cand_cnt && out_eos_logp && out_lse,
+             DS_E_INVALID, "ds_refine_select: NULL pointer argument");
+  return launch_refine_select(cand_id, cand_logp, cand_cnt, eos_logp, lse, K, M_max, n_update, mask_id, block_tokens,
+                              out_cand_id, out_cand_logp, out_cand_cnt, out_eos_logp, out_lse,
+                              static_cast<hipStream_t>(stream));
+}
+
 int ds_adl_create(int k_min, int k_max, double delta, double rho, ds_adl** out) {
   DS_REQUIRE(out, DS_E_INVALID, "out is NULL");
   *out = nullptr;

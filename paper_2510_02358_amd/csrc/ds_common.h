@@ -65,4 +65,15 @@ int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* ca
                int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, hipStream_t st);
 size_t cps_ws_bytes(int batch, int K, int m_max);
 
+// ---- stochastic acceptance and refinement update (k_sample.hip) -----------------------------------
+size_t sample_ws_bytes(int m);
+int launch_sample_accept(const float* p_logits, const float* q_logits, int m, int vocab, const int32_t* block,
+                         const int32_t* path_len, const float* u, int32_t eos_id, int32_t* n_accept,
+                         int32_t* next_token, int32_t* eos_accepted, float* alpha, void* ws, size_t ws_bytes,
+                         hipStream_t st);
+int launch_refine_select(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
+                         const float* eos_logp, const float* lse, int K, int m_max, int n_update, int32_t mask_id,
+                         int32_t* block_tokens, int32_t* o_id, float* o_logp, int32_t* o_cnt, float* o_eos,
+                         float* o_lse, hipStream_t st);
+
 }  // namespace ds

@@ -32,6 +32,8 @@ struct Workspace {
   float* logits;   // [rows, vocab]
   void* scan;      // acceptance partials
   size_t scan_bytes;
+  void* sample;    // stochastic acceptance: log-sum-exp of the verifier and drafter rows
+  size_t sample_bytes;
   size_t total;
 };
 
@@ -132,6 +134,8 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
   w.logits = static_cast<float*>(take((size_t)rows * c.vocab * 4));
   w.scan_bytes = accept_ws_bytes(rows, c.vocab);
   w.scan = take(w.scan_bytes);
+  w.sample_bytes = sample_ws_bytes(rows);
+  w.sample = take(w.sample_bytes);
   w.total = off;
   return w;
 }
@@ -189,14 +193,15 @@ int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float
 // tokens, the rest are [MASK] rows.  Leaves the final-normed states of all rows in ws.y (GEMM input
 // order) and, if hidden_out is given, a row-major copy of rows >= hidden_row0 there.
 template <typename T>
-int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real, int32_t fill, int rows,
+int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real, const int32_t* src2, int32_t fill,
+                 int rows,
                  int n_causal, float* hidden_out, int hidden_row0, hipStream_t st) {
   const ds_model_cfg& c = m->cfg;
   const int rp = ceil_div(rows, 16) * 16;
   const int pos0 = m->kv_len, n_keys = pos0 + rows;
   const int d = c.d_model, hd = c.head_dim;
   int rc;
-  if ((rc = launch_embed_norm<T>(src, n_real, fill, c.vocab, pos0, hd, (double)c.rope_base, w.cs, m->embed, w.x, rows,
+  if ((rc = launch_embed_norm<T>(src, n_real, src2, fill, c.vocab, pos0, hd, (double)c.rope_base, w.cs, m->embed, w.x, rows,
                                  rp, d, m->canon[0].norm1, c.rms_eps, w.h, st)))
     return rc;
   const int n_split_att = attn_splits(c.dtype, n_keys);
@@ -230,12 +235,12 @@ int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real
   return DS_OK;
 }
 
-// src: n_real device tokens; rows past n_real are `fill` ([MASK]).
-int forward_dispatch(ds_model* m, const Workspace& w, const int32_t* src, int n_real, int32_t fill, int rows,
-                     int n_causal, float* hidden_out, int hidden_row0, hipStream_t st) {
+// src: n_real device tokens; rows past n_real read src2[r - n_real], or are `fill` ([MASK]) if src2 is NULL.
+int forward_dispatch(ds_model* m, const Workspace& w, const int32_t* src, int n_real, const int32_t* src2,
+                     int32_t fill, int rows, int n_causal, float* hidden_out, int hidden_row0, hipStream_t st) {
   return m->cfg.dtype == DS_BF16
-             ? forward_rows<bf16_t>(m, w, src, n_real, fill, rows, n_causal, hidden_out, hidden_row0, st)
-             : forward_rows<float>(m, w, src, n_real, fill, rows, n_causal, hidden_out, hidden_row0, st);
+             ? forward_rows<bf16_t>(m, w, src, n_real, src2, fill, rows, n_causal, hidden_out, hidden_row0, st)
+             : forward_rows<float>(m, w, src, n_real, src2, fill, rows, n_causal, hidden_out, hidden_row0, st);
 }
 
 int lm_head_rows(ds_model* m, const void* y_gemm_in, int rows, float* logits, hipStream_t st) {
@@ -397,7 +402,7 @@ int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, vo
   for (int done = 0; done < n; done += chunk) {
     const int rows = n - done < chunk ? n - done : chunk;
     w = carve(m->cfg, rows, ws);
-    if ((rc = forward_dispatch(m, w, tokens + done, rows, 0, rows, rows, nullptr, 0, st))) {
+    if ((rc = forward_dispatch(m, w, tokens + done, rows, nullptr, 0, rows, rows, nullptr, 0, st))) {
       m->kv_len = start_len;
       return rc;
     }
@@ -426,7 +431,7 @@ int ds_draft_block(ds_model* m, const int32_t* pending, int n_pend, int K, int32
   int rc = check_ws(m, rows, ws, ws_bytes, &w);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = forward_dispatch(m, w, pending, n_pend, mask_id, rows, n_pend, hidden_out, n_pend, st))) return rc;
+  if ((rc = forward_dispatch(m, w, pending, n_pend, nullptr, mask_id, rows, n_pend, hidden_out, n_pend, st))) return rc;
   m->kv_len += n_pend;  // mask rows are never committed
   return DS_OK;
 }
@@ -461,11 +466,53 @@ int ds_verify_block(ds_model* m, const int32_t* block, int mlen, const int32_t* 
   int rc = check_ws(m, rows, ws, ws_bytes, &w);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = forward_dispatch(m, w, block, rows, 0, rows, rows, nullptr, 0, st))) return rc;
+  if ((rc = forward_dispatch(m, w, block, rows, nullptr, 0, rows, rows, nullptr, 0, st))) return rc;
   float* logits = logits_out ? logits_out : w.logits;
   if ((rc = lm_head_rows(m, w.y, rows, logits, st))) return rc;
   return launch_argmax_accept(logits, rows, m->cfg.vocab, block, path_len, eos_id, n_accept, next_token, argmax,
                               eos_accepted, w.scan, w.scan_bytes, st);
+}
+
+int ds_draft_block_tokens(ds_model* m, const int32_t* pending, int n_pend, const int32_t* block_tokens, int K,
+                          float* hidden_out, void* ws, size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m && hidden_out && block_tokens, DS_E_INVALID, "ds_draft_block_tokens: NULL pointer argument");
+  DS_REQUIRE(n_pend >= 0 && K >= 1, DS_E_SHAPE, "need n_pend >= 0 and K >= 1 (got %d, %d)", n_pend, K);
+  DS_REQUIRE(pending || n_pend == 0, DS_E_INVALID, "pending is NULL while n_pend > 0");
+  const int rows = n_pend + K;
+  DS_REQUIRE(rows <= DS_MAX_ROWS, DS_E_SHAPE, "n_pend + K = %d exceeds %d rows", rows, DS_MAX_ROWS);
+  DS_REQUIRE(m->kv_len + rows <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d rows exceed capacity %d",
+             m->kv_len, rows, m->cfg.kv_capacity);
+  Workspace w;
+  int rc = check_ws(m, rows, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = forward_dispatch(m, w, pending, n_pend, block_tokens, 0, rows, n_pend, hidden_out, n_pend, st))) return rc;
+  m->kv_len += n_pend;  // block rows are never committed
+  return DS_OK;
+}
+
+int ds_verify_block_stochastic(ds_model* m, const int32_t* block, int mlen, const int32_t* path_len,
+                               const float* q_logits, const float* u, int32_t eos_id, int32_t* n_accept,
+                               int32_t* next_token, int32_t* eos_accepted, float* alpha, float* logits_out, void* ws,
+                               size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m && block && u && n_accept && next_token && eos_accepted, DS_E_INVALID,
+             "ds_verify_block_stochastic: NULL pointer argument");
+  DS_REQUIRE(mlen >= 0 && mlen + 1 <= DS_MAX_ROWS, DS_E_SHAPE, "m = %d: m + 1 rows outside [1, %d]", mlen,
+             DS_MAX_ROWS);
+  DS_REQUIRE(mlen == 0 || (q_logits && alpha), DS_E_INVALID, "q_logits / alpha is NULL while m > 0");
+  DS_REQUIRE(eos_id < m->cfg.vocab, DS_E_INVALID, "eos_id %d >= vocab", eos_id);
+  const int rows = mlen + 1;
+  DS_REQUIRE(m->kv_len + rows <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d rows exceed capacity %d",
+             m->kv_len, rows, m->cfg.kv_capacity);
+  Workspace w;
+  int rc = check_ws(m, rows, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = forward_dispatch(m, w, block, rows, nullptr, 0, rows, rows, nullptr, 0, st))) return rc;
+  float* logits = logits_out ? logits_out : w.logits;
+  if ((rc = lm_head_rows(m, w.y, rows, logits, st))) return rc;
+  return launch_sample_accept(logits, q_logits, mlen, m->cfg.vocab, block, path_len, u, eos_id, n_accept, next_token,
+                              eos_accepted, alpha, w.sample, w.sample_bytes, st);
 }
 
 }  // extern "C"

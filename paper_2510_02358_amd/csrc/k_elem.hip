@@ -31,7 +31,8 @@ constexpr int kMaxPlanes = 10;  // split-K planes summed per element (gemm_bf16_
 
 // Token and rotary arguments of the first kernel of a forward (FROM_EMBED).
 struct Prologue {
-  const int32_t* src;  // [n_real] real tokens, rows past n_real are `fill`; ids outside [0, vocab) read as 0
+  const int32_t* src;   // [n_real] real tokens; ids outside [0, vocab) read as 0
+  const int32_t* src2;  // tokens of the rows past n_real (row r reads src2[r - n_real]); NULL: those rows are `fill`
   int n_real, vocab;
   int32_t fill;
   int pos0, half;      // rotary table: cs[r][i] = (cos, sin)((pos0 + r) * base^(-i / half)), i < half
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, const T* __
   const int r = blockIdx.x;
   int token = 0;
   if (FROM_EMBED) {
-    token = r < pro.n_real ? pro.src[r] : pro.fill;
+    token = r < pro.n_real ? pro.src[r] : (pro.src2 ? pro.src2[r - pro.n_real] : pro.fill);
     token = (token < 0 || token >= pro.vocab) ? 0 : token;
     if ((int)threadIdx.x < pro.half) {
       const double theta = exp2(-((double)threadIdx.x / (double)pro.half) * pro.log2_base);
@@ -188,10 +189,10 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
 }  // namespace
 
 template <typename T>
-int launch_embed_norm(const int32_t* src, int n_real, int32_t fill, int vocab, int pos0, int hd, double rope_base,
-                      float2* cs, const void* embed, float* x, int rows, int rows_pad, int d, const float* gain,
-                      float eps, void* h, hipStream_t st) {
-  Prologue pro{src, n_real, vocab, fill, pos0, hd / 2, log2(rope_base), cs};
+int launch_embed_norm(const int32_t* src, int n_real, const int32_t* src2, int32_t fill, int vocab, int pos0, int hd,
+                      double rope_base, float2* cs, const void* embed, float* x, int rows, int rows_pad, int d,
+                      const float* gain, float eps, void* h, hipStream_t st) {
+  Prologue pro{src, src2, n_real, vocab, fill, pos0, hd / 2, log2(rope_base), cs};
   if (d >= 2048)
     hipLaunchKernelGGL((norm_kernel<T, true, 1024>), dim3(rows), dim3(1024), 0, st, pro, static_cast<const T*>(embed),
                        x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr,
@@ -245,8 +246,8 @@ int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, 
 }
 
 #define DS_INSTANTIATE(T)                                                                                          \
-  template int launch_embed_norm<T>(const int32_t*, int, int32_t, int, int, int, double, float2*, const void*,     \
-                                    float*, int, int, int, const float*, float, void*, hipStream_t);               \
+  template int launch_embed_norm<T>(const int32_t*, int, const int32_t*, int32_t, int, int, int, double, float2*,  \
+                                    const void*, float*, int, int, int, const float*, float, void*, hipStream_t);  \
   template int launch_add_norm<T>(float*, const float*, int, int, int, int, const float*, float, void*, float*,   \
                                   int, hipStream_t);                                                               \
   template int launch_to_gemm_input<T>(const float*, int, int, int, void*, hipStream_t);                           \

@@ -1,0 +1,226 @@
+// Two small pieces beyond the greedy single-pass round:
+//
+//  * stochastic block verification (Sec. 2, "Parallel verification": accept draft token i with
+//    probability min(1, p / q), replace the first rejected token by a draw from the residual
+//    max(p - q, 0), draw a bonus token from p after full acceptance).  The uniforms are inputs, so the
+//    kernels hold no random-number generator; the draw is an inverse-CDF walk in vocabulary order.
+//  * the update step of multi-pass refinement (Sec. 2, refinement update equation): fix the most
+//    confident still-masked positions to their arg-max token and freeze their lattice rows.
+//
+// Both are latency-sized (a few rows of the vocabulary, at most 256 block positions): plain ALU code,
+// float32 arithmetic, every sum taken in a fixed order.
+#include <limits.h>
+#include <math.h>
+
+#include "ds_common.h"
+
+namespace ds {
+namespace {
+
+constexpr int kStatThreads = 1024;
+
+// max then sum of one workgroup (same value in every thread)
+__device__ __forceinline__ float block_max(float v, float* red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  float m = red[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) m = fmaxf(m, red[w]);
+  return m;
+}
+__device__ __forceinline__ float block_sum(float v, float* red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  float s = 0.f;
+  for (int w = 0; w < (int)(blockDim.x >> 6); ++w) s += red[w];
+  return s;
+}
+
+// lse[b] = log sum exp of one logits row.  Workgroup b < n_p takes verifier row b, the others drafter row b - n_p.
+__global__ __launch_bounds__(kStatThreads) void row_lse_kernel(const float* __restrict__ p_logits, int n_p,
+                                                              const float* __restrict__ q_logits, int vocab,
+                                                              float* __restrict__ lse) {
+  __shared__ float red[kStatThreads / 64];
+  const int b = blockIdx.x;
+  const float* row = b < n_p ? p_logits + (size_t)b * vocab : q_logits + (size_t)(b - n_p) * vocab;
+  float mx = -INFINITY;
+  for (int v = threadIdx.x; v < vocab; v += kStatThreads) mx = fmaxf(mx, row[v]);
+  mx = block_max(mx, red);
+  float s = 0.f;
+  for (int v = threadIdx.x; v < vocab; v += kStatThreads) s += __expf(row[v] - mx);
+  s = block_sum(s, red);
+  if (threadIdx.x == 0) lse[b] = mx + __logf(s);
+}
+
+// One workgroup: acceptance decisions, then the inverse-CDF draw on the row after the accepted prefix.
+// lse: [m + 1] verifier rows, then [m] drafter rows.  u: [m] acceptance uniforms, then the draw's uniform.
+__global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
+    const float* __restrict__ p_logits, const float* __restrict__ q_logits, int m, int vocab,
+    const float* __restrict__ lse, const int32_t* __restrict__ block, const int32_t* __restrict__ path_len,
+    const float* __restrict__ u, int32_t eos_id, int32_t* __restrict__ n_accept, int32_t* __restrict__ next_token,
+    int32_t* __restrict__ eos_accepted, float* __restrict__ alpha_out) {
+  __shared__ float part[2][kStatThreads];
+  __shared__ int s_first, s_slice, s_last, s_eos;
+  const int t = threadIdx.x;
+  int m_eff = m;
+  if (path_len) {
+    const int pl = *path_len;
+    m_eff = pl < m ? (pl < 0 ? 0 : pl) : m;
+  }
+  if (t == 0) {
+    s_first = m_eff;
+    s_slice = INT_MAX;
+    s_last = -1;
+    s_eos = 0;
+  }
+  __syncthreads();
+  for (int i = t; i < m; i += kStatThreads) {
+    const int tok = block[i + 1];
+    float a = 0.f;
+    if (tok >= 0 && tok < vocab) {
+      const float lp = p_logits[(size_t)i * vocab + tok] - lse[i];
+      const float lq = q_logits[(size_t)i * vocab + tok] - lse[m + 1 + i];
+      a = lq <= lp ? 1.0f : __expf(lp - lq);
+    }
+    alpha_out[i] = a;
+    if (i < m_eff && !(u[i] < a)) atomicMin(&s_first, i);
+  }
+  __syncthreads();
+  const int L = s_first;  // accepted prefix length; the draw uses verifier row L
+  for (int i = t; i < L; i += kStatThreads)
+    if (eos_id >= 0 && block[i + 1] == eos_id) atomicOr(&s_eos, 1);
+
+  const float* prow = p_logits + (size_t)L * vocab;
+  const float* qrow = L < m ? q_logits + (size_t)L * vocab : nullptr;
+  const float lse_p = lse[L], lse_q = L < m ? lse[m + 1 + L] : 0.f;
+  const int len = (vocab + kStatThreads - 1) / kStatThreads;  // contiguous slice per thread
+  const int v0 = t * len, v1 = min(vocab, v0 + len);
+  bool residual = L < m_eff;
+  float total = 0.f, excl = 0.f;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    float s = 0.f;
+    for (int v = v0; v < v1; ++v) {
+      float w = __expf(prow[v] - lse_p);
+      if (residual) w = fmaxf(w - __expf(qrow[v] - lse_q), 0.f);
+      s += w;
+    }
+    // inclusive scan over the 1024 slice sums (Hillis-Steele, fixed order)
+    int cur = 0;
+    part[0][t] = s;
+    __syncthreads();
+    for (int off = 1; off < kStatThreads; off <<= 1) {
+      const float x = part[cur][t] + (t >= off ? part[cur][t - off] : 0.f);
+      part[cur ^ 1][t] = x;
+      cur ^= 1;
+      __syncthreads();
+    }
+    const float incl = part[cur][t];
+    total = part[cur][kStatThreads - 1];
+    excl = incl - s;
+    if (t > 0) excl = part[cur][t - 1];
+    __syncthreads();
+    if (!(residual && !(total > 0.f))) {
+      const float target = u[m] * total;
+      if (s > 0.f) {
+        atomicMax(&s_last, t);
+        if (incl > target) atomicMin(&s_slice, t);
+      }
+      break;
+    }
+    residual = false;  // p == q up to rounding: the residual is empty, draw from p instead
+  }
+  __syncthreads();
+  const int pick = s_slice != INT_MAX ? s_slice : s_last;  // s_last: rounding left the target past the mass
+  if (t == pick) {
+    const float target = u[m] * total;
+    float c = excl;
+    int chosen = -1, last_pos = -1;
+    for (int v = v0; v < v1; ++v) {
+      float w = __expf(prow[v] - lse_p);
+      if (residual) w = fmaxf(w - __expf(qrow[v] - lse_q), 0.f);
+      c += w;
+      if (w > 0.f) {
+        last_pos = v;
+        if (c > target) {
+          chosen = v;
+          break;
+        }
+      }
+    }
+    if (chosen < 0) chosen = last_pos;
+    *n_accept = L;
+    *next_token = chosen;
+    *eos_accepted = (s_eos || (eos_id >= 0 && chosen == eos_id)) ? 1 : 0;
+  }
+}
+
+// Refinement update: among positions whose block token is still mask_id, the n_update with the largest
+// top-1 log-probability (ties: lower position) take their arg-max token, and their lattice rows are
+// copied to the output lattice.  One workgroup, one thread per position.
+__global__ __launch_bounds__(256) void refine_select_kernel(
+    const int32_t* __restrict__ cand_id, const float* __restrict__ cand_logp, const int32_t* __restrict__ cand_cnt,
+    const float* __restrict__ eos_logp, const float* __restrict__ lse, int K, int m_max, int n_update,
+    int32_t mask_id, int32_t* __restrict__ block_tokens, int32_t* __restrict__ o_id, float* __restrict__ o_logp,
+    int32_t* __restrict__ o_cnt, float* __restrict__ o_eos, float* __restrict__ o_lse) {
+  __shared__ float conf[256];
+  __shared__ int masked[256];
+  const int i = threadIdx.x;
+  if (i < K) {
+    masked[i] = block_tokens[i] == mask_id;
+    conf[i] = cand_logp[(size_t)i * m_max];
+  }
+  __syncthreads();
+  if (i >= K || !masked[i]) return;
+  int rank = 0;
+  const float mine = conf[i];
+  for (int j = 0; j < K; ++j)
+    if (masked[j] && (conf[j] > mine || (conf[j] == mine && j < i))) ++rank;
+  if (rank >= n_update) return;
+  block_tokens[i] = cand_id[(size_t)i * m_max];
+  for (int c = 0; c < m_max; ++c) {
+    o_id[(size_t)i * m_max + c] = cand_id[(size_t)i * m_max + c];
+    o_logp[(size_t)i * m_max + c] = cand_logp[(size_t)i * m_max + c];
+  }
+  o_cnt[i] = cand_cnt[i];
+  o_eos[i] = eos_logp[i];
+  o_lse[i] = lse[i];
+}
+
+}  // namespace
+
+size_t sample_ws_bytes(int m) { return align_up((size_t)(2 * m + 1) * sizeof(float), 256); }
+
+int launch_sample_accept(const float* p_logits, const float* q_logits, int m, int vocab, const int32_t* block,
+                         const int32_t* path_len, const float* u, int32_t eos_id, int32_t* n_accept,
+                         int32_t* next_token, int32_t* eos_accepted, float* alpha, void* ws, size_t ws_bytes,
+                         hipStream_t st) {
+  DS_REQUIRE(ws_bytes >= sample_ws_bytes(m), DS_E_CAPACITY, "sampling workspace: need %zu bytes, got %zu",
+             sample_ws_bytes(m), ws_bytes);
+  float* lse = static_cast<float*>(ws);
+  hipLaunchKernelGGL(row_lse_kernel, dim3(2 * m + 1), dim3(kStatThreads), 0, st, p_logits, m + 1, q_logits, vocab,
+                     lse);
+  DS_LAUNCH_CHECK("row_lse_kernel");
+  hipLaunchKernelGGL(sample_accept_kernel, dim3(1), dim3(kStatThreads), 0, st, p_logits, q_logits, m, vocab, lse,
+                     block, path_len, u, eos_id, n_accept, next_token, eos_accepted, alpha);
+  DS_LAUNCH_CHECK("sample_accept_kernel");
+  return DS_OK;
+}
+
+int launch_refine_select(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
+                         const float* eos_logp, const float* lse, int K, int m_max, int n_update, int32_t mask_id,
+                         int32_t* block_tokens, int32_t* o_id, float* o_logp, int32_t* o_cnt, float* o_eos,
+                         float* o_lse, hipStream_t st) {
+  hipLaunchKernelGGL(refine_select_kernel, dim3(1), dim3(256), 0, st, cand_id, cand_logp, cand_cnt, eos_logp, lse, K,
+                     m_max, n_update, mask_id, block_tokens, o_id, o_logp, o_cnt, o_eos, o_lse);
+  DS_LAUNCH_CHECK("refine_select_kernel");
+  return DS_OK;
+}
+
+}  // namespace ds

@@ -80,6 +80,19 @@ class RoundParams:
     k_max: int = 64
     delta: float = 10.0
     rho: float = 0.5
+    refine_steps: int = 1  # drafter passes per round (1: the single-pass round)
+
+
+def refine_update_sizes(k: int, steps: int) -> List[int]:
+    """How many still-masked positions each refinement pass fixes: equal shares, larger ones first."""
+    sizes, left = [], k
+    for s in range(steps):
+        if left == 0:
+            break
+        n = (left + steps - s - 1) // (steps - s)
+        sizes.append(n)
+        left -= n
+    return sizes
 
 
 class SpecDecoder:
@@ -111,6 +124,16 @@ class SpecDecoder:
         self.path_score = torch.zeros(1, dtype=f32, device=DEV)
         self.result = torch.zeros(3, dtype=i32, device=DEV)               # n_accept, next_token, eos_accepted
         self.argmax = torch.empty(k_cap + 1, dtype=i32, device=DEV)
+        # multi-pass refinement: current draft y^(s) and the lattice frozen row by row
+        self.blk = torch.zeros(k_cap, dtype=i32, device=DEV)
+        self.f_cand_id = torch.empty(k_cap, m, dtype=i32, device=DEV)
+        self.f_cand_logp = torch.empty(k_cap, m, dtype=f32, device=DEV)
+        self.f_cand_cnt = torch.empty(k_cap, dtype=i32, device=DEV)
+        self.f_eos_logp = torch.empty(k_cap, dtype=f32, device=DEV)
+        self.f_lse = torch.empty(k_cap, dtype=f32, device=DEV)
+        # stochastic verification: uniforms in, acceptance probabilities out
+        self.u = torch.zeros(k_cap + 1, dtype=f32, device=DEV)
+        self.alpha = torch.zeros(k_cap, dtype=f32, device=DEV)
         self.pending_dev = torch.zeros(ds.DS_MAX_ROWS, dtype=i32, device=DEV)
         self.host = torch.empty(4 + k_cap + 1, dtype=i32).pin_memory()
         self.k_cap = k_cap
@@ -147,27 +170,48 @@ class SpecDecoder:
         self.tokens = [int(x) for x in prefix] + [first]
         self.pending = [first]
 
-    def enqueue_round(self, k: int, stream=None, inject=None) -> None:
+    def enqueue_round(self, k: int, stream=None, inject=None, uniforms=None) -> None:
         """Enqueue draft -> LM head -> lattice -> path search -> verify for the current state.  No sync.
 
         inject = (device int32 tensor, a): overwrite the first `a` searched path tokens with these tokens before
         verification and let all k block positions take part in acceptance (synthetic acceptance for benchmarks
         and tests; plain device copies).
+        uniforms = device float32 tensor [k + 1]: verify with the stochastic acceptance rule instead of greedy
+        (u[i] decides draft token i + 1, u[k] drives the replacement / bonus draw).
         """
         p = self.p
         n_pend = len(self.pending)
-        ds.ds_draft_block(self.d.handle, self.pending_dev, n_pend, k, self.mask_id, self.hidden, self.d.ws, stream)
-        ds.ds_lm_head(self.d.handle, self.hidden, k, self.d_logits, self.d.ws, stream)
-        ds.ds_build_lattice(self.d_logits, k, self.d.cfg.vocab, p.m_max, p.tau, self.eos_id, self.cand_id,
-                            self.cand_logp, self.cand_cnt, self.eos_logp, self.lse, self.lat_ws, stream)
-        ds.ds_cps_path(self.cand_id, self.cand_logp, self.cand_cnt, self.eos_logp, 1, k, p.m_max, p.beam, p.lam,
-                       self.proxy, self.ctx, self.eos_id, self.block[1:], self.path_len, self.path_score, self.cps_ws,
-                       stream)
+        vocab = self.d.cfg.vocab
+        lat = (self.cand_id, self.cand_logp, self.cand_cnt, self.eos_logp, self.lse)
+        sizes = refine_update_sizes(k, p.refine_steps)
+        if len(sizes) <= 1:
+            ds.ds_draft_block(self.d.handle, self.pending_dev, n_pend, k, self.mask_id, self.hidden, self.d.ws, stream)
+            ds.ds_lm_head(self.d.handle, self.hidden, k, self.d_logits, self.d.ws, stream)
+            ds.ds_build_lattice(self.d_logits, k, vocab, p.m_max, p.tau, self.eos_id, *lat, self.lat_ws, stream)
+        else:
+            self.blk[:k].fill_(self.mask_id)
+            final = (self.f_cand_id, self.f_cand_logp, self.f_cand_cnt, self.f_eos_logp, self.f_lse)
+            for s, n in enumerate(sizes):
+                ds.ds_draft_block_tokens(self.d.handle, self.pending_dev if s == 0 else None, n_pend if s == 0 else 0,
+                                         self.blk, k, self.hidden, self.d.ws, stream)
+                ds.ds_lm_head(self.d.handle, self.hidden, k, self.d_logits, self.d.ws, stream)
+                ds.ds_build_lattice(self.d_logits, k, vocab, p.m_max, p.tau, self.eos_id, *lat, self.lat_ws, stream)
+                ds.ds_refine_select(*lat, k, p.m_max, n, self.mask_id, self.blk, *final, stream)
+            lat = final
+        ds.ds_cps_path(lat[0], lat[1], lat[2], lat[3], 1, k, p.m_max, p.beam, p.lam, self.proxy, self.ctx, self.eos_id,
+                       self.block[1:], self.path_len, self.path_score, self.cps_ws, stream)
+        self.lat_used = lat
         if inject is not None and inject[1] > 0:
             self.block[1:1 + inject[1]].copy_(inject[0][:inject[1]], non_blocking=True)
             self.path_len.fill_(k)  # the searched path may have stopped at an EOS before the injected length
-        ds.ds_verify_block(self.v.handle, self.block, k, self.path_len, self.eos_id, self.result[0:1],
-                           self.result[1:2], self.argmax, self.result[2:3], None, self.v.ws, stream)
+        if uniforms is None:
+            ds.ds_verify_block(self.v.handle, self.block, k, self.path_len, self.eos_id, self.result[0:1],
+                               self.result[1:2], self.argmax, self.result[2:3], None, self.v.ws, stream)
+        else:
+            # the drafter rows of the path positions: with one drafter pass, the logits the lattice was built from
+            ds.ds_verify_block_stochastic(self.v.handle, self.block, k, self.path_len, self.d_logits, uniforms,
+                                          self.eos_id, self.result[0:1], self.result[1:2], self.result[2:3],
+                                          self.alpha, None, self.v.ws, stream)
 
     def stage_inputs(self) -> None:
         """Host -> device: pending tokens, last committed token, proxy context (a few ints)."""
@@ -181,13 +225,19 @@ class SpecDecoder:
         h[n + 2] = self.tokens[-1]
         self.ctx.copy_(h[n + 1:n + 3], non_blocking=True)
 
-    def round(self, k: int, inject=None) -> dict:
+    def round(self, k: int, inject=None, uniforms=None) -> dict:
         """One full round including the host read-back, KV commit and the draft-length update."""
         self.stage_inputs()
         v_len = self.v.kv_len
-        self.enqueue_round(k, inject=inject)
+        if uniforms is not None:
+            if self.p.refine_steps > 1:
+                raise ValueError("stochastic verification needs the single-pass draft (its rows are the left-to-right "
+                                 "proxy's distribution)")
+            self.u[:k + 1].copy_(uniforms if isinstance(uniforms, torch.Tensor)
+                                 else torch.from_numpy(np.asarray(uniforms, dtype=np.float32)), non_blocking=False)
+        self.enqueue_round(k, inject=inject, uniforms=self.u if uniforms is not None else None)
         res = self.result.cpu()                 # synchronises the stream
-        raw0 = self.cand_id[:k, 0].cpu().numpy()
+        raw0 = self.lat_used[0][:k, 0].cpu().numpy()
         plen = int(self.path_len.item())
         path = self.block[1:1 + plen].cpu().numpy()
         n_acc, nxt, eos = int(res[0]), int(res[1]), int(res[2])
