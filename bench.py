@@ -308,6 +308,35 @@ def main() -> int:
         "committed_stream_equals_ar_greedy": bool(lossless),
         "note": "acceptance injected from the verifier's greedy stream (geometric, mean 6); K fixed at 32"}
 
+    # Variants of the round beyond the default (same workload, same timing protocol, 20 repetitions each):
+    # S drafter passes with the confidence-ranked refinement update, and the stochastic acceptance rule.
+    def time_variant(steps, uniforms):
+        dec.p.refine_steps = steps
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for rep in range(23):
+            if rep == 3:
+                e0.record()
+            dm.set_kv_len(p0)
+            vm.set_kv_len(p0)
+            dec.enqueue_round(K_DRAFT, uniforms=uniforms)
+            dec.host[:3].copy_(dec.result, non_blocking=True)
+            torch.cuda.current_stream().synchronize()
+        e1.record()
+        torch.cuda.synchronize()
+        dec.p.refine_steps = 1
+        return e0.elapsed_time(e1) / 20.0
+
+    dec.start(prefix)
+    dec.stage_inputs()
+    dec.u[:K_DRAFT + 1].copy_(torch.from_numpy(np.random.default_rng(6).random(K_DRAFT + 1).astype(np.float32)))
+    variants = {}
+    for steps in (2, 4):
+        ms = time_variant(steps, None)
+        variants[f"refine_steps_{steps}"] = {"ms_per_round": round(ms, 4), "rounds_per_s": round(1e3 / ms, 1)}
+    ms = time_variant(1, dec.u)
+    variants["stochastic_verify"] = {"ms_per_round": round(ms, 4), "rounds_per_s": round(1e3 / ms, 1)}
+    out["variants"] = variants
+
     if not args.no_cpu_baseline:
         from oracle import round as o_round
         try:
