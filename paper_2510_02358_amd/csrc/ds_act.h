@@ -37,13 +37,30 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float f) {
   return __builtin_bit_cast(uint16_t, h);
 }
 
+// Half-precision KV cache of one head: 64-key chunks, each stored as the 16 matrix-core operand tiles
+// (1 KB, 64 lanes x 8 halfs) the attention kernel multiplies with, so that staging a chunk is a linear copy.
+//   K tile (kb, s), kb = key block of 16, s = 32-column step: lane (16 g + i) holds K[16 kb + i][32 s + 8 g .. + 7].
+//   V tile (db, t2), db = 16 output columns, t2 = 32-key half: lane (16 g + i) holds column 16 db + i of the keys
+//     32 t2 + 4 g + {0..3} and 32 t2 + 16 + 4 g + {0..3}  (the key order in which the transposed score
+//     accumulator delivers the probabilities).
+// Offsets are in elements from the head's base; pos = absolute key position, dim = column.
+__host__ __device__ static inline size_t kv_k_offset(int pos, int dim) {
+  const int c = pos >> 6, kb = (pos >> 4) & 3, i = pos & 15, s = dim >> 5, g = (dim >> 3) & 3, e = dim & 7;
+  return ((size_t)c * 16 + kb * 4 + s) * 512 + (size_t)(g * 16 + i) * 8 + e;
+}
+__host__ __device__ static inline size_t kv_v_offset(int pos, int dim) {
+  const int c = pos >> 6, t2 = (pos >> 5) & 1, r = pos & 31, g = (r & 15) >> 2, e = (r & 3) + ((r >> 4) << 2);
+  const int db = dim >> 4, i = dim & 15;
+  return ((size_t)c * 16 + db * 2 + t2) * 512 + (size_t)(g * 16 + i) * 8 + e;
+}
+
 template <typename T>
 struct Act;
 
 template <>
 struct Act<float> {
   using kv_t = float;                         // element type of q / K cache / V cache
-  static constexpr bool kTransposedV = false;
+  static constexpr bool kTiledKV = false;     // row-major [capacity][head_dim] per head
   // GEMM-input store: element (m, k) of a [rows_pad, K] activation
   __device__ static __forceinline__ void put(float* base, int m, int k, int K, float v) {
     base[(size_t)m * K + k] = v;
@@ -60,7 +77,7 @@ struct Act<float> {
 template <>
 struct Act<bf16_t> {
   using kv_t = uint16_t;                      // IEEE half bits
-  static constexpr bool kTransposedV = true;  // V cache kept as [head_dim][capacity] per head
+  static constexpr bool kTiledKV = true;      // operand-tile order, see kv_k_offset / kv_v_offset
   // GEMM-input store: element (m, k) of a [rows_pad, K] half activation in tile order (values beyond the half
   // range saturate to +-65504 instead of becoming infinite)
   __device__ static __forceinline__ uint16_t gemm_in(float v) {
@@ -106,10 +123,14 @@ int launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* 
 
 // Attention over keys [0, n_keys) of one layer's cache for `rows` query rows at positions pos0 + r.
 // Row r sees key p iff r >= n_causal (a [MASK] row) or p <= pos0 + r.
-int attn_splits(int dtype, int n_keys);
-int attn_max_splits(int dtype, int capacity);
+// part_o / part_ml hold attn_partial_rows(rows_pad) * n_q rows of head_dim / 2 floats.
+struct AttnPlan {
+  int n_split, chunks_per_split;
+};
+AttnPlan attn_plan(int dtype, int n_keys, int rows_pad, int n_q, int n_kv);
+int attn_partial_rows(int rows_pad);
 int launch_attention(int dtype, const void* q, const void* kc, const void* vc, int rows, int rows_pad, int n_causal,
-                     int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, int n_split, float* part_o,
-                     float* part_ml, void* att_out, hipStream_t st);
+                     int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, float* part_o, float* part_ml,
+                     void* att_out, hipStream_t st);
 
 }  // namespace ds

@@ -128,9 +128,9 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
   size_t gf = 0;
   widest_split_floats(c, rows, &gf);
   w.gemm_out = static_cast<float*>(take(gf * 4));
-  const int max_split = attn_max_splits(c.dtype, c.kv_capacity);
-  w.att_o = static_cast<float*>(take((size_t)max_split * c.n_q * rp * c.head_dim * 4));
-  w.att_ml = static_cast<float*>(take((size_t)max_split * c.n_q * rp * 2 * 4));
+  const size_t part_rows = (size_t)attn_partial_rows(rp) * c.n_q;  // splits x heads x padded rows
+  w.att_o = static_cast<float*>(take(part_rows * c.head_dim * 4));
+  w.att_ml = static_cast<float*>(take(part_rows * 2 * 4));
   w.logits = static_cast<float*>(take((size_t)rows * c.vocab * 4));
   w.scan_bytes = accept_ws_bytes(rows, c.vocab);
   w.scan = take(w.scan_bytes);
@@ -204,10 +204,6 @@ int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real
   if ((rc = launch_embed_norm<T>(src, n_real, src2, fill, c.vocab, pos0, hd, (double)c.rope_base, w.cs, m->embed, w.x, rows,
                                  rp, d, m->canon[0].norm1, c.rms_eps, w.h, st)))
     return rc;
-  const int n_split_att = attn_splits(c.dtype, n_keys);
-  DS_REQUIRE(n_split_att <= attn_max_splits(c.dtype, c.kv_capacity), DS_E_CAPACITY,
-             "attention partials: %d splits exceed the workspace's %d", n_split_att,
-             attn_max_splits(c.dtype, c.kv_capacity));
   for (int li = 0; li < c.n_layers; ++li) {
     const size_t layer_elems = (size_t)c.n_kv * c.kv_capacity * hd;
     char* kc = static_cast<char*>(m->kv_k) + (size_t)li * layer_elems * m->esize;
@@ -218,7 +214,7 @@ int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real
                                  st)))
       return rc;
     if ((rc = launch_attention(c.dtype, w.q, kc, vc, rows, rp, n_causal, pos0, n_keys, c.n_q, c.n_kv, hd,
-                               c.kv_capacity, n_split_att, w.att_o, w.att_ml, w.att, st)))
+                               c.kv_capacity, w.att_o, w.att_ml, w.att, st)))
       return rc;
     if ((rc = gemm<T>(m, li, 1, w.att, rows, w.gemm_out, &sp, st))) return rc;
     if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr, 0, st)))

@@ -6,13 +6,19 @@
 //
 // Half-precision kernel (bf16 models, head_dim 128; q, K, V and probabilities are IEEE half): the
 // query rows of all heads that share a KV head are packed together, so one pass over that head's
-// keys/values serves group x rows query rows; both products run on the 16x16x32 f16 matrix cores.  Scores are computed transposed, S^T = K Q^T, because the accumulator
-// layout of S^T (lane = query row, 4 consecutive keys per register quad) is already the operand
-// layout the second product P V needs: probabilities never leave registers.  For that product the
-// value cache is stored transposed ([head_dim][capacity]) so that a lane reads its keys contiguously.
-// K and V^T chunks of 64 keys are staged once per workgroup into LDS in operand order.
+// keys/values serves group x rows query rows; both products run on the 16x16x32 f16 matrix cores.
+// Scores are computed transposed, S^T = K Q^T, because the accumulator layout of S^T (lane = query
+// row, 4 consecutive keys per register quad) is already the operand layout the second product P V
+// needs: probabilities never leave registers.
 //
-// f32 kernel: plain ALU version for the float32 parity mode (any head_dim <= 128).
+// Cache layout (private to the library): per KV head the cache is a sequence of 64-key chunks, and a
+// chunk of K (and of V) is stored as the 16 matrix-core operand tiles the kernel multiplies with
+// (kv_k_offset / kv_v_offset in ds_act.h).  Staging a chunk is therefore a straight, fully coalesced
+// 16 KB + 16 KB copy into LDS; two LDS buffers alternate, so the copy of chunk c + 1 (global ->
+// registers before the math, registers -> LDS after it) overlaps the math of chunk c with one barrier
+// per chunk.
+//
+// f32 kernel: plain ALU version for the float32 parity mode (any head_dim <= 128, row-major cache).
 #include <math.h>
 
 #include "ds_act.h"
@@ -28,7 +34,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 namespace {
 
 constexpr int kChunk = 64;  // keys per staged chunk
-constexpr int kHd = 128;    // head_dim of the bf16 kernel
+constexpr int kHd = 128;    // head_dim of the half-precision kernel
+constexpr int kChunkElems = kChunk * kHd;  // halfs per chunk of K (and of V): 16 tiles x 512
 
 union Pack8 {
   f16x8 v;
@@ -38,14 +45,14 @@ union Pack8 {
 };
 
 template <int QB>
-__global__ __launch_bounds__(256) void attn_f16_kernel(const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_f16_kernel(const uint16_t* __restrict__ q,
                                                         const uint16_t* __restrict__ kc,
-                                                        const uint16_t* __restrict__ vt, int rows_pad,
+                                                        const uint16_t* __restrict__ vc, int rows, int rows_pad,
                                                         int n_causal, int pos0, int n_keys, int n_q, int n_kv,
-                                                        int cap, int chunks_per_split, float scale,
+                                                        int cap, int chunks_per_split, float scale_log2,
                                                         float* __restrict__ part_o, float* __restrict__ part_ml) {
-  __shared__ __attribute__((aligned(16))) uint16_t ks_lds[16 * 512];
-  __shared__ __attribute__((aligned(16))) uint16_t vs_lds[16 * 512];
+  __shared__ __attribute__((aligned(16))) uint16_t ks_lds[2][kChunkElems];
+  __shared__ __attribute__((aligned(16))) uint16_t vs_lds[2][kChunkElems];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 15, g = lane >> 4;
   const int split = blockIdx.x, kvh = blockIdx.y;
@@ -55,16 +62,16 @@ __global__ __launch_bounds__(256) void attn_f16_kernel(const uint16_t* __restric
   int c_end = c_begin + chunks_per_split;
   if (c_end > n_chunks) c_end = n_chunks;
 
-  int qb[QB], head[QB], rb[QB];
+  int head[QB], rb[QB], lim_min[QB], limit[QB];
   bool valid[QB];
   f16x8 bq[QB][4];
   f32x4 o[QB][8];
-  float m_run[QB], l_run[QB];
+  float m_run[QB], l_run[QB];  // running maximum in log2 units, running sum
 #pragma unroll
   for (int t = 0; t < QB; ++t) {
-    qb[t] = (blockIdx.z * 4 + wave) * QB + t;
-    valid[t] = qb[t] < n_qb;
-    const int qbc = valid[t] ? qb[t] : 0;
+    const int qb = (blockIdx.z * 4 + wave) * QB + t;
+    valid[t] = qb < n_qb;
+    const int qbc = valid[t] ? qb : 0;
     head[t] = kvh * group + qbc / rb_count;
     rb[t] = qbc % rb_count;
     const uint16_t* qh = q + (size_t)head[t] * rows_pad * kHd + (size_t)rb[t] * 4 * 512;
@@ -74,138 +81,137 @@ __global__ __launch_bounds__(256) void attn_f16_kernel(const uint16_t* __restric
     for (int d = 0; d < 8; ++d) o[t][d] = f32x4{0.f, 0.f, 0.f, 0.f};
     m_run[t] = -INFINITY;
     l_run[t] = 0.f;
+    const int r = rb[t] * 16 + j;
+    limit[t] = (r >= n_causal) ? n_keys - 1 : pos0 + r;                       // last key this lane's row sees
+    lim_min[t] = (rb[t] * 16 >= n_causal) ? n_keys - 1 : pos0 + rb[t] * 16;   // smallest limit in the row block
   }
 
   const uint16_t* kbase = kc + (size_t)kvh * cap * kHd;
-  const uint16_t* vbase = vt + (size_t)kvh * kHd * cap;
+  const uint16_t* vbase = vc + (size_t)kvh * cap * kHd;
 
-  // Staging: each thread moves 4 K pieces (16 B) and 4 V^T pieces (2 x 8 B) per chunk, global -> registers ->
-  // LDS; the registers of chunk c + 1 are filled while chunk c is multiplied.
-  u32x4 kreg[4];
-  u32x2 vreg[4][2];
+  // Staging: a chunk is 2 x 1024 pieces of 16 bytes, already in operand order; thread t moves pieces
+  // t, t + 256, t + 512, t + 768 of K and of V.
+  u32x4 kreg[4], vreg[4];
   auto load_chunk = [&](int c) {
-    const int c0 = c * kChunk;
+    const uint16_t* ksrc = kbase + (size_t)c * kChunkElems + threadIdx.x * 8;
+    const uint16_t* vsrc = vbase + (size_t)c * kChunkElems + threadIdx.x * 8;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      const int tile = wave + 4 * p;
-      {  // K tile (kb, ks): lane (16 g + i) <- K[c0 + 16 kb + i][32 ks + 8 g ..]
-        const int kb = tile >> 2, s = tile & 3;
-        int key = c0 + kb * 16 + j;
-        key = key < n_keys ? key : n_keys - 1;
-        kreg[p] = *reinterpret_cast<const u32x4*>(kbase + (size_t)key * kHd + s * 32 + g * 8);
-      }
-      {  // V^T tile (db, t2): lane (16 g + i) <- V^T[16 db + i][c0 + 32 t2 + {4g..4g+3, 16+4g..16+4g+3}]
-        const int db = tile >> 1, t2 = tile & 1;
-        const uint16_t* src = vbase + (size_t)(db * 16 + j) * cap + c0 + 32 * t2 + 4 * g;
-        vreg[p][0] = *reinterpret_cast<const u32x2*>(src);
-        vreg[p][1] = *reinterpret_cast<const u32x2*>(src + 16);
-      }
+      kreg[p] = *reinterpret_cast<const u32x4*>(ksrc + p * 2048);
+      vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + p * 2048);
     }
   };
-  auto store_chunk = [&](int c) {
+  auto store_chunk = [&](int c, int buf) {
     const int c0 = c * kChunk;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      const int tile = wave + 4 * p;
-      *reinterpret_cast<u32x4*>(&ks_lds[(tile * 64 + lane) * 8]) = kreg[p];
+      *reinterpret_cast<u32x4*>(&ks_lds[buf][(threadIdx.x + p * 256) * 8]) = kreg[p];
       Pack8 pk;
-      pk.half[0] = vreg[p][0];
-      pk.half[1] = vreg[p][1];
+      pk.q = vreg[p];
       if (c0 + kChunk > n_keys) {  // tail chunk: slots past the last key may hold anything -> zero
-        const int t2 = tile & 1;
+        const int t2 = (wave + 4 * p) & 1;  // tile index of this piece = wave + 4 p (V tile = db * 2 + t2)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int key = c0 + 32 * t2 + 4 * g + (e & 3) + ((e >> 2) << 4);
           if (key >= n_keys) pk.h[e] = 0;
         }
       }
-      *reinterpret_cast<u32x4*>(&vs_lds[(tile * 64 + lane) * 8]) = pk.q;
+      *reinterpret_cast<u32x4*>(&vs_lds[buf][(threadIdx.x + p * 256) * 8]) = pk.q;
     }
   };
 
   if (c_begin < c_end) {
     load_chunk(c_begin);
-    store_chunk(c_begin);
+    store_chunk(c_begin, 0);
   }
   __syncthreads();
-  for (int c = c_begin; c < c_end; ++c) {
+  int buf = 0;
+  for (int c = c_begin; c < c_end; ++c, buf ^= 1) {
     const int c0 = c * kChunk;
     const int c_next = c + 1 < c_end ? c + 1 : c;  // clamped: the last iteration reloads its own chunk
     load_chunk(c_next);
     __builtin_amdgcn_sched_barrier(0);
 
+    // scores: every K tile is read once and used for all QB query blocks; consecutive products go to
+    // different accumulators
+    f32x4 s4[QB][4];
 #pragma unroll
-    for (int t = 0; t < QB; ++t) {
-      if (!valid[t]) continue;
-      f32x4 s4[4];
+    for (int t = 0; t < QB; ++t)
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) s4[t][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb) {
-        s4[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const f16x8 a = *reinterpret_cast<const f16x8*>(&ks_lds[buf][((kb * 4 + s) * 64 + lane) * 8]);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const f16x8 a = *reinterpret_cast<const f16x8*>(&ks_lds[((kb * 4 + s) * 64 + lane) * 8]);
-          s4[kb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[t][s], s4[kb], 0, 0, 0);
-        }
+        for (int t = 0; t < QB; ++t)
+          s4[t][kb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[t][s], s4[t][kb], 0, 0, 0);
       }
-      // s4[kb][e] = score of key c0 + 16 kb + 4 g + e for query row 16 rb + j
-      const int r = rb[t] * 16 + j;
-      const int limit = (r >= n_causal) ? n_keys - 1 : pos0 + r;
+    // s4[t][kb][e] = score of key c0 + 16 kb + 4 g + e for query row 16 rb + j
+    Pack8 pb[QB][2];
+#pragma unroll
+    for (int t = 0; t < QB; ++t) {
+      const bool need_mask = c0 + kChunk - 1 > lim_min[t];  // same for the whole wavefront
       float mx = -INFINITY;
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int key = c0 + kb * 16 + 4 * g + e;
-          const float sv = (key <= limit && key < n_keys) ? s4[kb][e] * scale : -INFINITY;
-          s4[kb][e] = sv;
+          float sv = s4[t][kb][e] * scale_log2;
+          if (need_mask && c0 + kb * 16 + 4 * g + e > limit[t]) sv = -INFINITY;
+          s4[t][kb][e] = sv;
           mx = fmaxf(mx, sv);
         }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const float m_new = fmaxf(m_run[t], mx);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __expf(m_run[t] - m_use);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[t] - m_use);
       float psum = 0.f;
-      Pack8 pb[2];
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float p = __expf(s4[kb][e] - m_use);
+          const float p = __builtin_amdgcn_exp2f(s4[t][kb][e] - m_use);
           psum += p;
-          pb[kb >> 1].h[(kb & 1) * 4 + e] = float_to_half_bits(p);
+          pb[t][kb >> 1].h[(kb & 1) * 4 + e] = float_to_half_bits(p);
         }
       l_run[t] = l_run[t] * alpha + psum;
       m_run[t] = m_new;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {  // the running maximum moved somewhere in the wavefront
 #pragma unroll
-      for (int d = 0; d < 8; ++d) {
-        o[t][d] *= alpha;
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
-          const f16x8 a = *reinterpret_cast<const f16x8*>(&vs_lds[((d * 2 + t2) * 64 + lane) * 8]);
-          o[t][d] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pb[t2].v, o[t][d], 0, 0, 0);
-        }
+        for (int d = 0; d < 8; ++d) o[t][d] *= alpha;
       }
     }
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int d = 0; d < 8; ++d) {
+        const f16x8 a = *reinterpret_cast<const f16x8*>(&vs_lds[buf][((d * 2 + t2) * 64 + lane) * 8]);
+#pragma unroll
+        for (int t = 0; t < QB; ++t)
+          o[t][d] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pb[t][t2].v, o[t][d], 0, 0, 0);
+      }
     __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();  // every wavefront is done reading chunk c
-    store_chunk(c_next);
+    store_chunk(c_next, buf ^ 1);  // the other buffer: nobody reads it until the barrier below
     __syncthreads();
   }
 
 #pragma unroll
   for (int t = 0; t < QB; ++t) {
-    if (!valid[t]) continue;
     float l = l_run[t];
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     const int r = rb[t] * 16 + j;
+    if (!valid[t] || r >= rows) continue;  // padding rows are never merged
     const size_t row = ((size_t)split * n_q + head[t]) * rows_pad + r;
 #pragma unroll
     for (int d = 0; d < 8; ++d)
       *reinterpret_cast<float4*>(part_o + row * kHd + d * 16 + 4 * g) =
           make_float4(o[t][d][0], o[t][d][1], o[t][d][2], o[t][d][3]);
-    if (g == 0) *reinterpret_cast<float2*>(part_ml + row * 2) = make_float2(m_run[t], l);
+    // the merge works in natural-log units
+    if (g == 0) *reinterpret_cast<float2*>(part_ml + row * 2) = make_float2(m_run[t] * 0.6931471805599453f, l);
   }
 }
 
@@ -304,50 +310,68 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
   Act<T>::put(att, r, head * hd + d, n_q * hd, num / den);
 }
 
-int chunks_per_split(int dtype, int n_keys) {
-  const int n_chunks = ceil_div(n_keys, kChunk);
-  const int max_split = 16;
-  return ceil_div(n_chunks, max_split);
-}
-
 }  // namespace
 
-int attn_splits(int dtype, int n_keys) {
-  return ceil_div(ceil_div(n_keys, kChunk), chunks_per_split(dtype, n_keys));
+// Rows-equivalents of partial results the workspace holds for a call with rows_pad padded rows:
+// splits * rows_pad never exceeds it.
+int attn_partial_rows(int rows_pad) {
+  const int a = 64 * rows_pad, b = 16 * DS_MAX_ROWS;
+  return a < b ? a : b;
 }
 
-// Upper bound of attn_splits over every n_keys <= capacity (the split count is not monotone in n_keys).
-int attn_max_splits(int dtype, int capacity) {
-  const int cap_chunks = ceil_div(capacity, kChunk);
-  const int max_split = 16;
-  return cap_chunks < max_split ? cap_chunks : max_split;
+// Split plan over the key axis.  Half-precision kernel: enough splits to put about two workgroups on
+// every compute unit (workgroups = splits x KV heads x query-block groups), at least two 64-key chunks
+// per split once there are that many, at most 64 splits and never more partial rows than the workspace
+// holds.  float32 kernel: up to 16 splits.
+AttnPlan attn_plan(int dtype, int n_keys, int rows_pad, int n_q, int n_kv) {
+  const int n_chunks = ceil_div(n_keys, kChunk);
+  int max_split = 16;
+  if (dtype == DS_BF16) {
+    const int n_qb = (n_q / n_kv) * (rows_pad >> 4);
+    const int wg_base = n_kv * ceil_div(n_qb, 8);
+    max_split = ceil_div(512, wg_base);
+    const int by_chunks = n_chunks >= 2 ? n_chunks / 2 : 1;
+    const int by_ws = attn_partial_rows(rows_pad) / rows_pad;
+    if (max_split > by_chunks) max_split = by_chunks;
+    if (max_split > by_ws) max_split = by_ws;
+    if (max_split > 64) max_split = 64;
+    if (max_split < 1) max_split = 1;
+  }
+  AttnPlan p;
+  p.chunks_per_split = ceil_div(n_chunks, max_split);
+  p.n_split = ceil_div(n_chunks, p.chunks_per_split);
+  return p;
 }
 
 int launch_attention(int dtype, const void* q, const void* kc, const void* vc, int rows, int rows_pad, int n_causal,
-                     int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, int n_split, float* part_o,
-                     float* part_ml, void* att_out, hipStream_t st) {
+                     int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, float* part_o, float* part_ml,
+                     void* att_out, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)hd);
-  const int cps = chunks_per_split(dtype, n_keys);
+  const AttnPlan plan = attn_plan(dtype, n_keys, rows_pad, n_q, n_kv);
+  DS_REQUIRE(plan.n_split * rows_pad <= attn_partial_rows(rows_pad), DS_E_CAPACITY,
+             "attention partials: %d splits x %d rows exceed the workspace", plan.n_split, rows_pad);
   if (dtype == DS_BF16) {
     DS_REQUIRE(hd == kHd, DS_E_UNSUPPORTED, "bf16 attention needs head_dim 128 (got %d)", hd);
+    DS_REQUIRE(cap % kChunk == 0, DS_E_SHAPE, "bf16 attention needs a cache capacity that is a multiple of %d", kChunk);
     const int n_qb = (n_q / n_kv) * (rows_pad >> 4);
     constexpr int QB = 2;
-    dim3 grid(n_split, n_kv, ceil_div(n_qb, 4 * QB));
+    dim3 grid(plan.n_split, n_kv, ceil_div(n_qb, 4 * QB));
     hipLaunchKernelGGL((attn_f16_kernel<QB>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
-                       static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc), rows_pad, n_causal, pos0,
-                       n_keys, n_q, n_kv, cap, cps, scale, part_o, part_ml);
+                       static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc), rows, rows_pad, n_causal,
+                       pos0, n_keys, n_q, n_kv, cap, plan.chunks_per_split, scale * 1.4426950408889634f, part_o,
+                       part_ml);
     DS_LAUNCH_CHECK("attn_f16_kernel");
-    hipLaunchKernelGGL((attn_merge_kernel<bf16_t>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, n_split, n_q,
-                       rows_pad, hd, static_cast<bf16_t*>(att_out));
+    hipLaunchKernelGGL((attn_merge_kernel<bf16_t>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, plan.n_split,
+                       n_q, rows_pad, hd, static_cast<bf16_t*>(att_out));
     DS_LAUNCH_CHECK("attn_merge_kernel<bf16>");
   } else {
     DS_REQUIRE(hd <= 128 && (hd & 1) == 0, DS_E_UNSUPPORTED, "f32 attention needs even head_dim <= 128 (got %d)", hd);
-    hipLaunchKernelGGL(attn_f32_kernel, dim3(n_split, n_q), dim3(256), 0, st, static_cast<const float*>(q),
+    hipLaunchKernelGGL(attn_f32_kernel, dim3(plan.n_split, n_q), dim3(256), 0, st, static_cast<const float*>(q),
                        static_cast<const float*>(kc), static_cast<const float*>(vc), rows, rows_pad, n_causal, pos0,
-                       n_keys, n_q, n_kv, hd, cap, cps, scale, part_o, part_ml);
+                       n_keys, n_q, n_kv, hd, cap, plan.chunks_per_split, scale, part_o, part_ml);
     DS_LAUNCH_CHECK("attn_f32_kernel");
-    hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, n_split, n_q,
-                       rows_pad, hd, static_cast<float*>(att_out));
+    hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, plan.n_split,
+                       n_q, rows_pad, hd, static_cast<float*>(att_out));
     DS_LAUNCH_CHECK("attn_merge_kernel<f32>");
   }
   return DS_OK;

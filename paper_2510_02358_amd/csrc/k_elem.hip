@@ -148,15 +148,21 @@ __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int 
     qh[Act<T>::q_off(r, i, hd)] = Act<T>::to_kv(a);
     qh[Act<T>::q_off(r, i + half, hd)] = Act<T>::to_kv(b);
   } else if (slot < n_q + n_kv) {
-    KV* kh = kc + ((size_t)(slot - n_q) * cap + pos) * hd;
-    kh[i] = Act<T>::to_kv(a);
-    kh[i + half] = Act<T>::to_kv(b);
+    if (Act<T>::kTiledKV) {
+      KV* kh = kc + (size_t)(slot - n_q) * cap * hd;
+      kh[kv_k_offset(pos, i)] = Act<T>::to_kv(a);
+      kh[kv_k_offset(pos, i + half)] = Act<T>::to_kv(b);
+    } else {
+      KV* kh = kc + ((size_t)(slot - n_q) * cap + pos) * hd;
+      kh[i] = Act<T>::to_kv(a);
+      kh[i + half] = Act<T>::to_kv(b);
+    }
   } else {
     const int kvh = slot - n_q - n_kv;
-    if (Act<T>::kTransposedV) {
-      KV* vh = vc + (size_t)kvh * hd * cap;
-      vh[(size_t)i * cap + pos] = Act<T>::to_kv(a);
-      vh[(size_t)(i + half) * cap + pos] = Act<T>::to_kv(b);
+    if (Act<T>::kTiledKV) {
+      KV* vh = vc + (size_t)kvh * cap * hd;
+      vh[kv_v_offset(pos, i)] = Act<T>::to_kv(a);
+      vh[kv_v_offset(pos, i + half)] = Act<T>::to_kv(b);
     } else {
       KV* vh = vc + ((size_t)kvh * cap + pos) * hd;
       vh[i] = Act<T>::to_kv(a);

@@ -143,6 +143,14 @@ def test_small_bf16_two_layers_gqa():
     _round_trip(cfg, w, prefix, [9, 8, 7, 6, 5], 17, 40, kv_cap=256, seed=3)
 
 
+def test_small_bf16_long_prefix_many_key_splits():
+    """4200 cached tokens (66 key chunks: split counts beyond 16, a ragged last chunk) on the small bf16 model."""
+    cfg = SMALL_BF16
+    w = synth.make_weights(cfg, 50)
+    prefix = synth.make_prefix(cfg, 4200, 51)
+    _round_trip(cfg, w, prefix, [3, 1, 4, 1, 5, 9, 2, 6], 40, 7, kv_cap=4480, seed=52)
+
+
 def test_bf16_lm_head_is_a_plain_gemm():
     """hidden (float32 -> IEEE half, round to nearest) x W^T with float32 accumulation: element by element the
     result stays within the rigorous rounding bound u * sum_k |x_k w_k| of one half rounding per activation
