@@ -127,7 +127,7 @@ int launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* 
 struct AttnPlan {
   int n_split, chunks_per_split;
 };
-AttnPlan attn_plan(int dtype, int n_keys, int rows_pad, int n_q, int n_kv);
+AttnPlan attn_plan(int dtype, int cap, int n_keys);
 int attn_partial_rows(int rows_pad);
 int launch_attention(int dtype, const void* q, const void* kc, const void* vc, int rows, int rows_pad, int n_causal,
                      int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, float* part_o, float* part_ml,

@@ -312,33 +312,28 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
 
 }  // namespace
 
-// Rows-equivalents of partial results the workspace holds for a call with rows_pad padded rows:
-// splits * rows_pad never exceeds it.
-int attn_partial_rows(int rows_pad) {
-  const int a = 64 * rows_pad, b = 16 * DS_MAX_ROWS;
-  return a < b ? a : b;
-}
+// Split plan over the key axis.  The split boundaries depend on the cache CAPACITY only (split s always
+// covers the same absolute key positions), never on how many keys or query rows a call has.  Masked keys
+// contribute exact zeros, empty splits merge with weight zero, and every other kernel of the forward works
+// row by row in a fixed order, so the result of a query row is bit-identical whether the row is computed
+// alone (one-token decoding) or inside a block (parallel verification): greedy verification then
+// reproduces the target's own greedy stream exactly, not just up to rounding.
+// Half-precision kernel: at most 32 splits over the capacity, at least two 64-key chunks per split.
+// float32 kernel: at most 16 splits.
+constexpr int kMaxSplitsF16 = 32, kMaxSplitsF32 = 16;
 
-// Split plan over the key axis.  Half-precision kernel: enough splits to put about two workgroups on
-// every compute unit (workgroups = splits x KV heads x query-block groups), at least two 64-key chunks
-// per split once there are that many, at most 64 splits and never more partial rows than the workspace
-// holds.  float32 kernel: up to 16 splits.
-AttnPlan attn_plan(int dtype, int n_keys, int rows_pad, int n_q, int n_kv) {
-  const int n_chunks = ceil_div(n_keys, kChunk);
-  int max_split = 16;
-  if (dtype == DS_BF16) {
-    const int n_qb = (n_q / n_kv) * (rows_pad >> 4);
-    const int wg_base = n_kv * ceil_div(n_qb, 8);
-    max_split = ceil_div(512, wg_base);
-    const int by_chunks = n_chunks >= 2 ? n_chunks / 2 : 1;
-    const int by_ws = attn_partial_rows(rows_pad) / rows_pad;
-    if (max_split > by_chunks) max_split = by_chunks;
-    if (max_split > by_ws) max_split = by_ws;
-    if (max_split > 64) max_split = 64;
-    if (max_split < 1) max_split = 1;
-  }
+// Rows-equivalents of partial results the workspace holds for a call with rows_pad padded rows.
+int attn_partial_rows(int rows_pad) { return kMaxSplitsF16 * rows_pad; }
+
+AttnPlan attn_plan(int dtype, int cap, int n_keys) {
+  const int cap_chunks = ceil_div(cap, kChunk), n_chunks = ceil_div(n_keys, kChunk);
   AttnPlan p;
-  p.chunks_per_split = ceil_div(n_chunks, max_split);
+  if (dtype == DS_BF16) {
+    p.chunks_per_split = ceil_div(cap_chunks, kMaxSplitsF16);
+    if (p.chunks_per_split < 2) p.chunks_per_split = 2;
+  } else {
+    p.chunks_per_split = ceil_div(cap_chunks, kMaxSplitsF32);
+  }
   p.n_split = ceil_div(n_chunks, p.chunks_per_split);
   return p;
 }
@@ -347,7 +342,8 @@ int launch_attention(int dtype, const void* q, const void* kc, const void* vc, i
                      int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, float* part_o, float* part_ml,
                      void* att_out, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)hd);
-  const AttnPlan plan = attn_plan(dtype, n_keys, rows_pad, n_q, n_kv);
+  DS_REQUIRE(n_keys >= 1 && n_keys <= cap, DS_E_CAPACITY, "attention: %d keys exceed the cache capacity %d", n_keys, cap);
+  const AttnPlan plan = attn_plan(dtype, cap, n_keys);
   DS_REQUIRE(plan.n_split * rows_pad <= attn_partial_rows(rows_pad), DS_E_CAPACITY,
              "attention partials: %d splits x %d rows exceed the workspace", plan.n_split, rows_pad);
   if (dtype == DS_BF16) {

@@ -151,6 +151,30 @@ def test_small_bf16_long_prefix_many_key_splits():
     _round_trip(cfg, w, prefix, [3, 1, 4, 1, 5, 9, 2, 6], 40, 7, kv_cap=4480, seed=52)
 
 
+@pytest.mark.parametrize("cfg_name", ["f32", "bf16"])
+def test_block_verification_is_bit_identical_to_one_token_decoding(cfg_name):
+    """A row's logits do not depend on which other rows share the call: verifying m + 1 rows at once gives, bit
+    for bit, the logits of decoding the same tokens one row at a time (so greedy verification reproduces the
+    target's own greedy stream exactly).  Prefix lengths straddle chunk and split boundaries."""
+    cfg = synth.CFG_TINY if cfg_name == "f32" else SMALL_BF16
+    w = synth.make_weights(cfg, 60)
+    rng = np.random.default_rng(61)
+    gm = gu.GpuModel(cfg, w, 1024)
+    try:
+        for n_prefix, m in ((120, 9), (250, 20), (511, 33), (700, 70)):
+            prefix = synth.make_prefix(cfg, n_prefix, 62 + n_prefix)
+            block = rng.integers(0, cfg.n_plain_tokens, m + 1).astype(np.int32)
+            gm.set_kv_len(0)
+            gm.prefill(prefix, want_logits=False)
+            whole = gm.verify(block)["logits"]
+            for r in range(m + 1):
+                gm.set_kv_len(n_prefix + r)               # rows 0 .. r-1 were written by the previous steps
+                one = gm.verify(block[r:r + 1])["logits"]
+                assert np.array_equal(one[0], whole[r]), (n_prefix, r)
+    finally:
+        gm.close()
+
+
 def test_bf16_lm_head_is_a_plain_gemm():
     """hidden (float32 -> IEEE half, round to nearest) x W^T with float32 accumulation: element by element the
     result stays within the rigorous rounding bound u * sum_k |x_k w_k| of one half rounding per activation
