@@ -121,7 +121,10 @@ int ds_draft_block(ds_model* drafter, const int32_t* pending, int n_pend, int K,
                    float* hidden_out, void* ws, size_t ws_bytes, void* stream);
 
 /* logits[rows, vocab] = hidden[rows, d_model] times the LM head (all [dev] float32; DS_BF16 models round
- * each hidden value to IEEE half and accumulate the half x half products in float32). */
+ * each hidden value to IEEE half and accumulate the half x half products in float32).
+ * hidden == NULL: multiply the block rows of the draft pass (ds_draft_block / ds_draft_block_tokens) that was the
+ * last forward on this model and this workspace, rows == its K; the result is bit-identical to passing that
+ * call's hidden_out, without converting it again.  Any other state fails with DS_E_INVALID. */
 int ds_lm_head(ds_model* m, const float* hidden, int rows, float* logits, void* ws, size_t ws_bytes,
                void* stream);
 

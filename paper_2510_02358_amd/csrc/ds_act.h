@@ -105,7 +105,7 @@ int launch_embed_norm(const int32_t* src, int n_real, const int32_t* src2, int32
                       const float* gain, float eps, void* h, hipStream_t st);
 template <typename T>
 int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
-                    float eps, void* h, float* rm_out, int rm_row0, hipStream_t st);
+                    float eps, void* h, float* rm_out, void* h_tail, int rm_row0, hipStream_t st);
 template <typename T>
 int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* dst, hipStream_t st);
 template <typename T>

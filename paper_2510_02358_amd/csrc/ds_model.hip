@@ -26,6 +26,7 @@ struct Workspace {
   void* att;       // GEMM input, n_q*hd columns
   void* act;       // GEMM input, d_ffn columns
   void* y;         // GEMM input, d columns (final-normed rows)
+  void* y_tail;    // GEMM input, d columns: the final-normed rows from hidden_row0 on, re-based to row 0
   float* gemm_out; // split-K planes of the widest projection
   float* att_o;    // attention partials
   float* att_ml;
@@ -49,6 +50,10 @@ struct ds_model {
   void *kv_k, *kv_v;
   int kv_len;
   size_t esize;
+  // what the last draft pass left behind for ds_lm_head(hidden = NULL): the block rows as a GEMM input
+  const void* tail_ptr = nullptr;
+  const void* tail_ws = nullptr;
+  int tail_rows = 0;
 };
 
 namespace {
@@ -125,6 +130,7 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
   w.att = take((size_t)rp * c.n_q * c.head_dim * es);
   w.act = take((size_t)rp * c.d_ffn * es);
   w.y = take((size_t)rp * c.d_model * es);
+  w.y_tail = take((size_t)rp * c.d_model * es);
   size_t gf = 0;
   widest_split_floats(c, rows, &gf);
   w.gemm_out = static_cast<float*>(take(gf * 4));
@@ -217,7 +223,7 @@ int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real
                                c.kv_capacity, w.att_o, w.att_ml, w.att, st)))
       return rc;
     if ((rc = gemm<T>(m, li, 1, w.att, rows, w.gemm_out, &sp, st))) return rc;
-    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr, 0, st)))
+    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr, nullptr, 0, st)))
       return rc;
     if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st))) return rc;
     if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, rp, c.d_ffn, w.act, st))) return rc;
@@ -225,7 +231,8 @@ int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real
     const bool last = li + 1 == c.n_layers;
     const float* gain = last ? m->final_norm : m->canon[li + 1].norm1;
     if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, gain, c.rms_eps, last ? w.y : w.h,
-                                 last ? hidden_out : nullptr, hidden_row0, st)))
+                                 last ? hidden_out : nullptr, (last && hidden_out) ? w.y_tail : nullptr,
+                                 hidden_row0, st)))
       return rc;
   }
   return DS_OK;
@@ -234,6 +241,7 @@ int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real
 // src: n_real device tokens; rows past n_real read src2[r - n_real], or are `fill` ([MASK]) if src2 is NULL.
 int forward_dispatch(ds_model* m, const Workspace& w, const int32_t* src, int n_real, const int32_t* src2,
                      int32_t fill, int rows, int n_causal, float* hidden_out, int hidden_row0, hipStream_t st) {
+  m->tail_ptr = nullptr;  // any forward overwrites the workspace
   return m->cfg.dtype == DS_BF16
              ? forward_rows<bf16_t>(m, w, src, n_real, src2, fill, rows, n_causal, hidden_out, hidden_row0, st)
              : forward_rows<float>(m, w, src, n_real, src2, fill, rows, n_causal, hidden_out, hidden_row0, st);
@@ -428,17 +436,25 @@ int ds_draft_block(ds_model* m, const int32_t* pending, int n_pend, int K, int32
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if ((rc = forward_dispatch(m, w, pending, n_pend, nullptr, mask_id, rows, n_pend, hidden_out, n_pend, st))) return rc;
+  m->tail_ptr = w.y_tail;
+  m->tail_ws = ws;
+  m->tail_rows = K;
   m->kv_len += n_pend;  // mask rows are never committed
   return DS_OK;
 }
 
 int ds_lm_head(ds_model* m, const float* hidden, int rows, float* logits, void* ws, size_t ws_bytes, void* stream) {
-  DS_REQUIRE(m && hidden && logits, DS_E_INVALID, "ds_lm_head: NULL pointer argument");
+  DS_REQUIRE(m && logits, DS_E_INVALID, "ds_lm_head: NULL pointer argument");
   DS_REQUIRE(rows >= 1 && rows <= DS_MAX_ROWS, DS_E_SHAPE, "rows %d outside [1, %d]", rows, DS_MAX_ROWS);
   Workspace w;
   int rc = check_ws(m, rows, ws, ws_bytes, &w);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!hidden) {  // the block rows of the last draft pass, still in the workspace as a GEMM input
+    DS_REQUIRE(m->tail_ptr && m->tail_ws == ws && m->tail_rows == rows, DS_E_INVALID,
+               "ds_lm_head(hidden = NULL) must directly follow a draft pass of %d block rows on this workspace", rows);
+    return lm_head_rows(m, m->tail_ptr, rows, logits, st);
+  }
   if (m->cfg.dtype == DS_BF16) {
     const int rp = ceil_div(rows, 16) * 16;
     if ((rc = launch_to_gemm_input<bf16_t>(hidden, rows, rp, m->cfg.d_model, w.y, st))) return rc;
@@ -483,6 +499,9 @@ int ds_draft_block_tokens(ds_model* m, const int32_t* pending, int n_pend, const
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if ((rc = forward_dispatch(m, w, pending, n_pend, block_tokens, 0, rows, n_pend, hidden_out, n_pend, st))) return rc;
+  m->tail_ptr = w.y_tail;
+  m->tail_ws = ws;
+  m->tail_rows = K;
   m->kv_len += n_pend;  // block rows are never committed
   return DS_OK;
 }

@@ -43,7 +43,8 @@ struct Prologue {
 // x[r] = E[tok[r]] or x[r] + sum of split-K planes ; h[r] = rmsnorm(x[r]) * gain, written as GEMM input.
 // FROM_EMBED: start from the embedding row (and fill this row of the rotary table, angles in double so
 // that long contexts stay exact), else from the float32 residual x plus `n_part` planes.
-// rm_out (optional): row-major float32 copy of rows >= rm_row0 (the boundary's hidden_out).
+// rm_out (optional): row-major float32 copy of rows >= rm_row0 (the boundary's hidden_out); h_tail (optional):
+// the same rows once more as a GEMM input that starts at row rm_row0 (what the LM head multiplies).
 // One workgroup per row (1024 threads for wide models so that every load of the row is issued at once),
 // four consecutive columns per thread and step (d_model % 4 == 0); the planes
 // are summed in index order, all loads of a step issued before the first add.
@@ -52,7 +53,8 @@ __global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, const T* __
                                                    float* __restrict__ x, const float* __restrict__ part,
                                                    int n_part, int rows, int rows_pad, int d,
                                                    const float* __restrict__ gain, float eps, T* __restrict__ h,
-                                                   float* __restrict__ rm_out, int rm_row0) {
+                                                   float* __restrict__ rm_out, T* __restrict__ h_tail,
+                                                   int rm_row0) {
   constexpr int kMaxVec = 8192 / (4 * THREADS);  // float4 groups per thread (d_model <= 8192)
   __shared__ float red[THREADS / 64];
   const int r = blockIdx.x;
@@ -105,6 +107,7 @@ __global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, const T* __
       const float4 y = make_float4(v[i].x * inv * gn.x, v[i].y * inv * gn.y, v[i].z * inv * gn.z, v[i].w * inv * gn.w);
       Act<T>::put4(h, r, c, d, y);
       if (rm_out && r >= rm_row0) *reinterpret_cast<float4*>(rm_out + (size_t)(r - rm_row0) * d + c) = y;
+      if (h_tail && r >= rm_row0) Act<T>::put4(h_tail, r - rm_row0, c, d, y);
     }
   }
 }
@@ -202,25 +205,27 @@ int launch_embed_norm(const int32_t* src, int n_real, const int32_t* src2, int32
   if (d >= 2048)
     hipLaunchKernelGGL((norm_kernel<T, true, 1024>), dim3(rows), dim3(1024), 0, st, pro, static_cast<const T*>(embed),
                        x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr,
-                       0);
+                       (T*)nullptr, 0);
   else
     hipLaunchKernelGGL((norm_kernel<T, true, 256>), dim3(rows), dim3(256), 0, st, pro, static_cast<const T*>(embed),
                        x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr,
-                       0);
+                       (T*)nullptr, 0);
   DS_LAUNCH_CHECK("norm_kernel<embed>");
   return DS_OK;
 }
 
 template <typename T>
 int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
-                    float eps, void* h, float* rm_out, int rm_row0, hipStream_t st) {
+                    float eps, void* h, float* rm_out, void* h_tail, int rm_row0, hipStream_t st) {
   DS_REQUIRE(n_part >= 0 && n_part <= kMaxPlanes, DS_E_SHAPE, "norm: %d partial planes, at most %d", n_part, kMaxPlanes);
   if (d >= 2048)
     hipLaunchKernelGGL((norm_kernel<T, false, 1024>), dim3(rows), dim3(1024), 0, st, Prologue{}, (const T*)nullptr, x,
-                       part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, rm_row0);
+                       part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, static_cast<T*>(h_tail),
+                       rm_row0);
   else
     hipLaunchKernelGGL((norm_kernel<T, false, 256>), dim3(rows), dim3(256), 0, st, Prologue{}, (const T*)nullptr, x,
-                       part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, rm_row0);
+                       part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, static_cast<T*>(h_tail),
+                       rm_row0);
   DS_LAUNCH_CHECK("norm_kernel<add>");
   return DS_OK;
 }
@@ -255,7 +260,7 @@ int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, 
   template int launch_embed_norm<T>(const int32_t*, int, const int32_t*, int32_t, int, int, int, double, float2*,  \
                                     const void*, float*, int, int, int, const float*, float, void*, hipStream_t);  \
   template int launch_add_norm<T>(float*, const float*, int, int, int, int, const float*, float, void*, float*,   \
-                                  int, hipStream_t);                                                               \
+                                  void*, int, hipStream_t);                                                        \
   template int launch_to_gemm_input<T>(const float*, int, int, int, void*, hipStream_t);                           \
   template int launch_qkv_rope<T>(const float*, int, int, int, int, int, int, const float2*, int, int, void*,     \
                                   void*, void*, hipStream_t);                                                      \

@@ -186,7 +186,7 @@ class SpecDecoder:
         sizes = refine_update_sizes(k, p.refine_steps)
         if len(sizes) <= 1:
             ds.ds_draft_block(self.d.handle, self.pending_dev, n_pend, k, self.mask_id, self.hidden, self.d.ws, stream)
-            ds.ds_lm_head(self.d.handle, self.hidden, k, self.d_logits, self.d.ws, stream)
+            ds.ds_lm_head(self.d.handle, None, k, self.d_logits, self.d.ws, stream)
             ds.ds_build_lattice(self.d_logits, k, vocab, p.m_max, p.tau, self.eos_id, *lat, self.lat_ws, stream)
         else:
             self.blk[:k].fill_(self.mask_id)
@@ -194,7 +194,7 @@ class SpecDecoder:
             for s, n in enumerate(sizes):
                 ds.ds_draft_block_tokens(self.d.handle, self.pending_dev if s == 0 else None, n_pend if s == 0 else 0,
                                          self.blk, k, self.hidden, self.d.ws, stream)
-                ds.ds_lm_head(self.d.handle, self.hidden, k, self.d_logits, self.d.ws, stream)
+                ds.ds_lm_head(self.d.handle, None, k, self.d_logits, self.d.ws, stream)
                 ds.ds_build_lattice(self.d_logits, k, vocab, p.m_max, p.tau, self.eos_id, *lat, self.lat_ws, stream)
                 ds.ds_refine_select(*lat, k, p.m_max, n, self.mask_id, self.blk, *final, stream)
             lat = final

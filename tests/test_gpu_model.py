@@ -175,6 +175,33 @@ def test_block_verification_is_bit_identical_to_one_token_decoding(cfg_name):
         gm.close()
 
 
+@pytest.mark.parametrize("cfg_name", ["f32", "bf16"])
+def test_lm_head_on_the_rows_the_draft_pass_left_behind(cfg_name):
+    """ds_lm_head(hidden = NULL) right after a draft pass == ds_lm_head on that pass's hidden_out, bit for bit;
+    in any other state the call is refused."""
+    cfg = synth.CFG_TINY if cfg_name == "f32" else SMALL_BF16
+    w = synth.make_weights(cfg, 70)
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        gm.prefill(synth.make_prefix(cfg, 90, 71), want_logits=False)
+        for pending, k in (([5], 8), ([1, 2, 3], 21), ([], 33)):
+            hid = gm.draft(pending, k)
+            direct = torch.empty(k, cfg.vocab, dtype=torch.float32, device=gu.DEV)
+            ds.ds_lm_head(gm.handle, None, k, direct, gm.ws)
+            with pytest.raises(ds.DsError) as e:
+                ds.ds_lm_head(gm.handle, None, k + 1, direct, gm.ws)     # wrong row count
+            assert e.value.code == ds.DS_E_INVALID
+            via_hidden = gm.lm_head(hid)
+            torch.cuda.synchronize()
+            assert torch.equal(direct, via_hidden)
+        gm.verify(np.array([1, 2, 3], np.int32))                          # another forward: the rows are gone
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_lm_head(gm.handle, None, 33, direct, gm.ws)
+        assert e.value.code == ds.DS_E_INVALID
+    finally:
+        gm.close()
+
+
 def test_bf16_lm_head_is_a_plain_gemm():
     """hidden (float32 -> IEEE half, round to nearest) x W^T with float32 accumulation: element by element the
     result stays within the rigorous rounding bound u * sum_k |x_k w_k| of one half rounding per activation
