@@ -44,31 +44,54 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 }
 
 // lse[b] = log sum exp of one logits row.  Workgroup b < n_p takes verifier row b, the others drafter row b - n_p.
+// Two passes over the row (max, then sum of exp), 16 bytes per lane and load where the row allows it.
 __global__ __launch_bounds__(kStatThreads) void row_lse_kernel(const float* __restrict__ p_logits, int n_p,
                                                               const float* __restrict__ q_logits, int vocab,
                                                               float* __restrict__ lse) {
   __shared__ float red[kStatThreads / 64];
   const int b = blockIdx.x;
   const float* row = b < n_p ? p_logits + (size_t)b * vocab : q_logits + (size_t)(b - n_p) * vocab;
+  const bool vec = (vocab & 3) == 0 && (((uintptr_t)row) & 15) == 0;
+  const int n4 = vec ? vocab >> 2 : 0;
   float mx = -INFINITY;
-  for (int v = threadIdx.x; v < vocab; v += kStatThreads) mx = fmaxf(mx, row[v]);
+  for (int i = threadIdx.x; i < n4; i += kStatThreads) {
+    const float4 v = reinterpret_cast<const float4*>(row)[i];
+    mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+  }
+  for (int v = n4 * 4 + threadIdx.x; v < vocab; v += kStatThreads) mx = fmaxf(mx, row[v]);
   mx = block_max(mx, red);
   float s = 0.f;
-  for (int v = threadIdx.x; v < vocab; v += kStatThreads) s += __expf(row[v] - mx);
+  for (int i = threadIdx.x; i < n4; i += kStatThreads) {
+    const float4 v = reinterpret_cast<const float4*>(row)[i];
+    s += (__expf(v.x - mx) + __expf(v.y - mx)) + (__expf(v.z - mx) + __expf(v.w - mx));
+  }
+  for (int v = n4 * 4 + threadIdx.x; v < vocab; v += kStatThreads) s += __expf(row[v] - mx);
   s = block_sum(s, red);
   if (threadIdx.x == 0) lse[b] = mx + __logf(s);
 }
 
 // One workgroup: acceptance decisions, then the inverse-CDF draw on the row after the accepted prefix.
 // lse: [m + 1] verifier rows, then [m] drafter rows.  u: [m] acceptance uniforms, then the draw's uniform.
+//
+// The draw walks the vocabulary in order, hierarchically and with coalesced loads: the row is cut into segments
+// of kSeg = 4096 consecutive tokens; inside a segment thread t owns the 4 consecutive tokens 4 t .. 4 t + 3.
+//   pass 1: every segment's total weight (per-wavefront sums in lane order, the 16 wavefront sums in order);
+//   the segment whose cumulative total first exceeds the target is found by one thread walking the <= 64 totals;
+//   pass 2: inside that segment, an inclusive scan of the 1024 four-token sums finds the owning thread, which
+//   walks its 4 tokens.  Every sum has a fixed order, so the drawn token is reproducible bit for bit.
+constexpr int kSeg = 4 * kStatThreads;
+constexpr int kMaxSeg = 64;  // vocabularies up to 262144 tokens
+
 __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
     const float* __restrict__ p_logits, const float* __restrict__ q_logits, int m, int vocab,
     const float* __restrict__ lse, const int32_t* __restrict__ block, const int32_t* __restrict__ path_len,
     const float* __restrict__ u, int32_t eos_id, int32_t* __restrict__ n_accept, int32_t* __restrict__ next_token,
     int32_t* __restrict__ eos_accepted, float* __restrict__ alpha_out) {
+  __shared__ float wave_sum[kMaxSeg][kStatThreads / 64];
   __shared__ float part[2][kStatThreads];
-  __shared__ int s_first, s_slice, s_last, s_eos;
-  const int t = threadIdx.x;
+  __shared__ float s_before, s_target, s_total;
+  __shared__ int s_first, s_seg, s_thread, s_last, s_eos;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   int m_eff = m;
   if (path_len) {
     const int pl = *path_len;
@@ -76,8 +99,6 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
   }
   if (t == 0) {
     s_first = m_eff;
-    s_slice = INT_MAX;
-    s_last = -1;
     s_eos = 0;
   }
   __syncthreads();
@@ -100,64 +121,132 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
   const float* prow = p_logits + (size_t)L * vocab;
   const float* qrow = L < m ? q_logits + (size_t)L * vocab : nullptr;
   const float lse_p = lse[L], lse_q = L < m ? lse[m + 1 + L] : 0.f;
-  const int len = (vocab + kStatThreads - 1) / kStatThreads;  // contiguous slice per thread
-  const int v0 = t * len, v1 = min(vocab, v0 + len);
+  const int n_seg = (vocab + kSeg - 1) / kSeg;
   bool residual = L < m_eff;
-  float total = 0.f, excl = 0.f;
-  for (int attempt = 0; attempt < 2; ++attempt) {
-    float s = 0.f;
-    for (int v = v0; v < v1; ++v) {
-      float w = __expf(prow[v] - lse_p);
-      if (residual) w = fmaxf(w - __expf(qrow[v] - lse_q), 0.f);
-      s += w;
-    }
-    // inclusive scan over the 1024 slice sums (Hillis-Steele, fixed order)
-    int cur = 0;
-    part[0][t] = s;
-    __syncthreads();
-    for (int off = 1; off < kStatThreads; off <<= 1) {
-      const float x = part[cur][t] + (t >= off ? part[cur][t - off] : 0.f);
-      part[cur ^ 1][t] = x;
-      cur ^= 1;
-      __syncthreads();
-    }
-    const float incl = part[cur][t];
-    total = part[cur][kStatThreads - 1];
-    excl = incl - s;
-    if (t > 0) excl = part[cur][t - 1];
-    __syncthreads();
-    if (!(residual && !(total > 0.f))) {
-      const float target = u[m] * total;
-      if (s > 0.f) {
-        atomicMax(&s_last, t);
-        if (incl > target) atomicMin(&s_slice, t);
+  const bool vec = (vocab & 3) == 0 && (((uintptr_t)prow) & 15) == 0 && (!qrow || (((uintptr_t)qrow) & 15) == 0);
+
+  // the four weights thread t owns in segment seg (0 beyond the vocabulary)
+  auto weights4 = [&](int seg, float w[4]) {
+    const int v0 = seg * kSeg + 4 * t;
+    float pv[4], qv[4];
+    if (vec && v0 + 3 < vocab) {
+      const float4 a = *reinterpret_cast<const float4*>(prow + v0);
+      pv[0] = a.x; pv[1] = a.y; pv[2] = a.z; pv[3] = a.w;
+      if (residual) {
+        const float4 c = *reinterpret_cast<const float4*>(qrow + v0);
+        qv[0] = c.x; qv[1] = c.y; qv[2] = c.z; qv[3] = c.w;
       }
-      break;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        pv[e] = v0 + e < vocab ? prow[v0 + e] : -INFINITY;
+        qv[e] = (residual && v0 + e < vocab) ? qrow[v0 + e] : -INFINITY;
+      }
     }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float x = __expf(pv[e] - lse_p);  // exp(-inf) = 0 beyond the vocabulary
+      if (residual) x = fmaxf(x - __expf(qv[e] - lse_q), 0.f);
+      w[e] = x;
+    }
+  };
+
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    // pass 1: segment totals
+    for (int seg = 0; seg < n_seg; ++seg) {
+      float w[4];
+      weights4(seg, w);
+      float s = (w[0] + w[1]) + (w[2] + w[3]);
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+      if (lane == 0) wave_sum[seg][wave] = s;
+    }
+    __syncthreads();
+    if (t == 0) {
+      float total = 0.f;
+      for (int seg = 0; seg < n_seg; ++seg) {
+        float ss = 0.f;
+        for (int w2 = 0; w2 < kStatThreads / 64; ++w2) ss += wave_sum[seg][w2];
+        wave_sum[seg][0] = ss;  // segment total
+        total += ss;
+      }
+      const float target = u[m] * total;
+      float c = 0.f;
+      int pick = -1, last_pos = -1;
+      for (int seg = 0; seg < n_seg; ++seg) {
+        const float ss = wave_sum[seg][0];
+        if (ss > 0.f) {
+          last_pos = seg;
+          if (c + ss > target) {
+            pick = seg;
+            break;
+          }
+        }
+        c += ss;
+      }
+      if (pick < 0) {  // rounding left the target past the mass: the last segment that has any
+        pick = last_pos;
+        c = 0.f;
+        for (int seg = 0; seg < pick; ++seg) c += wave_sum[seg][0];
+      }
+      s_total = total;
+      s_target = target;
+      s_before = c;
+      s_seg = pick;
+    }
+    __syncthreads();
+    if (!(residual && !(s_total > 0.f))) break;
     residual = false;  // p == q up to rounding: the residual is empty, draw from p instead
+    __syncthreads();
+  }
+
+  // pass 2: inside the chosen segment
+  const int seg = s_seg;
+  float w[4] = {0.f, 0.f, 0.f, 0.f};
+  if (seg >= 0) weights4(seg, w);
+  const float s4 = (w[0] + w[1]) + (w[2] + w[3]);
+  int cur = 0;
+  part[0][t] = s4;
+  if (t == 0) {
+    s_thread = INT_MAX;
+    s_last = -1;
   }
   __syncthreads();
-  const int pick = s_slice != INT_MAX ? s_slice : s_last;  // s_last: rounding left the target past the mass
-  if (t == pick) {
-    const float target = u[m] * total;
+  for (int off = 1; off < kStatThreads; off <<= 1) {
+    const float x = part[cur][t] + (t >= off ? part[cur][t - off] : 0.f);
+    part[cur ^ 1][t] = x;
+    cur ^= 1;
+    __syncthreads();
+  }
+  const float incl = s_before + part[cur][t];
+  const float excl = s_before + (t > 0 ? part[cur][t - 1] : 0.f);
+  if (s4 > 0.f) {
+    atomicMax(&s_last, t);
+    if (incl > s_target) atomicMin(&s_thread, t);
+  }
+  __syncthreads();
+  const int pick_t = s_thread != INT_MAX ? s_thread : s_last;
+  if (pick_t < 0 && t == 0) {  // no positive weight anywhere (NaN logits are a caller error): defined outputs
+    *n_accept = L;
+    *next_token = 0;
+    *eos_accepted = s_eos;
+  }
+  if (t == pick_t) {
     float c = excl;
     int chosen = -1, last_pos = -1;
-    for (int v = v0; v < v1; ++v) {
-      float w = __expf(prow[v] - lse_p);
-      if (residual) w = fmaxf(w - __expf(qrow[v] - lse_q), 0.f);
-      c += w;
-      if (w > 0.f) {
-        last_pos = v;
-        if (c > target) {
-          chosen = v;
-          break;
-        }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      c += w[e];
+      if (w[e] > 0.f) {
+        last_pos = e;
+        if (chosen < 0 && c > s_target) chosen = e;
       }
     }
     if (chosen < 0) chosen = last_pos;
+    const int tok = seg * kSeg + 4 * t + chosen;
     *n_accept = L;
-    *next_token = chosen;
-    *eos_accepted = (s_eos || (eos_id >= 0 && chosen == eos_id)) ? 1 : 0;
+    *next_token = tok;
+    *eos_accepted = (s_eos || (eos_id >= 0 && tok == eos_id)) ? 1 : 0;
   }
 }
 
@@ -203,6 +292,8 @@ int launch_sample_accept(const float* p_logits, const float* q_logits, int m, in
                          hipStream_t st) {
   DS_REQUIRE(ws_bytes >= sample_ws_bytes(m), DS_E_CAPACITY, "sampling workspace: need %zu bytes, got %zu",
              sample_ws_bytes(m), ws_bytes);
+  DS_REQUIRE(vocab <= kSeg * kMaxSeg, DS_E_UNSUPPORTED, "stochastic acceptance: vocab %d exceeds %d", vocab,
+             kSeg * kMaxSeg);
   float* lse = static_cast<float*>(ws);
   hipLaunchKernelGGL(row_lse_kernel, dim3(2 * m + 1), dim3(kStatThreads), 0, st, p_logits, m + 1, q_logits, vocab,
                      lse);
