@@ -119,7 +119,9 @@ class SpecDecoder:
         self.lat_ws = torch.empty(ds.ds_lattice_workspace_bytes(k_cap, vocab, m), dtype=torch.uint8, device=DEV)
         self.cps_ws = torch.empty(ds.ds_cps_workspace_bytes(1, k_cap, m), dtype=torch.uint8, device=DEV)
         self.block = torch.zeros(k_cap + 1, dtype=i32, device=DEV)       # [last token, path...]
-        self.ctx = torch.zeros(2, dtype=i32, device=DEV)
+        # proxy context (2 ints) and pending tokens share one staging tensor: one host -> device copy per round
+        self.stage = torch.zeros(2 + ds.DS_MAX_ROWS, dtype=i32, device=DEV)
+        self.ctx = self.stage[0:2]
         self.path_len = torch.zeros(1, dtype=i32, device=DEV)
         self.path_score = torch.zeros(1, dtype=f32, device=DEV)
         self.result = torch.zeros(3, dtype=i32, device=DEV)               # n_accept, next_token, eos_accepted
@@ -134,8 +136,10 @@ class SpecDecoder:
         # stochastic verification: uniforms in, acceptance probabilities out
         self.u = torch.zeros(k_cap + 1, dtype=f32, device=DEV)
         self.alpha = torch.zeros(k_cap, dtype=f32, device=DEV)
-        self.pending_dev = torch.zeros(ds.DS_MAX_ROWS, dtype=i32, device=DEV)
-        self.host = torch.empty(4 + k_cap + 1, dtype=i32).pin_memory()
+        self.pending_dev = self.stage[2:]
+        self.host = torch.empty(3 + ds.DS_MAX_ROWS, dtype=i32).pin_memory()
+        self.host_np = self.host.numpy()
+        self.host_out = torch.empty(4 + 2 * k_cap, dtype=i32).pin_memory()   # result(3), path_len, path, raw draft
         self.k_cap = k_cap
         self.tokens: List[int] = []
         self.pending: List[int] = []
@@ -214,16 +218,15 @@ class SpecDecoder:
                                           self.alpha, None, self.v.ws, stream)
 
     def stage_inputs(self) -> None:
-        """Host -> device: pending tokens, last committed token, proxy context (a few ints)."""
+        """Host -> device: proxy context, pending tokens, last committed token (a few ints, two async copies)."""
         n = len(self.pending)
-        h = self.host
-        h[:n] = torch.tensor(self.pending, dtype=torch.int32)
-        self.pending_dev[:n].copy_(h[:n], non_blocking=True)
-        h[n] = self.tokens[-1]
-        self.block[0:1].copy_(h[n:n + 1], non_blocking=True)
-        h[n + 1] = self.tokens[-2]
-        h[n + 2] = self.tokens[-1]
-        self.ctx.copy_(h[n + 1:n + 3], non_blocking=True)
+        h = self.host_np
+        h[0] = self.tokens[-2]
+        h[1] = self.tokens[-1]
+        h[2:2 + n] = self.pending
+        h[2 + n] = self.tokens[-1]
+        self.stage[:2 + n].copy_(self.host[:2 + n], non_blocking=True)
+        self.block[0:1].copy_(self.host[2 + n:3 + n], non_blocking=True)
 
     def round(self, k: int, inject=None, uniforms=None) -> dict:
         """One full round including the host read-back, KV commit and the draft-length update."""
@@ -236,11 +239,17 @@ class SpecDecoder:
             self.u[:k + 1].copy_(uniforms if isinstance(uniforms, torch.Tensor)
                                  else torch.from_numpy(np.asarray(uniforms, dtype=np.float32)), non_blocking=False)
         self.enqueue_round(k, inject=inject, uniforms=self.u if uniforms is not None else None)
-        res = self.result.cpu()                 # synchronises the stream
-        raw0 = self.lat_used[0][:k, 0].cpu().numpy()
-        plen = int(self.path_len.item())
-        path = self.block[1:1 + plen].cpu().numpy()
-        n_acc, nxt, eos = int(res[0]), int(res[1]), int(res[2])
+        # one host crossing: four small async copies into pinned memory, then a single stream sync
+        ho = self.host_out
+        ho[0:3].copy_(self.result, non_blocking=True)
+        ho[3:4].copy_(self.path_len, non_blocking=True)
+        ho[4:4 + k].copy_(self.block[1:1 + k], non_blocking=True)
+        ho[4 + self.k_cap:4 + self.k_cap + k].copy_(self.lat_used[0][:k, 0], non_blocking=True)
+        torch.cuda.current_stream().synchronize()
+        out = ho.numpy()
+        n_acc, nxt, eos, plen = int(out[0]), int(out[1]), int(out[2]), int(out[3])
+        path = out[4:4 + plen].copy()
+        raw0 = out[4 + self.k_cap:4 + self.k_cap + k]
         self.v.set_kv_len(v_len + 1 + n_acc)
         committed = [int(t) for t in path[:n_acc]] + [nxt]
         self.tokens += committed
