@@ -17,7 +17,8 @@
  *   - Ownership: the caller allocates and frees ALL device memory (weights, packed weights, KV
  *     caches, workspace, inputs, outputs) and passes raw device pointers.  The library only
  *     allocates small host structs behind the opaque handles, released by the *_destroy calls.
- *     Pointers marked [dev] are device memory, [host] host memory.
+ *     Pointers marked [dev] are device memory (any memory the GPU can address: small outputs such as the
+ *     acceptance verdict may also live in pinned, device-visible host memory), [host] host memory.
  *   - All device work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream) and the call returns without synchronising.  Outputs are device memory; the caller
  *     synchronises the stream before reading them.

@@ -124,7 +124,9 @@ class SpecDecoder:
         self.ctx = self.stage[0:2]
         self.path_len = torch.zeros(1, dtype=i32, device=DEV)
         self.path_score = torch.zeros(1, dtype=f32, device=DEV)
-        self.result = torch.zeros(3, dtype=i32, device=DEV)               # n_accept, next_token, eos_accepted
+        # n_accept, next_token, eos_accepted: pinned host memory (device-visible), so that the acceptance kernel
+        # writes the round's verdict where the host reads it after the stream sync, without a copy in between
+        self.result = torch.zeros(3, dtype=i32).pin_memory()
         self.argmax = torch.empty(k_cap + 1, dtype=i32, device=DEV)
         # multi-pass refinement: current draft y^(s) and the lattice frozen row by row
         self.blk = torch.zeros(k_cap, dtype=i32, device=DEV)
@@ -239,15 +241,15 @@ class SpecDecoder:
             self.u[:k + 1].copy_(uniforms if isinstance(uniforms, torch.Tensor)
                                  else torch.from_numpy(np.asarray(uniforms, dtype=np.float32)), non_blocking=False)
         self.enqueue_round(k, inject=inject, uniforms=self.u if uniforms is not None else None)
-        # one host crossing: four small async copies into pinned memory, then a single stream sync
+        # one host crossing: three small async copies into pinned memory, then a single stream sync
         ho = self.host_out
-        ho[0:3].copy_(self.result, non_blocking=True)
         ho[3:4].copy_(self.path_len, non_blocking=True)
         ho[4:4 + k].copy_(self.block[1:1 + k], non_blocking=True)
         ho[4 + self.k_cap:4 + self.k_cap + k].copy_(self.lat_used[0][:k, 0], non_blocking=True)
         torch.cuda.current_stream().synchronize()
         out = ho.numpy()
-        n_acc, nxt, eos, plen = int(out[0]), int(out[1]), int(out[2]), int(out[3])
+        res = self.result.numpy()
+        n_acc, nxt, eos, plen = int(res[0]), int(res[1]), int(res[2]), int(out[3])
         path = out[4:4 + plen].copy()
         raw0 = out[4 + self.k_cap:4 + self.k_cap + k]
         self.v.set_kv_len(v_len + 1 + n_acc)
