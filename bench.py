@@ -5,7 +5,7 @@ A step is one full round through the C ABI: drafter pass over 1 pending + K=32 [
 causal rows + LM head + greedy acceptance -> host read-back of the accepted length -> draft-length update.
 Inputs (weights, KV caches, proxy table) are resident in HBM before the timed region.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (the fields are described in the README).
 """
 from __future__ import annotations
 
