@@ -45,6 +45,75 @@ def traffic_from_profiles():
     return None
 
 
+def run_stress(args) -> int:
+    """cfg3: the lattice and the path search on their own (no model): float32 logits [16, K, 152064] drawn as g / T
+    (g ~ N(0, 1), one T ~ U[0.5, 2] per row), K in {8, 16, 32, 64}, top-16 lattice, beam 8.  Reports the lattice's
+    achieved GB/s against 4 bytes per logit and the path search's time."""
+    import numpy as np
+    import torch
+
+    from paper_2510_02358_amd import binding as ds
+    from paper_2510_02358_amd import synth
+    from paper_2510_02358_amd import round as rnd
+
+    vocab, batch, m_max, beam, lam = 152064, 16, 16, 8, 0.5
+    eos_id = vocab - 2
+    table = rnd.upload(synth.make_ngram_table(3))
+    proxy = ds.ds_ngram_create(table, synth.NGRAM_LOG2_SIZE)
+    res = {}
+    for k in (8, 16, 32, 64):
+        rows = batch * k
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(100 + k)
+        logits = torch.randn(rows, vocab, generator=gen, device="cuda", dtype=torch.float32)
+        logits /= torch.empty(rows, 1, device="cuda").uniform_(0.5, 2.0, generator=gen)
+        i32, f32 = torch.int32, torch.float32
+        cand_id = torch.empty(rows, m_max, dtype=i32, device="cuda")
+        cand_logp = torch.empty(rows, m_max, dtype=f32, device="cuda")
+        cand_cnt = torch.empty(rows, dtype=i32, device="cuda")
+        eos_logp = torch.empty(rows, dtype=f32, device="cuda")
+        lse = torch.empty(rows, dtype=f32, device="cuda")
+        lat_ws = torch.empty(ds.ds_lattice_workspace_bytes(rows, vocab, m_max), dtype=torch.uint8, device="cuda")
+        cps_ws = torch.empty(ds.ds_cps_workspace_bytes(batch, k, m_max), dtype=torch.uint8, device="cuda")
+        ctx = rnd.upload(synth.make_contexts(vocab, batch, 7))
+        path = torch.empty(batch, k, dtype=i32, device="cuda")
+        plen = torch.empty(batch, dtype=i32, device="cuda")
+        score = torch.empty(batch, dtype=f32, device="cuda")
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        lat_us, cps_us = [], []
+        for rep in range(12):
+            ev[0].record()
+            ds.ds_build_lattice(logits, rows, vocab, m_max, 0.8, eos_id, cand_id, cand_logp, cand_cnt, eos_logp, lse,
+                                lat_ws)
+            ev[1].record()
+            ds.ds_cps_path(cand_id, cand_logp, cand_cnt, eos_logp, batch, k, m_max, beam, lam, proxy, ctx, eos_id, path,
+                           plen, score, cps_ws)
+            ev[2].record()
+            torch.cuda.synchronize()
+            if rep >= 2:
+                lat_us.append(ev[0].elapsed_time(ev[1]) * 1e3)
+                cps_us.append(ev[1].elapsed_time(ev[2]) * 1e3)
+        lat = float(np.median(lat_us))
+        res[f"K={k}"] = {"rows": rows, "lattice_us": round(lat, 1),
+                         "lattice_GBps": round(rows * vocab * 4 / (lat * 1e-6) / 1e9, 1),
+                         "lattice_hbm_frac": round(rows * vocab * 4 / (lat * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                         "cps_us": round(float(np.median(cps_us)), 1)}
+        del logits
+    ds.ds_ngram_destroy(proxy)
+    k64 = res["K=64"]
+    out = {"metric": "lattice_GBps", "value": k64["lattice_GBps"], "unit": "GB/s", "n_gpus": 1, "steps": 10, "warmup": 2,
+           "ms_per_step": round(k64["lattice_us"] / 1e3, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "cfg3: float32 logits [16, K, 152064], K in {8, 16, 32, 64}, top-16 lattice with mass "
+                                  "pruning 0.8, beam 8, hashed 3-gram proxy"},
+           "roofline": {"bound": "hbm", "kernel": "scan_rows_kernel<softmax> + lattice_merge_kernel (K = 64)",
+                        "achieved": k64["lattice_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": k64["lattice_hbm_frac"], "traffic": None},
+           "sizes": res, "cpu_baseline": None}
+    print(json.dumps(out))
+    return 0
+
+
 def run_deep(args) -> int:
     """Full-depth pairs (extra evidence beside the default workload; weights are drawn on the device, no CPU leg).
 
@@ -140,7 +209,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["cfg1", "cfg2", "cfg4"], default="cfg1",
+    ap.add_argument("--workload", choices=["cfg1", "cfg2", "cfg3", "cfg4"], default="cfg1",
                     help="cfg1 (default): the benchmark workload.  cfg2: full 28-layer 7B-shaped drafter + verifier, "
                          "prefix 1024, draft length adapted in [4, 64] over 64 rounds.  cfg4: that drafter + 64-layer "
                          "32B-shaped verifier, prefix 16384, K=64 (both: extra evidence, no CPU leg)")
@@ -164,6 +233,8 @@ def main() -> int:
 
     ds.load()  # raises if the HIP library is missing: there is no fallback
     torch.cuda.set_device(0)
+    if args.workload == "cfg3":
+        return run_stress(args)
     if args.workload != "cfg1":
         return run_deep(args)
     cfg = synth.CFG_7B_LAYER

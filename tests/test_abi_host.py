@@ -79,6 +79,25 @@ def test_bad_arguments_are_rejected_on_the_host_before_any_launch():
     assert lib.ds_cps_path(one, one, one, one, 1, 8, 4, 17, 0.5, None, one, -1, one, one, one, None, 0, None) == ds.DS_E_SHAPE
     assert lib.ds_cps_path(one, one, one, one, 1, 8, 4, 4, 1.5, None, one, -1, one, one, one, None, 0, None) == ds.DS_E_INVALID
     assert ds.ds_cps_workspace_bytes(1, 32, 8) == (32 * 729 * 4 + 255) // 256 * 256
+    # stochastic acceptance and the refinement update
+    assert lib.ds_accept_stochastic(one, one, -1, 10, one, None, one, -1, one, one, one, one, one, 1024, None) == ds.DS_E_SHAPE
+    assert lib.ds_accept_stochastic(one, one, 144, 10, one, None, one, -1, one, one, one, one, one, 1 << 20, None) == ds.DS_E_SHAPE
+    assert lib.ds_accept_stochastic(one, None, 2, 10, one, None, one, -1, one, one, one, one, one, 1024, None) == ds.DS_E_INVALID
+    assert lib.ds_accept_stochastic(one, one, 2, 10, one, None, one, 10, one, one, one, one, one, 1024, None) == ds.DS_E_INVALID
+    assert lib.ds_accept_stochastic(one, one, 2, 10, one, None, one, -1, one, one, one, one, one, 8, None) == ds.DS_E_CAPACITY
+    assert lib.ds_accept_stochastic(one, one, 2, 300000, one, None, one, -1, one, one, one, one, one, 1024, None) == ds.DS_E_UNSUPPORTED
+    assert ds.ds_sample_workspace_bytes(32) == 256 * ((65 * 4 + 255) // 256)
+    sel = [one] * 5 + [8, 4, 3, 99] + [one] * 6 + [None]
+    assert lib.ds_refine_select(*(sel[:5] + [0] + sel[6:])) == ds.DS_E_SHAPE        # K = 0
+    assert lib.ds_refine_select(*(sel[:5] + [257] + sel[6:])) == ds.DS_E_SHAPE      # K > 256
+    assert lib.ds_refine_select(*(sel[:6] + [17] + sel[7:])) == ds.DS_E_SHAPE       # M_max > 16
+    assert lib.ds_refine_select(*(sel[:7] + [-1] + sel[8:])) == ds.DS_E_SHAPE       # n_update < 0
+    assert lib.ds_refine_select(*([None] + sel[1:])) == ds.DS_E_INVALID
+    # model-level calls refuse a NULL handle before touching anything
+    assert lib.ds_draft_block_tokens(None, None, 0, one, 4, one, one, 1 << 20, None) == ds.DS_E_INVALID
+    assert lib.ds_verify_block_stochastic(None, one, 2, None, one, one, -1, one, one, one, one, None, one, 1 << 20,
+                                          None) == ds.DS_E_INVALID
+    assert lib.ds_lm_head(None, None, 4, one, one, 1 << 20, None) == ds.DS_E_INVALID
     # model configuration
     cfg = ds.ModelCfgC(1, 3584, 28, 4, 128, 18944, 152064, 1e6, 1e-6, ds.DS_BF16, 4096)
     assert ds.ds_model_packed_bytes(cfg) == (233046016 + 544997376) * 2 + 256   # + weight-range flag
