@@ -118,57 +118,82 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
         for (int c = 0; c < 4; ++c) v[j][c] = (i0 + c < vocab) ? rowp[i0 + c] : -INFINITY;
       }
     }
-    // this lane's best of its 32 values (value descending, index ascending)
-    float loc = -INFINITY;
-    int loc_idx = INT_MAX;
-#pragma unroll
-    for (int j = 0; j < kUnroll; ++j)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int idx = base + j * (kWave * 4) + lane * 4 + c;
-        if (idx < vocab && beats(v[j][c], idx, loc, loc_idx)) {
-          loc = v[j][c];
-          loc_idx = idx;
-        }
-      }
     if (!SOFTMAX) {
+      // this lane's best of its 32 values (value descending, index ascending)
+      float loc = -INFINITY;
+      int loc_idx = INT_MAX;
+#pragma unroll
+      for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int idx = base + j * (kWave * 4) + lane * 4 + c;
+          if (idx < vocab && beats(v[j][c], idx, loc, loc_idx)) {
+            loc = v[j][c];
+            loc_idx = idx;
+          }
+        }
       if (beats(loc, loc_idx, ev, eid)) {
         ev = loc;
         eid = loc_idx;
       }
       continue;
     }
-    if (loc > run_max) {
-      run_sum *= __expf(run_max - loc);  // run_max = -inf gives 0 * 0
-      run_max = loc;
+    // this lane's largest value (positions past the vocabulary were loaded as -inf)
+    float lm = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+      lm = fmaxf(fmaxf(lm, fmaxf(v[j][0], v[j][1])), fmaxf(v[j][2], v[j][3]));
+    if (lm > run_max) {
+      run_sum *= __expf(run_max - lm);  // run_max = -inf gives 0 * 0
+      run_max = lm;
     }
     if (run_max > -INFINITY) {
+      // exp(v - run_max) as 2^(v * log2(e) - run_max * log2(e)): one fused multiply-add and one exp2 per value
+      const float nm = -run_max * 1.4426950408889634f;
       float acc = 0.f;
 #pragma unroll
       for (int j = 0; j < kUnroll; ++j)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc += __expf(v[j][c] - run_max);
+        for (int c = 0; c < 4; ++c) acc += __builtin_amdgcn_exp2f(fmaf(v[j][c], 1.4426950408889634f, nm));
       run_sum += acc;
     }
+    // top-M list.  `thr` is the value of the M-th entry (wavefront-uniform, only ever rises); nothing below
+    // it can enter the list, so a step whose lane maxima all lie below it is done, and inside a step only the
+    // values that reach it are offered (list_offer decides ties by index).
     int own = -1;  // index already in the list (skipped below)
     if (list_empty) {
       // start the list from the 64 per-lane bests in one sort; the bar is then already high
+      float loc = -INFINITY;
+      int loc_idx = INT_MAX;
+#pragma unroll
+      for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int idx = base + j * (kWave * 4) + lane * 4 + c;
+          if (idx < vocab && beats(v[j][c], idx, loc, loc_idx)) {
+            loc = v[j][c];
+            loc_idx = idx;
+          }
+        }
       ev = loc;
       eid = loc_idx;
       wave_sort_best_first(ev, eid, lane);
       own = loc_idx;
       list_empty = false;
-    } else {
-      const float thr = lane_value(ev, m_max - 1);
-      if (!__ballot(loc >= thr)) continue;
+    } else if (!__ballot(lm >= lane_value(ev, m_max - 1))) {
+      continue;
     }
+    float thr = lane_value(ev, m_max - 1);
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int idx = base + j * (kWave * 4) + lane * 4 + c;
-        const bool skip = idx >= vocab || idx == own;
-        list_offer(ev, eid, skip ? -INFINITY : v[j][c], skip ? INT_MAX : idx, m_max, lane);
+        const bool ok = idx < vocab && idx != own && v[j][c] >= thr;
+        if (__ballot(ok)) {
+          list_offer(ev, eid, ok ? v[j][c] : -INFINITY, ok ? idx : INT_MAX, m_max, lane);
+          thr = lane_value(ev, m_max - 1);
+        }
       }
   }
 
@@ -351,7 +376,7 @@ struct ScanPlan {
 
 ScanPlan plan_scan(int rows, int vocab) {
   int tiles = ceil_div(vocab, kTile);
-  int want = ceil_div(4096, rows);
+  int want = ceil_div(2048, rows);  // about 2048 workgroups: long segments once there are many rows
   int n_seg = want < 1 ? 1 : (want > tiles ? tiles : want);
   int tps = ceil_div(tiles, n_seg);
   n_seg = ceil_div(tiles, tps);
