@@ -376,7 +376,8 @@ struct ScanPlan {
 
 ScanPlan plan_scan(int rows, int vocab) {
   int tiles = ceil_div(vocab, kTile);
-  int want = ceil_div(2048, rows);  // about 2048 workgroups: long segments once there are many rows
+  // as many workgroups as are resident at once (7 wavefronts per SIMD: 1792 workgroups of 4), no second round
+  int want = 1792 / rows;
   int n_seg = want < 1 ? 1 : (want > tiles ? tiles : want);
   int tps = ceil_div(tiles, n_seg);
   n_seg = ceil_div(tiles, tps);
