@@ -57,6 +57,11 @@ size_t accept_ws_bytes(int rows, int vocab);
 int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t* block,
                          const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
                          int32_t* argmax, int32_t* eos_accepted, void* ws, size_t ws_bytes, hipStream_t st);
+// The same verdict from per-tile (largest logit, column) records written by the LM-head product's epilogue
+// (layout and size: gemm_bf16_best_bytes, plus DS_MAX_ROWS words behind it).
+int launch_tiles_accept(float2* tile_best, int rows, int n_tiles, const int32_t* block,
+                        const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
+                        int32_t* argmax, int32_t* eos_accepted, hipStream_t st);
 
 // ---- path search (k_cps.hip) --------------------------------------------------------------------
 int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,

@@ -33,6 +33,7 @@ struct Workspace {
   float* logits;   // [rows, vocab]
   void* scan;      // acceptance partials
   size_t scan_bytes;
+  float2* tile_best; // per LM-head column tile and row: largest logit and its column (greedy acceptance)
   void* sample;    // stochastic acceptance: log-sum-exp of the verifier and drafter rows
   size_t sample_bytes;
   size_t total;
@@ -140,6 +141,9 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
   w.logits = static_cast<float*>(take((size_t)rows * c.vocab * 4));
   w.scan_bytes = accept_ws_bytes(rows, c.vocab);
   w.scan = take(w.scan_bytes);
+  // also holds the acceptance kernel's per-row arg-max exchange behind the counter
+  w.tile_best = static_cast<float2*>(
+      take(gemm_bf16_best_bytes(rows, c.vocab, 128) + (size_t)DS_MAX_ROWS * sizeof(int32_t)));
   w.sample_bytes = sample_ws_bytes(rows);
   w.sample = take(w.sample_bytes);
   w.total = off;
@@ -148,7 +152,7 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
 
 template <typename T>
 int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float* out, int* n_split,
-         hipStream_t st) {
+         hipStream_t st, float2* best = nullptr) {
   // which: 0 qkv, 1 o, 2 gate/up, 3 down, 4 lm head
   const ds_model_cfg& c = m->cfg;
   const int d = c.d_model, f = c.d_ffn, qo = c.n_q * c.head_dim;
@@ -170,7 +174,7 @@ int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float
     // two row blocks per wavefront where N is large (LM head, gate/up): half the X traffic per weight byte
     const int nbw = (which == 4 || which == 2) ? 2 : 1;
     *n_split = which == 4 ? 1 : gemm_bf16_splits(N, K, nbw);
-    return launch_gemm_bf16(w, x_in, rows, N, K, nbw, *n_split, out, st);
+    return launch_gemm_bf16(w, x_in, rows, N, K, nbw, *n_split, out, best, st);
   }
   *n_split = 1;
   const float* x = static_cast<const float*>(x_in);
@@ -247,10 +251,17 @@ int forward_dispatch(ds_model* m, const Workspace& w, const int32_t* src, int n_
              : forward_rows<float>(m, w, src, n_real, src2, fill, rows, n_causal, hidden_out, hidden_row0, st);
 }
 
-int lm_head_rows(ds_model* m, const void* y_gemm_in, int rows, float* logits, hipStream_t st) {
+// tile_best (bf16 path with lm_head_tile() > 0 only): also leave the per-tile arg-max records; logits may then be NULL.
+int lm_head_rows(ds_model* m, const void* y_gemm_in, int rows, float* logits, hipStream_t st,
+                 float2* tile_best = nullptr) {
   int sp = 1;
-  return m->cfg.dtype == DS_BF16 ? gemm<bf16_t>(m, 0, 4, y_gemm_in, rows, logits, &sp, st)
+  return m->cfg.dtype == DS_BF16 ? gemm<bf16_t>(m, 0, 4, y_gemm_in, rows, logits, &sp, st, tile_best)
                                  : gemm<float>(m, 0, 4, y_gemm_in, rows, logits, &sp, st);
+}
+
+// Columns per tile of the LM head's arg-max epilogue, 0 where the model cannot use it.
+int lm_head_tile(const ds_model* m) {
+  return m->cfg.dtype == DS_BF16 ? gemm_bf16_best_tile(m->cfg.vocab, 2, 1) : 0;
 }
 
 int check_ws(const ds_model* m, int rows, void* ws, size_t ws_bytes, Workspace* out) {
@@ -479,6 +490,12 @@ int ds_verify_block(ds_model* m, const int32_t* block, int mlen, const int32_t* 
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if ((rc = forward_dispatch(m, w, block, rows, nullptr, 0, rows, rows, nullptr, 0, st))) return rc;
+  if (const int tile = lm_head_tile(m)) {
+    // The product's epilogue reports every tile's largest logit; the logits themselves are written only if asked for.
+    if ((rc = lm_head_rows(m, w.y, rows, logits_out, st, w.tile_best))) return rc;
+    return launch_tiles_accept(w.tile_best, rows, m->cfg.vocab / tile, block, path_len, eos_id, n_accept, next_token,
+                               argmax, eos_accepted, st);
+  }
   float* logits = logits_out ? logits_out : w.logits;
   if ((rc = lm_head_rows(m, w.y, rows, logits, st))) return rc;
   return launch_argmax_accept(logits, rows, m->cfg.vocab, block, path_len, eos_id, n_accept, next_token, argmax,

@@ -24,6 +24,8 @@
 //     order (deterministic, no atomics).
 //
 // f32 path: a plain wavefront-per-output-column kernel for the float32 parity mode.
+#include <limits.h>
+#include <math.h>
 #include <type_traits>
 
 #include "ds_common.h"
@@ -70,12 +72,20 @@ __global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K,
   if (bad) atomicOr(range_flag, 1u);
 }
 
-template <int MB, int NB>
+// EPI selects the epilogue at compile time, so that the split-K layer products carry none of the LM head's code:
+//   kEpiPlanes  plain stores into this split's plane of `out`;
+//   kEpiStream  unsplit product, non-temporal stores (logits are consumed once, later);
+//   kEpiBest    unsplit product of full tiles: per-tile arg-max records into `best`, and the non-temporal stores
+//               only if `out` is not NULL.
+enum { kEpiPlanes = 0, kEpiStream = 1, kEpiBest = 2 };
+
+template <int MB, int NB, int EPI>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(min_waves_for(MB, NB))))
 void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
                                                                  const uint16_t* __restrict__ xt, int M, int N,
                                                                  int K, int groups_per_split, int n_big,
-                                                                 float* __restrict__ out) {
+                                                                 float* __restrict__ out,
+                                                                 float2* __restrict__ best) {
   constexpr int kTiles = MB * kKSC;  // X tiles per chunk: row blocks x k-steps
   __shared__ __attribute__((aligned(16))) uint16_t xs[2][kTiles * 512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -199,16 +209,74 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   }
 
   // D[i][j]: lane (16 g + j) holds rows i = 4 g .. 4 g + 3 of column j  ->  out[m = 16 mb + j][n = 16 nb + 4 g ..]
+  if (EPI != kEpiBest || out) {
 #pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    if (nb[b] >= nb_end) continue;
+    for (int b = 0; b < NB; ++b) {
+      if (nb[b] >= nb_end) continue;
+#pragma unroll
+      for (int m = 0; m < MB; ++m) {
+        const int row = m * 16 + j_out;
+        if (row < M) {
+          float* dst = out_plane + (size_t)row * N + nb[b] * 16 + g_out * 4;
+          if (EPI != kEpiPlanes) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) __builtin_nontemporal_store(acc[b][m][e], dst + e);
+          } else {
+            *reinterpret_cast<float4*>(dst) = make_float4(acc[b][m][0], acc[b][m][1], acc[b][m][2], acc[b][m][3]);
+          }
+        }
+      }
+    }
+  }
+  // The largest value of every output row inside this workgroup's 64 * NB columns and its column (ties: lower
+  // column): best[workgroup][row] = (value, column bits), MB * 16 rows per workgroup (padding rows included, so
+  // that each workgroup writes one contiguous run of whole sectors).  A row's arg-max over all columns then needs
+  // these pairs only, not the logits.  The word after the last record is the consumer's arrival counter, cleared
+  // here.
+  if (EPI == kEpiBest) {
+    float2* red = reinterpret_cast<float2*>(&xs[0][0]);  // [4 waves][MB * 16 rows]; the main loop is past its last barrier
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
-      const int row = m * 16 + j_out;
-      if (row < M) {
-        float4 v = make_float4(acc[b][m][0], acc[b][m][1], acc[b][m][2], acc[b][m][3]);
-        *reinterpret_cast<float4*>(out_plane + (size_t)row * N + nb[b] * 16 + g_out * 4) = v;
+      float bv = -INFINITY;
+      int bi = INT_MAX;
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int col = nb[b] * 16 + g_out * 4 + e;
+          const float x = acc[b][m][e];
+          if (x > bv || (x == bv && col < bi)) {
+            bv = x;
+            bi = col;
+          }
+        }
+#pragma unroll
+      for (int off = 16; off <= 32; off <<= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int oi = __shfl_xor(bi, off);
+        if (ov > bv || (ov == bv && oi < bi)) {
+          bv = ov;
+          bi = oi;
+        }
       }
+      if (g_out == 0) red[(wave * MB + m) * 16 + j_out] = make_float2(bv, __int_as_float(bi));
+    }
+    __syncthreads();
+    const int row = threadIdx.x;
+    if (blockIdx.x == 0 && row == 0) *reinterpret_cast<uint32_t*>(best + (size_t)gridDim.x * MB * 16) = 0u;
+    if (row < MB * 16) {
+      float bv = -INFINITY;
+      int bi = INT_MAX;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float2 q = red[w * MB * 16 + row];
+        const int qi = __float_as_int(q.y);
+        if (q.x > bv || (q.x == bv && qi < bi)) {
+          bv = q.x;
+          bi = qi;
+        }
+      }
+      best[(size_t)blockIdx.x * MB * 16 + row] = make_float2(bv, __int_as_float(bi));
     }
   }
   __syncthreads();  // the next pass restages X into the same LDS buffers
@@ -244,7 +312,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 
 template <int MB>
 int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, int nbw, int n_split, float* out,
-                   hipStream_t st) {
+                   float2* best, hipStream_t st) {
   const int n_groups = (K >> 5) / kGroup;
   const int gps = ceil_div(n_groups, n_split);
   // One workgroup per full pass of 4 * nbw row blocks; a remainder goes to half-size workgroups at the end.
@@ -252,10 +320,14 @@ int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, 
   const int n_big = n_blocks / full;
   const int n_small = ceil_div(n_blocks - n_big * full, half);
   dim3 grid(n_big + n_small, n_split);
-  if (nbw == 1)
-    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 1>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, n_big, out);
-  else
-    hipLaunchKernelGGL((gemm_bf16_kernel<MB, 2>), grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, n_big, out);
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, n_big, out, best);
+  };
+  if (best) go(gemm_bf16_kernel<MB, 2, kEpiBest>);  // the caller has checked nbw == 2 and n_split == 1
+  else if (n_split == 1 && nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiStream>);
+  else if (n_split == 1) go(gemm_bf16_kernel<MB, 1, kEpiStream>);
+  else if (nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiPlanes>);
+  else go(gemm_bf16_kernel<MB, 1, kEpiPlanes>);
   DS_LAUNCH_CHECK("gemm_bf16_kernel");
   return DS_OK;
 }
@@ -287,22 +359,36 @@ int gemm_bf16_splits(int N, int K, int nbw) {
   return ceil_div(n_groups, gps);
 }
 
+// Width of the column tiles the per-tile arg-max epilogue reports, or 0 if this shape cannot use it (it needs one
+// unsplit pass in which every workgroup owns a full tile).  The records take gemm_bf16_best_bytes.
+int gemm_bf16_best_tile(int N, int nbw, int n_split) {
+  const int w = 64 * nbw;
+  return (nbw == 2 && n_split == 1 && N % w == 0) ? w : 0;
+}
+
+size_t gemm_bf16_best_bytes(int rows, int N, int tile) {
+  return (size_t)(N / tile) * (ceil_div(rows, 16) * 16) * sizeof(float2) + 256;  // records, then the counter
+}
+
 int launch_gemm_bf16(const void* wp, const void* xt, int M, int N, int K, int nbw, int n_split, float* out,
-                     hipStream_t st) {
+                     float2* best, hipStream_t st) {
   DS_REQUIRE(M >= 1 && M <= DS_MAX_ROWS, DS_E_SHAPE, "GEMM rows %d outside [1, %d]", M, DS_MAX_ROWS);
   DS_REQUIRE((N & 15) == 0 && (K & 127) == 0, DS_E_SHAPE, "GEMM [%d x %d]: N %% 16 and K %% 128 must be 0", N, K);
+  DS_REQUIRE(out || best, DS_E_INVALID, "GEMM: neither an output nor a per-tile arg-max buffer");
+  DS_REQUIRE(!best || gemm_bf16_best_tile(N, nbw, n_split) > 0, DS_E_SHAPE,
+             "GEMM [%d x %d]: the per-tile arg-max needs an unsplit pass of full tiles", N, K);
   const uint16_t* w = static_cast<const uint16_t*>(wp);
   const uint16_t* x = static_cast<const uint16_t*>(xt);
   switch (ceil_div(M, 16)) {
-    case 1: return launch_bf16_mb<1>(w, x, M, N, K, nbw, n_split, out, st);
-    case 2: return launch_bf16_mb<2>(w, x, M, N, K, nbw, n_split, out, st);
-    case 3: return launch_bf16_mb<3>(w, x, M, N, K, nbw, n_split, out, st);
-    case 4: return launch_bf16_mb<4>(w, x, M, N, K, nbw, n_split, out, st);
-    case 5: return launch_bf16_mb<5>(w, x, M, N, K, nbw, n_split, out, st);
-    case 6: return launch_bf16_mb<6>(w, x, M, N, K, nbw, n_split, out, st);
-    case 7: return launch_bf16_mb<7>(w, x, M, N, K, nbw, n_split, out, st);
-    case 8: return launch_bf16_mb<8>(w, x, M, N, K, nbw, n_split, out, st);
-    default: return launch_bf16_mb<9>(w, x, M, N, K, nbw, n_split, out, st);
+    case 1: return launch_bf16_mb<1>(w, x, M, N, K, nbw, n_split, out, best, st);
+    case 2: return launch_bf16_mb<2>(w, x, M, N, K, nbw, n_split, out, best, st);
+    case 3: return launch_bf16_mb<3>(w, x, M, N, K, nbw, n_split, out, best, st);
+    case 4: return launch_bf16_mb<4>(w, x, M, N, K, nbw, n_split, out, best, st);
+    case 5: return launch_bf16_mb<5>(w, x, M, N, K, nbw, n_split, out, best, st);
+    case 6: return launch_bf16_mb<6>(w, x, M, N, K, nbw, n_split, out, best, st);
+    case 7: return launch_bf16_mb<7>(w, x, M, N, K, nbw, n_split, out, best, st);
+    case 8: return launch_bf16_mb<8>(w, x, M, N, K, nbw, n_split, out, best, st);
+    default: return launch_bf16_mb<9>(w, x, M, N, K, nbw, n_split, out, best, st);
   }
 }
 

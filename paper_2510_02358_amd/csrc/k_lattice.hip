@@ -370,6 +370,90 @@ __global__ __launch_bounds__(1024) void accept_merge_kernel(int rows, int n_part
   }
 }
 
+// Same rule, fed by the LM-head product's own epilogue instead of a scan of the logits: tile_best[tile][row] is the
+// largest logit of the row inside one tile of columns and its column (int bits in .y), tiles in column order,
+// rows_pad rows per tile.  One workgroup per row reduces its records; the workgroup that arrives last (a counter
+// behind the records, left at zero by the product) applies the accepted-prefix rule.  Every workgroup ends after
+// one pass; nobody waits.
+__global__ __launch_bounds__(256) void accept_tiles_kernel(int rows, int rows_pad, int n_tiles,
+                                                          const float2* __restrict__ tile_best,
+                                                          uint32_t* __restrict__ counter, int32_t* am,
+                                                          const int32_t* __restrict__ block,
+                                                          const int32_t* __restrict__ path_len, int32_t eos_id,
+                                                          int32_t* __restrict__ n_accept,
+                                                          int32_t* __restrict__ next_token,
+                                                          int32_t* __restrict__ argmax_out,
+                                                          int32_t* __restrict__ eos_accepted) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  __shared__ bool last;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int r = blockIdx.x;
+  float ev = -INFINITY;
+  int eid = INT_MAX;
+#pragma unroll 8
+  for (int t = threadIdx.x; t < n_tiles; t += (int)blockDim.x) {
+    const float2 q = tile_best[(size_t)t * rows_pad + r];
+    const int xid = __float_as_int(q.y);
+    if (beats(q.x, xid, ev, eid)) {
+      ev = q.x;
+      eid = xid;
+    }
+  }
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) {
+    const float ov = __shfl_xor(ev, off);
+    const int oid = __shfl_xor(eid, off);
+    if (beats(ov, oid, ev, eid)) {
+      ev = ov;
+      eid = oid;
+    }
+  }
+  if (lane == 0) {
+    sv[wave] = ev;
+    si[wave] = eid;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < (int)(blockDim.x / kWave); ++w)
+      if (beats(sv[w], si[w], ev, eid)) {
+        ev = sv[w];
+        eid = si[w];
+      }
+    argmax_out[r] = eid;
+    __hip_atomic_store(&am[r], eid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();  // the row's result is visible device-wide before the arrival is counted
+    const uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    last = seen == (uint32_t)rows - 1u;
+  }
+  __syncthreads();
+  if (!last) return;
+  __threadfence();
+  __shared__ int32_t ams[DS_MAX_ROWS];
+  for (int i = threadIdx.x; i < rows; i += (int)blockDim.x)
+    ams[i] = __hip_atomic_load(&am[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int m = rows - 1;
+    if (path_len) {
+      int pl = *path_len;
+      m = pl < m ? (pl < 0 ? 0 : pl) : m;
+    }
+    int n = 0;
+    bool eos = false;
+    while (n < m && ams[n] == block[n + 1]) {
+      eos |= (eos_id >= 0 && block[n + 1] == eos_id);
+      ++n;
+    }
+    const int nxt = ams[n];
+    eos |= (eos_id >= 0 && nxt == eos_id);
+    *n_accept = n;
+    *next_token = nxt;
+    *eos_accepted = eos ? 1 : 0;
+  }
+}
+
 struct ScanPlan {
   int n_seg, tiles_per_seg, n_part;
 };
@@ -424,6 +508,22 @@ int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t
   hipLaunchKernelGGL(accept_merge_kernel, dim3(1), dim3(1024), 0, st, rows, p.n_part, partial, block, path_len,
                      eos_id, n_accept, next_token, argmax, eos_accepted);
   DS_LAUNCH_CHECK("accept_merge_kernel");
+  return DS_OK;
+}
+
+int launch_tiles_accept(float2* tile_best, int rows, int n_tiles, const int32_t* block,
+                        const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
+                        int32_t* argmax, int32_t* eos_accepted, hipStream_t st) {
+  DS_REQUIRE(rows >= 1 && rows <= DS_MAX_ROWS, DS_E_SHAPE, "acceptance rows %d outside [1, %d]", rows,
+             DS_MAX_ROWS);
+  DS_REQUIRE(tile_best && n_tiles >= 1, DS_E_INVALID, "acceptance from tiles: no tile records");
+  const int rows_pad = ceil_div(rows, 16) * 16;
+  // behind the records: the arrival counter (64 words reserved), then one arg-max word per row
+  uint32_t* counter = reinterpret_cast<uint32_t*>(tile_best + (size_t)n_tiles * rows_pad);
+  int32_t* am = reinterpret_cast<int32_t*>(counter + 64);
+  hipLaunchKernelGGL(accept_tiles_kernel, dim3(rows), dim3(256), 0, st, rows, rows_pad, n_tiles, tile_best, counter,
+                     am, block, path_len, eos_id, n_accept, next_token, argmax, eos_accepted);
+  DS_LAUNCH_CHECK("accept_tiles_kernel");
   return DS_OK;
 }
 

@@ -225,6 +225,67 @@ def test_bf16_lm_head_is_a_plain_gemm():
         gm.close()
 
 
+def test_bf16_verify_argmax_comes_from_the_lm_head_epilogue():
+    """The bf16 verifier takes each row's arg-max from per-tile records of the LM-head product, with or without
+    the logits being written.  Both ways give the same verdict; the arg-max is exactly the arg-max of the logits
+    the same call returns (first index on ties); and exact ties planted across tiles and inside one tile (LM-head
+    rows duplicated, so the logits are bit-equal) resolve to the lowest token id."""
+    cfg = SMALL_BF16
+    w = dict(synth.make_weights(cfg, 90))
+    lm = np.array(w["lm_head"], copy=True)
+    rng = np.random.default_rng(91)
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        gm.prefill(synth.make_prefix(cfg, 70, 92), want_logits=False)
+        block = rng.integers(0, cfg.n_plain_tokens, 34).astype(np.int32)
+        for n in range(6):                      # make the first six drafted tokens the verifier's own choices
+            gm.set_kv_len(70)
+            block[n + 1] = gm.verify(block, want_logits=False)["argmax"][n]
+        gm.set_kv_len(70)
+        base = gm.verify(block)
+    finally:
+        gm.close()
+    assert np.array_equal(base["argmax"], np.argmax(base["logits"], axis=1))
+    assert base["n_accept"] >= 6
+    # duplicate each of the first rows' winning LM-head row into a later tile, a lower id in another tile and
+    # a neighbour in the same tile
+    planted = {}
+    for r in range(0, 34, 3):
+        a = int(base["argmax"][r])
+        for b in ((a + 1000) % cfg.vocab, (a + 2 * 128 + 5) % cfg.vocab, a ^ 1):
+            if b in planted or b in base["argmax"]:
+                continue
+            lm[b] = lm[a]
+            planted[b] = a
+    w["lm_head"] = lm
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        gm.prefill(synth.make_prefix(cfg, 70, 92), want_logits=False)
+        full = gm.verify(block)
+        gm.set_kv_len(70)
+        bare = gm.verify(block, want_logits=False)
+        eos = int(full["argmax"][2])
+        for pl in (0, 5, 33):
+            dev_pl = gu.to_dev(np.array([pl], np.int32))
+            gm.set_kv_len(70)
+            a = gm.verify(block, path_len=dev_pl, eos_id=eos)
+            gm.set_kv_len(70)
+            b = gm.verify(block, path_len=dev_pl, eos_id=eos, want_logits=False)
+            got = (a["n_accept"], a["next_token"], a["eos_accepted"])
+            assert got == (b["n_accept"], b["next_token"], b["eos_accepted"])
+            n_acc, nxt, _, eos_acc = o_accept.verify_greedy(a["logits"][:pl + 1], block[1:pl + 1], eos)
+            assert got == (n_acc, nxt, eos_acc), (pl, got)
+    finally:
+        gm.close()
+    first_max = np.argmax(full["logits"], axis=1)
+    assert np.array_equal(full["argmax"], first_max) and np.array_equal(bare["argmax"], first_max)
+    ties = 0
+    for r in range(34):
+        row = full["logits"][r]
+        ties += int(np.sum(row == row[first_max[r]]) > 1)
+    assert ties >= 8, "the planted duplicates must produce exact ties"
+
+
 def test_7b_layer_bf16_prefix2048_k32():
     """7B-shaped layer + LM head, prefix 2048, K = 32 draft rows, 33 verify rows (one model in both roles)."""
     cfg = synth.CFG_7B_LAYER
