@@ -146,12 +146,15 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
     for (int p = 0; p < kXPer; ++p)
       *reinterpret_cast<u32x4*>(&xs[buf][(threadIdx.x + p * kGemmThreads) * 8]) = xreg[p];
   };
+  // Weights are read exactly once per product: non-temporal loads keep them from displacing the activations
+  // (re-read by every workgroup) and the output lines in the caches.
   auto load_a = [&](auto set, int c) {
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int s = 0; s < kKSC; ++s)
-        areg[set][b][s] = *reinterpret_cast<const f16x8*>(wrow[b] + ((size_t)c * kKSC + s) * 512);
+        areg[set][b][s] =
+            __builtin_nontemporal_load(reinterpret_cast<const f16x8*>(wrow[b] + ((size_t)c * kKSC + s) * 512));
   };
   auto compute = [&](auto set, int buf) {
 #pragma unroll
