@@ -351,10 +351,11 @@ int launch_pack_weight(const void* w, int N, int K, void* dst, uint32_t* range_f
 int gemm_bf16_splits(int N, int K, int nbw) {
   const int units = ceil_div(N >> 4, 4 * nbw);
   const int n_groups = (K >> 5) / kGroup;
-  // about two workgroups per compute unit (512 on the chip): the nearest split count, one more if that
-  // would leave the chip visibly underfilled; at most 10 planes (the consumers sum up to 10)
-  int s = (512 + units / 2) / units;
-  if (units * s < 448) ++s;
+  // two workgroups per compute unit are resident at once (512 on the chip): the largest split count that still
+  // fits one residency round, one more if that would leave the chip visibly underfilled; at most 10 planes (the
+  // consumers sum up to 10).  Depends on the weight shape only, never on the row count.
+  int s = 512 / units;
+  if (units * s < 416) ++s;
   if (s > 10) s = 10;
   if (s > n_groups) s = n_groups;
   if (s < 1) s = 1;
