@@ -271,11 +271,11 @@ def main() -> int:
         ds.ds_draft_block(dm.handle, dec.pending_dev, 1, K_DRAFT, dec.mask_id, dec.hidden, dm.ws)
         if i_timed >= 0:
             ev[i_timed][0].record()
-        ds.ds_lm_head(dm.handle, None, K_DRAFT, dec.d_logits, dm.ws)
+        ds.ds_lm_head_tiles(dm.handle, None, K_DRAFT, dec.eos_id, None, dm.ws)     # the logits stay on chip
         if i_timed >= 0:
             ev[i_timed][1].record()
-        ds.ds_build_lattice(dec.d_logits, K_DRAFT, cfg.vocab, p.m_max, p.tau, dec.eos_id, dec.cand_id, dec.cand_logp,
-                            dec.cand_cnt, dec.eos_logp, dec.lse, dec.lat_ws)
+        ds.ds_lattice_from_tiles(dm.handle, K_DRAFT, p.m_max, p.tau, dec.eos_id, dec.cand_id, dec.cand_logp,
+                                 dec.cand_cnt, dec.eos_logp, dec.lse, dm.ws)
         ds.ds_cps_path(dec.cand_id, dec.cand_logp, dec.cand_cnt, dec.eos_logp, 1, K_DRAFT, p.m_max, p.beam, p.lam,
                        dec.proxy, dec.ctx, dec.eos_id, dec.block[1:], dec.path_len, dec.path_score, dec.cps_ws)
         ds.ds_verify_block(vm.handle, dec.block, K_DRAFT, dec.path_len, dec.eos_id, dec.result[0:1],
@@ -317,10 +317,10 @@ def main() -> int:
         marks[r][0].record()
         ds.ds_draft_block(dm.handle, dec.pending_dev, 1, K_DRAFT, dec.mask_id, dec.hidden, dm.ws)
         marks[r][1].record()
-        ds.ds_lm_head(dm.handle, None, K_DRAFT, dec.d_logits, dm.ws)
+        ds.ds_lm_head_tiles(dm.handle, None, K_DRAFT, dec.eos_id, None, dm.ws)
         marks[r][2].record()
-        ds.ds_build_lattice(dec.d_logits, K_DRAFT, cfg.vocab, p.m_max, p.tau, dec.eos_id, dec.cand_id, dec.cand_logp,
-                            dec.cand_cnt, dec.eos_logp, dec.lse, dec.lat_ws)
+        ds.ds_lattice_from_tiles(dm.handle, K_DRAFT, p.m_max, p.tau, dec.eos_id, dec.cand_id, dec.cand_logp,
+                                 dec.cand_cnt, dec.eos_logp, dec.lse, dm.ws)
         marks[r][3].record()
         ds.ds_cps_path(dec.cand_id, dec.cand_logp, dec.cand_cnt, dec.eos_logp, 1, K_DRAFT, p.m_max, p.beam, p.lam,
                        dec.proxy, dec.ctx, dec.eos_id, dec.block[1:], dec.path_len, dec.path_score, dec.cps_ws)

@@ -144,6 +144,28 @@ int ds_build_lattice(const float* logits, int rows, int vocab, int M_max, float 
                      int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* Steps 1b + 2 without the logits round trip (Sec. 3.2 "Lattice and pruning").
+ * ds_lm_head_tiles: the LM head of ds_lm_head (hidden as there; NULL = the block rows of the preceding draft
+ * pass), leaving in the workspace what the lattice needs.  On DS_BF16 models those are per-tile records written by
+ * the product itself (per 128 token ids and row: the two largest logits with their ids, the third largest value,
+ * the sum of exponentials) plus the logits of eos_id, so with logits_out == NULL the logits never reach memory;
+ * logits_out [dev] float[rows, vocab] receives them if given.  DS_F32 models (and vocabularies the records do not
+ * cover: not a multiple of 128, or above 262144) keep the logits, in logits_out or the workspace.
+ * ds_lattice_from_tiles: the lattice of ds_build_lattice for those rows, same outputs, same rules (ties: lower id).
+ * It must directly follow ds_lm_head_tiles on the same model and workspace with the same rows and eos_id
+ * (DS_E_INVALID otherwise).  A tile whose third value could still enter the top-M_max is recomputed with the
+ * product's own instruction sequence, so the candidates are exactly those of the logits ds_lm_head would write;
+ * lse is summed tile by tile and may differ from ds_build_lattice's in the last bits.
+ * ds_draft_lattice: both steps in one call. */
+int ds_lm_head_tiles(ds_model* drafter, const float* hidden, int rows, int32_t eos_id, float* logits_out, void* ws,
+                     size_t ws_bytes, void* stream);
+int ds_lattice_from_tiles(ds_model* drafter, int rows, int M_max, float tau, int32_t eos_id, int32_t* cand_id,
+                          float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse, void* ws,
+                          size_t ws_bytes, void* stream);
+int ds_draft_lattice(ds_model* drafter, const float* hidden, int rows, int M_max, float tau, int32_t eos_id,
+                     int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
+                     float* logits_out, void* ws, size_t ws_bytes, void* stream);
+
 /* Causal proxy for the path search: a table of 2^log2_size float32 natural-log scores [dev]; the
  * 3-gram (u, v, w) reads slot hash(u, v, w) (fixed uint32 multiply / xor-shift mix). */
 int ds_ngram_create(const float* table, int log2_size, ds_ngram** out);

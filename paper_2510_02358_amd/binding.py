@@ -21,7 +21,7 @@ DS_OK, DS_E_INVALID, DS_E_SHAPE, DS_E_CAPACITY, DS_E_UNSUPPORTED, DS_E_HIP = 0, 
 EXPORTS = [
     "ds_version", "ds_last_error", "ds_model_packed_bytes", "ds_workspace_bytes", "ds_kv_bytes",
     "ds_model_create", "ds_model_destroy", "ds_model_kv_len", "ds_model_kv_set_len", "ds_prefill",
-    "ds_draft_block", "ds_lm_head", "ds_lattice_workspace_bytes", "ds_build_lattice", "ds_ngram_create",
+    "ds_draft_block", "ds_lm_head", "ds_draft_lattice", "ds_lm_head_tiles", "ds_lattice_from_tiles", "ds_lattice_workspace_bytes", "ds_build_lattice", "ds_ngram_create",
     "ds_ngram_destroy", "ds_cps_workspace_bytes", "ds_cps_path", "ds_verify_block", "ds_adl_create", "ds_adl_destroy",
     "ds_adl_update", "ds_adl_state", "ds_sample_workspace_bytes", "ds_accept_stochastic",
     "ds_verify_block_stochastic", "ds_draft_block_tokens", "ds_refine_select",
@@ -83,6 +83,9 @@ def load():
     lib.ds_draft_block.argtypes = [vp, vp, C.c_int, C.c_int, i32, vp, vp, sz, vp]
     lib.ds_lm_head.argtypes = [vp, vp, C.c_int, vp, vp, sz, vp]
     lib.ds_lattice_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(sz)]
+    lib.ds_lm_head_tiles.argtypes = [vp, vp, C.c_int, i32, vp, vp, sz, vp]
+    lib.ds_lattice_from_tiles.argtypes = [vp, C.c_int, C.c_int, f32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ds_draft_lattice.argtypes = [vp, vp, C.c_int, C.c_int, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_build_lattice.argtypes = [vp, C.c_int, C.c_int, C.c_int, f32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_ngram_create.argtypes = [vp, C.c_int, C.POINTER(vp)]
     lib.ds_ngram_destroy.argtypes = [vp]
@@ -214,6 +217,25 @@ def ds_build_lattice(logits, rows: int, vocab: int, m_max: int, tau: float, eos_
     _check(load().ds_build_lattice(_ptr(logits), rows, vocab, m_max, tau, eos_id, _ptr(cand_id), _ptr(cand_logp),
                                    _ptr(cand_cnt), _ptr(eos_logp), _ptr(lse), _ptr(ws),
                                    _nbytes(ws) if ws is not None else 0, _stream(stream)))
+
+
+def ds_lm_head_tiles(model: int, hidden, rows: int, eos_id: int, logits_out, ws, stream=None) -> None:
+    _check(load().ds_lm_head_tiles(model, _ptr(hidden), rows, eos_id, _ptr(logits_out), _ptr(ws), _nbytes(ws),
+                                   _stream(stream)))
+
+
+def ds_lattice_from_tiles(model: int, rows: int, m_max: int, tau: float, eos_id: int, cand_id, cand_logp, cand_cnt,
+                          eos_logp, lse, ws, stream=None) -> None:
+    _check(load().ds_lattice_from_tiles(model, rows, m_max, tau, eos_id, _ptr(cand_id), _ptr(cand_logp),
+                                        _ptr(cand_cnt), _ptr(eos_logp), _ptr(lse), _ptr(ws), _nbytes(ws),
+                                        _stream(stream)))
+
+
+def ds_draft_lattice(model: int, hidden, rows: int, m_max: int, tau: float, eos_id: int, cand_id, cand_logp, cand_cnt,
+                     eos_logp, lse, logits_out, ws, stream=None) -> None:
+    _check(load().ds_draft_lattice(model, _ptr(hidden), rows, m_max, tau, eos_id, _ptr(cand_id), _ptr(cand_logp),
+                                   _ptr(cand_cnt), _ptr(eos_logp), _ptr(lse), _ptr(logits_out), _ptr(ws),
+                                   _nbytes(ws), _stream(stream)))
 
 
 def ds_ngram_create(table, log2_size: int) -> int:

@@ -117,13 +117,26 @@ int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, 
 // bf16 -> half re-encoding into stream order; *range_flag [dev] is set to 1 if any |w| exceeds the half range
 int launch_pack_weight(const void* w, int N, int K, void* dst, uint32_t* range_flag, hipStream_t st);
 int gemm_bf16_splits(int N, int K, int nbw);
-// out may be NULL if best is given.  best (optional): per tile of 64 * nbw columns and per output row (padded to
-// 16), the largest value and its column (as int bits), [N / tile][rows_pad], followed by a 32-bit arrival counter
-// for the consumer which the product clears; gemm_bf16_best_bytes in all.  See gemm_bf16_best_tile.
+// What an unsplit product of full tiles (gemm_bf16_best_tile() > 0) leaves besides, or instead of, its output:
+//   kBest  per tile of 64 * nbw columns and output row (padded to 16): the largest value and its column (int bits),
+//          float2 [N / tile][rows_pad], then a 32-bit arrival counter for the consumer, which the product clears;
+//          gemm_bf16_best_bytes in all;
+//   kTop   per tile and row two float4: (v1, col1, v2, col2) the two largest values with their columns and
+//          (v3, sum exp(x - v1), 0, 0) the third largest value and the tile's exponential sum; gemm_bf16_top_bytes;
+//          export_out[row] (rows_pad floats, optional) receives the values of column export_col.
+// With records the output pointer may be NULL.
+struct GemmEpilogue {
+  enum Kind { kNone = 0, kBest = 1, kTop = 2 };
+  Kind kind = kNone;
+  void* records = nullptr;
+  int export_col = -1;
+  float* export_out = nullptr;
+};
 int gemm_bf16_best_tile(int N, int nbw, int n_split);
 size_t gemm_bf16_best_bytes(int rows, int N, int tile);
+size_t gemm_bf16_top_bytes(int rows, int N, int tile);
 int launch_gemm_bf16(const void* wp, const void* xt, int M, int N, int K, int nbw, int n_split, float* out,
-                     float2* best, hipStream_t st);
+                     const GemmEpilogue& epi, hipStream_t st);
 int launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* out, int ldc, hipStream_t st);
 
 // Attention over keys [0, n_keys) of one layer's cache for `rows` query rows at positions pos0 + r.

@@ -63,6 +63,14 @@ int launch_tiles_accept(float2* tile_best, int rows, int n_tiles, const int32_t*
                         const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
                         int32_t* argmax, int32_t* eos_accepted, hipStream_t st);
 
+// The lattice from the LM-head product's per-tile records (GemmEpilogue::kTop layout, tiles of 128 columns); wp / xt
+// are the product's own operands (stream-order weights, tile-order activations), re-read for the rare tile whose
+// records do not settle the top-M.  eos_logit: rows_pad floats written by the product (needed if eos_id >= 0).
+bool lattice_tiles_supported(int n_tiles, int tile_cols);
+int launch_lattice_tiles(const void* rec, int rows, int n_tiles, int m_max, float tau, int32_t eos_id,
+                         const float* eos_logit, const void* wp, const void* xt, int K, int32_t* cand_id,
+                         float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse, hipStream_t st);
+
 // ---- path search (k_cps.hip) --------------------------------------------------------------------
 int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
                const float* eos_logp, int batch, int K, int m_max, int B, float lambda,

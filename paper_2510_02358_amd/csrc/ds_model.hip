@@ -33,7 +33,10 @@ struct Workspace {
   float* logits;   // [rows, vocab]
   void* scan;      // acceptance partials
   size_t scan_bytes;
-  float2* tile_best; // per LM-head column tile and row: largest logit and its column (greedy acceptance)
+  void* tile_rec;  // per LM-head column tile and row: arg-max records (greedy acceptance) or lattice records
+  float* eos_col;  // [rows_pad] EOS logits exported by the LM-head product
+  void* lat;       // lattice scan partials (unfused path)
+  size_t lat_bytes;
   void* sample;    // stochastic acceptance: log-sum-exp of the verifier and drafter rows
   size_t sample_bytes;
   size_t total;
@@ -55,6 +58,13 @@ struct ds_model {
   const void* tail_ptr = nullptr;
   const void* tail_ws = nullptr;
   int tail_rows = 0;
+  // what ds_lm_head_tiles left behind for ds_lattice_from_tiles: the product's activation operand (bf16 models,
+  // records in the workspace) or the logits (float32 models)
+  const void* rec_ws = nullptr;
+  const void* rec_y = nullptr;
+  const float* rec_logits = nullptr;
+  int rec_rows = 0;
+  int32_t rec_eos = -1;
 };
 
 namespace {
@@ -141,9 +151,15 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
   w.logits = static_cast<float*>(take((size_t)rows * c.vocab * 4));
   w.scan_bytes = accept_ws_bytes(rows, c.vocab);
   w.scan = take(w.scan_bytes);
-  // also holds the acceptance kernel's per-row arg-max exchange behind the counter
-  w.tile_best = static_cast<float2*>(
-      take(gemm_bf16_best_bytes(rows, c.vocab, 128) + (size_t)DS_MAX_ROWS * sizeof(int32_t)));
+  {
+    // arg-max records + counter + per-row exchange words, or lattice records: whichever is larger
+    const size_t best = gemm_bf16_best_bytes(rows, c.vocab, 128) + (size_t)DS_MAX_ROWS * sizeof(int32_t);
+    const size_t top = gemm_bf16_top_bytes(rows, c.vocab, 128);
+    w.tile_rec = take(best > top ? best : top);
+  }
+  w.eos_col = static_cast<float*>(take((size_t)rp * sizeof(float)));
+  w.lat_bytes = lattice_ws_bytes(rows, c.vocab, DS_MAX_TOPM);
+  w.lat = take(w.lat_bytes);
   w.sample_bytes = sample_ws_bytes(rows);
   w.sample = take(w.sample_bytes);
   w.total = off;
@@ -152,7 +168,7 @@ Workspace carve(const ds_model_cfg& c, int rows, void* base) {
 
 template <typename T>
 int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float* out, int* n_split,
-         hipStream_t st, float2* best = nullptr) {
+         hipStream_t st, const GemmEpilogue& epi = GemmEpilogue{}) {
   // which: 0 qkv, 1 o, 2 gate/up, 3 down, 4 lm head
   const ds_model_cfg& c = m->cfg;
   const int d = c.d_model, f = c.d_ffn, qo = c.n_q * c.head_dim;
@@ -174,7 +190,7 @@ int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float
     // two row blocks per wavefront where N is large (LM head, gate/up): half the X traffic per weight byte
     const int nbw = (which == 4 || which == 2) ? 2 : 1;
     *n_split = which == 4 ? 1 : gemm_bf16_splits(N, K, nbw);
-    return launch_gemm_bf16(w, x_in, rows, N, K, nbw, *n_split, out, best, st);
+    return launch_gemm_bf16(w, x_in, rows, N, K, nbw, *n_split, out, epi, st);
   }
   *n_split = 1;
   const float* x = static_cast<const float*>(x_in);
@@ -246,16 +262,17 @@ int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real
 int forward_dispatch(ds_model* m, const Workspace& w, const int32_t* src, int n_real, const int32_t* src2,
                      int32_t fill, int rows, int n_causal, float* hidden_out, int hidden_row0, hipStream_t st) {
   m->tail_ptr = nullptr;  // any forward overwrites the workspace
+  m->rec_ws = nullptr;
   return m->cfg.dtype == DS_BF16
              ? forward_rows<bf16_t>(m, w, src, n_real, src2, fill, rows, n_causal, hidden_out, hidden_row0, st)
              : forward_rows<float>(m, w, src, n_real, src2, fill, rows, n_causal, hidden_out, hidden_row0, st);
 }
 
-// tile_best (bf16 path with lm_head_tile() > 0 only): also leave the per-tile arg-max records; logits may then be NULL.
+// epi (bf16 path with lm_head_tile() > 0 only): also leave per-tile records; logits may then be NULL.
 int lm_head_rows(ds_model* m, const void* y_gemm_in, int rows, float* logits, hipStream_t st,
-                 float2* tile_best = nullptr) {
+                 const GemmEpilogue& epi = GemmEpilogue{}) {
   int sp = 1;
-  return m->cfg.dtype == DS_BF16 ? gemm<bf16_t>(m, 0, 4, y_gemm_in, rows, logits, &sp, st, tile_best)
+  return m->cfg.dtype == DS_BF16 ? gemm<bf16_t>(m, 0, 4, y_gemm_in, rows, logits, &sp, st, epi)
                                  : gemm<float>(m, 0, 4, y_gemm_in, rows, logits, &sp, st);
 }
 
@@ -461,6 +478,7 @@ int ds_lm_head(ds_model* m, const float* hidden, int rows, float* logits, void* 
   int rc = check_ws(m, rows, ws, ws_bytes, &w);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  m->rec_ws = nullptr;
   if (!hidden) {  // the block rows of the last draft pass, still in the workspace as a GEMM input
     DS_REQUIRE(m->tail_ptr && m->tail_ws == ws && m->tail_rows == rows, DS_E_INVALID,
                "ds_lm_head(hidden = NULL) must directly follow a draft pass of %d block rows on this workspace", rows);
@@ -472,6 +490,89 @@ int ds_lm_head(ds_model* m, const float* hidden, int rows, float* logits, void* 
     return lm_head_rows(m, w.y, rows, logits, st);
   }
   return lm_head_rows(m, hidden, rows, logits, st);
+}
+
+int ds_lm_head_tiles(ds_model* m, const float* hidden, int rows, int32_t eos_id, float* logits_out, void* ws,
+                     size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m, DS_E_INVALID, "ds_lm_head_tiles: NULL model");
+  DS_REQUIRE(rows >= 1 && rows <= DS_MAX_ROWS, DS_E_SHAPE, "rows %d outside [1, %d]", rows, DS_MAX_ROWS);
+  const int vocab = m->cfg.vocab;
+  DS_REQUIRE(eos_id < vocab, DS_E_INVALID, "eos_id %d >= vocab %d", eos_id, vocab);
+  Workspace w;
+  int rc = check_ws(m, rows, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  m->rec_ws = nullptr;
+  const void* y = nullptr;
+  if (!hidden) {  // the block rows of the last draft pass, still in the workspace as a GEMM input
+    DS_REQUIRE(m->tail_ptr && m->tail_ws == ws && m->tail_rows == rows, DS_E_INVALID,
+               "ds_lm_head_tiles(hidden = NULL) must directly follow a draft pass of %d block rows on this workspace",
+               rows);
+    y = m->tail_ptr;
+  } else if (m->cfg.dtype == DS_BF16) {
+    const int rp = ceil_div(rows, 16) * 16;
+    if ((rc = launch_to_gemm_input<bf16_t>(hidden, rows, rp, m->cfg.d_model, w.y, st))) return rc;
+    y = w.y;
+  } else {
+    y = hidden;
+  }
+  const int tile = lm_head_tile(m);
+  if (tile > 0 && lattice_tiles_supported(vocab / tile, tile)) {
+    GemmEpilogue epi;
+    epi.kind = GemmEpilogue::kTop;
+    epi.records = w.tile_rec;
+    epi.export_col = eos_id;
+    epi.export_out = eos_id >= 0 ? w.eos_col : nullptr;
+    if ((rc = lm_head_rows(m, y, rows, logits_out, st, epi))) return rc;
+    m->rec_logits = nullptr;
+  } else {
+    float* logits = logits_out ? logits_out : w.logits;
+    if ((rc = lm_head_rows(m, y, rows, logits, st))) return rc;
+    m->rec_logits = logits;
+  }
+  m->rec_ws = ws;
+  m->rec_y = y;
+  m->rec_rows = rows;
+  m->rec_eos = eos_id;
+  return DS_OK;
+}
+
+int ds_lattice_from_tiles(ds_model* m, int rows, int M_max, float tau, int32_t eos_id, int32_t* cand_id,
+                          float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse, void* ws,
+                          size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m && cand_id && cand_logp && cand_cnt && eos_logp && lse, DS_E_INVALID,
+             "ds_lattice_from_tiles: NULL pointer argument");
+  DS_REQUIRE(rows >= 1 && rows <= DS_MAX_ROWS, DS_E_SHAPE, "rows %d outside [1, %d]", rows, DS_MAX_ROWS);
+  const int vocab = m->cfg.vocab;
+  DS_REQUIRE(M_max >= 1 && M_max <= DS_MAX_TOPM && M_max <= vocab, DS_E_SHAPE,
+             "M_max %d outside [1, min(%d, vocab)]", M_max, DS_MAX_TOPM);
+  DS_REQUIRE(!isnan(tau) && tau > 0.f, DS_E_INVALID, "tau must be positive");
+  DS_REQUIRE(m->rec_ws && m->rec_ws == ws && m->rec_rows == rows && m->rec_eos == eos_id, DS_E_INVALID,
+             "ds_lattice_from_tiles must directly follow ds_lm_head_tiles with the same rows (%d), eos_id and workspace",
+             rows);
+  Workspace w;
+  int rc = check_ws(m, rows, ws, ws_bytes, &w);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (m->rec_logits)
+    return launch_lattice(m->rec_logits, rows, vocab, M_max, tau, eos_id, cand_id, cand_logp, cand_cnt, eos_logp, lse,
+                          w.lat, w.lat_bytes, st);
+  return launch_lattice_tiles(w.tile_rec, rows, vocab / lm_head_tile(m), M_max, tau, eos_id, w.eos_col, m->lm_head,
+                              m->rec_y, m->cfg.d_model, cand_id, cand_logp, cand_cnt, eos_logp, lse, st);
+}
+
+int ds_draft_lattice(ds_model* m, const float* hidden, int rows, int M_max, float tau, int32_t eos_id,
+                     int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
+                     float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m && cand_id && cand_logp && cand_cnt && eos_logp && lse, DS_E_INVALID,
+             "ds_draft_lattice: NULL pointer argument");
+  DS_REQUIRE(m->cfg.vocab >= M_max && M_max >= 1 && M_max <= DS_MAX_TOPM, DS_E_SHAPE,
+             "M_max %d outside [1, min(%d, vocab)]", M_max, DS_MAX_TOPM);
+  DS_REQUIRE(!isnan(tau) && tau > 0.f, DS_E_INVALID, "tau must be positive");
+  int rc = ds_lm_head_tiles(m, hidden, rows, eos_id, logits_out, ws, ws_bytes, stream);
+  if (rc) return rc;
+  return ds_lattice_from_tiles(m, rows, M_max, tau, eos_id, cand_id, cand_logp, cand_cnt, eos_logp, lse, ws, ws_bytes,
+                               stream);
 }
 
 int ds_verify_block(ds_model* m, const int32_t* block, int mlen, const int32_t* path_len, int32_t eos_id,
@@ -492,8 +593,11 @@ int ds_verify_block(ds_model* m, const int32_t* block, int mlen, const int32_t* 
   if ((rc = forward_dispatch(m, w, block, rows, nullptr, 0, rows, rows, nullptr, 0, st))) return rc;
   if (const int tile = lm_head_tile(m)) {
     // The product's epilogue reports every tile's largest logit; the logits themselves are written only if asked for.
-    if ((rc = lm_head_rows(m, w.y, rows, logits_out, st, w.tile_best))) return rc;
-    return launch_tiles_accept(w.tile_best, rows, m->cfg.vocab / tile, block, path_len, eos_id, n_accept, next_token,
+    GemmEpilogue epi;
+    epi.kind = GemmEpilogue::kBest;
+    epi.records = w.tile_rec;
+    if ((rc = lm_head_rows(m, w.y, rows, logits_out, st, epi))) return rc;
+    return launch_tiles_accept(static_cast<float2*>(w.tile_rec), rows, m->cfg.vocab / tile, block, path_len, eos_id, n_accept, next_token,
                                argmax, eos_accepted, st);
   }
   float* logits = logits_out ? logits_out : w.logits;

@@ -28,6 +28,7 @@
 #include <math.h>
 #include <type_traits>
 
+#include "ds_act.h"
 #include "ds_common.h"
 
 namespace ds {
@@ -75,9 +76,38 @@ __global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K,
 // EPI selects the epilogue at compile time, so that the split-K layer products carry none of the LM head's code:
 //   kEpiPlanes  plain stores into this split's plane of `out`;
 //   kEpiStream  unsplit product, non-temporal stores (logits are consumed once, later);
-//   kEpiBest    unsplit product of full tiles: per-tile arg-max records into `best`, and the non-temporal stores
-//               only if `out` is not NULL.
-enum { kEpiPlanes = 0, kEpiStream = 1, kEpiBest = 2 };
+//   kEpiBest    unsplit product of full tiles: per-tile arg-max records into `rec`, and the non-temporal stores
+//               only if `out` is not NULL;
+//   kEpiTop     as kEpiBest, with per-tile lattice records instead: the two largest values with their columns,
+//               the third largest value, the sum of exp(x - largest); and the values of one chosen column.
+enum { kEpiPlanes = 0, kEpiStream = 1, kEpiBest = 2, kEpiTop = 3 };
+
+// Running (largest, second largest, third largest) of a stream of values; the first two carry their columns and
+// order equal values by column, the third is a value only.
+struct Top3 {
+  float v1 = -INFINITY, v2 = -INFINITY, v3 = -INFINITY;
+  int i1 = INT_MAX, i2 = INT_MAX;
+  __device__ __forceinline__ void offer(float x, int col) {
+    if (x > v1 || (x == v1 && col < i1)) {
+      v3 = v2;
+      v2 = v1;
+      i2 = i1;
+      v1 = x;
+      i1 = col;
+    } else if (x > v2 || (x == v2 && col < i2)) {
+      v3 = v2;
+      v2 = x;
+      i2 = col;
+    } else {
+      v3 = fmaxf(v3, x);
+    }
+  }
+  __device__ __forceinline__ void merge(float ov1, int oi1, float ov2, int oi2, float ov3) {
+    offer(ov1, oi1);
+    offer(ov2, oi2);
+    v3 = fmaxf(v3, ov3);
+  }
+};
 
 template <int MB, int NB, int EPI>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(min_waves_for(MB, NB))))
@@ -85,7 +115,8 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
                                                                  const uint16_t* __restrict__ xt, int M, int N,
                                                                  int K, int groups_per_split, int n_big,
                                                                  float* __restrict__ out,
-                                                                 float2* __restrict__ best) {
+                                                                 void* __restrict__ rec, int export_col,
+                                                                 float* __restrict__ export_out) {
   constexpr int kTiles = MB * kKSC;  // X tiles per chunk: row blocks x k-steps
   __shared__ __attribute__((aligned(16))) uint16_t xs[2][kTiles * 512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -212,7 +243,7 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   }
 
   // D[i][j]: lane (16 g + j) holds rows i = 4 g .. 4 g + 3 of column j  ->  out[m = 16 mb + j][n = 16 nb + 4 g ..]
-  if (EPI != kEpiBest || out) {
+  if ((EPI != kEpiBest && EPI != kEpiTop) || out) {
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       if (nb[b] >= nb_end) continue;
@@ -237,6 +268,7 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   // these pairs only, not the logits.  The word after the last record is the consumer's arrival counter, cleared
   // here.
   if (EPI == kEpiBest) {
+    float2* best = static_cast<float2*>(rec);
     float2* red = reinterpret_cast<float2*>(&xs[0][0]);  // [4 waves][MB * 16 rows]; the main loop is past its last barrier
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
@@ -282,6 +314,68 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
       best[(size_t)blockIdx.x * MB * 16 + row] = make_float2(bv, __int_as_float(bi));
     }
   }
+  // Lattice records of this workgroup's 128 columns, per output row: rec[workgroup][row] = two float4,
+  // (v1, col1 bits, v2, col2 bits) and (v3, sum of exp(x - v1), 0, 0).  The log-sum-exp and the top-M of a row follow
+  // from the records of all tiles unless some tile's third value could still enter the top-M, which the consumer
+  // checks.  export_out[row] receives the value of column export_col (the EOS logit), if that column is here.
+  if (EPI == kEpiTop) {
+    constexpr float kLog2e = 1.4426950408889634f;
+    float4* red_a = reinterpret_cast<float4*>(&xs[0][0]);        // [4 waves][MB * 16 rows]
+    float2* red_b = reinterpret_cast<float2*>(red_a + 4 * MB * 16);
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+      Top3 t;
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t.offer(acc[b][m][e], nb[b] * 16 + g_out * 4 + e);
+#pragma unroll
+      for (int off = 16; off <= 32; off <<= 1) {
+        const float ov1 = __shfl_xor(t.v1, off), ov2 = __shfl_xor(t.v2, off), ov3 = __shfl_xor(t.v3, off);
+        const int oi1 = __shfl_xor(t.i1, off), oi2 = __shfl_xor(t.i2, off);
+        t.merge(ov1, oi1, ov2, oi2, ov3);
+      }
+      const float nm = -t.v1 * kLog2e;
+      float sum = 0.f;
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f(fmaf(acc[b][m][e], kLog2e, nm));
+      sum += __shfl_xor(sum, 16);
+      sum += __shfl_xor(sum, 32);
+      if (g_out == 0) {
+        red_a[(wave * MB + m) * 16 + j_out] = make_float4(t.v1, __int_as_float(t.i1), t.v2, __int_as_float(t.i2));
+        red_b[(wave * MB + m) * 16 + j_out] = make_float2(t.v3, sum);
+      }
+      if (export_out) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (nb[b] * 16 + g_out * 4 + e == export_col) export_out[m * 16 + j_out] = acc[b][m][e];
+      }
+    }
+    __syncthreads();
+    const int row = threadIdx.x;
+    if (row < MB * 16) {
+      Top3 t;
+      float vw[4], sw[4];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float4 a = red_a[w * MB * 16 + row];
+        const float2 b = red_b[w * MB * 16 + row];
+        vw[w] = a.x;
+        sw[w] = b.y;
+        t.merge(a.x, __float_as_int(a.y), a.z, __float_as_int(a.w), b.x);
+      }
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) sum += sw[w] * __builtin_amdgcn_exp2f((vw[w] - t.v1) * kLog2e);
+      float4* dst = static_cast<float4*>(rec) + ((size_t)blockIdx.x * MB * 16 + row) * 2;
+      dst[0] = make_float4(t.v1, __int_as_float(t.i1), t.v2, __int_as_float(t.i2));
+      dst[1] = make_float4(t.v3, sum, 0.f, 0.f);
+    }
+  }
   __syncthreads();  // the next pass restages X into the same LDS buffers
   }  // passes
 }
@@ -315,7 +409,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 
 template <int MB>
 int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, int nbw, int n_split, float* out,
-                   float2* best, hipStream_t st) {
+                   const GemmEpilogue& epi, hipStream_t st) {
   const int n_groups = (K >> 5) / kGroup;
   const int gps = ceil_div(n_groups, n_split);
   // One workgroup per full pass of 4 * nbw row blocks; a remainder goes to half-size workgroups at the end.
@@ -324,9 +418,12 @@ int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, 
   const int n_small = ceil_div(n_blocks - n_big * full, half);
   dim3 grid(n_big + n_small, n_split);
   auto go = [&](auto kernel) {
-    hipLaunchKernelGGL(kernel, grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, n_big, out, best);
+    hipLaunchKernelGGL(kernel, grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, n_big, out, epi.records,
+                       epi.export_col, epi.export_out);
   };
-  if (best) go(gemm_bf16_kernel<MB, 2, kEpiBest>);  // the caller has checked nbw == 2 and n_split == 1
+  // records: the caller has checked nbw == 2 and n_split == 1
+  if (epi.kind == GemmEpilogue::kBest) go(gemm_bf16_kernel<MB, 2, kEpiBest>);
+  else if (epi.kind == GemmEpilogue::kTop) go(gemm_bf16_kernel<MB, 2, kEpiTop>);
   else if (n_split == 1 && nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiStream>);
   else if (n_split == 1) go(gemm_bf16_kernel<MB, 1, kEpiStream>);
   else if (nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiPlanes>);
@@ -374,25 +471,30 @@ size_t gemm_bf16_best_bytes(int rows, int N, int tile) {
   return (size_t)(N / tile) * (ceil_div(rows, 16) * 16) * sizeof(float2) + 256;  // records, then the counter
 }
 
+size_t gemm_bf16_top_bytes(int rows, int N, int tile) {
+  return (size_t)(N / tile) * (ceil_div(rows, 16) * 16) * 2 * sizeof(float4);
+}
+
 int launch_gemm_bf16(const void* wp, const void* xt, int M, int N, int K, int nbw, int n_split, float* out,
-                     float2* best, hipStream_t st) {
+                     const GemmEpilogue& epi, hipStream_t st) {
   DS_REQUIRE(M >= 1 && M <= DS_MAX_ROWS, DS_E_SHAPE, "GEMM rows %d outside [1, %d]", M, DS_MAX_ROWS);
   DS_REQUIRE((N & 15) == 0 && (K & 127) == 0, DS_E_SHAPE, "GEMM [%d x %d]: N %% 16 and K %% 128 must be 0", N, K);
-  DS_REQUIRE(out || best, DS_E_INVALID, "GEMM: neither an output nor a per-tile arg-max buffer");
-  DS_REQUIRE(!best || gemm_bf16_best_tile(N, nbw, n_split) > 0, DS_E_SHAPE,
-             "GEMM [%d x %d]: the per-tile arg-max needs an unsplit pass of full tiles", N, K);
+  const bool records = epi.kind != GemmEpilogue::kNone;
+  DS_REQUIRE(out || records, DS_E_INVALID, "GEMM: neither an output nor a per-tile record buffer");
+  DS_REQUIRE(!records || (epi.records && gemm_bf16_best_tile(N, nbw, n_split) > 0), DS_E_SHAPE,
+             "GEMM [%d x %d]: per-tile records need a buffer and an unsplit pass of full tiles", N, K);
   const uint16_t* w = static_cast<const uint16_t*>(wp);
   const uint16_t* x = static_cast<const uint16_t*>(xt);
   switch (ceil_div(M, 16)) {
-    case 1: return launch_bf16_mb<1>(w, x, M, N, K, nbw, n_split, out, best, st);
-    case 2: return launch_bf16_mb<2>(w, x, M, N, K, nbw, n_split, out, best, st);
-    case 3: return launch_bf16_mb<3>(w, x, M, N, K, nbw, n_split, out, best, st);
-    case 4: return launch_bf16_mb<4>(w, x, M, N, K, nbw, n_split, out, best, st);
-    case 5: return launch_bf16_mb<5>(w, x, M, N, K, nbw, n_split, out, best, st);
-    case 6: return launch_bf16_mb<6>(w, x, M, N, K, nbw, n_split, out, best, st);
-    case 7: return launch_bf16_mb<7>(w, x, M, N, K, nbw, n_split, out, best, st);
-    case 8: return launch_bf16_mb<8>(w, x, M, N, K, nbw, n_split, out, best, st);
-    default: return launch_bf16_mb<9>(w, x, M, N, K, nbw, n_split, out, best, st);
+    case 1: return launch_bf16_mb<1>(w, x, M, N, K, nbw, n_split, out, epi, st);
+    case 2: return launch_bf16_mb<2>(w, x, M, N, K, nbw, n_split, out, epi, st);
+    case 3: return launch_bf16_mb<3>(w, x, M, N, K, nbw, n_split, out, epi, st);
+    case 4: return launch_bf16_mb<4>(w, x, M, N, K, nbw, n_split, out, epi, st);
+    case 5: return launch_bf16_mb<5>(w, x, M, N, K, nbw, n_split, out, epi, st);
+    case 6: return launch_bf16_mb<6>(w, x, M, N, K, nbw, n_split, out, epi, st);
+    case 7: return launch_bf16_mb<7>(w, x, M, N, K, nbw, n_split, out, epi, st);
+    case 8: return launch_bf16_mb<8>(w, x, M, N, K, nbw, n_split, out, epi, st);
+    default: return launch_bf16_mb<9>(w, x, M, N, K, nbw, n_split, out, epi, st);
   }
 }
 

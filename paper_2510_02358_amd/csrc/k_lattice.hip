@@ -10,6 +10,7 @@
 #include <math.h>
 
 #include "ds_common.h"
+#include "ds_wave.h"
 
 namespace ds {
 namespace {
@@ -454,6 +455,278 @@ __global__ __launch_bounds__(256) void accept_tiles_kernel(int rows, int rows_pa
   }
 }
 
+// ---- lattice straight from the LM-head product's per-tile records ---------------------------------------------
+//
+// The product leaves, per tile of 128 vocabulary columns and per row, the tile's two largest logits with their
+// columns, its third largest value and its sum of exp(x - largest).  The log-sum-exp of a row follows from the
+// records exactly as from the logits.  The top-M of the row is the top-M of all recorded pairs PROVIDED no tile hides
+// a third value that could still enter it: a tile is "open" if its third value exceeds the M-th best found so far, or
+// equals it while the tile's first column is lower than that entry's (equal logits rank by token id).  Open tiles
+// are rare (three of a row's M best tokens within 128 consecutive ids); for each of them the workgroup recomputes the
+// tile's 128 logits with the very MFMA sequence of the product (same operands, same order: the same bits) and offers
+// them to the list, after which the result is exact.
+typedef _Float16 lt_f16x8 __attribute__((ext_vector_type(8)));
+typedef float lt_f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kTilesPerThread = 8;  // records held in registers per thread: at most 256 * 8 tiles per row
+constexpr int kTileCols = 128;
+constexpr int kOpenList = 64;
+
+// The best (value descending, id ascending) of one pair per lane: its lane, wavefront-uniform; the pair in bv / bid.
+__device__ __forceinline__ int wave_best(float v, int id, float& bv, int& bid) {
+  const uint32_t key = ordered_bits(v);
+  const uint32_t top = wave_max_u32(key);
+  const unsigned long long at_top = __ballot(key == top);
+  int src = __ffsll((long long)at_top) - 1;
+  if (__popcll(at_top) > 1) {  // equal values: the lowest id among them
+    const uint32_t idk = key == top ? 0xFFFFFFFFu - (uint32_t)id : 0u;
+    const uint32_t low = wave_max_u32(idk);
+    src = __ffsll((long long)__ballot(idk == low)) - 1;
+  }
+  bv = lane_value(v, src);
+  bid = lane_value(id, src);
+  return src;
+}
+
+// PER: tile records per thread (256 * PER >= tiles per row).
+template <int PER>
+__global__ __launch_bounds__(256) void lattice_tiles_kernel(const float4* __restrict__ rec, int rows_pad, int n_tiles,
+                                                           int m_max, float tau, int32_t eos_id,
+                                                           const float* __restrict__ eos_logit,
+                                                           const uint16_t* __restrict__ wp,
+                                                           const uint16_t* __restrict__ xt, int ksteps,
+                                                           int32_t* __restrict__ cand_id,
+                                                           float* __restrict__ cand_logp,
+                                                           int32_t* __restrict__ cand_cnt,
+                                                           float* __restrict__ eos_logp,
+                                                           float* __restrict__ lse_out) {
+  __shared__ float l_val[4][DS_MAX_TOPM];
+  __shared__ int l_id[4][DS_MAX_TOPM];
+  __shared__ float s_max[4], s_sum[4];
+  __shared__ float thr_v;
+  __shared__ int thr_i;
+  __shared__ int n_open;
+  __shared__ int open_tile[kOpenList];
+  __shared__ float tile_vals[kTileCols];
+  const int r = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+
+  float v1[PER], v2[PER], v3[PER], ss[PER];
+  int i1[PER], i2[PER];
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    const int t = q * 256 + tid;
+    v1[q] = v2[q] = v3[q] = -INFINITY;
+    ss[q] = 0.f;
+    i1[q] = i2[q] = INT_MAX;
+    if (t < n_tiles) {
+      const float4 a = rec[((size_t)t * rows_pad + r) * 2], b = rec[((size_t)t * rows_pad + r) * 2 + 1];
+      v1[q] = a.x;
+      i1[q] = __float_as_int(a.y);
+      v2[q] = a.z;
+      i2[q] = __float_as_int(a.w);
+      v3[q] = b.x;
+      ss[q] = b.y;
+    }
+  }
+
+  // log-sum-exp pieces of this wavefront
+  float mx = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < PER; ++q) mx = fmaxf(mx, v1[q]);
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  float sum = 0.f;
+#pragma unroll
+  for (int q = 0; q < PER; ++q)
+    if (v1[q] > -INFINITY) sum += ss[q] * __expf(v1[q] - mx);
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+
+  // this wavefront's best m_max of its recorded pairs: m_max rounds of arg-max over each lane's best open pair
+  // (a tile's second value opens when its first has been taken)
+  float cv[PER];
+  int ci[PER];
+#pragma unroll
+  for (int q = 0; q < PER; ++q) {
+    cv[q] = v1[q];
+    ci[q] = i1[q];
+  }
+  uint32_t second = 0u;  // bit q: tile q already gave its first value
+  auto lane_best = [&](float& lb, int& li, int& lq) {
+    lb = -INFINITY;
+    li = INT_MAX;
+    lq = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q)
+      if (beats(cv[q], ci[q], lb, li)) {
+        lb = cv[q];
+        li = ci[q];
+        lq = q;
+      }
+  };
+  float lb;
+  int li, lq;
+  lane_best(lb, li, lq);
+  float ev = -INFINITY;
+  int eid = INT_MAX;
+  for (int i = 0; i < m_max; ++i) {
+    float bv;
+    int bid;
+    const int src = wave_best(lb, li, bv, bid);
+    if (lane == i) {
+      ev = bv;
+      eid = bid;
+    }
+    if (lane == src) {
+#pragma unroll
+      for (int q = 0; q < PER; ++q)
+        if (q == lq) {
+          const bool was_second = (second >> q) & 1u;
+          cv[q] = was_second ? -INFINITY : v2[q];
+          ci[q] = was_second ? INT_MAX : i2[q];
+          second |= 1u << q;
+        }
+      lane_best(lb, li, lq);
+    }
+  }
+  if (lane < m_max) {
+    l_val[wave][lane] = ev;
+    l_id[wave][lane] = eid;
+  }
+  if (lane == 0) {
+    s_max[wave] = mx;
+    s_sum[wave] = sum;
+  }
+  __syncthreads();
+
+  // wavefront 0 merges the four lists (one entry per lane) the same way; from here on it owns the list, lane i
+  // holding the i-th best
+  if (wave == 0) {
+    float xv = -INFINITY;
+    int xi = INT_MAX;
+    if (lane < 4 * m_max) {
+      xv = l_val[lane / m_max][lane % m_max];
+      xi = l_id[lane / m_max][lane % m_max];
+    }
+    ev = -INFINITY;
+    eid = INT_MAX;
+    for (int i = 0; i < m_max; ++i) {
+      float bv;
+      int bid;
+      const int src = wave_best(xv, xi, bv, bid);
+      if (lane == i) {
+        ev = bv;
+        eid = bid;
+      }
+      if (lane == src) {
+        xv = -INFINITY;
+        xi = INT_MAX;
+      }
+    }
+    if (lane == m_max - 1) {
+      thr_v = ev;
+      thr_i = eid;
+    }
+    if (lane == 0) n_open = 0;
+  }
+  __syncthreads();
+
+  // open tiles: recompute and offer, until none is left (a tile is visited at most once)
+  for (;;) {
+    const float tv = thr_v;
+    const int ti = thr_i;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int t = q * 256 + tid;
+      if (t < n_tiles && (v3[q] > tv || (v3[q] == tv && t * kTileCols < ti))) {
+        const int k = atomicAdd(&n_open, 1);
+        if (k < kOpenList) {
+          open_tile[k] = t;
+          v3[q] = -INFINITY;  // visited
+        }
+      }
+    }
+    __syncthreads();
+    const int n_now = n_open < kOpenList ? n_open : kOpenList;
+    if (n_now == 0) break;
+    for (int u = 0; u < n_now; ++u) {
+      const int t = open_tile[u];
+      // the product's arithmetic for this tile and this row's block of 16: wavefront w owns column blocks w and 4 + w
+      const uint16_t* w0 = wp + ((size_t)(t * 8 + wave) * ksteps) * 512 + lane * 8;
+      const uint16_t* w1 = wp + ((size_t)(t * 8 + 4 + wave) * ksteps) * 512 + lane * 8;
+      const uint16_t* xb = xt + ((size_t)(r >> 4) * ksteps) * 512 + lane * 8;
+      lt_f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+      for (int ks = 0; ks < ksteps; ++ks) {
+        const lt_f16x8 a0 = *reinterpret_cast<const lt_f16x8*>(w0 + (size_t)ks * 512);
+        const lt_f16x8 a1 = *reinterpret_cast<const lt_f16x8*>(w1 + (size_t)ks * 512);
+        const lt_f16x8 bx = *reinterpret_cast<const lt_f16x8*>(xb + (size_t)ks * 512);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, bx, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, bx, acc1, 0, 0, 0);
+      }
+      if ((lane & 15) == (r & 15)) {
+        const int g = lane >> 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          tile_vals[wave * 16 + g * 4 + e] = acc0[e];
+          tile_vals[(4 + wave) * 16 + g * 4 + e] = acc1[e];
+        }
+      }
+      __syncthreads();
+      if (wave == 0) {
+        const float4 a = rec[((size_t)t * rows_pad + r) * 2];
+        const int skip1 = __float_as_int(a.y), skip2 = __float_as_int(a.w);  // already in the list (or beaten)
+#pragma unroll
+        for (int h = 0; h < kTileCols / kWave; ++h) {
+          const int id = t * kTileCols + h * kWave + lane;
+          const bool ok = id != skip1 && id != skip2;
+          list_offer(ev, eid, ok ? tile_vals[h * kWave + lane] : -INFINITY, ok ? id : INT_MAX, m_max, lane);
+        }
+      }
+      __syncthreads();
+    }
+    if (wave == 0) {
+      if (lane == m_max - 1) {
+        thr_v = ev;
+        thr_i = eid;
+      }
+      if (lane == 0) n_open = 0;
+    }
+    __syncthreads();
+  }
+  if (wave != 0) return;
+
+  float all_max = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+  float all_sum = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    if (s_max[w] > -INFINITY) all_sum += s_sum[w] * __expf(s_max[w] - all_max);
+  const float lse = all_max + logf(all_sum);
+  const float lp = ev - lse;
+  if (lane < m_max) {
+    cand_id[(size_t)r * m_max + lane] = eid;
+    cand_logp[(size_t)r * m_max + lane] = lp;
+  }
+  int cnt = m_max;
+  if (tau < 1.0f) {
+    float cum = 0.f;
+    bool done = false;
+    for (int i = 0; i < m_max; ++i) {
+      float p = expf(__shfl(lp, i));
+      cum = __fadd_rn(cum, p);
+      if (!done && cum >= tau) {
+        cnt = i + 1;
+        done = true;
+      }
+    }
+  }
+  if (lane == 0) {
+    cand_cnt[r] = cnt;
+    lse_out[r] = lse;
+    eos_logp[r] = (eos_id >= 0) ? eos_logit[r] - lse : 0.f;
+  }
+}
+
 struct ScanPlan {
   int n_seg, tiles_per_seg, n_part;
 };
@@ -508,6 +781,35 @@ int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t
   hipLaunchKernelGGL(accept_merge_kernel, dim3(1), dim3(1024), 0, st, rows, p.n_part, partial, block, path_len,
                      eos_id, n_accept, next_token, argmax, eos_accepted);
   DS_LAUNCH_CHECK("accept_merge_kernel");
+  return DS_OK;
+}
+
+bool lattice_tiles_supported(int n_tiles, int tile_cols) {
+  return tile_cols == kTileCols && n_tiles >= 1 && n_tiles <= 256 * kTilesPerThread;
+}
+
+int launch_lattice_tiles(const void* rec, int rows, int n_tiles, int m_max, float tau, int32_t eos_id,
+                         const float* eos_logit, const void* wp, const void* xt, int K, int32_t* cand_id,
+                         float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse, hipStream_t st) {
+  DS_REQUIRE(rows >= 1 && rows <= DS_MAX_ROWS, DS_E_SHAPE, "lattice rows %d outside [1, %d]", rows, DS_MAX_ROWS);
+  DS_REQUIRE(lattice_tiles_supported(n_tiles, kTileCols), DS_E_SHAPE, "lattice from tile records: %d tiles unsupported",
+             n_tiles);
+  DS_REQUIRE(m_max >= 1 && m_max <= DS_MAX_TOPM, DS_E_SHAPE, "M_max %d outside [1, %d]", m_max, DS_MAX_TOPM);
+  DS_REQUIRE(rec && wp && xt && (K & 31) == 0 && (eos_id < 0 || eos_logit), DS_E_INVALID,
+             "lattice from tile records: missing operand");
+  const int per = ceil_div(n_tiles, 256);
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, dim3(rows), dim3(256), 0, st, static_cast<const float4*>(rec),
+                       ceil_div(rows, 16) * 16, n_tiles, m_max, tau, eos_id, eos_logit,
+                       static_cast<const uint16_t*>(wp), static_cast<const uint16_t*>(xt), K >> 5, cand_id, cand_logp,
+                       cand_cnt, eos_logp, lse);
+  };
+  if (per <= 1) go(lattice_tiles_kernel<1>);
+  else if (per <= 2) go(lattice_tiles_kernel<2>);
+  else if (per <= 3) go(lattice_tiles_kernel<3>);
+  else if (per <= 5) go(lattice_tiles_kernel<5>);
+  else go(lattice_tiles_kernel<kTilesPerThread>);
+  DS_LAUNCH_CHECK("lattice_tiles_kernel");
   return DS_OK;
 }
 

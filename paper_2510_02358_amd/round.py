@@ -99,8 +99,11 @@ class SpecDecoder:
     """One drafter + one verifier on one GPU, both caches holding the same prefix."""
 
     def __init__(self, drafter: DeviceModel, verifier: DeviceModel, table: Optional[np.ndarray], log2_size: int,
-                 params: RoundParams, k_cap: int = 64):
+                 params: RoundParams, k_cap: int = 64, keep_draft_logits: bool = False):
+        """keep_draft_logits: also write the drafter's logits to `d_logits` every round (the lattice does not need
+        them in memory; stochastic verification does and gets them regardless)."""
         self.d, self.v, self.p = drafter, verifier, params
+        self.keep_draft_logits = keep_draft_logits
         self.eos_id = drafter.cfg.eos_id
         self.mask_id = drafter.cfg.mask_id
         vocab = drafter.cfg.vocab
@@ -116,7 +119,6 @@ class SpecDecoder:
         self.cand_cnt = torch.empty(k_cap, dtype=i32, device=DEV)
         self.eos_logp = torch.empty(k_cap, dtype=f32, device=DEV)
         self.lse = torch.empty(k_cap, dtype=f32, device=DEV)
-        self.lat_ws = torch.empty(ds.ds_lattice_workspace_bytes(k_cap, vocab, m), dtype=torch.uint8, device=DEV)
         self.cps_ws = torch.empty(ds.ds_cps_workspace_bytes(1, k_cap, m), dtype=torch.uint8, device=DEV)
         self.block = torch.zeros(k_cap + 1, dtype=i32, device=DEV)       # [last token, path...]
         # proxy context (2 ints) and pending tokens share one staging tensor: one host -> device copy per round
@@ -190,18 +192,18 @@ class SpecDecoder:
         vocab = self.d.cfg.vocab
         lat = (self.cand_id, self.cand_logp, self.cand_cnt, self.eos_logp, self.lse)
         sizes = refine_update_sizes(k, p.refine_steps)
+        logits_out = self.d_logits if (self.keep_draft_logits or uniforms is not None) else None
         if len(sizes) <= 1:
             ds.ds_draft_block(self.d.handle, self.pending_dev, n_pend, k, self.mask_id, self.hidden, self.d.ws, stream)
-            ds.ds_lm_head(self.d.handle, None, k, self.d_logits, self.d.ws, stream)
-            ds.ds_build_lattice(self.d_logits, k, vocab, p.m_max, p.tau, self.eos_id, *lat, self.lat_ws, stream)
+            ds.ds_draft_lattice(self.d.handle, None, k, p.m_max, p.tau, self.eos_id, *lat, logits_out, self.d.ws, stream)
         else:
             self.blk[:k].fill_(self.mask_id)
             final = (self.f_cand_id, self.f_cand_logp, self.f_cand_cnt, self.f_eos_logp, self.f_lse)
             for s, n in enumerate(sizes):
                 ds.ds_draft_block_tokens(self.d.handle, self.pending_dev if s == 0 else None, n_pend if s == 0 else 0,
                                          self.blk, k, self.hidden, self.d.ws, stream)
-                ds.ds_lm_head(self.d.handle, None, k, self.d_logits, self.d.ws, stream)
-                ds.ds_build_lattice(self.d_logits, k, vocab, p.m_max, p.tau, self.eos_id, *lat, self.lat_ws, stream)
+                ds.ds_draft_lattice(self.d.handle, None, k, p.m_max, p.tau, self.eos_id, *lat, logits_out, self.d.ws,
+                                    stream)
                 ds.ds_refine_select(*lat, k, p.m_max, n, self.mask_id, self.blk, *final, stream)
             lat = final
         ds.ds_cps_path(lat[0], lat[1], lat[2], lat[3], 1, k, p.m_max, p.beam, p.lam, self.proxy, self.ctx, self.eos_id,

@@ -89,6 +89,21 @@ class GpuModel:
         ds.ds_lm_head(self.handle, hidden, rows, logits, self.ws)
         return logits
 
+    def draft_lattice(self, hidden, rows: int, m_max: int, tau: float, eos_id: int, want_logits: bool = True) -> dict:
+        """ds_draft_lattice; hidden None = the block rows of the preceding draft pass.  Device tensors."""
+        out = {
+            "cand_id": torch.empty(rows, m_max, dtype=torch.int32, device=DEV),
+            "cand_logp": torch.empty(rows, m_max, dtype=torch.float32, device=DEV),
+            "cand_cnt": torch.empty(rows, dtype=torch.int32, device=DEV),
+            "eos_logp": torch.empty(rows, dtype=torch.float32, device=DEV),
+            "lse": torch.empty(rows, dtype=torch.float32, device=DEV),
+        }
+        logits = torch.empty(rows, self.cfg.vocab, dtype=torch.float32, device=DEV) if want_logits else None
+        ds.ds_draft_lattice(self.handle, hidden, rows, m_max, tau, eos_id, out["cand_id"], out["cand_logp"],
+                            out["cand_cnt"], out["eos_logp"], out["lse"], logits, self.ws)
+        torch.cuda.synchronize()
+        return out, logits
+
     def verify(self, block, path_len=None, eos_id: int = -1, want_logits: bool = True):
         blk = block if isinstance(block, torch.Tensor) else to_dev(np.asarray(block, dtype=np.int32))
         rows = blk.shape[0]

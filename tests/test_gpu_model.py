@@ -11,6 +11,7 @@ import pytest
 import torch
 
 from oracle import accept as o_accept
+from oracle import lattice as o_lat
 from oracle import model as o_model
 from paper_2510_02358_amd import binding as ds
 from paper_2510_02358_amd import synth
@@ -284,6 +285,100 @@ def test_bf16_verify_argmax_comes_from_the_lm_head_epilogue():
         row = full["logits"][r]
         ties += int(np.sum(row == row[first_max[r]]) > 1)
     assert ties >= 8, "the planted duplicates must produce exact ties"
+
+
+LSE_TOL = 1e-5
+
+
+def _check_fused_lattice(gm, hidden, rows, m_max, tau, eos_id):
+    """ds_draft_lattice with and without the logits written: identical outputs; candidates, counts and log-scores
+    are those the oracle builds from the logits the same call returned (ids / counts exact, float values 1e-5);
+    and log-score == logit - lse exactly in float32."""
+    full, logits = gm.draft_lattice(hidden, rows, m_max, tau, eos_id, want_logits=True)
+    bare, _ = gm.draft_lattice(hidden, rows, m_max, tau, eos_id, want_logits=False)
+    for k in full:
+        assert torch.equal(full[k], bare[k]), k
+    lg = gu.from_dev(logits)
+    ref = o_lat.build_lattice(lg, m_max, tau, eos_id)
+    g = {k: gu.from_dev(v) for k, v in full.items()}
+    assert np.array_equal(g["cand_id"], ref["cand_id"])
+    assert np.array_equal(g["cand_cnt"], ref["cand_cnt"])
+    for k in ("lse", "cand_logp", "eos_logp"):
+        assert np.max(np.abs(g[k] - ref[k])) <= LSE_TOL, k
+    assert np.array_equal(g["cand_logp"], lg[np.arange(rows)[:, None], g["cand_id"]] - g["lse"][:, None])
+    return g, lg
+
+
+def test_bf16_lattice_from_the_lm_head_epilogue():
+    """The fused LM head + lattice call on a bf16 model, against the oracle's lattice of the same logits:
+    ordinary rows; rows whose best tokens all sit inside one 128-id tile (the tile is recomputed), with exact ties
+    inside the cluster; an all-zero hidden row (every logit equal: ids 0 .. M-1); EOS inside and outside the
+    cluster; M = 1, 8, 16; pruning on and off; 1, 33 and 144 rows."""
+    cfg = SMALL_BF16
+    w = dict(synth.make_weights(cfg, 95))
+    lm = np.array(w["lm_head"], copy=True).astype(np.float32)
+    rng = np.random.default_rng(96)
+    u = rng.standard_normal(cfg.d_model).astype(np.float32)
+    u /= np.linalg.norm(u)
+    base = 5 * 128 + 40                       # a cluster of 12 ids inside tile 5
+    for k in range(12):
+        lm[base + k] = (0.30 + 0.01 * (k % 7)) * u      # (k % 7): ids base + 0 / + 7, + 1 / + 8 ... tie exactly
+    lm[7 * 128 + 3] = 0.33 * u                # and one strong id in another tile
+    w["lm_head"] = synth.round_to_bf16(lm)
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        for rows in (1, 33, 144):
+            hid = rng.standard_normal((rows, cfg.d_model)).astype(np.float32)
+            hid[::3] += 40.0 * u              # every third row lights the cluster up
+            if rows > 4:
+                hid[4] = 0.0                  # all logits equal
+            for m_max, tau, eos in ((8, 1.0, base + 2), (16, 0.9, 3000), (1, 1.0, -1), (8, 0.5, 7 * 128 + 3)):
+                g, lg = _check_fused_lattice(gm, gu.to_dev(hid), rows, m_max, tau, eos)
+                if m_max == 8:
+                    top = g["cand_id"][0]
+                    assert np.sum((top >= 5 * 128) & (top < 6 * 128)) >= 7, "row 0 must draw from the cluster"
+                    if rows > 4:
+                        assert list(g["cand_id"][4]) == list(range(8))
+        # straight after a draft pass (hidden = NULL), as the round calls it
+        gm.prefill(synth.make_prefix(cfg, 50, 97), want_logits=False)
+        gm.draft([3], 21)
+        g, lg = _check_fused_lattice(gm, None, 21, 8, 0.95, cfg.eos_id)
+        gm.verify(np.array([1, 2], np.int32))
+        with pytest.raises(ds.DsError) as e:
+            gm.draft_lattice(None, 21, 8, 0.95, cfg.eos_id)
+        assert e.value.code == ds.DS_E_INVALID
+    finally:
+        gm.close()
+
+
+def test_f32_fused_call_equals_the_two_separate_calls():
+    cfg = synth.CFG_TINY
+    w = synth.make_weights(cfg, 98)
+    gm = gu.GpuModel(cfg, w, 128)
+    try:
+        gm.prefill(synth.make_prefix(cfg, 30, 99), want_logits=False)
+        hid = gm.draft([2], 9)
+        fused, logits = gm.draft_lattice(None, 9, 4, 0.9, cfg.eos_id)
+        sep = gu.gpu_lattice(gm.lm_head(hid), 4, 0.9, cfg.eos_id)
+        for k in fused:
+            assert torch.equal(fused[k], sep[k]), k
+    finally:
+        gm.close()
+
+
+def test_7b_layer_bf16_fused_lattice_full_vocabulary():
+    """LM head 152064 x 3584 (1188 tiles), 32 rows, top-8 and top-16, straight after a draft pass."""
+    cfg = synth.CFG_7B_LAYER
+    w = synth.make_weights(cfg, 0)
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        gm.prefill(synth.make_prefix(cfg, 100, 2), want_logits=False)
+        gm.draft([11], 32)
+        _check_fused_lattice(gm, None, 32, 8, 0.9, cfg.eos_id)
+        gm.draft([], 32)
+        _check_fused_lattice(gm, None, 32, 16, 1.0, -1)
+    finally:
+        gm.close()
 
 
 def test_7b_layer_bf16_prefix2048_k32():

@@ -36,7 +36,7 @@ def test_tiny_pair_rounds_match_oracle_and_are_lossless(lam, tau):
     m_max, beam, n_rounds, k1 = 4, 4, 6, 8
     params = rnd.RoundParams(m_max=m_max, tau=tau, beam=beam, lam=lam, k_min=2, k_max=12, delta=2.0, rho=0.5)
     dm, vm = rnd.DeviceModel(cfg, dw, 256), rnd.DeviceModel(cfg, vw, 256)
-    dec = rnd.SpecDecoder(dm, vm, table, synth.NGRAM_LOG2_SIZE, params, k_cap=16)
+    dec = rnd.SpecDecoder(dm, vm, table, synth.NGRAM_LOG2_SIZE, params, k_cap=16, keep_draft_logits=True)
     try:
         dec.start(prefix)
         st = o_round.SpecState(cfg, dw, cfg, vw, prefix)
@@ -70,6 +70,41 @@ def test_tiny_pair_rounds_match_oracle_and_are_lossless(lam, tau):
             assert produced == ref_stream
     finally:
         dec.close(); dm.close(); vm.close()
+
+
+def test_bf16_rounds_do_not_depend_on_the_logits_being_written():
+    """Two decoders on the same small bf16 pair, one keeping the drafter's logits in memory and one not (the lattice
+    then comes from the LM-head product's tile records alone), walk through the same rounds with identical lattices,
+    paths and verdicts; and the lattice is the oracle's lattice of the logits the first decoder kept."""
+    from oracle import lattice as o_lat
+    cfg = synth.ModelCfg(n_layers=2, d_model=256, n_q=4, n_kv=2, head_dim=128, d_ffn=512, vocab=4096,
+                         rope_base=1.0e6, dtype="bf16")
+    dw, vw = synth.make_weights(cfg, 10), synth.make_weights(cfg, 11)
+    prefix = synth.make_prefix(cfg, 100, 12)
+    table = synth.make_ngram_table(3)
+    params = rnd.RoundParams(m_max=8, tau=0.95, beam=4, lam=0.5, k_min=4, k_max=32, delta=2.0, rho=0.5)
+    models = [rnd.DeviceModel(cfg, w, 512) for w in (dw, vw, dw, vw)]
+    a = rnd.SpecDecoder(models[0], models[1], table, synth.NGRAM_LOG2_SIZE, params, k_cap=32, keep_draft_logits=True)
+    b = rnd.SpecDecoder(models[2], models[3], table, synth.NGRAM_LOG2_SIZE, params, k_cap=32)
+    try:
+        a.start(prefix)
+        b.start(prefix)
+        k = 21
+        for t in range(6):
+            ga, gb = a.round(k), b.round(k)
+            for name in ("cand_id", "cand_logp", "cand_cnt", "eos_logp", "lse"):
+                assert torch.equal(getattr(a, name)[:k], getattr(b, name)[:k]), (t, name)
+            assert list(ga["path"]) == list(gb["path"]) and ga["n_accept"] == gb["n_accept"]
+            assert ga["next_token"] == gb["next_token"] and ga["k_next"] == gb["k_next"]
+            assert a.tokens == b.tokens
+            ref = o_lat.build_lattice(a.d_logits[:k].cpu().numpy(), params.m_max, params.tau, cfg.eos_id)
+            assert np.array_equal(a.cand_id[:k].cpu().numpy(), ref["cand_id"])
+            assert np.array_equal(a.cand_cnt[:k].cpu().numpy(), ref["cand_cnt"])
+            k = ga["k_next"]
+    finally:
+        a.close(); b.close()
+        for m in models:
+            m.close()
 
 
 def test_forced_greedy_path_is_fully_accepted_on_gpu():
