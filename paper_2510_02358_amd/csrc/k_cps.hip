@@ -150,7 +150,14 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
   if (PRE && g) {  // scores were gathered by cps_gather_kernel: plain copy into LDS
     const int total = K * CM * CM * CM;
     const float* src = g + (size_t)seq * total;
-    for (int idx = tid; idx < total; idx += n_thr) L.ng[idx] = src[idx];
+    if ((total & 3) == 0 && (((uintptr_t)src | (uintptr_t)L.ng) & 15) == 0) {  // 16 bytes per load, several in flight
+      const float4* src4 = reinterpret_cast<const float4*>(src);
+      float4* dst4 = reinterpret_cast<float4*>(L.ng);
+#pragma unroll 4
+      for (int idx = tid; idx < total / 4; idx += n_thr) dst4[idx] = src4[idx];
+    } else {
+      for (int idx = tid; idx < total; idx += n_thr) L.ng[idx] = src[idx];
+    }
   } else if (PRE) {  // gather here: proxy score of every (u, v, w) the search can ask for
     const int pairs = K * CM * CM;
     for (int p = tid; p < pairs; p += n_thr) {
@@ -221,9 +228,17 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
       }
     }
 
-    // keep the best B by (score descending, expansion index ascending); survivors (not ending in EOS)
-    // are written straight into the next beam by the lane that owns the winning expansion
+    // keep the best B by (score descending, expansion index ascending).  Each selection round only marks its
+    // winner (the owning lane notes the beam slot it will fill, or that it ended in EOS and is dropped); the
+    // survivors are written to the next beam in one go after the last round, so a round is a short branch-free
+    // chain: wavefront maximum, first lane at the maximum, a few scalar operations.
     const int n_keep = n_exp < B ? n_exp : B;
+    int e_par[kSlots], e_dst[kSlots];  // parent of this expansion; beam slot it won (-1: none)
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j) {
+      e_par[j] = (int)(((uint32_t)(lane + j * kWave) * inv) >> 16);
+      e_dst[j] = -1;
+    }
     int live = 0;
     for (int r = 0; r < n_keep; ++r) {
       uint32_t best_bits = 0;
@@ -261,25 +276,26 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
         finished = true;
         break;
       }
-      if (lane == owner) {
 #pragma unroll
-        for (int j = 0; j < kSlots; ++j)
-          if (j == slot) {
-            e_bits[j] = 0u;  // taken
-            if (!is_eos) {
-              nxt[live] = make_int4((int)__float_as_uint(e_score[j]), e_v[j], e_tok[j], e_rank[j]);
-              L.bp_tok[i * B + live] = e_tok[j];
-              L.bp_par[i * B + live] = (uint8_t)par;
-            }
-          }
+      for (int j = 0; j < kSlots; ++j) {
+        const bool mine = lane == owner && j == slot;
+        e_bits[j] = mine ? 0u : e_bits[j];                     // taken
+        e_dst[j] = (mine && !is_eos) ? live : e_dst[j];
       }
-      if (!is_eos) {
-        if (live == 0 && i == K - 1) out_score = __uint_as_float(top & 0x80000000u ? (top & 0x7FFFFFFFu) : ~top);
-        ++live;
-      }
+      live += is_eos ? 0 : 1;
     }
+    if (finished) break;
+#pragma unroll
+    for (int j = 0; j < kSlots; ++j)
+      if (e_dst[j] >= 0) {
+        nxt[e_dst[j]] = make_int4((int)__float_as_uint(e_score[j]), e_v[j], e_tok[j], e_rank[j]);
+        L.bp_tok[i * B + e_dst[j]] = e_tok[j];
+        L.bp_par[i * B + e_dst[j]] = (uint8_t)e_par[j];
+      }
     n_live = live;
   }
+  // the search ran to the end: the result is the best live hypothesis of the last step
+  if (!finished && n_live > 0) out_score = __uint_as_float((uint32_t)L.beam[(K & 1) * B].x);
 
   // back-track (lane 0 reads what other lanes of this wavefront wrote: LDS operations complete in order)
   if (lane == 0) {

@@ -100,6 +100,9 @@ def test_bad_arguments_are_rejected_on_the_host_before_any_launch():
     assert lib.ds_lm_head(None, None, 4, one, one, 1 << 20, None) == ds.DS_E_INVALID
     assert lib.ds_draft_lattice(None, None, 4, 8, 1.0, -1, one, one, one, one, one, None, one, 1 << 20,
                                 None) == ds.DS_E_INVALID
+    assert lib.ds_lm_head_tiles(None, None, 4, -1, None, one, 1 << 20, None) == ds.DS_E_INVALID
+    assert lib.ds_lattice_from_tiles(None, 4, 8, 1.0, -1, one, one, one, one, one, one, 1 << 20,
+                                     None) == ds.DS_E_INVALID
     # model configuration
     cfg = ds.ModelCfgC(1, 3584, 28, 4, 128, 18944, 152064, 1e6, 1e-6, ds.DS_BF16, 4096)
     assert ds.ds_model_packed_bytes(cfg) == (233046016 + 544997376) * 2 + 256   # + weight-range flag

@@ -347,6 +347,25 @@ def test_bf16_lattice_from_the_lm_head_epilogue():
         with pytest.raises(ds.DsError) as e:
             gm.draft_lattice(None, 21, 8, 0.95, cfg.eos_id)
         assert e.value.code == ds.DS_E_INVALID
+        # the two-step form: the second step must follow the first with the same rows and EOS id
+        hid = gu.to_dev(rng.standard_normal((9, cfg.d_model)).astype(np.float32))
+        outs = [torch.empty(9, 8, dtype=torch.int32, device=gu.DEV), torch.empty(9, 8, device=gu.DEV),
+                torch.empty(9, dtype=torch.int32, device=gu.DEV), torch.empty(9, device=gu.DEV),
+                torch.empty(9, device=gu.DEV)]
+        for bad_rows, bad_eos, between in ((8, 5, None), (9, 6, None), (9, 5, "forward"), (9, 5, "lm_head")):
+            ds.ds_lm_head_tiles(gm.handle, hid, 9, 5, None, gm.ws)
+            if between == "forward":
+                gm.verify(np.array([1, 2], np.int32))
+            elif between == "lm_head":
+                gm.lm_head(hid)
+            with pytest.raises(ds.DsError) as e:
+                ds.ds_lattice_from_tiles(gm.handle, bad_rows, 8, 1.0, bad_eos, *outs, gm.ws)
+            assert e.value.code == ds.DS_E_INVALID
+        ds.ds_lm_head_tiles(gm.handle, hid, 9, 5, None, gm.ws)
+        ds.ds_lattice_from_tiles(gm.handle, 9, 8, 1.0, 5, *outs, gm.ws)
+        one_call, _ = gm.draft_lattice(hid, 9, 8, 1.0, 5, want_logits=False)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0], one_call["cand_id"]) and torch.equal(outs[4], one_call["lse"])
     finally:
         gm.close()
 
