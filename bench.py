@@ -362,22 +362,26 @@ def main() -> int:
     stream = rnd.ar_greedy(vm, prefix, n_rounds_inj * 8 + K_DRAFT + 8, timing=ar_t)
     ar_tok_s = ar_t["steps"] / (ar_t["decode_ms"] * 1e-3)
     stream_dev = rnd.upload(np.asarray(stream, dtype=np.int32))
-    dec.start(prefix)
-    rng = np.random.default_rng(5)
-    torch.cuda.synchronize()
-    i0 = time.perf_counter()
-    n_tok, n_acc_sum, n_done = 0, 0, 0
-    for _ in range(n_rounds_inj):
-        done = len(dec.tokens) - len(prefix)
-        if done + K_DRAFT + 1 >= len(stream):
-            break
-        a = int(min(K_DRAFT, rng.geometric(1.0 / 7.0) - 1))
-        got = dec.round(K_DRAFT, inject=(stream_dev[done:done + a], a))
-        n_tok += got["n_accept"] + 1
-        n_acc_sum += got["n_accept"]
-        n_done += 1
-    torch.cuda.synchronize()
-    inj_el = time.perf_counter() - i0
+    def injected_loop():
+        dec.start(prefix)
+        rng = np.random.default_rng(5)
+        torch.cuda.synchronize()
+        i0 = time.perf_counter()
+        n_tok, n_acc_sum, n_done = 0, 0, 0
+        for _ in range(n_rounds_inj):
+            done = len(dec.tokens) - len(prefix)
+            if done + K_DRAFT + 1 >= len(stream):
+                break
+            a = int(min(K_DRAFT, rng.geometric(1.0 / 7.0) - 1))
+            got = dec.round(K_DRAFT, inject=(stream_dev[done:done + a], a))
+            n_tok += got["n_accept"] + 1
+            n_acc_sum += got["n_accept"]
+            n_done += 1
+        torch.cuda.synchronize()
+        return n_tok, n_acc_sum, n_done, time.perf_counter() - i0
+
+    injected_loop()  # untimed pass: the pending-row counts of this loop launch kernel variants not loaded so far
+    n_tok, n_acc_sum, n_done, inj_el = injected_loop()
     lossless = dec.tokens[len(prefix):] == stream[:len(dec.tokens) - len(prefix)]
     out["synthetic_acceptance"] = {
         "rounds": n_done, "mean_accepted_per_round": round(n_acc_sum / max(n_done, 1), 2),
