@@ -1,5 +1,5 @@
-// Model handle and the forward passes behind ds_prefill / ds_draft_block / ds_lm_head /
-// ds_verify_block.  Host code only orchestrates: every arithmetic step runs in a kernel.
+// Model handle and the forward passes behind ds_prefill / ds_draft_block / ds_lm_head / ds_lm_head_tiles /
+// ds_lattice_from_tiles / ds_verify_block.  Host code only orchestrates: every arithmetic step runs in a kernel.
 #include <math.h>
 #include <string.h>
 

@@ -1,11 +1,15 @@
-// Vocabulary-wide scans: token lattice (log-sum-exp + per-row top-M) and greedy acceptance
-// (per-row arg-max, compare with the drafted path, longest accepted prefix).
+// Token lattice (log-sum-exp + per-row top-M) and greedy acceptance (per-row arg-max, compare with the drafted
+// path, longest accepted prefix), each in two forms.
 //
-// Both are one pass over the float32 logits, 4 bytes per logit, HBM-bound.  A row is cut into
-// segments so that even a few rows fill the chip; every wavefront keeps its running top-M as a
-// sorted list spread over its lanes (lane i holds the i-th best) and only touches it when some
-// lane's value beats the current M-th best, which becomes rare after the first few hundred values.
-// A second tiny kernel merges the per-wavefront partial results of each row.
+// From logits in memory (any caller-supplied logits; float32 models): one pass over the float32 logits, 4 bytes per
+// logit, HBM-bound.  A row is cut into segments so that even a few rows fill the chip; every wavefront keeps its
+// running top-M as a sorted list spread over its lanes (lane i holds the i-th best) and only touches it when some
+// lane's value beats the current M-th best, which becomes rare after the first few hundred values.  A second tiny
+// kernel merges the per-wavefront partial results of each row.
+//
+// From the LM-head product's per-tile records (the round's path on bf16 models): the product's epilogue has already
+// reduced every 128-column tile to a few numbers per row, so the logits are never written or read; see
+// lattice_tiles_kernel and accept_tiles_kernel.
 #include <limits.h>
 #include <math.h>
 

@@ -370,6 +370,29 @@ def test_bf16_lattice_from_the_lm_head_epilogue():
         gm.close()
 
 
+def test_bf16_vocabulary_that_the_tile_records_do_not_cover():
+    """vocab = 4096 + 16 is a multiple of 16 (so the bf16 product runs) but not of 128: the LM head ends in a
+    half-size workgroup, the record epilogues do not apply, and both the fused lattice call and the verifier fall
+    back to the stored logits with unchanged results."""
+    cfg = dataclasses.replace(SMALL_BF16, vocab=4096 + 16)
+    w = synth.make_weights(cfg, 110)
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        gm.prefill(synth.make_prefix(cfg, 40, 111), want_logits=False)
+        gm.draft([5, 6], 19)
+        _check_fused_lattice(gm, None, 19, 8, 0.9, cfg.eos_id)
+        block = np.random.default_rng(112).integers(0, cfg.n_plain_tokens, 20).astype(np.int32)
+        full = gm.verify(block)
+        gm.set_kv_len(42)
+        bare = gm.verify(block, want_logits=False)
+        assert np.array_equal(full["argmax"], np.argmax(full["logits"], axis=1))
+        assert np.array_equal(full["argmax"], bare["argmax"]) and full["n_accept"] == bare["n_accept"]
+        ref = o_model.lm_head(w, np.zeros((1, cfg.d_model)))
+        assert ref.shape[1] == cfg.vocab
+    finally:
+        gm.close()
+
+
 def test_f32_fused_call_equals_the_two_separate_calls():
     cfg = synth.CFG_TINY
     w = synth.make_weights(cfg, 98)
