@@ -114,17 +114,25 @@ class SpecDecoder:
         i32, f32 = torch.int32, torch.float32
         self.hidden = torch.empty(k_cap, drafter.cfg.d_model, dtype=torch.float32, device=DEV)
         self.d_logits = torch.empty(k_cap, vocab, dtype=f32, device=DEV)
-        self.cand_id = torch.empty(k_cap, m, dtype=i32, device=DEV)
         self.cand_logp = torch.empty(k_cap, m, dtype=f32, device=DEV)
         self.cand_cnt = torch.empty(k_cap, dtype=i32, device=DEV)
         self.eos_logp = torch.empty(k_cap, dtype=f32, device=DEV)
         self.lse = torch.empty(k_cap, dtype=f32, device=DEV)
         self.cps_ws = torch.empty(ds.ds_cps_workspace_bytes(1, k_cap, m), dtype=torch.uint8, device=DEV)
-        self.block = torch.zeros(k_cap + 1, dtype=i32, device=DEV)       # [last token, path...]
-        # proxy context (2 ints) and pending tokens share one staging tensor: one host -> device copy per round
-        self.stage = torch.zeros(2 + ds.DS_MAX_ROWS, dtype=i32, device=DEV)
-        self.ctx = self.stage[0:2]
-        self.path_len = torch.zeros(1, dtype=i32, device=DEV)
+        # Everything the host sends per round (pending tokens, proxy context) and reads back per round (searched path,
+        # its length, the candidate ids) lives in ONE device tensor, so that a round costs one host -> device and one
+        # device -> host copy:   [pending, right-aligned | ctx0 | ctx1 = block[0] | path ... | path_len | pad | cand_id]
+        # The last committed token is both the newer context token and the first row of the verify block.
+        P = ds.DS_MAX_ROWS
+        self._p = P
+        self._out0 = P + 2                                   # first int the host reads back
+        self._len_at = P + 2 + k_cap
+        self._cand_at = (self._len_at + 1 + 3) // 4 * 4       # 16-byte aligned
+        self.io = torch.zeros(self._cand_at + k_cap * m, dtype=i32, device=DEV)
+        self.ctx = self.io[P:P + 2]
+        self.block = self.io[P + 1:P + 2 + k_cap]             # [last token, path...]
+        self.path_len = self.io[self._len_at:self._len_at + 1]
+        self.cand_id = self.io[self._cand_at:].view(k_cap, m)
         self.path_score = torch.zeros(1, dtype=f32, device=DEV)
         # n_accept, next_token, eos_accepted: pinned host memory (device-visible), so that the acceptance kernel
         # writes the round's verdict where the host reads it after the stream sync, without a copy in between
@@ -140,10 +148,10 @@ class SpecDecoder:
         # stochastic verification: uniforms in, acceptance probabilities out
         self.u = torch.zeros(k_cap + 1, dtype=f32, device=DEV)
         self.alpha = torch.zeros(k_cap, dtype=f32, device=DEV)
-        self.pending_dev = self.stage[2:]
-        self.host = torch.empty(3 + ds.DS_MAX_ROWS, dtype=i32).pin_memory()
+        self.host = torch.empty(2 + ds.DS_MAX_ROWS, dtype=i32).pin_memory()
         self.host_np = self.host.numpy()
-        self.host_out = torch.empty(4 + 2 * k_cap, dtype=i32).pin_memory()   # result(3), path_len, path, raw draft
+        self.host_out = torch.empty(self.io.numel() - self._out0, dtype=i32).pin_memory()   # io[_out0:] as the host sees it
+        self.host_raw0 = torch.empty(k_cap, dtype=i32).pin_memory()          # refinement rounds: the final lattice's top-1
         self.k_cap = k_cap
         self.tokens: List[int] = []
         self.pending: List[int] = []
@@ -221,16 +229,20 @@ class SpecDecoder:
                                           self.eos_id, self.result[0:1], self.result[1:2], self.result[2:3],
                                           self.alpha, None, self.v.ws, stream)
 
+    @property
+    def pending_dev(self) -> torch.Tensor:
+        """Device view of the pending tokens (the tokens committed since the drafter last ran)."""
+        return self.io[self._p - len(self.pending):self._p]
+
     def stage_inputs(self) -> None:
-        """Host -> device: proxy context, pending tokens, last committed token (a few ints, two async copies)."""
+        """Host -> device: pending tokens and the proxy context (whose newer token is also the first row of the
+        verify block): a few ints, one async copy."""
         n = len(self.pending)
         h = self.host_np
-        h[0] = self.tokens[-2]
-        h[1] = self.tokens[-1]
-        h[2:2 + n] = self.pending
-        h[2 + n] = self.tokens[-1]
-        self.stage[:2 + n].copy_(self.host[:2 + n], non_blocking=True)
-        self.block[0:1].copy_(self.host[2 + n:3 + n], non_blocking=True)
+        h[:n] = self.pending
+        h[n] = self.tokens[-2]
+        h[n + 1] = self.tokens[-1]
+        self.io[self._p - n:self._p + 2].copy_(self.host[:n + 2], non_blocking=True)
 
     def round(self, k: int, inject=None, uniforms=None) -> dict:
         """One full round including the host read-back, KV commit and the draft-length update."""
@@ -243,17 +255,21 @@ class SpecDecoder:
             self.u[:k + 1].copy_(uniforms if isinstance(uniforms, torch.Tensor)
                                  else torch.from_numpy(np.asarray(uniforms, dtype=np.float32)), non_blocking=False)
         self.enqueue_round(k, inject=inject, uniforms=self.u if uniforms is not None else None)
-        # one host crossing: three small async copies into pinned memory, then a single stream sync
-        ho = self.host_out
-        ho[3:4].copy_(self.path_len, non_blocking=True)
-        ho[4:4 + k].copy_(self.block[1:1 + k], non_blocking=True)
-        ho[4 + self.k_cap:4 + self.k_cap + k].copy_(self.lat_used[0][:k, 0], non_blocking=True)
+        # one host crossing: one small async copy into pinned memory (path, its length, candidate ids), one stream sync
+        refined = self.lat_used[0] is not self.cand_id
+        self.host_out.copy_(self.io[self._out0:], non_blocking=True)
+        if refined:
+            self.host_raw0[:k].copy_(self.lat_used[0][:k, 0], non_blocking=True)
         torch.cuda.current_stream().synchronize()
-        out = ho.numpy()
+        out = self.host_out.numpy()
         res = self.result.numpy()
-        n_acc, nxt, eos, plen = int(res[0]), int(res[1]), int(res[2]), int(out[3])
-        path = out[4:4 + plen].copy()
-        raw0 = out[4 + self.k_cap:4 + self.k_cap + k]
+        n_acc, nxt, eos, plen = int(res[0]), int(res[1]), int(res[2]), int(out[self._len_at - self._out0])
+        path = out[:plen].copy()
+        if refined:
+            raw0 = self.host_raw0.numpy()[:k]
+        else:
+            c0 = self._cand_at - self._out0
+            raw0 = out[c0:c0 + k * self.p.m_max:self.p.m_max]
         self.v.set_kv_len(v_len + 1 + n_acc)
         committed = [int(t) for t in path[:n_acc]] + [nxt]
         self.tokens += committed
