@@ -421,6 +421,28 @@ def test_7b_layer_bf16_fused_lattice_full_vocabulary():
         _check_fused_lattice(gm, None, 32, 16, 1.0, -1)
     finally:
         gm.close()
+    # the same shape with a planted run of strong neighbouring ids (tile 700) and one exact tie inside it: rows that
+    # light the run up have their whole top-8 in one tile, which the kernel must recompute (112 k-steps, 5 records
+    # per thread)
+    w = dict(w)
+    lm = np.array(w["lm_head"], copy=True)
+    rng = np.random.default_rng(7)
+    u = rng.standard_normal(cfg.d_model).astype(np.float32)
+    u /= np.linalg.norm(u)
+    base = 700 * 128 + 100
+    for k in range(12):
+        lm[base + k] = (0.30 + 0.01 * (k % 9)) * u
+    w["lm_head"] = synth.round_to_bf16(lm)
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        hid = rng.standard_normal((33, cfg.d_model)).astype(np.float32)
+        hid[::2] += 60.0 * u
+        g, lg = _check_fused_lattice(gm, gu.to_dev(hid), 33, 8, 0.9, base + 3)
+        top = g["cand_id"][0]
+        assert np.all((top >= 700 * 128) & (top < 701 * 128)), "row 0 must draw its whole top-8 from the planted run"
+        assert not np.any((g["cand_id"][1] >= base) & (g["cand_id"][1] < base + 12))
+    finally:
+        gm.close()
 
 
 def test_7b_layer_bf16_prefix2048_k32():
