@@ -116,7 +116,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_rows_kernel(const float* __
     for (int j = 0; j < kUnroll; ++j) {
       const int i0 = base + j * (kWave * 4) + lane * 4;
       if (vec && i0 + 3 < vocab) {
-        float4 q = *reinterpret_cast<const float4*>(rowp + i0);
+        typedef float vec4 __attribute__((ext_vector_type(4)));
+        const vec4 q = __builtin_nontemporal_load(reinterpret_cast<const vec4*>(rowp + i0));  // read once
         v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
       } else {
 #pragma unroll
