@@ -43,31 +43,80 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return s;
 }
 
-// lse[b] = log sum exp of one logits row.  Workgroup b < n_p takes verifier row b, the others drafter row b - n_p.
-// Two passes over the row (max, then sum of exp), 16 bytes per lane and load where the row allows it.
-__global__ __launch_bounds__(kStatThreads) void row_lse_kernel(const float* __restrict__ p_logits, int n_p,
-                                                              const float* __restrict__ q_logits, int vocab,
-                                                              float* __restrict__ lse) {
-  __shared__ float red[kStatThreads / 64];
-  const int b = blockIdx.x;
+// Log-sum-exp of the logits rows, in two steps so that a handful of rows still fills the chip: every row is cut
+// into kLseSeg equal segments of whole float4 groups (the last one also takes the tail); workgroup (b, g) leaves
+// (max, sum of exp(x - max)) of segment g of row b in part[b][g]; the acceptance kernel combines the kLseSeg pairs
+// of a row in segment order.  Row b < n_p is verifier row b, the others drafter row b - n_p.
+constexpr int kLseSeg = 8;
+constexpr int kLseThreads = 256;
+
+__global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const float* __restrict__ p_logits, int n_p,
+                                                             const float* __restrict__ q_logits, int vocab,
+                                                             float2* __restrict__ part) {
+  __shared__ float red[kLseThreads / 64];
+  const int b = blockIdx.x, g = blockIdx.y;
   const float* row = b < n_p ? p_logits + (size_t)b * vocab : q_logits + (size_t)(b - n_p) * vocab;
   const bool vec = (vocab & 3) == 0 && (((uintptr_t)row) & 15) == 0;
-  const int n4 = vec ? vocab >> 2 : 0;
-  float mx = -INFINITY;
-  for (int i = threadIdx.x; i < n4; i += kStatThreads) {
-    const float4 v = reinterpret_cast<const float4*>(row)[i];
-    mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+  // segment bounds in elements: multiples of 4 except the end of the last segment
+  const int per = ((vocab / kLseSeg) + 3) & ~3;
+  int lo = g * per, hi = (g == kLseSeg - 1) ? vocab : lo + per;
+  lo = lo < vocab ? lo : vocab;
+  hi = hi < vocab ? hi : vocab;
+  const int n4 = vec ? (hi - lo) >> 2 : 0;
+  typedef float vec4 __attribute__((ext_vector_type(4)));
+  const vec4* row4 = reinterpret_cast<const vec4*>(row + lo);
+  // one pass: each thread keeps a running (max, sum) over batches of kLseBatch independent 16-byte loads
+  constexpr int kLseBatch = 8;
+  float tm = -INFINITY, ts = 0.f;
+  for (int i0 = threadIdx.x; i0 < n4; i0 += kLseThreads * kLseBatch) {
+    vec4 v[kLseBatch];
+#pragma unroll
+    for (int k = 0; k < kLseBatch; ++k) {
+      const int i = i0 + k * kLseThreads;
+      // ordinary loads on purpose: the acceptance kernel reads one of these rows again right afterwards
+      v[k] = i < n4 ? row4[i] : vec4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    }
+    float bm = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kLseBatch; ++k) bm = fmaxf(bm, fmaxf(fmaxf(v[k][0], v[k][1]), fmaxf(v[k][2], v[k][3])));
+    if (bm > tm) {
+      ts *= __expf(tm - bm);  // tm = -inf: 0 * 0
+      tm = bm;
+    }
+    if (tm > -INFINITY) {
+      float acc = 0.f;
+#pragma unroll
+      for (int k = 0; k < kLseBatch; ++k)
+        acc += (__expf(v[k][0] - tm) + __expf(v[k][1] - tm)) + (__expf(v[k][2] - tm) + __expf(v[k][3] - tm));
+      ts += acc;
+    }
   }
-  for (int v = n4 * 4 + threadIdx.x; v < vocab; v += kStatThreads) mx = fmaxf(mx, row[v]);
-  mx = block_max(mx, red);
-  float s = 0.f;
-  for (int i = threadIdx.x; i < n4; i += kStatThreads) {
-    const float4 v = reinterpret_cast<const float4*>(row)[i];
-    s += (__expf(v.x - mx) + __expf(v.y - mx)) + (__expf(v.z - mx) + __expf(v.w - mx));
+  for (int v = lo + n4 * 4 + threadIdx.x; v < hi; v += kLseThreads) {
+    const float x = row[v];
+    if (x > tm) {
+      ts *= __expf(tm - x);
+      tm = x;
+    }
+    if (tm > -INFINITY) ts += __expf(x - tm);
   }
-  for (int v = n4 * 4 + threadIdx.x; v < vocab; v += kStatThreads) s += __expf(row[v] - mx);
+  const float mx = block_max(tm, red);
+  float s = (tm > -INFINITY) ? ts * __expf(tm - mx) : 0.f;
   s = block_sum(s, red);
-  if (threadIdx.x == 0) lse[b] = mx + __logf(s);
+  if (threadIdx.x == 0) part[(size_t)b * kLseSeg + g] = make_float2(mx, s);
+}
+
+// lse of row b from its segment pairs (fixed order).
+__device__ __forceinline__ float combine_lse(const float2* __restrict__ part, int b) {
+  float mx = -INFINITY;
+#pragma unroll
+  for (int g = 0; g < kLseSeg; ++g) mx = fmaxf(mx, part[(size_t)b * kLseSeg + g].x);
+  float s = 0.f;
+#pragma unroll
+  for (int g = 0; g < kLseSeg; ++g) {
+    const float2 q = part[(size_t)b * kLseSeg + g];
+    if (q.x > -INFINITY) s += q.y * __expf(q.x - mx);
+  }
+  return mx + __logf(s);
 }
 
 // One workgroup: acceptance decisions, then the inverse-CDF draw on the row after the accepted prefix.
@@ -84,9 +133,10 @@ constexpr int kMaxSeg = 64;  // vocabularies up to 262144 tokens
 
 __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
     const float* __restrict__ p_logits, const float* __restrict__ q_logits, int m, int vocab,
-    const float* __restrict__ lse, const int32_t* __restrict__ block, const int32_t* __restrict__ path_len,
+    const float2* __restrict__ lse_part, const int32_t* __restrict__ block, const int32_t* __restrict__ path_len,
     const float* __restrict__ u, int32_t eos_id, int32_t* __restrict__ n_accept, int32_t* __restrict__ next_token,
     int32_t* __restrict__ eos_accepted, float* __restrict__ alpha_out) {
+  __shared__ float lse[2 * DS_MAX_ROWS];  // [m + 1] verifier rows, then [m] drafter rows
   __shared__ float wave_sum[kMaxSeg][kStatThreads / 64];
   __shared__ float part[2][kStatThreads];
   __shared__ float s_before, s_target, s_total;
@@ -101,6 +151,7 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
     s_first = m_eff;
     s_eos = 0;
   }
+  for (int b = t; b < 2 * m + 1; b += kStatThreads) lse[b] = combine_lse(lse_part, b);
   __syncthreads();
   for (int i = t; i < m; i += kStatThreads) {
     const int tok = block[i + 1];
@@ -284,7 +335,7 @@ __global__ __launch_bounds__(256) void refine_select_kernel(
 
 }  // namespace
 
-size_t sample_ws_bytes(int m) { return align_up((size_t)(2 * m + 1) * sizeof(float), 256); }
+size_t sample_ws_bytes(int m) { return align_up((size_t)(2 * m + 1) * kLseSeg * sizeof(float2), 256); }
 
 int launch_sample_accept(const float* p_logits, const float* q_logits, int m, int vocab, const int32_t* block,
                          const int32_t* path_len, const float* u, int32_t eos_id, int32_t* n_accept,
@@ -294,9 +345,9 @@ int launch_sample_accept(const float* p_logits, const float* q_logits, int m, in
              sample_ws_bytes(m), ws_bytes);
   DS_REQUIRE(vocab <= kSeg * kMaxSeg, DS_E_UNSUPPORTED, "stochastic acceptance: vocab %d exceeds %d", vocab,
              kSeg * kMaxSeg);
-  float* lse = static_cast<float*>(ws);
-  hipLaunchKernelGGL(row_lse_kernel, dim3(2 * m + 1), dim3(kStatThreads), 0, st, p_logits, m + 1, q_logits, vocab,
-                     lse);
+  float2* lse = static_cast<float2*>(ws);  // per-segment (max, sum) pairs
+  hipLaunchKernelGGL(row_lse_kernel, dim3(2 * m + 1, kLseSeg), dim3(kLseThreads), 0, st, p_logits, m + 1, q_logits,
+                     vocab, lse);
   DS_LAUNCH_CHECK("row_lse_kernel");
   hipLaunchKernelGGL(sample_accept_kernel, dim3(1), dim3(kStatThreads), 0, st, p_logits, q_logits, m, vocab, lse,
                      block, path_len, u, eos_id, n_accept, next_token, eos_accepted, alpha);
