@@ -119,29 +119,32 @@ __device__ __forceinline__ float combine_lse(const float2* __restrict__ part, in
   return mx + __logf(s);
 }
 
-// One workgroup: acceptance decisions, then the inverse-CDF draw on the row after the accepted prefix.
-// lse: [m + 1] verifier rows, then [m] drafter rows.  u: [m] acceptance uniforms, then the draw's uniform.
+// Stochastic acceptance in two kernels.
 //
-// The draw walks the vocabulary in order, hierarchically and with coalesced loads: the row is cut into segments
-// of kSeg = 4096 consecutive tokens; inside a segment thread t owns the 4 consecutive tokens 4 t .. 4 t + 3.
-//   pass 1: every segment's total weight (per-wavefront sums in lane order, the 16 wavefront sums in order);
-//   the segment whose cumulative total first exceeds the target is found by one thread walking the <= 64 totals;
+// sample_decide_kernel (one workgroup): log-sum-exp of every row from its segment pairs, the acceptance
+// probabilities alpha, the accepted prefix length L (first i with u[i] >= alpha_i) and whether an accepted token is
+// EOS.  Leaves {L, eos flag, effective path length, arrival counter = 0} in ctl and the lse values in lse.
+//
+// sample_draw_kernel (one workgroup per segment of kSeg = 4096 consecutive tokens): the inverse-CDF draw on verifier
+// row L, in vocabulary order, hierarchically and with coalesced loads; inside a segment thread t owns the 4
+// consecutive tokens 4 t .. 4 t + 3.
+//   pass 1: every workgroup sums the weights of its segment (per-wavefront sums in lane order, the 16 wavefront
+//   sums in order) and leaves the total in seg_tot; the workgroup that arrives last goes on alone (nobody waits):
+//   it finds the segment whose cumulative total first exceeds the target by walking the <= 64 totals in order;
 //   pass 2: inside that segment, an inclusive scan of the 1024 four-token sums finds the owning thread, which
 //   walks its 4 tokens.  Every sum has a fixed order, so the drawn token is reproducible bit for bit.
+//   If the residual max(p - q, 0) is empty (p == q up to rounding) the last workgroup redoes pass 1 on p alone, by
+//   itself: rare, and then slower.
 constexpr int kSeg = 4 * kStatThreads;
 constexpr int kMaxSeg = 64;  // vocabularies up to 262144 tokens
 
-__global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
+__global__ __launch_bounds__(256) void sample_decide_kernel(
     const float* __restrict__ p_logits, const float* __restrict__ q_logits, int m, int vocab,
     const float2* __restrict__ lse_part, const int32_t* __restrict__ block, const int32_t* __restrict__ path_len,
-    const float* __restrict__ u, int32_t eos_id, int32_t* __restrict__ n_accept, int32_t* __restrict__ next_token,
-    int32_t* __restrict__ eos_accepted, float* __restrict__ alpha_out) {
-  __shared__ float lse[2 * DS_MAX_ROWS];  // [m + 1] verifier rows, then [m] drafter rows
-  __shared__ float wave_sum[kMaxSeg][kStatThreads / 64];
-  __shared__ float part[2][kStatThreads];
-  __shared__ float s_before, s_target, s_total;
-  __shared__ int s_first, s_seg, s_thread, s_last, s_eos;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const float* __restrict__ u, int32_t eos_id, float* __restrict__ lse, int32_t* __restrict__ ctl,
+    float* __restrict__ alpha_out) {
+  __shared__ int s_first, s_eos;
+  const int t = threadIdx.x;
   int m_eff = m;
   if (path_len) {
     const int pl = *path_len;
@@ -151,14 +154,14 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
     s_first = m_eff;
     s_eos = 0;
   }
-  for (int b = t; b < 2 * m + 1; b += kStatThreads) lse[b] = combine_lse(lse_part, b);
-  __syncthreads();
-  for (int i = t; i < m; i += kStatThreads) {
+  for (int b = t; b < 2 * m + 1; b += blockDim.x) lse[b] = combine_lse(lse_part, b);
+  __syncthreads();  // also orders this workgroup's lse stores before its own loads below
+  for (int i = t; i < m; i += blockDim.x) {
     const int tok = block[i + 1];
     float a = 0.f;
     if (tok >= 0 && tok < vocab) {
-      const float lp = p_logits[(size_t)i * vocab + tok] - lse[i];
-      const float lq = q_logits[(size_t)i * vocab + tok] - lse[m + 1 + i];
+      const float lp = p_logits[(size_t)i * vocab + tok] - combine_lse(lse_part, i);
+      const float lq = q_logits[(size_t)i * vocab + tok] - combine_lse(lse_part, m + 1 + i);
       a = lq <= lp ? 1.0f : __expf(lp - lq);
     }
     alpha_out[i] = a;
@@ -166,8 +169,30 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
   }
   __syncthreads();
   const int L = s_first;  // accepted prefix length; the draw uses verifier row L
-  for (int i = t; i < L; i += kStatThreads)
+  for (int i = t; i < L; i += blockDim.x)
     if (eos_id >= 0 && block[i + 1] == eos_id) atomicOr(&s_eos, 1);
+  __syncthreads();
+  if (t == 0) {
+    ctl[0] = L;
+    ctl[1] = s_eos;
+    ctl[2] = m_eff;
+    ctl[3] = 0;  // arrival counter of the draw kernel
+  }
+}
+
+__global__ __launch_bounds__(kStatThreads) void sample_draw_kernel(
+    const float* __restrict__ p_logits, const float* __restrict__ q_logits, int m, int vocab,
+    const float* __restrict__ lse, int32_t* __restrict__ ctl, float* seg_tot, const float* __restrict__ u,
+    int32_t eos_id, int32_t* __restrict__ n_accept, int32_t* __restrict__ next_token,
+    int32_t* __restrict__ eos_accepted) {
+  __shared__ float wave_sum[kStatThreads / 64];
+  __shared__ float seg_total[kMaxSeg];
+  __shared__ float part[2][kStatThreads];
+  __shared__ float s_before, s_target, s_total;
+  __shared__ int s_seg, s_thread, s_last;
+  __shared__ bool s_is_last;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int L = ctl[0], acc_eos = ctl[1], m_eff = ctl[2];
 
   const float* prow = p_logits + (size_t)L * vocab;
   const float* qrow = L < m ? q_logits + (size_t)L * vocab : nullptr;
@@ -201,31 +226,48 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
       w[e] = x;
     }
   };
-
-  for (int attempt = 0; attempt < 2; ++attempt) {
-    // pass 1: segment totals
-    for (int seg = 0; seg < n_seg; ++seg) {
-      float w[4];
-      weights4(seg, w);
-      float s = (w[0] + w[1]) + (w[2] + w[3]);
+  // total weight of one segment: wavefront sums in lane order, then the wavefront sums in order (every thread
+  // of the workgroup calls this; the value is valid in thread 0)
+  auto segment_total = [&](int seg) {
+    float w[4];
+    weights4(seg, w);
+    float s = (w[0] + w[1]) + (w[2] + w[3]);
 #pragma unroll
-      for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
-      if (lane == 0) wave_sum[seg][wave] = s;
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    __syncthreads();
+    if (lane == 0) wave_sum[wave] = s;
+    __syncthreads();
+    float ss = 0.f;
+    if (t == 0)
+      for (int w2 = 0; w2 < kStatThreads / 64; ++w2) ss += wave_sum[w2];
+    return ss;
+  };
+
+  // pass 1, this workgroup's segment; the last workgroup to arrive continues
+  {
+    const float ss = segment_total((int)blockIdx.x);
+    if (t == 0) {
+      __hip_atomic_store(&seg_tot[blockIdx.x], ss, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __threadfence();
+      const int seen = __hip_atomic_fetch_add(&ctl[3], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+      s_is_last = seen == n_seg - 1;
     }
     __syncthreads();
+    if (!s_is_last) return;
+    __threadfence();
+    if (t < n_seg) seg_total[t] = __hip_atomic_load(&seg_tot[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+  }
+
+  for (int attempt = 0; attempt < 2; ++attempt) {
     if (t == 0) {
       float total = 0.f;
-      for (int seg = 0; seg < n_seg; ++seg) {
-        float ss = 0.f;
-        for (int w2 = 0; w2 < kStatThreads / 64; ++w2) ss += wave_sum[seg][w2];
-        wave_sum[seg][0] = ss;  // segment total
-        total += ss;
-      }
+      for (int seg = 0; seg < n_seg; ++seg) total += seg_total[seg];
       const float target = u[m] * total;
       float c = 0.f;
       int pick = -1, last_pos = -1;
       for (int seg = 0; seg < n_seg; ++seg) {
-        const float ss = wave_sum[seg][0];
+        const float ss = seg_total[seg];
         if (ss > 0.f) {
           last_pos = seg;
           if (c + ss > target) {
@@ -238,7 +280,7 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
       if (pick < 0) {  // rounding left the target past the mass: the last segment that has any
         pick = last_pos;
         c = 0.f;
-        for (int seg = 0; seg < pick; ++seg) c += wave_sum[seg][0];
+        for (int seg = 0; seg < pick; ++seg) c += seg_total[seg];
       }
       s_total = total;
       s_target = target;
@@ -248,6 +290,10 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
     __syncthreads();
     if (!(residual && !(s_total > 0.f))) break;
     residual = false;  // p == q up to rounding: the residual is empty, draw from p instead
+    for (int seg = 0; seg < n_seg; ++seg) {
+      const float ss = segment_total(seg);
+      if (t == 0) seg_total[seg] = ss;
+    }
     __syncthreads();
   }
 
@@ -280,7 +326,7 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
   if (pick_t < 0 && t == 0) {  // no positive weight anywhere (NaN logits are a caller error): defined outputs
     *n_accept = L;
     *next_token = 0;
-    *eos_accepted = s_eos;
+    *eos_accepted = acc_eos;
   }
   if (t == pick_t) {
     float c = excl;
@@ -297,7 +343,7 @@ __global__ __launch_bounds__(kStatThreads) void sample_accept_kernel(
     const int tok = seg * kSeg + 4 * t + chosen;
     *n_accept = L;
     *next_token = tok;
-    *eos_accepted = (s_eos || (eos_id >= 0 && tok == eos_id)) ? 1 : 0;
+    *eos_accepted = (acc_eos || (eos_id >= 0 && tok == eos_id)) ? 1 : 0;
   }
 }
 
@@ -335,7 +381,11 @@ __global__ __launch_bounds__(256) void refine_select_kernel(
 
 }  // namespace
 
-size_t sample_ws_bytes(int m) { return align_up((size_t)(2 * m + 1) * kLseSeg * sizeof(float2), 256); }
+// workspace: segment pairs of the row log-sum-exps, the log-sum-exps, the control words, the segment totals
+size_t sample_ws_bytes(int m) {
+  return align_up((size_t)(2 * m + 1) * kLseSeg * sizeof(float2), 256) + align_up((size_t)(2 * m + 1) * sizeof(float), 256) +
+         256 + align_up(kMaxSeg * sizeof(float), 256);
+}
 
 int launch_sample_accept(const float* p_logits, const float* q_logits, int m, int vocab, const int32_t* block,
                          const int32_t* path_len, const float* u, int32_t eos_id, int32_t* n_accept,
@@ -345,13 +395,23 @@ int launch_sample_accept(const float* p_logits, const float* q_logits, int m, in
              sample_ws_bytes(m), ws_bytes);
   DS_REQUIRE(vocab <= kSeg * kMaxSeg, DS_E_UNSUPPORTED, "stochastic acceptance: vocab %d exceeds %d", vocab,
              kSeg * kMaxSeg);
-  float2* lse = static_cast<float2*>(ws);  // per-segment (max, sum) pairs
+  char* base = static_cast<char*>(ws);
+  float2* lse_part = reinterpret_cast<float2*>(base);  // per-segment (max, sum) pairs
+  base += align_up((size_t)(2 * m + 1) * kLseSeg * sizeof(float2), 256);
+  float* lse = reinterpret_cast<float*>(base);
+  base += align_up((size_t)(2 * m + 1) * sizeof(float), 256);
+  int32_t* ctl = reinterpret_cast<int32_t*>(base);
+  float* seg_tot = reinterpret_cast<float*>(base + 256);
   hipLaunchKernelGGL(row_lse_kernel, dim3(2 * m + 1, kLseSeg), dim3(kLseThreads), 0, st, p_logits, m + 1, q_logits,
-                     vocab, lse);
+                     vocab, lse_part);
   DS_LAUNCH_CHECK("row_lse_kernel");
-  hipLaunchKernelGGL(sample_accept_kernel, dim3(1), dim3(kStatThreads), 0, st, p_logits, q_logits, m, vocab, lse,
-                     block, path_len, u, eos_id, n_accept, next_token, eos_accepted, alpha);
-  DS_LAUNCH_CHECK("sample_accept_kernel");
+  hipLaunchKernelGGL(sample_decide_kernel, dim3(1), dim3(256), 0, st, p_logits, q_logits, m, vocab, lse_part, block,
+                     path_len, u, eos_id, lse, ctl, alpha);
+  DS_LAUNCH_CHECK("sample_decide_kernel");
+  const int n_seg = ceil_div(vocab, kSeg);
+  hipLaunchKernelGGL(sample_draw_kernel, dim3(n_seg), dim3(kStatThreads), 0, st, p_logits, q_logits, m, vocab, lse, ctl,
+                     seg_tot, u, eos_id, n_accept, next_token, eos_accepted);
+  DS_LAUNCH_CHECK("sample_draw_kernel");
   return DS_OK;
 }
 

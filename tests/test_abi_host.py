@@ -82,11 +82,11 @@ def test_bad_arguments_are_rejected_on_the_host_before_any_launch():
     # stochastic acceptance and the refinement update
     assert lib.ds_accept_stochastic(one, one, -1, 10, one, None, one, -1, one, one, one, one, one, 1024, None) == ds.DS_E_SHAPE
     assert lib.ds_accept_stochastic(one, one, 144, 10, one, None, one, -1, one, one, one, one, one, 1 << 20, None) == ds.DS_E_SHAPE
-    assert lib.ds_accept_stochastic(one, None, 2, 10, one, None, one, -1, one, one, one, one, one, 1024, None) == ds.DS_E_INVALID
-    assert lib.ds_accept_stochastic(one, one, 2, 10, one, None, one, 10, one, one, one, one, one, 1024, None) == ds.DS_E_INVALID
+    assert lib.ds_accept_stochastic(one, None, 2, 10, one, None, one, -1, one, one, one, one, one, 4096, None) == ds.DS_E_INVALID
+    assert lib.ds_accept_stochastic(one, one, 2, 10, one, None, one, 10, one, one, one, one, one, 4096, None) == ds.DS_E_INVALID
     assert lib.ds_accept_stochastic(one, one, 2, 10, one, None, one, -1, one, one, one, one, one, 8, None) == ds.DS_E_CAPACITY
-    assert lib.ds_accept_stochastic(one, one, 2, 300000, one, None, one, -1, one, one, one, one, one, 1024, None) == ds.DS_E_UNSUPPORTED
-    assert ds.ds_sample_workspace_bytes(32) == 256 * ((65 * 8 * 8 + 255) // 256)   # 65 rows x 8 segments x (max, sum)
+    assert lib.ds_accept_stochastic(one, one, 2, 300000, one, None, one, -1, one, one, one, one, one, 4096, None) == ds.DS_E_UNSUPPORTED
+    assert ds.ds_sample_workspace_bytes(32) == 4352 + 512 + 256 + 256   # lse pairs, lse, control words, segment totals
     sel = [one] * 5 + [8, 4, 3, 99] + [one] * 6 + [None]
     assert lib.ds_refine_select(*(sel[:5] + [0] + sel[6:])) == ds.DS_E_SHAPE        # K = 0
     assert lib.ds_refine_select(*(sel[:5] + [257] + sel[6:])) == ds.DS_E_SHAPE      # K > 256
