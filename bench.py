@@ -268,6 +268,7 @@ def main() -> int:
         dm.set_kv_len(p0)
         vm.set_kv_len(p0)
         p = dec.p
+        dec.arm_verdict()
         ds.ds_draft_block(dm.handle, dec.pending_dev, 1, K_DRAFT, dec.mask_id, dec.hidden, dm.ws)
         if i_timed >= 0:
             ev[i_timed][0].record()
@@ -280,8 +281,8 @@ def main() -> int:
                        dec.proxy, dec.ctx, dec.eos_id, dec.block[1:], dec.path_len, dec.path_score, dec.cps_ws)
         ds.ds_verify_block(vm.handle, dec.block, K_DRAFT, dec.path_len, dec.eos_id, dec.result[0:1],
                            dec.result[1:2], dec.argmax, dec.result[2:3], None, vm.ws)
-        torch.cuda.current_stream().synchronize()      # the round's one host crossing: accepted length
-        n_acc = int(dec.result[0])                     # written by the acceptance kernel into pinned host memory
+        dec.wait_verdict()                             # the round's one host crossing: poll the pinned verdict
+        n_acc = int(dec.result_np[0])                  # written by the acceptance kernel into pinned host memory
         k_next = ds.ds_adl_update(dec.adl, K_DRAFT, 0, n_acc)
         if i_timed >= 0:
             acc_tokens += n_acc + 1

@@ -199,7 +199,10 @@ int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* c
  * Keys/values of all rows are written at [len, len + m + 1) but the committed length is NOT advanced:
  * after reading n_accept the caller commits with ds_model_kv_set_len(len + 1 + n_accept).
  * Outputs [dev]: n_accept, next_token, eos_accepted int32[1]; argmax int32[m + 1];
- * logits_out float[m + 1, vocab] or NULL.  0 <= m, m + 1 <= DS_MAX_ROWS. */
+ * logits_out float[m + 1, vocab] or NULL.  0 <= m, m + 1 <= DS_MAX_ROWS.
+ * eos_accepted is stored last, after a system-scope fence: if the three scalars live in device-visible pinned
+ * host memory, a host that sees eos_accepted change also sees n_accept and next_token (the round's one host
+ * crossing can be a poll of that word instead of a stream synchronisation). */
 int ds_verify_block(ds_model* verifier, const int32_t* block, int m, const int32_t* path_len,
                     int32_t eos_id, int32_t* n_accept, int32_t* next_token, int32_t* argmax,
                     int32_t* eos_accepted, float* logits_out, void* ws, size_t ws_bytes, void* stream);

@@ -372,6 +372,7 @@ __global__ __launch_bounds__(1024) void accept_merge_kernel(int rows, int n_part
     eos |= (eos_id >= 0 && nxt == eos_id);
     *n_accept = n;
     *next_token = nxt;
+    __threadfence_system();  // eos_accepted last: a host polling it in device-visible memory then sees all three
     *eos_accepted = eos ? 1 : 0;
   }
 }
@@ -456,6 +457,7 @@ __global__ __launch_bounds__(256) void accept_tiles_kernel(int rows, int rows_pa
     eos |= (eos_id >= 0 && nxt == eos_id);
     *n_accept = n;
     *next_token = nxt;
+    __threadfence_system();  // eos_accepted last: a host polling it in device-visible memory then sees all three
     *eos_accepted = eos ? 1 : 0;
   }
 }

@@ -326,6 +326,7 @@ __global__ __launch_bounds__(kStatThreads) void sample_draw_kernel(
   if (pick_t < 0 && t == 0) {  // no positive weight anywhere (NaN logits are a caller error): defined outputs
     *n_accept = L;
     *next_token = 0;
+    __threadfence_system();
     *eos_accepted = acc_eos;
   }
   if (t == pick_t) {
@@ -343,6 +344,7 @@ __global__ __launch_bounds__(kStatThreads) void sample_draw_kernel(
     const int tok = seg * kSeg + 4 * t + chosen;
     *n_accept = L;
     *next_token = tok;
+    __threadfence_system();  // eos_accepted last, as in the greedy kernels
     *eos_accepted = (acc_eos || (eos_id >= 0 && tok == eos_id)) ? 1 : 0;
   }
 }
