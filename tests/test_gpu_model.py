@@ -276,6 +276,15 @@ def test_bf16_verify_argmax_comes_from_the_lm_head_epilogue():
             assert got == (b["n_accept"], b["next_token"], b["eos_accepted"])
             n_acc, nxt, _, eos_acc = o_accept.verify_greedy(a["logits"][:pl + 1], block[1:pl + 1], eos)
             assert got == (n_acc, nxt, eos_acc), (pl, got)
+        # the widest block the library takes (144 rows: nine row blocks per workgroup) and the narrowest (one row)
+        for n_rows in (ds.DS_MAX_ROWS, 1):
+            wide = rng.integers(0, cfg.n_plain_tokens, n_rows).astype(np.int32)
+            gm.set_kv_len(70)
+            a = gm.verify(wide)
+            gm.set_kv_len(70)
+            b = gm.verify(wide, want_logits=False)
+            assert np.array_equal(a["argmax"], np.argmax(a["logits"], axis=1))
+            assert np.array_equal(a["argmax"], b["argmax"]) and a["next_token"] == b["next_token"]
     finally:
         gm.close()
     first_max = np.argmax(full["logits"], axis=1)
