@@ -51,7 +51,7 @@ def _round_trip(cfg, w, prefix, pending_extra, k1, k2, kv_cap, seed):
         scale = float(np.std(ref_last))
         assert err <= 0.05 * scale, f"prefill err {err} vs logits std {scale}"
 
-        # ---- draft round 1: one pending token
+        # ---- first draft pass: one pending token
         pend = [int(np.argmax(ref_last))]
         ref_hid = o_model.draft_block(cfg, w, oc, pend, k1)
         hid = gm.draft(pend, k1)
@@ -65,7 +65,7 @@ def _round_trip(cfg, w, prefix, pending_extra, k1, k2, kv_cap, seed):
         assert l_err <= tol, f"draft logits err {l_err}"
         assert l_err <= 0.05 * float(np.std(ref_logits))
 
-        # ---- draft round 2: several pending tokens (as after an accepted prefix), different K
+        # ---- second draft pass: several pending tokens (as after an accepted prefix), different K
         ref_hid = o_model.draft_block(cfg, w, oc, pending_extra, k2)
         hid = gm.draft(pending_extra, k2)
         logits = gm.lm_head(hid)
