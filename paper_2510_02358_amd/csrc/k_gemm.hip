@@ -22,6 +22,13 @@
 //     output columns of row j, stored as one float4.
 //   * Split-K writes float32 partial planes out[s][M][N]; the consumer kernel sums them in a fixed
 //     order (deterministic, no atomics).
+//   * The weight loads are non-temporal: every weight byte is used once, and keeping the stream out of
+//     the caches leaves them to the activation tiles that all workgroups re-read (measured: 6 % faster
+//     on the LM head, 5-15 % on the layer projections).
+//   * The unsplit LM-head product has three epilogues besides plain planes: logits stored non-temporally;
+//     per-tile arg-max records (greedy verification); per-tile lattice records (two largest values with
+//     their columns, third largest value, sum of exponentials).  With records the logits need not be
+//     written at all: at 32 rows their 19.5 MB of writes cost as much as 100 MB of the read stream.
 //
 // f32 path: a plain wavefront-per-output-column kernel for the float32 parity mode.
 #include <limits.h>
