@@ -132,12 +132,25 @@ __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int 
   const int r = blockIdx.x, slot = blockIdx.y, i = threadIdx.x, half = hd >> 1;
   if (i >= half) return;
   const int n_tot = (n_q + 2 * n_kv) * hd;
-  float a = 0.f, b = 0.f;
-  for (int s = 0; s < n_part; ++s) {
-    const float* p = part + ((size_t)s * rows + r) * n_tot + (size_t)slot * hd;
-    a += p[i];
-    b += p[i + half];
+  // all planes' loads are issued before the first add (one memory round trip instead of n_part); the sum keeps
+  // the plane order
+  float pa[kMaxPlanes], pb[kMaxPlanes];
+#pragma unroll
+  for (int s = 0; s < kMaxPlanes; ++s) {
+    pa[s] = pb[s] = 0.f;
+    if (s < n_part) {
+      const float* p = part + ((size_t)s * rows + r) * n_tot + (size_t)slot * hd;
+      pa[s] = p[i];
+      pb[s] = p[i + half];
+    }
   }
+  float a = 0.f, b = 0.f;
+#pragma unroll
+  for (int s = 0; s < kMaxPlanes; ++s)
+    if (s < n_part) {
+      a += pa[s];
+      b += pb[s];
+    }
   if (slot < n_q + n_kv) {
     const float2 t = cs[r * half + i];
     const float ra = a * t.x - b * t.y;
@@ -182,14 +195,24 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
   const int r = blockIdx.y;
   const int f = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (f >= F) return;
-  float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
-  for (int s = 0; s < n_part; ++s) {
-    const float* p = part + ((size_t)s * rows + r) * (2 * (size_t)F);
-    const float4 a = *reinterpret_cast<const float4*>(p + f);
-    const float4 b = *reinterpret_cast<const float4*>(p + F + f);
-    g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
-    u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+  // all planes' loads first, then the sums in plane order
+  float4 pg[kMaxPlanes], pu[kMaxPlanes];
+#pragma unroll
+  for (int s = 0; s < kMaxPlanes; ++s) {
+    pg[s] = pu[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (s < n_part) {
+      const float* p = part + ((size_t)s * rows + r) * (2 * (size_t)F);
+      pg[s] = *reinterpret_cast<const float4*>(p + f);
+      pu[s] = *reinterpret_cast<const float4*>(p + F + f);
+    }
   }
+  float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+#pragma unroll
+  for (int s = 0; s < kMaxPlanes; ++s)
+    if (s < n_part) {
+      g.x += pg[s].x; g.y += pg[s].y; g.z += pg[s].z; g.w += pg[s].w;
+      u.x += pu[s].x; u.y += pu[s].y; u.z += pu[s].z; u.w += pu[s].w;
+    }
   const float4 y = make_float4(g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
                                g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w);
   Act<T>::put4(act, r, f, F, y);
@@ -241,6 +264,7 @@ int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* 
 template <typename T>
 int launch_qkv_rope(const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv, int hd,
                     const float2* cs, int pos0, int cap, void* q, void* kc, void* vc, hipStream_t st) {
+  DS_REQUIRE(n_part >= 1 && n_part <= kMaxPlanes, DS_E_SHAPE, "rope: %d partial planes, at most %d", n_part, kMaxPlanes);
   hipLaunchKernelGGL((qkv_rope_kernel<T>), dim3(rows, n_q + 2 * n_kv), dim3(hd / 2), 0, st, part, n_part, rows,
                      rows_pad, n_q, n_kv, hd, cs, pos0, cap, static_cast<typename Act<T>::kv_t*>(q),
                      static_cast<typename Act<T>::kv_t*>(kc), static_cast<typename Act<T>::kv_t*>(vc));
@@ -250,6 +274,7 @@ int launch_qkv_rope(const float* part, int n_part, int rows, int rows_pad, int n
 
 template <typename T>
 int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, hipStream_t st) {
+  DS_REQUIRE(n_part >= 1 && n_part <= kMaxPlanes, DS_E_SHAPE, "SwiGLU: %d partial planes, at most %d", n_part, kMaxPlanes);
   hipLaunchKernelGGL((swiglu_kernel<T>), dim3(ceil_div(F, 1024), rows), dim3(256), 0, st, part, n_part, rows,
                      rows_pad, F, static_cast<T*>(act));
   DS_LAUNCH_CHECK("swiglu_kernel");
