@@ -188,8 +188,10 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
   float out_score = 0.f;
   bool finished = false;
 
+  int4 mt_next = L.meta[0];  // the next step's meta is read one step ahead, off the dependent chain
   for (int i = 0; i < K && !finished; ++i) {
-    const int4 mt = L.meta[i];
+    const int4 mt = mt_next;
+    mt_next = L.meta[i + 1 < K ? i + 1 : i];
     const int n_cand = __builtin_amdgcn_readfirstlane(mt.x), eos_rank = __builtin_amdgcn_readfirstlane(mt.y);
     const uint32_t inv = (uint32_t)__builtin_amdgcn_readfirstlane(mt.z);
     const int n_exp = n_live * n_cand;
