@@ -402,6 +402,60 @@ def test_bf16_vocabulary_that_the_tile_records_do_not_cover():
         gm.close()
 
 
+@pytest.mark.parametrize("vocab", [128, 1024, 8192, 33024])
+def test_bf16_tile_records_seeded_sweep(vocab):
+    """Seeded sweep over row counts, M, tau, EOS ids and planted runs of strong neighbouring ids with exact ties:
+    the record-based lattice equals the oracle's lattice of the returned logits, with and without the logits being
+    written, and the verifier's record-based arg-max equals the arg-max of its returned logits.  vocab = 128 is a
+    single tile; 33024 needs two records per thread."""
+    rng = np.random.default_rng(1000 + vocab)
+    cfg = synth.ModelCfg(n_layers=1, d_model=256, n_q=2, n_kv=1, head_dim=128, d_ffn=256, vocab=vocab,
+                         rope_base=1.0e6, dtype="bf16")
+    for trial in range(2):
+        w = dict(synth.make_weights(cfg, int(rng.integers(1 << 30))))
+        lm = np.array(w["lm_head"], copy=True)
+        u = rng.standard_normal(cfg.d_model).astype(np.float32)
+        u /= np.linalg.norm(u)
+        for _ in range(int(rng.integers(1, 4))):
+            start, n = int(rng.integers(0, vocab - 20)), int(rng.integers(3, 18))
+            for k in range(n):
+                lm[start + k] = (0.3 + 0.01 * int(rng.integers(0, 5))) * u
+        w["lm_head"] = synth.round_to_bf16(lm)
+        gm = gu.GpuModel(cfg, w, 192)
+        try:
+            for sub in range(3):
+                rows = int(rng.choice([1, 2, 15, 16, 17, 33, 64, 100, 144]))
+                m_max = int(rng.integers(1, min(16, vocab) + 1))
+                tau = float(rng.choice([1.0, 0.99, 0.9, 0.5]))
+                eos = int(rng.integers(-1, vocab))
+                hid = rng.standard_normal((rows, cfg.d_model)).astype(np.float32)
+                hid[rng.random(rows) < 0.4] += 40.0 * u
+                if rows > 2:
+                    hid[1] = 0.0
+                full, logits = gm.draft_lattice(gu.to_dev(hid), rows, m_max, tau, eos, want_logits=True)
+                bare, _ = gm.draft_lattice(gu.to_dev(hid), rows, m_max, tau, eos, want_logits=False)
+                for k in full:
+                    assert torch.equal(full[k], bare[k]), (trial, sub, k)
+                lg = gu.from_dev(logits)
+                ref = o_lat.build_lattice(lg, m_max, tau, eos)
+                g = {k: gu.from_dev(v) for k, v in full.items()}
+                assert np.array_equal(g["cand_id"], ref["cand_id"]), (rows, m_max, tau, eos)
+                for r in np.nonzero(g["cand_cnt"] != ref["cand_cnt"])[0]:   # only a mass within rounding of tau
+                    cum = np.cumsum(np.exp(ref["cand_logp"][r].astype(np.float64)))
+                    assert np.min(np.abs(cum - tau)) < 1e-5, (rows, r, cum, tau)
+                for k in ("lse", "cand_logp", "eos_logp"):
+                    assert np.max(np.abs(g[k] - ref[k])) <= LSE_TOL, (k, rows)
+                blk = rng.integers(0, max(1, vocab - 2), int(rng.choice([1, 9, 33, 144]))).astype(np.int32)
+                gm.set_kv_len(0)
+                a = gm.verify(blk)
+                gm.set_kv_len(0)
+                b = gm.verify(blk, want_logits=False)
+                assert np.array_equal(a["argmax"], np.argmax(a["logits"], axis=1))
+                assert np.array_equal(a["argmax"], b["argmax"]) and a["n_accept"] == b["n_accept"]
+        finally:
+            gm.close()
+
+
 def test_f32_fused_call_equals_the_two_separate_calls():
     cfg = synth.CFG_TINY
     w = synth.make_weights(cfg, 98)
