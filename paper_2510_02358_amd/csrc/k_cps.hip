@@ -21,6 +21,11 @@
 #include "ds_common.h"
 #include "ds_wave.h"
 
+// The score arithmetic must stay unfused (see above).  It is written with plain operators under this pragma: the
+// __fmul_rn / __fadd_rn helpers are ordinary * and + compiled in their own header, where contraction is allowed, so
+// after inlining the compiler may still fuse them into a multiply-add (whether it does depends on scheduling).
+#pragma clang fp contract(off)
+
 namespace ds {
 namespace {
 
@@ -182,7 +187,7 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
   if (tid >= kWave) return;  // the search runs in the first wavefront
 
   // ---- phase B: the beam lives in LDS (beam[depth parity][slot]); lanes hold expansions --------------
-  const float one_minus = __fsub_rn(1.0f, lambda);
+  const float one_minus = 1.0f - lambda;
   int n_live = 1;
   int out_len = K;
   float out_score = 0.f;
@@ -221,8 +226,9 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
         } else if (table) {
           lng = table[ngram_slot((uint32_t)st.y, (uint32_t)st.z, (uint32_t)tok, table_mask)];
         }
-        const float term = __fadd_rn(__fmul_rn(lambda, ld), __fmul_rn(one_minus, lng));
-        e_score[j] = __fadd_rn(__uint_as_float((uint32_t)st.x), term);
+        const float dlm_part = lambda * ld, ng_part = one_minus * lng;  // two roundings, then two more below
+        const float term = dlm_part + ng_part;
+        e_score[j] = __uint_as_float((uint32_t)st.x) + term;
         e_bits[j] = ordered_bits(e_score[j]);
         e_v[j] = st.z;
         e_tok[j] = tok;

@@ -130,6 +130,23 @@ def test_cps_shapes_and_edge_parameters(batch, k_len, m_max, beam, lam, eos, tau
     _cps_case(batch, k_len, m_max, beam, lam, eos, seed=batch * 7 + k_len, tau=tau)
 
 
+@pytest.mark.parametrize("seed", [11, 12])
+def test_cps_seeded_sweep_with_inexact_lambda(seed):
+    """Seeded sweep over batch, depth, M, beam, EOS and pruning with mixing weights that are NOT exact in binary
+    (0.3, 0.7, 0.37): the products lambda * l_dlm and (1 - lambda) * l_ng then round, so a fused multiply-add
+    anywhere in the kernel's score update would change score bits (and occasionally the kept hypotheses)."""
+    rng = np.random.default_rng(seed)
+    for _ in range(30):
+        batch = int(rng.choice([1, 2, 5, 16]))
+        k_len = int(rng.choice([1, 2, 7, 8, 31, 32, 64]))
+        m_max, beam = int(rng.integers(1, 17)), int(rng.integers(1, 17))
+        lam = float(rng.choice([0.3, 0.7, 0.37, 0.5]))
+        eos = int(rng.choice([-1, VOCAB - 2]))
+        tau = float(rng.choice([1.0, 0.8]))
+        _cps_case(batch, k_len, m_max, beam, lam, eos, int(rng.integers(1 << 30)), peaky=bool(rng.random() < 0.3),
+                  tau=tau)
+
+
 def test_cps_without_proxy_and_peaky_lattice():
     _cps_case(4, 16, 8, 4, 0.5, -1, seed=3, use_table=False)
     lens = _cps_case(8, 24, 8, 4, 0.5, VOCAB - 2, seed=4, peaky=True)
