@@ -27,7 +27,7 @@ def _near_tie_in_argmax(ref_logits):
     return bool(np.any(srt[:, -1] - srt[:, -2] < 2 * TOL))
 
 
-@pytest.mark.parametrize("lam,tau", [(0.5, 1.0), (1.0, 0.8)])
+@pytest.mark.parametrize("lam,tau", [(0.5, 1.0), (1.0, 0.8), (0.3, 0.9)])
 def test_tiny_pair_rounds_match_oracle_and_are_lossless(lam, tau):
     cfg = synth.CFG_TINY
     dw, vw = synth.make_weights(cfg, 0), synth.make_weights(cfg, 1)
