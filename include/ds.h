@@ -144,6 +144,17 @@ int ds_build_lattice(const float* logits, int rows, int vocab, int M_max, float 
                      int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* ds_build_lattice for callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation): same inputs, outputs, rules and kernels, but the
+ * scan's partial records live in a 2 MiB array inside the library's own device image (one copy per GPU, held until
+ * the process ends).  The call allocates nothing.  Shapes whose ds_lattice_workspace_bytes() exceeds 2 MiB fail with
+ * DS_E_CAPACITY (every rows <= 3855 fits at any vocab and M_max).  Nothing in the array needs clearing between
+ * calls (each call overwrites what it reads), but all calls on one GPU share it: calls that overlap on one GPU
+ * (different streams or threads) race and must be serialised by the caller. */
+int ds_build_lattice_static(const float* logits, int rows, int vocab, int M_max, float tau, int32_t eos_id,
+                            int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
+                            void* stream);
+
 /* Steps 1b + 2 without the logits round trip (Sec. 3.2 "Lattice and pruning").
  * ds_lm_head_tiles: the LM head of ds_lm_head (hidden as there; NULL = the block rows of the preceding draft
  * pass), leaving in the workspace what the lattice needs.  On DS_BF16 models those are per-tile records written by

@@ -24,7 +24,7 @@ EXPORTS = [
     "ds_draft_block", "ds_lm_head", "ds_draft_lattice", "ds_lm_head_tiles", "ds_lattice_from_tiles", "ds_lattice_workspace_bytes", "ds_build_lattice", "ds_ngram_create",
     "ds_ngram_destroy", "ds_cps_workspace_bytes", "ds_cps_path", "ds_verify_block", "ds_adl_create", "ds_adl_destroy",
     "ds_adl_update", "ds_adl_state", "ds_sample_workspace_bytes", "ds_accept_stochastic",
-    "ds_verify_block_stochastic", "ds_draft_block_tokens", "ds_refine_select",
+    "ds_verify_block_stochastic", "ds_draft_block_tokens", "ds_refine_select", "ds_build_lattice_static",
 ]
 
 
@@ -87,6 +87,7 @@ def load():
     lib.ds_lattice_from_tiles.argtypes = [vp, C.c_int, C.c_int, f32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_draft_lattice.argtypes = [vp, vp, C.c_int, C.c_int, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_build_lattice.argtypes = [vp, C.c_int, C.c_int, C.c_int, f32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ds_build_lattice_static.argtypes = [vp, C.c_int, C.c_int, C.c_int, f32, i32, vp, vp, vp, vp, vp, vp]
     lib.ds_ngram_create.argtypes = [vp, C.c_int, C.POINTER(vp)]
     lib.ds_ngram_destroy.argtypes = [vp]
     lib.ds_cps_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(sz)]
@@ -217,6 +218,12 @@ def ds_build_lattice(logits, rows: int, vocab: int, m_max: int, tau: float, eos_
     _check(load().ds_build_lattice(_ptr(logits), rows, vocab, m_max, tau, eos_id, _ptr(cand_id), _ptr(cand_logp),
                                    _ptr(cand_cnt), _ptr(eos_logp), _ptr(lse), _ptr(ws),
                                    _nbytes(ws) if ws is not None else 0, _stream(stream)))
+
+
+def ds_build_lattice_static(logits, rows: int, vocab: int, m_max: int, tau: float, eos_id: int, cand_id, cand_logp,
+                            cand_cnt, eos_logp, lse, stream=None) -> None:
+    _check(load().ds_build_lattice_static(_ptr(logits), rows, vocab, m_max, tau, eos_id, _ptr(cand_id),
+                                          _ptr(cand_logp), _ptr(cand_cnt), _ptr(eos_logp), _ptr(lse), _stream(stream)))
 
 
 def ds_lm_head_tiles(model: int, hidden, rows: int, eos_id: int, logits_out, ws, stream=None) -> None:

@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "ds_common.h"
@@ -39,6 +40,32 @@ struct ds_adl {
 
 using namespace ds;
 
+// ---- library-owned scratch for callers that cannot allocate ------------------------------------------
+// ds_build_lattice_static keeps the scan's per-wavefront partial records here instead of in a caller workspace.
+// In host code `scratch` is only a stand-in for the symbol: the device address is looked up once per GPU (each GPU
+// holds its own copy of the array) and from then on only that address is used.
+constexpr size_t kStaticScratchBytes = (size_t)2 << 20;  // 2 MiB per GPU, held until the process ends
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current GPU (looked up on the first call per GPU; allocates nothing).
+static int static_scratch(void** out) {
+  int dev = -1;
+  DS_HIP_CHECK(hipGetDevice(&dev));
+  DS_REQUIRE(dev >= 0 && dev < kMaxDevices, DS_E_UNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    DS_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    DS_REQUIRE(p && (((uintptr_t)p) & 255) == 0, DS_E_HIP, "static scratch: bad device address %p", p);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DS_OK;
+}
+
 extern "C" {
 
 const char* ds_version(void) { return "diffuspec-mi355x 0.1 (gfx950)"; }
@@ -68,6 +95,31 @@ int ds_build_lattice(const float* logits, int rows, int vocab, int M_max, float 
   DS_REQUIRE((((uintptr_t)logits) & 3) == 0, DS_E_INVALID, "logits not 4-byte aligned");
   return launch_lattice(logits, rows, vocab, M_max, tau, eos_id, cand_id, cand_logp, cand_cnt, eos_logp, lse, ws,
                         ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int ds_build_lattice_static(const float* logits, int rows, int vocab, int M_max, float tau, int32_t eos_id,
+                            int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
+                            void* stream) {
+  DS_REQUIRE(rows >= 0, DS_E_SHAPE, "rows %d is negative", rows);
+  if (rows == 0) return DS_OK;
+  DS_REQUIRE(logits && cand_id && cand_logp && cand_cnt && eos_logp && lse, DS_E_INVALID,
+             "ds_build_lattice_static: NULL pointer argument");
+  DS_REQUIRE(vocab >= 1 && (long long)rows * vocab < (1ll << 40), DS_E_SHAPE, "vocab %d not supported", vocab);
+  DS_REQUIRE(M_max >= 1 && M_max <= DS_MAX_TOPM && M_max <= vocab, DS_E_SHAPE,
+             "M_max %d outside [1, min(%d, vocab)]", M_max, DS_MAX_TOPM);
+  DS_REQUIRE(eos_id < vocab, DS_E_INVALID, "eos_id %d >= vocab %d", eos_id, vocab);
+  DS_REQUIRE(!isnan(tau) && tau > 0.f, DS_E_INVALID, "tau must be positive");
+  DS_REQUIRE((((uintptr_t)logits) & 3) == 0, DS_E_INVALID, "logits not 4-byte aligned");
+  const size_t need = lattice_ws_bytes(rows, vocab, M_max);
+  DS_REQUIRE(need <= kStaticScratchBytes, DS_E_CAPACITY,
+             "ds_build_lattice_static: %d rows x %d logits at M_max %d need %zu bytes of scratch, the library holds %zu "
+             "(use ds_build_lattice with a caller workspace)",
+             rows, vocab, M_max, need, kStaticScratchBytes);
+  void* ws = nullptr;
+  int rc = static_scratch(&ws);
+  if (rc) return rc;
+  return launch_lattice(logits, rows, vocab, M_max, tau, eos_id, cand_id, cand_logp, cand_cnt, eos_logp, lse, ws,
+                        kStaticScratchBytes, static_cast<hipStream_t>(stream));
 }
 
 int ds_cps_workspace_bytes(int batch, int K, int M_max, size_t* bytes) {
