@@ -257,10 +257,20 @@ int ds_refine_select(const int32_t* cand_id, const float* cand_logp, const int32
                      int32_t* block_tokens, int32_t* out_cand_id, float* out_cand_logp, int32_t* out_cand_cnt,
                      float* out_eos_logp, float* out_lse, void* stream);
 
+/* The update schedule of the refinement (Sec. 2, refinement update equation; the paper leaves |U_s| open): pass s of
+ * S fixes |U_s| = ceil(|M_{s-1}| / (S - s + 1)) of the still-masked positions, so a block of K positions is complete
+ * after exactly min(S, K) passes.  Pure host code.  sizes [host] int[steps] receives |U_1|, |U_2|, ...; *n_sizes the
+ * number of passes (<= steps). */
+int ds_refine_update_sizes(int K, int steps, int* sizes, int* n_sizes);
+
 /* Step 4 tail, adaptive draft length (Sec. 3.3: generation-length signal, moving averages,
  * controller).  Pure host code in double precision.  first_eos: 1-based index of the first EOS in the
  * raw draft (per-position top-1 before the search), 0 if none.  Averages start at 0 (Alg. 1 init). */
 int ds_adl_create(int k_min, int k_max, double delta, double rho, ds_adl** out);
+/* s_t of the generation-length signal (Sec. 3.3): the 1-based index of the first eos_id in the raw draft, 0 if
+ * there is none or eos_id < 0.  raw_draft [host]: token i at raw_draft[i * stride], i < k (the top-1 column of the
+ * candidate ids as the host read them back: stride = M_max).  Pure host code. */
+int ds_adl_first_eos(const int32_t* raw_draft, int k, int stride, int32_t eos_id, int* first_eos);
 void ds_adl_destroy(ds_adl* a);
 int ds_adl_update(ds_adl* a, int k_t, int first_eos, int l_acc, int* k_next);
 int ds_adl_state(const ds_adl* a, double* l_gen_ema, double* l_acc_ema);

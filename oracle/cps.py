@@ -54,11 +54,14 @@ def step_term(lam: f32, l_dlm: f32, l_ng: f32) -> f32:
 
 
 def cps_path(lat: dict, row0: int, k_len: int, beam: int, lam: float, table, log2_size: int,
-             ctx, eos_id: int):
+             ctx, eos_id: int, margins=None):
     """Beam search over lattice rows row0 .. row0+k_len-1.
 
     table: float32 array of 2^log2_size proxy scores, or None (then l_ng = 0).
     ctx: the two tokens that precede the block (older first).
+    margins (diagnostic, optional list): per depth, the smallest score gap between neighbours among the kept
+    hypotheses and the best dropped one is appended (inf if there is a single expansion), so that a test can
+    tell whether a differing search result sits on a near-tie.  It changes nothing in the search.
     Returns (path tokens list, score float32, number of candidate evaluations).
     """
     lam = f32(lam)
@@ -74,6 +77,9 @@ def cps_path(lat: dict, row0: int, k_len: int, beam: int, lam: float, table, log
                 evals += 1
         grown.sort(key=lambda e: (-float(e[0]), e[1], e[2]))
         kept = grown[:beam]
+        if margins is not None:
+            top = [float(e[0]) for e in grown[:beam + 1]]
+            margins.append(min((a - b for a, b in zip(top, top[1:])), default=float("inf")))
         new_hyps = []
         for rank, (score, b, c) in enumerate(kept):
             w = cands[c][0]

@@ -25,6 +25,7 @@ EXPORTS = [
     "ds_ngram_destroy", "ds_cps_workspace_bytes", "ds_cps_path", "ds_verify_block", "ds_adl_create", "ds_adl_destroy",
     "ds_adl_update", "ds_adl_state", "ds_sample_workspace_bytes", "ds_accept_stochastic",
     "ds_verify_block_stochastic", "ds_draft_block_tokens", "ds_refine_select", "ds_build_lattice_static",
+    "ds_refine_update_sizes", "ds_adl_first_eos",
 ]
 
 
@@ -102,6 +103,8 @@ def load():
     lib.ds_adl_create.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double, C.POINTER(vp)]
     lib.ds_adl_destroy.argtypes = [vp]
     lib.ds_adl_update.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int)]
+    lib.ds_refine_update_sizes.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    lib.ds_adl_first_eos.argtypes = [vp, C.c_int, C.c_int, i32, C.POINTER(C.c_int)]
     lib.ds_adl_state.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     _lib = lib
     return lib
@@ -321,6 +324,25 @@ def ds_adl_destroy(handle: int) -> None:
 def ds_adl_update(handle: int, k_t: int, first_eos: int, l_acc: int) -> int:
     out = C.c_int(0)
     _check(load().ds_adl_update(handle, k_t, first_eos, l_acc, C.byref(out)))
+    return out.value
+
+
+def ds_refine_update_sizes(k: int, steps: int) -> list:
+    buf = (C.c_int * max(steps, 1))()
+    n = C.c_int(0)
+    _check(load().ds_refine_update_sizes(k, steps, buf, C.byref(n)))
+    return [int(buf[i]) for i in range(n.value)]
+
+
+def ds_adl_first_eos(raw_draft, k: int, stride: int, eos_id: int) -> int:
+    """raw_draft: host memory (numpy int32 array or pinned torch tensor) holding token i at [i * stride]."""
+    if isinstance(raw_draft, np.ndarray):
+        assert raw_draft.dtype == np.int32 and raw_draft.flags["C_CONTIGUOUS"]
+        addr = raw_draft.ctypes.data
+    else:
+        addr = _ptr(raw_draft)
+    out = C.c_int(0)
+    _check(load().ds_adl_first_eos(addr, k, stride, eos_id, C.byref(out)))
     return out.value
 
 

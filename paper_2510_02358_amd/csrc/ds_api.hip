@@ -199,6 +199,33 @@ int ds_refine_select(const int32_t* cand_id, const float* cand_logp, const int32
                               static_cast<hipStream_t>(stream));
 }
 
+int ds_refine_update_sizes(int K, int steps, int* sizes, int* n_sizes) {
+  DS_REQUIRE(sizes && n_sizes, DS_E_INVALID, "ds_refine_update_sizes: NULL pointer argument");
+  DS_REQUIRE(K >= 1 && K <= 256 && steps >= 1, DS_E_SHAPE, "need 1 <= K <= 256 and steps >= 1 (got %d, %d)", K, steps);
+  int left = K, n = 0;
+  for (int s = 1; s <= steps && left > 0; ++s) {
+    const int share = steps - s + 1;
+    const int u = (left + share - 1) / share;  // ceil(|M_{s-1}| / (S - s + 1))
+    sizes[n++] = u;
+    left -= u;
+  }
+  *n_sizes = n;
+  return DS_OK;
+}
+
+int ds_adl_first_eos(const int32_t* raw_draft, int k, int stride, int32_t eos_id, int* first_eos) {
+  DS_REQUIRE(raw_draft && first_eos, DS_E_INVALID, "ds_adl_first_eos: NULL pointer argument");
+  DS_REQUIRE(k >= 0 && stride >= 1, DS_E_SHAPE, "need k >= 0 and stride >= 1 (got %d, %d)", k, stride);
+  *first_eos = 0;
+  if (eos_id < 0) return DS_OK;
+  for (int i = 0; i < k; ++i)
+    if (raw_draft[(size_t)i * stride] == eos_id) {
+      *first_eos = i + 1;
+      break;
+    }
+  return DS_OK;
+}
+
 int ds_adl_create(int k_min, int k_max, double delta, double rho, ds_adl** out) {
   DS_REQUIRE(out, DS_E_INVALID, "out is NULL");
   *out = nullptr;

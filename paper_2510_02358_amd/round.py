@@ -84,27 +84,24 @@ class RoundParams:
     refine_steps: int = 1  # drafter passes per round (1: the single-pass round)
 
 
-def refine_update_sizes(k: int, steps: int) -> List[int]:
-    """How many still-masked positions each refinement pass fixes: equal shares, larger ones first."""
-    sizes, left = [], k
-    for s in range(steps):
-        if left == 0:
-            break
-        n = (left + steps - s - 1) // (steps - s)
-        sizes.append(n)
-        left -= n
-    return sizes
-
-
 class SpecDecoder:
     """One drafter + one verifier on one GPU, both caches holding the same prefix."""
 
     def __init__(self, drafter: DeviceModel, verifier: DeviceModel, table: Optional[np.ndarray], log2_size: int,
-                 params: RoundParams, k_cap: int = 64, keep_draft_logits: bool = False):
+                 params: RoundParams, k_cap: int = 64, keep_draft_logits: bool = False,
+                 keep_verify_logits: bool = False):
         """keep_draft_logits: also write the drafter's logits to `d_logits` every round (the lattice does not need
-        them in memory; stochastic verification does and gets them regardless)."""
+        them in memory; stochastic verification does and gets them regardless).  keep_verify_logits: also write the
+        verifier's logits of the block rows to `v_logits` (tests compare them with the oracle's)."""
+        if not 1 <= k_cap < ds.DS_MAX_ROWS:
+            raise ValueError(f"k_cap {k_cap} outside [1, {ds.DS_MAX_ROWS})")
+        if params.k_max > k_cap:
+            raise ValueError(f"params.k_max {params.k_max} exceeds k_cap {k_cap}: every per-round buffer is sized "
+                             "by k_cap")
         self.d, self.v, self.p = drafter, verifier, params
         self.keep_draft_logits = keep_draft_logits
+        self.v_logits = (torch.empty(k_cap + 1, verifier.cfg.vocab, dtype=torch.float32, device=DEV)
+                         if keep_verify_logits else None)
         self.eos_id = drafter.cfg.eos_id
         self.mask_id = drafter.cfg.mask_id
         vocab = drafter.cfg.vocab
@@ -202,9 +199,12 @@ class SpecDecoder:
         """
         p = self.p
         n_pend = len(self.pending)
-        vocab = self.d.cfg.vocab
+        if not 1 <= k <= self.k_cap:
+            raise ValueError(f"draft length {k} outside [1, k_cap = {self.k_cap}]")
+        if n_pend + k > ds.DS_MAX_ROWS:
+            raise ValueError(f"{n_pend} pending + {k} draft rows exceed {ds.DS_MAX_ROWS} rows per call")
         lat = (self.cand_id, self.cand_logp, self.cand_cnt, self.eos_logp, self.lse)
-        sizes = refine_update_sizes(k, p.refine_steps)
+        sizes = ds.ds_refine_update_sizes(k, p.refine_steps)
         logits_out = self.d_logits if (self.keep_draft_logits or uniforms is not None) else None
         if len(sizes) <= 1:
             ds.ds_draft_block(self.d.handle, self.pending_dev, n_pend, k, self.mask_id, self.hidden, self.d.ws, stream)
@@ -231,12 +231,12 @@ class SpecDecoder:
                 self.host_raw0[:k].copy_(lat[0][:k, 0], non_blocking=True)
         if uniforms is None:
             ds.ds_verify_block(self.v.handle, self.block, k, self.path_len, self.eos_id, self.result[0:1],
-                               self.result[1:2], self.argmax, self.result[2:3], None, self.v.ws, stream)
+                               self.result[1:2], self.argmax, self.result[2:3], self.v_logits, self.v.ws, stream)
         else:
             # the drafter rows of the path positions: with one drafter pass, the logits the lattice was built from
             ds.ds_verify_block_stochastic(self.v.handle, self.block, k, self.path_len, self.d_logits, uniforms,
                                           self.eos_id, self.result[0:1], self.result[1:2], self.result[2:3],
-                                          self.alpha, None, self.v.ws, stream)
+                                          self.alpha, self.v_logits, self.v.ws, stream)
 
     @property
     def pending_dev(self) -> torch.Tensor:
@@ -292,17 +292,16 @@ class SpecDecoder:
         res = self.result.numpy()
         n_acc, nxt, eos, plen = int(res[0]), int(res[1]), int(res[2]), int(out[self._len_at - self._out0])
         path = out[:plen].copy()
+        # the raw draft (per-position top-1 before the search) as the host read it back: s_t of the controller
         if refined:
-            raw0 = self.host_raw0.numpy()[:k]
+            first_eos = ds.ds_adl_first_eos(self.host_raw0, k, 1, self.eos_id)
         else:
-            c0 = self._cand_at - self._out0
-            raw0 = out[c0:c0 + k * self.p.m_max:self.p.m_max]
+            first_eos = ds.ds_adl_first_eos(self.host_out.data_ptr() + 4 * (self._cand_at - self._out0), k,
+                                            self.p.m_max, self.eos_id)
         self.v.set_kv_len(v_len + 1 + n_acc)
         committed = [int(t) for t in path[:n_acc]] + [nxt]
         self.tokens += committed
         self.pending = committed
-        eos_pos = np.nonzero(raw0 == self.eos_id)[0]
-        first_eos = int(eos_pos[0]) + 1 if len(eos_pos) else 0
         k_next = ds.ds_adl_update(self.adl, k, first_eos, n_acc)
         return {"k": k, "path": path, "path_len": plen, "n_accept": n_acc, "next_token": nxt, "eos_accepted": eos,
                 "committed": committed, "first_eos": first_eos, "k_next": k_next}

@@ -63,6 +63,31 @@ def test_adl_state_and_argument_errors():
             ds.ds_adl_create(*bad)
 
 
+def test_refinement_schedule_and_first_eos_through_the_c_abi_match_the_oracle():
+    """The two small host-side method steps the library owns (update-set sizes of the refinement equation, s_t of
+    the generation-length signal) against the oracle's own statements of them, over every K / S of interest."""
+    import numpy as np
+    from oracle import adl as o_adl
+    from oracle import refine as o_refine
+    for k in (1, 2, 3, 7, 8, 16, 31, 32, 64, 100, 256):
+        for steps in (1, 2, 3, 4, 7, 8, 10, 64, 300):
+            got = ds.ds_refine_update_sizes(k, steps)
+            assert got == o_refine.update_sizes(k, steps), (k, steps)
+            assert sum(got) == k and len(got) == min(k, steps) and got == sorted(got, reverse=True)
+    with pytest.raises(ds.DsError):
+        ds.ds_refine_update_sizes(0, 2)
+    rng = np.random.default_rng(0)
+    for case in range(200):
+        k, stride = int(rng.integers(0, 70)), int(rng.integers(1, 17))
+        eos = int(rng.choice([-1, 5, 9]))
+        buf = rng.integers(0, 12, size=max(k * stride, 1)).astype(np.int32)
+        raw = buf[: k * stride: stride] if k else buf[:0]
+        assert ds.ds_adl_first_eos(buf, k, stride, eos) == o_adl.first_eos_index(raw, eos), case
+    # the columns between the strided entries are ignored
+    buf = np.array([1, 9, 9, 2, 9, 9, 9, 0, 0], np.int32)
+    assert ds.ds_adl_first_eos(buf, 3, 3, 9) == 3 and ds.ds_adl_first_eos(buf, 2, 3, 9) == 0
+
+
 def test_bad_arguments_are_rejected_on_the_host_before_any_launch():
     lib = ds.load()
     # lattice: null pointers / bad widths

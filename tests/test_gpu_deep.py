@@ -1,0 +1,165 @@
+"""GPU parity at the shapes of the two deep workloads: the long-context attention plan of the 32B-shaped verifier
+(16384 cached keys) and several layers of the 7B shape driven through whole rounds with the adaptive draft length.
+
+The oracle cannot afford these workloads at full depth (64 GB of float64 conversions per forward), so depth and
+vocabulary are reduced while every per-layer shape, the cache capacity and the key count stay those of the workload.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import accept as o_accept
+from oracle import adl as o_adl
+from oracle import model as o_model
+from oracle import round as o_round
+from paper_2510_02358_amd import round as rnd
+from paper_2510_02358_amd import synth
+
+import gpu_util as gu
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+
+
+def _first_layer_cache(cfg, w, tokens):
+    """Oracle KV cache of a ONE-layer model for `tokens` at positions 0 .. n-1, from the oracle's own primitives.
+    In the first layer a token's key and value depend on its embedding and position only (attention feeds later
+    layers), so the causal prefill's attention, whose float64 cost grows with the square of the prefix, is not
+    needed to fill the cache.  The caller checks this against o_model.prefill on a short prefix."""
+    assert cfg.n_layers == 1
+    lw = w["layers"][0]
+    n = len(tokens)
+    cache = o_model.KVCache(cfg)
+    ks, vs = [], []
+    for lo in range(0, n, 2048):
+        tok = np.asarray(tokens[lo:lo + 2048])
+        h = o_model.rmsnorm(w["embed"][tok].astype(np.float64), lw["norm1"], cfg.rms_eps)
+        k = o_model.matmul_t(h, lw["wk"]).reshape(len(tok), cfg.n_kv, cfg.head_dim)
+        ks.append(o_model.rope(k, lo + np.arange(len(tok)), cfg.rope_base))
+        vs.append(o_model.matmul_t(h, lw["wv"]).reshape(len(tok), cfg.n_kv, cfg.head_dim))
+    cache.k[0], cache.v[0] = np.concatenate(ks), np.concatenate(vs)
+    return cache
+
+
+def test_32b_layer_bf16_prefix16384_k64_long_context_plan():
+    """One 32B-shaped layer (d = 5120, 40 query / 8 KV heads x 128, FFN 27648; vocabulary cut to 16384), cache
+    capacity 17408, 16384 cached keys: the split plan the long-context workload runs (29 key splits of 9 chunks).
+    Draft pass with 1 pending + 64 mask rows and a 65-row verifier pass, logits against the oracle within 2e-2;
+    arg-max rows exact or flagged on their own top-2 gap; the prefill's last-row logits (a row that attends to all
+    16384 keys through 114 prefill chunks) as well."""
+    cfg = replace(synth.CFG_32B_LAYER, vocab=16384)
+    w = synth.make_weights(cfg, 6)
+    synth.randomize_norm_gains(w, 16)
+    n_prefix, cap, k = 16384, 17408, 64
+    prefix = synth.make_prefix(cfg, n_prefix, 17)
+    # the shortcut for the oracle's cache, checked against the oracle's own prefill where that is affordable
+    short = o_model.KVCache(cfg)
+    o_model.prefill(cfg, w, short, prefix[:192])
+    quick = _first_layer_cache(cfg, w, prefix[:192])
+    assert np.allclose(quick.k[0], short.k[0], rtol=0, atol=1e-12) and np.allclose(quick.v[0], short.v[0], rtol=0, atol=1e-12)
+    oc = _first_layer_cache(cfg, w, prefix)
+    gm = gu.GpuModel(cfg, w, cap)
+    try:
+        got_last = gm.prefill(prefix)
+        assert gm.kv_len == n_prefix
+        oc.truncate(n_prefix - 1)
+        ref_last = o_model.verify_logits(cfg, w, oc, [int(prefix[-1])])[0]      # re-appends the last token
+        assert oc.length == n_prefix
+        err = float(np.max(np.abs(got_last - ref_last)))
+        assert err <= TOL, f"prefill last-row logits err {err}"
+        # draft: 1 pending + 64 mask rows see all 16384 + 65 keys
+        pend = [int(np.argmax(ref_last))]
+        ref_hid = o_model.draft_block(cfg, w, oc, pend, k)
+        hid = gm.draft(pend, k)
+        logits = gu.from_dev(gm.lm_head(hid))
+        ref_logits = o_model.lm_head(w, ref_hid)
+        h_err = float(np.max(np.abs(gu.from_dev(hid) - ref_hid)))
+        d_err = float(np.max(np.abs(logits - ref_logits)))
+        assert h_err <= 1e-2 and d_err <= TOL, (h_err, d_err)
+        assert d_err <= 0.05 * float(np.std(ref_logits))
+        # verify: 65 causal rows against the 16385-token cache
+        rng = np.random.default_rng(18)
+        block = np.concatenate([pend, rng.integers(0, cfg.n_plain_tokens, k)]).astype(np.int32)
+        gm.set_kv_len(n_prefix)
+        oc.truncate(n_prefix)
+        ref_v = o_model.verify_logits(cfg, w, oc, block)
+        out = gm.verify(block, eos_id=cfg.eos_id)
+        v_err = float(np.max(np.abs(out["logits"] - ref_v)))
+        assert v_err <= TOL, f"verify logits err {v_err}"
+        flagged = pu.argmax_rows_flagged(out["argmax"], ref_v, TOL)
+        n_acc, nxt, am, eos = o_accept.verify_greedy(out["logits"], block[1:], cfg.eos_id)
+        assert np.array_equal(out["argmax"], am) and (out["n_accept"], out["next_token"]) == (n_acc, nxt)
+        print(f"PARITY-COUNTS 32B layer at 16384 keys: prefill err {err:.2e}, draft hidden {h_err:.2e}, draft logits "
+              f"{d_err:.2e}, verify logits {v_err:.2e}, arg-max rows flagged {len(flagged)} of {k + 1}")
+    finally:
+        gm.close()
+
+
+def test_7b_shape_three_layers_bf16_rounds_with_adaptive_draft_length(record_property):
+    """Three layers of the 7B shape (d = 3584, 28 query / 4 KV heads, FFN 18944; vocabulary cut to 8192), a drafter
+    and a verifier with their own weights and random norm gains, prefix 256.
+    (1) Activations layer by layer: the draft pass of the first 1, 2 and 3 layers (each closed by the final norm)
+        against the oracle at the same depth, so that error growth through the float32 residual stream is seen.
+    (2) Four whole rounds with the draft length following ds_adl_update from 16 in [4, 64]: drafter and verifier
+        logits within 2e-2 every round; lattice rows, searched path and verdict exact or flagged on the deviating
+        item's own near-tie (tests/parity_util.py); the search and the acceptance rule exact on the GPU's own
+        numbers; KV lengths, committed tokens and the next draft length equal to the oracle's."""
+    cfg = replace(synth.with_layers(synth.CFG_7B_LAYER, 3), vocab=8192)
+    dw, vw = synth.make_weights(cfg, 20), synth.make_weights(cfg, 21)
+    synth.randomize_norm_gains(dw, 22)
+    synth.randomize_norm_gains(vw, 23)
+    prefix = synth.make_prefix(cfg, 256, 24)
+    table = synth.make_ngram_table(3)
+    # (1) depth by depth
+    growth = []
+    for depth in (1, 2, 3):
+        sub = synth.with_layers(cfg, depth)
+        sw = dict(dw)
+        sw["layers"] = dw["layers"][:depth]
+        gm = gu.GpuModel(sub, sw, 512)
+        try:
+            oc = o_model.KVCache(sub)
+            ref_last = o_model.prefill(sub, sw, oc, prefix)
+            got_last = gm.prefill(prefix)
+            ref_hid = o_model.draft_block(sub, sw, oc, [7], 32)
+            hid = gu.from_dev(gm.draft([7], 32))
+            growth.append((float(np.max(np.abs(got_last - ref_last))), float(np.max(np.abs(hid - ref_hid)))))
+            assert growth[-1][0] <= TOL and growth[-1][1] <= 1e-2, (depth, growth)
+        finally:
+            gm.close()
+    print("PARITY-COUNTS 7B shape, error after 1 / 2 / 3 layers (prefill logits, draft hidden):", growth)
+    # (2) whole rounds
+    params = rnd.RoundParams(m_max=8, tau=1.0, beam=4, lam=0.5, k_min=4, k_max=64, delta=10.0, rho=0.5)
+    dm, vm = rnd.DeviceModel(cfg, dw, 512), rnd.DeviceModel(cfg, vw, 512)
+    dec = rnd.SpecDecoder(dm, vm, table, synth.NGRAM_LOG2_SIZE, params, k_cap=64, keep_draft_logits=True,
+                          keep_verify_logits=True)
+    counts = pu.new_counts()
+    try:
+        dec.start(prefix)
+        st = o_round.SpecState(cfg, dw, cfg, vw, prefix)
+        if dec.tokens != st.tokens:    # the first pending token is a verifier arg-max: only a near-tie may move it
+            vc = o_model.KVCache(cfg)
+            pu.argmax_rows_flagged(np.array([dec.tokens[-1]]), o_model.prefill(cfg, vw, vc, prefix)[None], TOL)
+            pytest.skip("the prefill arg-max sits on a near-tie: the two streams start apart")
+        adl = o_adl.AdlState(params.k_min, params.k_max, params.delta, params.rho)
+        k, ks = 16, []
+        for t in range(4):
+            ks.append(k)
+            got = dec.round(k)
+            ref = pu.compare_round(dec, st, got, k, params, table, TOL, counts)
+            if ref is None:
+                break
+            counts["rounds"] += 1
+            k_ref = o_adl.adl_update(adl, k, got["first_eos"], ref["n_accept"])
+            assert got["k_next"] == k_ref and dec.tokens == st.tokens
+            assert dm.kv_len == st.dcache.length and vm.kv_len == st.vcache.length
+            k = k_ref
+        print("PARITY-COUNTS 7B shape x 3 layers, rounds with adaptive draft length", ks, counts)
+        record_property("parity_counts", counts)
+        assert counts["rounds"] >= 2, counts
+    finally:
+        dec.close(); dm.close(); vm.close()

@@ -33,13 +33,14 @@ def _compare_lattice(got: dict, ref: dict, logits: np.ndarray):
     return g
 
 
-@pytest.mark.parametrize("k_len", [8, 16])
-def test_lattice_full_vocab_batch16(k_len):
-    """Stress-test shape: 16 sequences x K positions x 152064 logits, top-16."""
+@pytest.mark.parametrize("k_len,tau", [(8, 1.0), (16, 1.0), (32, 0.8)])
+def test_lattice_full_vocab_batch16(k_len, tau):
+    """Stress-test shape: 16 sequences x K positions x 152064 logits, top-16; every row of every array against the
+    oracle (K = 32 with mass pruning on: 512 rows, 311 MB of logits)."""
     logits = synth.make_logits(16, k_len, VOCAB, seed=40 + k_len)
     eos = VOCAB - 2
-    ref = o_lat.build_lattice(logits, 16, 1.0, eos)
-    got = gu.gpu_lattice(gu.to_dev(logits), 16, 1.0, eos)
+    ref = o_lat.build_lattice(logits, 16, tau, eos)
+    got = gu.gpu_lattice(gu.to_dev(logits), 16, tau, eos)
     _compare_lattice(got, ref, logits)
 
 

@@ -273,3 +273,24 @@ def test_ngram_slot_is_a_fixed_uint32_function():
         assert cps.ngram_slot(u, v, w, 22) == ref(u, v, w, 22)
     assert cps.ngram_slot(0, 0, 0, 22) == 0
     assert len({cps.ngram_slot(1, 2, w, 22) for w in range(1000)}) > 990
+
+
+def test_search_margins_are_the_gaps_at_the_beam_boundary():
+    """The diagnostic margins of the oracle search: per depth the smallest gap between neighbouring scores among the
+    kept hypotheses and the best dropped one (hand-made two-position lattice, no proxy, lambda = 1)."""
+    lat = {"cand_id": np.array([[1, 2, 3], [4, 5, 6]], np.int32),
+           "cand_logp": np.array([[-1.0, -1.5, -4.0], [-0.25, -2.0, -2.125]], np.float32),
+           "cand_cnt": np.array([3, 3], np.int32), "eos_logp": np.zeros(2, np.float32)}
+    m = []
+    toks, score, _ = cps.cps_path(lat, 0, 2, 2, 1.0, None, 0, [0, 0], -1, margins=m)
+    assert toks == [1, 4] and score == f32(-1.25)
+    # depth 0: kept -1.0, -1.5, dropped -4.0 -> gaps 0.5, 2.5; depth 1: scores -1.25, -1.75 kept, -3.0 dropped
+    assert m == [0.5, 0.5]
+    m = []
+    cps.cps_path(lat, 0, 2, 3, 1.0, None, 0, [0, 0], -1, margins=m)
+    # beam 3, depth 1: nine expansions -1.25 -1.75 -3.0 -3.125 -3.5 -3.625 ...: kept three, best dropped -3.125
+    assert m == [0.5, 0.125]
+    m = []
+    cps.cps_path(lat, 0, 1, 4, 1.0, None, 0, [0, 0], -1, margins=m)
+    assert m == [0.5]
+    assert cps.cps_path(lat, 0, 2, 2, 1.0, None, 0, [0, 0], -1)[0] == [1, 4]   # unchanged without the list
