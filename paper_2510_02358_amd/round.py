@@ -185,7 +185,8 @@ class SpecDecoder:
         self.tokens = [int(x) for x in prefix] + [first]
         self.pending = [first]
 
-    def enqueue_round(self, k: int, stream=None, inject=None, uniforms=None, readback: bool = False) -> None:
+    def enqueue_round(self, k: int, stream=None, inject=None, uniforms=None, readback: bool = False,
+                      lm_events=None) -> None:
         """Enqueue draft -> LM head -> lattice -> path search -> verify for the current state.  No sync.
 
         inject = (device int32 tensor, a): overwrite the first `a` searched path tokens with these tokens before
@@ -196,6 +197,8 @@ class SpecDecoder:
         readback: also copy the searched path, its length and the candidate ids to pinned host memory; the copy is
         issued BEFORE the verifier pass (everything it reads is final by then), so it is long done when the verdict
         arrives and the round's host crossing is the verdict alone.
+        lm_events = (start, end) torch events: recorded around the drafter's LM-head product alone (the two-call form
+        of ds_draft_lattice; same kernels), for benchmarks that report that kernel's time.
         """
         p = self.p
         n_pend = len(self.pending)
@@ -208,7 +211,14 @@ class SpecDecoder:
         logits_out = self.d_logits if (self.keep_draft_logits or uniforms is not None) else None
         if len(sizes) <= 1:
             ds.ds_draft_block(self.d.handle, self.pending_dev, n_pend, k, self.mask_id, self.hidden, self.d.ws, stream)
-            ds.ds_draft_lattice(self.d.handle, None, k, p.m_max, p.tau, self.eos_id, *lat, logits_out, self.d.ws, stream)
+            if lm_events is None:
+                ds.ds_draft_lattice(self.d.handle, None, k, p.m_max, p.tau, self.eos_id, *lat, logits_out, self.d.ws,
+                                    stream)
+            else:
+                lm_events[0].record()
+                ds.ds_lm_head_tiles(self.d.handle, None, k, self.eos_id, logits_out, self.d.ws, stream)
+                lm_events[1].record()
+                ds.ds_lattice_from_tiles(self.d.handle, k, p.m_max, p.tau, self.eos_id, *lat, self.d.ws, stream)
         else:
             self.blk[:k].fill_(self.mask_id)
             final = (self.f_cand_id, self.f_cand_logp, self.f_cand_cnt, self.f_eos_logp, self.f_lse)
@@ -274,7 +284,7 @@ class SpecDecoder:
         h[n + 1] = self.tokens[-1]
         self.io[self._p - n:self._p + 2].copy_(self.host[:n + 2], non_blocking=True)
 
-    def round(self, k: int, inject=None, uniforms=None) -> dict:
+    def round(self, k: int, inject=None, uniforms=None, lm_events=None) -> dict:
         """One full round including the host read-back, KV commit and the draft-length update."""
         self.stage_inputs()
         v_len = self.v.kv_len
@@ -285,7 +295,8 @@ class SpecDecoder:
             self.u[:k + 1].copy_(uniforms if isinstance(uniforms, torch.Tensor)
                                  else torch.from_numpy(np.asarray(uniforms, dtype=np.float32)), non_blocking=False)
         self.arm_verdict()
-        self.enqueue_round(k, inject=inject, uniforms=self.u if uniforms is not None else None, readback=True)
+        self.enqueue_round(k, inject=inject, uniforms=self.u if uniforms is not None else None, readback=True,
+                           lm_events=lm_events)
         refined = self.lat_used[0] is not self.cand_id
         self.wait_verdict()  # the one host crossing; the path / candidate copy finished during the verifier pass
         out = self.host_out.numpy()
