@@ -100,6 +100,12 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
                     void* kv_k, void* kv_v, void* stream, ds_model** out);
 void ds_model_destroy(ds_model* m);
 
+/* DS_BF16 models run every activation that meets a weight, and q / k / v, in IEEE half: a value beyond +-65504 (or a
+ * NaN) is clamped to +-65504 instead of becoming infinite, and counted.  *count [host] receives the number of such
+ * activation values since the model was created or the counter was last reset (reset != 0 clears it); 0 means no
+ * forward of this model was touched by the half range.  Always 0 for DS_F32.  Synchronises `stream`. */
+int ds_model_overflow_count(ds_model* m, int reset, void* stream, uint32_t* count);
+
 /* Committed KV length: query, and set (truncate after a rejection / commit after verification). */
 int ds_model_kv_len(const ds_model* m, int* len);
 int ds_model_kv_set_len(ds_model* m, int len);

@@ -25,7 +25,7 @@ EXPORTS = [
     "ds_ngram_destroy", "ds_cps_workspace_bytes", "ds_cps_path", "ds_verify_block", "ds_adl_create", "ds_adl_destroy",
     "ds_adl_update", "ds_adl_state", "ds_sample_workspace_bytes", "ds_accept_stochastic",
     "ds_verify_block_stochastic", "ds_draft_block_tokens", "ds_refine_select", "ds_build_lattice_static",
-    "ds_refine_update_sizes", "ds_adl_first_eos",
+    "ds_refine_update_sizes", "ds_adl_first_eos", "ds_model_overflow_count",
 ]
 
 
@@ -78,6 +78,7 @@ def load():
     lib.ds_kv_bytes.argtypes = [C.POINTER(ModelCfgC), C.POINTER(sz)]
     lib.ds_model_create.argtypes = [C.POINTER(ModelCfgC), C.POINTER(WeightsC), vp, sz, vp, vp, vp, C.POINTER(vp)]
     lib.ds_model_destroy.argtypes = [vp]
+    lib.ds_model_overflow_count.argtypes = [vp, C.c_int, vp, C.POINTER(C.c_uint32)]
     lib.ds_model_kv_len.argtypes = [vp, C.POINTER(C.c_int)]
     lib.ds_model_kv_set_len.argtypes = [vp, C.c_int]
     lib.ds_prefill.argtypes = [vp, vp, C.c_int, vp, vp, sz, vp]
@@ -187,6 +188,12 @@ def ds_model_create(cfgc: ModelCfgC, weights: dict, packed, kv_k, kv_v, stream=N
 
 def ds_model_destroy(model: int) -> None:
     load().ds_model_destroy(model)
+
+
+def ds_model_overflow_count(model: int, reset: bool = False, stream=None) -> int:
+    out = C.c_uint32(0)
+    _check(load().ds_model_overflow_count(model, 1 if reset else 0, _stream(stream), C.byref(out)))
+    return out.value
 
 
 def ds_model_kv_len(model: int) -> int:

@@ -57,20 +57,23 @@ __host__ __device__ static inline size_t kv_v_offset(int pos, int dim) {
 template <typename T>
 struct Act;
 
+// `ovf` in the stores below: the model's activation-overflow counter ([dev] uint32, or NULL).  A half-precision
+// model counts there every activation that did not fit the half range and was clamped to +-65504 (or was NaN), so
+// that a caller can tell a clean forward from one whose logits the clamp has touched; float32 models never count.
 template <>
 struct Act<float> {
   using kv_t = float;                         // element type of q / K cache / V cache
   static constexpr bool kTiledKV = false;     // row-major [capacity][head_dim] per head
   // GEMM-input store: element (m, k) of a [rows_pad, K] activation
-  __device__ static __forceinline__ void put(float* base, int m, int k, int K, float v) {
+  __device__ static __forceinline__ void put(float* base, int m, int k, int K, float v, uint32_t*) {
     base[(size_t)m * K + k] = v;
   }
   // four consecutive columns k .. k+3 (k % 4 == 0)
-  __device__ static __forceinline__ void put4(float* base, int m, int k, int K, float4 v) {
+  __device__ static __forceinline__ void put4(float* base, int m, int k, int K, float4 v, uint32_t*) {
     *reinterpret_cast<float4*>(base + (size_t)m * K + k) = v;
   }
   __device__ static __forceinline__ size_t q_off(int m, int k, int K) { return (size_t)m * K + k; }
-  __device__ static __forceinline__ float to_kv(float v) { return v; }
+  __device__ static __forceinline__ float to_kv(float v, uint32_t*) { return v; }
   __device__ static __forceinline__ float weight(float v) { return v; }
 };
 
@@ -80,19 +83,27 @@ struct Act<bf16_t> {
   static constexpr bool kTiledKV = true;      // operand-tile order, see kv_k_offset / kv_v_offset
   // GEMM-input store: element (m, k) of a [rows_pad, K] half activation in tile order (values beyond the half
   // range saturate to +-65504 instead of becoming infinite)
+  __device__ static __forceinline__ bool over(float v) { return !(fabsf(v) <= 65504.f); }  // also true for NaN
   __device__ static __forceinline__ uint16_t gemm_in(float v) {
     return float_to_half_bits(fminf(fmaxf(v, -65504.f), 65504.f));
   }
-  __device__ static __forceinline__ void put(bf16_t* base, int m, int k, int K, float v) {
+  __device__ static __forceinline__ void put(bf16_t* base, int m, int k, int K, float v, uint32_t* ovf) {
     base[xt_offset(m, k, K)].bits = gemm_in(v);
+    if (ovf && over(v)) atomicAdd(ovf, 1u);
   }
   // four consecutive columns k .. k+3 (k % 4 == 0) are adjacent in tile order: one 8-byte store
-  __device__ static __forceinline__ void put4(bf16_t* base, int m, int k, int K, float4 v) {
+  __device__ static __forceinline__ void put4(bf16_t* base, int m, int k, int K, float4 v, uint32_t* ovf) {
     const uint32_t h0 = gemm_in(v.x), h1 = gemm_in(v.y), h2 = gemm_in(v.z), h3 = gemm_in(v.w);
     *reinterpret_cast<uint2*>(base + xt_offset(m, k, K)) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+    const uint32_t n = (uint32_t)over(v.x) + (uint32_t)over(v.y) + (uint32_t)over(v.z) + (uint32_t)over(v.w);
+    if (ovf && n) atomicAdd(ovf, n);
   }
   __device__ static __forceinline__ size_t q_off(int m, int k, int K) { return xt_offset(m, k, K); }
-  __device__ static __forceinline__ uint16_t to_kv(float v) { return float_to_half_bits(v); }
+  // queries, keys and values: clamped like every other half activation, and counted
+  __device__ static __forceinline__ uint16_t to_kv(float v, uint32_t* ovf) {
+    if (ovf && over(v)) atomicAdd(ovf, 1u);
+    return gemm_in(v);
+  }
   __device__ static __forceinline__ float weight(bf16_t v) { return bf16_bits_to_float(v.bits); }
 };
 
@@ -102,17 +113,18 @@ struct Act<bf16_t> {
 template <typename T>
 int launch_embed_norm(const int32_t* src, int n_real, const int32_t* src2, int32_t fill, int vocab, int pos0, int hd,
                       double rope_base, float2* cs, const void* embed, float* x, int rows, int rows_pad, int d,
-                      const float* gain, float eps, void* h, hipStream_t st);
+                      const float* gain, float eps, void* h, uint32_t* ovf, hipStream_t st);
 template <typename T>
 int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
-                    float eps, void* h, float* rm_out, void* h_tail, int rm_row0, hipStream_t st);
+                    float eps, void* h, float* rm_out, void* h_tail, int rm_row0, uint32_t* ovf, hipStream_t st);
 template <typename T>
-int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* dst, hipStream_t st);
+int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* dst, uint32_t* ovf, hipStream_t st);
 template <typename T>
 int launch_qkv_rope(const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv, int hd,
-                    const float2* cs, int pos0, int cap, void* q, void* kc, void* vc, hipStream_t st);
+                    const float2* cs, int pos0, int cap, void* q, void* kc, void* vc, uint32_t* ovf, hipStream_t st);
 template <typename T>
-int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, hipStream_t st);
+int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, uint32_t* ovf,
+                  hipStream_t st);
 
 // bf16 -> half re-encoding into stream order; *range_flag [dev] is set to 1 if any |w| exceeds the half range
 int launch_pack_weight(const void* w, int N, int K, void* dst, uint32_t* range_flag, hipStream_t st);
@@ -149,6 +161,6 @@ AttnPlan attn_plan(int dtype, int cap, int n_keys);
 int attn_partial_rows(int rows_pad);
 int launch_attention(int dtype, const void* q, const void* kc, const void* vc, int rows, int rows_pad, int n_causal,
                      int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, float* part_o, float* part_ml,
-                     void* att_out, hipStream_t st);
+                     void* att_out, uint32_t* ovf, hipStream_t st);
 
 }  // namespace ds

@@ -54,6 +54,7 @@ struct ds_model {
   void *kv_k, *kv_v;
   int kv_len;
   size_t esize;
+  uint32_t* ovf = nullptr;  // [dev] activation-overflow counter (bf16 models: a word of the packed buffer's tail)
   // what the last draft pass left behind for ds_lm_head(hidden = NULL): the block rows as a GEMM input
   const void* tail_ptr = nullptr;
   const void* tail_ws = nullptr;
@@ -228,7 +229,7 @@ int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real
   const int d = c.d_model, hd = c.head_dim;
   int rc;
   if ((rc = launch_embed_norm<T>(src, n_real, src2, fill, c.vocab, pos0, hd, (double)c.rope_base, w.cs, m->embed, w.x, rows,
-                                 rp, d, m->canon[0].norm1, c.rms_eps, w.h, st)))
+                                 rp, d, m->canon[0].norm1, c.rms_eps, w.h, m->ovf, st)))
     return rc;
   for (int li = 0; li < c.n_layers; ++li) {
     const size_t layer_elems = (size_t)c.n_kv * c.kv_capacity * hd;
@@ -237,22 +238,23 @@ int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real
     int sp = 1;
     if ((rc = gemm<T>(m, li, 0, w.h, rows, w.gemm_out, &sp, st))) return rc;
     if ((rc = launch_qkv_rope<T>(w.gemm_out, sp, rows, rp, c.n_q, c.n_kv, hd, w.cs, pos0, c.kv_capacity, w.q, kc, vc,
-                                 st)))
+                                 m->ovf, st)))
       return rc;
     if ((rc = launch_attention(c.dtype, w.q, kc, vc, rows, rp, n_causal, pos0, n_keys, c.n_q, c.n_kv, hd,
-                               c.kv_capacity, w.att_o, w.att_ml, w.att, st)))
+                               c.kv_capacity, w.att_o, w.att_ml, w.att, m->ovf, st)))
       return rc;
     if ((rc = gemm<T>(m, li, 1, w.att, rows, w.gemm_out, &sp, st))) return rc;
-    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr, nullptr, 0, st)))
+    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr, nullptr, 0,
+                                 m->ovf, st)))
       return rc;
     if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st))) return rc;
-    if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, rp, c.d_ffn, w.act, st))) return rc;
+    if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, rp, c.d_ffn, w.act, m->ovf, st))) return rc;
     if ((rc = gemm<T>(m, li, 3, w.act, rows, w.gemm_out, &sp, st))) return rc;
     const bool last = li + 1 == c.n_layers;
     const float* gain = last ? m->final_norm : m->canon[li + 1].norm1;
     if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, gain, c.rms_eps, last ? w.y : w.h,
                                  last ? hidden_out : nullptr, (last && hidden_out) ? w.y_tail : nullptr,
-                                 hidden_row0, st)))
+                                 hidden_row0, m->ovf, st)))
       return rc;
   }
   return DS_OK;
@@ -357,7 +359,8 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
     char* p = static_cast<char*>(packed);
     const int d = cfg->d_model, f = cfg->d_ffn, hd = cfg->head_dim, qo = cfg->n_q * hd, kvn = cfg->n_kv * hd;
     uint32_t* flag = reinterpret_cast<uint32_t*>(p + need - kFlagBytes);
-    if (hipMemsetAsync(flag, 0, sizeof(uint32_t), st) != hipSuccess) {
+    m->ovf = flag + 16;  // its own 64-byte line of the tail
+    if (hipMemsetAsync(flag, 0, kFlagBytes, st) != hipSuccess) {
       delete m;
       return fail(DS_E_HIP, "hipMemsetAsync(weight-range flag) failed");
     }
@@ -402,6 +405,17 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
 
 void ds_model_destroy(ds_model* m) { delete m; }
 
+int ds_model_overflow_count(ds_model* m, int reset, void* stream, uint32_t* count) {
+  DS_REQUIRE(m && count, DS_E_INVALID, "ds_model_overflow_count: NULL pointer argument");
+  *count = 0;
+  if (!m->ovf) return DS_OK;  // float32 models have no half-precision rounding points
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DS_HIP_CHECK(hipMemcpyAsync(count, m->ovf, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+  if (reset) DS_HIP_CHECK(hipMemsetAsync(m->ovf, 0, sizeof(uint32_t), st));
+  DS_HIP_CHECK(hipStreamSynchronize(st));
+  return DS_OK;
+}
+
 int ds_model_kv_len(const ds_model* m, int* len) {
   DS_REQUIRE(m && len, DS_E_INVALID, "ds_model_kv_len: NULL pointer argument");
   *len = m->kv_len;
@@ -441,9 +455,13 @@ int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, vo
     m->kv_len += rows;
     if (last_logits && done + rows == n) {
       // logits of all rows of the last chunk, then copy the last row out
-      if ((rc = lm_head_rows(m, w.y, rows, w.logits, st))) return rc;
-      DS_HIP_CHECK(hipMemcpyAsync(last_logits, w.logits + (size_t)(rows - 1) * m->cfg.vocab,
-                                  (size_t)m->cfg.vocab * 4, hipMemcpyDeviceToDevice, st));
+      if ((rc = lm_head_rows(m, w.y, rows, w.logits, st)) ||
+          (hipMemcpyAsync(last_logits, w.logits + (size_t)(rows - 1) * m->cfg.vocab, (size_t)m->cfg.vocab * 4,
+                          hipMemcpyDeviceToDevice, st) != hipSuccess &&
+           (rc = fail(DS_E_HIP, "ds_prefill: copying the last row's logits failed")))) {
+        m->kv_len = start_len;  // a failed call changes no state
+        return rc;
+      }
     }
   }
   return DS_OK;
@@ -486,7 +504,7 @@ int ds_lm_head(ds_model* m, const float* hidden, int rows, float* logits, void* 
   }
   if (m->cfg.dtype == DS_BF16) {
     const int rp = ceil_div(rows, 16) * 16;
-    if ((rc = launch_to_gemm_input<bf16_t>(hidden, rows, rp, m->cfg.d_model, w.y, st))) return rc;
+    if ((rc = launch_to_gemm_input<bf16_t>(hidden, rows, rp, m->cfg.d_model, w.y, m->ovf, st))) return rc;
     return lm_head_rows(m, w.y, rows, logits, st);
   }
   return lm_head_rows(m, hidden, rows, logits, st);
@@ -511,7 +529,7 @@ int ds_lm_head_tiles(ds_model* m, const float* hidden, int rows, int32_t eos_id,
     y = m->tail_ptr;
   } else if (m->cfg.dtype == DS_BF16) {
     const int rp = ceil_div(rows, 16) * 16;
-    if ((rc = launch_to_gemm_input<bf16_t>(hidden, rows, rp, m->cfg.d_model, w.y, st))) return rc;
+    if ((rc = launch_to_gemm_input<bf16_t>(hidden, rows, rp, m->cfg.d_model, w.y, m->ovf, st))) return rc;
     y = w.y;
   } else {
     y = hidden;

@@ -288,7 +288,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
 // several splits are in flight together.
 template <typename T>
 __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int n_split,
-                                  int n_q, int rows_pad, int hd, T* __restrict__ att) {
+                                  int n_q, int rows_pad, int hd, T* __restrict__ att, uint32_t* __restrict__ ovf) {
   // att: GEMM input [rows_pad, n_q * hd] of the output projection
   const int r = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
   if (d >= hd) return;
@@ -307,7 +307,7 @@ __global__ void attn_merge_kernel(const float* __restrict__ part_o, const float*
     num += o * w;
     den += l * w;
   }
-  Act<T>::put(att, r, head * hd + d, n_q * hd, num / den);
+  Act<T>::put(att, r, head * hd + d, n_q * hd, num / den, ovf);
 }
 
 }  // namespace
@@ -340,7 +340,7 @@ AttnPlan attn_plan(int dtype, int cap, int n_keys) {
 
 int launch_attention(int dtype, const void* q, const void* kc, const void* vc, int rows, int rows_pad, int n_causal,
                      int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, float* part_o, float* part_ml,
-                     void* att_out, hipStream_t st) {
+                     void* att_out, uint32_t* ovf, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)hd);
   DS_REQUIRE(n_keys >= 1 && n_keys <= cap, DS_E_CAPACITY, "attention: %d keys exceed the cache capacity %d", n_keys, cap);
   const AttnPlan plan = attn_plan(dtype, cap, n_keys);
@@ -358,7 +358,7 @@ int launch_attention(int dtype, const void* q, const void* kc, const void* vc, i
                        part_ml);
     DS_LAUNCH_CHECK("attn_f16_kernel");
     hipLaunchKernelGGL((attn_merge_kernel<bf16_t>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, plan.n_split,
-                       n_q, rows_pad, hd, static_cast<bf16_t*>(att_out));
+                       n_q, rows_pad, hd, static_cast<bf16_t*>(att_out), ovf);
     DS_LAUNCH_CHECK("attn_merge_kernel<bf16>");
   } else {
     DS_REQUIRE(hd <= 128 && (hd & 1) == 0, DS_E_UNSUPPORTED, "f32 attention needs even head_dim <= 128 (got %d)", hd);
@@ -367,7 +367,7 @@ int launch_attention(int dtype, const void* q, const void* kc, const void* vc, i
                        n_keys, n_q, n_kv, hd, cap, plan.chunks_per_split, scale, part_o, part_ml);
     DS_LAUNCH_CHECK("attn_f32_kernel");
     hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, plan.n_split,
-                       n_q, rows_pad, hd, static_cast<float*>(att_out));
+                       n_q, rows_pad, hd, static_cast<float*>(att_out), ovf);
     DS_LAUNCH_CHECK("attn_merge_kernel<f32>");
   }
   return DS_OK;

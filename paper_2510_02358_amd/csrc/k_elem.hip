@@ -54,7 +54,7 @@ __global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, const T* __
                                                    int n_part, int rows, int rows_pad, int d,
                                                    const float* __restrict__ gain, float eps, T* __restrict__ h,
                                                    float* __restrict__ rm_out, T* __restrict__ h_tail,
-                                                   int rm_row0) {
+                                                   int rm_row0, uint32_t* __restrict__ ovf) {
   constexpr int kMaxVec = 8192 / (4 * THREADS);  // float4 groups per thread (d_model <= 8192)
   __shared__ float red[THREADS / 64];
   const int r = blockIdx.x;
@@ -105,19 +105,20 @@ __global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, const T* __
     if (c < d) {
       const float4 gn = *reinterpret_cast<const float4*>(gain + c);
       const float4 y = make_float4(v[i].x * inv * gn.x, v[i].y * inv * gn.y, v[i].z * inv * gn.z, v[i].w * inv * gn.w);
-      Act<T>::put4(h, r, c, d, y);
+      Act<T>::put4(h, r, c, d, y, ovf);
       if (rm_out && r >= rm_row0) *reinterpret_cast<float4*>(rm_out + (size_t)(r - rm_row0) * d + c) = y;
-      if (h_tail && r >= rm_row0) Act<T>::put4(h_tail, r - rm_row0, c, d, y);
+      if (h_tail && r >= rm_row0) Act<T>::put4(h_tail, r - rm_row0, c, d, y, nullptr);
     }
   }
 }
 
 // Row-major float32 hidden states [rows, d] -> GEMM input order.
 template <typename T>
-__global__ void to_gemm_input_kernel(const float* __restrict__ src, int rows_pad, int d, T* __restrict__ dst) {
+__global__ void to_gemm_input_kernel(const float* __restrict__ src, int rows_pad, int d, T* __restrict__ dst,
+                                     uint32_t* __restrict__ ovf) {
   const int r = blockIdx.x;
   for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4)
-    Act<T>::put4(dst, r, c, d, *reinterpret_cast<const float4*>(src + (size_t)r * d + c));
+    Act<T>::put4(dst, r, c, d, *reinterpret_cast<const float4*>(src + (size_t)r * d + c), ovf);
 }
 
 // One wavefront per (row, head slot): sums the QKV partial planes, rotates q and k, writes q in the
@@ -127,7 +128,7 @@ template <typename T>
 __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int n_q,
                                 int n_kv, int hd, const float2* __restrict__ cs, int pos0, int cap,
                                 typename Act<T>::kv_t* __restrict__ q, typename Act<T>::kv_t* __restrict__ kc,
-                                typename Act<T>::kv_t* __restrict__ vc) {
+                                typename Act<T>::kv_t* __restrict__ vc, uint32_t* __restrict__ ovf) {
   using KV = typename Act<T>::kv_t;
   const int r = blockIdx.x, slot = blockIdx.y, i = threadIdx.x, half = hd >> 1;
   if (i >= half) return;
@@ -161,28 +162,28 @@ __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int 
   const int pos = pos0 + r;
   if (slot < n_q) {
     KV* qh = q + (size_t)slot * rows_pad * hd;
-    qh[Act<T>::q_off(r, i, hd)] = Act<T>::to_kv(a);
-    qh[Act<T>::q_off(r, i + half, hd)] = Act<T>::to_kv(b);
+    qh[Act<T>::q_off(r, i, hd)] = Act<T>::to_kv(a, ovf);
+    qh[Act<T>::q_off(r, i + half, hd)] = Act<T>::to_kv(b, ovf);
   } else if (slot < n_q + n_kv) {
     if (Act<T>::kTiledKV) {
       KV* kh = kc + (size_t)(slot - n_q) * cap * hd;
-      kh[kv_k_offset(pos, i)] = Act<T>::to_kv(a);
-      kh[kv_k_offset(pos, i + half)] = Act<T>::to_kv(b);
+      kh[kv_k_offset(pos, i)] = Act<T>::to_kv(a, ovf);
+      kh[kv_k_offset(pos, i + half)] = Act<T>::to_kv(b, ovf);
     } else {
       KV* kh = kc + ((size_t)(slot - n_q) * cap + pos) * hd;
-      kh[i] = Act<T>::to_kv(a);
-      kh[i + half] = Act<T>::to_kv(b);
+      kh[i] = Act<T>::to_kv(a, ovf);
+      kh[i + half] = Act<T>::to_kv(b, ovf);
     }
   } else {
     const int kvh = slot - n_q - n_kv;
     if (Act<T>::kTiledKV) {
       KV* vh = vc + (size_t)kvh * cap * hd;
-      vh[kv_v_offset(pos, i)] = Act<T>::to_kv(a);
-      vh[kv_v_offset(pos, i + half)] = Act<T>::to_kv(b);
+      vh[kv_v_offset(pos, i)] = Act<T>::to_kv(a, ovf);
+      vh[kv_v_offset(pos, i + half)] = Act<T>::to_kv(b, ovf);
     } else {
       KV* vh = vc + ((size_t)kvh * cap + pos) * hd;
-      vh[i] = Act<T>::to_kv(a);
-      vh[i + half] = Act<T>::to_kv(b);
+      vh[i] = Act<T>::to_kv(a, ovf);
+      vh[i + half] = Act<T>::to_kv(b, ovf);
     }
   }
 }
@@ -191,7 +192,7 @@ __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int 
 // consecutive f per thread (F % 4 == 0).
 template <typename T>
 __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int F,
-                              T* __restrict__ act) {
+                              T* __restrict__ act, uint32_t* __restrict__ ovf) {
   const int r = blockIdx.y;
   const int f = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (f >= F) return;
@@ -215,7 +216,7 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
     }
   const float4 y = make_float4(g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
                                g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w);
-  Act<T>::put4(act, r, f, F, y);
+  Act<T>::put4(act, r, f, F, y, ovf);
 }
 
 }  // namespace
@@ -223,73 +224,75 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
 template <typename T>
 int launch_embed_norm(const int32_t* src, int n_real, const int32_t* src2, int32_t fill, int vocab, int pos0, int hd,
                       double rope_base, float2* cs, const void* embed, float* x, int rows, int rows_pad, int d,
-                      const float* gain, float eps, void* h, hipStream_t st) {
+                      const float* gain, float eps, void* h, uint32_t* ovf, hipStream_t st) {
   Prologue pro{src, src2, n_real, vocab, fill, pos0, hd / 2, log2(rope_base), cs};
   if (d >= 2048)
     hipLaunchKernelGGL((norm_kernel<T, true, 1024>), dim3(rows), dim3(1024), 0, st, pro, static_cast<const T*>(embed),
                        x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr,
-                       (T*)nullptr, 0);
+                       (T*)nullptr, 0, ovf);
   else
     hipLaunchKernelGGL((norm_kernel<T, true, 256>), dim3(rows), dim3(256), 0, st, pro, static_cast<const T*>(embed),
                        x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr,
-                       (T*)nullptr, 0);
+                       (T*)nullptr, 0, ovf);
   DS_LAUNCH_CHECK("norm_kernel<embed>");
   return DS_OK;
 }
 
 template <typename T>
 int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
-                    float eps, void* h, float* rm_out, void* h_tail, int rm_row0, hipStream_t st) {
+                    float eps, void* h, float* rm_out, void* h_tail, int rm_row0, uint32_t* ovf, hipStream_t st) {
   DS_REQUIRE(n_part >= 0 && n_part <= kMaxPlanes, DS_E_SHAPE, "norm: %d partial planes, at most %d", n_part, kMaxPlanes);
   if (d >= 2048)
     hipLaunchKernelGGL((norm_kernel<T, false, 1024>), dim3(rows), dim3(1024), 0, st, Prologue{}, (const T*)nullptr, x,
                        part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, static_cast<T*>(h_tail),
-                       rm_row0);
+                       rm_row0, ovf);
   else
     hipLaunchKernelGGL((norm_kernel<T, false, 256>), dim3(rows), dim3(256), 0, st, Prologue{}, (const T*)nullptr, x,
                        part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, static_cast<T*>(h_tail),
-                       rm_row0);
+                       rm_row0, ovf);
   DS_LAUNCH_CHECK("norm_kernel<add>");
   return DS_OK;
 }
 
 template <typename T>
-int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* dst, hipStream_t st) {
+int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* dst, uint32_t* ovf, hipStream_t st) {
   hipLaunchKernelGGL((to_gemm_input_kernel<T>), dim3(rows), dim3(256), 0, st, src, rows_pad, d,
-                     static_cast<T*>(dst));
+                     static_cast<T*>(dst), ovf);
   DS_LAUNCH_CHECK("to_gemm_input_kernel");
   return DS_OK;
 }
 
 template <typename T>
 int launch_qkv_rope(const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv, int hd,
-                    const float2* cs, int pos0, int cap, void* q, void* kc, void* vc, hipStream_t st) {
+                    const float2* cs, int pos0, int cap, void* q, void* kc, void* vc, uint32_t* ovf, hipStream_t st) {
   DS_REQUIRE(n_part >= 1 && n_part <= kMaxPlanes, DS_E_SHAPE, "rope: %d partial planes, at most %d", n_part, kMaxPlanes);
   hipLaunchKernelGGL((qkv_rope_kernel<T>), dim3(rows, n_q + 2 * n_kv), dim3(hd / 2), 0, st, part, n_part, rows,
                      rows_pad, n_q, n_kv, hd, cs, pos0, cap, static_cast<typename Act<T>::kv_t*>(q),
-                     static_cast<typename Act<T>::kv_t*>(kc), static_cast<typename Act<T>::kv_t*>(vc));
+                     static_cast<typename Act<T>::kv_t*>(kc), static_cast<typename Act<T>::kv_t*>(vc), ovf);
   DS_LAUNCH_CHECK("qkv_rope_kernel");
   return DS_OK;
 }
 
 template <typename T>
-int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, hipStream_t st) {
+int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, uint32_t* ovf,
+                  hipStream_t st) {
   DS_REQUIRE(n_part >= 1 && n_part <= kMaxPlanes, DS_E_SHAPE, "SwiGLU: %d partial planes, at most %d", n_part, kMaxPlanes);
   hipLaunchKernelGGL((swiglu_kernel<T>), dim3(ceil_div(F, 1024), rows), dim3(256), 0, st, part, n_part, rows,
-                     rows_pad, F, static_cast<T*>(act));
+                     rows_pad, F, static_cast<T*>(act), ovf);
   DS_LAUNCH_CHECK("swiglu_kernel");
   return DS_OK;
 }
 
 #define DS_INSTANTIATE(T)                                                                                          \
   template int launch_embed_norm<T>(const int32_t*, int, const int32_t*, int32_t, int, int, int, double, float2*,  \
-                                    const void*, float*, int, int, int, const float*, float, void*, hipStream_t);  \
+                                    const void*, float*, int, int, int, const float*, float, void*, uint32_t*,      \
+                                    hipStream_t);                                                                  \
   template int launch_add_norm<T>(float*, const float*, int, int, int, int, const float*, float, void*, float*,   \
-                                  void*, int, hipStream_t);                                                        \
-  template int launch_to_gemm_input<T>(const float*, int, int, int, void*, hipStream_t);                           \
+                                  void*, int, uint32_t*, hipStream_t);                                             \
+  template int launch_to_gemm_input<T>(const float*, int, int, int, void*, uint32_t*, hipStream_t);                \
   template int launch_qkv_rope<T>(const float*, int, int, int, int, int, int, const float2*, int, int, void*,     \
-                                  void*, void*, hipStream_t);                                                      \
-  template int launch_swiglu<T>(const float*, int, int, int, int, void*, hipStream_t);
+                                  void*, void*, uint32_t*, hipStream_t);                                           \
+  template int launch_swiglu<T>(const float*, int, int, int, int, void*, uint32_t*, hipStream_t);
 DS_INSTANTIATE(float)
 DS_INSTANTIATE(bf16_t)
 

@@ -1,0 +1,105 @@
+"""GPU tests at the edges of the half-precision range (DS_BF16 models run their products in IEEE half: bf16 weights
+re-encoded exactly where they fit, half activations): weights below the half normal range, weights beyond the half
+range, activations that overflow it, and a weight scale far from the benchmark's N(0, 0.02)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import model as o_model
+from paper_2510_02358_amd import binding as ds
+from paper_2510_02358_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+CFG = synth.ModelCfg(n_layers=2, d_model=256, n_q=4, n_kv=2, head_dim=128, d_ffn=512, vocab=4096, rope_base=1.0e6,
+                     dtype="bf16")
+
+
+def _logits_err(cfg, w, prefix, k):
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        oc = o_model.KVCache(cfg)
+        ref_last = o_model.prefill(cfg, w, oc, prefix)
+        got_last = gm.prefill(prefix)
+        ref = o_model.lm_head(w, o_model.draft_block(cfg, w, oc, [5], k))
+        got = gu.from_dev(gm.lm_head(gm.draft([5], k)))
+        n_over = ds.ds_model_overflow_count(gm.handle)
+        return (max(float(np.max(np.abs(got_last - ref_last))), float(np.max(np.abs(got - ref)))), float(np.std(ref)),
+                n_over, got)
+    finally:
+        gm.close()
+
+
+def test_weights_below_the_half_normal_range_cost_at_most_their_subnormal_rounding():
+    """Two matrices of every layer (O and down) drawn at std 1e-5: almost every weight lies below 2^-14 and lands on
+    the half subnormal grid (absolute error <= 2^-25 per weight).  The logits stay within the usual bar; the error
+    the re-encoding can add is bounded by 2^-25 * sum |activation| per output, orders of magnitude below it."""
+    w = synth.make_weights(CFG, 200)
+    rng = np.random.default_rng(201)
+    for lw in w["layers"]:
+        for name in ("wo", "w_down"):
+            lw[name] = synth.round_to_bf16((rng.standard_normal(lw[name].shape) * 1e-5).astype(np.float32))
+        assert np.mean(np.abs(lw["wo"]) < 2.0 ** -14) > 0.99
+    err, scale, n_over, _ = _logits_err(CFG, w, synth.make_prefix(CFG, 70, 202), 9)
+    print(f"PARITY-COUNTS tiny weights: max |dlogit| {err:.2e} at logit std {scale:.3f}")
+    assert err <= 2e-2 and n_over == 0
+
+
+@pytest.mark.parametrize("bad", [70000.0, -3.0e38, float("nan")])
+def test_a_weight_beyond_the_half_range_is_refused_at_creation(bad):
+    w = synth.make_weights(CFG, 203)
+    w["layers"][1]["w_up"] = np.array(w["layers"][1]["w_up"], copy=True)
+    w["layers"][1]["w_up"][17, 33] = synth.round_to_bf16(np.array([bad], np.float32))[0]
+    with pytest.raises(ds.DsError) as e:
+        gu.GpuModel(CFG, w, 64)
+    assert e.value.code == ds.DS_E_UNSUPPORTED and "half" in str(e.value)
+
+
+def test_activations_beyond_the_half_range_are_clamped_and_counted():
+    """Gate / up weights at std 10 drive silu(gate) * up far beyond 65504: the products saturate instead of turning
+    infinite, every logit stays finite, and the model's overflow counter reports it; the same model with ordinary
+    weights reports zero, and the counter can be cleared."""
+    w = synth.make_weights(CFG, 204)
+    prefix = synth.make_prefix(CFG, 40, 205)
+    gm = gu.GpuModel(CFG, w, 128)
+    try:
+        gm.prefill(prefix)
+        gm.lm_head(gm.draft([3], 8))
+        torch.cuda.synchronize()
+        assert ds.ds_model_overflow_count(gm.handle) == 0
+    finally:
+        gm.close()
+    rng = np.random.default_rng(206)
+    for lw in w["layers"]:
+        for name in ("w_gate", "w_up"):
+            lw[name] = synth.round_to_bf16((rng.standard_normal(lw[name].shape) * 10.0).astype(np.float32))
+    gm = gu.GpuModel(CFG, w, 128)
+    try:
+        last = gm.prefill(prefix)
+        logits = gu.from_dev(gm.lm_head(gm.draft([3], 8)))
+        assert np.all(np.isfinite(last)) and np.all(np.isfinite(logits))
+        n = ds.ds_model_overflow_count(gm.handle, reset=True)
+        assert n > 0
+        assert ds.ds_model_overflow_count(gm.handle) == 0
+        gm.verify(np.array([1, 2, 3], np.int32))
+        assert ds.ds_model_overflow_count(gm.handle) > 0
+        print(f"PARITY-COUNTS overflow: {n} activation values clamped in one prefill + draft pass")
+    finally:
+        gm.close()
+
+
+@pytest.mark.parametrize("std", [0.2, 0.005])
+def test_weight_scale_far_from_the_benchmark_scale(std):
+    """Every matrix at std 0.2 (ten times the benchmark's) or 0.005, random norm gains: the half-precision error
+    scales with the logits, so the comparison is relative to the oracle logits' standard deviation (at N(0, 0.02)
+    the 2e-2 bar is about 6 % of it; the measured error is about 2 %); whether the absolute bar holds is printed."""
+    w = synth.make_weights(CFG, 210, std=std)
+    synth.randomize_norm_gains(w, 211)
+    err, scale, n_over, _ = _logits_err(CFG, w, synth.make_prefix(CFG, 90, 212), 17)
+    print(f"PARITY-COUNTS weight std {std}: max |dlogit| {err:.3e}, logit std {scale:.3f}, ratio {err / scale:.3e}, "
+          f"absolute 2e-2 bar {'holds' if err <= 2e-2 else 'does NOT hold'}")
+    assert err <= 0.04 * scale and n_over == 0
