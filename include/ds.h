@@ -49,7 +49,10 @@ extern "C" {
 #define DS_MAX_TOPM 16  /* largest lattice width M_max */
 #define DS_MAX_BEAM 16  /* largest beam width B */
 
+#define DS_MAX_SEQ 8    /* most sequences one batched forward call may carry */
+
 typedef struct ds_model ds_model;
+typedef struct ds_kv ds_kv;
 typedef struct ds_ngram ds_ngram;
 typedef struct ds_adl ds_adl;
 
@@ -268,6 +271,38 @@ int ds_refine_select(const int32_t* cand_id, const float* cand_logp, const int32
  * after exactly min(S, K) passes.  Pure host code.  sizes [host] int[steps] receives |U_1|, |U_2|, ...; *n_sizes the
  * number of passes (<= steps). */
 int ds_refine_update_sizes(int K, int steps, int* sizes, int* n_sizes);
+
+/* Several sequences per call (batch > 1; Sec. 6 names batching as the way to better hardware use; every step of the
+ * round is defined per sequence, so a batch is n_seq independent rounds that share one pass over the weights).
+ * A ds_kv is one more sequence's KV cache of a model: kv_k / kv_v [dev] of ds_kv_bytes() each, owned by the caller;
+ * its committed length starts at 0.  The cache passed to ds_model_create is the model's built-in sequence, used by
+ * the single-sequence calls; the batched calls take explicit handles (distinct, all of the same model).
+ * ds_prefill_seq: ds_prefill into the given sequence.
+ * ds_draft_block_batch: ds_draft_block for n_seq <= DS_MAX_SEQ sequences.  pending [dev]: the pending tokens of all
+ * sequences, concatenated in sequence order; n_pend [host] int[n_seq]; the same K for every sequence; hidden_out
+ * [dev] float[n_seq * K, d_model], sequence-major.  Each sequence's rows are placed at a multiple of 16 inside the
+ * call: sum over sequences of (n_pend[s] + K rounded up to 16; the last one not rounded) must not exceed DS_MAX_ROWS.
+ * A following ds_draft_lattice(hidden = NULL, rows = n_seq * K) gives the lattice rows [s * K, (s + 1) * K) that
+ * ds_cps_path(batch = n_seq) searches.
+ * ds_verify_block_batch: ds_verify_block for n_seq sequences of m + 1 rows each: first [dev] int32[n_seq] (each
+ * sequence's last committed token), path [dev] int32[n_seq, m] (what ds_cps_path wrote), path_len [dev] int32[n_seq]
+ * or NULL.  Outputs [dev]: n_accept, next_token, eos_accepted int32[n_seq]; argmax int32[n_seq, m + 1]; logits_out
+ * float[rows, vocab] or NULL, where sequence s occupies rows [s * R, s * R + m + 1) with R = m + 1 rounded up to 16.
+ * The eos_accepted words are stored last, after a system-scope fence.  Committed lengths are not advanced: the caller
+ * commits each sequence with ds_kv_set_len(len + 1 + n_accept[s]).
+ * Every row's result is bit-identical to what the single-sequence call gives for that sequence alone. */
+int ds_kv_create(ds_model* m, void* kv_k, void* kv_v, ds_kv** out);
+void ds_kv_destroy(ds_kv* kv);
+int ds_kv_len(const ds_kv* kv, int* len);
+int ds_kv_set_len(ds_kv* kv, int len);
+int ds_prefill_seq(ds_model* m, ds_kv* kv, const int32_t* tokens, int n, float* last_logits, void* ws,
+                   size_t ws_bytes, void* stream);
+int ds_draft_block_batch(ds_model* drafter, ds_kv* const* seqs, int n_seq, const int32_t* pending, const int* n_pend,
+                         int K, int32_t mask_id, float* hidden_out, void* ws, size_t ws_bytes, void* stream);
+int ds_verify_block_batch(ds_model* verifier, ds_kv* const* seqs, int n_seq, const int32_t* first,
+                          const int32_t* path, int m, const int32_t* path_len, int32_t eos_id, int32_t* n_accept,
+                          int32_t* next_token, int32_t* argmax, int32_t* eos_accepted, float* logits_out, void* ws,
+                          size_t ws_bytes, void* stream);
 
 /* Step 4 tail, adaptive draft length (Sec. 3.3: generation-length signal, moving averages,
  * controller).  Pure host code in double precision.  first_eos: 1-based index of the first EOS in the

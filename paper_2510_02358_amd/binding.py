@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdiffusp
 _lib = None
 
 DS_F32, DS_BF16 = 0, 1
-DS_MAX_ROWS, DS_MAX_TOPM, DS_MAX_BEAM = 144, 16, 16
+DS_MAX_ROWS, DS_MAX_TOPM, DS_MAX_BEAM, DS_MAX_SEQ = 144, 16, 16, 8
 DS_OK, DS_E_INVALID, DS_E_SHAPE, DS_E_CAPACITY, DS_E_UNSUPPORTED, DS_E_HIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = [
@@ -26,6 +26,8 @@ EXPORTS = [
     "ds_adl_update", "ds_adl_state", "ds_sample_workspace_bytes", "ds_accept_stochastic",
     "ds_verify_block_stochastic", "ds_draft_block_tokens", "ds_refine_select", "ds_build_lattice_static",
     "ds_refine_update_sizes", "ds_adl_first_eos", "ds_model_overflow_count",
+    "ds_kv_create", "ds_kv_destroy", "ds_kv_len", "ds_kv_set_len", "ds_prefill_seq", "ds_draft_block_batch",
+    "ds_verify_block_batch",
 ]
 
 
@@ -72,6 +74,7 @@ def load():
     lib.ds_model_destroy.restype = None
     lib.ds_ngram_destroy.restype = None
     lib.ds_adl_destroy.restype = None
+    lib.ds_kv_destroy.restype = None
     vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
     lib.ds_model_packed_bytes.argtypes = [C.POINTER(ModelCfgC), C.POINTER(sz)]
     lib.ds_workspace_bytes.argtypes = [C.POINTER(ModelCfgC), C.c_int, C.POINTER(sz)]
@@ -79,6 +82,15 @@ def load():
     lib.ds_model_create.argtypes = [C.POINTER(ModelCfgC), C.POINTER(WeightsC), vp, sz, vp, vp, vp, C.POINTER(vp)]
     lib.ds_model_destroy.argtypes = [vp]
     lib.ds_model_overflow_count.argtypes = [vp, C.c_int, vp, C.POINTER(C.c_uint32)]
+    lib.ds_kv_create.argtypes = [vp, vp, vp, C.POINTER(vp)]
+    lib.ds_kv_destroy.argtypes = [vp]
+    lib.ds_kv_len.argtypes = [vp, C.POINTER(C.c_int)]
+    lib.ds_kv_set_len.argtypes = [vp, C.c_int]
+    lib.ds_prefill_seq.argtypes = [vp, vp, vp, C.c_int, vp, vp, sz, vp]
+    lib.ds_draft_block_batch.argtypes = [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(C.c_int), C.c_int, i32, vp, vp, sz,
+                                         vp]
+    lib.ds_verify_block_batch.argtypes = [vp, C.POINTER(vp), C.c_int, vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp,
+                                          sz, vp]
     lib.ds_model_kv_len.argtypes = [vp, C.POINTER(C.c_int)]
     lib.ds_model_kv_set_len.argtypes = [vp, C.c_int]
     lib.ds_prefill.argtypes = [vp, vp, C.c_int, vp, vp, sz, vp]
@@ -194,6 +206,45 @@ def ds_model_overflow_count(model: int, reset: bool = False, stream=None) -> int
     out = C.c_uint32(0)
     _check(load().ds_model_overflow_count(model, 1 if reset else 0, _stream(stream), C.byref(out)))
     return out.value
+
+
+def ds_kv_create(model: int, kv_k, kv_v) -> int:
+    out = C.c_void_p(None)
+    _check(load().ds_kv_create(model, _ptr(kv_k), _ptr(kv_v), C.byref(out)))
+    return out.value
+
+
+def ds_kv_destroy(kv: int) -> None:
+    load().ds_kv_destroy(kv)
+
+
+def ds_kv_len(kv: int) -> int:
+    out = C.c_int(0)
+    _check(load().ds_kv_len(kv, C.byref(out)))
+    return out.value
+
+
+def ds_kv_set_len(kv: int, length: int) -> None:
+    _check(load().ds_kv_set_len(kv, length))
+
+
+def ds_prefill_seq(model: int, kv: int, tokens, n: int, last_logits, ws, stream=None) -> None:
+    _check(load().ds_prefill_seq(model, kv, _ptr(tokens), n, _ptr(last_logits), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ds_draft_block_batch(model: int, seqs, pending, n_pend, k: int, mask_id: int, hidden_out, ws, stream=None) -> None:
+    """seqs: list of ds_kv handles; n_pend: list of ints (host)."""
+    n = len(seqs)
+    _check(load().ds_draft_block_batch(model, (C.c_void_p * n)(*seqs), n, _ptr(pending), (C.c_int * n)(*n_pend), k,
+                                       mask_id, _ptr(hidden_out), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ds_verify_block_batch(model: int, seqs, first, path, m: int, path_len, eos_id: int, n_accept, next_token, argmax,
+                          eos_accepted, logits_out, ws, stream=None) -> None:
+    n = len(seqs)
+    _check(load().ds_verify_block_batch(model, (C.c_void_p * n)(*seqs), n, _ptr(first), _ptr(path), m, _ptr(path_len),
+                                        eos_id, _ptr(n_accept), _ptr(next_token), _ptr(argmax), _ptr(eos_accepted),
+                                        _ptr(logits_out), _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def ds_model_kv_len(model: int) -> int:

@@ -108,20 +108,21 @@ struct Act<bf16_t> {
 };
 
 // ---- launchers implemented in k_elem.hip / k_gemm.hip / k_attn.hip --------------------------------
-// First kernel of a forward: token gather (rows past n_real read src2, or are `fill` if src2 is NULL), rotary
-// table, embedding, RMSNorm.
+// First kernel of a forward: token gather (see SeqTable: tok_a / tok_b / fill), rotary table, embedding, RMSNorm.
 template <typename T>
-int launch_embed_norm(const int32_t* src, int n_real, const int32_t* src2, int32_t fill, int vocab, int pos0, int hd,
+int launch_embed_norm(const SeqTable& tab, const int32_t* tok_a, const int32_t* tok_b, int32_t fill, int vocab, int hd,
                       double rope_base, float2* cs, const void* embed, float* x, int rows, int rows_pad, int d,
                       const float* gain, float eps, void* h, uint32_t* ovf, hipStream_t st);
+// rm_out / h_tail (optional): the rows every sequence hands on (SeqTable::tail0 / tail_base), compacted.
 template <typename T>
-int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
-                    float eps, void* h, float* rm_out, void* h_tail, int rm_row0, uint32_t* ovf, hipStream_t st);
+int launch_add_norm(const SeqTable& tab, float* x, const float* part, int n_part, int rows, int rows_pad, int d,
+                    const float* gain, float eps, void* h, float* rm_out, void* h_tail, uint32_t* ovf,
+                    hipStream_t st);
 template <typename T>
 int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* dst, uint32_t* ovf, hipStream_t st);
 template <typename T>
-int launch_qkv_rope(const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv, int hd,
-                    const float2* cs, int pos0, int cap, void* q, void* kc, void* vc, uint32_t* ovf, hipStream_t st);
+int launch_qkv_rope(const SeqTable& tab, const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv,
+                    int hd, const float2* cs, int cap, void* q, uint32_t* ovf, hipStream_t st);
 template <typename T>
 int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, uint32_t* ovf,
                   hipStream_t st);
@@ -151,16 +152,16 @@ int launch_gemm_bf16(const void* wp, const void* xt, int M, int N, int K, int nb
                      const GemmEpilogue& epi, hipStream_t st);
 int launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* out, int ldc, hipStream_t st);
 
-// Attention over keys [0, n_keys) of one layer's cache for `rows` query rows at positions pos0 + r.
-// Row r sees key p iff r >= n_causal (a [MASK] row) or p <= pos0 + r.
-// part_o / part_ml hold attn_partial_rows(rows_pad) * n_q rows of head_dim / 2 floats.
+// Attention of every sequence of the call (SeqTable: rows, cache, position and causal boundary per sequence) over
+// its own keys [0, pos0 + n_rows).  Row i of a sequence sees key p iff i >= n_causal (a [MASK] row) or p <= pos0 + i.
+// rows / rows_pad: all rows of the call.  part_o / part_ml hold attn_partial_rows(rows_pad) * n_q rows of head_dim /
+// 2 floats.
 struct AttnPlan {
   int n_split, chunks_per_split;
 };
 AttnPlan attn_plan(int dtype, int cap, int n_keys);
 int attn_partial_rows(int rows_pad);
-int launch_attention(int dtype, const void* q, const void* kc, const void* vc, int rows, int rows_pad, int n_causal,
-                     int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, float* part_o, float* part_ml,
-                     void* att_out, uint32_t* ovf, hipStream_t st);
+int launch_attention(int dtype, const SeqTable& tab, const void* q, int rows, int rows_pad, int n_q, int n_kv, int hd,
+                     int cap, float* part_o, float* part_ml, void* att_out, uint32_t* ovf, hipStream_t st);
 
 }  // namespace ds

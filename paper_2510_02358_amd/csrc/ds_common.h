@@ -48,18 +48,59 @@ __host__ __device__ static inline size_t xt_offset(int m, int k, int K) {
   return ((size_t)mb * (size_t)(K >> 5) + (size_t)ks) * 512 + (size_t)((g << 4) + j) * 8 + e;
 }
 
+// ---- sequences of one forward call ------------------------------------------------------------------
+// A forward call carries the rows of up to kMaxSeq independent sequences through ONE pass over the weights
+// (everything except attention and the cache append works row by row, so the rows of different sequences simply
+// share the products).  Sequence s owns rows [row0[s], row0[s] + n_rows[s]); row0[s] is a multiple of 16 (the rows
+// between two sequences are padding: finite, never stored anywhere that counts) and row0[n_seq] is the call's total
+// row count.  Passed to kernels by value.
+constexpr int kMaxSeq = 8;
+struct SeqTable {
+  int n_seq;
+  int row0[kMaxSeq + 1];
+  int n_rows[kMaxSeq];     // rows of the sequence in this call
+  int n_a[kMaxSeq];        // the first n_a rows read their token from tok_a[off_a + i], the rest from tok_b[off_b + i - n_a]
+  int off_a[kMaxSeq];      //   (or are `fill` if tok_b is NULL)
+  int off_b[kMaxSeq];
+  int pos0[kMaxSeq];       // absolute position of the sequence's first row = its committed cache length
+  int n_causal[kMaxSeq];   // rows [0, n_causal) are causal real-token rows, the rest see every key
+  int tail0[kMaxSeq];      // first row (within the sequence) whose final-normed state is handed on, and
+  int tail_base[kMaxSeq];  //   the row it gets in the compact hand-on array
+  void* kc[kMaxSeq];       // this layer's key / value cache of the sequence
+  void* vc[kMaxSeq];
+};
+// The sequence a row belongs to, or -1 for a padding row.
+__host__ __device__ static inline int seq_of_row(const SeqTable& t, int r) {
+  int s = 0;
+  while (s + 1 < t.n_seq && r >= t.row0[s + 1]) ++s;
+  return (r - t.row0[s] < t.n_rows[s]) ? s : -1;
+}
+
+// Sequences of one verification call as the acceptance kernels see them: sequence s owns rows [row0[s], row0[s] +
+// m[s] + 1) of the verifier pass; its path token n is path_tok[tok_off[s] + n]; its arg-max row i is written to
+// argmax[out_off[s] + i] (rows of no sequence are written nowhere).
+struct AcceptSeqs {
+  int n_seq;
+  int row0[kMaxSeq], m[kMaxSeq], tok_off[kMaxSeq], out_off[kMaxSeq];
+};
+__host__ __device__ static inline int accept_out_index(const AcceptSeqs& q, int r) {
+  for (int s = 0; s < q.n_seq; ++s)
+    if (r >= q.row0[s] && r <= q.row0[s] + q.m[s]) return q.out_off[s] + r - q.row0[s];
+  return -1;
+}
+
 // ---- lattice / acceptance kernels (k_lattice.hip) ----------------------------------------------
 size_t lattice_ws_bytes(int rows, int vocab, int m_max);
 int launch_lattice(const float* logits, int rows, int vocab, int m_max, float tau, int32_t eos_id,
                    int32_t* cand_id, float* cand_logp, int32_t* cand_cnt, float* eos_logp, float* lse,
                    void* ws, size_t ws_bytes, hipStream_t st);
 size_t accept_ws_bytes(int rows, int vocab);
-int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t* block,
+int launch_argmax_accept(const float* logits, int rows, int vocab, const AcceptSeqs& sq, const int32_t* path_tok,
                          const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
                          int32_t* argmax, int32_t* eos_accepted, void* ws, size_t ws_bytes, hipStream_t st);
 // The same verdict from per-tile (largest logit, column) records written by the LM-head product's epilogue
 // (layout and size: gemm_bf16_best_bytes, plus DS_MAX_ROWS words behind it).
-int launch_tiles_accept(float2* tile_best, int rows, int n_tiles, const int32_t* block,
+int launch_tiles_accept(float2* tile_best, int rows, int n_tiles, const AcceptSeqs& sq, const int32_t* path_tok,
                         const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
                         int32_t* argmax, int32_t* eos_accepted, hipStream_t st);
 

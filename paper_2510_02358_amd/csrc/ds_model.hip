@@ -44,6 +44,13 @@ struct Workspace {
 
 }  // namespace
 
+// One sequence's KV cache of a model: the two caller buffers and the committed length.
+struct ds_kv {
+  ds_model* owner;
+  void *k, *v;
+  int len;
+};
+
 struct ds_model {
   ds_model_cfg cfg;
   const void* embed;
@@ -51,8 +58,7 @@ struct ds_model {
   std::vector<PackedLayer> packed;
   const float* final_norm;
   const void* lm_head;  // bf16: stream order; f32: canonical
-  void *kv_k, *kv_v;
-  int kv_len;
+  ds_kv self;  // the cache given to ds_model_create (what the single-sequence calls use)
   size_t esize;
   uint32_t* ovf = nullptr;  // [dev] activation-overflow counter (bf16 models: a word of the packed buffer's tail)
   // what the last draft pass left behind for ds_lm_head(hidden = NULL): the block rows as a GEMM input
@@ -216,58 +222,113 @@ int gemm(const ds_model* m, int li, int which, const void* x_in, int rows, float
   }
 }
 
-// Forward of `rows` token rows placed after the committed cache.  Rows [0, n_causal) are causal real
-// tokens, the rest are [MASK] rows.  Leaves the final-normed states of all rows in ws.y (GEMM input
-// order) and, if hidden_out is given, a row-major copy of rows >= hidden_row0 there.
+// One forward call: up to kMaxSeq sequences, each with its own cache, share one pass over the weights.
+struct FwdSeq {
+  ds_kv* kv;
+  int n_a;       // rows that read their token from tok_a (the rest read tok_b, or are `fill`)
+  int n_rows;    // rows of the sequence in this call
+  int n_causal;  // leading causal real-token rows; the rest see every key ([MASK] / block rows)
+  int tail0;     // rows >= tail0 are handed on (hidden_out and the LM head's input); n_rows: none
+};
+struct FwdCall {
+  int n_seq = 0;
+  FwdSeq seq[kMaxSeq];
+  const int32_t* tok_a = nullptr;
+  const int32_t* tok_b = nullptr;
+  int32_t fill = 0;
+  float* hidden_out = nullptr;
+};
+
+// Row layout of a call (each sequence starts at a multiple of 16) and the host-side checks every forward needs.
+int plan_call(const ds_model* m, const FwdCall& call, SeqTable* tab, int* rows_total, int* tail_rows) {
+  DS_REQUIRE(call.n_seq >= 1 && call.n_seq <= kMaxSeq, DS_E_SHAPE, "%d sequences outside [1, %d]", call.n_seq, kMaxSeq);
+  SeqTable t{};
+  t.n_seq = call.n_seq;
+  int row = 0, off_a = 0, off_b = 0, tail = 0;
+  for (int s = 0; s < call.n_seq; ++s) {
+    const FwdSeq& q = call.seq[s];
+    DS_REQUIRE(q.kv && q.kv->owner == m, DS_E_INVALID, "sequence %d: KV handle is NULL or belongs to another model", s);
+    for (int o = 0; o < s; ++o)
+      DS_REQUIRE(call.seq[o].kv != q.kv, DS_E_INVALID, "sequences %d and %d share one KV handle", o, s);
+    DS_REQUIRE(q.n_rows >= 1 && q.n_a >= 0 && q.n_a <= q.n_rows && q.n_causal >= 0 && q.n_causal <= q.n_rows &&
+                   q.tail0 >= 0 && q.tail0 <= q.n_rows,
+               DS_E_SHAPE, "sequence %d: bad row counts", s);
+    DS_REQUIRE(q.kv->len + q.n_rows <= m->cfg.kv_capacity, DS_E_CAPACITY,
+               "KV cache of sequence %d: %d + %d rows exceed capacity %d", s, q.kv->len, q.n_rows, m->cfg.kv_capacity);
+    row = ceil_div(row, 16) * 16;
+    t.row0[s] = row;
+    t.n_rows[s] = q.n_rows;
+    t.n_a[s] = q.n_a;
+    t.off_a[s] = off_a;
+    t.off_b[s] = off_b;
+    t.pos0[s] = q.kv->len;
+    t.n_causal[s] = q.n_causal;
+    t.tail0[s] = q.tail0;
+    t.tail_base[s] = tail;
+    row += q.n_rows;
+    off_a += q.n_a;
+    off_b += q.n_rows - q.n_a;
+    tail += q.n_rows - q.tail0;
+  }
+  t.row0[call.n_seq] = row;
+  DS_REQUIRE(row <= DS_MAX_ROWS, DS_E_SHAPE,
+             "%d rows (every sequence padded to a multiple of 16 but the last) exceed %d rows per call", row, DS_MAX_ROWS);
+  DS_REQUIRE(call.tok_a || off_a == 0, DS_E_INVALID, "token pointer is NULL");
+  *tab = t;
+  *rows_total = row;
+  *tail_rows = tail;
+  return DS_OK;
+}
+
+// Forward of the call's rows, each sequence placed after its committed cache.  Leaves the final-normed states of all
+// rows in ws.y (GEMM input order) and, for the rows every sequence hands on, a compact GEMM input in ws.y_tail and
+// (if given) a row-major copy in call.hidden_out.
 template <typename T>
-int forward_rows(ds_model* m, const Workspace& w, const int32_t* src, int n_real, const int32_t* src2, int32_t fill,
-                 int rows,
-                 int n_causal, float* hidden_out, int hidden_row0, hipStream_t st) {
+int forward_rows(ds_model* m, const Workspace& w, const FwdCall& call, const SeqTable& tab, int rows, bool tail,
+                 hipStream_t st) {
   const ds_model_cfg& c = m->cfg;
   const int rp = ceil_div(rows, 16) * 16;
-  const int pos0 = m->kv_len, n_keys = pos0 + rows;
   const int d = c.d_model, hd = c.head_dim;
   int rc;
-  if ((rc = launch_embed_norm<T>(src, n_real, src2, fill, c.vocab, pos0, hd, (double)c.rope_base, w.cs, m->embed, w.x, rows,
-                                 rp, d, m->canon[0].norm1, c.rms_eps, w.h, m->ovf, st)))
+  if ((rc = launch_embed_norm<T>(tab, call.tok_a, call.tok_b, call.fill, c.vocab, hd, (double)c.rope_base, w.cs, m->embed,
+                                 w.x, rows, rp, d, m->canon[0].norm1, c.rms_eps, w.h, m->ovf, st)))
     return rc;
   for (int li = 0; li < c.n_layers; ++li) {
-    const size_t layer_elems = (size_t)c.n_kv * c.kv_capacity * hd;
-    char* kc = static_cast<char*>(m->kv_k) + (size_t)li * layer_elems * m->esize;
-    char* vc = static_cast<char*>(m->kv_v) + (size_t)li * layer_elems * m->esize;
+    const size_t layer_bytes = (size_t)c.n_kv * c.kv_capacity * hd * m->esize;
+    SeqTable lt = tab;  // this layer's caches
+    for (int s = 0; s < tab.n_seq; ++s) {
+      lt.kc[s] = static_cast<char*>(call.seq[s].kv->k) + (size_t)li * layer_bytes;
+      lt.vc[s] = static_cast<char*>(call.seq[s].kv->v) + (size_t)li * layer_bytes;
+    }
     int sp = 1;
     if ((rc = gemm<T>(m, li, 0, w.h, rows, w.gemm_out, &sp, st))) return rc;
-    if ((rc = launch_qkv_rope<T>(w.gemm_out, sp, rows, rp, c.n_q, c.n_kv, hd, w.cs, pos0, c.kv_capacity, w.q, kc, vc,
-                                 m->ovf, st)))
+    if ((rc = launch_qkv_rope<T>(lt, w.gemm_out, sp, rows, rp, c.n_q, c.n_kv, hd, w.cs, c.kv_capacity, w.q, m->ovf, st)))
       return rc;
-    if ((rc = launch_attention(c.dtype, w.q, kc, vc, rows, rp, n_causal, pos0, n_keys, c.n_q, c.n_kv, hd,
-                               c.kv_capacity, w.att_o, w.att_ml, w.att, m->ovf, st)))
+    if ((rc = launch_attention(c.dtype, lt, w.q, rows, rp, c.n_q, c.n_kv, hd, c.kv_capacity, w.att_o, w.att_ml, w.att,
+                               m->ovf, st)))
       return rc;
     if ((rc = gemm<T>(m, li, 1, w.att, rows, w.gemm_out, &sp, st))) return rc;
-    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr, nullptr, 0,
-                                 m->ovf, st)))
+    if ((rc = launch_add_norm<T>(tab, w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr,
+                                 nullptr, m->ovf, st)))
       return rc;
     if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st))) return rc;
     if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, rp, c.d_ffn, w.act, m->ovf, st))) return rc;
     if ((rc = gemm<T>(m, li, 3, w.act, rows, w.gemm_out, &sp, st))) return rc;
     const bool last = li + 1 == c.n_layers;
     const float* gain = last ? m->final_norm : m->canon[li + 1].norm1;
-    if ((rc = launch_add_norm<T>(w.x, w.gemm_out, sp, rows, rp, d, gain, c.rms_eps, last ? w.y : w.h,
-                                 last ? hidden_out : nullptr, (last && hidden_out) ? w.y_tail : nullptr,
-                                 hidden_row0, m->ovf, st)))
+    if ((rc = launch_add_norm<T>(tab, w.x, w.gemm_out, sp, rows, rp, d, gain, c.rms_eps, last ? w.y : w.h,
+                                 last ? call.hidden_out : nullptr, (last && tail) ? w.y_tail : nullptr, m->ovf, st)))
       return rc;
   }
   return DS_OK;
 }
 
-// src: n_real device tokens; rows past n_real read src2[r - n_real], or are `fill` ([MASK]) if src2 is NULL.
-int forward_dispatch(ds_model* m, const Workspace& w, const int32_t* src, int n_real, const int32_t* src2,
-                     int32_t fill, int rows, int n_causal, float* hidden_out, int hidden_row0, hipStream_t st) {
+int forward_dispatch(ds_model* m, const Workspace& w, const FwdCall& call, const SeqTable& tab, int rows, bool tail,
+                     hipStream_t st) {
   m->tail_ptr = nullptr;  // any forward overwrites the workspace
   m->rec_ws = nullptr;
-  return m->cfg.dtype == DS_BF16
-             ? forward_rows<bf16_t>(m, w, src, n_real, src2, fill, rows, n_causal, hidden_out, hidden_row0, st)
-             : forward_rows<float>(m, w, src, n_real, src2, fill, rows, n_causal, hidden_out, hidden_row0, st);
+  return m->cfg.dtype == DS_BF16 ? forward_rows<bf16_t>(m, w, call, tab, rows, tail, st)
+                                 : forward_rows<float>(m, w, call, tab, rows, tail, st);
 }
 
 // epi (bf16 path with lm_head_tile() > 0 only): also leave per-tile records; logits may then be NULL.
@@ -349,9 +410,7 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
   m->embed = w->embed;
   m->canon.assign(w->layers, w->layers + cfg->n_layers);
   m->final_norm = w->final_norm;
-  m->kv_k = kv_k;
-  m->kv_v = kv_v;
-  m->kv_len = 0;
+  m->self = ds_kv{m, kv_k, kv_v, 0};
   m->esize = esize_of(cfg->dtype);
   m->lm_head = w->lm_head;
   if (cfg->dtype == DS_BF16) {
@@ -418,7 +477,7 @@ int ds_model_overflow_count(ds_model* m, int reset, void* stream, uint32_t* coun
 
 int ds_model_kv_len(const ds_model* m, int* len) {
   DS_REQUIRE(m && len, DS_E_INVALID, "ds_model_kv_len: NULL pointer argument");
-  *len = m->kv_len;
+  *len = m->self.len;
   return DS_OK;
 }
 
@@ -426,16 +485,48 @@ int ds_model_kv_set_len(ds_model* m, int len) {
   DS_REQUIRE(m, DS_E_INVALID, "model is NULL");
   DS_REQUIRE(len >= 0 && len <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV length %d outside [0, %d]", len,
              m->cfg.kv_capacity);
-  m->kv_len = len;
+  m->self.len = len;
   return DS_OK;
 }
 
-int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, void* ws, size_t ws_bytes,
-               void* stream) {
-  DS_REQUIRE(m && tokens, DS_E_INVALID, "ds_prefill: NULL pointer argument");
+int ds_kv_create(ds_model* m, void* kv_k, void* kv_v, ds_kv** out) {
+  DS_REQUIRE(out, DS_E_INVALID, "out is NULL");
+  *out = nullptr;
+  DS_REQUIRE(m && kv_k && kv_v, DS_E_INVALID, "ds_kv_create: NULL pointer argument");
+  DS_REQUIRE((((uintptr_t)kv_k | (uintptr_t)kv_v) & 15) == 0, DS_E_INVALID, "KV buffers must be 16-byte aligned");
+  ds_kv* kv = new (std::nothrow) ds_kv{m, kv_k, kv_v, 0};
+  DS_REQUIRE(kv, DS_E_INVALID, "out of host memory");
+  *out = kv;
+  return DS_OK;
+}
+
+void ds_kv_destroy(ds_kv* kv) { delete kv; }
+
+int ds_kv_len(const ds_kv* kv, int* len) {
+  DS_REQUIRE(kv && len, DS_E_INVALID, "ds_kv_len: NULL pointer argument");
+  *len = kv->len;
+  return DS_OK;
+}
+
+int ds_kv_set_len(ds_kv* kv, int len) {
+  DS_REQUIRE(kv, DS_E_INVALID, "KV handle is NULL");
+  DS_REQUIRE(len >= 0 && len <= kv->owner->cfg.kv_capacity, DS_E_CAPACITY, "KV length %d outside [0, %d]", len,
+             kv->owner->cfg.kv_capacity);
+  kv->len = len;
+  return DS_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+int prefill_impl(ds_model* m, ds_kv* kv, const int32_t* tokens, int n, float* last_logits, void* ws, size_t ws_bytes,
+                 void* stream) {
+  DS_REQUIRE(m && kv && tokens, DS_E_INVALID, "prefill: NULL pointer argument");
+  DS_REQUIRE(kv->owner == m, DS_E_INVALID, "prefill: the KV handle belongs to another model");
   DS_REQUIRE(n >= 1, DS_E_SHAPE, "n %d must be >= 1", n);
-  DS_REQUIRE(m->kv_len + n <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d tokens exceed capacity %d",
-             m->kv_len, n, m->cfg.kv_capacity);
+  DS_REQUIRE(kv->len + n <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d tokens exceed capacity %d", kv->len,
+             n, m->cfg.kv_capacity);
   // largest chunk the workspace can carry
   int chunk = n < DS_MAX_ROWS ? n : DS_MAX_ROWS;
   DS_REQUIRE(ws, DS_E_INVALID, "workspace is NULL");
@@ -444,22 +535,28 @@ int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, vo
   int rc = check_ws(m, chunk, ws, ws_bytes, &w);
   if (rc) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int start_len = m->kv_len;
+  const int start_len = kv->len;
   for (int done = 0; done < n; done += chunk) {
     const int rows = n - done < chunk ? n - done : chunk;
     w = carve(m->cfg, rows, ws);
-    if ((rc = forward_dispatch(m, w, tokens + done, rows, nullptr, 0, rows, rows, nullptr, 0, st))) {
-      m->kv_len = start_len;
+    FwdCall call;
+    call.n_seq = 1;
+    call.seq[0] = FwdSeq{kv, rows, rows, rows, rows};
+    call.tok_a = tokens + done;
+    SeqTable tab;
+    int total = 0, tail = 0;
+    if ((rc = plan_call(m, call, &tab, &total, &tail)) || (rc = forward_dispatch(m, w, call, tab, total, false, st))) {
+      kv->len = start_len;
       return rc;
     }
-    m->kv_len += rows;
+    kv->len += rows;
     if (last_logits && done + rows == n) {
       // logits of all rows of the last chunk, then copy the last row out
       if ((rc = lm_head_rows(m, w.y, rows, w.logits, st)) ||
           (hipMemcpyAsync(last_logits, w.logits + (size_t)(rows - 1) * m->cfg.vocab, (size_t)m->cfg.vocab * 4,
                           hipMemcpyDeviceToDevice, st) != hipSuccess &&
-           (rc = fail(DS_E_HIP, "ds_prefill: copying the last row's logits failed")))) {
-        m->kv_len = start_len;  // a failed call changes no state
+           (rc = fail(DS_E_HIP, "prefill: copying the last row's logits failed")))) {
+        kv->len = start_len;  // a failed call changes no state
         return rc;
       }
     }
@@ -467,26 +564,123 @@ int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, vo
   return DS_OK;
 }
 
-int ds_draft_block(ds_model* m, const int32_t* pending, int n_pend, int K, int32_t mask_id, float* hidden_out,
-                   void* ws, size_t ws_bytes, void* stream) {
-  DS_REQUIRE(m && hidden_out, DS_E_INVALID, "ds_draft_block: NULL pointer argument");
-  DS_REQUIRE(n_pend >= 0 && K >= 1, DS_E_SHAPE, "need n_pend >= 0 and K >= 1 (got %d, %d)", n_pend, K);
-  DS_REQUIRE(pending || n_pend == 0, DS_E_INVALID, "pending is NULL while n_pend > 0");
-  const int rows = n_pend + K;
-  DS_REQUIRE(rows <= DS_MAX_ROWS, DS_E_SHAPE, "n_pend + K = %d exceeds %d rows", rows, DS_MAX_ROWS);
-  DS_REQUIRE(mask_id >= 0 && mask_id < m->cfg.vocab, DS_E_INVALID, "mask_id %d outside the vocabulary", mask_id);
-  DS_REQUIRE(m->kv_len + rows <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d rows exceed capacity %d",
-             m->kv_len, rows, m->cfg.kv_capacity);
-  Workspace w;
-  int rc = check_ws(m, rows, ws, ws_bytes, &w);
+// Drafter pass over n_seq sequences: n_pend[s] pending real tokens (causal) followed by K block rows each.
+// block_tokens NULL: every block row is `mask_id`; else block row i of sequence s holds block_tokens[s * K + i].
+int draft_impl(ds_model* m, ds_kv* const* kvs, int n_seq, const int32_t* pending, const int* n_pend, int K,
+               const int32_t* block_tokens, int32_t mask_id, float* hidden_out, void* ws, size_t ws_bytes,
+               void* stream) {
+  DS_REQUIRE(m && hidden_out && kvs && n_pend, DS_E_INVALID, "draft pass: NULL pointer argument");
+  DS_REQUIRE(n_seq >= 1 && n_seq <= kMaxSeq, DS_E_SHAPE, "%d sequences outside [1, %d]", n_seq, kMaxSeq);
+  DS_REQUIRE(K >= 1, DS_E_SHAPE, "K %d must be >= 1", K);
+  DS_REQUIRE(block_tokens || (mask_id >= 0 && mask_id < m->cfg.vocab), DS_E_INVALID, "mask_id %d outside the vocabulary",
+             mask_id);
+  FwdCall call;
+  call.n_seq = n_seq;
+  int n_pend_all = 0;
+  for (int s = 0; s < n_seq; ++s) {
+    DS_REQUIRE(n_pend[s] >= 0, DS_E_SHAPE, "sequence %d: n_pend %d is negative", s, n_pend[s]);
+    DS_REQUIRE(n_pend[s] + K <= DS_MAX_ROWS, DS_E_SHAPE, "n_pend + K = %d exceeds %d rows", n_pend[s] + K, DS_MAX_ROWS);
+    call.seq[s] = FwdSeq{kvs[s], n_pend[s], n_pend[s] + K, n_pend[s], n_pend[s]};
+    n_pend_all += n_pend[s];
+  }
+  DS_REQUIRE(pending || n_pend_all == 0, DS_E_INVALID, "pending is NULL while n_pend > 0");
+  call.tok_a = pending;
+  call.tok_b = block_tokens;
+  call.fill = mask_id;
+  call.hidden_out = hidden_out;
+  SeqTable tab;
+  int rows = 0, tail = 0;
+  int rc = plan_call(m, call, &tab, &rows, &tail);
   if (rc) return rc;
+  Workspace w;
+  if ((rc = check_ws(m, rows, ws, ws_bytes, &w))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = forward_dispatch(m, w, pending, n_pend, nullptr, mask_id, rows, n_pend, hidden_out, n_pend, st))) return rc;
+  if ((rc = forward_dispatch(m, w, call, tab, rows, true, st))) return rc;
   m->tail_ptr = w.y_tail;
   m->tail_ws = ws;
-  m->tail_rows = K;
-  m->kv_len += n_pend;  // mask rows are never committed
+  m->tail_rows = tail;  // n_seq * K
+  for (int s = 0; s < n_seq; ++s) kvs[s]->len += n_pend[s];  // block rows are never committed
   return DS_OK;
+}
+
+// Verifier pass + greedy acceptance over n_seq sequences of mlen + 1 causal rows each.  Row i of sequence s reads
+// its token from first[s] (i == 0) or path[s * path_stride + i - 1]; the single-sequence entry point passes its
+// block as first = block, path = block + 1.
+int verify_impl(ds_model* m, ds_kv* const* kvs, int n_seq, const int32_t* first, const int32_t* path, int path_stride,
+                int mlen, const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
+                int32_t* argmax, int32_t* eos_accepted, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m && kvs && first && n_accept && next_token && argmax && eos_accepted, DS_E_INVALID,
+             "verifier pass: NULL pointer argument");
+  DS_REQUIRE(n_seq >= 1 && n_seq <= kMaxSeq, DS_E_SHAPE, "%d sequences outside [1, %d]", n_seq, kMaxSeq);
+  DS_REQUIRE(mlen >= 0 && mlen + 1 <= DS_MAX_ROWS, DS_E_SHAPE, "m = %d: m + 1 rows outside [1, %d]", mlen, DS_MAX_ROWS);
+  DS_REQUIRE(path || mlen == 0, DS_E_INVALID, "path is NULL while m > 0");
+  DS_REQUIRE(eos_id < m->cfg.vocab, DS_E_INVALID, "eos_id %d >= vocab", eos_id);
+  const int rows_s = mlen + 1;
+  FwdCall call;
+  call.n_seq = n_seq;
+  AcceptSeqs aq{};
+  aq.n_seq = n_seq;
+  // token sources: tok_a = first (one per sequence), tok_b = path rows; the table's offsets advance by n_a and by
+  // n_rows - n_a per sequence, so a dense path array needs path_stride == mlen (checked by the callers)
+  for (int s = 0; s < n_seq; ++s) call.seq[s] = FwdSeq{kvs[s], 1, rows_s, rows_s, rows_s};
+  call.tok_a = first;
+  call.tok_b = path;
+  SeqTable tab;
+  int rows = 0, tail = 0;
+  int rc = plan_call(m, call, &tab, &rows, &tail);
+  if (rc) return rc;
+  for (int s = 0; s < n_seq; ++s) {
+    tab.off_a[s] = s;
+    tab.off_b[s] = s * path_stride;
+    aq.row0[s] = tab.row0[s];
+    aq.m[s] = mlen;
+    aq.tok_off[s] = s * path_stride;
+    aq.out_off[s] = s * rows_s;
+  }
+  Workspace w;
+  if ((rc = check_ws(m, rows, ws, ws_bytes, &w))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = forward_dispatch(m, w, call, tab, rows, false, st))) return rc;
+  if (const int tile = lm_head_tile(m)) {
+    // The product's epilogue reports every tile's largest logit; the logits themselves are written only if asked for.
+    GemmEpilogue epi;
+    epi.kind = GemmEpilogue::kBest;
+    epi.records = w.tile_rec;
+    if ((rc = lm_head_rows(m, w.y, rows, logits_out, st, epi))) return rc;
+    return launch_tiles_accept(static_cast<float2*>(w.tile_rec), rows, m->cfg.vocab / tile, aq, path, path_len, eos_id,
+                               n_accept, next_token, argmax, eos_accepted, st);
+  }
+  float* logits = logits_out ? logits_out : w.logits;
+  if ((rc = lm_head_rows(m, w.y, rows, logits, st))) return rc;
+  return launch_argmax_accept(logits, rows, m->cfg.vocab, aq, path, path_len, eos_id, n_accept, next_token, argmax,
+                              eos_accepted, w.scan, w.scan_bytes, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ds_prefill(ds_model* m, const int32_t* tokens, int n, float* last_logits, void* ws, size_t ws_bytes,
+               void* stream) {
+  DS_REQUIRE(m, DS_E_INVALID, "ds_prefill: NULL model");
+  return prefill_impl(m, &m->self, tokens, n, last_logits, ws, ws_bytes, stream);
+}
+
+int ds_prefill_seq(ds_model* m, ds_kv* kv, const int32_t* tokens, int n, float* last_logits, void* ws,
+                   size_t ws_bytes, void* stream) {
+  return prefill_impl(m, kv, tokens, n, last_logits, ws, ws_bytes, stream);
+}
+
+int ds_draft_block(ds_model* m, const int32_t* pending, int n_pend, int K, int32_t mask_id, float* hidden_out,
+                   void* ws, size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m, DS_E_INVALID, "ds_draft_block: NULL model");
+  ds_kv* kv = &m->self;
+  return draft_impl(m, &kv, 1, pending, &n_pend, K, nullptr, mask_id, hidden_out, ws, ws_bytes, stream);
+}
+
+int ds_draft_block_batch(ds_model* m, ds_kv* const* seqs, int n_seq, const int32_t* pending, const int* n_pend, int K,
+                         int32_t mask_id, float* hidden_out, void* ws, size_t ws_bytes, void* stream) {
+  return draft_impl(m, seqs, n_seq, pending, n_pend, K, nullptr, mask_id, hidden_out, ws, ws_bytes, stream);
 }
 
 int ds_lm_head(ds_model* m, const float* hidden, int rows, float* logits, void* ws, size_t ws_bytes, void* stream) {
@@ -596,53 +790,25 @@ int ds_draft_lattice(ds_model* m, const float* hidden, int rows, int M_max, floa
 int ds_verify_block(ds_model* m, const int32_t* block, int mlen, const int32_t* path_len, int32_t eos_id,
                     int32_t* n_accept, int32_t* next_token, int32_t* argmax, int32_t* eos_accepted,
                     float* logits_out, void* ws, size_t ws_bytes, void* stream) {
-  DS_REQUIRE(m && block && n_accept && next_token && argmax && eos_accepted, DS_E_INVALID,
-             "ds_verify_block: NULL pointer argument");
-  DS_REQUIRE(mlen >= 0 && mlen + 1 <= DS_MAX_ROWS, DS_E_SHAPE, "m = %d: m + 1 rows outside [1, %d]", mlen,
-             DS_MAX_ROWS);
-  DS_REQUIRE(eos_id < m->cfg.vocab, DS_E_INVALID, "eos_id %d >= vocab", eos_id);
-  const int rows = mlen + 1;
-  DS_REQUIRE(m->kv_len + rows <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d rows exceed capacity %d",
-             m->kv_len, rows, m->cfg.kv_capacity);
-  Workspace w;
-  int rc = check_ws(m, rows, ws, ws_bytes, &w);
-  if (rc) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = forward_dispatch(m, w, block, rows, nullptr, 0, rows, rows, nullptr, 0, st))) return rc;
-  if (const int tile = lm_head_tile(m)) {
-    // The product's epilogue reports every tile's largest logit; the logits themselves are written only if asked for.
-    GemmEpilogue epi;
-    epi.kind = GemmEpilogue::kBest;
-    epi.records = w.tile_rec;
-    if ((rc = lm_head_rows(m, w.y, rows, logits_out, st, epi))) return rc;
-    return launch_tiles_accept(static_cast<float2*>(w.tile_rec), rows, m->cfg.vocab / tile, block, path_len, eos_id, n_accept, next_token,
-                               argmax, eos_accepted, st);
-  }
-  float* logits = logits_out ? logits_out : w.logits;
-  if ((rc = lm_head_rows(m, w.y, rows, logits, st))) return rc;
-  return launch_argmax_accept(logits, rows, m->cfg.vocab, block, path_len, eos_id, n_accept, next_token, argmax,
-                              eos_accepted, w.scan, w.scan_bytes, st);
+  DS_REQUIRE(m && block, DS_E_INVALID, "ds_verify_block: NULL pointer argument");
+  ds_kv* kv = &m->self;
+  return verify_impl(m, &kv, 1, block, block + 1, mlen, mlen, path_len, eos_id, n_accept, next_token, argmax,
+                     eos_accepted, logits_out, ws, ws_bytes, stream);
+}
+
+int ds_verify_block_batch(ds_model* m, ds_kv* const* seqs, int n_seq, const int32_t* first, const int32_t* path,
+                          int mlen, const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
+                          int32_t* argmax, int32_t* eos_accepted, float* logits_out, void* ws, size_t ws_bytes,
+                          void* stream) {
+  return verify_impl(m, seqs, n_seq, first, path, mlen, mlen, path_len, eos_id, n_accept, next_token, argmax,
+                     eos_accepted, logits_out, ws, ws_bytes, stream);
 }
 
 int ds_draft_block_tokens(ds_model* m, const int32_t* pending, int n_pend, const int32_t* block_tokens, int K,
                           float* hidden_out, void* ws, size_t ws_bytes, void* stream) {
-  DS_REQUIRE(m && hidden_out && block_tokens, DS_E_INVALID, "ds_draft_block_tokens: NULL pointer argument");
-  DS_REQUIRE(n_pend >= 0 && K >= 1, DS_E_SHAPE, "need n_pend >= 0 and K >= 1 (got %d, %d)", n_pend, K);
-  DS_REQUIRE(pending || n_pend == 0, DS_E_INVALID, "pending is NULL while n_pend > 0");
-  const int rows = n_pend + K;
-  DS_REQUIRE(rows <= DS_MAX_ROWS, DS_E_SHAPE, "n_pend + K = %d exceeds %d rows", rows, DS_MAX_ROWS);
-  DS_REQUIRE(m->kv_len + rows <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d rows exceed capacity %d",
-             m->kv_len, rows, m->cfg.kv_capacity);
-  Workspace w;
-  int rc = check_ws(m, rows, ws, ws_bytes, &w);
-  if (rc) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = forward_dispatch(m, w, pending, n_pend, block_tokens, 0, rows, n_pend, hidden_out, n_pend, st))) return rc;
-  m->tail_ptr = w.y_tail;
-  m->tail_ws = ws;
-  m->tail_rows = K;
-  m->kv_len += n_pend;  // block rows are never committed
-  return DS_OK;
+  DS_REQUIRE(m && block_tokens, DS_E_INVALID, "ds_draft_block_tokens: NULL pointer argument");
+  ds_kv* kv = &m->self;
+  return draft_impl(m, &kv, 1, pending, &n_pend, K, block_tokens, 0, hidden_out, ws, ws_bytes, stream);
 }
 
 int ds_verify_block_stochastic(ds_model* m, const int32_t* block, int mlen, const int32_t* path_len,
@@ -656,13 +822,18 @@ int ds_verify_block_stochastic(ds_model* m, const int32_t* block, int mlen, cons
   DS_REQUIRE(mlen == 0 || (q_logits && alpha), DS_E_INVALID, "q_logits / alpha is NULL while m > 0");
   DS_REQUIRE(eos_id < m->cfg.vocab, DS_E_INVALID, "eos_id %d >= vocab", eos_id);
   const int rows = mlen + 1;
-  DS_REQUIRE(m->kv_len + rows <= m->cfg.kv_capacity, DS_E_CAPACITY, "KV cache: %d + %d rows exceed capacity %d",
-             m->kv_len, rows, m->cfg.kv_capacity);
-  Workspace w;
-  int rc = check_ws(m, rows, ws, ws_bytes, &w);
+  FwdCall call;
+  call.n_seq = 1;
+  call.seq[0] = FwdSeq{&m->self, rows, rows, rows, rows};
+  call.tok_a = block;
+  SeqTable tab;
+  int total = 0, tail = 0;
+  int rc = plan_call(m, call, &tab, &total, &tail);
   if (rc) return rc;
+  Workspace w;
+  if ((rc = check_ws(m, rows, ws, ws_bytes, &w))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = forward_dispatch(m, w, block, rows, nullptr, 0, rows, rows, nullptr, 0, st))) return rc;
+  if ((rc = forward_dispatch(m, w, call, tab, rows, false, st))) return rc;
   float* logits = logits_out ? logits_out : w.logits;
   if ((rc = lm_head_rows(m, w.y, rows, logits, st))) return rc;
   return launch_sample_accept(logits, q_logits, mlen, m->cfg.vocab, block, path_len, u, eos_id, n_accept, next_token,

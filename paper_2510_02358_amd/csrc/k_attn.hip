@@ -48,9 +48,11 @@ template <int QB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_f16_kernel(const uint16_t* __restrict__ q,
                                                         const uint16_t* __restrict__ kc,
                                                         const uint16_t* __restrict__ vc, int rows, int rows_pad,
-                                                        int n_causal, int pos0, int n_keys, int n_q, int n_kv,
-                                                        int cap, int chunks_per_split, float scale_log2,
+                                                        int rows_stride, int n_causal, int pos0, int n_keys, int n_q,
+                                                        int n_kv, int cap, int chunks_per_split, float scale_log2,
                                                         float* __restrict__ part_o, float* __restrict__ part_ml) {
+  // rows / rows_pad: the rows of ONE sequence (q, part_o and part_ml already point at its first row);
+  // rows_stride: padded rows of the whole call (stride between heads and between splits)
   __shared__ __attribute__((aligned(16))) uint16_t ks_lds[2][kChunkElems];
   __shared__ __attribute__((aligned(16))) uint16_t vs_lds[2][kChunkElems];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -74,7 +76,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     const int qbc = valid[t] ? qb : 0;
     head[t] = kvh * group + qbc / rb_count;
     rb[t] = qbc % rb_count;
-    const uint16_t* qh = q + (size_t)head[t] * rows_pad * kHd + (size_t)rb[t] * 4 * 512;
+    const uint16_t* qh = q + (size_t)head[t] * rows_stride * kHd + (size_t)rb[t] * 4 * 512;
 #pragma unroll
     for (int s = 0; s < 4; ++s) bq[t][s] = *reinterpret_cast<const f16x8*>(qh + s * 512 + lane * 8);
 #pragma unroll
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     l += __shfl_xor(l, 32);
     const int r = rb[t] * 16 + j;
     if (!valid[t] || r >= rows) continue;  // padding rows are never merged
-    const size_t row = ((size_t)split * n_q + head[t]) * rows_pad + r;
+    const size_t row = ((size_t)split * n_q + head[t]) * rows_stride + r;
 #pragma unroll
     for (int d = 0; d < 8; ++d)
       *reinterpret_cast<float4*>(part_o + row * kHd + d * 16 + 4 * g) =
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 
 // float32 parity mode.  grid (n_split, n_q); each wavefront walks rows r = wave, wave + 4, ...
 __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__ q, const float* __restrict__ kc,
-                                                       const float* __restrict__ vc, int rows, int rows_pad,
+                                                       const float* __restrict__ vc, int rows, int rows_stride,
                                                        int n_causal, int pos0, int n_keys, int n_q, int n_kv,
                                                        int hd, int cap, int chunks_per_split, float scale,
                                                        float* __restrict__ part_o, float* __restrict__ part_ml) {
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
   const float* vh = vc + (size_t)kvh * cap * hd;
 
   for (int r = wave; r < rows; r += 4) {
-    const float* qr = q + ((size_t)head * rows_pad + r) * hd;
+    const float* qr = q + ((size_t)head * rows_stride + r) * hd;
     for (int d = lane; d < hd; d += 64) qbuf[wave][d] = qr[d];
     __builtin_amdgcn_wave_barrier();
     const int limit = (r >= n_causal) ? n_keys - 1 : pos0 + r;
@@ -273,7 +275,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
       }
       __builtin_amdgcn_wave_barrier();
     }
-    const size_t row = ((size_t)split * n_q + head) * rows_pad + r;
+    const size_t row = ((size_t)split * n_q + head) * rows_stride + r;
     if (lane < hd) part_o[row * hd + lane] = o0;
     if (lane + 64 < hd) part_o[row * hd + lane + 64] = o1;
     if (lane == 0) {
@@ -287,11 +289,17 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
 // One workgroup per (row, head), one thread per output column; loops are unrolled so that the loads of
 // several splits are in flight together.
 template <typename T>
-__global__ void attn_merge_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, int n_split,
-                                  int n_q, int rows_pad, int hd, T* __restrict__ att, uint32_t* __restrict__ ovf) {
-  // att: GEMM input [rows_pad, n_q * hd] of the output projection
+__global__ void attn_merge_kernel(SeqTable tab, const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                  int n_split, int n_q, int rows_pad, int hd, T* __restrict__ att,
+                                  uint32_t* __restrict__ ovf) {
+  // att: GEMM input [rows_pad, n_q * hd] of the output projection.  n_split: the largest split count among the
+  // call's sequences (a sequence with fewer keys has left empty partials, weight zero, in the others).
   const int r = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
   if (d >= hd) return;
+  if (seq_of_row(tab, r) < 0) {  // padding row between two sequences: no partials exist; keep the row finite
+    Act<T>::put(att, r, head * hd + d, n_q * hd, 0.f, nullptr);
+    return;
+  }
   const size_t stride = (size_t)n_q * rows_pad;           // rows between consecutive splits
   const size_t row0 = (size_t)head * rows_pad + r;
   float mx = -INFINITY;
@@ -338,38 +346,60 @@ AttnPlan attn_plan(int dtype, int cap, int n_keys) {
   return p;
 }
 
-int launch_attention(int dtype, const void* q, const void* kc, const void* vc, int rows, int rows_pad, int n_causal,
-                     int pos0, int n_keys, int n_q, int n_kv, int hd, int cap, float* part_o, float* part_ml,
-                     void* att_out, uint32_t* ovf, hipStream_t st) {
+int launch_attention(int dtype, const SeqTable& tab, const void* q, int rows, int rows_pad, int n_q, int n_kv, int hd,
+                     int cap, float* part_o, float* part_ml, void* att_out, uint32_t* ovf, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)hd);
-  DS_REQUIRE(n_keys >= 1 && n_keys <= cap, DS_E_CAPACITY, "attention: %d keys exceed the cache capacity %d", n_keys, cap);
-  const AttnPlan plan = attn_plan(dtype, cap, n_keys);
-  DS_REQUIRE(plan.n_split * rows_pad <= attn_partial_rows(rows_pad), DS_E_CAPACITY,
-             "attention partials: %d splits x %d rows exceed the workspace", plan.n_split, rows_pad);
+  DS_REQUIRE(tab.n_seq >= 1 && tab.n_seq <= kMaxSeq, DS_E_SHAPE, "attention: %d sequences outside [1, %d]", tab.n_seq,
+             kMaxSeq);
   if (dtype == DS_BF16) {
     DS_REQUIRE(hd == kHd, DS_E_UNSUPPORTED, "bf16 attention needs head_dim 128 (got %d)", hd);
     DS_REQUIRE(cap % kChunk == 0, DS_E_SHAPE, "bf16 attention needs a cache capacity that is a multiple of %d", kChunk);
-    const int n_qb = (n_q / n_kv) * (rows_pad >> 4);
-    constexpr int QB = 2;
-    dim3 grid(plan.n_split, n_kv, ceil_div(n_qb, 4 * QB));
-    hipLaunchKernelGGL((attn_f16_kernel<QB>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
-                       static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc), rows, rows_pad, n_causal,
-                       pos0, n_keys, n_q, n_kv, cap, plan.chunks_per_split, scale * 1.4426950408889634f, part_o,
-                       part_ml);
-    DS_LAUNCH_CHECK("attn_f16_kernel");
-    hipLaunchKernelGGL((attn_merge_kernel<bf16_t>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, plan.n_split,
-                       n_q, rows_pad, hd, static_cast<bf16_t*>(att_out), ovf);
-    DS_LAUNCH_CHECK("attn_merge_kernel<bf16>");
   } else {
     DS_REQUIRE(hd <= 128 && (hd & 1) == 0, DS_E_UNSUPPORTED, "f32 attention needs even head_dim <= 128 (got %d)", hd);
-    hipLaunchKernelGGL(attn_f32_kernel, dim3(plan.n_split, n_q), dim3(256), 0, st, static_cast<const float*>(q),
-                       static_cast<const float*>(kc), static_cast<const float*>(vc), rows, rows_pad, n_causal, pos0,
-                       n_keys, n_q, n_kv, hd, cap, plan.chunks_per_split, scale, part_o, part_ml);
-    DS_LAUNCH_CHECK("attn_f32_kernel");
-    hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(rows, n_q), dim3(hd), 0, st, part_o, part_ml, plan.n_split,
-                       n_q, rows_pad, hd, static_cast<float*>(att_out), ovf);
-    DS_LAUNCH_CHECK("attn_merge_kernel<f32>");
   }
+  // every sequence runs the split plan of its own key count; the merge walks the largest split count, so each
+  // sequence's launch covers that many splits (the ones past its keys leave empty partials)
+  int n_split_max = 1;
+  for (int s = 0; s < tab.n_seq; ++s) {
+    const int n_keys = tab.pos0[s] + tab.n_rows[s];
+    DS_REQUIRE(tab.n_rows[s] >= 1 && (tab.row0[s] & 15) == 0 && tab.row0[s] + tab.n_rows[s] <= rows, DS_E_SHAPE,
+               "attention: sequence %d has a bad row range", s);
+    DS_REQUIRE(n_keys >= 1 && n_keys <= cap, DS_E_CAPACITY, "attention: %d keys exceed the cache capacity %d", n_keys, cap);
+    const AttnPlan plan = attn_plan(dtype, cap, n_keys);
+    n_split_max = plan.n_split > n_split_max ? plan.n_split : n_split_max;
+  }
+  DS_REQUIRE(n_split_max * rows_pad <= attn_partial_rows(rows_pad), DS_E_CAPACITY,
+             "attention partials: %d splits x %d rows exceed the workspace", n_split_max, rows_pad);
+  for (int s = 0; s < tab.n_seq; ++s) {
+    const int n_keys = tab.pos0[s] + tab.n_rows[s], r0 = tab.row0[s], sr = tab.n_rows[s];
+    const int srp = ceil_div(sr, 16) * 16;
+    const AttnPlan plan = attn_plan(dtype, cap, n_keys);
+    if (dtype == DS_BF16) {
+      const int n_qb = (n_q / n_kv) * (srp >> 4);
+      constexpr int QB = 2;
+      dim3 grid(n_split_max, n_kv, ceil_div(n_qb, 4 * QB));
+      hipLaunchKernelGGL((attn_f16_kernel<QB>), grid, dim3(256), 0, st,
+                         static_cast<const uint16_t*>(q) + (size_t)(r0 >> 4) * 4 * 512,
+                         static_cast<const uint16_t*>(tab.kc[s]), static_cast<const uint16_t*>(tab.vc[s]), sr, srp,
+                         rows_pad, tab.n_causal[s], tab.pos0[s], n_keys, n_q, n_kv, cap, plan.chunks_per_split,
+                         scale * 1.4426950408889634f, part_o + (size_t)r0 * kHd, part_ml + (size_t)r0 * 2);
+      DS_LAUNCH_CHECK("attn_f16_kernel");
+    } else {
+      hipLaunchKernelGGL(attn_f32_kernel, dim3(n_split_max, n_q), dim3(256), 0, st,
+                         static_cast<const float*>(q) + (size_t)r0 * hd, static_cast<const float*>(tab.kc[s]),
+                         static_cast<const float*>(tab.vc[s]), sr, rows_pad, tab.n_causal[s], tab.pos0[s], n_keys, n_q,
+                         n_kv, hd, cap, plan.chunks_per_split, scale, part_o + (size_t)r0 * hd,
+                         part_ml + (size_t)r0 * 2);
+      DS_LAUNCH_CHECK("attn_f32_kernel");
+    }
+  }
+  if (dtype == DS_BF16)
+    hipLaunchKernelGGL((attn_merge_kernel<bf16_t>), dim3(rows, n_q), dim3(hd), 0, st, tab, part_o, part_ml, n_split_max,
+                       n_q, rows_pad, hd, static_cast<bf16_t*>(att_out), ovf);
+  else
+    hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(rows, n_q), dim3(hd), 0, st, tab, part_o, part_ml, n_split_max,
+                       n_q, rows_pad, hd, static_cast<float*>(att_out), ovf);
+  DS_LAUNCH_CHECK("attn_merge_kernel");
   return DS_OK;
 }
 

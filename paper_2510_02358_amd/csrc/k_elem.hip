@@ -29,13 +29,15 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 
 constexpr int kMaxPlanes = 10;  // split-K planes summed per element (gemm_bf16_splits never exceeds it)
 
-// Token and rotary arguments of the first kernel of a forward (FROM_EMBED).
+// Token and rotary arguments of the first kernel of a forward (FROM_EMBED).  Row i of sequence s reads its token
+// from tok_a[off_a[s] + i] if i < n_a[s], else from tok_b[off_b[s] + i - n_a[s]] (or is `fill` if tok_b is NULL); ids
+// outside [0, vocab) read as 0, and so do the padding rows between sequences (position 0).
 struct Prologue {
-  const int32_t* src;   // [n_real] real tokens; ids outside [0, vocab) read as 0
-  const int32_t* src2;  // tokens of the rows past n_real (row r reads src2[r - n_real]); NULL: those rows are `fill`
-  int n_real, vocab;
+  const int32_t* tok_a;
+  const int32_t* tok_b;
+  int vocab;
   int32_t fill;
-  int pos0, half;      // rotary table: cs[r][i] = (cos, sin)((pos0 + r) * base^(-i / half)), i < half
+  int half;            // rotary table: cs[r][i] = (cos, sin)(position(r) * base^(-i / half)), i < half
   double log2_base;
   float2* cs;
 };
@@ -43,32 +45,43 @@ struct Prologue {
 // x[r] = E[tok[r]] or x[r] + sum of split-K planes ; h[r] = rmsnorm(x[r]) * gain, written as GEMM input.
 // FROM_EMBED: start from the embedding row (and fill this row of the rotary table, angles in double so
 // that long contexts stay exact), else from the float32 residual x plus `n_part` planes.
-// rm_out (optional): row-major float32 copy of rows >= rm_row0 (the boundary's hidden_out); h_tail (optional):
-// the same rows once more as a GEMM input that starts at row rm_row0 (what the LM head multiplies).
+// rm_out (optional): row-major float32 copy of the rows each sequence hands on (the boundary's hidden_out: rows
+// tail0 .. of every sequence, compacted in sequence order); h_tail (optional): the same rows once more as a GEMM
+// input (what the LM head multiplies).
 // One workgroup per row (1024 threads for wide models so that every load of the row is issued at once),
 // four consecutive columns per thread and step (d_model % 4 == 0); the planes
 // are summed in index order, all loads of a step issued before the first add.
 template <typename T, bool FROM_EMBED, int THREADS>
-__global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, const T* __restrict__ embed,
+__global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, SeqTable tab, const T* __restrict__ embed,
                                                    float* __restrict__ x, const float* __restrict__ part,
                                                    int n_part, int rows, int rows_pad, int d,
                                                    const float* __restrict__ gain, float eps, T* __restrict__ h,
                                                    float* __restrict__ rm_out, T* __restrict__ h_tail,
-                                                   int rm_row0, uint32_t* __restrict__ ovf) {
+                                                   uint32_t* __restrict__ ovf) {
   constexpr int kMaxVec = 8192 / (4 * THREADS);  // float4 groups per thread (d_model <= 8192)
   __shared__ float red[THREADS / 64];
   const int r = blockIdx.x;
+  const int sq = seq_of_row(tab, r);
+  const int ri = sq >= 0 ? r - tab.row0[sq] : 0;  // row within its sequence
   int token = 0;
   if (FROM_EMBED) {
-    token = r < pro.n_real ? pro.src[r] : (pro.src2 ? pro.src2[r - pro.n_real] : pro.fill);
-    token = (token < 0 || token >= pro.vocab) ? 0 : token;
+    int pos = 0;
+    if (sq >= 0) {
+      pos = tab.pos0[sq] + ri;
+      token = ri < tab.n_a[sq] ? pro.tok_a[tab.off_a[sq] + ri]
+                               : (pro.tok_b ? pro.tok_b[tab.off_b[sq] + ri - tab.n_a[sq]] : pro.fill);
+      token = (token < 0 || token >= pro.vocab) ? 0 : token;
+    }
     if ((int)threadIdx.x < pro.half) {
       const double theta = exp2(-((double)threadIdx.x / (double)pro.half) * pro.log2_base);
       double sn, cs;
-      sincos((double)(pro.pos0 + r) * theta, &sn, &cs);
+      sincos((double)pos * theta, &sn, &cs);
       pro.cs[r * pro.half + threadIdx.x] = make_float2((float)cs, (float)sn);
     }
   }
+  // rows handed on (rm_out / h_tail): rows ri >= tail0 of each sequence, compacted to tail_base + (ri - tail0)
+  const bool is_tail = sq >= 0 && ri >= tab.tail0[sq];
+  const int tail_row = is_tail ? tab.tail_base[sq] + ri - tab.tail0[sq] : 0;
   float4 v[kMaxVec];
   float ss = 0.f;
 #pragma unroll
@@ -106,8 +119,8 @@ __global__ __launch_bounds__(THREADS) void norm_kernel(Prologue pro, const T* __
       const float4 gn = *reinterpret_cast<const float4*>(gain + c);
       const float4 y = make_float4(v[i].x * inv * gn.x, v[i].y * inv * gn.y, v[i].z * inv * gn.z, v[i].w * inv * gn.w);
       Act<T>::put4(h, r, c, d, y, ovf);
-      if (rm_out && r >= rm_row0) *reinterpret_cast<float4*>(rm_out + (size_t)(r - rm_row0) * d + c) = y;
-      if (h_tail && r >= rm_row0) Act<T>::put4(h_tail, r - rm_row0, c, d, y, nullptr);
+      if (rm_out && is_tail) *reinterpret_cast<float4*>(rm_out + (size_t)tail_row * d + c) = y;
+      if (h_tail && is_tail) Act<T>::put4(h_tail, tail_row, c, d, y, nullptr);
     }
   }
 }
@@ -126,12 +139,16 @@ __global__ void to_gemm_input_kernel(const float* __restrict__ src, int rows_pad
 // Head slots: [0, n_q) queries, [n_q, n_q + n_kv) keys, then values.
 template <typename T>
 __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int n_q,
-                                int n_kv, int hd, const float2* __restrict__ cs, int pos0, int cap,
-                                typename Act<T>::kv_t* __restrict__ q, typename Act<T>::kv_t* __restrict__ kc,
-                                typename Act<T>::kv_t* __restrict__ vc, uint32_t* __restrict__ ovf) {
+                                int n_kv, int hd, const float2* __restrict__ cs, SeqTable tab, int cap,
+                                typename Act<T>::kv_t* __restrict__ q, uint32_t* __restrict__ ovf) {
   using KV = typename Act<T>::kv_t;
   const int r = blockIdx.x, slot = blockIdx.y, i = threadIdx.x, half = hd >> 1;
   if (i >= half) return;
+  const int sq = seq_of_row(tab, r);
+  if (sq < 0 && slot >= n_q) return;  // a padding row has no place in any cache (its q stays finite and unused)
+  KV* kc = sq >= 0 ? static_cast<KV*>(tab.kc[sq]) : nullptr;
+  KV* vc = sq >= 0 ? static_cast<KV*>(tab.vc[sq]) : nullptr;
+  const int pos0 = sq >= 0 ? tab.pos0[sq] - tab.row0[sq] : 0;  // position of row r = pos0 + r
   const int n_tot = (n_q + 2 * n_kv) * hd;
   // all planes' loads are issued before the first add (one memory round trip instead of n_part); the sum keeps
   // the plane order
@@ -222,34 +239,35 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
 }  // namespace
 
 template <typename T>
-int launch_embed_norm(const int32_t* src, int n_real, const int32_t* src2, int32_t fill, int vocab, int pos0, int hd,
+int launch_embed_norm(const SeqTable& tab, const int32_t* tok_a, const int32_t* tok_b, int32_t fill, int vocab, int hd,
                       double rope_base, float2* cs, const void* embed, float* x, int rows, int rows_pad, int d,
                       const float* gain, float eps, void* h, uint32_t* ovf, hipStream_t st) {
-  Prologue pro{src, src2, n_real, vocab, fill, pos0, hd / 2, log2(rope_base), cs};
+  Prologue pro{tok_a, tok_b, vocab, fill, hd / 2, log2(rope_base), cs};
   if (d >= 2048)
-    hipLaunchKernelGGL((norm_kernel<T, true, 1024>), dim3(rows), dim3(1024), 0, st, pro, static_cast<const T*>(embed),
-                       x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr,
-                       (T*)nullptr, 0, ovf);
+    hipLaunchKernelGGL((norm_kernel<T, true, 1024>), dim3(rows), dim3(1024), 0, st, pro, tab,
+                       static_cast<const T*>(embed), x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps,
+                       static_cast<T*>(h), (float*)nullptr, (T*)nullptr, ovf);
   else
-    hipLaunchKernelGGL((norm_kernel<T, true, 256>), dim3(rows), dim3(256), 0, st, pro, static_cast<const T*>(embed),
-                       x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps, static_cast<T*>(h), (float*)nullptr,
-                       (T*)nullptr, 0, ovf);
+    hipLaunchKernelGGL((norm_kernel<T, true, 256>), dim3(rows), dim3(256), 0, st, pro, tab,
+                       static_cast<const T*>(embed), x, (const float*)nullptr, 0, rows, rows_pad, d, gain, eps,
+                       static_cast<T*>(h), (float*)nullptr, (T*)nullptr, ovf);
   DS_LAUNCH_CHECK("norm_kernel<embed>");
   return DS_OK;
 }
 
 template <typename T>
-int launch_add_norm(float* x, const float* part, int n_part, int rows, int rows_pad, int d, const float* gain,
-                    float eps, void* h, float* rm_out, void* h_tail, int rm_row0, uint32_t* ovf, hipStream_t st) {
+int launch_add_norm(const SeqTable& tab, float* x, const float* part, int n_part, int rows, int rows_pad, int d,
+                    const float* gain, float eps, void* h, float* rm_out, void* h_tail, uint32_t* ovf,
+                    hipStream_t st) {
   DS_REQUIRE(n_part >= 0 && n_part <= kMaxPlanes, DS_E_SHAPE, "norm: %d partial planes, at most %d", n_part, kMaxPlanes);
   if (d >= 2048)
-    hipLaunchKernelGGL((norm_kernel<T, false, 1024>), dim3(rows), dim3(1024), 0, st, Prologue{}, (const T*)nullptr, x,
-                       part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, static_cast<T*>(h_tail),
-                       rm_row0, ovf);
+    hipLaunchKernelGGL((norm_kernel<T, false, 1024>), dim3(rows), dim3(1024), 0, st, Prologue{}, tab,
+                       (const T*)nullptr, x, part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out,
+                       static_cast<T*>(h_tail), ovf);
   else
-    hipLaunchKernelGGL((norm_kernel<T, false, 256>), dim3(rows), dim3(256), 0, st, Prologue{}, (const T*)nullptr, x,
-                       part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out, static_cast<T*>(h_tail),
-                       rm_row0, ovf);
+    hipLaunchKernelGGL((norm_kernel<T, false, 256>), dim3(rows), dim3(256), 0, st, Prologue{}, tab,
+                       (const T*)nullptr, x, part, n_part, rows, rows_pad, d, gain, eps, static_cast<T*>(h), rm_out,
+                       static_cast<T*>(h_tail), ovf);
   DS_LAUNCH_CHECK("norm_kernel<add>");
   return DS_OK;
 }
@@ -263,12 +281,11 @@ int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* 
 }
 
 template <typename T>
-int launch_qkv_rope(const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv, int hd,
-                    const float2* cs, int pos0, int cap, void* q, void* kc, void* vc, uint32_t* ovf, hipStream_t st) {
+int launch_qkv_rope(const SeqTable& tab, const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv,
+                    int hd, const float2* cs, int cap, void* q, uint32_t* ovf, hipStream_t st) {
   DS_REQUIRE(n_part >= 1 && n_part <= kMaxPlanes, DS_E_SHAPE, "rope: %d partial planes, at most %d", n_part, kMaxPlanes);
   hipLaunchKernelGGL((qkv_rope_kernel<T>), dim3(rows, n_q + 2 * n_kv), dim3(hd / 2), 0, st, part, n_part, rows,
-                     rows_pad, n_q, n_kv, hd, cs, pos0, cap, static_cast<typename Act<T>::kv_t*>(q),
-                     static_cast<typename Act<T>::kv_t*>(kc), static_cast<typename Act<T>::kv_t*>(vc), ovf);
+                     rows_pad, n_q, n_kv, hd, cs, tab, cap, static_cast<typename Act<T>::kv_t*>(q), ovf);
   DS_LAUNCH_CHECK("qkv_rope_kernel");
   return DS_OK;
 }
@@ -284,14 +301,14 @@ int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, 
 }
 
 #define DS_INSTANTIATE(T)                                                                                          \
-  template int launch_embed_norm<T>(const int32_t*, int, const int32_t*, int32_t, int, int, int, double, float2*,  \
-                                    const void*, float*, int, int, int, const float*, float, void*, uint32_t*,      \
-                                    hipStream_t);                                                                  \
-  template int launch_add_norm<T>(float*, const float*, int, int, int, int, const float*, float, void*, float*,   \
-                                  void*, int, uint32_t*, hipStream_t);                                             \
+  template int launch_embed_norm<T>(const SeqTable&, const int32_t*, const int32_t*, int32_t, int, int, double,    \
+                                    float2*, const void*, float*, int, int, int, const float*, float, void*,       \
+                                    uint32_t*, hipStream_t);                                                       \
+  template int launch_add_norm<T>(const SeqTable&, float*, const float*, int, int, int, int, const float*, float, \
+                                  void*, float*, void*, uint32_t*, hipStream_t);                                   \
   template int launch_to_gemm_input<T>(const float*, int, int, int, void*, uint32_t*, hipStream_t);                \
-  template int launch_qkv_rope<T>(const float*, int, int, int, int, int, int, const float2*, int, int, void*,     \
-                                  void*, void*, uint32_t*, hipStream_t);                                           \
+  template int launch_qkv_rope<T>(const SeqTable&, const float*, int, int, int, int, int, int, const float2*, int, \
+                                  void*, uint32_t*, hipStream_t);                                                  \
   template int launch_swiglu<T>(const float*, int, int, int, int, void*, uint32_t*, hipStream_t);
 DS_INSTANTIATE(float)
 DS_INSTANTIATE(bf16_t)

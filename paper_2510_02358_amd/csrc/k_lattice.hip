@@ -317,10 +317,42 @@ __global__ __launch_bounds__(kWave) void lattice_merge_kernel(const float* __res
   }
 }
 
+// The accepted-prefix rule for every sequence of the call, by one thread: am[row] holds every row's arg-max.
+// Sequence s owns rows [row0[s], row0[s] + m[s] + 1); row i predicts the token after block row i, and path token n
+// (0-based, = block row n + 1) is path_tok[tok_off[s] + n].  eos_accepted is stored last, after a system-scope
+// fence: a host polling the last sequence's word in device-visible memory then sees every other output.
+__device__ __forceinline__ void write_verdicts(const AcceptSeqs& sq, const int32_t* am, const int32_t* path_tok,
+                                               const int32_t* path_len, int32_t eos_id, int32_t* n_accept,
+                                               int32_t* next_token, int32_t* eos_accepted) {
+  bool eos_flag[kMaxSeq];
+  for (int s = 0; s < sq.n_seq; ++s) {
+    int m = sq.m[s];
+    if (path_len) {
+      const int pl = path_len[s];
+      m = pl < m ? (pl < 0 ? 0 : pl) : m;
+    }
+    const int32_t* a = am + sq.row0[s];
+    const int32_t* tok = path_tok + sq.tok_off[s];
+    int n = 0;
+    bool eos = false;
+    while (n < m && a[n] == tok[n]) {
+      eos |= (eos_id >= 0 && tok[n] == eos_id);
+      ++n;
+    }
+    const int nxt = a[n];
+    eos |= (eos_id >= 0 && nxt == eos_id);
+    n_accept[s] = n;
+    next_token[s] = nxt;
+    eos_flag[s] = eos;
+  }
+  __threadfence_system();
+  for (int s = 0; s < sq.n_seq; ++s) eos_accepted[s] = eos_flag[s] ? 1 : 0;
+}
+
 // One workgroup: arg-max of every row from the partial lists, then the accepted-prefix rule.
 __global__ __launch_bounds__(1024) void accept_merge_kernel(int rows, int n_part,
-                                                           const uint32_t* __restrict__ partial,
-                                                           const int32_t* __restrict__ block,
+                                                           const uint32_t* __restrict__ partial, AcceptSeqs sq,
+                                                           const int32_t* __restrict__ path_tok,
                                                            const int32_t* __restrict__ path_len, int32_t eos_id,
                                                            int32_t* __restrict__ n_accept,
                                                            int32_t* __restrict__ next_token,
@@ -352,29 +384,12 @@ __global__ __launch_bounds__(1024) void accept_merge_kernel(int rows, int n_part
     }
     if (lane == 0) {
       am[r] = eid;
-      argmax_out[r] = eid;
+      const int o = accept_out_index(sq, r);
+      if (o >= 0) argmax_out[o] = eid;
     }
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int m = rows - 1;
-    if (path_len) {
-      int pl = *path_len;
-      m = pl < m ? (pl < 0 ? 0 : pl) : m;
-    }
-    int n = 0;
-    bool eos = false;
-    while (n < m && am[n] == block[n + 1]) {
-      eos |= (eos_id >= 0 && block[n + 1] == eos_id);
-      ++n;
-    }
-    const int nxt = am[n];
-    eos |= (eos_id >= 0 && nxt == eos_id);
-    *n_accept = n;
-    *next_token = nxt;
-    __threadfence_system();  // eos_accepted last: a host polling it in device-visible memory then sees all three
-    *eos_accepted = eos ? 1 : 0;
-  }
+  if (threadIdx.x == 0) write_verdicts(sq, am, path_tok, path_len, eos_id, n_accept, next_token, eos_accepted);
 }
 
 // Same rule, fed by the LM-head product's own epilogue instead of a scan of the logits: tile_best[tile][row] is the
@@ -385,7 +400,7 @@ __global__ __launch_bounds__(1024) void accept_merge_kernel(int rows, int n_part
 __global__ __launch_bounds__(256) void accept_tiles_kernel(int rows, int rows_pad, int n_tiles,
                                                           const float2* __restrict__ tile_best,
                                                           uint32_t* __restrict__ counter, int32_t* am,
-                                                          const int32_t* __restrict__ block,
+                                                          AcceptSeqs sq, const int32_t* __restrict__ path_tok,
                                                           const int32_t* __restrict__ path_len, int32_t eos_id,
                                                           int32_t* __restrict__ n_accept,
                                                           int32_t* __restrict__ next_token,
@@ -427,7 +442,8 @@ __global__ __launch_bounds__(256) void accept_tiles_kernel(int rows, int rows_pa
         ev = sv[w];
         eid = si[w];
       }
-    argmax_out[r] = eid;
+    const int o = accept_out_index(sq, r);
+    if (o >= 0) argmax_out[o] = eid;
     __hip_atomic_store(&am[r], eid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __threadfence();  // the row's result is visible device-wide before the arrival is counted
     const uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
@@ -442,23 +458,7 @@ __global__ __launch_bounds__(256) void accept_tiles_kernel(int rows, int rows_pa
   __syncthreads();
   if (threadIdx.x == 0) {
     __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    int m = rows - 1;
-    if (path_len) {
-      int pl = *path_len;
-      m = pl < m ? (pl < 0 ? 0 : pl) : m;
-    }
-    int n = 0;
-    bool eos = false;
-    while (n < m && ams[n] == block[n + 1]) {
-      eos |= (eos_id >= 0 && block[n + 1] == eos_id);
-      ++n;
-    }
-    const int nxt = ams[n];
-    eos |= (eos_id >= 0 && nxt == eos_id);
-    *n_accept = n;
-    *next_token = nxt;
-    __threadfence_system();  // eos_accepted last: a host polling it in device-visible memory then sees all three
-    *eos_accepted = eos ? 1 : 0;
+    write_verdicts(sq, ams, path_tok, path_len, eos_id, n_accept, next_token, eos_accepted);
   }
 }
 
@@ -773,7 +773,7 @@ int launch_lattice(const float* logits, int rows, int vocab, int m_max, float ta
 
 size_t accept_ws_bytes(int rows, int vocab) { return lattice_ws_bytes(rows, vocab, 1); }
 
-int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t* block,
+int launch_argmax_accept(const float* logits, int rows, int vocab, const AcceptSeqs& sq, const int32_t* path_tok,
                          const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
                          int32_t* argmax, int32_t* eos_accepted, void* ws, size_t ws_bytes, hipStream_t st) {
   DS_REQUIRE(ws_bytes >= accept_ws_bytes(rows, vocab), DS_E_CAPACITY,
@@ -785,7 +785,7 @@ int launch_argmax_accept(const float* logits, int rows, int vocab, const int32_t
   hipLaunchKernelGGL(scan_rows_kernel<false>, dim3(p.n_seg, rows), dim3(kScanThreads), 0, st, logits, vocab, 1,
                      p.tiles_per_seg, partial);
   DS_LAUNCH_CHECK("scan_rows_kernel<argmax>");
-  hipLaunchKernelGGL(accept_merge_kernel, dim3(1), dim3(1024), 0, st, rows, p.n_part, partial, block, path_len,
+  hipLaunchKernelGGL(accept_merge_kernel, dim3(1), dim3(1024), 0, st, rows, p.n_part, partial, sq, path_tok, path_len,
                      eos_id, n_accept, next_token, argmax, eos_accepted);
   DS_LAUNCH_CHECK("accept_merge_kernel");
   return DS_OK;
@@ -820,7 +820,7 @@ int launch_lattice_tiles(const void* rec, int rows, int n_tiles, int m_max, floa
   return DS_OK;
 }
 
-int launch_tiles_accept(float2* tile_best, int rows, int n_tiles, const int32_t* block,
+int launch_tiles_accept(float2* tile_best, int rows, int n_tiles, const AcceptSeqs& sq, const int32_t* path_tok,
                         const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
                         int32_t* argmax, int32_t* eos_accepted, hipStream_t st) {
   DS_REQUIRE(rows >= 1 && rows <= DS_MAX_ROWS, DS_E_SHAPE, "acceptance rows %d outside [1, %d]", rows,
@@ -831,7 +831,7 @@ int launch_tiles_accept(float2* tile_best, int rows, int n_tiles, const int32_t*
   uint32_t* counter = reinterpret_cast<uint32_t*>(tile_best + (size_t)n_tiles * rows_pad);
   int32_t* am = reinterpret_cast<int32_t*>(counter + 64);
   hipLaunchKernelGGL(accept_tiles_kernel, dim3(rows), dim3(256), 0, st, rows, rows_pad, n_tiles, tile_best, counter,
-                     am, block, path_len, eos_id, n_accept, next_token, argmax, eos_accepted);
+                     am, sq, path_tok, path_len, eos_id, n_accept, next_token, argmax, eos_accepted);
   DS_LAUNCH_CHECK("accept_tiles_kernel");
   return DS_OK;
 }

@@ -59,9 +59,23 @@ class DeviceModel:
         self.torch_dtype = torch.bfloat16 if bf else torch.float32
 
     def close(self) -> None:
+        for kv, _, _ in getattr(self, "sequences", []):
+            ds.ds_kv_destroy(kv)
+        self.sequences = []
         if self.handle:
             ds.ds_model_destroy(self.handle)
             self.handle = None
+
+    def new_sequence(self) -> int:
+        """One more sequence's KV cache of this model (for the batched calls); returns its ds_kv handle."""
+        kvb = ds.ds_kv_bytes(self.cfgc)
+        k = torch.zeros(kvb, dtype=torch.uint8, device=DEV)
+        v = torch.zeros(kvb, dtype=torch.uint8, device=DEV)
+        kv = ds.ds_kv_create(self.handle, k, v)
+        if not hasattr(self, "sequences"):
+            self.sequences = []
+        self.sequences.append((kv, k, v))
+        return kv
 
     @property
     def kv_len(self) -> int:
@@ -316,6 +330,141 @@ class SpecDecoder:
         k_next = ds.ds_adl_update(self.adl, k, first_eos, n_acc)
         return {"k": k, "path": path, "path_len": plen, "n_accept": n_acc, "next_token": nxt, "eos_accepted": eos,
                 "committed": committed, "first_eos": first_eos, "k_next": k_next}
+
+
+class BatchSpecDecoder:
+    """n_seq independent sequences driven through the batched calls: every round is one drafter pass, one LM head +
+    lattice, one path search and one verifier pass for all of them (one stream of each model's weights), with the
+    same draft length K.  Bookkeeping only, as in SpecDecoder; each sequence has its own draft-length controller,
+    whose proposals are reported and left to the caller (the batch shares one K)."""
+
+    def __init__(self, drafter: DeviceModel, verifier: DeviceModel, n_seq: int, table: Optional[np.ndarray],
+                 log2_size: int, params: RoundParams, k_cap: int = 32, keep_logits: bool = False):
+        if not 1 <= n_seq <= ds.DS_MAX_SEQ:
+            raise ValueError(f"n_seq {n_seq} outside [1, {ds.DS_MAX_SEQ}]")
+        if params.refine_steps != 1:
+            raise ValueError("the batched round is the single-pass round")
+        self.d, self.v, self.p, self.n, self.k_cap = drafter, verifier, params, n_seq, k_cap
+        self.eos_id, self.mask_id = drafter.cfg.eos_id, drafter.cfg.mask_id
+        self.d_kv = [drafter.new_sequence() for _ in range(n_seq)]
+        self.v_kv = [verifier.new_sequence() for _ in range(n_seq)]
+        self.table = upload(table) if table is not None else None
+        self.proxy = ds.ds_ngram_create(self.table, log2_size) if table is not None else None
+        self.adl = [ds.ds_adl_create(params.k_min, params.k_max, params.delta, params.rho) for _ in range(n_seq)]
+        m, i32, f32 = params.m_max, torch.int32, torch.float32
+        rows = n_seq * k_cap
+        self.hidden = torch.empty(rows, drafter.cfg.d_model, dtype=f32, device=DEV)
+        self.cand_id = torch.empty(rows, m, dtype=i32, device=DEV)
+        self.cand_logp = torch.empty(rows, m, dtype=f32, device=DEV)
+        self.cand_cnt = torch.empty(rows, dtype=i32, device=DEV)
+        self.eos_logp = torch.empty(rows, dtype=f32, device=DEV)
+        self.lse = torch.empty(rows, dtype=f32, device=DEV)
+        self.cps_ws = torch.empty(ds.ds_cps_workspace_bytes(n_seq, k_cap, m), dtype=torch.uint8, device=DEV)
+        # host -> device per round: [pending of all sequences | ctx [n, 2] | first [n]]; device -> host: path, path_len, cand ids
+        self.n_in = ds.DS_MAX_ROWS + 3 * n_seq
+        self.inp = torch.zeros(self.n_in, dtype=i32, device=DEV)
+        self.inp_host = torch.zeros(self.n_in, dtype=i32).pin_memory()
+        self.ctx = self.inp[ds.DS_MAX_ROWS:ds.DS_MAX_ROWS + 2 * n_seq]
+        self.first = self.inp[ds.DS_MAX_ROWS + 2 * n_seq:]
+        self.path = torch.zeros(n_seq * k_cap, dtype=i32, device=DEV)
+        self.path_len = torch.zeros(n_seq, dtype=i32, device=DEV)
+        self.path_score = torch.zeros(n_seq, dtype=f32, device=DEV)
+        self.argmax = torch.zeros(n_seq * (k_cap + 1), dtype=i32, device=DEV)
+        self.result = torch.zeros(3 * n_seq, dtype=i32).pin_memory()   # n_accept [n] | next_token [n] | eos_accepted [n]
+        self.result_np = self.result.numpy()
+        self.d_logits = self.v_logits = None
+        if keep_logits:
+            self.d_logits = torch.empty(rows, drafter.cfg.vocab, dtype=f32, device=DEV)
+            self.v_logits = torch.empty(ds.DS_MAX_ROWS, verifier.cfg.vocab, dtype=f32, device=DEV)
+        self.tokens: List[List[int]] = [[] for _ in range(n_seq)]
+        self.pending: List[List[int]] = [[] for _ in range(n_seq)]
+
+    def close(self) -> None:
+        if self.proxy:
+            ds.ds_ngram_destroy(self.proxy)
+            self.proxy = None
+        for a in self.adl:
+            ds.ds_adl_destroy(a)
+        self.adl = []
+
+    def start(self, prefixes) -> None:
+        """Prefill every sequence's two caches with its prefix; the verifier's greedy token after it becomes pending."""
+        vocab = self.v.cfg.vocab
+        last = torch.empty(vocab, dtype=torch.float32, device=DEV)
+        cid = torch.empty(1, 1, dtype=torch.int32, device=DEV)
+        tmp_f = torch.empty(3, dtype=torch.float32, device=DEV)
+        tmp_i = torch.empty(1, dtype=torch.int32, device=DEV)
+        ws = torch.empty(ds.ds_lattice_workspace_bytes(1, vocab, 1), dtype=torch.uint8, device=DEV)
+        for s, prefix in enumerate(prefixes):
+            t = upload(np.asarray(prefix, dtype=np.int32))
+            ds.ds_kv_set_len(self.d_kv[s], 0)
+            ds.ds_kv_set_len(self.v_kv[s], 0)
+            ds.ds_prefill_seq(self.d.handle, self.d_kv[s], t, len(prefix), None, self.d.ws)
+            ds.ds_prefill_seq(self.v.handle, self.v_kv[s], t, len(prefix), last, self.v.ws)
+            ds.ds_build_lattice(last, 1, vocab, 1, 1.0, -1, cid, tmp_f[0:1], tmp_i, tmp_f[1:2], tmp_f[2:3], ws)
+            torch.cuda.synchronize()
+            first = int(cid.item())
+            self.tokens[s] = [int(x) for x in prefix] + [first]
+            self.pending[s] = [first]
+
+    _PENDING = -0x7EADBEEF
+
+    def round(self, k: int) -> list:
+        """One round of every sequence with draft length k; returns one record per sequence."""
+        n, p = self.n, self.p
+        if not 1 <= k <= self.k_cap:
+            raise ValueError(f"draft length {k} outside [1, k_cap = {self.k_cap}]")
+        n_pend = [len(q) for q in self.pending]
+        h = self.inp_host.numpy()
+        flat = [t for q in self.pending for t in q]
+        if len(flat) > ds.DS_MAX_ROWS:
+            raise ValueError("too many pending tokens")
+        h[:len(flat)] = flat
+        base = ds.DS_MAX_ROWS
+        for s in range(n):
+            h[base + 2 * s] = self.tokens[s][-2]
+            h[base + 2 * s + 1] = self.tokens[s][-1]
+            h[base + 2 * n + s] = self.tokens[s][-1]
+        self.inp.copy_(self.inp_host, non_blocking=True)
+        v_len = [ds.ds_kv_len(kv) for kv in self.v_kv]
+        self.result_np[2 * n:] = self._PENDING
+        rows = n * k
+        lat = (self.cand_id, self.cand_logp, self.cand_cnt, self.eos_logp, self.lse)
+        ds.ds_draft_block_batch(self.d.handle, self.d_kv, self.inp, n_pend, k, self.mask_id, self.hidden, self.d.ws)
+        ds.ds_draft_lattice(self.d.handle, None, rows, p.m_max, p.tau, self.eos_id, *lat, self.d_logits, self.d.ws)
+        ds.ds_cps_path(lat[0], lat[1], lat[2], lat[3], n, k, p.m_max, p.beam, p.lam, self.proxy, self.ctx, self.eos_id,
+                       self.path, self.path_len, self.path_score, self.cps_ws)
+        path_h = torch.empty(n * k, dtype=torch.int32).pin_memory()
+        plen_h = torch.empty(n, dtype=torch.int32).pin_memory()
+        raw_h = torch.empty(rows, dtype=torch.int32).pin_memory()
+        path_h.copy_(self.path[:n * k], non_blocking=True)
+        plen_h.copy_(self.path_len, non_blocking=True)
+        raw_h.copy_(self.cand_id[:rows, 0], non_blocking=True)
+        ds.ds_verify_block_batch(self.v.handle, self.v_kv, self.first, self.path, k, self.path_len, self.eos_id,
+                                 self.result[0:n], self.result[n:2 * n], self.argmax, self.result[2 * n:3 * n],
+                                 self.v_logits, self.v.ws)
+        res, spins = self.result_np, 0
+        while np.any(res[2 * n:] == self._PENDING):   # the round's host crossing: poll the pinned verdicts
+            spins += 1
+            if (spins & 0xFFFF) == 0:
+                torch.cuda.current_stream().synchronize()
+                if np.any(res[2 * n:] == self._PENDING):
+                    raise RuntimeError("no verdict from the acceptance kernel")
+        torch.cuda.current_stream().synchronize()     # the small read-back copies were issued before the verifier pass
+        out = []
+        paths, plens, raw = path_h.numpy().reshape(n, k), plen_h.numpy(), raw_h.numpy().reshape(n, k)
+        for s in range(n):
+            n_acc, nxt, eos, plen = int(res[s]), int(res[n + s]), int(res[2 * n + s]), int(plens[s])
+            path = paths[s, :plen].copy()
+            ds.ds_kv_set_len(self.v_kv[s], v_len[s] + 1 + n_acc)
+            committed = [int(t) for t in path[:n_acc]] + [nxt]
+            self.tokens[s] += committed
+            self.pending[s] = committed
+            first_eos = ds.ds_adl_first_eos(np.ascontiguousarray(raw[s]), k, 1, self.eos_id)
+            k_next = ds.ds_adl_update(self.adl[s], k, first_eos, n_acc)
+            out.append({"k": k, "path": path, "path_len": plen, "n_accept": n_acc, "next_token": nxt,
+                        "eos_accepted": eos, "committed": committed, "first_eos": first_eos, "k_next": k_next})
+        return out
 
 
 def ar_greedy(model: DeviceModel, prefix: np.ndarray, n_new: int, timing: Optional[dict] = None) -> List[int]:
