@@ -676,6 +676,34 @@ def main() -> int:
     out["variants"] = variants
     dec.close()
 
+    # Batched rounds: n_seq independent sequences (own prefixes, own caches) share every weight stream of the round.
+    # Rows per sequence are 1 pending + K; K = 31 at four sequences keeps 4 x 32 rows inside one call (144 rows).
+    batched = {}
+    for n_seq, kb in ((2, 32), (4, 31)):
+        bdec = rnd.BatchSpecDecoder(dm, vm, n_seq, table, synth.NGRAM_LOG2_SIZE,
+                                    rnd.RoundParams(m_max=M_MAX, beam=BEAM, lam=LAM, k_max=32), k_cap=32)
+        bdec.start([synth.make_prefix(cfg, PREFIX, 40 + s) for s in range(n_seq)])
+        for _ in range(5):
+            bdec.round(kb)
+        torch.cuda.synchronize()
+        b0 = time.perf_counter()
+        n_rounds_b, n_tok_b = 40, 0
+        for _ in range(n_rounds_b):
+            for rec in bdec.round(kb):
+                n_tok_b += rec["n_accept"] + 1
+        torch.cuda.synchronize()
+        b_el = time.perf_counter() - b0
+        batched[f"n_seq={n_seq}"] = {"K": kb, "rows_per_call": (n_seq - 1) * ((1 + kb + 15) // 16 * 16) + 1 + kb,
+                                     "ms_per_round": round(b_el * 1e3 / n_rounds_b, 4),
+                                     "rounds_per_s": round(n_rounds_b / b_el, 1),
+                                     "sequence_rounds_per_s": round(n_seq * n_rounds_b / b_el, 1),
+                                     "committed_tokens_per_s": round(n_tok_b / b_el, 1),
+                                     "vs_one_sequence": round(n_seq * n_rounds_b / b_el / rounds_per_s, 3)}
+        bdec.close()
+    batched["note"] = ("every round drafts, searches and verifies all sequences with one pass over each model's weights; "
+                       "natural acceptance (one committed token per sequence and round)")
+    out["batched_rounds"] = batched
+
     out["cpu_baseline"] = None
     legs = {}
     if with_cpu:

@@ -372,6 +372,9 @@ class BatchSpecDecoder:
         self.argmax = torch.zeros(n_seq * (k_cap + 1), dtype=i32, device=DEV)
         self.result = torch.zeros(3 * n_seq, dtype=i32).pin_memory()   # n_accept [n] | next_token [n] | eos_accepted [n]
         self.result_np = self.result.numpy()
+        self.path_h = torch.empty(n_seq * k_cap, dtype=i32).pin_memory()
+        self.plen_h = torch.empty(n_seq, dtype=i32).pin_memory()
+        self.raw_h = torch.empty(rows, dtype=i32).pin_memory()
         self.d_logits = self.v_logits = None
         if keep_logits:
             self.d_logits = torch.empty(rows, drafter.cfg.vocab, dtype=f32, device=DEV)
@@ -434,9 +437,7 @@ class BatchSpecDecoder:
         ds.ds_draft_lattice(self.d.handle, None, rows, p.m_max, p.tau, self.eos_id, *lat, self.d_logits, self.d.ws)
         ds.ds_cps_path(lat[0], lat[1], lat[2], lat[3], n, k, p.m_max, p.beam, p.lam, self.proxy, self.ctx, self.eos_id,
                        self.path, self.path_len, self.path_score, self.cps_ws)
-        path_h = torch.empty(n * k, dtype=torch.int32).pin_memory()
-        plen_h = torch.empty(n, dtype=torch.int32).pin_memory()
-        raw_h = torch.empty(rows, dtype=torch.int32).pin_memory()
+        path_h, plen_h, raw_h = self.path_h[:n * k], self.plen_h, self.raw_h[:rows]
         path_h.copy_(self.path[:n * k], non_blocking=True)
         plen_h.copy_(self.path_len, non_blocking=True)
         raw_h.copy_(self.cand_id[:rows, 0], non_blocking=True)
