@@ -122,7 +122,7 @@ template <typename T>
 int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* dst, uint32_t* ovf, hipStream_t st);
 template <typename T>
 int launch_qkv_rope(const SeqTable& tab, const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv,
-                    int hd, const float2* cs, int cap, void* q, uint32_t* ovf, hipStream_t st);
+                    int hd, const float2* cs, int cap, float q_scale, void* q, uint32_t* ovf, hipStream_t st);
 template <typename T>
 int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, uint32_t* ovf,
                   hipStream_t st);
@@ -160,6 +160,7 @@ struct AttnPlan {
   int n_split, chunks_per_split;
 };
 AttnPlan attn_plan(int dtype, int cap, int n_keys);
+float attn_q_scale(int dtype, int hd);  // factor the producer of q folds into the queries
 int attn_partial_rows(int rows_pad);
 int launch_attention(int dtype, const SeqTable& tab, const void* q, int rows, int rows_pad, int n_q, int n_kv, int hd,
                      int cap, float* part_o, float* part_ml, void* att_out, uint32_t* ovf, hipStream_t st);

@@ -302,7 +302,8 @@ int forward_rows(ds_model* m, const Workspace& w, const FwdCall& call, const Seq
     }
     int sp = 1;
     if ((rc = gemm<T>(m, li, 0, w.h, rows, w.gemm_out, &sp, st))) return rc;
-    if ((rc = launch_qkv_rope<T>(lt, w.gemm_out, sp, rows, rp, c.n_q, c.n_kv, hd, w.cs, c.kv_capacity, w.q, m->ovf, st)))
+    if ((rc = launch_qkv_rope<T>(lt, w.gemm_out, sp, rows, rp, c.n_q, c.n_kv, hd, w.cs, c.kv_capacity,
+                                 attn_q_scale(c.dtype, hd), w.q, m->ovf, st)))
       return rc;
     if ((rc = launch_attention(c.dtype, lt, w.q, rows, rp, c.n_q, c.n_kv, hd, c.kv_capacity, w.att_o, w.att_ml, w.att,
                                m->ovf, st)))

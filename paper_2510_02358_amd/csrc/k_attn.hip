@@ -5,8 +5,9 @@
 //   r >= n_causal (a [MASK] row of the draft block: sees everything)  or  p <= pos0 + r (causal).
 //
 // Half-precision kernel (bf16 models, head_dim 128; q, K, V and probabilities are IEEE half): the
-// query rows of all heads that share a KV head are packed together, so one pass over that head's
-// keys/values serves group x rows query rows; both products run on the 16x16x32 f16 matrix cores.
+// query rows of all heads that share a KV head are packed densely into blocks of 16 (row v = head-in-group x
+// rows + row; a block may span two heads), so one pass over that head's keys/values serves group x rows
+// query rows with no padding between heads; both products run on the 16x16x32 f16 matrix cores.
 // Scores are computed transposed, S^T = K Q^T, because the accumulator layout of S^T (lane = query
 // row, 4 consecutive keys per register quad) is already the operand layout the second product P V
 // needs: probabilities never leave registers.
@@ -14,12 +15,13 @@
 // Cache layout (private to the library): per KV head the cache is a sequence of 64-key chunks, and a
 // chunk of K (and of V) is stored as the 16 matrix-core operand tiles the kernel multiplies with
 // (kv_k_offset / kv_v_offset in ds_act.h).  Staging a chunk is therefore a straight, fully coalesced
-// 16 KB + 16 KB copy into LDS; two LDS buffers alternate, so the copy of chunk c + 1 (global ->
-// registers before the math, registers -> LDS after it) overlaps the math of chunk c with one barrier
-// per chunk.
+// 16 KB + 16 KB copy, issued as global -> LDS loads that pass through no registers; two LDS buffers
+// alternate, so the copy of chunk c + 1 runs under the math of chunk c with one barrier per chunk.
 //
 // f32 kernel: plain ALU version for the float32 parity mode (any head_dim <= 128, row-major cache).
 #include <math.h>
+
+#include <type_traits>
 
 #include "ds_act.h"
 #include "ds_common.h"
@@ -30,6 +32,8 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -40,181 +44,324 @@ constexpr int kChunkElems = kChunk * kHd;  // halfs per chunk of K (and of V): 1
 union Pack8 {
   f16x8 v;
   uint16_t h[8];
+  uint32_t w[4];
   u32x2 half[2];
   u32x4 q;
 };
 
+// xor-reduction of a maximum over the four 16-lane rows of a wavefront (the lanes that hold one query row), with the
+// row-swap instructions of the vector unit: no trip through the LDS crossbar.
+__device__ __forceinline__ float max_over_lane_rows(float x) {
+  // Written as assembly: through the compiler's builtins the maximum of a swap's two results is folded to the first
+  // result, which drops the exchange.  The no-op covers the wait states a swap needs after a vector write of its
+  // operands.
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));  // a = [lo, lo], b = [hi, hi] halves
+  const float y = fmaxf(a, b);
+  float c = y, d = y;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(c), "+v"(d));  // even rows and odd rows
+  return fmaxf(c, d);
+}
+
+// Scores arrive in log2 units (the queries are stored pre-multiplied by log2(e) / sqrt(head_dim)) and relative to a
+// per-row reference m_ref: the score accumulators start at -m_ref instead of zero, so a probability is one exp2 of
+// the accumulator, p = 2^(s - m_ref), with no further arithmetic per score.  m_ref follows the running maximum
+// lazily: it moves only when a chunk's maximum exceeds it by more than kRefSlack (then o and l are rescaled), so
+// p <= 2^kRefSlack, far inside the half range.  Row sums l come from the matrix core too (a product of P with an
+// all-ones tile), summed from the same half-precision probabilities that weight V.
+constexpr float kRefSlack = 8.0f;
+
+// Matrix work of a chunk: o += V^T P and l += 1^T P for the probabilities in pb (has_pv), or s4 = K Q^T - m_ref
+// (has_qk).  LDS reads run four tiles ahead of the products that consume them (the scheduling barriers pin that
+// order), so the matrix core does not wait for every read.
+template <int QB, bool has_pv, bool has_qk>
+__device__ __forceinline__ void attn_matrix_phase(const uint16_t* __restrict__ vs, const uint16_t* __restrict__ ks,
+                                                  int lane, const f16x8 (&bq)[QB][4],
+                                                  const Pack8 (&pb)[QB][2], const f32x4 (&neg_m)[QB], f32x4 (&o)[QB][8],
+                                                  f32x4 (&l_acc)[QB], f32x4 (&s4)[QB][4]) {
+  constexpr int kAhead = 4;
+  if (has_pv) {  // V tiles in the order (key half t2, column block d)
+    f16x8 b[16];
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i)
+      b[i] = *reinterpret_cast<const f16x8*>(&vs[(((i & 7) * 2 + (i >> 3)) * 64 + lane) * 8]);
+    Pack8 ones;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) ones.w[e] = 0x3C003C00u;
+#pragma unroll
+    for (int t = 0; t < QB; ++t)
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+        l_acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones.v, pb[t][t2].v, l_acc[t], 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+#pragma unroll
+      for (int t = 0; t < QB; ++t)
+        o[t][i & 7] = __builtin_amdgcn_mfma_f32_16x16x32_f16(b[i], pb[t][i >> 3].v, o[t][i & 7], 0, 0, 0);
+      if (i + kAhead < 16) {
+        const int n = i + kAhead;
+        b[n] = *reinterpret_cast<const f16x8*>(&vs[(((n & 7) * 2 + (n >> 3)) * 64 + lane) * 8]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  if (has_qk) {  // K tiles in the order (column step s, key block kb): consecutive products go to different accumulators
+    f16x8 a[16];
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i)
+      a[i] = *reinterpret_cast<const f16x8*>(&ks[(((i & 3) * 4 + (i >> 2)) * 64 + lane) * 8]);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+#pragma unroll
+      for (int t = 0; t < QB; ++t)
+        s4[t][i & 3] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], bq[t][i >> 2], i < 4 ? neg_m[t] : s4[t][i & 3], 0, 0, 0);
+      if (i + kAhead < 16) {
+        const int n = i + kAhead;
+        a[n] = *reinterpret_cast<const f16x8*>(&ks[(((n & 3) * 4 + (n >> 2)) * 64 + lane) * 8]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+// Softmax phase of the chunk starting at key c0: s4[t][kb][e] = score - m_ref of key c0 + 16 kb + 4 g + e for query
+// row 16 rb + j.  Leaves the probabilities in pb (half, the P V operand).  Every decision is taken per row from that
+// row's own values (the wavefront-wide test only skips work that would change nothing), so a row's result does not
+// depend on which other rows share its wavefront.
 template <int QB>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_f16_kernel(const uint16_t* __restrict__ q,
-                                                        const uint16_t* __restrict__ kc,
-                                                        const uint16_t* __restrict__ vc, int rows, int rows_pad,
-                                                        int rows_stride, int n_causal, int pos0, int n_keys, int n_q,
-                                                        int n_kv, int cap, int chunks_per_split, float scale_log2,
-                                                        float* __restrict__ part_o, float* __restrict__ part_ml) {
-  // rows / rows_pad: the rows of ONE sequence (q, part_o and part_ml already point at its first row);
+__device__ __forceinline__ void attn_softmax_phase(int g, int c0, const int (&lim_min)[QB], const int (&limit)[QB],
+                                                   f32x4 (&s4)[QB][4], Pack8 (&pb)[QB][2], f32x4 (&o)[QB][8],
+                                                   f32x4 (&l_acc)[QB], float (&m_ref)[QB], f32x4 (&neg_m)[QB]) {
+#pragma unroll
+  for (int t = 0; t < QB; ++t) {
+    if (c0 + kChunk - 1 > lim_min[t]) {  // same for the whole wavefront: only the last chunks of a row block mask
+      const int rel = limit[t] - c0 - 4 * g;
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (kb * 16 + e > rel) s4[t][kb][e] = -INFINITY;
+    }
+    float mx = fmaxf(s4[t][0][0], s4[t][0][1]);
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int e = (kb == 0 ? 2 : 0); e < 4; e += 2) mx = fmaxf(fmaxf(mx, s4[t][kb][e]), s4[t][kb][e + 1]);
+    mx = max_over_lane_rows(mx);  // the chunk's maximum for this lane's query row, relative to m_ref
+    const bool first = m_ref[t] == -INFINITY;  // nothing seen yet: the accumulators started at zero
+    const float delta = first ? (mx == -INFINITY ? 0.f : mx) : (mx > kRefSlack ? mx : 0.f);
+    if (__builtin_amdgcn_ballot_w64(delta != 0.f)) {  // some row of the wavefront moves its reference
+      // The rare path updates its registers in place (assembly with tied operands): written as ordinary code, the
+      // compiler gives the two sides of this branch different registers and copies all of o on the common side.
+      const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta);
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) asm volatile("v_sub_f32 %0, %0, %1" : "+v"(s4[t][kb][e]) : "v"(delta));
+#pragma unroll
+      for (int d = 0; d < 8; ++d)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(o[t][d][e]) : "v"(alpha));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(l_acc[t][e]) : "v"(alpha));
+      m_ref[t] = first ? (mx == -INFINITY ? -INFINITY : mx) : m_ref[t] + delta;
+      const float nm = (m_ref[t] == -INFINITY) ? 0.f : -m_ref[t];
+      neg_m[t] = f32x4{nm, nm, nm, nm};
+    }
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int e = 0; e < 4; e += 2) {
+        const f32x2 pp = {__builtin_amdgcn_exp2f(s4[t][kb][e]), __builtin_amdgcn_exp2f(s4[t][kb][e + 1])};
+        pb[t][kb >> 1].w[((kb & 1) * 4 + e) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, f16x2));
+      }
+  }
+  // The exponentials belong to this phase (the vector unit's turn): passing the packed probabilities through an
+  // empty asm statement makes them exist here; otherwise the compiler sinks them behind the barrier, next to the
+  // products that use them.
+#pragma unroll
+  for (int t = 0; t < QB; ++t)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(pb[t][h].w[k]));
+}
+
+// Barrier that closes a chunk: LDS traffic of this wavefront is complete (the tail patch writes LDS), then the
+// workgroup barrier.  Unlike __syncthreads() it carries no wait for memory operations the compiler knows of.
+__device__ __forceinline__ void phase_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+constexpr int kAttnThreads = 256;  // four wavefronts; two workgroups share a CU (64 KB of LDS each)
+constexpr int kAttnQB = 2;         // query blocks of 16 rows per wavefront
+
+// The chunk loop of one wavefront with NB live query blocks (NB = 0: a wavefront without query rows only copies and
+// keeps the barriers).  i = chunk index within the split; chunk i uses LDS buffer i & 1.
+template <int NB>
+struct AttnWave {
+  f16x8 bq[NB ? NB : 1][4];
+  f32x4 o[NB ? NB : 1][8], s4[NB ? NB : 1][4], l_acc[NB ? NB : 1], neg_m[NB ? NB : 1];
+  Pack8 pb[NB ? NB : 1][2];
+  float m_ref[NB ? NB : 1];  // reference of the row's exponentials, log2 units (-inf until the row has seen a key)
+  int lim_min[NB ? NB : 1], limit[NB ? NB : 1];
+};
+
+template <int QB>
+__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2))) void attn_f16_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, int rows,
+    int rows_stride, int n_causal, int pos0, int n_keys, int n_q, int n_kv, int cap, int chunks_per_split,
+    float* __restrict__ part_o, float* __restrict__ part_ml) {
+  // q: queries in log2 units (attn_q_scale folded in by the producer), per head [rows_stride rows] in tile order
+  // rows: the rows of ONE sequence (q, part_o and part_ml already point at its first row, a multiple of 16);
   // rows_stride: padded rows of the whole call (stride between heads and between splits)
-  __shared__ __attribute__((aligned(16))) uint16_t ks_lds[2][kChunkElems];
-  __shared__ __attribute__((aligned(16))) uint16_t vs_lds[2][kChunkElems];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __shared__ __attribute__((aligned(16))) uint16_t k_lds[2 * kChunkElems];
+  __shared__ __attribute__((aligned(16))) uint16_t v_lds[2 * kChunkElems];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane & 15, g = lane >> 4;
   const int split = blockIdx.x, kvh = blockIdx.y;
-  const int group = n_q / n_kv, rb_count = rows_pad >> 4, n_qb = group * rb_count;
+  const int group = n_q / n_kv, n_vrows = group * rows, n_qb = (n_vrows + 15) >> 4;
   const int n_chunks = (n_keys + kChunk - 1) / kChunk;
   const int c_begin = split * chunks_per_split;
   int c_end = c_begin + chunks_per_split;
   if (c_end > n_chunks) c_end = n_chunks;
+  const int n = c_end > c_begin ? c_end - c_begin : 0;  // chunks of this split (same for the whole workgroup)
+  const int qb0 = (blockIdx.z * 4 + wave) * QB;         // first query block of this wavefront
+  const int nb = n_qb - qb0 >= QB ? QB : (n_qb > qb0 ? n_qb - qb0 : 0);  // its live blocks (a scalar)
 
-  int head[QB], rb[QB], lim_min[QB], limit[QB];
-  bool valid[QB];
-  f16x8 bq[QB][4];
-  f32x4 o[QB][8];
-  float m_run[QB], l_run[QB];  // running maximum in log2 units, running sum
-#pragma unroll
-  for (int t = 0; t < QB; ++t) {
-    const int qb = (blockIdx.z * 4 + wave) * QB + t;
-    valid[t] = qb < n_qb;
-    const int qbc = valid[t] ? qb : 0;
-    head[t] = kvh * group + qbc / rb_count;
-    rb[t] = qbc % rb_count;
-    const uint16_t* qh = q + (size_t)head[t] * rows_stride * kHd + (size_t)rb[t] * 4 * 512;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) bq[t][s] = *reinterpret_cast<const f16x8*>(qh + s * 512 + lane * 8);
-#pragma unroll
-    for (int d = 0; d < 8; ++d) o[t][d] = f32x4{0.f, 0.f, 0.f, 0.f};
-    m_run[t] = -INFINITY;
-    l_run[t] = 0.f;
-    const int r = rb[t] * 16 + j;
-    limit[t] = (r >= n_causal) ? n_keys - 1 : pos0 + r;                       // last key this lane's row sees
-    lim_min[t] = (rb[t] * 16 >= n_causal) ? n_keys - 1 : pos0 + rb[t] * 16;   // smallest limit in the row block
-  }
+  const uint16_t* kbase = kc + ((size_t)kvh * cap + (size_t)c_begin * kChunk) * kHd;
+  const uint16_t* vbase = vc + ((size_t)kvh * cap + (size_t)c_begin * kChunk) * kHd;
+  const uint32_t k_lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)k_lds;
+  const uint32_t v_lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)v_lds;
 
-  const uint16_t* kbase = kc + (size_t)kvh * cap * kHd;
-  const uint16_t* vbase = vc + (size_t)kvh * cap * kHd;
-
-  // Staging: a chunk is 2 x 1024 pieces of 16 bytes, already in operand order; thread t moves pieces
-  // t, t + 256, t + 512, t + 768 of K and of V.
-  u32x4 kreg[4], vreg[4];
-  auto load_chunk = [&](int c) {
-    const uint16_t* ksrc = kbase + (size_t)c * kChunkElems + threadIdx.x * 8;
-    const uint16_t* vsrc = vbase + (size_t)c * kChunkElems + threadIdx.x * 8;
+  // Staging: a chunk is 2 x 1024 pieces of 16 bytes, already in operand order.  Each wavefront copies pieces
+  // [64 wave + 256 p, + 64) of K and of V, p = 0..3, straight from global memory into LDS (16 bytes per lane, the
+  // lanes of a wavefront land side by side from the wavefront's base address, which M0 carries).  Written as
+  // assembly so that the compiler's wait-count bookkeeping does not put a wait for the copies in front of the LDS
+  // reads of the chunk being computed (it cannot tell the two buffers apart); the wait that matters is explicit
+  // (finish_chunk).  Nothing else in this kernel uses M0.
+  auto issue_chunk = [&](int i) {
+    const size_t off = (size_t)i * kChunkElems + threadIdx.x * 8;
+    const uint32_t buf = (uint32_t)((i & 1) * kChunkElems * 2);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      kreg[p] = *reinterpret_cast<const u32x4*>(ksrc + p * 2048);
-      vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + p * 2048);
+      const uint32_t dst = buf + (uint32_t)(wave * 64 + p * 256) * 16u;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(k_lds_addr + dst),
+                   "v"(kbase + off + p * 2048)
+                   : "memory");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(v_lds_addr + dst),
+                   "v"(vbase + off + p * 2048)
+                   : "memory");
     }
   };
-  auto store_chunk = [&](int c, int buf) {
-    const int c0 = c * kChunk;
+  // After this wavefront's copies of chunk i have landed (and before the barrier that publishes them): in the tail
+  // chunk the V slots past the last key may hold anything -> zero, so that probability 0 times that slot is 0.
+  // Every thread patches the pieces its own lane copied.
+  auto finish_chunk = [&](int i) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    const int c0 = (c_begin + i) * kChunk;
+    if (c0 + kChunk > n_keys) {
+      uint16_t* vd = v_lds + (i & 1) * kChunkElems;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      *reinterpret_cast<u32x4*>(&ks_lds[buf][(threadIdx.x + p * 256) * 8]) = kreg[p];
-      Pack8 pk;
-      pk.q = vreg[p];
-      if (c0 + kChunk > n_keys) {  // tail chunk: slots past the last key may hold anything -> zero
+      for (int p = 0; p < 4; ++p) {
+        Pack8 pk;
+        pk.q = *reinterpret_cast<const u32x4*>(&vd[(threadIdx.x + p * 256) * 8]);
         const int t2 = (wave + 4 * p) & 1;  // tile index of this piece = wave + 4 p (V tile = db * 2 + t2)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int key = c0 + 32 * t2 + 4 * g + (e & 3) + ((e >> 2) << 4);
           if (key >= n_keys) pk.h[e] = 0;
         }
+        *reinterpret_cast<u32x4*>(&vd[(threadIdx.x + p * 256) * 8]) = pk.q;
       }
-      *reinterpret_cast<u32x4*>(&vs_lds[buf][(threadIdx.x + p * 256) * 8]) = pk.q;
     }
   };
 
-  if (c_begin < c_end) {
-    load_chunk(c_begin);
-    store_chunk(c_begin, 0);
-  }
-  __syncthreads();
-  int buf = 0;
-  for (int c = c_begin; c < c_end; ++c, buf ^= 1) {
-    const int c0 = c * kChunk;
-    const int c_next = c + 1 < c_end ? c + 1 : c;  // clamped: the last iteration reloads its own chunk
-    load_chunk(c_next);
-    __builtin_amdgcn_sched_barrier(0);
-
-    // scores: every K tile is read once and used for all QB query blocks; consecutive products go to
-    // different accumulators
-    f32x4 s4[QB][4];
-#pragma unroll
-    for (int t = 0; t < QB; ++t)
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb) s4[t][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb) {
-        const f16x8 a = *reinterpret_cast<const f16x8*>(&ks_lds[buf][((kb * 4 + s) * 64 + lane) * 8]);
-#pragma unroll
-        for (int t = 0; t < QB; ++t)
-          s4[t][kb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq[t][s], s4[t][kb], 0, 0, 0);
-      }
-    // s4[t][kb][e] = score of key c0 + 16 kb + 4 g + e for query row 16 rb + j
-    Pack8 pb[QB][2];
-#pragma unroll
-    for (int t = 0; t < QB; ++t) {
-      const bool need_mask = c0 + kChunk - 1 > lim_min[t];  // same for the whole wavefront
-      float mx = -INFINITY;
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float sv = s4[t][kb][e] * scale_log2;
-          if (need_mask && c0 + kb * 16 + 4 * g + e > limit[t]) sv = -INFINITY;
-          s4[t][kb][e] = sv;
-          mx = fmaxf(mx, sv);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[t], mx);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[t] - m_use);
-      float psum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float p = __builtin_amdgcn_exp2f(s4[t][kb][e] - m_use);
-          psum += p;
-          pb[t][kb >> 1].h[(kb & 1) * 4 + e] = float_to_half_bits(p);
-        }
-      l_run[t] = l_run[t] * alpha + psum;
-      m_run[t] = m_new;
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {  // the running maximum moved somewhere in the wavefront
-#pragma unroll
-        for (int d = 0; d < 8; ++d) o[t][d] *= alpha;
-      }
-    }
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-      for (int d = 0; d < 8; ++d) {
-        const f16x8 a = *reinterpret_cast<const f16x8*>(&vs_lds[buf][((d * 2 + t2) * 64 + lane) * 8]);
-#pragma unroll
-        for (int t = 0; t < QB; ++t)
-          o[t][d] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, pb[t][t2].v, o[t][d], 0, 0, 0);
-      }
-    __builtin_amdgcn_sched_barrier(0);
-    store_chunk(c_next, buf ^ 1);  // the other buffer: nobody reads it until the barrier below
-    __syncthreads();
-  }
-
+  // The rows of block qb0 + t that this lane works for: virtual row v -> (head, row); lanes past the last virtual row
+  // repeat it (they compute a copy that nobody stores).
+  int head[QB], row[QB];
+  bool live[QB];
 #pragma unroll
   for (int t = 0; t < QB; ++t) {
-    float l = l_run[t];
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    const int r = rb[t] * 16 + j;
-    if (!valid[t] || r >= rows) continue;  // padding rows are never merged
-    const size_t row = ((size_t)split * n_q + head[t]) * rows_stride + r;
-#pragma unroll
-    for (int d = 0; d < 8; ++d)
-      *reinterpret_cast<float4*>(part_o + row * kHd + d * 16 + 4 * g) =
-          make_float4(o[t][d][0], o[t][d][1], o[t][d][2], o[t][d][3]);
-    // the merge works in natural-log units
-    if (g == 0) *reinterpret_cast<float2*>(part_ml + row * 2) = make_float2(m_run[t] * 0.6931471805599453f, l);
+    int v = (qb0 + t) * 16 + j;
+    live[t] = v < n_vrows;
+    if (v >= n_vrows) v = n_vrows - 1;
+    head[t] = kvh * group + v / rows;
+    row[t] = v % rows;
   }
+
+  if (n == 0) {
+    // An empty split (the whole workgroup takes this branch): a sequence of a batched call with fewer keys than
+    // the longest one.  The merge walks every split, so leave partials of weight zero.
+#pragma unroll
+    for (int t = 0; t < QB; ++t) {
+      if (!live[t]) continue;
+      const size_t prow = ((size_t)split * n_q + head[t]) * rows_stride + row[t];
+#pragma unroll
+      for (int d = 0; d < 8; ++d)
+        *reinterpret_cast<float4*>(part_o + prow * kHd + d * 16 + 4 * g) = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (g == 0) *reinterpret_cast<float2*>(part_ml + prow * 2) = make_float2(-INFINITY, 0.f);
+    }
+    return;
+  }
+
+  issue_chunk(0);
+  auto run = [&](auto nb_tag) {
+    constexpr int NB = decltype(nb_tag)::value;
+    AttnWave<NB> w;
+    if constexpr (NB > 0) {
+#pragma unroll
+      for (int t = 0; t < NB; ++t) {
+        const uint16_t* qh = q + (size_t)head[t] * rows_stride * kHd + (size_t)(row[t] >> 4) * 4 * 512 + g * 128 +
+                             (row[t] & 15) * 8;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) w.bq[t][s] = *reinterpret_cast<const f16x8*>(qh + s * 512);
+#pragma unroll
+        for (int d = 0; d < 8; ++d) w.o[t][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+        w.l_acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        w.neg_m[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        w.m_ref[t] = -INFINITY;
+        w.limit[t] = (row[t] >= n_causal) ? n_keys - 1 : pos0 + row[t];  // last key this lane's row sees
+        int lm = w.limit[t];                                              // smallest limit in the block
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) lm = min(lm, __shfl_xor(lm, off));
+        w.lim_min[t] = lm;
+      }
+    }
+    finish_chunk(0);
+    __syncthreads();
+    for (int i = 0; i < n; ++i) {
+      if (i + 1 < n) issue_chunk(i + 1);
+      if constexpr (NB > 0) {
+        const uint16_t* ks = k_lds + (i & 1) * kChunkElems;
+        const uint16_t* vs = v_lds + (i & 1) * kChunkElems;
+        attn_matrix_phase<NB, false, true>(vs, ks, lane, w.bq, w.pb, w.neg_m, w.o, w.l_acc, w.s4);
+        attn_softmax_phase<NB>(g, (c_begin + i) * kChunk, w.lim_min, w.limit, w.s4, w.pb, w.o, w.l_acc, w.m_ref, w.neg_m);
+        attn_matrix_phase<NB, true, false>(vs, ks, lane, w.bq, w.pb, w.neg_m, w.o, w.l_acc, w.s4);
+      }
+      if (i + 1 < n) finish_chunk(i + 1);
+      phase_barrier();
+    }
+    if constexpr (NB > 0) {
+#pragma unroll
+      for (int t = 0; t < NB; ++t) {
+        if (!live[t]) continue;  // lanes past the last virtual row
+        const size_t prow = ((size_t)split * n_q + head[t]) * rows_stride + row[t];
+#pragma unroll
+        for (int d = 0; d < 8; ++d)
+          *reinterpret_cast<float4*>(part_o + prow * kHd + d * 16 + 4 * g) =
+              make_float4(w.o[t][d][0], w.o[t][d][1], w.o[t][d][2], w.o[t][d][3]);
+        // the merge works in natural-log units; every lane of a row holds the row's whole sum
+        if (g == 0)
+          *reinterpret_cast<float2*>(part_ml + prow * 2) =
+              make_float2(w.m_ref[t] * 0.6931471805599453f, w.l_acc[t][0]);
+      }
+    }
+  };
+  if (nb == QB)
+    run(std::integral_constant<int, QB>{});
+  else if (nb == 1)
+    run(std::integral_constant<int, 1>{});
+  else
+    run(std::integral_constant<int, 0>{});
 }
 
 // float32 parity mode.  grid (n_split, n_q); each wavefront walks rows r = wave, wave + 4, ...
@@ -326,12 +473,16 @@ __global__ void attn_merge_kernel(SeqTable tab, const float* __restrict__ part_o
 // row by row in a fixed order, so the result of a query row is bit-identical whether the row is computed
 // alone (one-token decoding) or inside a block (parallel verification): greedy verification then
 // reproduces the target's own greedy stream exactly, not just up to rounding.
-// Half-precision kernel: at most 32 splits over the capacity, at least two 64-key chunks per split.
+// Half-precision kernel: at most 21 splits over the capacity (at the long-context benchmark shape, 20 splits x 8 KV
+// heads x 3 workgroups fill the 512 workgroup slots of the chip in one round), at least two 64-key chunks per split.
 // float32 kernel: at most 16 splits.
-constexpr int kMaxSplitsF16 = 32, kMaxSplitsF32 = 16;
+constexpr int kMaxSplitsF16 = 21, kMaxSplitsF32 = 16;
 
 // Rows-equivalents of partial results the workspace holds for a call with rows_pad padded rows.
 int attn_partial_rows(int rows_pad) { return kMaxSplitsF16 * rows_pad; }
+
+// What the producer of q multiplies the rotated queries by: the half-precision kernel takes them in log2 units.
+float attn_q_scale(int dtype, int hd) { return dtype == DS_BF16 ? 1.4426950408889634f / sqrtf((float)hd) : 1.0f; }
 
 AttnPlan attn_plan(int dtype, int cap, int n_keys) {
   const int cap_chunks = ceil_div(cap, kChunk), n_chunks = ceil_div(n_keys, kChunk);
@@ -375,14 +526,14 @@ int launch_attention(int dtype, const SeqTable& tab, const void* q, int rows, in
     const int srp = ceil_div(sr, 16) * 16;
     const AttnPlan plan = attn_plan(dtype, cap, n_keys);
     if (dtype == DS_BF16) {
-      const int n_qb = (n_q / n_kv) * (srp >> 4);
-      constexpr int QB = 2;
+      const int n_qb = ceil_div((n_q / n_kv) * sr, 16);  // blocks of 16 densely packed (head, row) pairs
+      constexpr int QB = kAttnQB;
       dim3 grid(n_split_max, n_kv, ceil_div(n_qb, 4 * QB));
-      hipLaunchKernelGGL((attn_f16_kernel<QB>), grid, dim3(256), 0, st,
+      hipLaunchKernelGGL((attn_f16_kernel<QB>), grid, dim3(kAttnThreads), 0, st,
                          static_cast<const uint16_t*>(q) + (size_t)(r0 >> 4) * 4 * 512,
-                         static_cast<const uint16_t*>(tab.kc[s]), static_cast<const uint16_t*>(tab.vc[s]), sr, srp,
+                         static_cast<const uint16_t*>(tab.kc[s]), static_cast<const uint16_t*>(tab.vc[s]), sr,
                          rows_pad, tab.n_causal[s], tab.pos0[s], n_keys, n_q, n_kv, cap, plan.chunks_per_split,
-                         scale * 1.4426950408889634f, part_o + (size_t)r0 * kHd, part_ml + (size_t)r0 * 2);
+                         part_o + (size_t)r0 * kHd, part_ml + (size_t)r0 * 2);
       DS_LAUNCH_CHECK("attn_f16_kernel");
     } else {
       hipLaunchKernelGGL(attn_f32_kernel, dim3(n_split_max, n_q), dim3(256), 0, st,

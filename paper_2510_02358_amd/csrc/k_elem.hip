@@ -139,7 +139,7 @@ __global__ void to_gemm_input_kernel(const float* __restrict__ src, int rows_pad
 // Head slots: [0, n_q) queries, [n_q, n_q + n_kv) keys, then values.
 template <typename T>
 __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int n_q,
-                                int n_kv, int hd, const float2* __restrict__ cs, SeqTable tab, int cap,
+                                int n_kv, int hd, const float2* __restrict__ cs, SeqTable tab, int cap, float q_scale,
                                 typename Act<T>::kv_t* __restrict__ q, uint32_t* __restrict__ ovf) {
   using KV = typename Act<T>::kv_t;
   const int r = blockIdx.x, slot = blockIdx.y, i = threadIdx.x, half = hd >> 1;
@@ -179,8 +179,9 @@ __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int 
   const int pos = pos0 + r;
   if (slot < n_q) {
     KV* qh = q + (size_t)slot * rows_pad * hd;
-    qh[Act<T>::q_off(r, i, hd)] = Act<T>::to_kv(a, ovf);
-    qh[Act<T>::q_off(r, i + half, hd)] = Act<T>::to_kv(b, ovf);
+    // the attention kernel's score scale goes into the queries before their one rounding
+    qh[Act<T>::q_off(r, i, hd)] = Act<T>::to_kv(a * q_scale, ovf);
+    qh[Act<T>::q_off(r, i + half, hd)] = Act<T>::to_kv(b * q_scale, ovf);
   } else if (slot < n_q + n_kv) {
     if (Act<T>::kTiledKV) {
       KV* kh = kc + (size_t)(slot - n_q) * cap * hd;
@@ -282,10 +283,10 @@ int launch_to_gemm_input(const float* src, int rows, int rows_pad, int d, void* 
 
 template <typename T>
 int launch_qkv_rope(const SeqTable& tab, const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv,
-                    int hd, const float2* cs, int cap, void* q, uint32_t* ovf, hipStream_t st) {
+                    int hd, const float2* cs, int cap, float q_scale, void* q, uint32_t* ovf, hipStream_t st) {
   DS_REQUIRE(n_part >= 1 && n_part <= kMaxPlanes, DS_E_SHAPE, "rope: %d partial planes, at most %d", n_part, kMaxPlanes);
   hipLaunchKernelGGL((qkv_rope_kernel<T>), dim3(rows, n_q + 2 * n_kv), dim3(hd / 2), 0, st, part, n_part, rows,
-                     rows_pad, n_q, n_kv, hd, cs, tab, cap, static_cast<typename Act<T>::kv_t*>(q), ovf);
+                     rows_pad, n_q, n_kv, hd, cs, tab, cap, q_scale, static_cast<typename Act<T>::kv_t*>(q), ovf);
   DS_LAUNCH_CHECK("qkv_rope_kernel");
   return DS_OK;
 }
@@ -307,7 +308,7 @@ int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, 
   template int launch_add_norm<T>(const SeqTable&, float*, const float*, int, int, int, int, const float*, float, \
                                   void*, float*, void*, uint32_t*, hipStream_t);                                   \
   template int launch_to_gemm_input<T>(const float*, int, int, int, void*, uint32_t*, hipStream_t);                \
-  template int launch_qkv_rope<T>(const SeqTable&, const float*, int, int, int, int, int, int, const float2*, int, \
+  template int launch_qkv_rope<T>(const SeqTable&, const float*, int, int, int, int, int, int, const float2*, int, float, \
                                   void*, uint32_t*, hipStream_t);                                                  \
   template int launch_swiglu<T>(const float*, int, int, int, int, void*, uint32_t*, hipStream_t);
 DS_INSTANTIATE(float)
