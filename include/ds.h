@@ -64,7 +64,8 @@ typedef struct {
   int32_t dtype;       /* DS_F32 or DS_BF16: storage type of the weights.  DS_BF16: bf16 weights (re-encoded
                           exactly as IEEE half inside the library), IEEE-half activations at every matrix
                           product and in the KV cache, float32 accumulation, residual stream and logits.
-                          DS_F32: everything float32. */
+                          Half activations saturate at +-65504 instead of overflowing; every saturated value
+                          is counted (ds_model_overflow_count).  DS_F32: everything float32. */
   int32_t kv_capacity; /* tokens each layer's KV buffer can hold (bf16: a multiple of 64) */
 } ds_model_cfg;
 
