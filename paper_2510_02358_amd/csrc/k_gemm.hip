@@ -116,8 +116,12 @@ struct Top3 {
   }
 };
 
-template <int MB, int NB, int EPI>
-__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(min_waves_for(MB, NB))))
+// WAVES: wavefronts per workgroup, 4 or 8.  All of them share the staged X chunk, so eight wavefronts (one
+// workgroup per CU instead of two) read X from L2 half as often per weight byte: with many rows the X loads, not the
+// weight stream, are what slows the product down (a 65-row product without them runs at the one-row rate).  Every
+// output element sees the same k order either way, so the choice does not change a single bit of the result.
+template <int MB, int NB, int EPI, int WAVES = 4>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(min_waves_for(MB, NB))))
 void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
                                                                  const uint16_t* __restrict__ xt, int M, int N,
                                                                  int K, int groups_per_split, int n_big,
@@ -132,9 +136,11 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   int c_end = c_begin + groups_per_split * (kGroup / kKSC);
   if (c_end > n_chunks) c_end = n_chunks;
 
+  static_assert(WAVES == 4 || EPI == kEpiPlanes || EPI == kEpiStream, "the record epilogues reduce over four wavefronts");
+  constexpr int kThreads = WAVES * 64;
   // This workgroup's share of the output row blocks.  The first n_big workgroups take a full pass of
-  // 4 * NB blocks each; a remainder goes to later workgroups in half-size pieces.
-  const int full = 4 * NB, half = full / 2 > 0 ? full / 2 : 1;
+  // WAVES * NB blocks each; a remainder goes to later workgroups in half-size pieces.
+  const int full = WAVES * NB, half = full / 2 > 0 ? full / 2 : 1;
   int nb_begin, nb_end;
   if ((int)blockIdx.x < n_big) {
     nb_begin = (int)blockIdx.x * full;
@@ -147,12 +153,12 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   const int j_out = lane & 15, g_out = lane >> 4;
   float* out_plane = out + (size_t)blockIdx.y * M * N;
 
-  for (int pass0 = nb_begin; pass0 < nb_end; pass0 += 4 * NB) {
+  for (int pass0 = nb_begin; pass0 < nb_end; pass0 += WAVES * NB) {
   int nb[NB];
   const uint16_t* wrow[NB];
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
-    nb[b] = pass0 + b * 4 + wave;
+    nb[b] = pass0 + b * WAVES + wave;
     const int nbc = nb[b] < nb_end ? nb[b] : nb_end - 1;  // clamp: loads stay in this workgroup's range
     wrow[b] = wp + ((size_t)nbc * ksteps) * 512 + lane * 8;
   }
@@ -163,10 +169,12 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
 #pragma unroll
     for (int m = 0; m < MB; ++m) acc[b][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // 16-byte pieces of X per chunk, order [mb][s][lane]; kTiles is a multiple of 4, so every
-  // thread moves exactly kXPer pieces (no tail predicate: the loads issue back to back).
-  constexpr int kXPer = kTiles * 64 / kGemmThreads;
-  static_assert((kTiles * 64) % kGemmThreads == 0, "X chunk must split evenly over the workgroup");
+  // 16-byte pieces of X per chunk, order [mb][s][lane]: kXPer per thread.  With four wavefronts the pieces split
+  // evenly; with eight and an odd MB the last round is half full: those threads re-load the chunk's last piece
+  // (no predicate on the loads, which therefore issue back to back) and skip the store.
+  constexpr int kPieces = kTiles * 64;
+  constexpr int kXPer = (kPieces + kThreads - 1) / kThreads;
+  constexpr bool kXTail = (kPieces % kThreads) != 0;
   constexpr int kStages = 3;  // weight-tile register sets: two chunks are in flight while one is multiplied
   u32x4 xreg[kXPer];
   f16x8 areg[kStages][NB][kKSC];
@@ -174,7 +182,8 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   auto load_x = [&](int c) {
 #pragma unroll
     for (int p = 0; p < kXPer; ++p) {
-      const int piece = threadIdx.x + p * kGemmThreads;
+      int piece = threadIdx.x + p * kThreads;
+      if (kXTail && piece >= kPieces) piece = kPieces - 1;
       const int mb = piece / (kKSC * 64), rest = piece - mb * (kKSC * 64);
       xreg[p] = *reinterpret_cast<const u32x4*>(xt + ((size_t)mb * ksteps + (size_t)c * kKSC) * 512 + rest * 8);
     }
@@ -182,7 +191,8 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   auto store_x = [&](int buf) {
 #pragma unroll
     for (int p = 0; p < kXPer; ++p)
-      *reinterpret_cast<u32x4*>(&xs[buf][(threadIdx.x + p * kGemmThreads) * 8]) = xreg[p];
+      if (!kXTail || (int)threadIdx.x + p * kThreads < kPieces)
+        *reinterpret_cast<u32x4*>(&xs[buf][(threadIdx.x + p * kThreads) * 8]) = xreg[p];
   };
   // Weights are read exactly once per product: non-temporal loads keep them from displacing the activations
   // (re-read by every workgroup) and the output lines in the caches.
@@ -419,15 +429,33 @@ int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, 
                    const GemmEpilogue& epi, hipStream_t st) {
   const int n_groups = (K >> 5) / kGroup;
   const int gps = ceil_div(n_groups, n_split);
-  // One workgroup per full pass of 4 * nbw row blocks; a remainder goes to half-size workgroups at the end.
-  const int n_blocks = N >> 4, full = 4 * nbw, half = full / 2 > 0 ? full / 2 : 1;
+  // Eight wavefronts per workgroup from 65 rows up (measured: at 33 rows four are as fast or faster, at 65 rows the
+  // 32B-shaped products gain 3 - 8 %, at 128 rows 20 %), where the row blocks divide into full passes, the
+  // product writes planes or values, the tile fits two wavefronts per SIMD, and the workgroups - one per CU now -
+  // fit the chip in one round; four otherwise.  Same bits either way.
+  const int n_blocks = N >> 4;
+  const bool wide = MB >= 5 && min_waves_for(MB, nbw) == 2 && epi.kind == GemmEpilogue::kNone &&
+                    n_blocks % (8 * nbw) == 0 && (n_blocks / (8 * nbw)) * n_split <= 256;
+  const int waves = wide ? 8 : 4;
+  // One workgroup per full pass of waves * nbw row blocks; a remainder goes to half-size workgroups at the end.
+  const int full = waves * nbw, half = full / 2 > 0 ? full / 2 : 1;
   const int n_big = n_blocks / full;
   const int n_small = ceil_div(n_blocks - n_big * full, half);
   dim3 grid(n_big + n_small, n_split);
   auto go = [&](auto kernel) {
-    hipLaunchKernelGGL(kernel, grid, dim3(kGemmThreads), 0, st, wp, xt, M, N, K, gps, n_big, out, epi.records,
+    hipLaunchKernelGGL(kernel, grid, dim3(waves * 64), 0, st, wp, xt, M, N, K, gps, n_big, out, epi.records,
                        epi.export_col, epi.export_out);
   };
+  if (wide) {
+    if constexpr (MB >= 5) {
+      if (n_split == 1 && nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiStream, 8>);
+      else if (n_split == 1) go(gemm_bf16_kernel<MB, 1, kEpiStream, 8>);
+      else if (nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiPlanes, 8>);
+      else go(gemm_bf16_kernel<MB, 1, kEpiPlanes, 8>);
+      DS_LAUNCH_CHECK("gemm_bf16_kernel");
+      return DS_OK;
+    }
+  }
   // records: the caller has checked nbw == 2 and n_split == 1
   if (epi.kind == GemmEpilogue::kBest) go(gemm_bf16_kernel<MB, 2, kEpiBest>);
   else if (epi.kind == GemmEpilogue::kTop) go(gemm_bf16_kernel<MB, 2, kEpiTop>);
