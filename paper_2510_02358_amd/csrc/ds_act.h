@@ -139,12 +139,16 @@ int gemm_bf16_splits(int N, int K, int nbw);
 //          export_out[row] (rows_pad floats, optional) receives the values of column export_col.
 // With records the output pointer may be NULL.
 struct GemmEpilogue {
-  enum Kind { kNone = 0, kBest = 1, kTop = 2 };
+  enum Kind { kNone = 0, kBest = 1, kTop = 2, kSwiGLU = 3 };
   Kind kind = kNone;
-  void* records = nullptr;
+  void* records = nullptr;   // kBest / kTop: the per-tile records; kSwiGLU: the half-precision output [rows padded, N / 2]
   int export_col = -1;
   float* export_out = nullptr;
+  uint32_t* ovf = nullptr;   // kSwiGLU: the model's saturation counter
 };
+// gate and up ([F, K] each) as one stream-order matrix with alternating 16-row blocks, for the kSwiGLU epilogue
+int launch_pack_weight_pair(const void* w_a, const void* w_b, int F, int K, void* dst, uint32_t* range_flag,
+                            hipStream_t st);
 int gemm_bf16_best_tile(int N, int nbw, int n_split);
 size_t gemm_bf16_best_bytes(int rows, int N, int tile);
 size_t gemm_bf16_top_bytes(int rows, int N, int tile);

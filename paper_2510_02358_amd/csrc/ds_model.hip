@@ -14,7 +14,7 @@ using namespace ds;
 namespace {
 
 struct PackedLayer {
-  const void *wqkv, *wo, *wgu, *wdown;  // bf16 stream order
+  const void *wqkv, *wo, *wgu, *wdown;  // bf16 stream order (wgu: see ds_model::fused_gu)
 };
 
 // Carve-up of the caller's workspace for a call with `rows` rows (all offsets 256-byte aligned).
@@ -61,6 +61,9 @@ struct ds_model {
   ds_kv self;  // the cache given to ds_model_create (what the single-sequence calls use)
   size_t esize;
   uint32_t* ovf = nullptr;  // [dev] activation-overflow counter (bf16 models: a word of the packed buffer's tail)
+  // bf16 models whose gate / up product is unsplit (a function of its shape alone): gate and up are packed with
+  // alternating 16-row blocks and the product's epilogue applies SwiGLU itself
+  bool fused_gu = false;
   // what the last draft pass left behind for ds_lm_head(hidden = NULL): the block rows as a GEMM input
   const void* tail_ptr = nullptr;
   const void* tail_ws = nullptr;
@@ -312,8 +315,16 @@ int forward_rows(ds_model* m, const Workspace& w, const FwdCall& call, const Seq
     if ((rc = launch_add_norm<T>(tab, w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr,
                                  nullptr, m->ovf, st)))
       return rc;
-    if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st))) return rc;
-    if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, rp, c.d_ffn, w.act, m->ovf, st))) return rc;
+    if (m->fused_gu) {  // SwiGLU in the product's epilogue: the next product's input comes out directly
+      GemmEpilogue epi;
+      epi.kind = GemmEpilogue::kSwiGLU;
+      epi.records = w.act;
+      epi.ovf = m->ovf;
+      if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st, epi))) return rc;
+    } else {
+      if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st))) return rc;
+      if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, rp, c.d_ffn, w.act, m->ovf, st))) return rc;
+    }
     if ((rc = gemm<T>(m, li, 3, w.act, rows, w.gemm_out, &sp, st))) return rc;
     const bool last = li + 1 == c.n_layers;
     const float* gain = last ? m->final_norm : m->canon[li + 1].norm1;
@@ -424,6 +435,7 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
       delete m;
       return fail(DS_E_HIP, "hipMemsetAsync(weight-range flag) failed");
     }
+    m->fused_gu = gemm_bf16_splits(2 * f, d, 2) == 1 && (f % 128) == 0;
     auto put = [&](const void* src, int N, int K) -> int {
       int r = launch_pack_weight(src, N, K, p, flag, st);
       p += (size_t)N * K * 2;
@@ -437,7 +449,12 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
       pl.wo = p;
       if ((rc = put(lw.wo, d, qo))) break;
       pl.wgu = p;
-      if ((rc = put(lw.w_gate, f, d)) || (rc = put(lw.w_up, f, d))) break;
+      if (m->fused_gu) {
+        if ((rc = launch_pack_weight_pair(lw.w_gate, lw.w_up, f, d, p, flag, st))) break;
+        p += (size_t)2 * f * d * 2;
+      } else if ((rc = put(lw.w_gate, f, d)) || (rc = put(lw.w_up, f, d))) {
+        break;
+      }
       pl.wdown = p;
       if ((rc = put(lw.w_down, d, f))) break;
       m->packed.push_back(pl);

@@ -54,8 +54,11 @@ constexpr int kKSC = 4;    // k-steps per LDS chunk: 128 columns (8 KB of X per 
 constexpr int min_waves_for(int MB, int NB) { return (NB == 2 && MB >= 6) ? 1 : 2; }
 
 // Copy a canonical row-major bf16 matrix W[N, K] into stream order as IEEE half.  One thread per 16-byte piece.
-__global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K, uint16_t* __restrict__ dst,
-                                   uint32_t* __restrict__ range_flag) {
+// With a second matrix w2 (same shape [N / 2, K] each): the destination's 16-row blocks alternate between the two,
+// block 2c = rows [16c, 16c + 16) of w, block 2c + 1 = the same rows of w2, so that a wavefront that multiplies two
+// adjacent blocks holds column block c of both products.
+__global__ void pack_weight_kernel(const uint16_t* __restrict__ w, const uint16_t* __restrict__ w2, int N, int K,
+                                   uint16_t* __restrict__ dst, uint32_t* __restrict__ range_flag) {
   const size_t piece = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t n_piece = (size_t)N * K / 8;
   if (piece >= n_piece) return;
@@ -65,7 +68,9 @@ __global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K,
   const int ks = (int)(tile % ksteps);
   const int nb = (int)(tile / ksteps);
   const int i = lane & 15, g = lane >> 4;
-  const uint4 v = *reinterpret_cast<const uint4*>(w + (size_t)(nb * 16 + i) * K + ks * 32 + g * 8);
+  const uint16_t* src = (w2 && (nb & 1)) ? w2 : w;
+  const int sb = w2 ? nb >> 1 : nb;
+  const uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)(sb * 16 + i) * K + ks * 32 + g * 8);
   const uint32_t in[4] = {v.x, v.y, v.z, v.w};
   uint32_t o[4];
   bool bad = false;
@@ -87,7 +92,11 @@ __global__ void pack_weight_kernel(const uint16_t* __restrict__ w, int N, int K,
 //               only if `out` is not NULL;
 //   kEpiTop     as kEpiBest, with per-tile lattice records instead: the two largest values with their columns,
 //               the third largest value, the sum of exp(x - largest); and the values of one chosen column.
-enum { kEpiPlanes = 0, kEpiStream = 1, kEpiBest = 2, kEpiTop = 3 };
+//   kEpiSwiGLU  unsplit product of a gate / up pair packed with alternating blocks (launch_pack_weight_pair): the
+//               wavefront's two adjacent blocks are column block c of gate and of up, so silu(gate) * up is taken
+//               in registers and stored as the next product's half-precision input; the float32 product never
+//               reaches memory and no separate kernel runs.
+enum { kEpiPlanes = 0, kEpiStream = 1, kEpiBest = 2, kEpiTop = 3, kEpiSwiGLU = 4 };
 
 // Running (largest, second largest, third largest) of a stream of values; the first two carry their columns and
 // order equal values by column, the third is a value only.
@@ -127,7 +136,8 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
                                                                  int K, int groups_per_split, int n_big,
                                                                  float* __restrict__ out,
                                                                  void* __restrict__ rec, int export_col,
-                                                                 float* __restrict__ export_out) {
+                                                                 float* __restrict__ export_out,
+                                                                 uint32_t* __restrict__ ovf) {
   constexpr int kTiles = MB * kKSC;  // X tiles per chunk: row blocks x k-steps
   __shared__ __attribute__((aligned(16))) uint16_t xs[2][kTiles * 512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -136,7 +146,9 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   int c_end = c_begin + groups_per_split * (kGroup / kKSC);
   if (c_end > n_chunks) c_end = n_chunks;
 
-  static_assert(WAVES == 4 || EPI == kEpiPlanes || EPI == kEpiStream, "the record epilogues reduce over four wavefronts");
+  static_assert(WAVES == 4 || EPI == kEpiPlanes || EPI == kEpiStream || EPI == kEpiSwiGLU,
+                "the record epilogues reduce over four wavefronts");
+  static_assert(EPI != kEpiSwiGLU || NB == 2, "the fused epilogue pairs a wavefront's two column blocks");
   constexpr int kThreads = WAVES * 64;
   // This workgroup's share of the output row blocks.  The first n_big workgroups take a full pass of
   // WAVES * NB blocks each; a remainder goes to later workgroups in half-size pieces.
@@ -158,7 +170,7 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   const uint16_t* wrow[NB];
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
-    nb[b] = pass0 + b * WAVES + wave;
+    nb[b] = pass0 + wave * NB + b;  // a wavefront's blocks are adjacent
     const int nbc = nb[b] < nb_end ? nb[b] : nb_end - 1;  // clamp: loads stay in this workgroup's range
     wrow[b] = wp + ((size_t)nbc * ksteps) * 512 + lane * 8;
   }
@@ -260,7 +272,26 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   }
 
   // D[i][j]: lane (16 g + j) holds rows i = 4 g .. 4 g + 3 of column j  ->  out[m = 16 mb + j][n = 16 nb + 4 g ..]
-  if ((EPI != kEpiBest && EPI != kEpiTop) || out) {
+  if (EPI == kEpiSwiGLU) {
+    // blocks 2c and 2c + 1 of the packed pair: gate and up of column block c.  rec: the half-precision GEMM input
+    // [rows padded, N / 2] of the next product (tile order).
+    bf16_t* act = static_cast<bf16_t*>(rec);
+    if (nb[0] < nb_end) {
+      const int col = (nb[0] >> 1) * 16 + g_out * 4;
+#pragma unroll
+      for (int m = 0; m < MB; ++m) {
+        const int row = m * 16 + j_out;
+        if (row < M) {
+          float4 y;
+          y.x = acc[0][m][0] / (1.0f + expf(-acc[0][m][0])) * acc[NB - 1][m][0];
+          y.y = acc[0][m][1] / (1.0f + expf(-acc[0][m][1])) * acc[NB - 1][m][1];
+          y.z = acc[0][m][2] / (1.0f + expf(-acc[0][m][2])) * acc[NB - 1][m][2];
+          y.w = acc[0][m][3] / (1.0f + expf(-acc[0][m][3])) * acc[NB - 1][m][3];
+          Act<bf16_t>::put4(act, row, col, N >> 1, y, ovf);
+        }
+      }
+    }
+  } else if ((EPI != kEpiBest && EPI != kEpiTop) || out) {
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
       if (nb[b] >= nb_end) continue;
@@ -434,7 +465,8 @@ int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, 
   // product writes planes or values, the tile fits two wavefronts per SIMD, and the workgroups - one per CU now -
   // fit the chip in one round; four otherwise.  Same bits either way.
   const int n_blocks = N >> 4;
-  const bool wide = MB >= 5 && min_waves_for(MB, nbw) == 2 && epi.kind == GemmEpilogue::kNone &&
+  const bool plain = epi.kind == GemmEpilogue::kNone || epi.kind == GemmEpilogue::kSwiGLU;
+  const bool wide = MB >= 5 && min_waves_for(MB, nbw) == 2 && plain &&
                     n_blocks % (8 * nbw) == 0 && (n_blocks / (8 * nbw)) * n_split <= 256;
   const int waves = wide ? 8 : 4;
   // One workgroup per full pass of waves * nbw row blocks; a remainder goes to half-size workgroups at the end.
@@ -444,11 +476,12 @@ int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, 
   dim3 grid(n_big + n_small, n_split);
   auto go = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, grid, dim3(waves * 64), 0, st, wp, xt, M, N, K, gps, n_big, out, epi.records,
-                       epi.export_col, epi.export_out);
+                       epi.export_col, epi.export_out, epi.ovf);
   };
   if (wide) {
     if constexpr (MB >= 5) {
-      if (n_split == 1 && nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiStream, 8>);
+      if (epi.kind == GemmEpilogue::kSwiGLU) go(gemm_bf16_kernel<MB, 2, kEpiSwiGLU, 8>);
+      else if (n_split == 1 && nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiStream, 8>);
       else if (n_split == 1) go(gemm_bf16_kernel<MB, 1, kEpiStream, 8>);
       else if (nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiPlanes, 8>);
       else go(gemm_bf16_kernel<MB, 1, kEpiPlanes, 8>);
@@ -459,6 +492,7 @@ int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, 
   // records: the caller has checked nbw == 2 and n_split == 1
   if (epi.kind == GemmEpilogue::kBest) go(gemm_bf16_kernel<MB, 2, kEpiBest>);
   else if (epi.kind == GemmEpilogue::kTop) go(gemm_bf16_kernel<MB, 2, kEpiTop>);
+  else if (epi.kind == GemmEpilogue::kSwiGLU) go(gemm_bf16_kernel<MB, 2, kEpiSwiGLU>);
   else if (n_split == 1 && nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiStream>);
   else if (n_split == 1) go(gemm_bf16_kernel<MB, 1, kEpiStream>);
   else if (nbw == 2) go(gemm_bf16_kernel<MB, 2, kEpiPlanes>);
@@ -474,7 +508,21 @@ int launch_pack_weight(const void* w, int N, int K, void* dst, uint32_t* range_f
              "bf16 matrix [%d, %d]: rows must be a multiple of 16 and columns of 128", N, K);
   const size_t n_piece = (size_t)N * K / 8;
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n_piece + 255) / 256)), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(w), N, K, static_cast<uint16_t*>(dst), range_flag);
+                     static_cast<const uint16_t*>(w), static_cast<const uint16_t*>(nullptr), N, K,
+                     static_cast<uint16_t*>(dst), range_flag);
+  DS_LAUNCH_CHECK("pack_weight_kernel");
+  return DS_OK;
+}
+
+// Two matrices [F, K] packed as one [2 F, K] with their 16-row blocks alternating (see pack_weight_kernel).
+int launch_pack_weight_pair(const void* w_a, const void* w_b, int F, int K, void* dst, uint32_t* range_flag,
+                            hipStream_t st) {
+  DS_REQUIRE((F & 15) == 0 && (K & 127) == 0, DS_E_SHAPE,
+             "bf16 matrix [%d, %d]: rows must be a multiple of 16 and columns of 128", F, K);
+  const size_t n_piece = (size_t)2 * F * K / 8;
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n_piece + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const uint16_t*>(w_a), static_cast<const uint16_t*>(w_b), 2 * F, K,
+                     static_cast<uint16_t*>(dst), range_flag);
   DS_LAUNCH_CHECK("pack_weight_kernel");
   return DS_OK;
 }
@@ -514,8 +562,12 @@ int launch_gemm_bf16(const void* wp, const void* xt, int M, int N, int K, int nb
                      const GemmEpilogue& epi, hipStream_t st) {
   DS_REQUIRE(M >= 1 && M <= DS_MAX_ROWS, DS_E_SHAPE, "GEMM rows %d outside [1, %d]", M, DS_MAX_ROWS);
   DS_REQUIRE((N & 15) == 0 && (K & 127) == 0, DS_E_SHAPE, "GEMM [%d x %d]: N %% 16 and K %% 128 must be 0", N, K);
-  const bool records = epi.kind != GemmEpilogue::kNone;
-  DS_REQUIRE(out || records, DS_E_INVALID, "GEMM: neither an output nor a per-tile record buffer");
+  if (epi.kind == GemmEpilogue::kSwiGLU)
+    DS_REQUIRE(epi.records && nbw == 2 && n_split == 1 && (N >> 4) % 16 == 0, DS_E_SHAPE,
+               "GEMM [%d x %d]: the fused gate / up epilogue needs an unsplit pass over whole pairs of blocks", N, K);
+  const bool records = epi.kind == GemmEpilogue::kBest || epi.kind == GemmEpilogue::kTop;
+  DS_REQUIRE(out || records || epi.kind == GemmEpilogue::kSwiGLU, DS_E_INVALID,
+             "GEMM: neither an output nor a per-tile record buffer");
   DS_REQUIRE(!records || (epi.records && gemm_bf16_best_tile(N, nbw, n_split) > 0), DS_E_SHAPE,
              "GEMM [%d x %d]: per-tile records need a buffer and an unsplit pass of full tiles", N, K);
   const uint16_t* w = static_cast<const uint16_t*>(wp);
