@@ -176,9 +176,9 @@ __device__ __forceinline__ void attn_softmax_phase(int g, int c0, const int (&li
         pb[t][kb >> 1].w[((kb & 1) * 4 + e) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, f16x2));
       }
   }
-  // The exponentials belong to this phase (the vector unit's turn): passing the packed probabilities through an
-  // empty asm statement makes them exist here; otherwise the compiler sinks them behind the barrier, next to the
-  // products that use them.
+  // Passing the packed probabilities through an empty asm statement makes them exist here, in one run of vector
+  // work; otherwise the compiler sinks each exponential down to the product that uses it, between the LDS reads
+  // and matrix instructions whose order the P V loop pins.
 #pragma unroll
   for (int t = 0; t < QB; ++t)
 #pragma unroll

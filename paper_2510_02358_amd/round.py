@@ -221,7 +221,7 @@ class SpecDecoder:
         if n_pend + k > ds.DS_MAX_ROWS:
             raise ValueError(f"{n_pend} pending + {k} draft rows exceed {ds.DS_MAX_ROWS} rows per call")
         lat = (self.cand_id, self.cand_logp, self.cand_cnt, self.eos_logp, self.lse)
-        sizes = ds.ds_refine_update_sizes(k, p.refine_steps)
+        sizes = ds.ds_refine_update_sizes(k, p.refine_steps) if p.refine_steps > 1 else [k]
         logits_out = self.d_logits if (self.keep_draft_logits or uniforms is not None) else None
         if len(sizes) <= 1:
             ds.ds_draft_block(self.d.handle, self.pending_dev, n_pend, k, self.mask_id, self.hidden, self.d.ws, stream)

@@ -166,3 +166,62 @@ def test_peaky_attention_block_rows_stay_bit_identical_to_one_row_decoding():
                 assert np.array_equal(one[0], whole[r]), (n_prefix, r)
     finally:
         gm.close()
+
+
+# A narrow model whose gate / up product is as wide as the 32B shape's (N = 2 x 27648): wide enough to run unsplit, so
+# the library packs gate and up with alternating blocks and applies SwiGLU in the product's epilogue.
+CFG_WIDE_FFN = synth.ModelCfg(n_layers=1, d_model=256, n_q=2, n_kv=1, head_dim=128, d_ffn=27648, vocab=4096,
+                              rope_base=1.0e6, dtype="bf16")
+
+
+def test_fused_gate_up_epilogue_against_the_oracle_and_across_row_counts():
+    """Prefill (70 rows: eight-wavefront workgroups), draft (12 rows), verify (40 rows) against the oracle, and the
+    rows of a 71-row block bit-identical to one-row decoding (four- and eight-wavefront workgroups, the same bits)."""
+    cfg = CFG_WIDE_FFN
+    w = synth.make_weights(cfg, 240)
+    synth.randomize_norm_gains(w, 241)
+    prefix = synth.make_prefix(cfg, 70, 242)
+    rng = np.random.default_rng(243)
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        oc = o_model.KVCache(cfg)
+        ref_last = o_model.prefill(cfg, w, oc, prefix)
+        got_last = gm.prefill(prefix)
+        ref_d = o_model.lm_head(w, o_model.draft_block(cfg, w, oc, [5, 6, 7], 9))
+        got_d = gu.from_dev(gm.lm_head(gm.draft([5, 6, 7], 9)))
+        block = rng.integers(0, cfg.n_plain_tokens, 40).astype(np.int32)
+        ref_v = o_model.verify_logits(cfg, w, oc, block)
+        got_v = gm.verify(block)["logits"]
+        errs = [float(np.max(np.abs(a - b))) for a, b in ((got_last, ref_last), (got_d, ref_d), (got_v, ref_v))]
+        print(f"PARITY-COUNTS fused gate/up epilogue: max |dlogit| prefill {errs[0]:.3e}, draft {errs[1]:.3e}, "
+              f"verify {errs[2]:.3e} at logit std {float(np.std(ref_v)):.3f}")
+        assert max(errs) <= 2e-2
+        assert ds.ds_model_overflow_count(gm.handle) == 0
+        big = rng.integers(0, cfg.n_plain_tokens, 71).astype(np.int32)
+        gm.set_kv_len(70)
+        whole = gm.verify(big)["logits"]
+        for r in (0, 1, 16, 40, 64, 70):
+            gm.set_kv_len(70)
+            if r:
+                gm.verify(big[:r], want_logits=False)       # writes the cache rows 70 .. 70 + r - 1
+            gm.set_kv_len(70 + r)
+            one = gm.verify(big[r:r + 1])["logits"]
+            assert np.array_equal(one[0], whole[r]), r
+    finally:
+        gm.close()
+
+
+def test_fused_gate_up_epilogue_counts_what_it_clamps():
+    cfg = CFG_WIDE_FFN
+    w = synth.make_weights(cfg, 250)
+    rng = np.random.default_rng(251)
+    for lw in w["layers"]:
+        for name in ("w_gate", "w_up"):
+            lw[name] = synth.round_to_bf16((rng.standard_normal(lw[name].shape) * 10.0).astype(np.float32))
+    gm = gu.GpuModel(cfg, w, 128)
+    try:
+        last = gm.prefill(synth.make_prefix(cfg, 20, 252))
+        assert np.all(np.isfinite(last))
+        assert ds.ds_model_overflow_count(gm.handle) > 0
+    finally:
+        gm.close()
