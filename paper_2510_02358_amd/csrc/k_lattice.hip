@@ -444,14 +444,17 @@ __global__ __launch_bounds__(256) void accept_tiles_kernel(int rows, int rows_pa
       }
     const int o = accept_out_index(sq, r);
     if (o >= 0) argmax_out[o] = eid;
+    // The row's result goes out as a device-scope (write-through) store and has completed before the arrival is
+    // counted; the last workgroup reads the results with device-scope loads.  No fence: a device-scope fence writes
+    // back and invalidates a whole L2, which costs more than this kernel's work.
     __hip_atomic_store(&am[r], eid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __threadfence();  // the row's result is visible device-wide before the arrival is counted
-    const uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    asm volatile("" ::: "memory");
+    const uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     last = seen == (uint32_t)rows - 1u;
   }
   __syncthreads();
   if (!last) return;
-  __threadfence();
   __shared__ int32_t ams[DS_MAX_ROWS];
   for (int i = threadIdx.x; i < rows; i += (int)blockDim.x)
     ams[i] = __hip_atomic_load(&am[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
