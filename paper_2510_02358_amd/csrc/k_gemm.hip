@@ -191,14 +191,26 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   u32x4 xreg[kXPer];
   f16x8 areg[kStages][NB][kKSC];
 
+  // Source offset of this thread's piece p within a chunk (halfs; the chunk offset is added per load).  A piece
+  // holds 8 columns of one row (row = piece & 15 of its row block).  Rows past M are padding whose products are never
+  // stored: their lanes read the block's last real row instead, which lands in the sectors the real rows fetch
+  // anyway, so that a 33-row call moves 36 rows' worth of X through L2, not 48.  (Branch-free: the same loads issue.)
+  size_t x_off[kXPer];
+#pragma unroll
+  for (int p = 0; p < kXPer; ++p) {
+    int piece = threadIdx.x + p * kThreads;
+    if (kXTail && piece >= kPieces) piece = kPieces - 1;
+    const int mb = piece / (kKSC * 64), rest = piece - mb * (kKSC * 64);
+    const int j = rest & 15;
+    int j_last = M - 1 - mb * 16;  // last real row of this block (>= 15: a full block)
+    j_last = j_last < 0 ? 0 : j_last;
+    const int jc = j < j_last ? j : j_last;
+    x_off[p] = (size_t)mb * ksteps * 512 + (size_t)(rest - j + jc) * 8;
+  }
   auto load_x = [&](int c) {
 #pragma unroll
-    for (int p = 0; p < kXPer; ++p) {
-      int piece = threadIdx.x + p * kThreads;
-      if (kXTail && piece >= kPieces) piece = kPieces - 1;
-      const int mb = piece / (kKSC * 64), rest = piece - mb * (kKSC * 64);
-      xreg[p] = *reinterpret_cast<const u32x4*>(xt + ((size_t)mb * ksteps + (size_t)c * kKSC) * 512 + rest * 8);
-    }
+    for (int p = 0; p < kXPer; ++p)
+      xreg[p] = *reinterpret_cast<const u32x4*>(xt + x_off[p] + (size_t)c * kKSC * 512);
   };
   auto store_x = [&](int buf) {
 #pragma unroll
