@@ -7,6 +7,7 @@ PyTorch is used for device memory only.
 """
 from __future__ import annotations
 
+import ctypes
 import time
 from dataclasses import dataclass
 from typing import List, Optional
@@ -98,6 +99,24 @@ class RoundParams:
     refine_steps: int = 1  # drafter passes per round (1: the single-pass round)
 
 
+_hip_rt = None
+
+
+def _hip_memcpy_h2d_async(dst_dev: int, src_pinned: int, n_bytes: int) -> None:
+    """hipMemcpyAsync(host -> device) on the default stream, called directly: the per-round staging copy is on the
+    host's critical path between a verdict and the next round's first launch, where a tensor-level copy_ costs several
+    microseconds of dispatch."""
+    global _hip_rt
+    if _hip_rt is None:
+        _hip_rt = ctypes.CDLL("libamdhip64.so")
+        _hip_rt.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
+                                           ctypes.c_void_p]
+        _hip_rt.hipMemcpyAsync.restype = ctypes.c_int
+    rc = _hip_rt.hipMemcpyAsync(dst_dev, src_pinned, n_bytes, 1, None)
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpyAsync failed with code {rc}")
+
+
 class SpecDecoder:
     """One drafter + one verifier on one GPU, both caches holding the same prefix."""
 
@@ -163,7 +182,10 @@ class SpecDecoder:
         self.alpha = torch.zeros(k_cap, dtype=f32, device=DEV)
         self.host = torch.empty(2 + ds.DS_MAX_ROWS, dtype=i32).pin_memory()
         self.host_np = self.host.numpy()
+        self._host_ptr, self._io_ptr = self.host.data_ptr(), self.io.data_ptr()
         self.host_out = torch.empty(self.io.numel() - self._out0, dtype=i32).pin_memory()   # io[_out0:] as the host sees it
+        self.host_out_np = self.host_out.numpy()
+        self._cand_host_ptr = self.host_out.data_ptr() + 4 * (self._cand_at - self._out0)
         self.host_raw0 = torch.empty(k_cap, dtype=i32).pin_memory()          # refinement rounds: the final lattice's top-1
         self.k_cap = k_cap
         self.tokens: List[int] = []
@@ -296,7 +318,7 @@ class SpecDecoder:
         h[:n] = self.pending
         h[n] = self.tokens[-2]
         h[n + 1] = self.tokens[-1]
-        self.io[self._p - n:self._p + 2].copy_(self.host[:n + 2], non_blocking=True)
+        _hip_memcpy_h2d_async(self._io_ptr + 4 * (self._p - n), self._host_ptr, 4 * (n + 2))
 
     def round(self, k: int, inject=None, uniforms=None, lm_events=None) -> dict:
         """One full round including the host read-back, KV commit and the draft-length update."""
@@ -313,16 +335,14 @@ class SpecDecoder:
                            lm_events=lm_events)
         refined = self.lat_used[0] is not self.cand_id
         self.wait_verdict()  # the one host crossing; the path / candidate copy finished during the verifier pass
-        out = self.host_out.numpy()
-        res = self.result.numpy()
+        out, res = self.host_out_np, self.result_np
         n_acc, nxt, eos, plen = int(res[0]), int(res[1]), int(res[2]), int(out[self._len_at - self._out0])
         path = out[:plen].copy()
         # the raw draft (per-position top-1 before the search) as the host read it back: s_t of the controller
         if refined:
             first_eos = ds.ds_adl_first_eos(self.host_raw0, k, 1, self.eos_id)
         else:
-            first_eos = ds.ds_adl_first_eos(self.host_out.data_ptr() + 4 * (self._cand_at - self._out0), k,
-                                            self.p.m_max, self.eos_id)
+            first_eos = ds.ds_adl_first_eos(self._cand_host_ptr, k, self.p.m_max, self.eos_id)
         self.v.set_kv_len(v_len + 1 + n_acc)
         committed = [int(t) for t in path[:n_acc]] + [nxt]
         self.tokens += committed
