@@ -228,6 +228,21 @@ int ds_verify_block(ds_model* verifier, const int32_t* block, int m, const int32
                     int32_t eos_id, int32_t* n_accept, int32_t* next_token, int32_t* argmax,
                     int32_t* eos_accepted, float* logits_out, void* ws, size_t ws_bytes, void* stream);
 
+/* ds_verify_block that also leaves on the device what the next round reads (Alg. 1: the accepted prefix and the
+ * verifier's token are appended to the sequence; the next round drafts after them, scores its first positions
+ * against the last two of them, and verifies a block that starts with the last one), so that a driver sends no
+ * token to the device between rounds.  carry [dev] int32[DS_MAX_ROWS + 2], written by the acceptance kernel
+ * before the verdict: the n_accept + 1 committed tokens (accepted path tokens, then next_token) right-aligned in
+ * carry[0, DS_MAX_ROWS), i.e. at carry + DS_MAX_ROWS - (n_accept + 1) -- the next ds_draft_block's `pending`;
+ * carry[DS_MAX_ROWS] = the token before the last committed one (block[0] if n_accept = 0) and
+ * carry[DS_MAX_ROWS + 1] = next_token -- the next ds_cps_path's ctx, and the next block's first word.
+ * carry may not overlap block, except that carry[DS_MAX_ROWS + 1] may be block[0] (read before it is written).
+ * Everything else as ds_verify_block. */
+int ds_verify_block_carry(ds_model* verifier, const int32_t* block, int m, const int32_t* path_len,
+                          int32_t eos_id, int32_t* n_accept, int32_t* next_token, int32_t* argmax,
+                          int32_t* eos_accepted, float* logits_out, int32_t* carry, void* ws, size_t ws_bytes,
+                          void* stream);
+
 /* Stochastic block verification (Sec. 2 "Parallel verification": acceptance probability
  * alpha_i = min(1, p(y_i) / q(y_i)), residual resampling; Sec. 2 left-to-right proxy q^L2R: with a single
  * drafter pass every in-block position is [MASK], so the drafter row of block position i IS the proxy).

@@ -27,7 +27,7 @@ EXPORTS = [
     "ds_verify_block_stochastic", "ds_draft_block_tokens", "ds_refine_select", "ds_build_lattice_static",
     "ds_refine_update_sizes", "ds_adl_first_eos", "ds_model_overflow_count",
     "ds_kv_create", "ds_kv_destroy", "ds_kv_len", "ds_kv_set_len", "ds_prefill_seq", "ds_draft_block_batch",
-    "ds_verify_block_batch",
+    "ds_verify_block_batch", "ds_verify_block_carry",
 ]
 
 
@@ -108,6 +108,7 @@ def load():
     lib.ds_cps_path.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, vp, i32, vp, vp, vp, vp, sz,
                                 vp]
     lib.ds_verify_block.argtypes = [vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ds_verify_block_carry.argtypes = [vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_sample_workspace_bytes.argtypes = [C.c_int, C.POINTER(sz)]
     lib.ds_accept_stochastic.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_verify_block_stochastic.argtypes = [vp, vp, C.c_int, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -334,6 +335,13 @@ def ds_verify_block(model: int, block, m: int, path_len, eos_id: int, n_accept, 
     _check(load().ds_verify_block(model, _ptr(block), m, _ptr(path_len), eos_id, _ptr(n_accept), _ptr(next_token),
                                   _ptr(argmax), _ptr(eos_accepted), _ptr(logits_out), _ptr(ws), _nbytes(ws),
                                   _stream(stream)))
+
+
+def ds_verify_block_carry(model: int, block, m: int, path_len, eos_id: int, n_accept, next_token, argmax,
+                          eos_accepted, logits_out, carry, ws, stream=None) -> None:
+    _check(load().ds_verify_block_carry(model, _ptr(block), m, _ptr(path_len), eos_id, _ptr(n_accept),
+                                        _ptr(next_token), _ptr(argmax), _ptr(eos_accepted), _ptr(logits_out),
+                                        _ptr(carry), _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def ds_sample_workspace_bytes(m: int) -> int:

@@ -79,9 +79,15 @@ __host__ __device__ static inline int seq_of_row(const SeqTable& t, int r) {
 // Sequences of one verification call as the acceptance kernels see them: sequence s owns rows [row0[s], row0[s] +
 // m[s] + 1) of the verifier pass; its path token n is path_tok[tok_off[s] + n]; its arg-max row i is written to
 // argmax[out_off[s] + i] (rows of no sequence are written nowhere).
+// carry (single-sequence calls; NULL: none): DS_MAX_ROWS + 2 words that receive what the next round reads from the
+// device, namely the n_accept + 1 committed tokens right-aligned in carry[0, DS_MAX_ROWS), then the token before the
+// last committed one and the last committed one.  first: the token of the sequence's row 0 (read before carry is
+// written, so carry[DS_MAX_ROWS + 1] may be that very word).
 struct AcceptSeqs {
   int n_seq;
   int row0[kMaxSeq], m[kMaxSeq], tok_off[kMaxSeq], out_off[kMaxSeq];
+  const int32_t* first;
+  int32_t* carry;
 };
 __host__ __device__ static inline int accept_out_index(const AcceptSeqs& q, int r) {
   for (int s = 0; s < q.n_seq; ++s)

@@ -626,9 +626,11 @@ int draft_impl(ds_model* m, ds_kv* const* kvs, int n_seq, const int32_t* pending
 // block as first = block, path = block + 1.
 int verify_impl(ds_model* m, ds_kv* const* kvs, int n_seq, const int32_t* first, const int32_t* path, int path_stride,
                 int mlen, const int32_t* path_len, int32_t eos_id, int32_t* n_accept, int32_t* next_token,
-                int32_t* argmax, int32_t* eos_accepted, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+                int32_t* argmax, int32_t* eos_accepted, float* logits_out, void* ws, size_t ws_bytes, void* stream,
+                int32_t* carry = nullptr) {
   DS_REQUIRE(m && kvs && first && n_accept && next_token && argmax && eos_accepted, DS_E_INVALID,
              "verifier pass: NULL pointer argument");
+  DS_REQUIRE(!carry || n_seq == 1, DS_E_INVALID, "carry is a single-sequence output");
   DS_REQUIRE(n_seq >= 1 && n_seq <= kMaxSeq, DS_E_SHAPE, "%d sequences outside [1, %d]", n_seq, kMaxSeq);
   DS_REQUIRE(mlen >= 0 && mlen + 1 <= DS_MAX_ROWS, DS_E_SHAPE, "m = %d: m + 1 rows outside [1, %d]", mlen, DS_MAX_ROWS);
   DS_REQUIRE(path || mlen == 0, DS_E_INVALID, "path is NULL while m > 0");
@@ -638,6 +640,8 @@ int verify_impl(ds_model* m, ds_kv* const* kvs, int n_seq, const int32_t* first,
   call.n_seq = n_seq;
   AcceptSeqs aq{};
   aq.n_seq = n_seq;
+  aq.first = first;
+  aq.carry = carry;
   // token sources: tok_a = first (one per sequence), tok_b = path rows; the table's offsets advance by n_a and by
   // n_rows - n_a per sequence, so a dense path array needs path_stride == mlen (checked by the callers)
   for (int s = 0; s < n_seq; ++s) call.seq[s] = FwdSeq{kvs[s], 1, rows_s, rows_s, rows_s};
@@ -812,6 +816,15 @@ int ds_verify_block(ds_model* m, const int32_t* block, int mlen, const int32_t* 
   ds_kv* kv = &m->self;
   return verify_impl(m, &kv, 1, block, block + 1, mlen, mlen, path_len, eos_id, n_accept, next_token, argmax,
                      eos_accepted, logits_out, ws, ws_bytes, stream);
+}
+
+int ds_verify_block_carry(ds_model* m, const int32_t* block, int mlen, const int32_t* path_len, int32_t eos_id,
+                          int32_t* n_accept, int32_t* next_token, int32_t* argmax, int32_t* eos_accepted,
+                          float* logits_out, int32_t* carry, void* ws, size_t ws_bytes, void* stream) {
+  DS_REQUIRE(m && block && carry, DS_E_INVALID, "ds_verify_block_carry: NULL pointer argument");
+  ds_kv* kv = &m->self;
+  return verify_impl(m, &kv, 1, block, block + 1, mlen, mlen, path_len, eos_id, n_accept, next_token, argmax,
+                     eos_accepted, logits_out, ws, ws_bytes, stream, carry);
 }
 
 int ds_verify_block_batch(ds_model* m, ds_kv* const* seqs, int n_seq, const int32_t* first, const int32_t* path,

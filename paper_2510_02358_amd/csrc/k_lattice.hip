@@ -344,6 +344,14 @@ __device__ __forceinline__ void write_verdicts(const AcceptSeqs& sq, const int32
     n_accept[s] = n;
     next_token[s] = nxt;
     eos_flag[s] = eos;
+    if (sq.carry && s == 0) {
+      const int32_t before_last = n > 0 ? tok[n - 1] : sq.first[0];
+      int32_t* c = sq.carry + DS_MAX_ROWS - 1 - n;
+      for (int i = 0; i < n; ++i) c[i] = tok[i];
+      c[n] = nxt;
+      c[n + 1] = before_last;
+      c[n + 2] = nxt;
+    }
   }
   __threadfence_system();
   for (int s = 0; s < sq.n_seq; ++s) eos_accepted[s] = eos_flag[s] ? 1 : 0;

@@ -190,6 +190,7 @@ class SpecDecoder:
         self.k_cap = k_cap
         self.tokens: List[int] = []
         self.pending: List[int] = []
+        self._carried = False  # True: the device already holds the next round's pending tokens and context
 
     def close(self) -> None:
         if self.proxy:
@@ -220,6 +221,7 @@ class SpecDecoder:
         first = int(cid.item())
         self.tokens = [int(x) for x in prefix] + [first]
         self.pending = [first]
+        self._carried = False
 
     def enqueue_round(self, k: int, stream=None, inject=None, uniforms=None, readback: bool = False,
                       lm_events=None) -> None:
@@ -276,8 +278,12 @@ class SpecDecoder:
             if lat[0] is not self.cand_id:  # refinement rounds keep the final lattice elsewhere
                 self.host_raw0[:k].copy_(lat[0][:k, 0], non_blocking=True)
         if uniforms is None:
-            ds.ds_verify_block(self.v.handle, self.block, k, self.path_len, self.eos_id, self.result[0:1],
-                               self.result[1:2], self.argmax, self.result[2:3], self.v_logits, self.v.ws, stream)
+            # the acceptance kernel itself leaves the committed tokens where the next round's drafter pass, path
+            # search and verify block read them (io[: P + 2]): no token travels host -> device between rounds
+            ds.ds_verify_block_carry(self.v.handle, self.block, k, self.path_len, self.eos_id, self.result[0:1],
+                                     self.result[1:2], self.argmax, self.result[2:3], self.v_logits, self.io,
+                                     self.v.ws, stream)
+            self._carried = True
         else:
             # the drafter rows of the path positions: with one drafter pass, the logits the lattice was built from
             ds.ds_verify_block_stochastic(self.v.handle, self.block, k, self.path_len, self.d_logits, uniforms,
@@ -313,6 +319,7 @@ class SpecDecoder:
     def stage_inputs(self) -> None:
         """Host -> device: pending tokens and the proxy context (whose newer token is also the first row of the
         verify block): a few ints, one async copy."""
+        self._carried = False
         n = len(self.pending)
         h = self.host_np
         h[:n] = self.pending
@@ -322,7 +329,9 @@ class SpecDecoder:
 
     def round(self, k: int, inject=None, uniforms=None, lm_events=None) -> dict:
         """One full round including the host read-back, KV commit and the draft-length update."""
-        self.stage_inputs()
+        if not self._carried:  # first round, or the last verdict came from a call that carries nothing
+            self.stage_inputs()
+        self._carried = False
         v_len = self.v.kv_len
         if uniforms is not None:
             if self.p.refine_steps > 1:

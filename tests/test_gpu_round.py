@@ -124,6 +124,101 @@ def test_forced_greedy_path_is_fully_accepted_on_gpu():
         vm.close()
 
 
+@pytest.mark.parametrize("cfg_name", ["f32", "bf16"])
+def test_verify_carry_leaves_the_next_rounds_inputs_on_the_device(cfg_name):
+    """ds_verify_block_carry returns what ds_verify_block returns and writes the committed tokens, right-aligned,
+    the token before the last one and the last one into its carry buffer (nothing else of it), for no / some / all
+    path tokens accepted and for a path cut by path_len; float32 model (arg-max scan) and bf16 model (per-tile
+    records).  Then whole rounds: after every round of the driver, the device holds exactly what the host would
+    have staged."""
+    from paper_2510_02358_amd import binding as ds
+    cfg = synth.CFG_TINY if cfg_name == "f32" else synth.ModelCfg(
+        n_layers=2, d_model=256, n_q=4, n_kv=2, head_dim=128, d_ffn=512, vocab=4096, rope_base=1.0e6, dtype="bf16")
+    dw, vw = synth.make_weights(cfg, 0), synth.make_weights(cfg, 1)
+    prefix = synth.make_prefix(cfg, 90, 11)
+    k, P = 6, ds.DS_MAX_ROWS
+    dm, vm = rnd.DeviceModel(cfg, dw, 256), rnd.DeviceModel(cfg, vw, 256)
+    dec = None
+    try:
+        ds.ds_prefill(vm.handle, rnd.upload(np.asarray(prefix, dtype=np.int32)), len(prefix), None, vm.ws)
+        res = torch.zeros(3, dtype=torch.int32, device=rnd.DEV)
+        am = torch.empty(k + 1, dtype=torch.int32, device=rnd.DEV)
+
+        def plain(block, pl):
+            ds.ds_verify_block(vm.handle, rnd.upload(block), k, pl, cfg.eos_id, res[0:1], res[1:2], am, res[2:3],
+                               None, vm.ws)
+            torch.cuda.synchronize()
+            return res.cpu().numpy().copy(), am.cpu().numpy().copy()
+
+        # the verifier's own greedy chain after the prefix's last token, one more settled position per call
+        chain = np.full(k + 1, 3, dtype=np.int32)
+        chain[0] = prefix[-1]
+        for i in range(k):
+            chain[i + 1] = plain(chain, None)[1][i]
+        cases = []
+        for n_keep, pl in ((k, None), (3, None), (0, None), (k, 2)):
+            block = chain.copy()
+            if n_keep < k:
+                block[n_keep + 1] = (block[n_keep + 1] + 1) % cfg.n_plain_tokens      # first rejected position
+            cases.append((block, pl))
+        for block, pl in cases:
+            pl_dev = rnd.upload(np.array([pl], dtype=np.int32)) if pl is not None else None
+            want, want_am = plain(block, pl_dev)
+            n, nxt = int(want[0]), int(want[1])
+            assert n == (pl if pl is not None else int(np.sum(np.cumprod(block[1:] == chain[1:]))))
+            carry = torch.full((P + 2,), -7, dtype=torch.int32, device=rnd.DEV)
+            res.zero_(); am.zero_()
+            ds.ds_verify_block_carry(vm.handle, rnd.upload(block), k, pl_dev, cfg.eos_id, res[0:1], res[1:2], am,
+                                     res[2:3], None, carry, vm.ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(res.cpu().numpy(), want) and np.array_equal(am.cpu().numpy(), want_am)
+            c = carry.cpu().numpy()
+            assert np.all(c[:P - 1 - n] == -7)
+            assert list(c[P - 1 - n:P]) == list(block[1:1 + n]) + [nxt]
+            assert c[P] == (block[n] if n > 0 else block[0]) and c[P + 1] == nxt
+            # the driver's layout: the block starts at the carry buffer's last word
+            io = torch.full((P + 2 + k,), -7, dtype=torch.int32, device=rnd.DEV)
+            io[P + 1:] = rnd.upload(block)
+            ds.ds_verify_block_carry(vm.handle, io[P + 1:], k, pl_dev, cfg.eos_id, res[0:1], res[1:2], am, res[2:3],
+                                     None, io, vm.ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(res.cpu().numpy(), want)
+            assert np.array_equal(io[:P + 2].cpu().numpy(), c)
+            assert np.array_equal(io[P + 2:].cpu().numpy(), block[1:])
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_verify_block_carry(vm.handle, rnd.upload(chain), k, None, cfg.eos_id, res[0:1], res[1:2], am,
+                                     res[2:3], None, None, vm.ws)
+        assert e.value.code == ds.DS_E_INVALID
+
+        # whole rounds, some of them with part of the path overwritten by the verifier's chain (accepted tokens)
+        vm.set_kv_len(0)
+        params = rnd.RoundParams(m_max=4, tau=0.9, beam=4, lam=0.5, k_min=2, k_max=12, delta=2.0, rho=0.5)
+        dec = rnd.SpecDecoder(dm, vm, synth.make_ngram_table(3), synth.NGRAM_LOG2_SIZE, params, k_cap=16)
+        dec.start(prefix)
+        staged = 0
+        for t in range(5):
+            inject = None
+            if t in (1, 3) and cfg_name == "f32":
+                # tokens the verifier will accept: its greedy continuation of the committed stream
+                nxt_tokens = o_round.ar_greedy(cfg, vw, dec.tokens, 3)
+                inject = (rnd.upload(np.asarray(nxt_tokens, dtype=np.int32)), 2)
+            was_carried = dec._carried
+            got = dec.round(8, inject=inject)
+            staged += 0 if was_carried else 1
+            n_p = len(dec.pending)
+            io = dec.io[:P + 2].cpu().numpy()
+            assert dec._carried and n_p == got["n_accept"] + 1
+            assert list(io[P - n_p:P]) == dec.pending
+            assert io[P] == dec.tokens[-2] and io[P + 1] == dec.tokens[-1]
+            if inject is not None:
+                assert got["n_accept"] >= 2
+        assert staged == 1          # the first round only
+    finally:
+        if dec is not None:
+            dec.close()
+        dm.close(); vm.close()
+
+
 def test_gpu_ar_greedy_matches_oracle_and_injected_rounds_are_lossless():
     """The GPU's one-token-per-step greedy decode equals the oracle's; speculative rounds whose path is
     partly overwritten with that stream (synthetic acceptance) commit exactly the same stream."""
