@@ -18,10 +18,18 @@ Readings fixed here (the paper leaves them open):
     that end in EOS are dropped and the rest go on; after the last position the best is returned;
   * no length normalisation;
   * float32, unfused: term = (lambda*l_dlm) + ((1-lambda)*l_ng); score = score + term.
+
+The same section names a tiny causal LM as the other form of the causal proxy (cps_path_lm): there l_ng of a
+hypothesis' next token w is log softmax(z)[w], z the proxy LM's logits after the committed tokens followed by the
+hypothesis' tokens (a small decoder of the family in model.py that shares the vocabulary); everything else is
+the search above.  The proxy's logits are float32 (model.lm_head); the log-softmax is taken in float64 and rounded
+once to float32.
 """
 from __future__ import annotations
 
 import numpy as np
+
+from . import model  # the decoder a tiny-causal-LM proxy is an instance of
 
 f32 = np.float32
 u32 = np.uint32
@@ -89,6 +97,57 @@ def cps_path(lat: dict, row0: int, k_len: int, beam: int, lam: float, table, log
                     return toks, score, evals
                 continue  # finished but not best: dropped, never expanded
             new_hyps.append((score, toks, hyps[b][3], w))
+        hyps = new_hyps
+    return hyps[0][1], hyps[0][0], evals
+
+
+def proxy_log_probs(logits_row: np.ndarray) -> np.ndarray:
+    """float32 log-softmax of one row of proxy logits: log-sum-exp in float64, one rounding."""
+    z = np.asarray(logits_row, dtype=np.float64)
+    m = z.max()
+    return (z - (m + np.log(np.exp(z - m).sum()))).astype(f32)
+
+
+def cps_path_lm(lat: dict, row0: int, k_len: int, beam: int, lam: float, pcfg, pw, cache, pending,
+                eos_id: int, margins=None):
+    """The search of cps_path with a tiny causal LM as the proxy (Sec. 3.2, "Scoring and search").
+
+    pcfg / pw: the proxy model; cache: its model.KVCache holding the committed tokens EXCEPT the last
+    len(pending) >= 1 of them, which `pending` lists (the last committed token among them).  The pending tokens
+    are appended to `cache` (they are committed); hypotheses work on copies.  Every kept hypothesis is advanced
+    by one proxy step (its own copy of the cache), which yields the distribution its extensions are scored with.
+    Returns (path tokens list, score float32, number of candidate evaluations).
+    """
+    lam = f32(lam)
+    root = proxy_log_probs(model.verify_logits(pcfg, pw, cache, [int(t) for t in pending])[-1])
+    hyps = [(f32(0.0), [], cache, root)]  # score, tokens, proxy cache after the tokens but the last, l_ng row
+    evals = 0
+    for i in range(k_len):
+        cands = position_candidates(lat, row0 + i, eos_id)
+        grown = []
+        for b, (score, toks, _, l_ng_row) in enumerate(hyps):
+            for c, (w, l_dlm) in enumerate(cands):
+                grown.append((f32(score + step_term(lam, l_dlm, f32(l_ng_row[w]))), b, c))
+                evals += 1
+        grown.sort(key=lambda e: (-float(e[0]), e[1], e[2]))
+        kept = grown[:beam]
+        if margins is not None:
+            top = [float(e[0]) for e in grown[:beam + 1]]
+            margins.append(min((a - b for a, b in zip(top, top[1:])), default=float("inf")))
+        new_hyps = []
+        for rank, (score, b, c) in enumerate(kept):
+            w = cands[c][0]
+            toks = hyps[b][1] + [w]
+            if w == eos_id and eos_id >= 0:
+                if rank == 0:
+                    return toks, score, evals
+                continue
+            if i + 1 < k_len:  # the proxy's distribution after this hypothesis: one more causal row
+                child = hyps[b][2].copy()
+                row = proxy_log_probs(model.verify_logits(pcfg, pw, child, [w])[-1])
+            else:
+                child, row = None, None
+            new_hyps.append((score, toks, child, row))
         hyps = new_hyps
     return hyps[0][1], hyps[0][0], evals
 

@@ -10,7 +10,7 @@ import itertools
 import numpy as np
 import pytest
 
-from oracle import cps, lattice
+from oracle import cps, lattice, model
 from paper_2510_02358_amd import synth
 
 f32 = np.float32
@@ -294,3 +294,107 @@ def test_search_margins_are_the_gaps_at_the_beam_boundary():
     cps.cps_path(lat, 0, 1, 4, 1.0, None, 0, [0, 0], -1, margins=m)
     assert m == [0.5]
     assert cps.cps_path(lat, 0, 2, 2, 1.0, None, 0, [0, 0], -1)[0] == [1, 4]   # unchanged without the list
+
+
+# ------------------------------------------------------------------ path search with a tiny causal LM as the proxy
+
+PROXY = synth.ModelCfg(n_layers=1, d_model=32, n_q=2, n_kv=1, head_dim=16, d_ffn=48, vocab=40, rope_base=1.0e4,
+                       dtype="f32")
+
+
+def _proxy_setup(seed, n_committed=9, n_pending=2):
+    pw = synth.make_weights(PROXY, 70 + seed)
+    for name in ("embed", "lm_head"):            # a proxy with opinions: log-probabilities spread over several nats
+        pw[name] = (pw[name] * 20.0).astype(np.float32)
+    rng = np.random.default_rng(80 + seed)
+    committed = [int(t) for t in rng.integers(0, 36, n_committed)]
+    cache = model.KVCache(PROXY)
+    if n_committed > n_pending:
+        model.prefill(PROXY, pw, cache, committed[:-n_pending])
+    return pw, committed, cache, committed[-n_pending:]
+
+
+def _lm_path_score(lat, pw, committed, toks, picks, lam):
+    """Left-to-right float32 score of one path; the proxy's distributions come from ONE causal pass over
+    committed + path tokens from an empty cache (no incremental cache, no copies)."""
+    seq = list(committed) + list(toks[:-1])
+    y = model.full_sequence(PROXY, pw, np.asarray(seq), np.zeros(len(seq), dtype=bool))
+    logits = model.lm_head(pw, y[len(committed) - 1:])
+    score = f32(0.0)
+    for i, w in enumerate(toks):
+        l_ng = cps.proxy_log_probs(logits[i])[w]
+        one_minus = f32(f32(1.0) - f32(lam))
+        score = f32(score + f32(f32(f32(lam) * picks[i][1]) + f32(one_minus * l_ng)))
+    return score
+
+
+def _enumerate_best_lm(lat, k, lam, pw, committed, eos_id):
+    live = [((), ())]
+    best = None
+    for i in range(k):
+        cands = cps.position_candidates(lat, i, eos_id)
+        ext = []
+        for toks, picks in live:
+            for w, l in cands:
+                t2, p2 = toks + (w,), picks + ((w, l),)
+                ext.append((_lm_path_score(lat, pw, committed, t2, p2, lam), t2, p2))
+        top = max(ext, key=lambda e: float(e[0]))
+        best = top
+        if eos_id >= 0 and top[1][-1] == eos_id:
+            return list(top[1]), top[0]
+        live = [(t, p) for _, t, p in ext if not (eos_id >= 0 and t[-1] == eos_id)]
+    return list(best[1]), best[0]
+
+
+def test_proxy_log_probs_is_a_normalised_log_softmax():
+    z = (np.random.default_rng(0).standard_normal(37) * 4).astype(np.float32)
+    lp = cps.proxy_log_probs(z)
+    assert lp.dtype == np.float32 and abs(float(np.exp(lp.astype(np.float64)).sum()) - 1.0) < 1e-6
+    assert np.argmax(lp) == np.argmax(z) and np.allclose(lp - lp[0], z - z[0], atol=1e-5)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_lm_proxy_wide_beam_equals_exhaustive_enumeration_from_scratch(seed):
+    rng = np.random.default_rng(100 + seed)
+    k, m_max, vocab = 3, 3, PROXY.vocab
+    eos = vocab - 2 if seed % 2 == 0 else -1
+    lat, _ = _random_lattice(rng, k, m_max, vocab, eos)
+    lat["cand_cnt"][:] = rng.integers(2, m_max + 1, size=k)
+    if eos >= 0:
+        lat["eos_logp"][:] = lat["cand_logp"][:, 0] - f32(0.05)
+    pw, committed, cache, pending = _proxy_setup(seed)
+    before = cache.length
+    toks, score, evals = cps.cps_path_lm(lat, 0, k, (m_max + 1) ** k, 0.4, PROXY, pw, cache, pending, eos)
+    assert cache.length == before + len(pending)          # the pending tokens are committed, nothing else
+    ref_toks, ref_score = _enumerate_best_lm(lat, k, 0.4, pw, committed, eos)
+    assert toks == ref_toks and abs(float(score) - float(ref_score)) <= 2e-6 * max(1.0, abs(float(ref_score)))
+    assert evals >= len(toks)
+
+
+def test_lm_proxy_with_lambda_one_is_the_proxy_free_search():
+    rng = np.random.default_rng(120)
+    lat, _ = _random_lattice(rng, 6, 4, PROXY.vocab, 38)
+    pw, _, cache, pending = _proxy_setup(5)
+    a = cps.cps_path_lm(lat, 0, 6, 3, 1.0, PROXY, pw, cache, pending, 38)
+    b = cps.cps_path(lat, 0, 6, 3, 1.0, None, LOG2, (0, 0), 38)
+    assert a[0] == b[0] and a[1] == b[1] and a[2] == b[2]
+
+
+def test_lm_proxy_changes_the_path_and_the_committed_tokens_matter():
+    rng = np.random.default_rng(121)
+    lat, _ = _random_lattice(rng, 6, 4, PROXY.vocab, -1)
+    lat["cand_logp"][:] = f32(-1.0)                        # the drafter is indifferent: the proxy decides
+    found = set()
+    for seed in range(4):
+        pw, _, cache, pending = _proxy_setup(seed)
+        toks, score, _ = cps.cps_path_lm(lat, 0, 6, 4, 0.5, PROXY, pw, cache, pending, -1)
+        # indifferent drafter: the score is lam * (-k) + (1 - lam) * sum of proxy log-probabilities
+        assert float(score) < 0.5 * -6.0
+        found.add(tuple(toks))
+    assert len(found) > 1
+    pw, committed, cache, pending = _proxy_setup(0)
+    base = cps.cps_path_lm(lat, 0, 6, 4, 0.5, PROXY, pw, cache, pending, -1)
+    other = model.KVCache(PROXY)
+    model.prefill(PROXY, pw, other, [(t + 7) % 36 for t in committed[:-2]])
+    moved = cps.cps_path_lm(lat, 0, 6, 4, 0.5, PROXY, pw, other, pending, -1)
+    assert base[1] != moved[1]                             # same pending tokens, another history: another score
