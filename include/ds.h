@@ -209,6 +209,39 @@ int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* c
                 const ds_ngram* proxy, const int32_t* ctx, int32_t eos_id, int32_t* path,
                 int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, void* stream);
 
+/* Step 3 with the other causal proxy the paper names: a tiny causal LM instead of the n-gram table
+ * (Sec. 3.2 "Scoring and search": the path score mixes the drafter's log-score with a small causal proxy,
+ * an n-gram or a tiny causal LM).  Here l_ng of a hypothesis' next token w is log softmax(z)[w] (float32), z the
+ * logits of the proxy model after the committed tokens followed by the hypothesis' tokens; the search itself
+ * (candidates, EOS rule, ordering, float32 score arithmetic) is that of ds_cps_path.  One sequence per call.
+ *
+ * The proxy is any ds_model that shares the vocabulary (a small one: it takes one step per depth and beam slot).
+ * ds_lmproxy_create binds it to `mem` [dev], ds_lmproxy_bytes(cfg of the model, beam) bytes, 256-byte aligned,
+ * caller-owned: 2 * beam KV caches (every beam slot is a sequence of its own; the beam's reordering copies the
+ * block region of a parent's cache) and the search state.  The model's own cache is not used.  `beam` (at most 8)
+ * is the widest beam later calls may ask for.
+ * ds_lmproxy_prefill appends n committed tokens [dev] to the proxy's history (chunked forward; setup path).
+ * ds_lmproxy_len / _set_len: committed length; it can only be cut back (for a replay from an earlier point).
+ * ds_cps_path_lm: pending [dev] int32[n_pend], n_pend >= 1: the tokens committed since the proxy's history was
+ * last extended, the last committed token included (what ds_draft_block takes as `pending`); they are appended to
+ * the history.  The lattice arguments, eos_id, B, lambda and the outputs path int32[K] (tail beyond the length
+ * = -1), path_len int32[1], path_score float[1] [dev] are those of ds_cps_path with batch = 1.
+ * 1 <= K <= 256, 1 <= B <= beam of the proxy, history + n_pend + K - 1 <= the model's kv_capacity.
+ * ws [dev]: the proxy model's workspace, ds_workspace_bytes(cfg, DS_MAX_ROWS) bytes.
+ * Everything is enqueued on `stream` (K proxy forwards, nothing returns to the host in between); after an
+ * EOS has ended the search the remaining steps run without effect. */
+typedef struct ds_lmproxy ds_lmproxy;
+int ds_lmproxy_bytes(const ds_model_cfg* cfg, int beam, size_t* bytes);
+int ds_lmproxy_create(ds_model* lm, int beam, void* mem, size_t mem_bytes, ds_lmproxy** out);
+void ds_lmproxy_destroy(ds_lmproxy* proxy);
+int ds_lmproxy_prefill(ds_lmproxy* proxy, const int32_t* tokens, int n, void* ws, size_t ws_bytes, void* stream);
+int ds_lmproxy_len(const ds_lmproxy* proxy, int* len);
+int ds_lmproxy_set_len(ds_lmproxy* proxy, int len);
+int ds_cps_path_lm(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
+                   const float* eos_logp, int K, int M_max, int B, float lambda, ds_lmproxy* proxy,
+                   const int32_t* pending, int n_pend, int32_t eos_id, int32_t* path, int32_t* path_len,
+                   float* path_score, void* ws, size_t ws_bytes, void* stream);
+
 /* Step 4, parallel verification with greedy acceptance (Sec. 2 "Parallel verification" and
  * "Accepted prefix length"; Alg. 1 step (3); greedy verification as in Sec. 4).
  * block [dev] int32[m + 1] = last committed token followed by the path (ids outside [0, vocab) are

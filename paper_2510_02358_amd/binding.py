@@ -28,6 +28,8 @@ EXPORTS = [
     "ds_refine_update_sizes", "ds_adl_first_eos", "ds_model_overflow_count",
     "ds_kv_create", "ds_kv_destroy", "ds_kv_len", "ds_kv_set_len", "ds_prefill_seq", "ds_draft_block_batch",
     "ds_verify_block_batch", "ds_verify_block_carry",
+    "ds_lmproxy_bytes", "ds_lmproxy_create", "ds_lmproxy_destroy", "ds_lmproxy_prefill", "ds_lmproxy_len",
+    "ds_lmproxy_set_len", "ds_cps_path_lm",
 ]
 
 
@@ -108,6 +110,15 @@ def load():
     lib.ds_cps_path.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, vp, i32, vp, vp, vp, vp, sz,
                                 vp]
     lib.ds_verify_block.argtypes = [vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ds_lmproxy_bytes.argtypes = [vp, C.c_int, C.POINTER(sz)]
+    lib.ds_lmproxy_create.argtypes = [vp, C.c_int, vp, sz, C.POINTER(vp)]
+    lib.ds_lmproxy_destroy.argtypes = [vp]
+    lib.ds_lmproxy_destroy.restype = None
+    lib.ds_lmproxy_prefill.argtypes = [vp, vp, C.c_int, vp, sz, vp]
+    lib.ds_lmproxy_len.argtypes = [vp, C.POINTER(C.c_int)]
+    lib.ds_lmproxy_set_len.argtypes = [vp, C.c_int]
+    lib.ds_cps_path_lm.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_float, vp, vp, C.c_int, i32, vp, vp,
+                                   vp, vp, sz, vp]
     lib.ds_verify_block_carry.argtypes = [vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_sample_workspace_bytes.argtypes = [C.c_int, C.POINTER(sz)]
     lib.ds_accept_stochastic.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -335,6 +346,43 @@ def ds_verify_block(model: int, block, m: int, path_len, eos_id: int, n_accept, 
     _check(load().ds_verify_block(model, _ptr(block), m, _ptr(path_len), eos_id, _ptr(n_accept), _ptr(next_token),
                                   _ptr(argmax), _ptr(eos_accepted), _ptr(logits_out), _ptr(ws), _nbytes(ws),
                                   _stream(stream)))
+
+
+def ds_lmproxy_bytes(cfg, beam: int) -> int:
+    out = C.c_size_t(0)
+    _check(load().ds_lmproxy_bytes(C.byref(cfg), beam, C.byref(out)))
+    return out.value
+
+
+def ds_lmproxy_create(model: int, beam: int, mem) -> int:
+    out = C.c_void_p()
+    _check(load().ds_lmproxy_create(model, beam, _ptr(mem), _nbytes(mem), C.byref(out)))
+    return out.value
+
+
+def ds_lmproxy_destroy(proxy: int) -> None:
+    load().ds_lmproxy_destroy(proxy)
+
+
+def ds_lmproxy_prefill(proxy: int, tokens, n: int, ws, stream=None) -> None:
+    _check(load().ds_lmproxy_prefill(proxy, _ptr(tokens), n, _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ds_lmproxy_len(proxy: int) -> int:
+    out = C.c_int(0)
+    _check(load().ds_lmproxy_len(proxy, C.byref(out)))
+    return out.value
+
+
+def ds_lmproxy_set_len(proxy: int, n: int) -> None:
+    _check(load().ds_lmproxy_set_len(proxy, n))
+
+
+def ds_cps_path_lm(cand_id, cand_logp, cand_cnt, eos_logp, k: int, m_max: int, beam: int, lam: float, proxy: int,
+                   pending, n_pend: int, eos_id: int, path, path_len, path_score, ws, stream=None) -> None:
+    _check(load().ds_cps_path_lm(_ptr(cand_id), _ptr(cand_logp), _ptr(cand_cnt), _ptr(eos_logp), k, m_max, beam, lam,
+                                 proxy, _ptr(pending), n_pend, eos_id, _ptr(path), _ptr(path_len), _ptr(path_score),
+                                 _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def ds_verify_block_carry(model: int, block, m: int, path_len, eos_id: int, n_accept, next_token, argmax,

@@ -872,3 +872,213 @@ int ds_verify_block_stochastic(ds_model* m, const int32_t* block, int mlen, cons
 }
 
 }  // extern "C"
+
+// ---- path search with a tiny causal LM as the causal proxy (Sec. 3.2, "Scoring and search") -----------------------
+//
+// The proxy is a ds_model; every beam slot is one sequence of its forward calls, with a KV cache of its own.  Two
+// sets of `beam` caches alternate: the beam step names each new slot's parent, the block-region keys / values of the
+// parent (in the set the last proxy step wrote) are copied into the slot's cache of the other set, and the next
+// proxy step runs there.  All caches hold the same committed tokens; the state the search kernels keep between
+// the steps lives behind them in the caller's buffer.
+struct ds_lmproxy {
+  ds_model* lm;
+  int beam;
+  ds_kv kv[2][kMaxSeq];
+  LmSearchState* state;
+  int len;  // committed tokens (every cache)
+};
+
+namespace {
+
+size_t lmproxy_bytes_of(const ds_model_cfg& c, int beam) {
+  return (size_t)4 * beam * align_up(kv_bytes_of(c), 256) + align_up(sizeof(LmSearchState), 256);
+}
+
+// Bytes of one (layer, head) cache segment that hold positions [p0, p1): whole 64-key chunks for the half layout
+// (the other positions of a chunk are either committed, hence equal in every cache, or not yet written).
+void kv_byte_range(const ds_model_cfg& c, int p0, int p1, size_t* lo, size_t* hi) {
+  if (c.dtype == DS_BF16) {
+    const size_t chunk = (size_t)64 * c.head_dim * 2;
+    *lo = (size_t)(p0 >> 6) * chunk;
+    *hi = (size_t)((p1 + 63) >> 6) * chunk;
+  } else {
+    *lo = (size_t)p0 * c.head_dim * 4;
+    *hi = (size_t)p1 * c.head_dim * 4;
+  }
+}
+
+int lmproxy_copy(ds_lmproxy* p, const KvCopyPlan& plan, const int32_t* par, const LmSearchState* st, int p0, int p1,
+                 hipStream_t s) {
+  if (p1 <= p0) return DS_OK;
+  const ds_model_cfg& c = p->lm->cfg;
+  size_t lo = 0, hi = 0;
+  kv_byte_range(c, p0, p1, &lo, &hi);
+  const size_t head_bytes = (size_t)c.kv_capacity * c.head_dim * p->lm->esize;
+  return launch_kv_copy(plan, par, st, c.n_layers * c.n_kv, head_bytes, lo, hi, s);
+}
+
+// Positions [p0, p1) of cache (0, 0) into every other cache.
+int lmproxy_broadcast(ds_lmproxy* p, int p0, int p1, hipStream_t s) {
+  KvCopyPlan plan{};
+  plan.n_src = 1;
+  plan.src_k[0] = p->kv[0][0].k;
+  plan.src_v[0] = p->kv[0][0].v;
+  for (int set = 0; set < 2; ++set)
+    for (int d = 0; d < p->beam; ++d) {
+      if (set == 0 && d == 0) continue;
+      plan.dst_k[plan.n_dst] = p->kv[set][d].k;
+      plan.dst_v[plan.n_dst] = p->kv[set][d].v;
+      plan.src_of[plan.n_dst] = 0;
+      ++plan.n_dst;
+    }
+  return lmproxy_copy(p, plan, nullptr, nullptr, p0, p1, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ds_lmproxy_bytes(const ds_model_cfg* cfg, int beam, size_t* bytes) {
+  DS_REQUIRE(bytes, DS_E_INVALID, "bytes is NULL");
+  int rc = validate_cfg(cfg);
+  if (rc) return rc;
+  DS_REQUIRE(beam >= 1 && beam <= kLmBeam, DS_E_SHAPE, "beam %d outside [1, %d]", beam, kLmBeam);
+  *bytes = lmproxy_bytes_of(*cfg, beam);
+  return DS_OK;
+}
+
+int ds_lmproxy_create(ds_model* lm, int beam, void* mem, size_t mem_bytes, ds_lmproxy** out) {
+  DS_REQUIRE(out, DS_E_INVALID, "out is NULL");
+  *out = nullptr;
+  DS_REQUIRE(lm && mem, DS_E_INVALID, "ds_lmproxy_create: NULL pointer argument");
+  DS_REQUIRE(beam >= 1 && beam <= kLmBeam, DS_E_SHAPE, "beam %d outside [1, %d]", beam, kLmBeam);
+  DS_REQUIRE((((uintptr_t)mem) & 255) == 0, DS_E_INVALID, "proxy buffer not 256-byte aligned");
+  const size_t need = lmproxy_bytes_of(lm->cfg, beam);
+  DS_REQUIRE(mem_bytes >= need, DS_E_CAPACITY, "proxy buffer: need %zu bytes, got %zu", need, mem_bytes);
+  ds_lmproxy* p = new (std::nothrow) ds_lmproxy{};
+  DS_REQUIRE(p, DS_E_INVALID, "out of host memory");
+  p->lm = lm;
+  p->beam = beam;
+  char* at = static_cast<char*>(mem);
+  const size_t one = align_up(kv_bytes_of(lm->cfg), 256);
+  for (int set = 0; set < 2; ++set)
+    for (int d = 0; d < beam; ++d) {
+      p->kv[set][d] = ds_kv{lm, at, at + one, 0};
+      at += 2 * one;
+    }
+  p->state = reinterpret_cast<LmSearchState*>(at);
+  p->len = 0;
+  *out = p;
+  return DS_OK;
+}
+
+void ds_lmproxy_destroy(ds_lmproxy* p) { delete p; }
+
+int ds_lmproxy_len(const ds_lmproxy* p, int* len) {
+  DS_REQUIRE(p && len, DS_E_INVALID, "ds_lmproxy_len: NULL pointer argument");
+  *len = p->len;
+  return DS_OK;
+}
+
+int ds_lmproxy_set_len(ds_lmproxy* p, int len) {
+  DS_REQUIRE(p, DS_E_INVALID, "proxy handle is NULL");
+  DS_REQUIRE(len >= 0 && len <= p->len, DS_E_CAPACITY, "proxy length %d outside [0, %d]: it can only be cut back", len,
+             p->len);
+  p->len = len;
+  return DS_OK;
+}
+
+int ds_lmproxy_prefill(ds_lmproxy* p, const int32_t* tokens, int n, void* ws, size_t ws_bytes, void* stream) {
+  DS_REQUIRE(p && tokens, DS_E_INVALID, "ds_lmproxy_prefill: NULL pointer argument");
+  ds_kv* first = &p->kv[0][0];
+  first->len = p->len;
+  int rc = prefill_impl(p->lm, first, tokens, n, nullptr, ws, ws_bytes, stream);
+  if (rc) return rc;
+  if ((rc = lmproxy_broadcast(p, p->len, p->len + n, static_cast<hipStream_t>(stream)))) return rc;
+  p->len += n;
+  return DS_OK;
+}
+
+int ds_cps_path_lm(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt, const float* eos_logp,
+                   int K, int M_max, int B, float lambda, ds_lmproxy* p, const int32_t* pending, int n_pend,
+                   int32_t eos_id, int32_t* path, int32_t* path_len, float* path_score, void* ws, size_t ws_bytes,
+                   void* stream) {
+  DS_REQUIRE(cand_id && cand_logp && cand_cnt && p && pending && path && path_len && path_score, DS_E_INVALID,
+             "ds_cps_path_lm: NULL pointer argument");
+  DS_REQUIRE(eos_logp || eos_id < 0, DS_E_INVALID, "eos_logp is NULL while eos_id >= 0");
+  DS_REQUIRE(K >= 1 && K <= kLmMaxK, DS_E_SHAPE, "K %d outside [1, %d]", K, kLmMaxK);
+  DS_REQUIRE(M_max >= 1 && M_max <= DS_MAX_TOPM, DS_E_SHAPE, "M_max %d outside [1, %d]", M_max, DS_MAX_TOPM);
+  DS_REQUIRE(B >= 1 && B <= p->beam, DS_E_SHAPE, "beam %d outside [1, %d] (the proxy's slot count)", B, p->beam);
+  DS_REQUIRE(!isnan(lambda), DS_E_INVALID, "lambda is NaN");
+  ds_model* m = p->lm;
+  DS_REQUIRE(eos_id < m->cfg.vocab, DS_E_INVALID, "eos_id %d >= the proxy's vocabulary", eos_id);
+  DS_REQUIRE(n_pend >= 1 && n_pend <= DS_MAX_ROWS, DS_E_SHAPE, "n_pend %d outside [1, %d]", n_pend, DS_MAX_ROWS);
+  DS_REQUIRE(p->len + n_pend + K - 1 <= m->cfg.kv_capacity, DS_E_CAPACITY,
+             "proxy KV cache: %d committed + %d pending + %d block tokens exceed capacity %d", p->len, n_pend, K - 1,
+             m->cfg.kv_capacity);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  LmSearchState* state = p->state;
+  int rc;
+  // depth 0: the pending tokens (committed) go through cache (0, 0); the last row's logits are the root's
+  {
+    p->kv[0][0].len = p->len;
+    FwdCall call;
+    call.n_seq = 1;
+    call.seq[0] = FwdSeq{&p->kv[0][0], n_pend, n_pend, n_pend, n_pend - 1};
+    call.tok_a = pending;
+    SeqTable tab;
+    int rows = 0, tail = 0;
+    if ((rc = plan_call(m, call, &tab, &rows, &tail))) return rc;
+    Workspace w;
+    if ((rc = check_ws(m, rows, ws, ws_bytes, &w))) return rc;
+    // the widest later call must fit as well, before anything is enqueued
+    Workspace w_all;
+    if ((rc = check_ws(m, 16 * (B - 1) + 1, ws, ws_bytes, &w_all))) return rc;
+    if ((rc = forward_dispatch(m, w, call, tab, rows, true, st))) return rc;
+    if ((rc = lm_head_rows(m, w.y_tail, 1, w.logits, st))) return rc;
+    if ((rc = lmproxy_broadcast(p, p->len, p->len + n_pend, st))) return rc;
+    p->len += n_pend;
+    if ((rc = launch_lm_init(state, st))) return rc;
+    if ((rc = launch_lm_score(w.logits, 1, m->cfg.vocab, cand_id, cand_cnt, 0, M_max, eos_id, state, st))) return rc;
+    if ((rc = launch_lm_beam_step(state, cand_id, cand_logp, cand_cnt, eos_logp, 0, K, M_max, B, lambda, eos_id, st)))
+      return rc;
+  }
+  const int base = p->len;
+  int cur = 0;
+  for (int i = 1; i < K; ++i) {
+    if (i >= 2) {  // every new slot inherits its parent's block-region keys / values (depths 0 .. i - 2)
+      KvCopyPlan plan{};
+      plan.n_dst = plan.n_src = B;
+      for (int d = 0; d < B; ++d) {
+        plan.dst_k[d] = p->kv[cur ^ 1][d].k;
+        plan.dst_v[d] = p->kv[cur ^ 1][d].v;
+        plan.src_k[d] = p->kv[cur][d].k;
+        plan.src_v[d] = p->kv[cur][d].v;
+      }
+      if ((rc = lmproxy_copy(p, plan, state->par, state, base, base + i - 1, st))) return rc;
+      cur ^= 1;
+    }
+    FwdCall call;
+    call.n_seq = B;
+    for (int d = 0; d < B; ++d) {
+      p->kv[cur][d].len = base + i - 1;
+      call.seq[d] = FwdSeq{&p->kv[cur][d], 1, 1, 1, 0};
+    }
+    call.tok_a = state->tok[i & 1];
+    SeqTable tab;
+    int rows = 0, tail = 0;
+    if ((rc = plan_call(m, call, &tab, &rows, &tail))) return rc;
+    Workspace w;
+    if ((rc = check_ws(m, rows, ws, ws_bytes, &w))) return rc;
+    if ((rc = forward_dispatch(m, w, call, tab, rows, true, st))) return rc;
+    if ((rc = lm_head_rows(m, w.y_tail, B, w.logits, st))) return rc;
+    if ((rc = launch_lm_score(w.logits, B, m->cfg.vocab, cand_id, cand_cnt, i, M_max, eos_id, state, st))) return rc;
+    if ((rc = launch_lm_beam_step(state, cand_id, cand_logp, cand_cnt, eos_logp, i, K, M_max, B, lambda, eos_id, st)))
+      return rc;
+  }
+  for (int set = 0; set < 2; ++set)
+    for (int d = 0; d < p->beam; ++d) p->kv[set][d].len = base;
+  return launch_lm_backtrack(state, K, path, path_len, path_score, st);
+}
+
+}  // extern "C"

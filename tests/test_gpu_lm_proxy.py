@@ -1,0 +1,200 @@
+"""GPU tests of the path search with a tiny causal LM as the causal proxy (ds_cps_path_lm).
+
+(1) Against the oracle (oracle.cps.cps_path_lm) over consecutive calls on one history: same path wherever the oracle's
+    own beam-boundary margins exclude a near-tie, score within the float32 budget; float32 and bf16 proxies, beams
+    1 .. 8, up to 16 + 1 candidates per position, EOS ending the search early, a block region that crosses a
+    64-key cache chunk.
+(2) Against the library itself: the returned score equals the score of the returned path when the proxy reads that
+    path in ONE causal pass (a check of the per-slot caches and their reordering that needs no oracle).
+(3) Argument errors.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cps as o_cps
+from oracle import lattice as o_lattice
+from oracle import model as o_model
+from paper_2510_02358_amd import binding as ds
+from paper_2510_02358_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+f32 = np.float32
+PROXY_F32 = synth.ModelCfg(n_layers=2, d_model=64, n_q=2, n_kv=1, head_dim=32, d_ffn=96, vocab=4096,
+                           rope_base=1.0e4, dtype="f32")
+PROXY_BF16 = synth.ModelCfg(n_layers=2, d_model=256, n_q=4, n_kv=2, head_dim=128, d_ffn=512, vocab=4096,
+                            rope_base=1.0e6, dtype="bf16")
+
+
+def _proxy_weights(cfg, seed, head_scale):
+    w = synth.make_weights(cfg, seed)
+    w["lm_head"] = (w["lm_head"] * f32(head_scale)).astype(np.float32)   # a power of two: stays bf16-exact
+    return w
+
+
+class GpuProxy:
+    def __init__(self, cfg, w, cap, beam):
+        self.gm = gu.GpuModel(cfg, w, cap)
+        self.mem = torch.empty(ds.ds_lmproxy_bytes(self.gm.cfgc, beam), dtype=torch.uint8, device=gu.DEV)
+        self.handle = ds.ds_lmproxy_create(self.gm.handle, beam, self.mem)
+
+    def close(self):
+        ds.ds_lmproxy_destroy(self.handle)
+        self.gm.close()
+
+
+def _lattice(rng, k, m_max, vocab, tau, eos_id, eos_boost_at=None):
+    logits = (rng.standard_normal((k, vocab)) * 2.5).astype(np.float32)
+    if eos_boost_at is not None:
+        logits[eos_boost_at, eos_id] = logits[eos_boost_at].max() + f32(6.0)
+    lat = o_lattice.build_lattice(logits, m_max, tau, eos_id)
+    dev = {n: gu.to_dev(lat[n]) for n in ("cand_id", "cand_logp", "cand_cnt", "eos_logp")}
+    return lat, dev
+
+
+def _gpu_search(px, dev, k, m_max, beam, lam, pending, eos_id):
+    path = torch.full((k,), -5, dtype=torch.int32, device=gu.DEV)
+    plen = torch.zeros(1, dtype=torch.int32, device=gu.DEV)
+    score = torch.zeros(1, dtype=torch.float32, device=gu.DEV)
+    ds.ds_cps_path_lm(dev["cand_id"], dev["cand_logp"], dev["cand_cnt"], dev["eos_logp"], k, m_max, beam, lam,
+                      px.handle, gu.to_dev(np.asarray(pending, dtype=np.int32)), len(pending), eos_id, path, plen,
+                      score, px.gm.ws)
+    torch.cuda.synchronize()
+    n = int(plen.item())
+    p = path.cpu().numpy()
+    assert np.all(p[n:] == -1)
+    return [int(t) for t in p[:n]], float(score.item())
+
+
+def _rescore_on_gpu(px, lat, history, toks, lam, eos_id):
+    """Score of `toks` after `history`, the proxy's rows coming from one causal pass of the library's verifier call
+    on the model's own cache (rows of a block are bit-identical to one-row steps)."""
+    gm = px.gm
+    gm.set_kv_len(0)
+    gm.prefill(np.asarray(history[:-1], dtype=np.int32), want_logits=False)
+    out = gm.verify(np.asarray([history[-1]] + toks[:-1], dtype=np.int32))
+    lp = torch.log_softmax(torch.from_numpy(out["logits"]).double(), dim=-1).numpy()
+    score = f32(0.0)
+    for i, w in enumerate(toks):
+        cands = o_cps.position_candidates(lat, i, eos_id)
+        l_dlm = [l for t, l in cands if t == w][0]
+        score = f32(score + o_cps.step_term(f32(lam), l_dlm, f32(lp[i, w])))
+    return float(score)
+
+
+CASES = [
+    # name, cfg, head scale, k, m_max, tau, beam, lam, eos at depth, history length, score tolerance, margin floor
+    ("f32-b4", PROXY_F32, 8.0, 12, 4, 0.9, 4, 0.5, None, 70, 2e-3, 2e-3),
+    ("f32-b1", PROXY_F32, 8.0, 9, 8, 1.0, 1, 0.3, None, 40, 2e-3, 2e-3),
+    ("f32-b8-m16", PROXY_F32, 8.0, 10, 16, 1.0, 8, 0.6, None, 33, 2e-3, 2e-3),
+    ("f32-eos", PROXY_F32, 8.0, 12, 4, 0.9, 3, 0.5, 5, 50, 2e-3, 2e-3),
+    ("f32-k1", PROXY_F32, 8.0, 1, 4, 1.0, 4, 0.5, None, 20, 2e-3, 2e-3),
+    ("bf16-b4-chunk-crossing", PROXY_BF16, 4.0, 12, 4, 0.9, 4, 0.5, None, 121, 5e-2, 8e-2),
+    ("bf16-b8-eos", PROXY_BF16, 4.0, 14, 8, 1.0, 8, 0.4, 9, 60, 5e-2, 8e-2),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_lm_proxy_search_against_the_oracle_over_consecutive_calls(case):
+    name, cfg, hs, k, m_max, tau, beam, lam, eos_at, n_hist, tol, floor = case
+    rng = np.random.default_rng(700 + [c[0] for c in CASES].index(name))
+    eos_id = cfg.eos_id
+    w = _proxy_weights(cfg, 50, hs)
+    px = GpuProxy(cfg, w, 256, 8)
+    try:
+        history = [int(t) for t in synth.make_prefix(cfg, n_hist, 60)]
+        n_pend = 3
+        ds.ds_lmproxy_prefill(px.handle, gu.to_dev(np.asarray(history[:-n_pend], dtype=np.int32)), n_hist - n_pend,
+                              px.gm.ws)
+        cache = o_model.KVCache(cfg)
+        o_model.prefill(cfg, w, cache, history[:-n_pend])
+        pending = history[-n_pend:]
+        compared = flagged = proxy_decided = 0
+        for call in range(3):
+            lat, dev = _lattice(rng, k, m_max, cfg.vocab, tau, eos_id, eos_at if call != 1 else None)
+            got_toks, got_score = _gpu_search(px, dev, k, m_max, beam, lam, pending, eos_id)
+            assert ds.ds_lmproxy_len(px.handle) == len(history)
+            margins = []
+            ref_toks, ref_score, _ = o_cps.cps_path_lm(lat, 0, k, beam, lam, cfg, w, cache, pending, eos_id, margins)
+            proxy_decided += ref_toks != o_cps.cps_path(lat, 0, k, beam, lam, None, 0, (0, 0), eos_id)[0]
+            assert cache.length == len(history)
+            # the library's own account of the path it returned
+            own = _rescore_on_gpu(px, lat, history, got_toks, lam, eos_id)
+            assert abs(own - got_score) <= 1e-4 * max(1.0, abs(own)), (name, call, own, got_score)
+            near_tie = min(margins) < floor
+            if got_toks == ref_toks:
+                compared += 1
+                assert abs(got_score - float(ref_score)) <= tol * max(1.0, abs(float(ref_score))), (name, call)
+            else:
+                assert near_tie, (name, call, got_toks, ref_toks, min(margins))
+                flagged += 1
+            if eos_at is not None and call != 1:
+                assert len(ref_toks) <= eos_at + 1
+            # commit something and go on: two path tokens and a correction, as a verifier would
+            committed = ref_toks[:2] + [int(rng.integers(0, cfg.n_plain_tokens))]
+            history += committed
+            pending = committed
+        print(f"PARITY-COUNTS lm proxy {name}: calls compared {compared}, near-tie flagged {flagged}, "
+              f"paths the proxy changed {proxy_decided}")
+        assert compared >= 2
+    finally:
+        px.close()
+
+
+def test_lm_proxy_history_can_be_cut_back_and_replayed():
+    cfg = PROXY_F32
+    w = _proxy_weights(cfg, 51, 8.0)
+    px = GpuProxy(cfg, w, 128, 4)
+    try:
+        rng = np.random.default_rng(5)
+        history = [int(t) for t in synth.make_prefix(cfg, 30, 61)]
+        ds.ds_lmproxy_prefill(px.handle, gu.to_dev(np.asarray(history[:-1], dtype=np.int32)), 29, px.gm.ws)
+        lat, dev = _lattice(rng, 8, 4, cfg.vocab, 1.0, cfg.eos_id)
+        first = _gpu_search(px, dev, 8, 4, 4, 0.5, history[-1:], cfg.eos_id)
+        assert ds.ds_lmproxy_len(px.handle) == 30
+        ds.ds_lmproxy_set_len(px.handle, 29)
+        again = _gpu_search(px, dev, 8, 4, 4, 0.5, history[-1:], cfg.eos_id)
+        assert first == again                                        # same bits: nothing of the first call lingers
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_lmproxy_set_len(px.handle, 31)
+        assert e.value.code == ds.DS_E_CAPACITY
+    finally:
+        px.close()
+
+
+def test_lm_proxy_argument_errors():
+    cfg = PROXY_F32
+    px = GpuProxy(cfg, _proxy_weights(cfg, 52, 8.0), 64, 2)
+    try:
+        rng = np.random.default_rng(6)
+        lat, dev = _lattice(rng, 8, 4, cfg.vocab, 1.0, cfg.eos_id)
+        ds.ds_lmproxy_prefill(px.handle, gu.to_dev(np.arange(10, dtype=np.int32)), 10, px.gm.ws)
+        path = torch.zeros(8, dtype=torch.int32, device=gu.DEV)
+        one_i = torch.zeros(1, dtype=torch.int32, device=gu.DEV)
+        one_f = torch.zeros(1, dtype=torch.float32, device=gu.DEV)
+        pend = gu.to_dev(np.array([3], dtype=np.int32))
+
+        def call(k=8, beam=2, n_pend=1, proxy=None):
+            ds.ds_cps_path_lm(dev["cand_id"], dev["cand_logp"], dev["cand_cnt"], dev["eos_logp"], k, 4, beam, 0.5,
+                              px.handle if proxy is None else proxy, pend, n_pend, cfg.eos_id, path, one_i, one_f,
+                              px.gm.ws)
+
+        for kwargs, code in (({"beam": 3}, ds.DS_E_SHAPE),            # wider than the proxy's slot count
+                             ({"n_pend": 0}, ds.DS_E_SHAPE),
+                             ({"k": 257}, ds.DS_E_SHAPE),
+                             ({"k": 56}, ds.DS_E_CAPACITY)):          # 10 + 1 + 55 > 64
+            with pytest.raises(ds.DsError) as e:
+                call(**kwargs)
+            assert e.value.code == code, kwargs
+        assert ds.ds_lmproxy_len(px.handle) == 10                     # refused calls commit nothing
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_lmproxy_create(px.gm.handle, 9, px.mem)
+        assert e.value.code == ds.DS_E_SHAPE
+        call()
+        torch.cuda.synchronize()
+        assert ds.ds_lmproxy_len(px.handle) == 11
+    finally:
+        px.close()
