@@ -673,8 +673,35 @@ def main() -> int:
         variants[f"refine_steps_{steps}"] = {"ms_per_round": round(ms, 4), "rounds_per_s": round(1e3 / ms, 1)}
     ms = time_variant(1, dec.u)
     variants["stochastic_verify"] = {"ms_per_round": round(ms, 4), "rounds_per_s": round(1e3 / ms, 1)}
-    out["variants"] = variants
     dec.close()
+
+    # The path search with a tiny causal LM as the causal proxy instead of the n-gram table: a 2-layer, d = 256
+    # decoder on the shared vocabulary, beam 4 (each beam slot a sequence of its own in the proxy's forward calls).
+    pcfg = synth.ModelCfg(n_layers=2, d_model=256, n_q=4, n_kv=2, head_dim=128, d_ffn=512, vocab=cfg.vocab,
+                          rope_base=1.0e6, dtype="bf16")
+    pm = rnd.DeviceModel(pcfg, synth.make_weights(pcfg, 7), cap)
+    dec_lm = rnd.SpecDecoder(dm, vm, None, 0, rnd.RoundParams(m_max=M_MAX, beam=BEAM, lam=LAM, k_max=K_DRAFT),
+                             k_cap=K_DRAFT, lm_proxy=pm)
+    dec_lm.start(prefix)
+    dec_lm.stage_inputs()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for rep in range(23):
+        if rep == 3:
+            e0.record()
+        dm.set_kv_len(p0)
+        vm.set_kv_len(p0)
+        ds.ds_lmproxy_set_len(dec_lm.lm_proxy, p0)
+        dec_lm.enqueue_round(K_DRAFT)
+        torch.cuda.current_stream().synchronize()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 20.0
+    variants["lm_proxy_path_search"] = {
+        "ms_per_round": round(ms, 4), "rounds_per_s": round(1e3 / ms, 1),
+        "proxy": "2 layers, d 256, 4q/2kv x128, FFN 512, vocab 152064, bf16; beam 4; 32 proxy steps per round"}
+    out["variants"] = variants
+    dec_lm.close()
+    pm.close()
 
     # Batched rounds: n_seq independent sequences (own prefixes, own caches) share every weight stream of the round.
     # Rows per sequence are 1 pending + K; K = 31 at four sequences keeps 4 x 32 rows inside one call (144 rows).

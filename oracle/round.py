@@ -25,13 +25,16 @@ class SpecState:
 
 
 def spec_round(st: SpecState, k_draft: int, m_max: int, tau: float, beam: int, lam: float,
-               table, log2_size: int, forced_path=None, refine_steps: int = 1, uniforms=None) -> dict:
+               table, log2_size: int, forced_path=None, refine_steps: int = 1, uniforms=None,
+               lm_proxy=None) -> dict:
     """One round.  `forced_path` (tests only) replaces the searched path before verification.
 
     refine_steps > 1: the drafter refines the block over several passes and the lattice is frozen row by row
     (refinement update equation).  uniforms (float [k_draft + 1]): verify with the stochastic acceptance rule,
     u[i] deciding draft token i + 1 and u[k_draft] driving the replacement / bonus draw; needs the single-pass
     draft, whose rows are the left-to-right proxy's distributions.
+    lm_proxy = (cfg, weights, KVCache holding the committed tokens but the pending ones): the path search scores with
+    this tiny causal LM instead of the n-gram table (Sec. 3.2, "Scoring and search").
     """
     eos_id = st.dcfg.eos_id
     ctx = st.tokens[-2:]
@@ -44,7 +47,11 @@ def spec_round(st: SpecState, k_draft: int, m_max: int, tau: float, beam: int, l
         hidden = model.draft_block(st.dcfg, st.dw, st.dcache, st.pending, k_draft)
         d_logits = model.lm_head(st.dw, hidden)
         lat = lattice.build_lattice(d_logits, m_max, tau, eos_id)
-    path, score, _ = cps.cps_path(lat, 0, k_draft, beam, lam, table, log2_size, ctx, eos_id)
+    if lm_proxy is not None:
+        path, score, _ = cps.cps_path_lm(lat, 0, k_draft, beam, lam, lm_proxy[0], lm_proxy[1], lm_proxy[2], st.pending,
+                                         eos_id)
+    else:
+        path, score, _ = cps.cps_path(lat, 0, k_draft, beam, lam, table, log2_size, ctx, eos_id)
     if forced_path is not None:
         path = [int(t) for t in forced_path]
     block = [st.tokens[-1]] + path

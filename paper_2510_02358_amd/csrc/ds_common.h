@@ -128,6 +128,7 @@ size_t cps_ws_bytes(int batch, int K, int m_max);
 // ---- path search with a tiny causal LM as the proxy (k_cps_lm.hip) ------------------------------------
 constexpr int kLmBeam = kMaxSeq;  // beam slots: each is one sequence of the proxy's forward call
 constexpr int kLmMaxK = 256;
+constexpr int kLmParts = 32;  // vocabulary segments the log-sum-exp of a proxy row is gathered from
 // Device-resident state of one search (all written by the kernels; the host only passes the pointer on).
 struct LmSearchState {
   int32_t tok[2][kLmBeam];   // [parity][slot] last token of each live hypothesis = input of the next proxy step
@@ -135,7 +136,7 @@ struct LmSearchState {
   int32_t par[kLmBeam];      // slot (of the previous depth) each new slot descends from
   int32_t n_live, finished, out_len;
   float out_score;
-  float lng[kLmBeam][DS_MAX_TOPM + 1];  // proxy log-probability of candidate c after the hypothesis of slot s
+  float2 part[kLmBeam][kLmParts];       // per slot and vocabulary segment: (largest logit, sum of exp(x - largest))
   int32_t bp_tok[kLmMaxK][kLmBeam];     // back-pointers: token and parent slot of (depth, slot)
   int32_t bp_par[kLmMaxK][kLmBeam];
 };
@@ -149,11 +150,10 @@ struct KvCopyPlan {
   int n_dst, n_src;
 };
 int launch_lm_init(LmSearchState* st, hipStream_t s);
-int launch_lm_score(const float* logits, int n_rows, int vocab, const int32_t* cand_id, const int32_t* cand_cnt,
-                    int row, int m_max, int32_t eos_id, LmSearchState* st, hipStream_t s);
-int launch_lm_beam_step(LmSearchState* st, const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
-                        const float* eos_logp, int i, int K, int m_max, int B, float lambda, int32_t eos_id,
-                        hipStream_t s);
+int launch_lm_score(const float* logits, int n_rows, int vocab, LmSearchState* st, hipStream_t s);
+int launch_lm_beam_step(LmSearchState* st, const float* logits, int vocab, const int32_t* cand_id,
+                        const float* cand_logp, const int32_t* cand_cnt, const float* eos_logp, int i, int K,
+                        int m_max, int B, float lambda, int32_t eos_id, hipStream_t s);
 int launch_lm_backtrack(const LmSearchState* st, int K, int32_t* path, int32_t* path_len, float* path_score,
                         hipStream_t s);
 // Bytes [lo, hi) of each of the n_segments (layer, head) segments (head_bytes apart) of every destination cache.

@@ -1039,8 +1039,9 @@ int ds_cps_path_lm(const int32_t* cand_id, const float* cand_logp, const int32_t
     if ((rc = lmproxy_broadcast(p, p->len, p->len + n_pend, st))) return rc;
     p->len += n_pend;
     if ((rc = launch_lm_init(state, st))) return rc;
-    if ((rc = launch_lm_score(w.logits, 1, m->cfg.vocab, cand_id, cand_cnt, 0, M_max, eos_id, state, st))) return rc;
-    if ((rc = launch_lm_beam_step(state, cand_id, cand_logp, cand_cnt, eos_logp, 0, K, M_max, B, lambda, eos_id, st)))
+    if ((rc = launch_lm_score(w.logits, 1, m->cfg.vocab, state, st))) return rc;
+    if ((rc = launch_lm_beam_step(state, w.logits, m->cfg.vocab, cand_id, cand_logp, cand_cnt, eos_logp, 0, K, M_max,
+                                  B, lambda, eos_id, st)))
       return rc;
   }
   const int base = p->len;
@@ -1072,8 +1073,9 @@ int ds_cps_path_lm(const int32_t* cand_id, const float* cand_logp, const int32_t
     if ((rc = check_ws(m, rows, ws, ws_bytes, &w))) return rc;
     if ((rc = forward_dispatch(m, w, call, tab, rows, true, st))) return rc;
     if ((rc = lm_head_rows(m, w.y_tail, B, w.logits, st))) return rc;
-    if ((rc = launch_lm_score(w.logits, B, m->cfg.vocab, cand_id, cand_cnt, i, M_max, eos_id, state, st))) return rc;
-    if ((rc = launch_lm_beam_step(state, cand_id, cand_logp, cand_cnt, eos_logp, i, K, M_max, B, lambda, eos_id, st)))
+    if ((rc = launch_lm_score(w.logits, B, m->cfg.vocab, state, st))) return rc;
+    if ((rc = launch_lm_beam_step(state, w.logits, m->cfg.vocab, cand_id, cand_logp, cand_cnt, eos_logp, i, K, M_max,
+                                  B, lambda, eos_id, st)))
       return rc;
   }
   for (int set = 0; set < 2; ++set)

@@ -5,11 +5,12 @@
 // the committed tokens and the hypothesis' own tokens, so the proxy has to take one step per depth for every live
 // hypothesis.  The host side (ds_cps_path_lm) therefore enqueues, per depth, one proxy forward of one row per beam
 // slot (each slot a sequence with its own KV cache) and three small kernels of this file:
-//   lm_score_kernel      per slot: log-sum-exp of the slot's logits row and the log-probabilities of the depth's
-//                        candidates;
-//   lm_beam_step_kernel  one wavefront: scores every (live hypothesis, candidate) expansion, keeps the best B by
-//                        (score descending, expansion index ascending), applies the EOS rule, and leaves the next
-//                        step's tokens, each new slot's parent and the back-pointers in device memory;
+//   lm_score_kernel      per slot and vocabulary segment: the segment's largest logit and its sum of
+//                        exp(x - largest), the pieces of the row's log-sum-exp;
+//   lm_beam_step_kernel  one wavefront: joins the pieces, scores every (live hypothesis, candidate) expansion with
+//                        log softmax = logit - lse, keeps the best B by (score descending, expansion index
+//                        ascending), applies the EOS rule, and leaves the next step's tokens, each new slot's parent
+//                        and the back-pointers in device memory;
 //   kv_copy_kernel       gives every new slot the block-region keys / values of its parent (the beam reorders).
 // Nothing returns to the host between the steps; after an EOS ends the search the remaining steps' kernels see the
 // `finished` flag and do nothing.  Score arithmetic is the unfused float32 order of k_cps.hip.
@@ -66,24 +67,30 @@ __global__ __launch_bounds__(64) void lm_init_kernel(LmSearchState* st) {
   }
 }
 
-// Workgroup s: lse of logits row s (float32: maximum, then the sum of exp(x - maximum) in a fixed order) and
-// lng[s][c] = logits[s][candidate c of lattice row `row`] - lse.
+// Workgroup (s, g): segment g of logits row s -> (largest value, sum of exp(x - largest)), float32, fixed order.
 __global__ __launch_bounds__(256) void lm_score_kernel(const float* __restrict__ logits, int vocab,
-                                                      const int32_t* __restrict__ cand_id,
-                                                      const int32_t* __restrict__ cand_cnt, int row, int m_max,
-                                                      int32_t eos_id, LmSearchState* st) {
+                                                      LmSearchState* st) {
   __shared__ float red[4];
-  __shared__ int32_t tok[kMaxCand];
-  __shared__ int n_cand;
-  const int s = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int s = blockIdx.x, g = blockIdx.y, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   if (st->finished || s >= st->n_live) return;  // uniform over the workgroup
-  if (tid == 0) {
-    int er;
-    n_cand = row_candidates(cand_id, nullptr, cand_cnt, nullptr, row, m_max, eos_id, tok, nullptr, &er);
-  }
+  const int seg = ((vocab + kLmParts - 1) / kLmParts + 3) & ~3;
+  const int lo = g * seg, hi = lo + seg < vocab ? lo + seg : vocab;
   const float* z = logits + (size_t)s * vocab;
+  // a thread keeps the values it reads (at most kPer float4) so that the row is read once
+  constexpr int kPer = 8;
+  const bool vec = (vocab & 3) == 0 && seg <= kPer * 256 * 4;
+  float4 v[kPer];
   float mx = -INFINITY;
-  for (int v = tid; v < vocab; v += 256) mx = fmaxf(mx, z[v]);
+  if (vec) {
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      const int c = lo + (j * 256 + tid) * 4;
+      v[j] = c < hi ? *reinterpret_cast<const float4*>(z + c) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      mx = fmaxf(fmaxf(mx, fmaxf(v[j].x, v[j].y)), fmaxf(v[j].z, v[j].w));
+    }
+  } else {
+    for (int c = lo + tid; c < hi; c += 256) mx = fmaxf(mx, z[c]);
+  }
 #pragma unroll
   for (int off = kWave / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
   if (lane == 0) red[wave] = mx;
@@ -91,21 +98,25 @@ __global__ __launch_bounds__(256) void lm_score_kernel(const float* __restrict__
   mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   __syncthreads();
   float sum = 0.f;
-  for (int v = tid; v < vocab; v += 256) sum += expf(z[v] - mx);
+  if (mx > -INFINITY) {
+    if (vec) {
+#pragma unroll
+      for (int j = 0; j < kPer; ++j)
+        sum += (expf(v[j].x - mx) + expf(v[j].y - mx)) + (expf(v[j].z - mx) + expf(v[j].w - mx));
+    } else {
+      for (int c = lo + tid; c < hi; c += 256) sum += expf(z[c] - mx);
+    }
+  }
 #pragma unroll
   for (int off = kWave / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
   if (lane == 0) red[wave] = sum;
   __syncthreads();
-  const float lse = mx + logf((red[0] + red[1]) + (red[2] + red[3]));
-  if (tid < n_cand) {
-    int t = tok[tid];
-    t = (t < 0 || t >= vocab) ? 0 : t;
-    st->lng[s][tid] = z[t] - lse;
-  }
+  if (tid == 0) st->part[s][g] = make_float2(mx, (red[0] + red[1]) + (red[2] + red[3]));
 }
 
 // Depth i of the search, one wavefront.  Reads the beam of parity i & 1, writes the beam of parity (i + 1) & 1.
-__global__ __launch_bounds__(64) void lm_beam_step_kernel(LmSearchState* st, const int32_t* __restrict__ cand_id,
+__global__ __launch_bounds__(64) void lm_beam_step_kernel(LmSearchState* st, const float* __restrict__ logits,
+                                                         int vocab, const int32_t* __restrict__ cand_id,
                                                          const float* __restrict__ cand_logp,
                                                          const int32_t* __restrict__ cand_cnt,
                                                          const float* __restrict__ eos_logp, int i, int K, int m_max,
@@ -113,6 +124,7 @@ __global__ __launch_bounds__(64) void lm_beam_step_kernel(LmSearchState* st, con
   __shared__ int32_t c_tok[kMaxCand];
   __shared__ float c_lp[kMaxCand];
   __shared__ int s_n, s_eos;
+  __shared__ float s_lse[kLmBeam];
   if (st->finished) return;
   const int lane = threadIdx.x;
   if (lane == 0) {
@@ -123,6 +135,18 @@ __global__ __launch_bounds__(64) void lm_beam_step_kernel(LmSearchState* st, con
   __syncthreads();
   const int n_cand = s_n, eos_rank = s_eos;
   const int n_live = st->n_live;
+  // log-sum-exp of every live row from its segments (fixed order: the same bits whatever else runs)
+  for (int b = 0; b < n_live; ++b) {
+    const float2 pc = lane < kLmParts ? st->part[b][lane] : make_float2(-INFINITY, 0.f);
+    float mx = pc.x;
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    float sum = pc.y > 0.f ? pc.y * expf(pc.x - mx) : 0.f;
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) s_lse[b] = mx + logf(sum);
+  }
+  __syncthreads();
   const int n_exp = n_live * n_cand;
   const float one_minus = 1.0f - lambda;
   const int cur = i & 1, nxt = cur ^ 1;
@@ -139,7 +163,10 @@ __global__ __launch_bounds__(64) void lm_beam_step_kernel(LmSearchState* st, con
     e_dst[j] = -1;
     if (e < n_exp) {
       const int b = e / n_cand, c = e - b * n_cand;
-      const float dlm_part = lambda * c_lp[c], ng_part = one_minus * st->lng[b][c];
+      int t = c_tok[c];
+      t = (t < 0 || t >= vocab) ? 0 : t;
+      const float lng = logits[(size_t)b * vocab + t] - s_lse[b];
+      const float dlm_part = lambda * c_lp[c], ng_part = one_minus * lng;
       const float term = dlm_part + ng_part;
       e_score[j] = st->score[cur][b] + term;
       e_bits[j] = ordered_bits(e_score[j]);
@@ -251,19 +278,17 @@ int launch_lm_init(LmSearchState* st, hipStream_t s) {
   return DS_OK;
 }
 
-int launch_lm_score(const float* logits, int n_rows, int vocab, const int32_t* cand_id, const int32_t* cand_cnt,
-                    int row, int m_max, int32_t eos_id, LmSearchState* st, hipStream_t s) {
-  hipLaunchKernelGGL(lm_score_kernel, dim3(n_rows), dim3(256), 0, s, logits, vocab, cand_id, cand_cnt, row, m_max,
-                     eos_id, st);
+int launch_lm_score(const float* logits, int n_rows, int vocab, LmSearchState* st, hipStream_t s) {
+  hipLaunchKernelGGL(lm_score_kernel, dim3(n_rows, kLmParts), dim3(256), 0, s, logits, vocab, st);
   DS_LAUNCH_CHECK("lm_score_kernel");
   return DS_OK;
 }
 
-int launch_lm_beam_step(LmSearchState* st, const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
-                        const float* eos_logp, int i, int K, int m_max, int B, float lambda, int32_t eos_id,
-                        hipStream_t s) {
-  hipLaunchKernelGGL(lm_beam_step_kernel, dim3(1), dim3(64), 0, s, st, cand_id, cand_logp, cand_cnt, eos_logp, i, K,
-                     m_max, B, lambda, eos_id);
+int launch_lm_beam_step(LmSearchState* st, const float* logits, int vocab, const int32_t* cand_id,
+                        const float* cand_logp, const int32_t* cand_cnt, const float* eos_logp, int i, int K,
+                        int m_max, int B, float lambda, int32_t eos_id, hipStream_t s) {
+  hipLaunchKernelGGL(lm_beam_step_kernel, dim3(1), dim3(64), 0, s, st, logits, vocab, cand_id, cand_logp, cand_cnt,
+                     eos_logp, i, K, m_max, B, lambda, eos_id);
   DS_LAUNCH_CHECK("lm_beam_step_kernel");
   return DS_OK;
 }

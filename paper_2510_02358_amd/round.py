@@ -122,8 +122,9 @@ class SpecDecoder:
 
     def __init__(self, drafter: DeviceModel, verifier: DeviceModel, table: Optional[np.ndarray], log2_size: int,
                  params: RoundParams, k_cap: int = 64, keep_draft_logits: bool = False,
-                 keep_verify_logits: bool = False):
-        """keep_draft_logits: also write the drafter's logits to `d_logits` every round (the lattice does not need
+                 keep_verify_logits: bool = False, lm_proxy: Optional[DeviceModel] = None):
+        """lm_proxy: a small model of the same vocabulary that serves as the path search's causal proxy in place of
+        the n-gram table (`table` is then ignored).  keep_draft_logits: also write the drafter's logits to `d_logits` every round (the lattice does not need
         them in memory; stochastic verification does and gets them regardless).  keep_verify_logits: also write the
         verifier's logits of the block rows to `v_logits` (tests compare them with the oracle's)."""
         if not 1 <= k_cap < ds.DS_MAX_ROWS:
@@ -140,6 +141,12 @@ class SpecDecoder:
         vocab = drafter.cfg.vocab
         self.table = upload(table) if table is not None else None
         self.proxy = ds.ds_ngram_create(self.table, log2_size) if table is not None else None
+        self.lm, self.lm_proxy, self.lm_mem = lm_proxy, None, None
+        if lm_proxy is not None:
+            if params.beam > 8:
+                raise ValueError("the LM proxy carries at most 8 beam slots")
+            self.lm_mem = torch.empty(ds.ds_lmproxy_bytes(lm_proxy.cfgc, params.beam), dtype=torch.uint8, device=DEV)
+            self.lm_proxy = ds.ds_lmproxy_create(lm_proxy.handle, params.beam, self.lm_mem)
         self.adl = ds.ds_adl_create(params.k_min, params.k_max, params.delta, params.rho)
         m = params.m_max
         i32, f32 = torch.int32, torch.float32
@@ -199,6 +206,9 @@ class SpecDecoder:
         if self.adl:
             ds.ds_adl_destroy(self.adl)
             self.adl = None
+        if self.lm_proxy:
+            ds.ds_lmproxy_destroy(self.lm_proxy)
+            self.lm_proxy = None
 
     def start(self, prefix: np.ndarray) -> None:
         """Prefill both caches with the prefix; the verifier's greedy token after it becomes pending."""
@@ -208,6 +218,9 @@ class SpecDecoder:
         self.v.set_kv_len(0)
         ds.ds_prefill(self.d.handle, t, len(prefix), None, self.d.ws)
         ds.ds_prefill(self.v.handle, t, len(prefix), last, self.v.ws)
+        if self.lm_proxy:
+            ds.ds_lmproxy_set_len(self.lm_proxy, 0)
+            ds.ds_lmproxy_prefill(self.lm_proxy, t, len(prefix), self.lm.ws)
         # first pending token = verifier arg-max after the prefix: a verify call with an empty path
         # would need the token before it; the arg-max of `last` is taken by the acceptance kernel
         # through a 1-row lattice (top-1, ties to the lower id)
@@ -267,8 +280,13 @@ class SpecDecoder:
                                     stream)
                 ds.ds_refine_select(*lat, k, p.m_max, n, self.mask_id, self.blk, *final, stream)
             lat = final
-        ds.ds_cps_path(lat[0], lat[1], lat[2], lat[3], 1, k, p.m_max, p.beam, p.lam, self.proxy, self.ctx, self.eos_id,
-                       self.block[1:], self.path_len, self.path_score, self.cps_ws, stream)
+        if self.lm_proxy:  # the proxy reads the same pending tokens as the drafter did
+            ds.ds_cps_path_lm(lat[0], lat[1], lat[2], lat[3], k, p.m_max, p.beam, p.lam, self.lm_proxy,
+                              self.pending_dev, n_pend, self.eos_id, self.block[1:], self.path_len, self.path_score,
+                              self.lm.ws, stream)
+        else:
+            ds.ds_cps_path(lat[0], lat[1], lat[2], lat[3], 1, k, p.m_max, p.beam, p.lam, self.proxy, self.ctx,
+                           self.eos_id, self.block[1:], self.path_len, self.path_score, self.cps_ws, stream)
         self.lat_used = lat
         if inject is not None and inject[1] > 0:
             self.block[1:1 + inject[1]].copy_(inject[0][:inject[1]], non_blocking=True)

@@ -198,3 +198,49 @@ def test_lm_proxy_argument_errors():
         assert ds.ds_lmproxy_len(px.handle) == 11
     finally:
         px.close()
+
+
+def test_whole_rounds_with_the_lm_proxy_match_oracle_rounds():
+    """The round driver with the LM proxy in place of the n-gram table against oracle rounds on the tiny float32
+    pair: lattice ids, searched path, verdict, committed tokens, draft-length proposals and every cache length."""
+    from oracle import adl as o_adl
+    from oracle import round as o_round
+    from paper_2510_02358_amd import round as rnd
+    cfg = synth.CFG_TINY
+    dw, vw = synth.make_weights(cfg, 0), synth.make_weights(cfg, 1)
+    pw = _proxy_weights(PROXY_F32, 53, 8.0)
+    prefix = synth.make_prefix(cfg, 96, 3)
+    params = rnd.RoundParams(m_max=4, tau=0.9, beam=3, lam=0.5, k_min=2, k_max=12, delta=2.0, rho=0.5)
+    dm, vm = rnd.DeviceModel(cfg, dw, 256), rnd.DeviceModel(cfg, vw, 256)
+    pm = rnd.DeviceModel(PROXY_F32, pw, 256)
+    dec = rnd.SpecDecoder(dm, vm, None, 0, params, k_cap=16, keep_draft_logits=True, lm_proxy=pm)
+    try:
+        dec.start(prefix)
+        st = o_round.SpecState(cfg, dw, cfg, vw, prefix)
+        pcache = o_model.KVCache(PROXY_F32)
+        o_model.prefill(PROXY_F32, pw, pcache, prefix)
+        adl = o_adl.AdlState(params.k_min, params.k_max, params.delta, params.rho)
+        k, rounds, changed = 8, 0, 0
+        for t in range(6):
+            got = dec.round(k)
+            ref = o_round.spec_round(st, k, params.m_max, params.tau, params.beam, params.lam, None, 0,
+                                     lm_proxy=(PROXY_F32, pw, pcache))
+            assert np.max(np.abs(dec.d_logits[:k].cpu().numpy() - ref["d_logits"])) <= 1e-4
+            assert np.array_equal(dec.cand_id[:k].cpu().numpy(), ref["lattice"]["cand_id"]), t
+            assert list(got["path"]) == ref["path"], t
+            assert abs(float(dec.path_score.item()) - float(ref["score"])) <= 2e-3 * max(1.0, abs(float(ref["score"])))
+            changed += ref["path"] != o_cps.cps_path(ref["lattice"], 0, k, params.beam, params.lam, None, 0, (0, 0),
+                                                     cfg.eos_id)[0]
+            assert (got["n_accept"], got["next_token"], got["eos_accepted"]) == \
+                (ref["n_accept"], ref["next_token"], ref["eos_accepted"]), t
+            assert dec.tokens == st.tokens
+            assert ds.ds_lmproxy_len(dec.lm_proxy) == pcache.length == len(st.tokens) - len(st.pending)
+            assert dm.kv_len == st.dcache.length and vm.kv_len == st.vcache.length
+            k_ref = o_adl.adl_update(adl, k, got["first_eos"], ref["n_accept"])
+            assert got["k_next"] == k_ref
+            k = k_ref
+            rounds += 1
+        print(f"PARITY-COUNTS lm proxy whole rounds: rounds compared {rounds}, paths the proxy changed {changed}")
+        assert changed >= 1
+    finally:
+        dec.close(); dm.close(); vm.close(); pm.close()
