@@ -19,7 +19,9 @@ a Viterbi DP for the path search; both forms of the accepted-length formula; han
 of the draft-length controller; refinement with one step == the single-pass draft, update-set sizes
 and order checked against an independent sort; stochastic verification against the exact output
 distribution it must reproduce (enumerated over a uniform grid on a tiny vocabulary) and numpy's
-searchsorted for the inverse CDF.  Parity unpinned: the beam path for beams narrower than
+searchsorted for the inverse CDF; the path search with a tiny causal LM as its proxy against an exhaustive
+enumeration whose proxy scores come from one uncached causal pass, and against the proxy-free search at
+lambda = 1.  Parity unpinned: the beam path for beams narrower than
 exhaustive is fixed only by the step-by-step reading of the search procedure.
 """
 from . import model, lattice, cps, accept, adl, round, refine, sample  # noqa: F401

@@ -54,3 +54,25 @@ def test_same_model_as_drafter_and_verifier_still_lossless_and_forced_greedy_pat
     ref = oround.ar_greedy(CFG, vw, prefix, len(st.tokens) - len(prefix))
     assert st.tokens[len(prefix):] == ref
     assert st.pending == r2["committed"]
+
+
+def test_rounds_with_a_tiny_lm_proxy_stay_lossless_and_keep_the_proxy_history_in_step():
+    """The causal proxy only steers the search: with a tiny causal LM in its place the committed stream is still the
+    verifier's greedy decode, and the proxy's cache always holds the committed tokens but the pending ones."""
+    dw, vw, prefix = _setup()
+    pcfg = synth.ModelCfg(n_layers=1, d_model=32, n_q=2, n_kv=1, head_dim=16, d_ffn=48, vocab=CFG.vocab,
+                          rope_base=1.0e4, dtype="f32")
+    pw = synth.make_weights(pcfg, 9, std=0.3)
+    pcache = model.KVCache(pcfg)
+    model.prefill(pcfg, pw, pcache, prefix)
+    st = oround.SpecState(CFG, dw, CFG, vw, prefix)
+    plain = oround.SpecState(CFG, dw, CFG, vw, prefix)
+    differs = 0
+    for _ in range(5):
+        r = oround.spec_round(st, 5, 3, 1.0, 2, 0.3, None, LOG2, lm_proxy=(pcfg, pw, pcache))
+        q = oround.spec_round(plain, 5, 3, 1.0, 2, 0.3, None, LOG2)
+        differs += r["path"] != q["path"]
+        assert pcache.length == len(st.tokens) - len(st.pending)
+    produced = st.tokens[len(prefix):]
+    assert produced == oround.ar_greedy(CFG, vw, prefix, len(produced))
+    assert differs >= 1          # the proxy does steer the search
