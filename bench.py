@@ -428,15 +428,61 @@ def oracle_legs(cfg, dw, vw, prefix, table, dm, vm, want_32b: bool) -> dict:
 
 
 # ---------------------------------------------------------------------------------------------------------------------
+def run_lm_proxy_search() -> dict:
+    """ds_cps_path_lm alone: a synthetic top-8 lattice of 32 positions on the 152064-token vocabulary, a 2-layer
+    d = 256 bf16 decoder as the causal proxy with 2048 committed tokens, beam 4."""
+    import numpy as np
+    import torch
+
+    from paper_2510_02358_amd import binding as ds
+    from paper_2510_02358_amd import round as rnd
+    from paper_2510_02358_amd import synth
+
+    pcfg = synth.ModelCfg(n_layers=2, d_model=256, n_q=4, n_kv=2, head_dim=128, d_ffn=512, vocab=152064,
+                          rope_base=1.0e6, dtype="bf16")
+    pm = rnd.DeviceModel(pcfg, synth.make_weights(pcfg, 7), 4096)
+    mem = torch.empty(ds.ds_lmproxy_bytes(pm.cfgc, BEAM), dtype=torch.uint8, device="cuda")
+    px = ds.ds_lmproxy_create(pm.handle, BEAM, mem)
+    ds.ds_lmproxy_prefill(px, rnd.upload(np.asarray(synth.make_prefix(pcfg, PREFIX, 2), dtype=np.int32)), PREFIX, pm.ws)
+    rng = np.random.default_rng(0)
+    logp = -np.sort(rng.random((K_DRAFT, M_MAX)).astype(np.float32) * 5.0, axis=1)
+    lat = [rnd.upload(rng.integers(0, pcfg.n_plain_tokens, (K_DRAFT, M_MAX)).astype(np.int32)), rnd.upload(logp),
+           rnd.upload(np.full(K_DRAFT, M_MAX, np.int32)), rnd.upload(np.full(K_DRAFT, -20.0, np.float32))]
+    pend = rnd.upload(np.array([5], np.int32))
+    path = torch.zeros(K_DRAFT, dtype=torch.int32, device="cuda")
+    plen = torch.zeros(1, dtype=torch.int32, device="cuda")
+    score = torch.zeros(1, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    for rep in range(reps + 3):
+        if rep == 3:
+            e0.record()
+        ds.ds_lmproxy_set_len(px, PREFIX)
+        ds.ds_cps_path_lm(*lat, K_DRAFT, M_MAX, BEAM, LAM, px, pend, 1, pcfg.eos_id, path, plen, score, pm.ws)
+        torch.cuda.current_stream().synchronize()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    ds.ds_lmproxy_destroy(px)
+    pm.close()
+    return {"metric": "lm_proxy_path_search_ms", "value": round(ms, 4), "unit": "ms", "n_gpus": 1, "steps": reps,
+            "warmup": 3, "higher_is_better": False, "data": "synthetic", "dtype": DTYPE,
+            "config": {"workload": "path search with a tiny causal LM as the causal proxy: K = 32, top-8 lattice, beam 4, "
+                                   "proxy = 2 layers, d 256, 4q/2kv x128, FFN 512, vocab 152064, bf16, 2048 committed "
+                                   "tokens"},
+            "path_len": int(plen.item()), "proxy_steps": K_DRAFT}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["all", "cfg1", "cfg2", "cfg3", "cfg4"], default="all",
+    ap.add_argument("--workload", choices=["all", "cfg1", "cfg2", "cfg3", "cfg4", "lm_proxy"], default="all",
                     help="all (default): the cfg1 line with the cfg2 / cfg3 / cfg4 blocks inside.  cfg1: the headline "
-                         "workload alone.  cfg2 / cfg3 / cfg4: that workload's own line")
+                         "workload alone.  cfg2 / cfg3 / cfg4: that workload's own line.  lm_proxy: the path search "
+                         "with a tiny causal LM as its proxy, alone, on a cfg1-shaped lattice")
     ap.add_argument("--core-only", action="store_true",
                     help="cfg1: only the timed rounds and the per-stage pass (keeps profiler runs short)")
     ap.add_argument("--calibrate", action="store_true",
@@ -460,6 +506,9 @@ def main() -> int:
     with_cpu = not args.no_cpu_baseline and not args.core_only
     if args.workload == "cfg3":
         print(json.dumps(stress_line(run_stress(with_cpu))))
+        return 0
+    if args.workload == "lm_proxy":
+        print(json.dumps(run_lm_proxy_search()))
         return 0
     if args.workload in ("cfg2", "cfg4"):
         print(json.dumps(deep_line(run_deep(args.workload), None)))
@@ -588,7 +637,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "cfg1: 7B-shaped decoder layer + LM head (d=3584, 28q/4kv x128, FFN 18944, "
                                "vocab 152064), drafter + verifier, prefix 2048, K=32, top-8 lattice, beam 4, "
-                               "33 verify rows, batch 1; full host loop (staging, path read-back, KV commit, "
+                               "33 verify rows, batch 1; full host loop (path read-back, KV commit, "
                                "draft-length update)"},
         "committed_tokens_per_s": round(n_committed / elapsed, 2),
         "accepted_draft_tokens_per_s": round(n_accepted / elapsed, 2),
@@ -597,7 +646,7 @@ def main() -> int:
         "round_hbm_frac": round(round_gbps / HBM_PEAK_GBS, 4),
         "device_only_round": {"ms": round(dev_ms, 4), "rounds_per_s": round(1e3 / dev_ms, 1),
                               "round_hbm_frac": round(ab["round"] / (dev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                              "note": "same calls without staging, path read-back and host bookkeeping"},
+                              "note": "same calls without path read-back and host bookkeeping"},
         "measured_copy_GBps": round(copy_gbps, 1),
         "roofline": roofline, "stages": stages, "setup_s": round(setup_s, 1),
     }

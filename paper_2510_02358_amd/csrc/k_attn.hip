@@ -205,16 +205,34 @@ struct AttnWave {
   int lim_min[NB ? NB : 1], limit[NB ? NB : 1];
 };
 
+// The sequences of one attention launch: blockIdx.z = sequence * zdim + group of query blocks.  Each sequence has its
+// own caches, row range (first row r0, a multiple of 16), key count and split plan; the launch covers the largest
+// split count and the most query-block groups, and workgroups past a sequence's own extent leave empty partials
+// or nothing.
+struct AttnSeqs {
+  const void* kc[kMaxSeq];
+  const void* vc[kMaxSeq];
+  int r0[kMaxSeq], rows[kMaxSeq], n_causal[kMaxSeq], pos0[kMaxSeq], n_keys[kMaxSeq], chunks_per_split[kMaxSeq];
+  int zdim;
+};
+
 template <int QB>
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2))) void attn_f16_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, int rows,
-    int rows_stride, int n_causal, int pos0, int n_keys, int n_q, int n_kv, int cap, int chunks_per_split,
-    float* __restrict__ part_o, float* __restrict__ part_ml) {
+    AttnSeqs sq, const uint16_t* __restrict__ q_all, int rows_stride, int n_q, int n_kv, int cap,
+    float* __restrict__ part_o_all, float* __restrict__ part_ml_all) {
   // q: queries in log2 units (attn_q_scale folded in by the producer), per head [rows_stride rows] in tile order
-  // rows: the rows of ONE sequence (q, part_o and part_ml already point at its first row, a multiple of 16);
+  // rows: the rows of this workgroup's sequence (q, part_o and part_ml point at its first row, a multiple of 16);
   // rows_stride: padded rows of the whole call (stride between heads and between splits)
   __shared__ __attribute__((aligned(16))) uint16_t k_lds[2 * kChunkElems];
   __shared__ __attribute__((aligned(16))) uint16_t v_lds[2 * kChunkElems];
+  const int seq = (int)blockIdx.z / sq.zdim, zq = (int)blockIdx.z - seq * sq.zdim;
+  const uint16_t* __restrict__ q = q_all + (size_t)(sq.r0[seq] >> 4) * 4 * 512;
+  const uint16_t* __restrict__ kc = static_cast<const uint16_t*>(sq.kc[seq]);
+  const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(sq.vc[seq]);
+  const int rows = sq.rows[seq], n_causal = sq.n_causal[seq], pos0 = sq.pos0[seq], n_keys = sq.n_keys[seq];
+  const int chunks_per_split = sq.chunks_per_split[seq];
+  float* __restrict__ part_o = part_o_all + (size_t)sq.r0[seq] * kHd;
+  float* __restrict__ part_ml = part_ml_all + (size_t)sq.r0[seq] * 2;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane & 15, g = lane >> 4;
   const int split = blockIdx.x, kvh = blockIdx.y;
@@ -224,7 +242,7 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
   int c_end = c_begin + chunks_per_split;
   if (c_end > n_chunks) c_end = n_chunks;
   const int n = c_end > c_begin ? c_end - c_begin : 0;  // chunks of this split (same for the whole workgroup)
-  const int qb0 = (blockIdx.z * 4 + wave) * QB;         // first query block of this wavefront
+  const int qb0 = (zq * 4 + wave) * QB;                 // first query block of this wavefront
   const int nb = n_qb - qb0 >= QB ? QB : (n_qb > qb0 ? n_qb - qb0 : 0);  // its live blocks (a scalar)
 
   const uint16_t* kbase = kc + ((size_t)kvh * cap + (size_t)c_begin * kChunk) * kHd;
@@ -365,13 +383,20 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
 }
 
 // float32 parity mode.  grid (n_split, n_q); each wavefront walks rows r = wave, wave + 4, ...
-__global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__ q, const float* __restrict__ kc,
-                                                       const float* __restrict__ vc, int rows, int rows_stride,
-                                                       int n_causal, int pos0, int n_keys, int n_q, int n_kv,
-                                                       int hd, int cap, int chunks_per_split, float scale,
-                                                       float* __restrict__ part_o, float* __restrict__ part_ml) {
+__global__ __launch_bounds__(256) void attn_f32_kernel(AttnSeqs sq, const float* __restrict__ q_all, int rows_stride,
+                                                       int n_q, int n_kv, int hd, int cap, float scale,
+                                                       float* __restrict__ part_o_all,
+                                                       float* __restrict__ part_ml_all) {
   __shared__ float qbuf[4][128];
   __shared__ float pbuf[4][kChunk];
+  const int seq = blockIdx.z;
+  const float* __restrict__ q = q_all + (size_t)sq.r0[seq] * hd;
+  const float* __restrict__ kc = static_cast<const float*>(sq.kc[seq]);
+  const float* __restrict__ vc = static_cast<const float*>(sq.vc[seq]);
+  const int rows = sq.rows[seq], n_causal = sq.n_causal[seq], pos0 = sq.pos0[seq], n_keys = sq.n_keys[seq];
+  const int chunks_per_split = sq.chunks_per_split[seq];
+  float* __restrict__ part_o = part_o_all + (size_t)sq.r0[seq] * hd;
+  float* __restrict__ part_ml = part_ml_all + (size_t)sq.r0[seq] * 2;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int split = blockIdx.x, head = blockIdx.y;
   const int kvh = head / (n_q / n_kv);
@@ -521,28 +546,34 @@ int launch_attention(int dtype, const SeqTable& tab, const void* q, int rows, in
   }
   DS_REQUIRE(n_split_max * rows_pad <= attn_partial_rows(rows_pad), DS_E_CAPACITY,
              "attention partials: %d splits x %d rows exceed the workspace", n_split_max, rows_pad);
+  // one launch for all sequences (blockIdx.z carries the sequence)
+  AttnSeqs sq{};
+  int n_qb_max = 1;
   for (int s = 0; s < tab.n_seq; ++s) {
-    const int n_keys = tab.pos0[s] + tab.n_rows[s], r0 = tab.row0[s], sr = tab.n_rows[s];
-    const int srp = ceil_div(sr, 16) * 16;
-    const AttnPlan plan = attn_plan(dtype, cap, n_keys);
-    if (dtype == DS_BF16) {
-      const int n_qb = ceil_div((n_q / n_kv) * sr, 16);  // blocks of 16 densely packed (head, row) pairs
-      constexpr int QB = kAttnQB;
-      dim3 grid(n_split_max, n_kv, ceil_div(n_qb, 4 * QB));
-      hipLaunchKernelGGL((attn_f16_kernel<QB>), grid, dim3(kAttnThreads), 0, st,
-                         static_cast<const uint16_t*>(q) + (size_t)(r0 >> 4) * 4 * 512,
-                         static_cast<const uint16_t*>(tab.kc[s]), static_cast<const uint16_t*>(tab.vc[s]), sr,
-                         rows_pad, tab.n_causal[s], tab.pos0[s], n_keys, n_q, n_kv, cap, plan.chunks_per_split,
-                         part_o + (size_t)r0 * kHd, part_ml + (size_t)r0 * 2);
-      DS_LAUNCH_CHECK("attn_f16_kernel");
-    } else {
-      hipLaunchKernelGGL(attn_f32_kernel, dim3(n_split_max, n_q), dim3(256), 0, st,
-                         static_cast<const float*>(q) + (size_t)r0 * hd, static_cast<const float*>(tab.kc[s]),
-                         static_cast<const float*>(tab.vc[s]), sr, rows_pad, tab.n_causal[s], tab.pos0[s], n_keys, n_q,
-                         n_kv, hd, cap, plan.chunks_per_split, scale, part_o + (size_t)r0 * hd,
-                         part_ml + (size_t)r0 * 2);
-      DS_LAUNCH_CHECK("attn_f32_kernel");
-    }
+    const int n_keys = tab.pos0[s] + tab.n_rows[s];
+    sq.kc[s] = tab.kc[s];
+    sq.vc[s] = tab.vc[s];
+    sq.r0[s] = tab.row0[s];
+    sq.rows[s] = tab.n_rows[s];
+    sq.n_causal[s] = tab.n_causal[s];
+    sq.pos0[s] = tab.pos0[s];
+    sq.n_keys[s] = n_keys;
+    sq.chunks_per_split[s] = attn_plan(dtype, cap, n_keys).chunks_per_split;
+    const int n_qb = ceil_div((n_q / n_kv) * tab.n_rows[s], 16);  // blocks of 16 densely packed (head, row) pairs
+    n_qb_max = n_qb > n_qb_max ? n_qb : n_qb_max;
+  }
+  if (dtype == DS_BF16) {
+    constexpr int QB = kAttnQB;
+    sq.zdim = ceil_div(n_qb_max, 4 * QB);
+    dim3 grid(n_split_max, n_kv, sq.zdim * tab.n_seq);
+    hipLaunchKernelGGL((attn_f16_kernel<QB>), grid, dim3(kAttnThreads), 0, st, sq, static_cast<const uint16_t*>(q),
+                       rows_pad, n_q, n_kv, cap, part_o, part_ml);
+    DS_LAUNCH_CHECK("attn_f16_kernel");
+  } else {
+    sq.zdim = 1;
+    hipLaunchKernelGGL(attn_f32_kernel, dim3(n_split_max, n_q, tab.n_seq), dim3(256), 0, st, sq,
+                       static_cast<const float*>(q), rows_pad, n_q, n_kv, hd, cap, scale, part_o, part_ml);
+    DS_LAUNCH_CHECK("attn_f32_kernel");
   }
   if (dtype == DS_BF16)
     hipLaunchKernelGGL((attn_merge_kernel<bf16_t>), dim3(rows, n_q), dim3(hd), 0, st, tab, part_o, part_ml, n_split_max,
