@@ -244,3 +244,44 @@ def test_whole_rounds_with_the_lm_proxy_match_oracle_rounds():
         assert changed >= 1
     finally:
         dec.close(); dm.close(); vm.close(); pm.close()
+
+
+def test_lm_proxy_search_at_the_benchmark_shape_against_the_oracle():
+    """The shape bench.py times: 152064-token vocabulary, 2048 committed tokens, K = 32, top-8 lattice, beam 4, the
+    2-layer d = 256 bf16 proxy.  Same checks as above (oracle path unless near-tied, score, one-pass rescoring)."""
+    cfg = synth.ModelCfg(n_layers=2, d_model=256, n_q=4, n_kv=2, head_dim=128, d_ffn=512, vocab=152064,
+                         rope_base=1.0e6, dtype="bf16")
+    k, m_max, beam, lam, tau = 32, 8, 4, 0.5, 1.0
+    w = _proxy_weights(cfg, 7, 4.0)
+    px = GpuProxy(cfg, w, 2304, beam)
+    try:
+        rng = np.random.default_rng(9)
+        history = [int(t) for t in synth.make_prefix(cfg, 2048, 2)]
+        ds.ds_lmproxy_prefill(px.handle, gu.to_dev(np.asarray(history[:-1], dtype=np.int32)), 2047, px.gm.ws)
+        cache = o_model.KVCache(cfg)
+        o_model.prefill(cfg, w, cache, history[:-1])
+        # a lattice with the drafter's kind of spread: top-8 of N(0, 2.5) logits over a 4096-token slice of the vocabulary
+        logits = np.full((k, cfg.vocab), -30.0, dtype=np.float32)
+        cols = rng.choice(cfg.n_plain_tokens, 4096, replace=False)
+        logits[:, cols] = (rng.standard_normal((k, 4096)) * 2.5).astype(np.float32)
+        lat = o_lattice.build_lattice(logits, m_max, tau, cfg.eos_id)
+        dev = {n: gu.to_dev(lat[n]) for n in ("cand_id", "cand_logp", "cand_cnt", "eos_logp")}
+        got_toks, got_score = _gpu_search(px, dev, k, m_max, beam, lam, history[-1:], cfg.eos_id)
+        margins = []
+        ref_toks, ref_score, _ = o_cps.cps_path_lm(lat, 0, k, beam, lam, cfg, w, cache, history[-1:], cfg.eos_id,
+                                                   margins)
+        own = _rescore_on_gpu(px, lat, history, got_toks, lam, cfg.eos_id)
+        assert abs(own - got_score) <= 1e-4 * max(1.0, abs(own))
+        same = 0
+        for a, b in zip(got_toks, ref_toks):
+            if a != b:
+                break
+            same += 1
+        print(f"PARITY-COUNTS lm proxy benchmark shape: path tokens equal {same} of {len(ref_toks)}, "
+              f"smallest oracle margin {min(margins):.3e}, scores {got_score:.4f} / {float(ref_score):.4f}")
+        if got_toks == ref_toks:
+            assert abs(got_score - float(ref_score)) <= 5e-2 * max(1.0, abs(float(ref_score)))
+        else:   # the paths part only where the oracle's own beam boundary is within the bf16 logit budget
+            assert min(margins[:same + 1]) < 8e-2, (same, margins[:same + 1])
+    finally:
+        px.close()
