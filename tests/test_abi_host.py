@@ -128,8 +128,22 @@ def test_bad_arguments_are_rejected_on_the_host_before_any_launch():
     assert lib.ds_lm_head_tiles(None, None, 4, -1, None, one, 1 << 20, None) == ds.DS_E_INVALID
     assert lib.ds_lattice_from_tiles(None, 4, 8, 1.0, -1, one, one, one, one, one, one, 1 << 20,
                                      None) == ds.DS_E_INVALID
+    assert lib.ds_verify_block_carry(None, one, 2, None, -1, one, one, one, one, None, one, one, 1 << 20,
+                                     None) == ds.DS_E_INVALID
+    # the LM proxy of the path search
+    assert lib.ds_cps_path_lm(one, one, one, one, 8, 4, 2, 0.5, None, one, 1, -1, one, one, one, one, 1 << 20,
+                              None) == ds.DS_E_INVALID
+    assert lib.ds_lmproxy_prefill(None, one, 4, one, 1 << 20, None) == ds.DS_E_INVALID
+    assert lib.ds_lmproxy_set_len(None, 0) == ds.DS_E_INVALID
     # model configuration
     cfg = ds.ModelCfgC(1, 3584, 28, 4, 128, 18944, 152064, 1e6, 1e-6, ds.DS_BF16, 4096)
+    tiny = ds.ModelCfgC(2, 256, 4, 2, 128, 512, 152064, 1e6, 1e-6, ds.DS_BF16, 4096)
+    assert ds.ds_lmproxy_bytes(tiny, 4) == 4 * 4 * ds.ds_kv_bytes(tiny) + (ds.ds_lmproxy_bytes(tiny, 1) - 4 * ds.ds_kv_bytes(tiny))
+    assert 16 * 1024 < ds.ds_lmproxy_bytes(tiny, 1) - 4 * ds.ds_kv_bytes(tiny) < 32 * 1024     # the search state
+    for beam in (0, 9):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_lmproxy_bytes(tiny, beam)
+        assert e.value.code == ds.DS_E_SHAPE
     assert ds.ds_model_packed_bytes(cfg) == (233046016 + 544997376) * 2 + 256   # + weight-range flag
     assert ds.ds_kv_bytes(cfg) == 4 * 4096 * 128 * 2
     assert ds.ds_workspace_bytes(cfg, 33) > 33 * 152064 * 4
