@@ -28,30 +28,6 @@ namespace {
 constexpr int kMaxCand = DS_MAX_TOPM + 1;  // + retained EOS
 constexpr int kSlots = (kLmBeam * kMaxCand + kWave - 1) / kWave;  // expansions per lane
 
-// Candidate list of one lattice row (first cand_cnt entries, EOS appended if absent); returns the count and the
-// rank at which EOS sits (-1: none).
-__device__ __forceinline__ int row_candidates(const int32_t* __restrict__ cand_id, const float* __restrict__ cand_logp,
-                                              const int32_t* __restrict__ cand_cnt,
-                                              const float* __restrict__ eos_logp, int row, int m_max, int32_t eos_id,
-                                              int32_t* tok, float* lp, int* eos_rank) {
-  int cnt = cand_cnt[row];
-  cnt = cnt < 1 ? 1 : (cnt > m_max ? m_max : cnt);
-  int er = -1;
-  for (int c = 0; c < cnt; ++c) {
-    tok[c] = cand_id[(size_t)row * m_max + c];
-    if (lp) lp[c] = cand_logp[(size_t)row * m_max + c];
-    if (eos_id >= 0 && tok[c] == eos_id && er < 0) er = c;
-  }
-  if (eos_id >= 0 && er < 0) {
-    tok[cnt] = eos_id;
-    if (lp) lp[cnt] = eos_logp[row];
-    er = cnt;
-    ++cnt;
-  }
-  *eos_rank = er;
-  return cnt;
-}
-
 __global__ __launch_bounds__(64) void lm_init_kernel(LmSearchState* st) {
   const int t = threadIdx.x;
   if (t < kLmBeam) {
@@ -123,17 +99,33 @@ __global__ __launch_bounds__(64) void lm_beam_step_kernel(LmSearchState* st, con
                                                          int B, float lambda, int32_t eos_id) {
   __shared__ int32_t c_tok[kMaxCand];
   __shared__ float c_lp[kMaxCand];
-  __shared__ int s_n, s_eos;
   __shared__ float s_lse[kLmBeam];
   if (st->finished) return;
   const int lane = threadIdx.x;
-  if (lane == 0) {
-    int er;
-    s_n = row_candidates(cand_id, cand_logp, cand_cnt, eos_logp, i, m_max, eos_id, c_tok, c_lp, &er);
-    s_eos = er;
+  // candidates of lattice row i, one per lane: the first cand_cnt entries, EOS appended if it is not among them
+  int n_cand = cand_cnt[i];
+  n_cand = n_cand < 1 ? 1 : (n_cand > m_max ? m_max : n_cand);
+  int my_tok = -1;
+  float my_lp = 0.f;
+  if (lane < n_cand) {
+    my_tok = cand_id[(size_t)i * m_max + lane];
+    my_lp = cand_logp[(size_t)i * m_max + lane];
+  }
+  const unsigned long long at_eos = __ballot(lane < n_cand && eos_id >= 0 && my_tok == eos_id);
+  int eos_rank = at_eos ? __ffsll((long long)at_eos) - 1 : -1;
+  if (eos_id >= 0 && eos_rank < 0) {
+    if (lane == n_cand) {
+      my_tok = eos_id;
+      my_lp = eos_logp[i];
+    }
+    eos_rank = n_cand;
+    ++n_cand;
+  }
+  if (lane < n_cand) {
+    c_tok[lane] = my_tok;
+    c_lp[lane] = my_lp;
   }
   __syncthreads();
-  const int n_cand = s_n, eos_rank = s_eos;
   const int n_live = st->n_live;
   // log-sum-exp of every live row from its segments (fixed order: the same bits whatever else runs)
   for (int b = 0; b < n_live; ++b) {
