@@ -21,7 +21,9 @@ and order checked against an independent sort; stochastic verification against t
 distribution it must reproduce (enumerated over a uniform grid on a tiny vocabulary) and numpy's
 searchsorted for the inverse CDF; the path search with a tiny causal LM as its proxy against an exhaustive
 enumeration whose proxy scores come from one uncached causal pass, and against the proxy-free search at
-lambda = 1.  Parity unpinned: the beam path for beams narrower than
-exhaustive is fixed only by the step-by-step reading of the search procedure.
+lambda = 1.  Beams narrower than exhaustive: a hand-worked three-position lattice on which beams 4, 2 and 1
+return three different paths (the prefix of the optimum is pruned), with hand-computed scores and margins; beyond
+such examples the narrow-beam path is fixed by the step-by-step reading of the search procedure (depth-synchronous
+pruning, the stated keep order), which no closed form pins.
 """
 from . import model, lattice, cps, accept, adl, round, refine, sample  # noqa: F401

@@ -171,6 +171,19 @@ def test_cps_eos_first_position_and_ties():
     assert np.array_equal(path, ref[0]) and list(path[0]) == [10] * 5
 
 
+def test_cps_hand_worked_narrow_beams():
+    """The hand-computed example of tests/hand_cases.py on the GPU: beams 4, 2, 1 return the three hand-derived paths
+    and scores (the narrower beams lose the optimum because its prefix is pruned at depth 1)."""
+    import hand_cases
+    log2 = 12
+    lat, table, ctx, expected = hand_cases.narrow_beam_case(log2, o_cps.ngram_slot)
+    for beam, want_toks, want_score in expected:
+        for with_ws in (True, False):
+            path, plen, score = gu.gpu_cps(lat, 1, 3, 2, beam, 0.5, gu.to_dev(table), log2,
+                                           np.array([ctx], dtype=np.int32), -1, with_ws=with_ws)
+            assert plen[0] == 3 and list(path[0]) == want_toks and score[0] == np.float32(want_score), beam
+
+
 def test_lattice_then_cps_end_to_end_on_device():
     """Lattice arrays stay on the device between the two calls; compared against the oracle chain fed
     with the SAME float32 logits.  Path equality can only break at float32 near-ties of scores, which

@@ -13,6 +13,8 @@ import pytest
 from oracle import cps, lattice, model
 from paper_2510_02358_amd import synth
 
+import hand_cases
+
 f32 = np.float32
 LOG2 = 12
 
@@ -294,6 +296,18 @@ def test_search_margins_are_the_gaps_at_the_beam_boundary():
     cps.cps_path(lat, 0, 1, 4, 1.0, None, 0, [0, 0], -1, margins=m)
     assert m == [0.5]
     assert cps.cps_path(lat, 0, 2, 2, 1.0, None, 0, [0, 0], -1)[0] == [1, 4]   # unchanged without the list
+
+
+def test_narrow_beams_on_a_hand_worked_lattice_where_pruning_loses_the_optimum():
+    """The worked example of tests/hand_cases.py (all sums done by hand there): beams 4, 2 and 1 return three
+    different paths, the narrower ones because the prefix of the optimum is pruned at depth 1."""
+    lat, table, ctx, expected = hand_cases.narrow_beam_case(LOG2, cps.ngram_slot)
+    for beam, want_toks, want_score in expected:
+        toks, score, _ = cps.cps_path(lat, 0, 3, beam, 0.5, table, LOG2, ctx, -1)
+        assert toks == want_toks and score == f32(want_score), beam
+    m = []
+    cps.cps_path(lat, 0, 3, 2, 0.5, table, LOG2, ctx, -1, margins=m)
+    assert m == [0.5, 0.5, 0.5]      # -0.5 | -1.0;  -1.5 | -2.0 | -3.0;  -7.0 | -7.5 | -8.0
 
 
 # ------------------------------------------------------------------ path search with a tiny causal LM as the proxy
