@@ -365,6 +365,65 @@ void ds_adl_destroy(ds_adl* a);
 int ds_adl_update(ds_adl* a, int k_t, int first_eos, int l_acc, int* k_next);
 int ds_adl_state(const ds_adl* a, double* l_gen_ema, double* l_acc_ema);
 
+/* The whole loop of Alg. 1 as one call: n_rounds rounds (draft -> lattice -> path search -> verification ->
+ * draft-length update) driven from inside the library, one host crossing per round (the verdict, polled in pinned
+ * memory) and no host -> device traffic between rounds (ds_verify_block_carry).  A client of the entry points above:
+ * the same kernels, the same results as calling them one by one.  Greedy verification, single-pass draft, one
+ * sequence, n-gram proxy (or none).
+ *
+ * ds_round_desc names every buffer; all caller-owned.  io [dev] int32[total of ds_round_io_layout(K_cap, M_max)]:
+ *   io[0, DS_MAX_ROWS)                  pending tokens, right-aligned (the next ds_draft_block's `pending`)
+ *   io[DS_MAX_ROWS], io[DS_MAX_ROWS+1]  the two tokens before the block; the second is also block[0]
+ *   io[path_at, path_at + K_cap)        the searched path (path_at = DS_MAX_ROWS + 2), io[len_at] its length
+ *   io[cand_at, + K_cap * M_max)        the lattice's candidate ids (cand_at a multiple of 4)
+ * Before the first call the caller writes the pending tokens and the two context tokens there; afterwards the
+ * acceptance kernel does.  host_out [host, pinned] int32[total - path_at] receives io[path_at, total) every round;
+ * verdict [host, pinned, device-visible] int32[3] receives n_accept, next_token, eos_accepted.  drafter / verifier:
+ * both caches committed to the same tokens but the *n_pend pending ones (drafter) / the last one (verifier).
+ * ev_every > 0: rounds 0, ev_every, 2 ev_every, ... record the HIP events ev_start[j] / ev_end[j] (hipEvent_t handles,
+ * j = round / ev_every) around the LM-head product alone, launched through the two-call form (same kernels).
+ *
+ * K: the first round's draft length (<= K_cap); follow_adl != 0: later rounds use the controller's proposal
+ * (clipped to K_cap), else K stays.  stop_at_eos != 0: return after the round that accepted eos_id.
+ * *n_pend in: the pending count of the first round; out: that of the next round (n_accept + 1 of the last one).
+ * records [host] ds_round_record[n_rounds], *rounds_done, tokens_out [host] int32[tokens_cap] (the committed tokens
+ * of all rounds in order, *n_tokens of them; DS_E_CAPACITY before a round that could overflow it).
+ * A round that fails returns its error; the rounds before it stand (their outputs and counts are valid). */
+typedef struct ds_round_desc {
+  ds_model* drafter;
+  ds_model* verifier;
+  const ds_ngram* proxy; /* NULL: no proxy term */
+  ds_adl* adl;
+  int32_t K_cap, M_max, beam, eos_id, mask_id;
+  float tau, lambda;
+  float* hidden;       /* [dev] float[K_cap, drafter d_model] */
+  float* cand_logp;    /* [dev] float[K_cap, M_max] */
+  int32_t* cand_cnt;   /* [dev] int32[K_cap] */
+  float* eos_logp;     /* [dev] float[K_cap] */
+  float* lse;          /* [dev] float[K_cap] */
+  int32_t* io;         /* [dev] see above */
+  float* path_score;   /* [dev] float[1] */
+  int32_t* argmax;     /* [dev] int32[K_cap + 1] */
+  void* cps_ws;        /* [dev] ds_cps_workspace_bytes(1, K_cap, M_max), or NULL */
+  size_t cps_ws_bytes;
+  void* drafter_ws;    /* [dev] model workspaces */
+  size_t drafter_ws_bytes;
+  void* verifier_ws;
+  size_t verifier_ws_bytes;
+  int32_t* verdict;    /* [host, pinned] int32[3] */
+  int32_t* host_out;   /* [host, pinned] */
+  int32_t ev_every;
+  void* const* ev_start;
+  void* const* ev_end;
+} ds_round_desc;
+typedef struct ds_round_record {
+  int32_t k, path_len, n_accept, next_token, eos_accepted, first_eos, k_next;
+} ds_round_record;
+int ds_round_io_layout(int K_cap, int M_max, int* path_at, int* len_at, int* cand_at, int* total);
+int ds_rounds_run(const ds_round_desc* d, int n_rounds, int K, int follow_adl, int stop_at_eos, int* n_pend,
+                  ds_round_record* records, int* rounds_done, int32_t* tokens_out, int tokens_cap, int* n_tokens,
+                  void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,7 @@ EXPORTS = [
     "ds_kv_create", "ds_kv_destroy", "ds_kv_len", "ds_kv_set_len", "ds_prefill_seq", "ds_draft_block_batch",
     "ds_verify_block_batch", "ds_verify_block_carry",
     "ds_lmproxy_bytes", "ds_lmproxy_create", "ds_lmproxy_destroy", "ds_lmproxy_prefill", "ds_lmproxy_len",
-    "ds_lmproxy_set_len", "ds_cps_path_lm",
+    "ds_lmproxy_set_len", "ds_cps_path_lm", "ds_round_io_layout", "ds_rounds_run",
 ]
 
 
@@ -53,6 +53,24 @@ class LayerWeightsC(C.Structure):
 class WeightsC(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("layers", C.POINTER(LayerWeightsC)), ("final_norm", C.c_void_p),
                 ("lm_head", C.c_void_p)]
+
+
+class RoundDescC(C.Structure):
+    _fields_ = [("drafter", C.c_void_p), ("verifier", C.c_void_p), ("proxy", C.c_void_p), ("adl", C.c_void_p),
+                ("K_cap", C.c_int32), ("M_max", C.c_int32), ("beam", C.c_int32), ("eos_id", C.c_int32),
+                ("mask_id", C.c_int32), ("tau", C.c_float), ("lam", C.c_float),
+                ("hidden", C.c_void_p), ("cand_logp", C.c_void_p), ("cand_cnt", C.c_void_p), ("eos_logp", C.c_void_p),
+                ("lse", C.c_void_p), ("io", C.c_void_p), ("path_score", C.c_void_p), ("argmax", C.c_void_p),
+                ("cps_ws", C.c_void_p), ("cps_ws_bytes", C.c_size_t),
+                ("drafter_ws", C.c_void_p), ("drafter_ws_bytes", C.c_size_t),
+                ("verifier_ws", C.c_void_p), ("verifier_ws_bytes", C.c_size_t),
+                ("verdict", C.c_void_p), ("host_out", C.c_void_p),
+                ("ev_every", C.c_int32), ("ev_start", C.POINTER(C.c_void_p)), ("ev_end", C.POINTER(C.c_void_p))]
+
+
+class RoundRecordC(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("k", "path_len", "n_accept", "next_token", "eos_accepted", "first_eos",
+                                         "k_next")]
 
 
 def lib_path() -> str:
@@ -119,6 +137,10 @@ def load():
     lib.ds_lmproxy_set_len.argtypes = [vp, C.c_int]
     lib.ds_cps_path_lm.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_float, vp, vp, C.c_int, i32, vp, vp,
                                    vp, vp, sz, vp]
+    ip = C.POINTER(C.c_int)
+    lib.ds_round_io_layout.argtypes = [C.c_int, C.c_int, ip, ip, ip, ip]
+    lib.ds_rounds_run.argtypes = [C.POINTER(RoundDescC), C.c_int, C.c_int, C.c_int, C.c_int, ip,
+                                  C.POINTER(RoundRecordC), ip, vp, C.c_int, ip, vp]
     lib.ds_verify_block_carry.argtypes = [vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_sample_workspace_bytes.argtypes = [C.c_int, C.POINTER(sz)]
     lib.ds_accept_stochastic.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -383,6 +405,23 @@ def ds_cps_path_lm(cand_id, cand_logp, cand_cnt, eos_logp, k: int, m_max: int, b
     _check(load().ds_cps_path_lm(_ptr(cand_id), _ptr(cand_logp), _ptr(cand_cnt), _ptr(eos_logp), k, m_max, beam, lam,
                                  proxy, _ptr(pending), n_pend, eos_id, _ptr(path), _ptr(path_len), _ptr(path_score),
                                  _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ds_round_io_layout(k_cap: int, m_max: int):
+    """(path_at, len_at, cand_at, total) of the round loop's device int buffer."""
+    out = [C.c_int(0) for _ in range(4)]
+    _check(load().ds_round_io_layout(k_cap, m_max, *[C.byref(o) for o in out]))
+    return tuple(o.value for o in out)
+
+
+def ds_rounds_run(desc: RoundDescC, n_rounds: int, k: int, follow_adl: bool, stop_at_eos: bool, n_pend: int,
+                  records, tokens_out, tokens_cap: int, stream=None):
+    """records: (RoundRecordC * n)() array; tokens_out: address of a host int32 buffer of tokens_cap entries.
+    Returns (rounds_done, n_tokens, n_pend of the next round)."""
+    pend, done, n_tok = C.c_int(n_pend), C.c_int(0), C.c_int(0)
+    _check(load().ds_rounds_run(C.byref(desc), n_rounds, k, int(follow_adl), int(stop_at_eos), C.byref(pend), records,
+                                C.byref(done), tokens_out, tokens_cap, C.byref(n_tok), _stream(stream)))
+    return done.value, n_tok.value, pend.value
 
 
 def ds_verify_block_carry(model: int, block, m: int, path_len, eos_id: int, n_accept, next_token, argmax,

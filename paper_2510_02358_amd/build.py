@@ -16,7 +16,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libdiffuspec.so")
-SOURCES = ["ds_api.hip", "ds_model.hip", "k_lattice.hip", "k_cps.hip", "k_cps_lm.hip", "k_gemm.hip", "k_elem.hip", "k_attn.hip",
+SOURCES = ["ds_api.hip", "ds_model.hip", "ds_round.hip", "k_lattice.hip", "k_cps.hip", "k_cps_lm.hip", "k_gemm.hip", "k_elem.hip", "k_attn.hip",
            "k_sample.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

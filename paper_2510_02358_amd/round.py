@@ -161,12 +161,11 @@ class SpecDecoder:
         # its length, the candidate ids) lives in ONE device tensor, so that a round costs one host -> device and one
         # device -> host copy:   [pending, right-aligned | ctx0 | ctx1 = block[0] | path ... | path_len | pad | cand_id]
         # The last committed token is both the newer context token and the first row of the verify block.
+        # (the layout the library's own round loop uses: ds_round_io_layout)
         P = ds.DS_MAX_ROWS
         self._p = P
-        self._out0 = P + 2                                   # first int the host reads back
-        self._len_at = P + 2 + k_cap
-        self._cand_at = (self._len_at + 1 + 3) // 4 * 4       # 16-byte aligned
-        self.io = torch.zeros(self._cand_at + k_cap * m, dtype=i32, device=DEV)
+        self._out0, self._len_at, self._cand_at, io_total = ds.ds_round_io_layout(k_cap, m)   # first int read back, ...
+        self.io = torch.zeros(io_total, dtype=i32, device=DEV)
         self.ctx = self.io[P:P + 2]
         self.block = self.io[P + 1:P + 2 + k_cap]             # [last token, path...]
         self.path_len = self.io[self._len_at:self._len_at + 1]
@@ -195,6 +194,7 @@ class SpecDecoder:
         self._cand_host_ptr = self.host_out.data_ptr() + 4 * (self._cand_at - self._out0)
         self.host_raw0 = torch.empty(k_cap, dtype=i32).pin_memory()          # refinement rounds: the final lattice's top-1
         self.k_cap = k_cap
+        self._desc = None
         self.tokens: List[int] = []
         self.pending: List[int] = []
         self._carried = False  # True: the device already holds the next round's pending tokens and context
@@ -377,6 +377,71 @@ class SpecDecoder:
         k_next = ds.ds_adl_update(self.adl, k, first_eos, n_acc)
         return {"k": k, "path": path, "path_len": plen, "n_accept": n_acc, "next_token": nxt, "eos_accepted": eos,
                 "committed": committed, "first_eos": first_eos, "k_next": k_next}
+
+
+    def _round_desc(self) -> "ds.RoundDescC":
+        if self._desc is None:
+            p, d = self.p, ds.RoundDescC()
+            d.drafter, d.verifier, d.proxy, d.adl = self.d.handle, self.v.handle, self.proxy, self.adl
+            d.K_cap, d.M_max, d.beam, d.eos_id, d.mask_id = self.k_cap, p.m_max, p.beam, self.eos_id, self.mask_id
+            d.tau, d.lam = p.tau, p.lam
+            d.hidden, d.cand_logp, d.cand_cnt = self.hidden.data_ptr(), self.cand_logp.data_ptr(), self.cand_cnt.data_ptr()
+            d.eos_logp, d.lse, d.io = self.eos_logp.data_ptr(), self.lse.data_ptr(), self.io.data_ptr()
+            d.path_score, d.argmax = self.path_score.data_ptr(), self.argmax.data_ptr()
+            d.cps_ws, d.cps_ws_bytes = self.cps_ws.data_ptr(), self.cps_ws.numel()
+            d.drafter_ws, d.drafter_ws_bytes = self.d.ws.data_ptr(), self.d.ws.numel()
+            d.verifier_ws, d.verifier_ws_bytes = self.v.ws.data_ptr(), self.v.ws.numel()
+            d.verdict, d.host_out = self.result.data_ptr(), self.host_out.data_ptr()
+            self._desc = d
+        return self._desc
+
+    def run(self, n_rounds: int, k: int, follow_adl: bool = True, stop_at_eos: bool = True, lm_events=None) -> list:
+        """n_rounds rounds inside the library's own loop (ds_rounds_run): greedy verification, single-pass draft,
+        n-gram proxy.  The same calls as round(), with the host's per-round work done in C.
+        lm_events = (ev_every, [(start, end) torch events, already recorded once so that their handles exist]):
+        round j * ev_every records pair j around the drafter's LM-head product.
+        Returns one dict per round done (the fields of round())."""
+        if self.p.refine_steps > 1 or self.lm_proxy:
+            raise ValueError("the library's round loop drives the single-pass draft with the n-gram proxy")
+        if n_rounds <= 0:
+            return []
+        if not self._carried:
+            self.stage_inputs()
+        self._carried = False
+        d = self._round_desc()
+        keep = None
+        if lm_events is not None:
+            every, pairs = lm_events
+            n_ev = (n_rounds + every - 1) // every
+            if len(pairs) < n_ev:
+                raise ValueError(f"{n_rounds} rounds with an event pair every {every} need {n_ev} pairs")
+            starts = (ctypes.c_void_p * n_ev)(*[a.cuda_event for a, _ in pairs[:n_ev]])
+            ends = (ctypes.c_void_p * n_ev)(*[b.cuda_event for _, b in pairs[:n_ev]])
+            d.ev_every, d.ev_start, d.ev_end, keep = every, starts, ends, (starts, ends)
+        else:
+            d.ev_every = 0
+        records = (ds.RoundRecordC * n_rounds)()
+        cap = n_rounds * (self.k_cap + 1)
+        tokens = np.empty(cap, dtype=np.int32)
+        try:
+            done, n_tok, _ = ds.ds_rounds_run(d, n_rounds, k, follow_adl, stop_at_eos, len(self.pending), records,
+                                              tokens.ctypes.data, cap)
+        finally:
+            d.ev_every = 0
+            del keep
+        out, at = [], 0
+        for r in records[:done]:
+            committed = [int(t) for t in tokens[at:at + r.n_accept + 1]]
+            at += r.n_accept + 1
+            out.append({"k": r.k, "path_len": r.path_len, "n_accept": r.n_accept, "next_token": r.next_token,
+                        "eos_accepted": r.eos_accepted, "committed": committed, "first_eos": r.first_eos,
+                        "k_next": r.k_next})
+        assert at == n_tok
+        self.tokens += [int(t) for t in tokens[:n_tok]]
+        if out:
+            self.pending = out[-1]["committed"]
+            self._carried = True
+        return out
 
 
 class BatchSpecDecoder:

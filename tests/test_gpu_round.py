@@ -219,6 +219,54 @@ def test_verify_carry_leaves_the_next_rounds_inputs_on_the_device(cfg_name):
         dm.close(); vm.close()
 
 
+@pytest.mark.parametrize("cfg_name", ["f32", "bf16"])
+def test_library_round_loop_equals_the_round_by_round_driver(cfg_name):
+    """ds_rounds_run (the loop inside the library) against SpecDecoder.round() called round by round on the same
+    models: the same verdicts, first-EOS indices, draft-length proposals, committed tokens and cache lengths, also
+    when the two ways of driving alternate, and with the event pairs around the LM head switched on."""
+    cfg = synth.CFG_TINY if cfg_name == "f32" else synth.ModelCfg(
+        n_layers=2, d_model=256, n_q=4, n_kv=2, head_dim=128, d_ffn=512, vocab=4096, rope_base=1.0e6, dtype="bf16")
+    dw, vw = synth.make_weights(cfg, 0), synth.make_weights(cfg, 1)
+    prefix = synth.make_prefix(cfg, 100, 13)
+    table = synth.make_ngram_table(3)
+    params = rnd.RoundParams(m_max=4, tau=0.9, beam=4, lam=0.5, k_min=2, k_max=12, delta=2.0, rho=0.5)
+    dm, vm = rnd.DeviceModel(cfg, dw, 256), rnd.DeviceModel(cfg, vw, 256)
+    keys = ("k", "path_len", "n_accept", "next_token", "eos_accepted", "first_eos", "k_next", "committed")
+    try:
+        a = rnd.SpecDecoder(dm, vm, table, synth.NGRAM_LOG2_SIZE, params, k_cap=16)
+        a.start(prefix)
+        want, k = [], 8
+        for _ in range(7):
+            got = a.round(k)
+            want.append({n: (list(got[n]) if n == "committed" else int(got[n])) for n in keys})
+            k = got["k_next"]
+        want_tokens, want_len = list(a.tokens), (dm.kv_len, vm.kv_len)
+        a.close()
+
+        b = rnd.SpecDecoder(dm, vm, table, synth.NGRAM_LOG2_SIZE, params, k_cap=16)
+        b.start(prefix)
+        got = b.run(2, 8)                                  # two rounds in the library's loop,
+        one = b.round(got[-1]["k_next"])                   # one by hand,
+        got.append({n: (list(one[n]) if n == "committed" else int(one[n])) for n in keys})
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(2)]
+        for e0, e1 in pairs:
+            e0.record(); e1.record()
+        torch.cuda.synchronize()
+        got += b.run(4, got[-1]["k_next"], lm_events=(2, pairs))   # and four more, two of them with events
+        torch.cuda.synchronize()
+        assert all(e0.elapsed_time(e1) > 0.0 for e0, e1 in pairs)
+        assert [{n: r[n] for n in keys} for r in got] == want
+        assert b.tokens == want_tokens and (dm.kv_len, vm.kv_len) == want_len
+        assert b.pending == want[-1]["committed"]
+        # a fixed draft length, and stopping at an accepted EOS (none here: all rounds run)
+        b.start(prefix)
+        fixed = b.run(3, 6, follow_adl=False, stop_at_eos=True)
+        assert [r["k"] for r in fixed] == [6, 6, 6] and len(fixed) == 3
+        b.close()
+    finally:
+        dm.close(); vm.close()
+
+
 def test_gpu_ar_greedy_matches_oracle_and_injected_rounds_are_lossless():
     """The GPU's one-token-per-step greedy decode equals the oracle's; speculative rounds whose path is
     partly overwritten with that stream (synthetic acceptance) commit exactly the same stream."""
