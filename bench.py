@@ -534,27 +534,42 @@ def main() -> int:
     setup_s = time.time() - t0
     p0 = PREFIX
 
-    # ---- the timed loop: full rounds of the host driver.  K stays 32 (the workload fixes it); the controller's
-    # proposal is computed every round and not followed.  With independent random-init models nothing is accepted, so
-    # every round commits one token and the next round has one pending row; the caches grow by one token per round.
-    # The LM-head GEMM is bracketed by two events on every EV_EVERY-th timed round (an event pair costs the round
-    # about 5 us of stream time, so timing every round would tax the quantity being measured).
+    # ---- the timed loop: full rounds of the host loop inside the library (ds_rounds_run: the four calls, path and
+    # candidate read-back, verdict, KV commit, first-EOS index, draft-length update, committed tokens appended to a host
+    # array).  K stays 32 (the workload fixes it); the controller's proposal is computed every round and not followed.
+    # With independent random-init models nothing is accepted, so every round commits one token and the next round has
+    # one pending row; the caches grow by one token per round.  The LM-head GEMM is bracketed by two events on every
+    # EV_EVERY-th timed round (an event pair costs the round about 5 us of stream time, so timing every round would tax
+    # the quantity being measured).
     EV_EVERY = 4
-    ev = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for i in range(0, args.steps, EV_EVERY)}
-    n_committed = n_accepted = 0
-    for _ in range(args.warmup):
-        dec.round(K_DRAFT)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(0, args.steps, EV_EVERY)]
+    for a, b in pairs:      # a first record creates the events' handles
+        a.record()
+        b.record()
+    dec.run(args.warmup, K_DRAFT, follow_adl=False, stop_at_eos=False)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for i in range(args.steps):
-        got = dec.round(K_DRAFT, lm_events=ev.get(i))
-        n_committed += got["n_accept"] + 1
-        n_accepted += got["n_accept"]
+    recs = dec.run(args.steps, K_DRAFT, follow_adl=False, stop_at_eos=False, lm_events=(EV_EVERY, pairs))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t1
+    assert len(recs) == args.steps
+    n_accepted = sum(r["n_accept"] for r in recs)
+    n_committed = n_accepted + len(recs)
     ms_per_step = elapsed * 1e3 / args.steps
     rounds_per_s = args.steps / elapsed
+    ev = dict(enumerate(pairs))
+
+    # the same loop driven round by round from Python (SpecDecoder.round(): one ctypes call per stage)
+    for _ in range(5):
+        dec.round(K_DRAFT)
+    torch.cuda.synchronize()
+    t_py = time.perf_counter()
+    n_py = max(20, args.steps // 2)
+    for _ in range(n_py):
+        dec.round(K_DRAFT)
+    torch.cuda.synchronize()
+    py_ms = (time.perf_counter() - t_py) * 1e3 / n_py
 
     lm_ms = sum(a.elapsed_time(b) for a, b in ev.values()) / len(ev)
     ab = algorithmic_bytes(cfg, PREFIX)
@@ -637,13 +652,15 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "cfg1: 7B-shaped decoder layer + LM head (d=3584, 28q/4kv x128, FFN 18944, "
                                "vocab 152064), drafter + verifier, prefix 2048, K=32, top-8 lattice, beam 4, "
-                               "33 verify rows, batch 1; full host loop (path read-back, KV commit, "
+                               "33 verify rows, batch 1; full host loop inside the library (path read-back, KV commit, "
                                "draft-length update)"},
         "committed_tokens_per_s": round(n_committed / elapsed, 2),
         "accepted_draft_tokens_per_s": round(n_accepted / elapsed, 2),
         "acceptance_note": "independent random-init models accept no draft token: one committed token (the verifier's "
                            "correction) per round; see synthetic_acceptance for the loop at the paper's acceptance level",
         "round_hbm_frac": round(round_gbps / HBM_PEAK_GBS, 4),
+        "python_driven_round": {"ms": round(py_ms, 4), "rounds_per_s": round(1e3 / py_ms, 1),
+                                "note": "the same full loop with the host's part in Python, one call per stage"},
         "device_only_round": {"ms": round(dev_ms, 4), "rounds_per_s": round(1e3 / dev_ms, 1),
                               "round_hbm_frac": round(ab["round"] / (dev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                               "note": "same calls without path read-back and host bookkeeping"},
