@@ -201,13 +201,18 @@ void ds_ngram_destroy(ds_ngram* g);
  * proxy NULL: l_ng = 0.  ctx [dev] int32[batch, 2]: the two tokens before each block (older first).
  * Outputs [dev]: path int32[batch, K] (tail beyond the length = -1), path_len int32[batch],
  * path_score float[batch].  1 <= B <= DS_MAX_BEAM, 1 <= M_max <= DS_MAX_TOPM, 1 <= K <= 256.
+ * host_mirror, optional (NULL allowed) [host, pinned, device-visible] int32[batch, 2 K + 1]: the kernel also stores
+ * there, per sequence, the path (K entries, tail -1), its length, and the raw draft (the top candidate of each of
+ * the K positions: what the first-EOS index of Sec. 3.3 is taken from), so that a host loop reads them without a
+ * copy of its own; they are complete once any later work of the stream is seen to have completed.
  * ws [dev], optional (NULL allowed): ds_cps_workspace_bytes() bytes of scratch that lets the proxy scores
  * be gathered by the whole chip before the search starts; results do not depend on it. */
 int ds_cps_workspace_bytes(int batch, int K, int M_max, size_t* bytes);
 int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
                 const float* eos_logp, int batch, int K, int M_max, int B, float lambda,
                 const ds_ngram* proxy, const int32_t* ctx, int32_t eos_id, int32_t* path,
-                int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, void* stream);
+                int32_t* path_len, float* path_score, int32_t* host_mirror, void* ws, size_t ws_bytes,
+                void* stream);
 
 /* Step 3 with the other causal proxy the paper names: a tiny causal LM instead of the n-gram table
  * (Sec. 3.2 "Scoring and search": the path score mixes the drafter's log-score with a small causal proxy,
@@ -377,7 +382,8 @@ int ds_adl_state(const ds_adl* a, double* l_gen_ema, double* l_acc_ema);
  *   io[path_at, path_at + K_cap)        the searched path (path_at = DS_MAX_ROWS + 2), io[len_at] its length
  *   io[cand_at, + K_cap * M_max)        the lattice's candidate ids (cand_at a multiple of 4)
  * Before the first call the caller writes the pending tokens and the two context tokens there; afterwards the
- * acceptance kernel does.  host_out [host, pinned] int32[total - path_at] receives io[path_at, total) every round;
+ * acceptance kernel does.  host_out [host, pinned, device-visible] int32[2 K_cap + 1] is the path search's
+ * host_mirror (path, length, raw draft of every round);
  * verdict [host, pinned, device-visible] int32[3] receives n_accept, next_token, eos_accepted.  drafter / verifier:
  * both caches committed to the same tokens but the *n_pend pending ones (drafter) / the last one (verifier).
  * ev_every > 0: rounds 0, ev_every, 2 ev_every, ... record the HIP events ev_start[j] / ev_end[j] (hipEvent_t handles,
@@ -411,7 +417,7 @@ typedef struct ds_round_desc {
   void* verifier_ws;
   size_t verifier_ws_bytes;
   int32_t* verdict;    /* [host, pinned] int32[3] */
-  int32_t* host_out;   /* [host, pinned] */
+  int32_t* host_out;   /* [host, pinned] int32[2 K_cap + 1] */
   int32_t ev_every;
   void* const* ev_start;
   void* const* ev_end;

@@ -125,7 +125,7 @@ def load():
     lib.ds_ngram_create.argtypes = [vp, C.c_int, C.POINTER(vp)]
     lib.ds_ngram_destroy.argtypes = [vp]
     lib.ds_cps_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(sz)]
-    lib.ds_cps_path.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, vp, i32, vp, vp, vp, vp, sz,
+    lib.ds_cps_path.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, vp, i32, vp, vp, vp, vp, vp, sz,
                                 vp]
     lib.ds_verify_block.argtypes = [vp, vp, C.c_int, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ds_lmproxy_bytes.argtypes = [vp, C.c_int, C.POINTER(sz)]
@@ -357,10 +357,11 @@ def ds_cps_workspace_bytes(batch: int, k: int, m_max: int) -> int:
 
 
 def ds_cps_path(cand_id, cand_logp, cand_cnt, eos_logp, batch: int, k: int, m_max: int, beam: int, lam: float,
-                proxy: Optional[int], ctx, eos_id: int, path, path_len, path_score, ws=None, stream=None) -> None:
+                proxy: Optional[int], ctx, eos_id: int, path, path_len, path_score, ws=None, stream=None,
+                host_mirror=None) -> None:
     _check(load().ds_cps_path(_ptr(cand_id), _ptr(cand_logp), _ptr(cand_cnt), _ptr(eos_logp), batch, k, m_max, beam,
                               lam, proxy, _ptr(ctx), eos_id, _ptr(path), _ptr(path_len), _ptr(path_score),
-                              _ptr(ws), _nbytes(ws) if ws is not None else 0, _stream(stream)))
+                              _ptr(host_mirror), _ptr(ws), _nbytes(ws) if ws is not None else 0, _stream(stream)))
 
 
 def ds_verify_block(model: int, block, m: int, path_len, eos_id: int, n_accept, next_token, argmax, eos_accepted,

@@ -146,7 +146,8 @@ void ds_ngram_destroy(ds_ngram* g) { delete g; }
 int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
                 const float* eos_logp, int batch, int K, int M_max, int B, float lambda,
                 const ds_ngram* proxy, const int32_t* ctx, int32_t eos_id, int32_t* path,
-                int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, void* stream) {
+                int32_t* path_len, float* path_score, int32_t* host_mirror, void* ws, size_t ws_bytes,
+                void* stream) {
   DS_REQUIRE(batch >= 0, DS_E_SHAPE, "batch %d is negative", batch);
   if (batch == 0) return DS_OK;
   DS_REQUIRE(cand_id && cand_logp && cand_cnt && ctx && path && path_len && path_score, DS_E_INVALID,
@@ -159,7 +160,7 @@ int ds_cps_path(const int32_t* cand_id, const float* cand_logp, const int32_t* c
   DS_REQUIRE(!ws || (((uintptr_t)ws) & 15) == 0, DS_E_INVALID, "workspace not 16-byte aligned");
   return launch_cps(cand_id, cand_logp, cand_cnt, eos_logp, batch, K, M_max, B, lambda,
                     proxy ? proxy->table : nullptr, proxy ? proxy->log2_size : 0, ctx, eos_id, path, path_len,
-                    path_score, ws, ws_bytes, static_cast<hipStream_t>(stream));
+                    path_score, host_mirror, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int ds_sample_workspace_bytes(int m, size_t* bytes) {

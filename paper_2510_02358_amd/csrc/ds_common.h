@@ -122,7 +122,7 @@ int launch_lattice_tiles(const void* rec, int rows, int n_tiles, int m_max, floa
 int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
                const float* eos_logp, int batch, int K, int m_max, int B, float lambda,
                const float* table, int log2_size, const int32_t* ctx, int32_t eos_id, int32_t* path,
-               int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, hipStream_t st);
+               int32_t* path_len, float* path_score, int32_t* mirror, void* ws, size_t ws_bytes, hipStream_t st);
 size_t cps_ws_bytes(int batch, int K, int m_max);
 
 // ---- path search with a tiny causal LM as the proxy (k_cps_lm.hip) ------------------------------------

@@ -1,8 +1,8 @@
 // Host side of the speculative loop (Alg. 1, all four stages, round after round) as one C-ABI call.
 //
 // This file is a client of the library's own entry points: it holds no kernel and no arithmetic of the method.
-// Per round it enqueues draft -> LM head / lattice -> path search -> copy of the searched path and the candidate
-// ids to pinned host memory -> verification with the carry output, then waits for the verdict (a poll of the word
+// Per round it enqueues draft -> LM head / lattice -> path search (whose kernel also leaves the path, its length and
+// the raw draft in pinned host memory) -> verification with the carry output, then waits for the verdict (a poll of the word
 // the acceptance kernel stores last in device-visible pinned memory; bounded, with a stream synchronisation as the
 // fallback), commits the verifier's cache length, takes the first-EOS index of the raw draft from the host copy,
 // updates the draft-length controller and appends the committed tokens to the caller's host array.  Nothing is
@@ -73,7 +73,6 @@ int ds_rounds_run(const ds_round_desc* d, int n_rounds, int K, int follow_adl, i
   int32_t* io = d->io;
   int32_t* cand_id = io + cand_at;
   volatile int32_t* verdict = d->verdict;
-  const size_t out_bytes = (size_t)(total - path_at) * sizeof(int32_t);
   int pend = *n_pend, used = 0;
   *n_tokens = 0;
   *rounds_done = 0;
@@ -104,23 +103,21 @@ int ds_rounds_run(const ds_round_desc* d, int n_rounds, int K, int follow_adl, i
       return rc;
     }
     if ((rc = ds_cps_path(cand_id, d->cand_logp, d->cand_cnt, d->eos_logp, 1, K, d->M_max, d->beam, d->lambda,
-                          d->proxy, io + P, d->eos_id, io + path_at, io + len_at, d->path_score, d->cps_ws,
-                          d->cps_ws_bytes, st)))
+                          d->proxy, io + P, d->eos_id, io + path_at, io + len_at, d->path_score, d->host_out,
+                          d->cps_ws, d->cps_ws_bytes, st)))
       return rc;
-    // everything the host reads besides the verdict is final now: the copy runs under the verifier pass
-    DS_HIP_CHECK(hipMemcpyAsync(d->host_out, io + path_at, out_bytes, hipMemcpyDeviceToHost, st));
     if ((rc = ds_verify_block_carry(d->verifier, io + P + 1, K, io + len_at, d->eos_id, d->verdict, d->verdict + 1,
                                     d->argmax, d->verdict + 2, nullptr, io, d->verifier_ws, d->verifier_ws_bytes,
                                     st)))
       return rc;
     if ((rc = wait_verdict(verdict + 2, st))) return rc;
     const int n_acc = verdict[0], nxt = verdict[1], eos = verdict[2];
-    const int plen = d->host_out[len_at - path_at];
+    const int plen = d->host_out[K];  // the search's mirror: path [K], length, raw draft [K]
     DS_REQUIRE(n_acc >= 0 && n_acc <= K && plen >= 0 && plen <= K && n_acc <= plen, DS_E_HIP,
                "round %d: verdict out of range (n_accept %d, path_len %d)", t, n_acc, plen);
     if ((rc = ds_model_kv_set_len(d->verifier, v_len + 1 + n_acc))) return rc;
     int first_eos = 0, k_next = K;
-    if ((rc = ds_adl_first_eos(d->host_out + (cand_at - path_at), K, d->M_max, d->eos_id, &first_eos))) return rc;
+    if ((rc = ds_adl_first_eos(d->host_out + K + 1, K, 1, d->eos_id, &first_eos))) return rc;
     if ((rc = ds_adl_update(d->adl, K, first_eos, n_acc, &k_next))) return rc;
     for (int i = 0; i < n_acc; ++i) tokens_out[used + i] = d->host_out[i];
     tokens_out[used + n_acc] = nxt;

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
                                                    uint32_t table_mask, const int32_t* __restrict__ ctx,
                                                    int32_t eos_id, const float* __restrict__ g,
                                                    int32_t* __restrict__ path, int32_t* __restrict__ path_len,
-                                                   float* __restrict__ path_score) {
+                                                   float* __restrict__ path_score, int32_t* __restrict__ mirror) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int CM = m_max + 1;
   Lds L;
@@ -306,16 +306,27 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
   if (!finished && n_live > 0) out_score = __uint_as_float((uint32_t)L.beam[(K & 1) * B].x);
 
   // back-track (lane 0 reads what other lanes of this wavefront wrote: LDS operations complete in order)
+  // mirror (optional, device-visible host memory): per sequence the path, its length and the raw draft (the top
+  // candidate of every position), so that a host loop needs no copy of its own to see them
+  int32_t* mine = mirror ? mirror + (size_t)seq * (2 * K + 1) : nullptr;
   if (lane == 0) {
     int slot = 0;
     for (int i = out_len - 1; i >= 0; --i) {
-      path[row0 + i] = L.bp_tok[i * B + slot];
+      const int32_t t = L.bp_tok[i * B + slot];
+      path[row0 + i] = t;
+      if (mine) mine[i] = t;
       slot = L.bp_par[i * B + slot];
     }
     path_len[seq] = out_len;
     path_score[seq] = out_score;
+    if (mine) mine[K] = out_len;
   }
-  for (int i = out_len + lane; i < K; i += kWave) path[row0 + i] = -1;
+  for (int i = out_len + lane; i < K; i += kWave) {
+    path[row0 + i] = -1;
+    if (mine) mine[i] = -1;
+  }
+  if (mine)
+    for (int i = lane; i < K; i += kWave) mine[K + 1 + i] = L.cand_tok[i * CM];
 }
 
 }  // namespace
@@ -328,7 +339,7 @@ size_t cps_ws_bytes(int batch, int K, int m_max) {
 int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* cand_cnt,
                const float* eos_logp, int batch, int K, int m_max, int B, float lambda,
                const float* table, int log2_size, const int32_t* ctx, int32_t eos_id, int32_t* path,
-               int32_t* path_len, float* path_score, void* ws, size_t ws_bytes, hipStream_t st) {
+               int32_t* path_len, float* path_score, int32_t* mirror, void* ws, size_t ws_bytes, hipStream_t st) {
   const int CM = m_max + 1;
   const size_t fixed = align_up(lds_fixed_bytes(K, CM, B), 16);
   const size_t pre = (size_t)K * CM * CM * CM * sizeof(float);
@@ -338,7 +349,7 @@ int launch_cps(const int32_t* cand_id, const float* cand_logp, const int32_t* ca
 #define DS_CPS_LAUNCH(PRE_, SLOTS_, THREADS_, LDS_)                                                          \
   hipLaunchKernelGGL((cps_kernel<PRE_, SLOTS_>), dim3(batch), dim3(THREADS_), LDS_, st, cand_id, cand_logp,   \
                      cand_cnt, eos_logp, K, m_max, B, lambda, table, mask, ctx, eos_id, g, path, path_len,   \
-                     path_score)
+                     path_score, mirror)
   const float* g = nullptr;
   if (use_pre && ws && ws_bytes >= cps_ws_bytes(batch, K, m_max)) {
     float* gw = static_cast<float*>(ws);

@@ -191,10 +191,12 @@ class SpecDecoder:
         self._host_ptr, self._io_ptr = self.host.data_ptr(), self.io.data_ptr()
         self.host_out = torch.empty(self.io.numel() - self._out0, dtype=i32).pin_memory()   # io[_out0:] as the host sees it
         self.host_out_np = self.host_out.numpy()
-        self._cand_host_ptr = self.host_out.data_ptr() + 4 * (self._cand_at - self._out0)
+        self._host_out_ptr = self.host_out.data_ptr()
+        self._cand_host_ptr = self._host_out_ptr + 4 * (self._cand_at - self._out0)
         self.host_raw0 = torch.empty(k_cap, dtype=i32).pin_memory()          # refinement rounds: the final lattice's top-1
         self.k_cap = k_cap
         self._desc = None
+        self._mirrored = False
         self.tokens: List[int] = []
         self.pending: List[int] = []
         self._carried = False  # True: the device already holds the next round's pending tokens and context
@@ -280,18 +282,22 @@ class SpecDecoder:
                                     stream)
                 ds.ds_refine_select(*lat, k, p.m_max, n, self.mask_id, self.blk, *final, stream)
             lat = final
+        # what the host reads besides the verdict: the search kernel mirrors path, length and raw draft into pinned
+        # host memory itself; rounds that change the path afterwards (injection) or search with the LM proxy copy
+        self._mirrored = readback and inject is None and not self.lm_proxy
         if self.lm_proxy:  # the proxy reads the same pending tokens as the drafter did
             ds.ds_cps_path_lm(lat[0], lat[1], lat[2], lat[3], k, p.m_max, p.beam, p.lam, self.lm_proxy,
                               self.pending_dev, n_pend, self.eos_id, self.block[1:], self.path_len, self.path_score,
                               self.lm.ws, stream)
         else:
             ds.ds_cps_path(lat[0], lat[1], lat[2], lat[3], 1, k, p.m_max, p.beam, p.lam, self.proxy, self.ctx,
-                           self.eos_id, self.block[1:], self.path_len, self.path_score, self.cps_ws, stream)
+                           self.eos_id, self.block[1:], self.path_len, self.path_score, self.cps_ws, stream,
+                           host_mirror=self.host_out if self._mirrored else None)
         self.lat_used = lat
         if inject is not None and inject[1] > 0:
             self.block[1:1 + inject[1]].copy_(inject[0][:inject[1]], non_blocking=True)
             self.path_len.fill_(k)  # the searched path may have stopped at an EOS before the injected length
-        if readback:
+        if readback and not self._mirrored:
             self.host_out.copy_(self.io[self._out0:], non_blocking=True)
             if lat[0] is not self.cand_id:  # refinement rounds keep the final lattice elsewhere
                 self.host_raw0[:k].copy_(lat[0][:k, 0], non_blocking=True)
@@ -363,13 +369,19 @@ class SpecDecoder:
         refined = self.lat_used[0] is not self.cand_id
         self.wait_verdict()  # the one host crossing; the path / candidate copy finished during the verifier pass
         out, res = self.host_out_np, self.result_np
-        n_acc, nxt, eos, plen = int(res[0]), int(res[1]), int(res[2]), int(out[self._len_at - self._out0])
-        path = out[:plen].copy()
-        # the raw draft (per-position top-1 before the search) as the host read it back: s_t of the controller
-        if refined:
-            first_eos = ds.ds_adl_first_eos(self.host_raw0, k, 1, self.eos_id)
+        n_acc, nxt, eos = int(res[0]), int(res[1]), int(res[2])
+        # the raw draft (per-position top-1 before the search) as the host sees it: s_t of the controller
+        if self._mirrored:      # [path k | length | raw draft k]
+            plen = int(out[k])
+            path = out[:plen].copy()
+            first_eos = ds.ds_adl_first_eos(self._host_out_ptr + 4 * (k + 1), k, 1, self.eos_id)
         else:
-            first_eos = ds.ds_adl_first_eos(self._cand_host_ptr, k, self.p.m_max, self.eos_id)
+            plen = int(out[self._len_at - self._out0])
+            path = out[:plen].copy()
+            if refined:
+                first_eos = ds.ds_adl_first_eos(self.host_raw0, k, 1, self.eos_id)
+            else:
+                first_eos = ds.ds_adl_first_eos(self._cand_host_ptr, k, self.p.m_max, self.eos_id)
         self.v.set_kv_len(v_len + 1 + n_acc)
         committed = [int(t) for t in path[:n_acc]] + [nxt]
         self.tokens += committed

@@ -99,10 +99,10 @@ def test_bad_arguments_are_rejected_on_the_host_before_any_launch():
     assert lib.ds_build_lattice(one, 4, 100, 4, 1.0, 100, one, one, one, one, one, one, 1 << 20, None) == ds.DS_E_INVALID
     assert lib.ds_build_lattice(one, 4, 100, 4, 1.0, -1, one, one, one, one, one, one, 16, None) == ds.DS_E_CAPACITY
     # path search
-    assert lib.ds_cps_path(None, None, None, None, 0, 8, 4, 4, 0.5, None, None, -1, None, None, None, None, 0, None) == ds.DS_OK
-    assert lib.ds_cps_path(one, one, one, one, 1, 0, 4, 4, 0.5, None, one, -1, one, one, one, None, 0, None) == ds.DS_E_SHAPE
-    assert lib.ds_cps_path(one, one, one, one, 1, 8, 4, 17, 0.5, None, one, -1, one, one, one, None, 0, None) == ds.DS_E_SHAPE
-    assert lib.ds_cps_path(one, one, one, one, 1, 8, 4, 4, 1.5, None, one, -1, one, one, one, None, 0, None) == ds.DS_E_INVALID
+    assert lib.ds_cps_path(None, None, None, None, 0, 8, 4, 4, 0.5, None, None, -1, None, None, None, None, None, 0, None) == ds.DS_OK
+    assert lib.ds_cps_path(one, one, one, one, 1, 0, 4, 4, 0.5, None, one, -1, one, one, one, None, None, 0, None) == ds.DS_E_SHAPE
+    assert lib.ds_cps_path(one, one, one, one, 1, 8, 4, 17, 0.5, None, one, -1, one, one, one, None, None, 0, None) == ds.DS_E_SHAPE
+    assert lib.ds_cps_path(one, one, one, one, 1, 8, 4, 4, 1.5, None, one, -1, one, one, one, None, None, 0, None) == ds.DS_E_INVALID
     assert ds.ds_cps_workspace_bytes(1, 32, 8) == (32 * 729 * 4 + 255) // 256 * 256
     # stochastic acceptance and the refinement update
     assert lib.ds_accept_stochastic(one, one, -1, 10, one, None, one, -1, one, one, one, one, one, 1024, None) == ds.DS_E_SHAPE

@@ -184,6 +184,44 @@ def test_cps_hand_worked_narrow_beams():
             assert plen[0] == 3 and list(path[0]) == want_toks and score[0] == np.float32(want_score), beam
 
 
+def test_cps_host_mirror_holds_path_length_and_raw_draft():
+    """The optional pinned-memory mirror of the search: per sequence the path (tail -1), its length and the top
+    candidate of every position, equal to what the device outputs and the lattice hold; with and without the
+    pre-gathered proxy scores, EOS stopping some sequences early."""
+    from paper_2510_02358_amd import binding as ds
+    rng = np.random.default_rng(77)
+    batch, k, m_max, beam, eos = 3, 11, 5, 4, VOCAB - 2
+    rows = batch * k
+    cand_id = np.stack([rng.choice(VOCAB - 2, size=m_max, replace=False) for _ in range(rows)]).astype(np.int32)
+    cand_logp = np.sort(rng.standard_normal((rows, m_max)).astype(np.float32) - 6.0, axis=1)[:, ::-1].copy()
+    eos_logp = (cand_logp[:, 0] - np.float32(1.0)).astype(np.float32)
+    eos_logp[k + 4] = cand_logp[k + 4, 0] + np.float32(7.0)          # sequence 1 stops at depth 5
+    lat = {"cand_id": cand_id, "cand_logp": cand_logp, "cand_cnt": np.full(rows, m_max, np.int32), "eos_logp": eos_logp}
+    d = {n: gu.to_dev(v) for n, v in lat.items()}
+    table = gu.to_dev(synth.make_ngram_table(3))
+    proxy = ds.ds_ngram_create(table, synth.NGRAM_LOG2_SIZE)
+    ctx = gu.to_dev(synth.make_contexts(VOCAB, batch, 5))
+    try:
+        for with_ws in (True, False):
+            path = torch.empty(batch, k, dtype=torch.int32, device=gu.DEV)
+            plen = torch.empty(batch, dtype=torch.int32, device=gu.DEV)
+            score = torch.empty(batch, dtype=torch.float32, device=gu.DEV)
+            mirror = torch.full((batch, 2 * k + 1), -9, dtype=torch.int32).pin_memory()
+            ws = torch.empty(ds.ds_cps_workspace_bytes(batch, k, m_max), dtype=torch.uint8, device=gu.DEV) if with_ws else None
+            ds.ds_cps_path(d["cand_id"], d["cand_logp"], d["cand_cnt"], d["eos_logp"], batch, k, m_max, beam, 0.5, proxy,
+                           ctx, eos, path, plen, score, ws, host_mirror=mirror)
+            torch.cuda.synchronize()
+            m = mirror.numpy()
+            assert np.array_equal(m[:, :k], path.cpu().numpy())
+            assert np.array_equal(m[:, k], plen.cpu().numpy()) and m[1, k] == 5 and m[1, 4] == eos
+            assert np.array_equal(m[:, k + 1:], cand_id[:, 0].reshape(batch, k))
+            ref = o_cps.cps_batch(lat, batch, k, beam, 0.5, synth.make_ngram_table(3), synth.NGRAM_LOG2_SIZE,
+                                  ctx.cpu().numpy(), eos)
+            assert np.array_equal(m[:, :k], ref[0])
+    finally:
+        ds.ds_ngram_destroy(proxy)
+
+
 def test_lattice_then_cps_end_to_end_on_device():
     """Lattice arrays stay on the device between the two calls; compared against the oracle chain fed
     with the SAME float32 logits.  Path equality can only break at float32 near-ties of scores, which
