@@ -305,28 +305,32 @@ __global__ __launch_bounds__(1024) void cps_kernel(const int32_t* __restrict__ c
   // the search ran to the end: the result is the best live hypothesis of the last step
   if (!finished && n_live > 0) out_score = __uint_as_float((uint32_t)L.beam[(K & 1) * B].x);
 
-  // back-track (lane 0 reads what other lanes of this wavefront wrote: LDS operations complete in order)
+  // back-track: lane 0 walks the parents (it reads what other lanes of this wavefront wrote: the LDS operations of a
+  // wavefront complete in order) and leaves the path's token of depth i in slot 0 of that depth, which the walk no
+  // longer needs; then all lanes store the path.
   // mirror (optional, device-visible host memory): per sequence the path, its length and the raw draft (the top
-  // candidate of every position), so that a host loop needs no copy of its own to see them
+  // candidate of every position), so that a host loop needs no copy of its own to see them.
   int32_t* mine = mirror ? mirror + (size_t)seq * (2 * K + 1) : nullptr;
   if (lane == 0) {
     int slot = 0;
     for (int i = out_len - 1; i >= 0; --i) {
       const int32_t t = L.bp_tok[i * B + slot];
-      path[row0 + i] = t;
-      if (mine) mine[i] = t;
       slot = L.bp_par[i * B + slot];
+      L.bp_tok[i * B] = t;
     }
     path_len[seq] = out_len;
     path_score[seq] = out_score;
     if (mine) mine[K] = out_len;
   }
-  for (int i = out_len + lane; i < K; i += kWave) {
-    path[row0 + i] = -1;
-    if (mine) mine[i] = -1;
+  __builtin_amdgcn_wave_barrier();
+  for (int i = lane; i < K; i += kWave) {
+    const int32_t t = i < out_len ? L.bp_tok[i * B] : -1;
+    path[row0 + i] = t;
+    if (mine) {
+      mine[i] = t;
+      mine[K + 1 + i] = L.cand_tok[i * CM];
+    }
   }
-  if (mine)
-    for (int i = lane; i < K; i += kWave) mine[K + 1 + i] = L.cand_tok[i * CM];
 }
 
 }  // namespace
