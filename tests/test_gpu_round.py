@@ -267,6 +267,76 @@ def test_library_round_loop_equals_the_round_by_round_driver(cfg_name):
         dm.close(); vm.close()
 
 
+def _successor_pair(cfg, succ: dict, seed: int):
+    """A drafter / verifier pair whose next token depends on the current token alone and is PLANTED for the tokens in
+    `succ`: the layers contribute nothing (zero output projections), so the final state is the token's embedding, and
+    the LM-head row of succ[t] carries a large multiple of the normalised embedding of t."""
+    w = synth.make_weights(cfg, seed)
+    for lw in w["layers"]:
+        lw["wo"][:] = 0.0
+        lw["w_down"][:] = 0.0
+    for t, nxt in succ.items():
+        e = w["embed"][t].astype(np.float64)
+        y = e / np.sqrt(np.mean(e * e) + cfg.rms_eps)
+        w["lm_head"][nxt] += (8.0 * y / np.sqrt(cfg.d_model)).astype(np.float32)
+    return w
+
+
+@pytest.mark.parametrize("case", ["all-accepted", "one-accepted"])
+def test_library_round_loop_with_accepted_tokens_on_a_planted_successor_model(case):
+    """Rounds that DO accept draft tokens, through both loop drivers, on a pair whose behaviour is known by
+    construction.  The drafter fills every masked position with token 7 (the planted successor of [MASK]); the
+    verifier follows the planted successors 5 -> 7 and either 7 -> 7 (every draft token accepted, K + 1 committed per
+    round) or 7 -> 9 -> 7 (exactly one accepted, next token 9).  Pending counts above one, the carried tokens, the
+    committed streams and the controller's proposals must agree between the library's loop and the round-by-round
+    driver, and with these hand-derived verdicts."""
+    cfg = synth.CFG_TINY
+    succ = {cfg.mask_id: 7, 5: 7, 7: 7 if case == "all-accepted" else 9, 9: 7}
+    prefix = np.concatenate([synth.make_prefix(cfg, 60, 14), [31]]).astype(np.int32)
+    succ[31] = 5                                       # the verifier's first token after the prefix
+    w = _successor_pair(cfg, succ, 20)
+    params = rnd.RoundParams(m_max=4, tau=1.0, beam=2, lam=1.0, k_min=2, k_max=8, delta=2.0, rho=0.5)
+    dm, vm = rnd.DeviceModel(cfg, w, 256), rnd.DeviceModel(cfg, w, 256)
+    k = 6
+    try:
+        a = rnd.SpecDecoder(dm, vm, None, 0, params, k_cap=8)
+        a.start(prefix)
+        assert a.tokens[-1] == 5
+        by_hand = [a.round(k) for _ in range(4)]
+        tokens_by_hand = list(a.tokens)
+        a.close()
+        for t, r in enumerate(by_hand):
+            assert list(r["path"]) == [7] * k
+            if case == "all-accepted":
+                assert (r["n_accept"], r["next_token"]) == (k, 7) and r["committed"] == [7] * (k + 1)
+            else:
+                assert (r["n_accept"], r["next_token"]) == (1, 9) and r["committed"] == [7, 9]
+        b = rnd.SpecDecoder(dm, vm, None, 0, params, k_cap=8)
+        b.start(prefix)
+        in_lib = b.run(4, k, follow_adl=False, stop_at_eos=False)
+        for r, q in zip(in_lib, by_hand):
+            for n in ("k", "path_len", "n_accept", "next_token", "eos_accepted", "first_eos", "k_next"):
+                assert r[n] == q[n], n
+            assert r["committed"] == q["committed"]
+        assert b.tokens == tokens_by_hand and len(b.pending) == (k + 1 if case == "all-accepted" else 2)
+        # the controller's proposals followed: rounds of different K and pending counts (fresh controllers)
+        b.close()
+        b = rnd.SpecDecoder(dm, vm, None, 0, params, k_cap=8)
+        b.start(prefix)
+        followed = b.run(5, 4)
+        a = rnd.SpecDecoder(dm, vm, None, 0, params, k_cap=8)
+        a.start(prefix)
+        kk = 4
+        for r in followed:
+            q = a.round(kk)
+            assert (r["k"], r["n_accept"], r["next_token"], r["k_next"]) == (kk, q["n_accept"], q["next_token"], q["k_next"])
+            kk = q["k_next"]
+        assert a.tokens == b.tokens
+        a.close(); b.close()
+    finally:
+        dm.close(); vm.close()
+
+
 def test_gpu_ar_greedy_matches_oracle_and_injected_rounds_are_lossless():
     """The GPU's one-token-per-step greedy decode equals the oracle's; speculative rounds whose path is
     partly overwritten with that stream (synthetic acceptance) commit exactly the same stream."""
