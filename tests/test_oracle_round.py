@@ -76,3 +76,31 @@ def test_rounds_with_a_tiny_lm_proxy_stay_lossless_and_keep_the_proxy_history_in
     produced = st.tokens[len(prefix):]
     assert produced == oround.ar_greedy(CFG, vw, prefix, len(produced))
     assert differs >= 1          # the proxy does steer the search
+
+
+def test_rounds_on_a_pair_with_planted_successors_give_the_hand_derived_verdicts():
+    """A pair whose next token is a planted function of the current token (zero output projections: the final state is
+    the token's embedding; the LM-head row of the successor carries the normalised embedding).  [MASK] -> 7, 5 -> 7 and
+    either 7 -> 7 (all K draft tokens accepted, next 7) or 7 -> 9 -> 7 (one accepted, next 9): worked by hand."""
+    for fixed_point in (True, False):
+        succ = {CFG.mask_id: 7, 31: 5, 5: 7, 7: 7 if fixed_point else 9, 9: 7}
+        w = synth.make_weights(CFG, 20, std=0.3)
+        for lw in w["layers"]:
+            lw["wo"][:] = 0.0
+            lw["w_down"][:] = 0.0
+        for t, nxt in succ.items():
+            e = w["embed"][t].astype(np.float64)
+            y = e / np.sqrt(np.mean(e * e) + CFG.rms_eps)
+            w["lm_head"][nxt] += (60.0 * y / np.sqrt(CFG.d_model)).astype(np.float32)
+        prefix = np.concatenate([synth.make_prefix(CFG, 10, 3), [31]])
+        st = oround.SpecState(CFG, w, CFG, w, prefix)
+        assert st.tokens[-1] == 5
+        k = 5
+        for _ in range(3):
+            r = oround.spec_round(st, k, 3, 1.0, 2, 1.0, None, LOG2)
+            assert r["path"] == [7] * k
+            if fixed_point:
+                assert (r["n_accept"], r["next_token"], r["committed"]) == (k, 7, [7] * (k + 1))
+            else:
+                assert (r["n_accept"], r["next_token"], r["committed"]) == (1, 9, [7, 9])
+        assert st.vcache.length == len(st.tokens) - 1 and st.dcache.length == len(st.tokens) - len(st.pending)
