@@ -575,8 +575,8 @@ def main() -> int:
     ab = algorithmic_bytes(cfg, PREFIX)
     achieved = ab["lm_head"] / (lm_ms * 1e-3) / 1e9
 
-    # ---- device-only round (what round 1 of this benchmark reported as its value): the same calls without staging,
-    # read-back and the host's bookkeeping, caches reset to the prefix every round
+    # ---- device-only round: the same calls without the path read-back and the host's bookkeeping, caches reset to
+    # the prefix every round
     dec.stage_inputs()
 
     def device_round():
