@@ -130,6 +130,20 @@ def test_bad_arguments_are_rejected_on_the_host_before_any_launch():
                                      None) == ds.DS_E_INVALID
     assert lib.ds_verify_block_carry(None, one, 2, None, -1, one, one, one, one, None, one, one, 1 << 20,
                                      None) == ds.DS_E_INVALID
+    # the library's round loop
+    assert ds.ds_round_io_layout(32, 8) == (146, 178, 180, 180 + 256)      # path_at, len_at, cand_at (4-aligned), total
+    assert ds.ds_round_io_layout(16, 4) == (146, 162, 164, 164 + 64)
+    for k_cap, m_max in ((0, 4), (144, 4), (16, 0), (16, 17)):
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_round_io_layout(k_cap, m_max)
+        assert e.value.code == ds.DS_E_SHAPE
+    n_pend, done, n_tok = (C.c_int(1), C.c_int(0), C.c_int(0))
+    assert lib.ds_rounds_run(None, 1, 8, 0, 0, C.byref(n_pend), None, C.byref(done), one, 16, C.byref(n_tok),
+                             None) == ds.DS_E_INVALID
+    desc = ds.RoundDescC()                                                  # every pointer NULL
+    recs = (ds.RoundRecordC * 1)()
+    assert lib.ds_rounds_run(C.byref(desc), 1, 8, 0, 0, C.byref(n_pend), recs, C.byref(done), one, 16, C.byref(n_tok),
+                             None) == ds.DS_E_INVALID
     # the LM proxy of the path search
     assert lib.ds_cps_path_lm(one, one, one, one, 8, 4, 2, 0.5, None, one, 1, -1, one, one, one, one, 1 << 20,
                               None) == ds.DS_E_INVALID
