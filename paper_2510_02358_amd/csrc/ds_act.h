@@ -124,7 +124,7 @@ template <typename T>
 int launch_qkv_rope(const SeqTable& tab, const float* part, int n_part, int rows, int rows_pad, int n_q, int n_kv,
                     int hd, const float2* cs, int cap, float q_scale, void* q, uint32_t* ovf, hipStream_t st);
 template <typename T>
-int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, uint32_t* ovf,
+int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, bool paired, void* act, uint32_t* ovf,
                   hipStream_t st);
 
 // bf16 -> half re-encoding into stream order; *range_flag [dev] is set to 1 if any |w| exceeds the half range

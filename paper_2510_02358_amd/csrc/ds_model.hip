@@ -61,9 +61,12 @@ struct ds_model {
   ds_kv self;  // the cache given to ds_model_create (what the single-sequence calls use)
   size_t esize;
   uint32_t* ovf = nullptr;  // [dev] activation-overflow counter (bf16 models: a word of the packed buffer's tail)
-  // bf16 models whose gate / up product is unsplit (a function of its shape alone): gate and up are packed with
-  // alternating 16-row blocks and the product's epilogue applies SwiGLU itself
-  bool fused_gu = false;
+  // bf16 models whose gate / up product takes one plane, or two equal ones (a function of its shape alone): gate
+  // and up are packed as a pair with alternating 16-row blocks (pair_gu).  One plane (fused_gu): the product's
+  // epilogue applies SwiGLU itself, always.  Two planes: up to kFuseTwoRows rows the workgroups walk both halves of K
+  // and fuse (measured faster there), above that the two planes are written and the SwiGLU kernel reads the paired
+  // columns; both ways produce the same bits.
+  bool fused_gu = false, pair_gu = false;
   // what the last draft pass left behind for ds_lm_head(hidden = NULL): the block rows as a GEMM input
   const void* tail_ptr = nullptr;
   const void* tail_ws = nullptr;
@@ -107,6 +110,7 @@ int validate_cfg(const ds_model_cfg* c) {
 
 size_t esize_of(int dtype) { return dtype == DS_BF16 ? 2 : 4; }
 
+constexpr int kFuseTwoRows = 48;  // a gate / up pair of two planes is fused up to this many rows
 constexpr size_t kFlagBytes = 256;  // tail of the packed buffer: weight-range flag written by the packing kernels
 
 size_t packed_bytes_of(const ds_model_cfg& c) {
@@ -315,7 +319,7 @@ int forward_rows(ds_model* m, const Workspace& w, const FwdCall& call, const Seq
     if ((rc = launch_add_norm<T>(tab, w.x, w.gemm_out, sp, rows, rp, d, m->canon[li].norm2, c.rms_eps, w.h, nullptr,
                                  nullptr, m->ovf, st)))
       return rc;
-    if (m->fused_gu) {  // SwiGLU in the product's epilogue: the next product's input comes out directly
+    if (m->fused_gu || (m->pair_gu && rows <= kFuseTwoRows)) {  // SwiGLU in the product's epilogue
       GemmEpilogue epi;
       epi.kind = GemmEpilogue::kSwiGLU;
       epi.records = w.act;
@@ -323,7 +327,7 @@ int forward_rows(ds_model* m, const Workspace& w, const FwdCall& call, const Seq
       if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st, epi))) return rc;
     } else {
       if ((rc = gemm<T>(m, li, 2, w.h, rows, w.gemm_out, &sp, st))) return rc;
-      if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, rp, c.d_ffn, w.act, m->ovf, st))) return rc;
+      if ((rc = launch_swiglu<T>(w.gemm_out, sp, rows, rp, c.d_ffn, m->pair_gu, w.act, m->ovf, st))) return rc;
     }
     if ((rc = gemm<T>(m, li, 3, w.act, rows, w.gemm_out, &sp, st))) return rc;
     const bool last = li + 1 == c.n_layers;
@@ -435,7 +439,9 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
       delete m;
       return fail(DS_E_HIP, "hipMemsetAsync(weight-range flag) failed");
     }
-    m->fused_gu = gemm_bf16_splits(2 * f, d, 2) == 1 && (f % 128) == 0;
+    const int gu_planes = gemm_bf16_splits(2 * f, d, 2);
+    m->fused_gu = gu_planes == 1 && (f % 128) == 0;
+    m->pair_gu = (f % 128) == 0 && (gu_planes == 1 || (gu_planes == 2 && (d / 128) % 2 == 0));
     auto put = [&](const void* src, int N, int K) -> int {
       int r = launch_pack_weight(src, N, K, p, flag, st);
       p += (size_t)N * K * 2;
@@ -449,7 +455,7 @@ int ds_model_create(const ds_model_cfg* cfg, const ds_weights* w, void* packed, 
       pl.wo = p;
       if ((rc = put(lw.wo, d, qo))) break;
       pl.wgu = p;
-      if (m->fused_gu) {
+      if (m->pair_gu) {
         if ((rc = launch_pack_weight_pair(lw.w_gate, lw.w_up, f, d, p, flag, st))) break;
         p += (size_t)2 * f * d * 2;
       } else if ((rc = put(lw.w_gate, f, d)) || (rc = put(lw.w_up, f, d))) {

@@ -207,9 +207,10 @@ __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int 
 }
 
 // act[r][f] = silu(gate) * up with gate = sum_s part[s][r][f], up = sum_s part[s][r][F + f]; four
-// consecutive f per thread (F % 4 == 0).
+// consecutive f per thread (F % 4 == 0).  paired: the product's columns alternate between 16 of gate and 16 of up
+// (the weights were packed as a pair): gate f sits at column 32 (f / 16) + f % 16, up f sixteen further.
 template <typename T>
-__global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int F,
+__global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int F, bool paired,
                               T* __restrict__ act, uint32_t* __restrict__ ovf) {
   const int r = blockIdx.y;
   const int f = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
@@ -221,8 +222,9 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
     pg[s] = pu[s] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (s < n_part) {
       const float* p = part + ((size_t)s * rows + r) * (2 * (size_t)F);
-      pg[s] = *reinterpret_cast<const float4*>(p + f);
-      pu[s] = *reinterpret_cast<const float4*>(p + F + f);
+      const int cg = paired ? ((f >> 4) << 5) + (f & 15) : f;
+      pg[s] = *reinterpret_cast<const float4*>(p + cg);
+      pu[s] = *reinterpret_cast<const float4*>(p + (paired ? cg + 16 : F + f));
     }
   }
   float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
@@ -292,11 +294,12 @@ int launch_qkv_rope(const SeqTable& tab, const float* part, int n_part, int rows
 }
 
 template <typename T>
-int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, void* act, uint32_t* ovf,
+int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, bool paired, void* act, uint32_t* ovf,
                   hipStream_t st) {
   DS_REQUIRE(n_part >= 1 && n_part <= kMaxPlanes, DS_E_SHAPE, "SwiGLU: %d partial planes, at most %d", n_part, kMaxPlanes);
+  DS_REQUIRE(!paired || (F & 15) == 0, DS_E_SHAPE, "SwiGLU: a paired product needs F %% 16 == 0");
   hipLaunchKernelGGL((swiglu_kernel<T>), dim3(ceil_div(F, 1024), rows), dim3(256), 0, st, part, n_part, rows,
-                     rows_pad, F, static_cast<T*>(act), ovf);
+                     rows_pad, F, paired, static_cast<T*>(act), ovf);
   DS_LAUNCH_CHECK("swiglu_kernel");
   return DS_OK;
 }
@@ -310,7 +313,7 @@ int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, 
   template int launch_to_gemm_input<T>(const float*, int, int, int, void*, uint32_t*, hipStream_t);                \
   template int launch_qkv_rope<T>(const SeqTable&, const float*, int, int, int, int, int, int, const float2*, int, float, \
                                   void*, uint32_t*, hipStream_t);                                                  \
-  template int launch_swiglu<T>(const float*, int, int, int, int, void*, uint32_t*, hipStream_t);
+  template int launch_swiglu<T>(const float*, int, int, int, int, bool, void*, uint32_t*, hipStream_t);
 DS_INSTANTIATE(float)
 DS_INSTANTIATE(bf16_t)
 

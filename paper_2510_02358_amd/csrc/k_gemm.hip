@@ -96,7 +96,11 @@ __global__ void pack_weight_kernel(const uint16_t* __restrict__ w, const uint16_
 //               wavefront's two adjacent blocks are column block c of gate and of up, so silu(gate) * up is taken
 //               in registers and stored as the next product's half-precision input; the float32 product never
 //               reaches memory and no separate kernel runs.
-enum { kEpiPlanes = 0, kEpiStream = 1, kEpiBest = 2, kEpiTop = 3, kEpiSwiGLU = 4 };
+//   kEpiSwiGLU2 the same for a pair whose product is split into TWO planes when it is not fused: wavefronts 0 and 1 of
+//               a workgroup walk the first half of K, wavefronts 2 and 3 the second half of the same columns, the
+//               second pair hands its sums over through LDS and the epilogue adds the halves in plane order, so the
+//               fused result has the bits of the two-plane product followed by the SwiGLU kernel.
+enum { kEpiPlanes = 0, kEpiStream = 1, kEpiBest = 2, kEpiTop = 3, kEpiSwiGLU = 4, kEpiSwiGLU2 = 5 };
 
 // Running (largest, second largest, third largest) of a stream of values; the first two carry their columns and
 // order equal values by column, the third is a value only.
@@ -139,20 +143,28 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
                                                                  float* __restrict__ export_out,
                                                                  uint32_t* __restrict__ ovf) {
   constexpr int kTiles = MB * kKSC;  // X tiles per chunk: row blocks x k-steps
-  __shared__ __attribute__((aligned(16))) uint16_t xs[2][kTiles * 512];
+  constexpr bool kTwo = EPI == kEpiSwiGLU2;  // two halves of K side by side in one workgroup
+  constexpr int kHalves = kTwo ? 2 : 1;
+  __shared__ __attribute__((aligned(16))) uint16_t xs[2][kHalves * kTiles * 512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n_blocks = N >> 4, ksteps = K >> 5, n_chunks = ksteps / kKSC;
-  const int c_begin = blockIdx.y * groups_per_split * (kGroup / kKSC);
-  int c_end = c_begin + groups_per_split * (kGroup / kKSC);
+  // kTwo: every step handles chunk c of the first half and chunk c_half + c of the second (the launcher has checked
+  // that the halves are equal); the loop below runs over the first half's range.
+  const int c_half = kTwo ? n_chunks / 2 : 0;
+  const int my_half = kTwo ? wave >> 1 : 0;
+  const int c_begin = kTwo ? 0 : blockIdx.y * groups_per_split * (kGroup / kKSC);
+  int c_end = kTwo ? c_half : c_begin + groups_per_split * (kGroup / kKSC);
   if (c_end > n_chunks) c_end = n_chunks;
 
   static_assert(WAVES == 4 || EPI == kEpiPlanes || EPI == kEpiStream || EPI == kEpiSwiGLU,
                 "the record epilogues reduce over four wavefronts");
-  static_assert(EPI != kEpiSwiGLU || NB == 2, "the fused epilogue pairs a wavefront's two column blocks");
+  static_assert((EPI != kEpiSwiGLU && EPI != kEpiSwiGLU2) || NB == 2,
+                "the fused epilogue pairs a wavefront's two column blocks");
   constexpr int kThreads = WAVES * 64;
+  constexpr int kColWaves = WAVES / kHalves;  // wavefronts side by side over the columns
   // This workgroup's share of the output row blocks.  The first n_big workgroups take a full pass of
-  // WAVES * NB blocks each; a remainder goes to later workgroups in half-size pieces.
-  const int full = WAVES * NB, half = full / 2 > 0 ? full / 2 : 1;
+  // kColWaves * NB blocks each; a remainder goes to later workgroups in half-size pieces.
+  const int full = kColWaves * NB, half = full / 2 > 0 ? full / 2 : 1;
   int nb_begin, nb_end;
   if ((int)blockIdx.x < n_big) {
     nb_begin = (int)blockIdx.x * full;
@@ -165,14 +177,14 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   const int j_out = lane & 15, g_out = lane >> 4;
   float* out_plane = out + (size_t)blockIdx.y * M * N;
 
-  for (int pass0 = nb_begin; pass0 < nb_end; pass0 += WAVES * NB) {
+  for (int pass0 = nb_begin; pass0 < nb_end; pass0 += kColWaves * NB) {
   int nb[NB];
   const uint16_t* wrow[NB];
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
-    nb[b] = pass0 + wave * NB + b;  // a wavefront's blocks are adjacent
+    nb[b] = pass0 + (kTwo ? wave & 1 : wave) * NB + b;  // a wavefront's blocks are adjacent
     const int nbc = nb[b] < nb_end ? nb[b] : nb_end - 1;  // clamp: loads stay in this workgroup's range
-    wrow[b] = wp + ((size_t)nbc * ksteps) * 512 + lane * 8;
+    wrow[b] = wp + ((size_t)nbc * ksteps + (size_t)my_half * c_half * kKSC) * 512 + lane * 8;
   }
 
   f32x4 acc[NB][MB];
@@ -184,7 +196,8 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   // 16-byte pieces of X per chunk, order [mb][s][lane]: kXPer per thread.  With four wavefronts the pieces split
   // evenly; with eight and an odd MB the last round is half full: those threads re-load the chunk's last piece
   // (no predicate on the loads, which therefore issue back to back) and skip the store.
-  constexpr int kPieces = kTiles * 64;
+  constexpr int kHalfPieces = kTiles * 64;
+  constexpr int kPieces = kHalves * kHalfPieces;
   constexpr int kXPer = (kPieces + kThreads - 1) / kThreads;
   constexpr bool kXTail = (kPieces % kThreads) != 0;
   constexpr int kStages = 3;  // weight-tile register sets: two chunks are in flight while one is multiplied
@@ -200,12 +213,14 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   for (int p = 0; p < kXPer; ++p) {
     int piece = threadIdx.x + p * kThreads;
     if (kXTail && piece >= kPieces) piece = kPieces - 1;
+    const int x_half = kTwo ? piece / kHalfPieces : 0;  // the pieces of the second half's chunk follow the first's
+    piece -= x_half * kHalfPieces;
     const int mb = piece / (kKSC * 64), rest = piece - mb * (kKSC * 64);
     const int j = rest & 15;
     int j_last = M - 1 - mb * 16;  // last real row of this block (>= 15: a full block)
     j_last = j_last < 0 ? 0 : j_last;
     const int jc = j < j_last ? j : j_last;
-    x_off[p] = (size_t)mb * ksteps * 512 + (size_t)(rest - j + jc) * 8;
+    x_off[p] = (size_t)mb * ksteps * 512 + (size_t)(rest - j + jc) * 8 + (size_t)x_half * c_half * kKSC * 512;
   }
   auto load_x = [&](int c) {
 #pragma unroll
@@ -234,7 +249,7 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
       f16x8 bx[MB];
 #pragma unroll
       for (int m = 0; m < MB; ++m)
-        bx[m] = *reinterpret_cast<const f16x8*>(&xs[buf][((m * kKSC + s) * 64 + lane) * 8]);
+        bx[m] = *reinterpret_cast<const f16x8*>(&xs[buf][my_half * (kTiles * 512) + ((m * kKSC + s) * 64 + lane) * 8]);
 #pragma unroll
       for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -284,11 +299,34 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
   }
 
   // D[i][j]: lane (16 g + j) holds rows i = 4 g .. 4 g + 3 of column j  ->  out[m = 16 mb + j][n = 16 nb + 4 g ..]
-  if (EPI == kEpiSwiGLU) {
+  if (kTwo) {
+    // the second half's sums go to the wavefront of the first half that holds the same columns (the main loop is
+    // past its last barrier: the X buffers are free); then plane order: the consumer of two planes starts from zero
+    f32x4* red = reinterpret_cast<f32x4*>(&xs[0][0]);  // [2 wavefronts][NB][MB][64 lanes]
+    static_assert(2 * NB * MB * 64 * sizeof(f32x4) <= sizeof(xs), "the exchange fits the X buffers");
+    if (my_half == 1) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int m = 0; m < MB; ++m) red[(((wave & 1) * NB + b) * MB + m) * 64 + lane] = acc[b][m];
+    }
+    __syncthreads();
+    if (my_half == 0) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+          const f32x4 other = red[(((wave & 1) * NB + b) * MB + m) * 64 + lane];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[b][m][e] = (0.f + acc[b][m][e]) + other[e];
+        }
+    }
+  }
+  if (EPI == kEpiSwiGLU || EPI == kEpiSwiGLU2) {
     // blocks 2c and 2c + 1 of the packed pair: gate and up of column block c.  rec: the half-precision GEMM input
     // [rows padded, N / 2] of the next product (tile order).
     bf16_t* act = static_cast<bf16_t*>(rec);
-    if (nb[0] < nb_end) {
+    if (nb[0] < nb_end && my_half == 0) {
       const int col = (nb[0] >> 1) * 16 + g_out * 4;
 #pragma unroll
       for (int m = 0; m < MB; ++m) {
@@ -303,6 +341,7 @@ void gemm_bf16_kernel(const uint16_t* __restrict__ wp,
         }
       }
     }
+    if (kTwo) __syncthreads();  // a further pass reuses the X buffers
   } else if ((EPI != kEpiBest && EPI != kEpiTop) || out) {
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -481,15 +520,26 @@ int launch_bf16_mb(const uint16_t* wp, const uint16_t* xt, int M, int N, int K, 
   const bool wide = MB >= 5 && min_waves_for(MB, nbw) == 2 && plain &&
                     n_blocks % (8 * nbw) == 0 && (n_blocks / (8 * nbw)) * n_split <= 256;
   const int waves = wide ? 8 : 4;
+  // A gate / up pair whose product takes two planes, fused: the workgroup's wavefronts pair up over the two halves of
+  // K, so a workgroup covers half the columns (as many workgroups and wavefronts as the two-plane launch has).
+  const bool two = epi.kind == GemmEpilogue::kSwiGLU && n_split == 2;
   // One workgroup per full pass of waves * nbw row blocks; a remainder goes to half-size workgroups at the end.
-  const int full = waves * nbw, half = full / 2 > 0 ? full / 2 : 1;
+  const int full = (two ? waves / 2 : waves) * nbw, half = full / 2 > 0 ? full / 2 : 1;
   const int n_big = n_blocks / full;
   const int n_small = ceil_div(n_blocks - n_big * full, half);
-  dim3 grid(n_big + n_small, n_split);
+  dim3 grid(n_big + n_small, two ? 1 : n_split);
   auto go = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, grid, dim3(waves * 64), 0, st, wp, xt, M, N, K, gps, n_big, out, epi.records,
                        epi.export_col, epi.export_out, epi.ovf);
   };
+  if (two) {
+    if constexpr (MB <= 3) {
+      go(gemm_bf16_kernel<MB, 2, kEpiSwiGLU2>);
+      DS_LAUNCH_CHECK("gemm_bf16_kernel");
+      return DS_OK;
+    }
+    return fail(DS_E_SHAPE, "GEMM: the fused two-plane gate / up product takes at most 48 rows");
+  }
   if (wide) {
     if constexpr (MB >= 5) {
       if (epi.kind == GemmEpilogue::kSwiGLU) go(gemm_bf16_kernel<MB, 2, kEpiSwiGLU, 8>);
@@ -575,8 +625,11 @@ int launch_gemm_bf16(const void* wp, const void* xt, int M, int N, int K, int nb
   DS_REQUIRE(M >= 1 && M <= DS_MAX_ROWS, DS_E_SHAPE, "GEMM rows %d outside [1, %d]", M, DS_MAX_ROWS);
   DS_REQUIRE((N & 15) == 0 && (K & 127) == 0, DS_E_SHAPE, "GEMM [%d x %d]: N %% 16 and K %% 128 must be 0", N, K);
   if (epi.kind == GemmEpilogue::kSwiGLU)
-    DS_REQUIRE(epi.records && nbw == 2 && n_split == 1 && (N >> 4) % 16 == 0, DS_E_SHAPE,
-               "GEMM [%d x %d]: the fused gate / up epilogue needs an unsplit pass over whole pairs of blocks", N, K);
+    DS_REQUIRE(epi.records && nbw == 2 && (N >> 4) % 16 == 0 &&
+                   (n_split == 1 || (n_split == 2 && M <= 48 && ((K >> 5) / kKSC) % 2 == 0 && kGroup == kKSC)),
+               DS_E_SHAPE,
+               "GEMM [%d x %d]: the fused gate / up epilogue needs whole pairs of blocks and one plane (or, up to 48 "
+               "rows, two equal ones)", N, K);
   const bool records = epi.kind == GemmEpilogue::kBest || epi.kind == GemmEpilogue::kTop;
   DS_REQUIRE(out || records || epi.kind == GemmEpilogue::kSwiGLU, DS_E_INVALID,
              "GEMM: neither an output nor a per-tile record buffer");

@@ -172,12 +172,19 @@ def test_peaky_attention_block_rows_stay_bit_identical_to_one_row_decoding():
 # the library packs gate and up with alternating blocks and applies SwiGLU in the product's epilogue.
 CFG_WIDE_FFN = synth.ModelCfg(n_layers=1, d_model=256, n_q=2, n_kv=1, head_dim=128, d_ffn=27648, vocab=4096,
                               rope_base=1.0e6, dtype="bf16")
+# The 7B shape's FFN width: its gate / up product takes two planes.  Up to 48 rows the workgroups walk both halves of K
+# and fuse SwiGLU; above that the planes are written and the SwiGLU kernel reads the paired columns.
+CFG_TWO_PLANE_FFN = synth.ModelCfg(n_layers=1, d_model=256, n_q=2, n_kv=1, head_dim=128, d_ffn=18944, vocab=4096,
+                                   rope_base=1.0e6, dtype="bf16")
+FUSED_CFGS = {"one-plane": CFG_WIDE_FFN, "two-planes": CFG_TWO_PLANE_FFN}
 
 
-def test_fused_gate_up_epilogue_against_the_oracle_and_across_row_counts():
-    """Prefill (70 rows: eight-wavefront workgroups), draft (12 rows), verify (40 rows) against the oracle, and the
-    rows of a 71-row block bit-identical to one-row decoding (four- and eight-wavefront workgroups, the same bits)."""
-    cfg = CFG_WIDE_FFN
+@pytest.mark.parametrize("shape", list(FUSED_CFGS))
+def test_fused_gate_up_epilogue_against_the_oracle_and_across_row_counts(shape):
+    """Prefill (70 rows), draft (12 rows), verify (40 rows) against the oracle, and the rows of a 71-row block
+    bit-identical to one-row decoding.  One plane: four- and eight-wavefront workgroups, the same bits.  Two planes:
+    the fused pass (12, 40 and 1 rows) and the two-plane product with the SwiGLU kernel (70, 71 rows), the same bits."""
+    cfg = FUSED_CFGS[shape]
     w = synth.make_weights(cfg, 240)
     synth.randomize_norm_gains(w, 241)
     prefix = synth.make_prefix(cfg, 70, 242)
@@ -193,7 +200,7 @@ def test_fused_gate_up_epilogue_against_the_oracle_and_across_row_counts():
         ref_v = o_model.verify_logits(cfg, w, oc, block)
         got_v = gm.verify(block)["logits"]
         errs = [float(np.max(np.abs(a - b))) for a, b in ((got_last, ref_last), (got_d, ref_d), (got_v, ref_v))]
-        print(f"PARITY-COUNTS fused gate/up epilogue: max |dlogit| prefill {errs[0]:.3e}, draft {errs[1]:.3e}, "
+        print(f"PARITY-COUNTS fused gate/up epilogue ({shape}): max |dlogit| prefill {errs[0]:.3e}, draft {errs[1]:.3e}, "
               f"verify {errs[2]:.3e} at logit std {float(np.std(ref_v)):.3f}")
         assert max(errs) <= 2e-2
         assert ds.ds_model_overflow_count(gm.handle) == 0
@@ -211,8 +218,9 @@ def test_fused_gate_up_epilogue_against_the_oracle_and_across_row_counts():
         gm.close()
 
 
-def test_fused_gate_up_epilogue_counts_what_it_clamps():
-    cfg = CFG_WIDE_FFN
+@pytest.mark.parametrize("shape", list(FUSED_CFGS))
+def test_fused_gate_up_epilogue_counts_what_it_clamps(shape):
+    cfg = FUSED_CFGS[shape]
     w = synth.make_weights(cfg, 250)
     rng = np.random.default_rng(251)
     for lw in w["layers"]:
