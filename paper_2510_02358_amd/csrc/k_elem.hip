@@ -207,10 +207,9 @@ __global__ void qkv_rope_kernel(const float* __restrict__ part, int n_part, int 
 }
 
 // act[r][f] = silu(gate) * up with gate = sum_s part[s][r][f], up = sum_s part[s][r][F + f]; four
-// consecutive f per thread (F % 4 == 0).  paired: the product's columns alternate between 16 of gate and 16 of up
-// (the weights were packed as a pair): gate f sits at column 32 (f / 16) + f % 16, up f sixteen further.
+// consecutive f per thread (F % 4 == 0).
 template <typename T>
-__global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int F, bool paired,
+__global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int F,
                               T* __restrict__ act, uint32_t* __restrict__ ovf) {
   const int r = blockIdx.y;
   const int f = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
@@ -222,9 +221,8 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
     pg[s] = pu[s] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (s < n_part) {
       const float* p = part + ((size_t)s * rows + r) * (2 * (size_t)F);
-      const int cg = paired ? ((f >> 4) << 5) + (f & 15) : f;
-      pg[s] = *reinterpret_cast<const float4*>(p + cg);
-      pu[s] = *reinterpret_cast<const float4*>(p + (paired ? cg + 16 : F + f));
+      pg[s] = *reinterpret_cast<const float4*>(p + f);
+      pu[s] = *reinterpret_cast<const float4*>(p + F + f);
     }
   }
   float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
@@ -237,6 +235,38 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int n_part, int ro
   const float4 y = make_float4(g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
                                g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w);
   Act<T>::put4(act, r, f, F, y, ovf);
+}
+
+// The same for a product whose columns alternate between 16 of gate and 16 of up (the weights were packed as a pair):
+// gate f sits at column 32 (f / 16) + f % 16, up f sixteen further.  A thread sums four consecutive columns of the
+// product (a wavefront reads 1 KB in one piece); the four lanes of a gate group take their up values from the four
+// lanes after them (F % 128 == 0: a group of 32 columns never straddles the end of the row).
+template <typename T>
+__global__ void swiglu_paired_kernel(const float* __restrict__ part, int n_part, int rows, int rows_pad, int F,
+                                     T* __restrict__ act, uint32_t* __restrict__ ovf) {
+  const int r = blockIdx.y;
+  const int col = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  const bool inside = col < 2 * F;  // whole groups of 32 columns are inside or outside together
+  float4 pv[kMaxPlanes];
+#pragma unroll
+  for (int s = 0; s < kMaxPlanes; ++s) {
+    pv[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (s < n_part && inside)
+      pv[s] = *reinterpret_cast<const float4*>(part + ((size_t)s * rows + r) * (2 * (size_t)F) + col);
+  }
+  float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int s = 0; s < kMaxPlanes; ++s)
+    if (s < n_part) {
+      x.x += pv[s].x; x.y += pv[s].y; x.z += pv[s].z; x.w += pv[s].w;
+    }
+  const float4 u = make_float4(__shfl_down(x.x, 4), __shfl_down(x.y, 4), __shfl_down(x.z, 4), __shfl_down(x.w, 4));
+  if (inside && (col & 16) == 0) {
+    const int f = ((col >> 5) << 4) + (col & 15);
+    const float4 y = make_float4(x.x / (1.0f + expf(-x.x)) * u.x, x.y / (1.0f + expf(-x.y)) * u.y,
+                                 x.z / (1.0f + expf(-x.z)) * u.z, x.w / (1.0f + expf(-x.w)) * u.w);
+    Act<T>::put4(act, r, f, F, y, ovf);
+  }
 }
 
 }  // namespace
@@ -297,9 +327,15 @@ template <typename T>
 int launch_swiglu(const float* part, int n_part, int rows, int rows_pad, int F, bool paired, void* act, uint32_t* ovf,
                   hipStream_t st) {
   DS_REQUIRE(n_part >= 1 && n_part <= kMaxPlanes, DS_E_SHAPE, "SwiGLU: %d partial planes, at most %d", n_part, kMaxPlanes);
-  DS_REQUIRE(!paired || (F & 15) == 0, DS_E_SHAPE, "SwiGLU: a paired product needs F %% 16 == 0");
+  if (paired) {
+    DS_REQUIRE((F & 127) == 0, DS_E_SHAPE, "SwiGLU: a paired product needs F %% 128 == 0");
+    hipLaunchKernelGGL((swiglu_paired_kernel<T>), dim3(ceil_div(2 * F, 1024), rows), dim3(256), 0, st, part, n_part,
+                       rows, rows_pad, F, static_cast<T*>(act), ovf);
+    DS_LAUNCH_CHECK("swiglu_paired_kernel");
+    return DS_OK;
+  }
   hipLaunchKernelGGL((swiglu_kernel<T>), dim3(ceil_div(F, 1024), rows), dim3(256), 0, st, part, n_part, rows,
-                     rows_pad, F, paired, static_cast<T*>(act), ovf);
+                     rows_pad, F, static_cast<T*>(act), ovf);
   DS_LAUNCH_CHECK("swiglu_kernel");
   return DS_OK;
 }
