@@ -541,7 +541,7 @@ def main() -> int:
     # one pending row; the caches grow by one token per round.  The LM-head GEMM is bracketed by two events on every
     # EV_EVERY-th timed round (an event pair costs the round about 5 us of stream time, so timing every round would tax
     # the quantity being measured).
-    EV_EVERY = 4
+    EV_EVERY = 8
     pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
              for _ in range(0, args.steps, EV_EVERY)]
     for a, b in pairs:      # a first record creates the events' handles
