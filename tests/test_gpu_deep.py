@@ -163,3 +163,31 @@ def test_7b_shape_three_layers_bf16_rounds_with_adaptive_draft_length(record_pro
         assert counts["rounds"] >= 2, counts
     finally:
         dec.close(); dm.close(); vm.close()
+
+
+def test_7b_layer_rows_are_bit_identical_across_the_fused_gate_up_boundary():
+    """One layer of the 7B shape (reduced vocabulary): a row's logits are the same bits whether it runs in a 65-row
+    block (gate / up as two planes + the SwiGLU kernel), in a 40-row block or alone (both halves of K fused in one
+    workgroup pass): 14 chunks of K per half, the shape the round runs."""
+    cfg = replace(synth.CFG_7B_LAYER, vocab=8192)
+    w = synth.make_weights(cfg, 260)
+    synth.randomize_norm_gains(w, 261)
+    rng = np.random.default_rng(262)
+    prefix = synth.make_prefix(cfg, 100, 263)
+    gm = gu.GpuModel(cfg, w, 256)
+    try:
+        gm.prefill(prefix, want_logits=False)
+        big = rng.integers(0, cfg.n_plain_tokens, 65).astype(np.int32)
+        whole = gm.verify(big)["logits"]
+        gm.set_kv_len(100)
+        part = gm.verify(big[:40])["logits"]
+        assert np.array_equal(part, whole[:40])
+        for r in (0, 20, 47, 48, 64):
+            gm.set_kv_len(100)
+            if r:
+                gm.verify(big[:r], want_logits=False)       # writes the cache rows 100 .. 100 + r - 1
+            gm.set_kv_len(100 + r)
+            one = gm.verify(big[r:r + 1])["logits"]
+            assert np.array_equal(one[0], whole[r]), r
+    finally:
+        gm.close()
